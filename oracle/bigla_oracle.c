@@ -1,0 +1,167 @@
+/*
+ * CPU oracle for the BiGLA token mixer and the 2D gating locality injection.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, float64 statement of
+ * what the hot path computes.  It shares no code with the HIP library and is
+ * linked, loaded or executed only by the tests, the smoke check and the
+ * cpu_baseline leg of the benchmark.
+ *
+ * Every routine is the paper's definition written out directly:
+ *   - bigla_ref_f64         : the two recurrences of Eq. (BiGLA), Section 4.2.1,
+ *                             run token by token, then averaged.
+ *   - locality_gate_ref_f64 : Section 4.2.2 (depthwise 3x3 convolution on the
+ *                             patch grid, sigmoid gate, convex blend).
+ * No blocking, chunking, fusion or reordering is applied.
+ *
+ * Pins (tests/test_oracle_pins.py): explicit-product quadratic form by brute
+ * force, the all-gates-one reduction to plain bidirectional linear attention,
+ * the closed forms for vanishing and constant gates, the reversal symmetry,
+ * the kill-one-direction causal check, trilinearity, a hand-worked L=2 case,
+ * and for the convolution a library conv2d plus closed-form kernels.
+ *
+ * Layout everywhere: dense row-major, innermost index = feature.
+ *   q, k, g_fwd, g_bwd : [B, H, L, dk]      v, out : [B, H, L, dv]
+ * g_* are LOG gates: alpha = exp(g) in (0, 1].
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* One (batch, head) slab.  S is a dk x dv scratch matrix, o_dir an L x dv scratch. */
+static void bigla_slab(const double *q, const double *k, const double *v,
+                       const double *g_fwd, const double *g_bwd, double *out,
+                       int L, int dk, int dv, double *S, double *o_fwd)
+{
+    /* forward direction: S_t = diag(alpha_fwd_t) S_{t-1} + k_t^T v_t ; o_t = q_t S_t */
+    memset(S, 0, sizeof(double) * (size_t)dk * dv);
+    for (int t = 0; t < L; ++t) {
+        for (int c = 0; c < dk; ++c) {
+            const double alpha = exp(g_fwd[(size_t)t * dk + c]);
+            const double kc = k[(size_t)t * dk + c];
+            for (int j = 0; j < dv; ++j)
+                S[(size_t)c * dv + j] = alpha * S[(size_t)c * dv + j] + kc * v[(size_t)t * dv + j];
+        }
+        for (int j = 0; j < dv; ++j) {
+            double acc = 0.0;
+            for (int c = 0; c < dk; ++c)
+                acc += q[(size_t)t * dk + c] * S[(size_t)c * dv + j];
+            o_fwd[(size_t)t * dv + j] = acc;
+        }
+    }
+    /* backward direction: S_t = diag(alpha_bwd_t) S_{t+1} + k_t^T v_t ; o_t = q_t S_t */
+    memset(S, 0, sizeof(double) * (size_t)dk * dv);
+    for (int t = L - 1; t >= 0; --t) {
+        for (int c = 0; c < dk; ++c) {
+            const double alpha = exp(g_bwd[(size_t)t * dk + c]);
+            const double kc = k[(size_t)t * dk + c];
+            for (int j = 0; j < dv; ++j)
+                S[(size_t)c * dv + j] = alpha * S[(size_t)c * dv + j] + kc * v[(size_t)t * dv + j];
+        }
+        for (int j = 0; j < dv; ++j) {
+            double acc = 0.0;
+            for (int c = 0; c < dk; ++c)
+                acc += q[(size_t)t * dk + c] * S[(size_t)c * dv + j];
+            /* o_t = (o_fwd_t + o_bwd_t) / 2 */
+            out[(size_t)t * dv + j] = 0.5 * (o_fwd[(size_t)t * dv + j] + acc);
+        }
+    }
+}
+
+/*
+ * BiGLA forward, Section 4.2.1, Eq. (BiGLA).  Both states start from zero
+ * (before the first token for the forward scan, after the last token for the
+ * backward scan).  Returns 0, or -1 on a bad argument / allocation failure.
+ * nthreads <= 0 means "all cores"; slabs (b, h) are independent units.
+ */
+int bigla_ref_f64(const double *q, const double *k, const double *v,
+                  const double *g_fwd, const double *g_bwd, double *out,
+                  int B, int H, int L, int dk, int dv, int nthreads)
+{
+    if (!q || !k || !v || !g_fwd || !g_bwd || !out) return -1;
+    if (B <= 0 || H <= 0 || L <= 0 || dk <= 0 || dv <= 0) return -1;
+    const long slabs = (long)B * H;
+    int failed = 0;
+#ifdef _OPENMP
+    if (nthreads <= 0) nthreads = omp_get_max_threads();
+#pragma omp parallel num_threads(nthreads)
+#endif
+    {
+        double *S = (double *)malloc(sizeof(double) * (size_t)dk * dv);
+        double *of = (double *)malloc(sizeof(double) * (size_t)L * dv);
+        if (!S || !of) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        } else {
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1)
+#endif
+            for (long s = 0; s < slabs; ++s) {
+                const size_t ok = (size_t)s * L * dk, ov = (size_t)s * L * dv;
+                bigla_slab(q + ok, k + ok, v + ov, g_fwd + ok, g_bwd + ok, out + ov, L, dk, dv, S, of);
+            }
+        }
+        free(S);
+        free(of);
+    }
+    return failed ? -1 : 0;
+}
+
+/* Number of threads bigla_ref_f64 / locality_gate_ref_f64 use for nthreads <= 0. */
+int oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/*
+ * 2D gating locality injection, Section 4.2.2:
+ *   O_local = DWConv3x3(X)              (stride 1, zero padding 1, cross-correlation,
+ *                                        one 3x3 filter per channel c = h*dv + j)
+ *   G       = sigmoid(z)
+ *   O       = G * O_local + (1 - G) * O_global
+ * x, z, o_global, out : [B, H, Hg*Wg, dv] with token index t = y*Wg + x_pos;
+ * w : [H*dv, 3, 3]; bias : [H*dv] or NULL.
+ */
+int locality_gate_ref_f64(const double *x, const double *w, const double *bias,
+                          const double *z, const double *o_global, double *out,
+                          int B, int H, int Hg, int Wg, int dv, int nthreads)
+{
+    if (!x || !w || !z || !o_global || !out) return -1;
+    if (B <= 0 || H <= 0 || Hg <= 0 || Wg <= 0 || dv <= 0) return -1;
+    const long slabs = (long)B * H;
+    const int L = Hg * Wg;
+#ifdef _OPENMP
+    if (nthreads <= 0) nthreads = omp_get_max_threads();
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+#endif
+    for (long s = 0; s < slabs; ++s) {
+        const int h = (int)(s % H);
+        const size_t base = (size_t)s * L * dv;
+        for (int y = 0; y < Hg; ++y)
+            for (int xp = 0; xp < Wg; ++xp)
+                for (int j = 0; j < dv; ++j) {
+                    const int c = h * dv + j;
+                    double local = bias ? bias[c] : 0.0;
+                    for (int dy = -1; dy <= 1; ++dy)
+                        for (int dx = -1; dx <= 1; ++dx) {
+                            const int yy = y + dy, xx = xp + dx;
+                            if (yy < 0 || yy >= Hg || xx < 0 || xx >= Wg) continue; /* zero pad */
+                            local += w[(size_t)c * 9 + (dy + 1) * 3 + (dx + 1)] *
+                                     x[base + ((size_t)yy * Wg + xx) * dv + j];
+                        }
+                    const size_t o = base + ((size_t)y * Wg + xp) * dv + j;
+                    const double gate = 1.0 / (1.0 + exp(-z[o]));
+                    out[o] = gate * local + (1.0 - gate) * o_global[o];
+                }
+    }
+    return 0;
+}

@@ -1,0 +1,286 @@
+"""Pins for the CPU oracle: facts that the paper's equations and plain mathematics fix.
+
+Each pin takes the implementation under test as a callable, so the same checks
+run on the real oracle (tests/test_oracle_pins.py) and on deliberately broken
+copies of it (tests/test_oracle_mutants.py: every planted mistake must trip at
+least one pin).  None of these re-types the recurrence: they use the O(L^2)
+explicit-product expansion, closed forms, symmetries and library routines.
+"""
+from __future__ import annotations
+
+import json
+import os
+
+import numpy as np
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _draw(seed, B=2, H=2, L=9, dk=3, dv=4, gate_scale=1.0):
+    r = _rng(seed)
+    q = r.standard_normal((B, H, L, dk))
+    k = r.standard_normal((B, H, L, dk))
+    v = r.standard_normal((B, H, L, dv))
+    gf = -gate_scale * r.random((B, H, L, dk))
+    gb = -gate_scale * r.random((B, H, L, dk))
+    return q, k, v, gf, gb
+
+
+def _close(a, b, tol=1e-11):
+    scale = max(1.0, float(np.max(np.abs(b))))
+    err = float(np.max(np.abs(np.asarray(a) - np.asarray(b))))
+    assert err <= tol * scale, f"max abs err {err:.3e} (scale {scale:.3e})"
+
+
+# --------------------------------------------------------------------------- #
+# BiGLA
+# --------------------------------------------------------------------------- #
+def quadratic_form(q, k, v, gf, gb):
+    """Explicit-product expansion of Eq. (BiGLA), Section 4.2.1, O(L^2), no cumulative sums.
+
+    Unrolling S_t = G_t . S_{t-1} + k_t^T v_t from a zero state gives
+      o_fwd_t = sum_{i<=t} sum_c q_tc k_ic (prod_{j=i+1..t} a_fwd_jc) v_i
+      o_bwd_t = sum_{i>=t} sum_c q_tc k_ic (prod_{j=t..i-1} a_bwd_jc) v_i
+    """
+    B, H, L, dk = q.shape
+    dv = v.shape[-1]
+    af, ab = np.exp(gf), np.exp(gb)
+    out = np.zeros((B, H, L, dv))
+    for b in range(B):
+        for h in range(H):
+            for t in range(L):
+                acc = np.zeros(dv)
+                for i in range(0, t + 1):
+                    w = 0.0
+                    for c in range(dk):
+                        p = 1.0
+                        for j in range(i + 1, t + 1):
+                            p *= af[b, h, j, c]
+                        w += q[b, h, t, c] * k[b, h, i, c] * p
+                    acc += w * v[b, h, i]
+                for i in range(t, L):
+                    w = 0.0
+                    for c in range(dk):
+                        p = 1.0
+                        for j in range(t, i):
+                            p *= ab[b, h, j, c]
+                        w += q[b, h, t, c] * k[b, h, i, c] * p
+                    acc += w * v[b, h, i]
+                out[b, h, t] = 0.5 * acc
+    return out
+
+
+def pin_quadratic_bruteforce(bigla):
+    for seed, shape in ((1, dict(B=2, H=2, L=9, dk=3, dv=4)), (2, dict(B=1, H=1, L=17, dk=5, dv=2)),
+                        (3, dict(B=1, H=3, L=1, dk=2, dv=3))):
+        q, k, v, gf, gb = _draw(seed, **shape)
+        _close(bigla(q, k, v, gf, gb), quadratic_form(q, k, v, gf, gb))
+
+
+def pin_handworked_L2(bigla):
+    with open(os.path.join(GOLDEN, "bigla_L2_handworked.json")) as f:
+        g = json.load(f)
+    sh = (1, 1, 2, 1)
+    arr = lambda key: np.array(g[key], dtype=np.float64).reshape(sh)
+    out = bigla(arr("q"), arr("k"), arr("v"), np.log(arr("alpha_fwd")), np.log(arr("alpha_bwd")))
+    _close(out.reshape(-1), np.array(g["out"]), 1e-13)
+
+
+def pin_all_gates_one(bigla):
+    """log-gates = 0: plain bidirectional linear attention (Section 3, linear attention).
+
+    o_fwd_t + o_bwd_t = q_t (sum_i k_i^T v_i) + (q_t . k_t) v_t, one GEMM."""
+    q, k, v, gf, _ = _draw(4, B=2, H=3, L=23, dk=6, dv=5)
+    z = np.zeros_like(gf)
+    kv = np.einsum("bhlc,bhlj->bhcj", k, v)
+    want = 0.5 * (np.einsum("bhlc,bhcj->bhlj", q, kv) + np.sum(q * k, -1, keepdims=True) * v)
+    _close(bigla(q, k, v, z, z), want)
+
+
+def pin_gates_vanish(bigla):
+    """alpha -> 0 in both directions: only the token's own k^T v survives, twice, then halved."""
+    q, k, v, gf, _ = _draw(5, L=11)
+    big = np.full_like(gf, -1.0e3)
+    _close(bigla(q, k, v, big, big), np.sum(q * k, -1, keepdims=True) * v)
+
+
+def pin_constant_gate_toeplitz(bigla):
+    """One scalar gate gamma everywhere: out_t = sum_i w_|t-i| (q_t.k_i) v_i, w_0 = 1, w_n = gamma^n / 2."""
+    q, k, v, gf, _ = _draw(6, B=1, H=2, L=14, dk=4, dv=3)
+    gamma = 0.83
+    g = np.full_like(gf, np.log(gamma))
+    L = q.shape[2]
+    n = np.abs(np.arange(L)[:, None] - np.arange(L)[None, :])
+    w = np.where(n == 0, 1.0, 0.5 * gamma ** n)
+    want = np.einsum("ti,bhti,bhij->bhtj", w, np.einsum("bhtc,bhic->bhti", q, k), v)
+    _close(bigla(q, k, v, g, g), want)
+
+
+def pin_reversal_symmetry(bigla):
+    """Reversing the sequence and swapping the two gate streams reverses the output."""
+    q, k, v, gf, gb = _draw(7, L=13)
+    rev = lambda a: a[:, :, ::-1].copy()
+    _close(bigla(rev(q), rev(k), rev(v), rev(gb), rev(gf)), rev(bigla(q, k, v, gf, gb)))
+    # and the two gate streams are NOT interchangeable in place
+    a, b = bigla(q, k, v, gf, gb), bigla(q, k, v, gb, gf)
+    assert np.max(np.abs(a - b)) > 1e-3
+
+
+def causal_gla(q, k, v, g):
+    """Unidirectional GLA (Section 3) by explicit products: o_t = sum_{i<=t} (q_t*k_i*prod a) v_i."""
+    B, H, L, dk = q.shape
+    out = np.zeros(v.shape)
+    a = np.exp(g)
+    for t in range(L):
+        for i in range(t + 1):
+            decay = np.prod(a[:, :, i + 1:t + 1], axis=2)  # [B,H,dk]
+            out[:, :, t] += np.sum(q[:, :, t] * k[:, :, i] * decay, -1, keepdims=True) * v[:, :, i]
+    return out
+
+
+def pin_kill_one_direction(bigla):
+    q, k, v, gf, gb = _draw(8, L=12)
+    dead = np.full_like(gf, -1.0e3)
+    self_term = np.sum(q * k, -1, keepdims=True) * v
+    # backward killed: causal GLA with the forward gates + the self term, halved
+    _close(bigla(q, k, v, gf, dead), 0.5 * (causal_gla(q, k, v, gf) + self_term))
+    # forward killed: anti-causal GLA = causal GLA of the reversed sequence; the backward scan
+    # applies token t's own gate, so the reversed gate stream lines up without a shift
+    rev = lambda a: a[:, :, ::-1].copy()
+    anti = rev(causal_gla(rev(q), rev(k), rev(v), rev(gb)))
+    _close(bigla(q, k, v, dead, gb), 0.5 * (anti + self_term))
+    # causality: with the backward direction dead, tokens > t cannot change out_t
+    t0 = 6
+    k2, v2, gf2 = k.copy(), v.copy(), gf.copy()
+    k2[:, :, t0 + 1:] += 3.0
+    v2[:, :, t0 + 1:] -= 2.0
+    gf2[:, :, t0 + 1:] *= 0.5
+    a, b = bigla(q, k, v, gf, dead), bigla(q, k2, v2, gf2, dead)
+    _close(a[:, :, :t0 + 1], b[:, :, :t0 + 1])
+    assert np.max(np.abs(a[:, :, t0 + 1:] - b[:, :, t0 + 1:])) > 1e-3
+
+
+def pin_unused_boundary_gates(bigla):
+    """g_fwd[0] and g_bwd[L-1] multiply a zero state: the output cannot depend on them."""
+    q, k, v, gf, gb = _draw(9, L=7)
+    gf2, gb2 = gf.copy(), gb.copy()
+    gf2[:, :, 0] = -5.0
+    gb2[:, :, -1] = -7.0
+    _close(bigla(q, k, v, gf2, gb2), bigla(q, k, v, gf, gb), 1e-13)
+    gf2[:, :, 1] -= 1.0  # any other gate does matter
+    assert np.max(np.abs(bigla(q, k, v, gf2, gb2) - bigla(q, k, v, gf, gb))) > 1e-4
+
+
+def pin_trilinear(bigla):
+    q, k, v, gf, gb = _draw(10, L=10)
+    q2, k2, v2, _, _ = _draw(11, L=10)
+    base = bigla(q, k, v, gf, gb)
+    _close(bigla(q + 2 * q2, k, v, gf, gb), base + 2 * bigla(q2, k, v, gf, gb))
+    _close(bigla(q, k - 3 * k2, v, gf, gb), base - 3 * bigla(q, k2, v, gf, gb))
+    _close(bigla(q, k, v + v2, gf, gb), base + bigla(q, k, v2, gf, gb))
+
+
+def pin_heads_independent(bigla):
+    """Slabs (b,h) do not interact and each equals a B=H=1 call on its own slice (non-square dk != dv)."""
+    q, k, v, gf, gb = _draw(12, B=2, H=3, L=8, dk=5, dv=2)
+    full = bigla(q, k, v, gf, gb)
+    for b in range(2):
+        for h in range(3):
+            s = (slice(b, b + 1), slice(h, h + 1))
+            _close(full[s], bigla(q[s], k[s], v[s], gf[s], gb[s]), 1e-13)
+
+
+BIGLA_PINS = (pin_quadratic_bruteforce, pin_handworked_L2, pin_all_gates_one, pin_gates_vanish,
+              pin_constant_gate_toeplitz, pin_reversal_symmetry, pin_kill_one_direction,
+              pin_unused_boundary_gates, pin_trilinear, pin_heads_independent)
+
+
+# --------------------------------------------------------------------------- #
+# locality gate
+# --------------------------------------------------------------------------- #
+def _draw_loc(seed, B=2, H=2, Hg=5, Wg=7, dv=3):
+    r = _rng(seed)
+    L = Hg * Wg
+    return (r.standard_normal((B, H, L, dv)), r.standard_normal((H * dv, 3, 3)),
+            r.standard_normal((B, H, L, dv)), r.standard_normal((B, H, L, dv)))
+
+
+def pin_loc_library_conv(loc):
+    """Against a library depthwise conv2d (groups = channels, zero padding 1) in float64."""
+    import torch
+    import torch.nn.functional as F
+
+    B, H, Hg, Wg, dv = 2, 2, 5, 7, 3
+    x, w, z, og = _draw_loc(20, B, H, Hg, Wg, dv)
+    bias = _rng(21).standard_normal(H * dv)
+    for bb in (None, bias):
+        xi = torch.from_numpy(x).reshape(B, H, Hg, Wg, dv).permute(0, 1, 4, 2, 3).reshape(B, H * dv, Hg, Wg)
+        conv = F.conv2d(xi, torch.from_numpy(w).reshape(H * dv, 1, 3, 3),
+                        None if bb is None else torch.from_numpy(bb), padding=1, groups=H * dv)
+        local = conv.reshape(B, H, dv, Hg, Wg).permute(0, 1, 3, 4, 2).reshape(B, H, Hg * Wg, dv).numpy()
+        gate = 1.0 / (1.0 + np.exp(-z))
+        _close(loc(x, w, z, og, Hg, Wg, bias=bb), gate * local + (1 - gate) * og)
+
+
+def pin_loc_centre_delta_and_gate_limits(loc):
+    B, H, Hg, Wg, dv = 1, 2, 4, 6, 3
+    x, w, z, og = _draw_loc(22, B, H, Hg, Wg, dv)
+    delta = np.zeros_like(w)
+    delta[:, 1, 1] = 1.0
+    _close(loc(x, delta, np.full_like(z, 50.0), og, Hg, Wg), x)          # G -> 1: O_local = x
+    _close(loc(x, w, np.full_like(z, -50.0), og, Hg, Wg), og)            # G -> 0: O_global
+    local = loc(x, w, np.full_like(z, 50.0), og, Hg, Wg)
+    _close(loc(x, w, np.zeros_like(z), og, Hg, Wg), 0.5 * (local + og))  # G = 1/2: the mean
+
+
+def pin_loc_single_tap_shifts(loc):
+    """A single off-centre tap is a pure shift with zero fill: fixes orientation (no kernel flip)."""
+    B, H, Hg, Wg, dv = 1, 1, 4, 5, 2
+    x, w, z, og = _draw_loc(23, B, H, Hg, Wg, dv)
+    big = np.full_like(z, 50.0)
+    xg = x.reshape(B, H, Hg, Wg, dv)
+    for ky in range(3):
+        for kx in range(3):
+            tap = np.zeros_like(w)
+            tap[:, ky, kx] = 1.0
+            want = np.zeros_like(xg)
+            dy, dx = ky - 1, kx - 1  # out[y,x] = in[y+dy, x+dx]
+            for y in range(Hg):
+                for xx in range(Wg):
+                    if 0 <= y + dy < Hg and 0 <= xx + dx < Wg:
+                        want[:, :, y, xx] = xg[:, :, y + dy, xx + dx]
+            _close(loc(x, tap, big, og, Hg, Wg), want.reshape(x.shape))
+
+
+def pin_loc_ones_kernel_counts(loc):
+    """All-ones kernel on a constant image counts in-bounds taps: 9 interior, 6 edge, 4 corner."""
+    B, H, Hg, Wg, dv = 1, 1, 4, 5, 2
+    x = np.full((B, H, Hg * Wg, dv), 2.5)
+    out = loc(x, np.ones((H * dv, 3, 3)), np.full_like(x, 50.0), np.zeros_like(x), Hg, Wg)
+    out = out.reshape(Hg, Wg, dv)
+    _close(out[1, 2], 9 * 2.5)
+    _close(out[0, 2], 6 * 2.5)
+    _close(out[2, 0], 6 * 2.5)
+    _close(out[0, 0], 4 * 2.5)
+    _close(out[Hg - 1, Wg - 1], 4 * 2.5)
+
+
+def pin_loc_channel_mapping(loc):
+    """Filter c = h*dv + j acts on head h, feature j only; bias is added inside O_local."""
+    B, H, Hg, Wg, dv = 1, 3, 3, 3, 2
+    x, w, z, og = _draw_loc(24, B, H, Hg, Wg, dv)
+    big = np.full_like(z, 50.0)
+    w2 = np.zeros_like(w)
+    w2[:, 1, 1] = np.arange(1, H * dv + 1)
+    want = x * np.arange(1, H * dv + 1).reshape(1, H, 1, dv)
+    _close(loc(x, w2, big, og, Hg, Wg), want)
+    bias = np.arange(H * dv) * 0.5
+    _close(loc(x, w2, big, og, Hg, Wg, bias=bias), want + bias.reshape(1, H, 1, dv))
+
+
+LOC_PINS = (pin_loc_library_conv, pin_loc_centre_delta_and_gate_limits, pin_loc_single_tap_shifts,
+            pin_loc_ones_kernel_counts, pin_loc_channel_mapping)
