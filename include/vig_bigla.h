@@ -1,0 +1,101 @@
+/*
+ * vig_bigla.h -- C ABI of the MI355X (gfx950) BiGLA token mixer and 2D gating locality
+ * injection: the forward hot path of the ViG block (Sections 4.2.1 and 4.2.2 of the paper).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never
+ *     allocates, frees or synchronises; work is enqueued on `stream` (a hipStream_t passed
+ *     as void*, NULL = the default stream) and the call returns at once.
+ *   - Tensors are dense, row-major, innermost index = feature.  All tensors of one call
+ *     share `dtype` (vig_dtype).  VIG_BF16: bf16 in, fp32 accumulate, bf16 out rounded to
+ *     nearest even.  VIG_F32: fp32 throughout.
+ *   - Every tensor pointer must be 16-byte aligned; outputs must not alias inputs.
+ *   - Return value: a vig_status.  Arguments are validated on the host before anything is
+ *     launched; nothing aborts or throws across this boundary.  After VIG_ERR_HIP the raw
+ *     hipError_t is available from vig_last_hip_error().
+ */
+#ifndef VIG_BIGLA_H
+#define VIG_BIGLA_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    VIG_OK = 0,
+    VIG_ERR_NULL = -1,        /* a required pointer is NULL                              */
+    VIG_ERR_SHAPE = -2,       /* a size is <= 0 or the product of sizes overflows        */
+    VIG_ERR_DTYPE = -3,       /* dtype is not a vig_dtype                                */
+    VIG_ERR_UNSUPPORTED = -4, /* dk or dv outside {16, 32, 64}                           */
+    VIG_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned                        */
+    VIG_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than bigla_workspace_bytes()  */
+    VIG_ERR_HIP = -7          /* a HIP call failed; see vig_last_hip_error()             */
+} vig_status;
+
+typedef enum { VIG_F32 = 0, VIG_BF16 = 1 } vig_dtype;
+
+/*
+ * Bytes of device scratch that bigla_fwd needs for this problem (0 if none).  The scratch
+ * holds the per-segment boundary states of the chunkwise evaluation; its contents before
+ * the call are ignored and after the call are unspecified.  Returns 0 for invalid sizes
+ * (bigla_fwd reports those).
+ */
+size_t bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype);
+
+/*
+ * BiGLA forward -- Section 4.2.1, Eq. (BiGLA).  For every batch b and head h, with
+ * alpha_fwd = exp(g_fwd), alpha_bwd = exp(g_bwd) (per key dimension):
+ *     S_fwd_t = diag(alpha_fwd_t) S_fwd_{t-1} + k_t^T v_t ,   S_fwd_{-1} = 0
+ *     S_bwd_t = diag(alpha_bwd_t) S_bwd_{t+1} + k_t^T v_t ,   S_bwd_{L}  = 0
+ *     out_t   = ( q_t S_fwd_t + q_t S_bwd_t ) / 2
+ * Both directions are evaluated in the same launches; no reversed copy of the sequence
+ * is ever written.  No scaling of q is applied.
+ *
+ *   q, k         [B, H, L, dk]   in
+ *   v            [B, H, L, dv]   in
+ *   g_fwd, g_bwd [B, H, L, dk]   in   LOG forget gates, log(alpha) <= 0
+ *                                     (log alpha = logsigmoid(.)/tau for the paper's gate);
+ *                                     positive or NaN values are outside the contract
+ *   out          [B, H, L, dv]   out
+ *   L >= 1 is arbitrary (ragged final chunk handled inside); dk, dv in {16, 32, 64}.
+ *   workspace / workspace_bytes: device scratch of at least bigla_workspace_bytes(...);
+ *   may be NULL/0 when that function returns 0.
+ *
+ * Numerics: VIG_BF16 with dk = dv = 64 runs the chunkwise MFMA path; per-step log gates
+ * below -5 are treated as -5 there (alpha < 0.0068 is indistinguishable from that within
+ * the bf16 tolerance).  Every other case runs the exact fp32 recurrence.
+ */
+int bigla_fwd(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+              void *out, int B, int H, int L, int dk, int dv, int dtype, void *workspace,
+              size_t workspace_bytes, void *stream);
+
+/*
+ * 2D gating locality injection forward -- Section 4.2.2.  Token t of the flattened
+ * sequence is patch (y, xp) of the Hg x Wg grid, t = y*Wg + xp; channel c = h*dv + j.
+ *     O_local[y,xp,c] = bias[c] + sum_{dy,dx in {-1,0,1}} w[c,dy+1,dx+1] * x[y+dy, xp+dx, c]
+ *                       (stride 1, zero padding, cross-correlation)
+ *     G   = sigmoid(gate_logits)
+ *     out = G * O_local + (1 - G) * o_global
+ *
+ *   x, gate_logits, o_global  [B, H, Hg*Wg, dv]   in
+ *   w                         [H*dv, 3, 3]        in
+ *   bias                      [H*dv] or NULL      in
+ *   out                       [B, H, Hg*Wg, dv]   out
+ *   dv in {16, 32, 64}.
+ */
+int locality_gate_fwd(const void *x, const void *w, const void *bias, const void *gate_logits,
+                      const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv,
+                      int dtype, void *stream);
+
+/* Human-readable name of a vig_status (static storage, never NULL). */
+const char *vig_status_str(int status);
+
+/* The hipError_t of the most recent VIG_ERR_HIP on this thread (0 if none). */
+int vig_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VIG_BIGLA_H */

@@ -1,0 +1,155 @@
+"""Thin ctypes binding over the C-ABI library (include/vig_bigla.h).
+
+Argument marshalling only: shapes, dtypes, device pointers and the current HIP stream are
+taken from torch tensors and handed to the library; every step of the path runs in the
+library's kernels.  There is no CPU or PyTorch fallback: if the HIP library is missing, or a
+tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvig_bigla.so")
+
+VIG_OK = 0
+VIG_ERR_NULL, VIG_ERR_SHAPE, VIG_ERR_DTYPE, VIG_ERR_UNSUPPORTED = -1, -2, -3, -4
+VIG_ERR_ALIGN, VIG_ERR_WORKSPACE, VIG_ERR_HIP = -5, -6, -7
+VIG_F32, VIG_BF16 = 0, 1
+
+# every symbol include/vig_bigla.h declares
+EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "locality_gate_fwd", "vig_status_str", "vig_last_hip_error")
+
+_lib = None
+
+
+class VigError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(message)
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """Load libvig_bigla.so (built in-tree by `__graft_entry__.build()`); raise if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "at the repository root (there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        L.bigla_workspace_bytes.argtypes = [ci] * 6
+        L.bigla_workspace_bytes.restype = sz
+        L.bigla_fwd.argtypes = [vp] * 6 + [ci] * 6 + [vp, sz, vp]
+        L.bigla_fwd.restype = ci
+        L.locality_gate_fwd.argtypes = [vp] * 6 + [ci] * 6 + [vp]
+        L.locality_gate_fwd.restype = ci
+        L.vig_status_str.argtypes = [ci]
+        L.vig_status_str.restype = ctypes.c_char_p
+        L.vig_last_hip_error.argtypes = []
+        L.vig_last_hip_error.restype = ci
+        _lib = L
+    return _lib
+
+
+def status_str(status: int) -> str:
+    return lib().vig_status_str(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != VIG_OK:
+        msg = f"{what}: {status_str(status)}"
+        if status == VIG_ERR_HIP:
+            msg += f" (hipError_t {lib().vig_last_hip_error()})"
+        raise VigError(status, msg)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return VIG_F32
+    if t.dtype == torch.bfloat16:
+        return VIG_BF16
+    raise VigError(VIG_ERR_DTYPE, f"unsupported tensor dtype {t.dtype}")
+
+
+def _dev(t: torch.Tensor, name: str, shape=None, like: torch.Tensor | None = None) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise VigError(VIG_ERR_NULL, f"{name} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise VigError(VIG_ERR_SHAPE, f"{name} must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise VigError(VIG_ERR_SHAPE, f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if like is not None and (t.dtype != like.dtype or t.device != like.device):
+        raise VigError(VIG_ERR_DTYPE, f"{name} must match dtype/device of the other tensors")
+    return t
+
+
+def _stream_ptr(device) -> int:
+    return int(torch.cuda.current_stream(device).cuda_stream)
+
+
+def bigla_workspace_bytes(B: int, H: int, L: int, dk: int, dv: int, dtype: int) -> int:
+    return int(lib().bigla_workspace_bytes(B, H, L, dk, dv, dtype))
+
+
+def bigla_fwd(q, k, v, g_fwd, g_bwd, out=None, workspace=None):
+    """BiGLA forward (Section 4.2.1).  q,k,g_fwd,g_bwd: [B,H,L,dk]; v: [B,H,L,dv] -> out [B,H,L,dv].
+
+    g_* are LOG forget gates (<= 0).  `workspace` is an optional uint8 GPU tensor of at least
+    bigla_workspace_bytes(...) bytes; one is allocated with torch when absent.
+    """
+    q = _dev(q, "q")
+    if q.dim() != 4:
+        raise VigError(VIG_ERR_SHAPE, "q must be [B,H,L,dk]")
+    B, H, L, dk = q.shape
+    k = _dev(k, "k", q.shape, q)
+    g_fwd = _dev(g_fwd, "g_fwd", q.shape, q)
+    g_bwd = _dev(g_bwd, "g_bwd", q.shape, q)
+    v = _dev(v, "v", like=q)
+    if v.dim() != 4 or tuple(v.shape[:3]) != (B, H, L):
+        raise VigError(VIG_ERR_SHAPE, "v must be [B,H,L,dv]")
+    dv = v.shape[3]
+    if out is None:
+        out = torch.empty((B, H, L, dv), dtype=q.dtype, device=q.device)
+    out = _dev(out, "out", (B, H, L, dv), q)
+    code = _dtype_code(q)
+    need = bigla_workspace_bytes(B, H, L, dk, dv, code)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(q.device):
+        st = lib().bigla_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), g_fwd.data_ptr(), g_bwd.data_ptr(),
+                             out.data_ptr(), B, H, L, dk, dv, code, ws_ptr, ws_bytes, _stream_ptr(q.device))
+    _check(st, "bigla_fwd")
+    return out
+
+
+def locality_gate_fwd(x, w, gate_logits, o_global, Hg: int, Wg: int, bias=None, out=None):
+    """2D gating locality injection (Section 4.2.2).
+
+    x, gate_logits, o_global: [B,H,Hg*Wg,dv]; w: [H*dv,3,3]; bias: [H*dv] or None -> out like x.
+    """
+    x = _dev(x, "x")
+    if x.dim() != 4:
+        raise VigError(VIG_ERR_SHAPE, "x must be [B,H,L,dv]")
+    B, H, L, dv = x.shape
+    if L != Hg * Wg:
+        raise VigError(VIG_ERR_SHAPE, "x.shape[2] must equal Hg*Wg")
+    w = _dev(w, "w", (H * dv, 3, 3), x)
+    gate_logits = _dev(gate_logits, "gate_logits", x.shape, x)
+    o_global = _dev(o_global, "o_global", x.shape, x)
+    if bias is not None:
+        bias = _dev(bias, "bias", (H * dv,), x)
+    if out is None:
+        out = torch.empty_like(x)
+    out = _dev(out, "out", x.shape, x)
+    with torch.cuda.device(x.device):
+        st = lib().locality_gate_fwd(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None,
+                                     gate_logits.data_ptr(), o_global.data_ptr(), out.data_ptr(), B, H, Hg, Wg, dv,
+                                     _dtype_code(x), _stream_ptr(x.device))
+    _check(st, "locality_gate_fwd")
+    return out

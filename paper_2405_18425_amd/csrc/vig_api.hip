@@ -1,0 +1,106 @@
+// C-ABI entry points (declared in include/vig_bigla.h): host-side validation and dispatch only.
+// Every step of the path runs in the kernels of the other translation units.
+#include <stdint.h>
+
+#include "../../include/vig_bigla.h"
+#include "vig_kernels.hpp"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+bool head_dim_ok(int d) { return d == 16 || d == 32 || d == 64; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// B*H*L*d elements must stay addressable with a comfortable margin
+bool sizes_ok(long a, long b, long c, long d)
+{
+    const long lim = 1L << 40;
+    long n = a;
+    if (n > lim / b) return false;
+    n *= b;
+    if (n > lim / c) return false;
+    n *= c;
+    if (n > lim / d) return false;
+    return true;
+}
+
+int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return VIG_OK;
+    g_last_hip_error = int(e);
+    return VIG_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype)
+{
+    if (B <= 0 || H <= 0 || L <= 0 || !head_dim_ok(dk) || !head_dim_ok(dv)) return 0;
+    if (dtype != VIG_F32 && dtype != VIG_BF16) return 0;
+    const bool bf16 = dtype == VIG_BF16;
+    if (!sizes_ok(B, H, L, dk > dv ? dk : dv)) return 0;
+    const long BH = long(B) * H;
+    if (vig::bigla_chunk_supported(dk, dv, bf16)) return vig::bigla_chunk_workspace_bytes(BH, L);
+    return vig::bigla_recurrent_workspace_bytes(BH, L, dv, bf16);
+}
+
+int bigla_fwd(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd, void *out,
+              int B, int H, int L, int dk, int dv, int dtype, void *workspace, size_t workspace_bytes,
+              void *stream)
+{
+    if (!q || !k || !v || !g_fwd || !g_bwd || !out) return VIG_ERR_NULL;
+    if (B <= 0 || H <= 0 || L <= 0 || dk <= 0 || dv <= 0) return VIG_ERR_SHAPE;
+    if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
+    if (!head_dim_ok(dk) || !head_dim_ok(dv)) return VIG_ERR_UNSUPPORTED;
+    if (!sizes_ok(B, H, L, dk > dv ? dk : dv) || long(B) * H > 0x7fffffffL) return VIG_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g_fwd) || !aligned16(g_bwd) ||
+        !aligned16(out) || !aligned16(workspace))
+        return VIG_ERR_ALIGN;
+    const size_t need = bigla_workspace_bytes(B, H, L, dk, dv, dtype);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return VIG_ERR_WORKSPACE;
+
+    const bool bf16 = dtype == VIG_BF16;
+    const long BH = long(B) * H;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (vig::bigla_chunk_supported(dk, dv, bf16))
+        return hip_status(vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, workspace, s));
+    return hip_status(vig::bigla_recurrent_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, dv, bf16, workspace, s));
+}
+
+int locality_gate_fwd(const void *x, const void *w, const void *bias, const void *gate_logits,
+                      const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv, int dtype,
+                      void *stream)
+{
+    if (!x || !w || !gate_logits || !o_global || !out) return VIG_ERR_NULL;
+    if (B <= 0 || H <= 0 || Hg <= 0 || Wg <= 0 || dv <= 0) return VIG_ERR_SHAPE;
+    if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
+    if (!head_dim_ok(dv)) return VIG_ERR_UNSUPPORTED;
+    if (!sizes_ok(B, H, Hg, long(Wg) * dv) || long(Hg) * Wg > 0x7fffffffL) return VIG_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(gate_logits) || !aligned16(o_global) ||
+        !aligned16(out))
+        return VIG_ERR_ALIGN;
+    return hip_status(vig::locality_gate_launch(x, w, bias, gate_logits, o_global, out, B, H, Hg, Wg, dv,
+                                                dtype == VIG_BF16, static_cast<hipStream_t>(stream)));
+}
+
+const char *vig_status_str(int status)
+{
+    switch (status) {
+        case VIG_OK: return "VIG_OK";
+        case VIG_ERR_NULL: return "VIG_ERR_NULL: a required pointer is NULL";
+        case VIG_ERR_SHAPE: return "VIG_ERR_SHAPE: a size is <= 0 or too large";
+        case VIG_ERR_DTYPE: return "VIG_ERR_DTYPE: dtype is not VIG_F32 or VIG_BF16";
+        case VIG_ERR_UNSUPPORTED: return "VIG_ERR_UNSUPPORTED: dk and dv must be 16, 32 or 64";
+        case VIG_ERR_ALIGN: return "VIG_ERR_ALIGN: a pointer is not 16-byte aligned";
+        case VIG_ERR_WORKSPACE: return "VIG_ERR_WORKSPACE: workspace missing or too small";
+        case VIG_ERR_HIP: return "VIG_ERR_HIP: a HIP call failed (see vig_last_hip_error)";
+    }
+    return "unknown vig_status";
+}
+
+int vig_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

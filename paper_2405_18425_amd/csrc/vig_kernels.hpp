@@ -1,0 +1,26 @@
+// Internal launch interface between the C-ABI layer and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+namespace vig {
+
+// ---- exact fp32 recurrence (any supported head shape, both dtypes) --------------------------
+size_t bigla_recurrent_workspace_bytes(long BH, int L, int dv, bool is_bf16);
+hipError_t bigla_recurrent_launch(const void *q, const void *k, const void *v, const void *g_fwd,
+                                  const void *g_bwd, void *out, long BH, int L, int dk, int dv, bool is_bf16,
+                                  void *workspace, hipStream_t stream);
+
+// ---- chunkwise bf16 MFMA path (dk = dv = 64) -------------------------------------------------
+bool bigla_chunk_supported(int dk, int dv, bool is_bf16);
+size_t bigla_chunk_workspace_bytes(long BH, int L);
+hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                              void *out, long BH, int L, void *workspace, hipStream_t stream);
+
+// ---- depthwise 3x3 conv + sigmoid-gated blend -------------------------------------------------
+hipError_t locality_gate_launch(const void *x, const void *w, const void *bias, const void *gate_logits,
+                                const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv,
+                                bool is_bf16, hipStream_t stream);
+
+}  // namespace vig

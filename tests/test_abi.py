@@ -1,0 +1,98 @@
+"""The C-ABI library loads, exports what include/vig_bigla.h declares, and validates arguments
+on the host before anything is launched (CPU only: every call here returns before a launch)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2405_18425_amd import binding as vb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "vig_bigla.h")
+
+PTR = 0x10000  # a non-NULL, 16-byte aligned dummy: validation must reject before dereferencing
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"}
+
+
+def test_header_and_exports_agree():
+    names = declared_functions()
+    assert names == set(vb.EXPORTS)
+    lib = vb.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    for code in range(-7, 1):
+        s = vb.status_str(code)
+        assert s and "unknown" not in s
+    assert "unknown" in vb.status_str(5)
+    assert vb.lib().vig_last_hip_error() == 0
+
+
+def call_bigla(q=PTR, k=PTR, v=PTR, gf=PTR, gb=PTR, out=PTR, B=1, H=1, L=8, dk=16, dv=16, dtype=vb.VIG_F32,
+               ws=None, ws_bytes=0):
+    return vb.lib().bigla_fwd(q, k, v, gf, gb, out, B, H, L, dk, dv, dtype, ws, ws_bytes, None)
+
+
+def test_bigla_validation_codes():
+    for name in ("q", "k", "v", "gf", "gb", "out"):
+        assert call_bigla(**{name: None}) == vb.VIG_ERR_NULL
+    for name in ("B", "H", "L", "dk", "dv"):
+        assert call_bigla(**{name: 0}) == vb.VIG_ERR_SHAPE
+        assert call_bigla(**{name: -3}) == vb.VIG_ERR_SHAPE
+    assert call_bigla(dtype=7) == vb.VIG_ERR_DTYPE
+    assert call_bigla(dk=48) == vb.VIG_ERR_UNSUPPORTED
+    assert call_bigla(dv=128) == vb.VIG_ERR_UNSUPPORTED
+    assert call_bigla(q=PTR + 8) == vb.VIG_ERR_ALIGN
+    assert call_bigla(out=PTR + 2) == vb.VIG_ERR_ALIGN
+    assert call_bigla(B=1 << 20, H=1 << 20, L=1 << 20) == vb.VIG_ERR_SHAPE
+    # bf16 needs scratch for every shape
+    for dk, dv in ((16, 16), (64, 64), (32, 64)):
+        need = vb.bigla_workspace_bytes(2, 3, 100, dk, dv, vb.VIG_BF16)
+        assert need > 0
+        assert call_bigla(B=2, H=3, L=100, dk=dk, dv=dv, dtype=vb.VIG_BF16) == vb.VIG_ERR_WORKSPACE
+        assert call_bigla(B=2, H=3, L=100, dk=dk, dv=dv, dtype=vb.VIG_BF16, ws=PTR,
+                          ws_bytes=need - 1) == vb.VIG_ERR_WORKSPACE
+        assert call_bigla(B=2, H=3, L=100, dk=dk, dv=dv, dtype=vb.VIG_BF16, ws=PTR + 4,
+                          ws_bytes=need) == vb.VIG_ERR_ALIGN
+
+
+def test_workspace_query():
+    assert vb.bigla_workspace_bytes(1, 1, 64, 16, 16, vb.VIG_F32) == 0
+    assert vb.bigla_workspace_bytes(0, 1, 64, 16, 16, vb.VIG_F32) == 0
+    assert vb.bigla_workspace_bytes(1, 1, 64, 48, 16, vb.VIG_BF16) == 0
+    a = vb.bigla_workspace_bytes(8, 6, 4096, 64, 64, vb.VIG_BF16)
+    b = vb.bigla_workspace_bytes(16, 6, 4096, 64, 64, vb.VIG_BF16)
+    assert 0 < a < b and a % 16 == 0
+
+
+def call_loc(x=PTR, w=PTR, bias=None, z=PTR, og=PTR, out=PTR, B=1, H=1, Hg=4, Wg=4, dv=16, dtype=vb.VIG_BF16):
+    return vb.lib().locality_gate_fwd(x, w, bias, z, og, out, B, H, Hg, Wg, dv, dtype, None)
+
+
+def test_locality_validation_codes():
+    for name in ("x", "w", "z", "og", "out"):
+        assert call_loc(**{name: None}) == vb.VIG_ERR_NULL
+    for name in ("B", "H", "Hg", "Wg", "dv"):
+        assert call_loc(**{name: 0}) == vb.VIG_ERR_SHAPE
+    assert call_loc(dtype=-1) == vb.VIG_ERR_DTYPE
+    assert call_loc(dv=24) == vb.VIG_ERR_UNSUPPORTED
+    assert call_loc(bias=PTR + 6) == vb.VIG_ERR_ALIGN
+    assert call_loc(w=PTR + 1) == vb.VIG_ERR_ALIGN
+
+
+def test_binding_rejects_cpu_tensors():
+    import torch
+
+    t = torch.zeros(1, 1, 4, 16)
+    with pytest.raises(vb.VigError):
+        vb.bigla_fwd(t, t, t, t, t)
+    with pytest.raises(vb.VigError):
+        vb.locality_gate_fwd(t, torch.zeros(16, 3, 3), t, t, 2, 2)

@@ -1,0 +1,163 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on the
+same seeded stored inputs."""
+import numpy as np
+import pytest
+
+from paper_2405_18425_amd import workloads as wl
+from parity import (TOL, assert_close, run_bigla_gpu, run_bigla_oracle, run_locality_gpu,
+                    run_locality_oracle)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# --------------------------------------------------------------------------- #
+# BiGLA
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("cfg", range(5))
+def test_bigla_configs_reduced_batch(cfg):
+    """The five configurations at full L, H, dk, dv; batch cut to 2 so the oracle takes seconds."""
+    w = wl.CONFIGS[cfg]
+    w = w.replace(B=min(w.B, 2))
+    _say(f"bigla cfg{cfg} {w}")
+    s = wl.generate(w, seed=0, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+    got = run_bigla_gpu(s, w.dtype)
+    ref = run_bigla_oracle(s, w.dtype)
+    rel = assert_close(got, ref, TOL[w.dtype], f"cfg{cfg}")
+    _say(f"  max|err|/max|ref| = {rel:.3e}")
+
+
+@pytest.mark.parametrize("cfg", (1, 2, 3, 4))
+def test_bigla_full_size_sampled_slabs(cfg):
+    """Full benchmark size, same launch as bench.py; the oracle recomputes a sample of (b,h) slabs
+    (an output row depends on its whole slab and on nothing else)."""
+    w = wl.CONFIGS[cfg]
+    _say(f"bigla full cfg{cfg} {w}")
+    s = wl.generate(w, seed=0, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+    got = run_bigla_gpu(s, w.dtype)
+    assert np.all(np.isfinite(got))
+    rng = np.random.default_rng(cfg)
+    slabs = [(0, 0), (w.B - 1, w.H - 1)] + [(int(rng.integers(w.B)), int(rng.integers(w.H))) for _ in range(6)]
+    ref = run_bigla_oracle(s, w.dtype, slabs=slabs)
+    sel = np.stack([got[b, h] for (b, h) in slabs])
+    rel = assert_close(sel[None], ref[None], TOL[w.dtype], f"cfg{cfg} full")
+    _say(f"  max|err|/max|ref| = {rel:.3e}")
+
+
+EDGE_L = (1, 2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 196, 255, 256, 257, 300, 513, 1000)
+
+
+@pytest.mark.parametrize("dtype,dk,dv", [("bf16", 64, 64), ("f32", 64, 64), ("f32", 16, 16), ("bf16", 32, 64),
+                                         ("bf16", 16, 32), ("f32", 32, 16)])
+def test_bigla_ragged_lengths(dtype, dk, dv):
+    for L in EDGE_L:
+        w = wl.Workload(f"edge_L{L}", B=2, H=3, Hg=1, Wg=L, dk=dk, dv=dv, dtype=dtype, gate_mu=-1.0)
+        _say(f"bigla edge {dtype} dk{dk} dv{dv} L{L}")
+        s = wl.generate(w, seed=L, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+        assert_close(run_bigla_gpu(s, dtype), run_bigla_oracle(s, dtype), TOL[dtype], f"L={L}")
+
+
+@pytest.mark.parametrize("dtype", ("bf16", "f32"))
+@pytest.mark.parametrize("gate", ("zero", "minus4", "minus40", "mixed_spikes", "tiny"))
+def test_bigla_adversarial_gates(dtype, gate):
+    """Degenerate gates: alpha = 1 everywhere, very fast decay, isolated hard resets, near-one."""
+    w = wl.Workload("adv", B=2, H=2, Hg=1, Wg=333, dk=64, dv=64, dtype=dtype, gate_mu=0.0)
+    _say(f"bigla adversarial {dtype} {gate}")
+    s = wl.generate(w, seed=11, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+    shape = (w.B, w.H, w.L, w.dk)
+    if gate == "zero":
+        g = np.zeros(shape)
+    elif gate == "minus4":
+        g = np.full(shape, -4.0)
+    elif gate == "minus40":
+        g = np.full(shape, -40.0)
+    elif gate == "tiny":
+        g = np.full(shape, -1e-3)
+    else:
+        r = np.random.default_rng(5)
+        g = -0.05 * r.random(shape)
+        g[r.random(shape) < 0.02] = -30.0
+    s["g_fwd"] = wl.store(g, dtype)
+    s["g_bwd"] = wl.store(g[:, :, ::-1].copy(), dtype)
+    assert_close(run_bigla_gpu(s, dtype), run_bigla_oracle(s, dtype), TOL[dtype], gate)
+
+
+@pytest.mark.parametrize("dtype", ("bf16", "f32"))
+def test_bigla_deterministic_and_stream(dtype):
+    import torch
+    from paper_2405_18425_amd import binding as vb
+
+    w = wl.Workload("det", B=3, H=2, Hg=1, Wg=777, dk=64, dv=64, dtype=dtype, gate_mu=0.0)
+    s = wl.generate(w, seed=3, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+    t = {n: wl.to_torch(a, dtype, "cuda:0") for n, a in s.items()}
+    a = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"])
+    b = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        c = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"])
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(a, c)
+    # a dirty workspace and a dirty output buffer must not matter
+    need = vb.bigla_workspace_bytes(w.B, w.H, w.L, w.dk, w.dv, vb.VIG_BF16 if dtype == "bf16" else vb.VIG_F32)
+    ws = torch.full((max(need, 16),), 0xAB, dtype=torch.uint8, device="cuda:0")
+    out = torch.full_like(a, float("nan"))
+    d = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], out=out, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a, d)
+
+
+# --------------------------------------------------------------------------- #
+# locality gate
+# --------------------------------------------------------------------------- #
+def _loc_inputs(w, seed):
+    s = wl.generate(w, seed=seed, tensors=("v", "conv_w", "gate_logits"))
+    og = wl.store(wl.normal(seed, "o_global_standin", (w.B, w.H, w.L, w.dv)) / 2.0, w.dtype)
+    return s["v"], s["conv_w"], s["gate_logits"], og
+
+
+@pytest.mark.parametrize("cfg", range(5))
+def test_locality_configs_full_size(cfg):
+    w = wl.CONFIGS[cfg]
+    _say(f"locality cfg{cfg} {w}")
+    x, cw, z, og = _loc_inputs(w, 0)
+    got = run_locality_gpu(x, cw, z, og, w.Hg, w.Wg, w.dtype)
+    ref = run_locality_oracle(x, cw, z, og, w.Hg, w.Wg, w.dtype)
+    # the only bf16 rounding is the final store (and fp32 vs fp64 arithmetic before it)
+    assert_close(got, ref, 8e-3 if w.dtype == "bf16" else 1e-5, f"locality cfg{cfg}")
+
+
+@pytest.mark.parametrize("dtype", ("bf16", "f32"))
+@pytest.mark.parametrize("Hg,Wg,dv", [(1, 1, 16), (1, 9, 64), (9, 1, 64), (2, 2, 32), (3, 5, 16), (14, 14, 64),
+                                      (17, 33, 64), (33, 17, 32), (8, 64, 64)])
+def test_locality_edge_grids(dtype, Hg, Wg, dv):
+    w = wl.Workload("loc_edge", B=2, H=3, Hg=Hg, Wg=Wg, dk=dv, dv=dv, dtype=dtype, gate_mu=0.0)
+    _say(f"locality edge {dtype} {Hg}x{Wg} dv{dv}")
+    x, cw, z, og = _loc_inputs(w, Hg * 100 + Wg)
+    bias = wl.store(wl.normal(1, "bias", (w.H * dv,)), dtype)
+    for b in (None, bias):
+        got = run_locality_gpu(x, cw, z, og, Hg, Wg, dtype, bias=b)
+        ref = run_locality_oracle(x, cw, z, og, Hg, Wg, dtype, bias=b)
+        assert_close(got, ref, 8e-3 if dtype == "bf16" else 1e-5, f"{Hg}x{Wg}")
+
+
+def test_path_end_to_end_config0():
+    """BiGLA then the locality gate on v, as the benchmark chains them (x := v, o_global := BiGLA out)."""
+    import torch
+    from paper_2405_18425_amd import binding as vb
+    import oracle
+
+    w = wl.CONFIGS[0]
+    s = wl.generate(w, seed=0)
+    t = {n: wl.to_torch(a, w.dtype, "cuda:0") for n, a in s.items()}
+    og = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"])
+    out = vb.locality_gate_fwd(t["v"], t["conv_w"], t["gate_logits"], og, w.Hg, w.Wg)
+    torch.cuda.synchronize()
+    wd = {n: wl.widen(a, w.dtype) for n, a in s.items()}
+    ref_og = oracle.bigla(wd["q"], wd["k"], wd["v"], wd["g_fwd"], wd["g_bwd"])
+    ref = oracle.locality_gate(wd["v"], wd["conv_w"], wd["gate_logits"], ref_og, w.Hg, w.Wg)
+    assert_close(wl.widen(wl.from_torch(out, w.dtype), w.dtype), ref, TOL[w.dtype], "end to end")
