@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the BiGLA + locality-gate forward on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic input:
+bigla_fwd(q, k, v, g_fwd, g_bwd) -> o_global, then locality_gate_fwd(x := v, w, z, o_global).
+Default workload: the high-resolution ViG-S-shaped block (B=8, H=6, 64x64 grid, L=4096,
+dk=dv=64, bf16) -- the configuration the headline metric is quoted on.
+
+Inputs are resident in HBM before the timed region.  The timed loop rotates through several
+independent buffer sets whose total size exceeds the 256 MB Infinity Cache, so that every step
+streams its operands from HBM rather than from a warm cache.
+
+Prints ONE JSON line (see the design doc for the fields).  `roofline` times the dominant kernel
+with HIP events recorded on its own stream inside the library (a second pass of the same K
+steps, so that event recording does not perturb `value`); `cpu_baseline` times the CPU oracle
+on the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA peak
+CACHE_BYTES = 256 << 20        # Infinity Cache; buffer sets rotate over more than this
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/), keyed by (kernel, workload); None until measured for that pair.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="workload index (paper_2405_18425_amd.workloads.CONFIGS)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget-s", type=float, default=12.0)
+    ap.add_argument("--single-set", action="store_true", help="reuse one buffer set (cache-warm timing)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU; multi-GPU runs are not part of it "
+              "(the path shards over (batch, head) slabs with no exchange -- see DESIGN.md).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2405_18425_amd import binding as vb
+    from paper_2405_18425_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    vb.lib()  # fail loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    w = wl.CONFIGS[args.config]
+    esize = 2 if w.dtype == "bf16" else 4
+
+    # ---- inputs: one seeded set on the host, further sets are batch-rotated copies on the device
+    stored = wl.generate(w, seed=args.seed)
+    base = {n: wl.to_torch(a, w.dtype, dev) for n, a in stored.items()}
+    set_bytes = sum(t.numel() * t.element_size() for t in base.values()) + 2 * base["v"].numel() * esize
+    n_sets = 1 if args.single_set else max(2, -(-2 * CACHE_BYTES // set_bytes))
+    sets = []
+    for i in range(n_sets):
+        s = {n: (t if i == 0 or n == "conv_w" else torch.roll(t, shifts=i, dims=0).contiguous())
+             for n, t in base.items()}
+        s["o_global"] = torch.empty_like(s["v"])
+        s["out"] = torch.empty_like(s["v"])
+        sets.append(s)
+    code = vb.VIG_BF16 if w.dtype == "bf16" else vb.VIG_F32
+    ws_bytes = vb.bigla_workspace_bytes(w.B, w.H, w.L, w.dk, w.dv, code)
+    workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
+    def step(i):
+        s = sets[i % n_sets]
+        vb.bigla_fwd(s["q"], s["k"], s["v"], s["g_fwd"], s["g_bwd"], out=s["o_global"], workspace=workspace)
+        vb.locality_gate_fwd(s["v"], s["conv_w"], s["gate_logits"], s["o_global"], w.Hg, w.Wg, out=s["out"])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = w.tokens / (ms_per_step * 1e-3)
+
+    # ---- per-kernel durations: same K steps again, events recorded by the library on its stream
+    vb.timing_enable(True)
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    kern = {}
+    for name in vb.KERNELS:
+        ms, n = vb.timing_collect(name)
+        if n:
+            kern[name] = {"avg_us": ms * 1e3 / n, "launches_per_step": n / args.steps}
+    vb.timing_enable(False)
+
+    # ---- roofline of the dominant kernel (algorithmic bytes / flops per head-token)
+    dominant = max(kern, key=lambda n: kern[n]["avg_us"] * kern[n]["launches_per_step"])
+    ht = w.head_tokens
+    bigla_bytes = (4 * w.dk + 2 * w.dv) * esize * ht          # q,k,g_fwd,g_bwd,v read once, out written once
+    bigla_flops = (8 * w.dk * w.dv + 2 * 64 * (w.dk + w.dv)) * ht  # chunkwise form at the nominal chunk of 64
+    loc_bytes = 4 * esize * ht * w.dv                          # x, z, o_global read; out written
+    if dominant == "locality_gate":
+        alg_bytes = loc_bytes
+    else:
+        alg_bytes = bigla_bytes  # the BiGLA launches share one algorithmic budget; the dominant one is charged all of it
+    dom_us = kern[dominant]["avg_us"]
+    achieved_gbs = alg_bytes / (dom_us * 1e-6) / 1e9
+    roofline = {
+        "kernel": dominant, "bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
+        "traffic": MEASURED_TRAFFIC_BYTES.get((dominant, w.name)),
+        "avg_us": round(dom_us, 2), "algorithmic_bytes": alg_bytes,
+    }
+    bigla_us = sum(kern[n]["avg_us"] * kern[n]["launches_per_step"]
+                   for n in ("segment_state", "state_scan", "segment_out", "recurrent") if n in kern)
+    extra = {
+        "kernels_us": {n: round(k["avg_us"] * k["launches_per_step"], 2) for n, k in kern.items()},
+        "bigla_us": round(bigla_us, 2),
+        "bigla_tokens_per_s": round(w.tokens / (bigla_us * 1e-6), 1),
+        "bigla_tflops": round(bigla_flops / (bigla_us * 1e-6) / 1e12, 2),
+        "bigla_frac_bf16_mfma_peak": round(bigla_flops / (bigla_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "bigla_hbm_gbs": round(bigla_bytes / (bigla_us * 1e-6) / 1e9, 1),
+        "bigla_frac_hbm_peak": round(bigla_bytes / (bigla_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+    if "locality_gate" in kern:
+        lus = kern["locality_gate"]["avg_us"]
+        extra["locality_hbm_gbs"] = round(loc_bytes / (lus * 1e-6) / 1e9, 1)
+        extra["locality_frac_hbm_peak"] = round(loc_bytes / (lus * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+
+    # ---- CPU oracle on the host cores (reported baseline, not the target)
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        wd = {n: wl.widen(a, w.dtype) for n, a in stored.items()}
+        best, spent, reps = float("inf"), 0.0, 0
+        while reps < 3 or (spent < args.cpu_budget_s and reps < 20):
+            c0 = time.perf_counter()
+            og = oracle.bigla(wd["q"], wd["k"], wd["v"], wd["g_fwd"], wd["g_bwd"])
+            oracle.locality_gate(wd["v"], wd["conv_w"], wd["gate_logits"], og, w.Hg, w.Wg)
+            dt = time.perf_counter() - c0
+            best, spent, reps = min(best, dt), spent + dt, reps + 1
+            if spent > 3 * args.cpu_budget_s:
+                break
+        cpu = {"value": round(w.tokens / best, 1), "unit": "tokens/s", "cores": oracle.max_threads(),
+               "kind": "oracle",
+               "sample": f"the whole workload ({w.B * w.H} slabs of L={w.L}), fp64, best of {reps} passes "
+                         f"({spent:.1f} s of CPU work)"}
+
+    line = {
+        "metric": "BiGLA fwd tokens/sec and % bf16 MFMA peak at L=4096, H=6, d=64 (1 GPU)",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "L": w.L, "grid": [w.Hg, w.Wg], "dk": w.dk, "dv": w.dv,
+                   "gate_logit_mean": w.gate_mu, "buffer_sets": n_sets, "set_bytes": set_bytes},
+        "roofline": roofline, "cpu_baseline": cpu, "detail": extra,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

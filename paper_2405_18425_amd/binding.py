@@ -21,7 +21,9 @@ VIG_ERR_ALIGN, VIG_ERR_WORKSPACE, VIG_ERR_HIP = -5, -6, -7
 VIG_F32, VIG_BF16 = 0, 1
 
 # every symbol include/vig_bigla.h declares
-EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "locality_gate_fwd", "vig_status_str", "vig_last_hip_error")
+EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "locality_gate_fwd", "vig_status_str", "vig_last_hip_error",
+           "vig_timing_enable", "vig_timing_collect")
+KERNELS = {"segment_state": 0, "state_scan": 1, "segment_out": 2, "recurrent": 3, "locality_gate": 4}
 
 _lib = None
 
@@ -51,6 +53,10 @@ def lib() -> ctypes.CDLL:
         L.vig_status_str.restype = ctypes.c_char_p
         L.vig_last_hip_error.argtypes = []
         L.vig_last_hip_error.restype = ci
+        L.vig_timing_enable.argtypes = [ci]
+        L.vig_timing_enable.restype = ci
+        L.vig_timing_collect.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_long)]
+        L.vig_timing_collect.restype = ci
         _lib = L
     return _lib
 
@@ -153,3 +159,15 @@ def locality_gate_fwd(x, w, gate_logits, o_global, Hg: int, Wg: int, bias=None, 
                                      _dtype_code(x), _stream_ptr(x.device))
     _check(st, "locality_gate_fwd")
     return out
+
+
+def timing_enable(on: bool) -> None:
+    """Start (and clear) or stop per-kernel HIP-event timing of this thread's launches."""
+    _check(lib().vig_timing_enable(1 if on else 0), "vig_timing_enable")
+
+
+def timing_collect(kernel: str):
+    """(total milliseconds, launches) of one kernel since timing was enabled."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_long(0)
+    _check(lib().vig_timing_collect(KERNELS[kernel], ctypes.byref(ms), ctypes.byref(n)), "vig_timing_collect")
+    return ms.value, n.value

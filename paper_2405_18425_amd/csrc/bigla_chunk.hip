@@ -1,11 +1,751 @@
-// placeholder until the chunkwise MFMA kernels land
+// Chunkwise bf16 MFMA evaluation of BiGLA (Section 4.2.1, Eq. (BiGLA)) for dk = dv = 64.
+//
+// The recurrence S_t = diag(alpha_t) S_{t-1} + k_t^T v_t, o_t = q_t S_t is regrouped exactly
+// (no approximation beyond bf16 operand rounding) over chunks of 64 tokens.  With b_t the
+// cumulative log-gate inside a chunk,
+//   o_t = sum_{i<=t, same chunk} (sum_c q_tc k_ic exp(b_tc - b_ic)) v_i   (intra-chunk, masked)
+//       + (q_t * exp(b_t)) S_in                                           (inter-chunk readout)
+//   S_out = diag(exp(b_end)) S_in + sum_i (k_i * exp(b_end - b_i))^T v_i  (state passing)
+// and the backward direction is the mirror image (suffix sums, keys to the right).  Every
+// contraction runs on v_mfma_f32_16x16x32_bf16 with fp32 accumulation; the carried state stays
+// fp32 in accumulator registers and only its readout copy is rounded to bf16.
+//
+// Numerical range.  exp(b_t - b_i) is never formed as exp(b_t) * exp(-b_i) across a whole
+// chunk.  A chunk is cut into four sub-blocks of 16 tokens; cumulative gates are local to a
+// sub-block (DPP row scans inside one wavefront).  Off-diagonal 16x16 tiles scale keys by the
+// decay to the END of the key's own sub-block and queries by the decay from the START of the
+// query's sub-block times the whole-sub-block factors in between, so every factor is <= 1 and
+// underflow to 0 is the correct limit.  The diagonal tile refers both sides to the MIDDLE of
+// the sub-block, so its factors span at most 8 steps of decay in either sense; with the
+// per-step log-gate floored at -8 (alpha >= 3.4e-4; anything smaller is a hard reset whose
+// leak is far below the bf16 tolerance) they stay within e^(+-64), inside fp32 and bf16 range.
+// Masking is by select, never by multiplying with 0.
+//
+// Parallel decomposition.  A sequence is cut into segments of kSegChunks chunks.
+//   1. bigla_segment_state_kernel : one workgroup per (slab, segment) computes, for BOTH
+//      directions in one pass over k, v, g, the segment's local end state and total decay.
+//   2. bigla_state_scan_kernel    : per state element, the sequential scan over segments in
+//      both directions turns local states into the states ENTERING each segment (in place).
+//   3. bigla_segment_out_kernel   : one workgroup per (slab, segment) sweeps its chunks
+//      left-to-right for the forward direction and right-to-left for the backward direction,
+//      holding the fp32 output tiles in registers between the sweeps, and writes
+//      (o_fwd + o_bwd)/2 once.  Sequences of at most one segment need only this launch.
+// Nothing is reversed or copied in HBM; both directions read the same q, k, v.
+//
+// Wavefront mapping (256 threads = 4 waves).  Wave w owns tokens [16w, 16w+16) of the chunk;
+// lane (r = lane%16, g = lane/16) holds channels {8g..8g+7} and {32+8g..32+8g+7} of token
+// 16w + r, which is exactly the A/B operand layout of the 16x16x32 MFMA (row r, k-slots
+// 8g..8g+7) for contractions over channels.  Contractions over tokens (P.V and the state
+// update) take their token-major operands from row-major LDS tiles through ds_read_b64_tr_b16.
+#include "vig_common.hpp"
 #include "vig_kernels.hpp"
+#include "vig_timing.hpp"
+
 namespace vig {
-bool bigla_chunk_supported(int, int, bool) { return false; }
-size_t bigla_chunk_workspace_bytes(long, int) { return 0; }
-hipError_t bigla_chunk_launch(const void *, const void *, const void *, const void *, const void *, void *, long, int,
-                              void *, hipStream_t)
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+constexpr int kC = 64;          // chunk length (tokens)
+constexpr int kD = 64;          // dk = dv
+constexpr int kPitch = 72;      // LDS row pitch in bf16 elements (64 + 8: 16-byte aligned, bank-staggered)
+constexpr int kSegChunks = 4;   // chunks per segment (ring of output tiles held in registers)
+constexpr int kThreads = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kGateFloorLog2 = -8.0f * kLog2e;  // per-step floor of the log-gate, log2 domain
+
+// ---- small device helpers ------------------------------------------------------------------
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_or_zero(float x)
 {
-    return hipErrorNotSupported;
+    // lanes whose DPP source falls outside the 16-lane row receive 0
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
 }
+
+// Inclusive scan over the 16 lanes of a DPP row: prefix (DIR 0) or suffix (DIR 1).
+template <int DIR>
+__device__ __forceinline__ float row_scan(float x)
+{
+    if (DIR == 0) {
+        x += dpp_or_zero<0x111>(x);  // row_shr:1
+        x += dpp_or_zero<0x112>(x);
+        x += dpp_or_zero<0x114>(x);
+        x += dpp_or_zero<0x118>(x);
+    } else {
+        x += dpp_or_zero<0x101>(x);  // row_shl:1
+        x += dpp_or_zero<0x102>(x);
+        x += dpp_or_zero<0x104>(x);
+        x += dpp_or_zero<0x108>(x);
+    }
+    return x;
+}
+
+// Row-wide broadcasts (row_newbcast:n).  In scan order the far-edge lane holds the sub-block
+// total (lane 15 for the prefix scan, lane 0 for the suffix scan); the middle lane is the last
+// lane of the first half in scan order (lane 7 / lane 8).
+template <int DIR>
+__device__ __forceinline__ float bcast_far(float x)
+{
+    return DIR == 0 ? dpp_or_zero<0x15f>(x) : dpp_or_zero<0x150>(x);
+}
+template <int DIR>
+__device__ __forceinline__ float bcast_mid(float x)
+{
+    return DIR == 0 ? dpp_or_zero<0x157>(x) : dpp_or_zero<0x158>(x);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi)
+{
+    f32x2 a = {lo, hi};
+    bf16x2 b = __builtin_convertvector(a, bf16x2);  // v_cvt_pk_bf16_f32, round to nearest even
+    return __builtin_bit_cast(uint32_t, b);
+}
+
+__device__ __forceinline__ bf16x8 pack8(const float *f)
+{
+    uint4 u;
+    u.x = pack2(f[0], f[1]);
+    u.y = pack2(f[2], f[3]);
+    u.z = pack2(f[4], f[5]);
+    u.w = pack2(f[6], f[7]);
+    return __builtin_bit_cast(bf16x8, u);
+}
+
+__device__ __forceinline__ void unpack8(const uint4 &u, float *f)
+{
+    f[0] = bf16_lo_to_f32(u.x); f[1] = bf16_hi_to_f32(u.x);
+    f[2] = bf16_lo_to_f32(u.y); f[3] = bf16_hi_to_f32(u.y);
+    f[4] = bf16_lo_to_f32(u.z); f[5] = bf16_hi_to_f32(u.z);
+    f[6] = bf16_lo_to_f32(u.w); f[7] = bf16_hi_to_f32(u.w);
+}
+
+__device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// Transposing LDS read: the 16 lanes of a row fetch a 4 (tokens) x 16 (columns) bf16 patch of a
+// row-major tile; lane n of the row receives the 4 tokens of column n.  Lane n supplies the
+// address of token n/4, columns 4*(n%4).. of the patch.
+__device__ __forceinline__ s16x4 lds_read_tr(const uint16_t *p)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
+}
+
+__device__ __forceinline__ bf16x8 join(s16x4 lo, s16x4 hi)
+{
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// 16 channels of one token: two 16-byte pieces at channel offsets 8g and 32+8g
+struct Row16 {
+    uint4 p[2];
+};
+
+__device__ __forceinline__ Row16 load_row16(const uint16_t *slab_base, long token, bool valid, int g)
+{
+    Row16 r;
+    if (valid) {
+        const uint4 *p = reinterpret_cast<const uint4 *>(slab_base + token * kD + 8 * g);
+        r.p[0] = p[0];
+        r.p[1] = p[4];  // +32 elements
+    } else {
+        r.p[0] = make_uint4(0, 0, 0, 0);
+        r.p[1] = make_uint4(0, 0, 0, 0);
+    }
+    return r;
+}
+
+__device__ __forceinline__ void unpack16(const Row16 &r, float (&f)[16])
+{
+    unpack8(r.p[0], f);
+    unpack8(r.p[1], f + 8);
+}
+
+__device__ __forceinline__ void store_row16(uint16_t (*tile)[kPitch], int row, int g, const float (&f)[16])
+{
+    uint4 a, b;
+    a.x = pack2(f[0], f[1]); a.y = pack2(f[2], f[3]); a.z = pack2(f[4], f[5]); a.w = pack2(f[6], f[7]);
+    b.x = pack2(f[8], f[9]); b.y = pack2(f[10], f[11]); b.z = pack2(f[12], f[13]); b.w = pack2(f[14], f[15]);
+    *reinterpret_cast<uint4 *>(&tile[row][8 * g]) = a;
+    *reinterpret_cast<uint4 *>(&tile[row][32 + 8 * g]) = b;
+}
+
+__device__ __forceinline__ void store_row16_raw(uint16_t (*tile)[kPitch], int row, int g, const Row16 &r)
+{
+    *reinterpret_cast<uint4 *>(&tile[row][8 * g]) = r.p[0];
+    *reinterpret_cast<uint4 *>(&tile[row][32 + 8 * g]) = r.p[1];
+}
+
+// the lane's 16 channels of a per-channel fp32 vector in LDS
+__device__ __forceinline__ void load_chan16(const float *vec, int g, float (&f)[16])
+{
+    const float4 *a = reinterpret_cast<const float4 *>(vec + 8 * g);
+    const float4 *b = reinterpret_cast<const float4 *>(vec + 32 + 8 * g);
+    float4 t;
+    t = a[0]; f[0] = t.x; f[1] = t.y; f[2] = t.z; f[3] = t.w;
+    t = a[1]; f[4] = t.x; f[5] = t.y; f[6] = t.z; f[7] = t.w;
+    t = b[0]; f[8] = t.x; f[9] = t.y; f[10] = t.z; f[11] = t.w;
+    t = b[1]; f[12] = t.x; f[13] = t.y; f[14] = t.z; f[15] = t.w;
+}
+
+__device__ __forceinline__ void store_chan16(float *vec, int g, const float (&f)[16])
+{
+    float4 *a = reinterpret_cast<float4 *>(vec + 8 * g);
+    float4 *b = reinterpret_cast<float4 *>(vec + 32 + 8 * g);
+    a[0] = make_float4(f[0], f[1], f[2], f[3]);
+    a[1] = make_float4(f[4], f[5], f[6], f[7]);
+    b[0] = make_float4(f[8], f[9], f[10], f[11]);
+    b[1] = make_float4(f[12], f[13], f[14], f[15]);
+}
+
+// Logical order of the four sub-blocks as seen from sub-block w in direction DIR:
+// slot 0 = w itself, slots 1..nb = the sub-blocks whose keys w's queries see (nearest first),
+// remaining slots = the sub-blocks after w (nearest first).
+template <int DIR>
+struct SubOrder {
+    int w, nb;
+    __device__ __forceinline__ explicit SubOrder(int w_) : w(w_), nb(DIR == 0 ? w_ : 3 - w_) {}
+    __device__ __forceinline__ int before(int d) const { return DIR == 0 ? w - d : w + d; }  // 1 <= d <= nb
+    __device__ __forceinline__ int after(int a) const { return DIR == 0 ? w + a : w - a; }   // 1 <= a <= 3-nb
+    __device__ __forceinline__ int slot(int s) const { return s == 0 ? w : (s <= nb ? before(s) : after(s - nb)); }
+};
+
+// Cumulative log2-gates of the lane's 16 channels inside its sub-block, inclusive of the lane's
+// own token, in scan order (prefix for DIR 0, suffix for DIR 1).  Floored per step, capped at 0.
+template <int DIR>
+__device__ __forceinline__ void gate_scan(const Row16 &graw, float (&b)[16])
+{
+    unpack16(graw, b);
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+        b[e] = row_scan<DIR>(__builtin_amdgcn_fmed3f(b[e] * kLog2e, kGateFloorLog2, 0.f));
+}
+
+// Gate factors of the output sweep for the lane's token t and 16 channels, with B_mid the
+// cumulative gate at the middle lane and B_tot the sub-block total:
+//   X    = exp(b_t - B_mid)      Y = 1/X = exp(B_mid - b_t)       (diagonal tile: q*X, k*Y)
+//   F    = exp(B_tot - b_t)      decay from t (exclusive) to the far edge      (keys, <= 1)
+//   Emid = exp(B_mid)            so that exp(b_t) = X * Emid                    (queries, <= 1)
+//   EB   = exp(B_tot)            whole-sub-block decay
+// Two transcendentals per element: the middle lane's own Y is 1 by definition, so its slot of
+// the second exp2 evaluates Emid instead, which a row broadcast then hands to every lane.
+template <int DIR>
+__device__ __forceinline__ void gate_factors(const Row16 &graw, int r, float (&X)[16], float (&Y)[16],
+                                             float (&F)[16], float (&Emid)[16], float (&EB)[16])
+{
+    float b[16];
+    gate_scan<DIR>(graw, b);
+    const bool is_mid = r == (DIR == 0 ? 7 : 8);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const float xa = b[e] - bcast_mid<DIR>(b[e]);
+        X[e] = fast_exp2(xa);
+        const float yraw = fast_exp2(is_mid ? b[e] : -xa);
+        Emid[e] = bcast_mid<DIR>(yraw);
+        Y[e] = is_mid ? 1.f : yraw;
+        const float xfar = bcast_far<DIR>(X[e]);
+        F[e] = Y[e] * xfar;
+        EB[e] = Emid[e] * xfar;
+    }
+}
+
+// Gate factors of the state pass: F and EB only.
+template <int DIR>
+__device__ __forceinline__ void gate_factors_state(const Row16 &graw, float (&F)[16], float (&EB)[16])
+{
+    float b[16];
+    gate_scan<DIR>(graw, b);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const float btot = bcast_far<DIR>(b[e]);
+        F[e] = fast_exp2(btot - b[e]);
+        EB[e] = fast_exp2(btot);
+    }
+}
+
+// ---- shared memory ---------------------------------------------------------------------------
+
+struct __align__(16) OutLds {
+    uint16_t khat[kC][kPitch];  // k * F                     [token][channel]  (intra-chunk keys)
+    uint16_t ks[kC][kPitch];    // k * exp(decay to chunk edge) [token][channel]  (state update keys)
+    uint16_t v[kC][kPitch];     // values                    [token][column]
+    uint16_t st[kD][kPitch];    // carried state, bf16 copy  [column][channel]  (readout operand)
+    float eb[4][kD];            // whole-sub-block decay factor per channel
+};
+
+struct __align__(16) StateLds {
+    uint16_t ks[2][kC][kPitch];
+    uint16_t v[kC][kPitch];
+    float eb[2][4][kD];
+};
+
+// Workspace layout per (slab, segment): two fp32 64x64 states then two fp32 decay vectors.
+constexpr size_t kSegStateFloats = 2 * size_t(kD) * kD;
+constexpr size_t kSegFloats = kSegStateFloats + 2 * kD;
+
+// ---- kernel 3: per-segment output sweep -------------------------------------------------------
+
+// One chunk of one direction.  O accumulates this chunk's output tile (rows 16w + 4g + e,
+// column 16*jt + r); S is this wave's 16 rows of the carried fp32 state.
+template <int DIR>
+__device__ __forceinline__ void out_chunk_step(OutLds &sm, const int w, const int r, const int g, const Row16 &qraw,
+                                               const Row16 &kraw, const Row16 &graw, const Row16 &vraw, f32x4 (&O)[4],
+                                               f32x4 (&S)[4])
+{
+    const SubOrder<DIR> ord(w);
+    const int row = 16 * w + r;
+
+    float X[16], Y[16], F[16], Emid[16], EB[16];
+    gate_factors<DIR>(graw, r, X, Y, F, Emid, EB);
+    if (r == 0) store_chan16(sm.eb[w], g, EB);  // whole-sub-block decay exp(B_w)
+    store_row16_raw(sm.v, row, g, vraw);
+
+    float qf[16], kf[16];
+    unpack16(qraw, qf);
+    unpack16(kraw, kf);
+    float khat[16], tmp[16], cum[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) khat[e] = kf[e] * F[e];
+    store_row16(sm.khat, row, g, khat);
+    // diagonal tile operands, both referred to the middle of the sub-block
+#pragma unroll
+    for (int e = 0; e < 16; ++e) tmp[e] = kf[e] * Y[e];
+    const bf16x8 kd0 = pack8(tmp), kd1 = pack8(tmp + 8);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) cum[e] = qf[e] * X[e];
+    const bf16x8 qd0 = pack8(cum), qd1 = pack8(cum + 8);
+
+    __syncthreads();  // eb, v, khat visible
+
+    // query variants: qv[d] pairs with the keys of before(d+1); readout uses the full product.
+    // q * exp(b_t) = (q * X) * Emid is the decay since the near edge of the query's sub-block.
+#pragma unroll
+    for (int e = 0; e < 16; ++e) cum[e] *= Emid[e];
+    bf16x8 qv[3][2];
+    qv[0][0] = pack8(cum);
+    qv[0][1] = pack8(cum + 8);
+#pragma unroll
+    for (int d = 1; d <= 3; ++d) {
+        if (d <= ord.nb) {
+            load_chan16(sm.eb[ord.before(d)], g, tmp);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) cum[e] *= tmp[e];
+            if (d < 3) {
+                qv[d][0] = pack8(cum);
+                qv[d][1] = pack8(cum + 8);
+            }
+        }
+    }
+    const bf16x8 qr0 = pack8(cum), qr1 = pack8(cum + 8);  // readout queries: q * exp(decay since chunk edge)
+
+    // state-update keys: khat times the whole sub-blocks after this one
+#pragma unroll
+    for (int a = 1; a <= 3; ++a) {
+        if (a <= 3 - ord.nb) {
+            load_chan16(sm.eb[ord.after(a)], g, tmp);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) khat[e] *= tmp[e];
+        }
+    }
+    store_row16(sm.ks, row, g, khat);
+
+    __syncthreads();  // ks visible
+
+    // ---- intra-chunk scores, transposed: P^T[i][t] = sum_c khat[i][c] * qv[t][c] ----------------
+    // result layout: lane holds keys i = 4g..4g+3 of the tile for query t = r
+    uint2 pk[4];  // bf16 scores per logical slot
+    {
+        f32x4 p = {0.f, 0.f, 0.f, 0.f};
+        p = mfma(kd0, qd0, p);
+        p = mfma(kd1, qd1, p);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = 4 * g + e;
+            const bool keep = DIR == 0 ? (i <= r) : (i >= r);  // own token included in both directions
+            p[e] = keep ? p[e] : 0.f;
+        }
+        pk[0] = make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3]));
+    }
+#pragma unroll
+    for (int d = 1; d <= 3; ++d) {
+        if (d <= ord.nb) {
+            const int kb = ord.before(d);
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.khat[16 * kb + r][8 * g]);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.khat[16 * kb + r][32 + 8 * g]);
+            f32x4 p = {0.f, 0.f, 0.f, 0.f};
+            p = mfma(a0, qv[d - 1][0], p);
+            p = mfma(a1, qv[d - 1][1], p);
+            pk[d] = make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3]));
+        } else {
+            pk[d] = make_uint2(0u, 0u);
+        }
+    }
+
+    // ---- token-major operands: values (shared by P.V and the state update) ---------------------
+    // k-slot layout of a token contraction: slots 0..3 = tokens 4g..4g+3 of sub-block slot(2p),
+    // slots 4..7 = the same tokens of sub-block slot(2p+1)
+    const int tr_row = 4 * g + (r >> 2), tr_col = 4 * (r & 3);
+    bf16x8 vop[2][4];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int s0 = ord.slot(2 * p), s1 = ord.slot(2 * p + 1);
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt)
+            vop[p][jt] = join(lds_read_tr(&sm.v[16 * s0 + tr_row][16 * jt + tr_col]),
+                              lds_read_tr(&sm.v[16 * s1 + tr_row][16 * jt + tr_col]));
+    }
+
+    // ---- O += P.V (visible sub-blocks only) + readout of the incoming state ---------------------
+    {
+        const bf16x8 pa0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0].x, pk[0].y, pk[1].x, pk[1].y));
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(pa0, vop[0][jt], O[jt]);
+        if (ord.nb >= 2) {
+            const bf16x8 pa1 = __builtin_bit_cast(bf16x8, make_uint4(pk[2].x, pk[2].y, pk[3].x, pk[3].y));
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(pa1, vop[1][jt], O[jt]);
+        }
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            const bf16x8 b0 = *reinterpret_cast<const bf16x8 *>(&sm.st[16 * jt + r][8 * g]);
+            const bf16x8 b1 = *reinterpret_cast<const bf16x8 *>(&sm.st[16 * jt + r][32 + 8 * g]);
+            O[jt] = mfma(qr0, b0, O[jt]);
+            O[jt] = mfma(qr1, b1, O[jt]);
+        }
+    }
+
+    // ---- state update: S = diag(chunk decay) S + ks^T V  (rows c = 16w + 4g + e) ---------------
+    {
+        float4 dch = *reinterpret_cast<const float4 *>(&sm.eb[0][16 * w + 4 * g]);
+#pragma unroll
+        for (int sb = 1; sb < 4; ++sb) {
+            const float4 t = *reinterpret_cast<const float4 *>(&sm.eb[sb][16 * w + 4 * g]);
+            dch.x *= t.x; dch.y *= t.y; dch.z *= t.z; dch.w *= t.w;
+        }
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            S[jt][0] *= dch.x; S[jt][1] *= dch.y; S[jt][2] *= dch.z; S[jt][3] *= dch.w;
+        }
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int s0 = ord.slot(2 * p), s1 = ord.slot(2 * p + 1);
+            const bf16x8 a = join(lds_read_tr(&sm.ks[16 * s0 + tr_row][16 * w + tr_col]),
+                                  lds_read_tr(&sm.ks[16 * s1 + tr_row][16 * w + tr_col]));
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) S[jt] = mfma(a, vop[p][jt], S[jt]);
+        }
+    }
+
+    __syncthreads();  // every read of st / khat / ks / v / eb of this step is done
+
+    // bf16 copy of the new state for the next chunk's readout, [column][channel]
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt)
+        *reinterpret_cast<uint2 *>(&sm.st[16 * jt + r][16 * w + 4 * g]) =
+            make_uint2(pack2(S[jt][0], S[jt][1]), pack2(S[jt][2], S[jt][3]));
+}
+
+__device__ __forceinline__ void load_state(const float *src, bool zero, int w, int r, int g, f32x4 (&S)[4])
+{
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) S[jt][e] = zero ? 0.f : src[(16 * w + 4 * g + e) * kD + 16 * jt + r];
+}
+
+__device__ __forceinline__ void publish_state(OutLds &sm, int w, int r, int g, const f32x4 (&S)[4])
+{
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt)
+        *reinterpret_cast<uint2 *>(&sm.st[16 * jt + r][16 * w + 4 * g]) =
+            make_uint2(pack2(S[jt][0], S[jt][1]), pack2(S[jt][2], S[jt][3]));
+}
+
+__global__ __launch_bounds__(kThreads) void bigla_segment_out_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
+    const uint16_t *__restrict__ g_fwd, const uint16_t *__restrict__ g_bwd, uint16_t *__restrict__ out,
+    const float *__restrict__ seg_states /* states entering each segment, or nullptr when one segment */, int L,
+    int n_seg)
+{
+    __shared__ OutLds sm;
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const long slab = blockIdx.x / n_seg;
+    const int seg = blockIdx.x % n_seg;
+    const long base = slab * L * kD;
+    q += base; k += base; v += base; g_fwd += base; g_bwd += base; out += base;
+
+    const int chunk0 = seg * kSegChunks;
+    const int n_chunks_total = (L + kC - 1) / kC;
+    const int nch = min(kSegChunks, n_chunks_total - chunk0);
+    const float *st_in = seg_states ? seg_states + (slab * n_seg + seg) * kSegFloats : nullptr;
+
+    // ring of output tiles: ring[0] is always the tile of the chunk being processed
+    f32x4 ring[kSegChunks][4];
+#pragma unroll
+    for (int m = 0; m < kSegChunks; ++m)
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) ring[m][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    f32x4 S[4];
+
+    // ---------------- forward sweep: chunks ascending ----------------
+    load_state(st_in, st_in == nullptr, w, r, g, S);
+    publish_state(sm, w, r, g, S);  // made visible by the first barrier inside the step
+    for (int m = 0; m < nch; ++m) {
+        const long tok = long(chunk0 + m) * kC + 16 * w + r;
+        const bool valid = tok < L;
+        const Row16 qraw = load_row16(q, tok, valid, g), kraw = load_row16(k, tok, valid, g);
+        const Row16 graw = load_row16(g_fwd, tok, valid, g), vraw = load_row16(v, tok, valid, g);
+        out_chunk_step<0>(sm, w, r, g, qraw, kraw, graw, vraw, ring[0], S);
+        // rotate left: the next chunk's tile moves to ring[0]
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            const f32x4 first = ring[0][jt];
+#pragma unroll
+            for (int p = 0; p + 1 < kSegChunks; ++p) ring[p][jt] = ring[p + 1][jt];
+            ring[kSegChunks - 1][jt] = first;
+        }
+    }
+
+    // ---------------- backward sweep: chunks descending ----------------
+    __syncthreads();  // the forward sweep's last state copy is no longer read
+    load_state(st_in ? st_in + size_t(kD) * kD : nullptr, st_in == nullptr, w, r, g, S);
+    publish_state(sm, w, r, g, S);
+    for (int m = nch - 1; m >= 0; --m) {
+        // rotate right: chunk m's forward tile moves to ring[0]
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            const f32x4 last = ring[kSegChunks - 1][jt];
+#pragma unroll
+            for (int p = kSegChunks - 1; p > 0; --p) ring[p][jt] = ring[p - 1][jt];
+            ring[0][jt] = last;
+        }
+        const long tok = long(chunk0 + m) * kC + 16 * w + r;
+        const bool valid = tok < L;
+        const Row16 qraw = load_row16(q, tok, valid, g), kraw = load_row16(k, tok, valid, g);
+        const Row16 graw = load_row16(g_bwd, tok, valid, g), vraw = load_row16(v, tok, valid, g);
+        out_chunk_step<1>(sm, w, r, g, qraw, kraw, graw, vraw, ring[0], S);
+        // o_t = (o_fwd_t + o_bwd_t) / 2, rows 16w + 4g + e, column 16*jt + r
+        const long t0 = long(chunk0 + m) * kC + 16 * w + 4 * g;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (t0 + e < L) {
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt)
+                    out[(t0 + e) * kD + 16 * jt + r] = uint16_t(f32_to_bf16_bits(0.5f * ring[0][jt][e]));
+            }
+        }
+    }
+}
+
+// ---- kernel 1: per-segment local end states, both directions in one pass ----------------------
+
+__global__ __launch_bounds__(kThreads) void bigla_segment_state_kernel(
+    const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, const uint16_t *__restrict__ g_fwd,
+    const uint16_t *__restrict__ g_bwd, float *__restrict__ seg_states, int L, int n_seg)
+{
+    __shared__ StateLds sm;
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const long slab = blockIdx.x / n_seg;
+    const int seg = blockIdx.x % n_seg;
+    const long base = slab * L * kD;
+    k += base; v += base; g_fwd += base; g_bwd += base;
+    float *dst = seg_states + (slab * n_seg + seg) * kSegFloats;
+
+    const int chunk0 = seg * kSegChunks;
+    const int n_chunks_total = (L + kC - 1) / kC;
+    const int nch = min(kSegChunks, n_chunks_total - chunk0);
+    const int row = 16 * w + r;
+    const int tr_row = 4 * g + (r >> 2), tr_col = 4 * (r & 3);
+
+    f32x4 Sf[4], Sb[4];
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) {
+        Sf[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        Sb[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    // backward direction, walked left to right: the state at the segment's LEFT edge is
+    // sum_n (product of the chunk decays of chunks left of n) * (chunk n's local state), so the
+    // running product is folded into chunk n's keys and nothing accumulated ever decays again.
+    float bcum[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) bcum[e] = 1.f;
+    float4 dtot_f = make_float4(1.f, 1.f, 1.f, 1.f), dtot_b = dtot_f;  // rows 16w + 4g + e
+
+    for (int m = 0; m < nch; ++m) {
+        const long tok = long(chunk0 + m) * kC + row;
+        const bool valid = tok < L;
+        const Row16 kraw = load_row16(k, tok, valid, g), vraw = load_row16(v, tok, valid, g);
+        const Row16 gfraw = load_row16(g_fwd, tok, valid, g), gbraw = load_row16(g_bwd, tok, valid, g);
+
+        float kf[16], EB[16], Ff[16], Fb[16];
+        unpack16(kraw, kf);
+        gate_factors_state<0>(gfraw, Ff, EB);
+        if (r == 0) store_chan16(sm.eb[0][w], g, EB);
+        gate_factors_state<1>(gbraw, Fb, EB);
+        if (r == 0) store_chan16(sm.eb[1][w], g, EB);
+        store_row16_raw(sm.v, row, g, vraw);
+        __syncthreads();
+
+        float tmp[16];
+        // forward keys: decay to the chunk's right edge = F * (sub-blocks to the right)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) Ff[e] *= kf[e];
+#pragma unroll
+        for (int sb = 1; sb < 4; ++sb) {
+            if (sb > w) {
+                load_chan16(sm.eb[0][sb], g, tmp);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) Ff[e] *= tmp[e];
+            }
+        }
+        store_row16(sm.ks[0], row, g, Ff);
+        // backward keys: decay to the chunk's left edge = F * (sub-blocks to the left) * running product
+#pragma unroll
+        for (int e = 0; e < 16; ++e) Fb[e] *= kf[e] * bcum[e];
+#pragma unroll
+        for (int sb = 0; sb < 3; ++sb) {
+            load_chan16(sm.eb[1][sb], g, tmp);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                if (sb < w) Fb[e] *= tmp[e];
+                bcum[e] *= tmp[e];
+            }
+        }
+        load_chan16(sm.eb[1][3], g, tmp);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) bcum[e] *= tmp[e];
+        store_row16(sm.ks[1], row, g, Fb);
+        __syncthreads();
+
+        // chunk decay of this wave's state rows, both directions
+        float4 df = *reinterpret_cast<const float4 *>(&sm.eb[0][0][16 * w + 4 * g]);
+        float4 db = *reinterpret_cast<const float4 *>(&sm.eb[1][0][16 * w + 4 * g]);
+#pragma unroll
+        for (int sb = 1; sb < 4; ++sb) {
+            const float4 a = *reinterpret_cast<const float4 *>(&sm.eb[0][sb][16 * w + 4 * g]);
+            const float4 b = *reinterpret_cast<const float4 *>(&sm.eb[1][sb][16 * w + 4 * g]);
+            df.x *= a.x; df.y *= a.y; df.z *= a.z; df.w *= a.w;
+            db.x *= b.x; db.y *= b.y; db.z *= b.z; db.w *= b.w;
+        }
+        dtot_f.x *= df.x; dtot_f.y *= df.y; dtot_f.z *= df.z; dtot_f.w *= df.w;
+        dtot_b.x *= db.x; dtot_b.y *= db.y; dtot_b.z *= db.z; dtot_b.w *= db.w;
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            Sf[jt][0] *= df.x; Sf[jt][1] *= df.y; Sf[jt][2] *= df.z; Sf[jt][3] *= df.w;
+        }
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const bf16x8 af = join(lds_read_tr(&sm.ks[0][32 * p + tr_row][16 * w + tr_col]),
+                                   lds_read_tr(&sm.ks[0][32 * p + 16 + tr_row][16 * w + tr_col]));
+            const bf16x8 ab = join(lds_read_tr(&sm.ks[1][32 * p + tr_row][16 * w + tr_col]),
+                                   lds_read_tr(&sm.ks[1][32 * p + 16 + tr_row][16 * w + tr_col]));
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) {
+                const bf16x8 vb = join(lds_read_tr(&sm.v[32 * p + tr_row][16 * jt + tr_col]),
+                                       lds_read_tr(&sm.v[32 * p + 16 + tr_row][16 * jt + tr_col]));
+                Sf[jt] = mfma(af, vb, Sf[jt]);
+                Sb[jt] = mfma(ab, vb, Sb[jt]);
+            }
+        }
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = (16 * w + 4 * g + e) * kD + 16 * jt + r;
+            dst[idx] = Sf[jt][e];
+            dst[size_t(kD) * kD + idx] = Sb[jt][e];
+        }
+    if (r == 0) {
+        *reinterpret_cast<float4 *>(dst + kSegStateFloats + 16 * w + 4 * g) = dtot_f;
+        *reinterpret_cast<float4 *>(dst + kSegStateFloats + kD + 16 * w + 4 * g) = dtot_b;
+    }
+}
+
+// ---- kernel 2: scan of segment states, in place ------------------------------------------------
+// On entry seg_states[slab][n] holds segment n's local end states and decays; on exit it holds the
+// states ENTERING segment n: from the left for the forward direction, from the right for the
+// backward direction.  One thread per (slab, direction, state element).
+__global__ __launch_bounds__(kThreads) void bigla_state_scan_kernel(float *__restrict__ seg_states, int n_seg)
+{
+    constexpr int kBlocksPerState = kD * kD / kThreads;
+    const int elem = (blockIdx.x % kBlocksPerState) * kThreads + threadIdx.x;  // 0 .. 4095
+    const int dir = (blockIdx.x / kBlocksPerState) & 1;
+    const long slab = blockIdx.x / (2 * kBlocksPerState);
+    float *base = seg_states + slab * n_seg * kSegFloats;
+    const int c = elem / kD;
+    float run = 0.f;
+    for (int i = 0; i < n_seg; ++i) {
+        const int n = dir == 0 ? i : n_seg - 1 - i;
+        float *s = base + n * kSegFloats;
+        const float local = s[dir * kD * kD + elem];
+        const float decay = s[kSegStateFloats + dir * kD + c];
+        s[dir * kD * kD + elem] = run;
+        run = fmaf(run, decay, local);
+    }
+}
+
+}  // namespace
+
+bool bigla_chunk_supported(int dk, int dv, bool is_bf16) { return is_bf16 && dk == kD && dv == kD; }
+
+size_t bigla_chunk_workspace_bytes(long BH, int L)
+{
+    const long n_chunks = (L + kC - 1) / kC;
+    const long n_seg = (n_chunks + kSegChunks - 1) / kSegChunks;
+    // always non-zero so that callers can size one buffer per problem; unused when n_seg == 1
+    return size_t(BH) * n_seg * kSegFloats * sizeof(float);
+}
+
+hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                              void *out, long BH, int L, void *workspace, hipStream_t stream)
+{
+    const long n_chunks = (L + kC - 1) / kC;
+    const int n_seg = int((n_chunks + kSegChunks - 1) / kSegChunks);
+    const long blocks = BH * n_seg;
+    if (blocks > 0x7fffffffL || BH * 2 * (kD * kD / kThreads) > 0x7fffffffL) return hipErrorInvalidValue;
+    const uint16_t *qq = static_cast<const uint16_t *>(q), *kk = static_cast<const uint16_t *>(k);
+    const uint16_t *vv = static_cast<const uint16_t *>(v);
+    const uint16_t *gf = static_cast<const uint16_t *>(g_fwd), *gb = static_cast<const uint16_t *>(g_bwd);
+    float *ws = static_cast<float *>(workspace);
+    if (n_seg > 1) {
+        {
+            LaunchTimer timer(kKernelSegmentState, stream);
+            hipLaunchKernelGGL(bigla_segment_state_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, kk, vv,
+                               gf, gb, ws, L, n_seg);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        {
+            LaunchTimer timer(kKernelStateScan, stream);
+            hipLaunchKernelGGL(bigla_state_scan_kernel, dim3((unsigned)(BH * 2 * (kD * kD / kThreads))),
+                               dim3(kThreads), 0, stream, ws, n_seg);
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    {
+        LaunchTimer timer(kKernelSegmentOut, stream);
+        hipLaunchKernelGGL(bigla_segment_out_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk, vv, gf,
+                           gb, static_cast<uint16_t *>(out), n_seg > 1 ? ws : nullptr, L, n_seg);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace vig

@@ -9,6 +9,7 @@
 // 16 at a time with coalesced loads; alpha = exp(log-gate) is evaluated once per element there.
 #include "vig_common.hpp"
 #include "vig_kernels.hpp"
+#include "vig_timing.hpp"
 
 namespace vig {
 
@@ -89,6 +90,7 @@ template <typename T, int DK, int DV>
 hipError_t launch(const void *q, const void *k, const void *v, const void *gf, const void *gb, void *out,
                   float *o_fwd, int BH, int L, hipStream_t stream)
 {
+    LaunchTimer timer(kKernelRecurrent, stream);
     hipLaunchKernelGGL((bigla_recurrent_kernel<T, DK, DV>), dim3(BH), dim3(DV * kSplit), 0, stream,
                        static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
                        static_cast<const T *>(gf), static_cast<const T *>(gb), static_cast<T *>(out), o_fwd, L);

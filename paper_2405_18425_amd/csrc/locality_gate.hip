@@ -11,6 +11,7 @@
 // row of the [.., y, x, channel] tensor per wavefront load.  Arithmetic is fp32 on either dtype.
 #include "vig_common.hpp"
 #include "vig_kernels.hpp"
+#include "vig_timing.hpp"
 
 namespace vig {
 
@@ -156,6 +157,7 @@ hipError_t launch(const void *x, const void *w, const void *bias, const void *z,
     const long total = slabs * n_strips * Wg * CG;
     const long blocks = (total + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+    LaunchTimer timer(kKernelLocalityGate, stream);
     hipLaunchKernelGGL((locality_gate_kernel<T, DV>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
                        static_cast<const T *>(x), static_cast<const T *>(w), static_cast<const T *>(bias),
                        static_cast<const T *>(z), static_cast<const T *>(og), static_cast<T *>(out), H, Hg, Wg, rows,
