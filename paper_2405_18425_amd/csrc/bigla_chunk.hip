@@ -296,8 +296,9 @@ constexpr size_t kSegFloats = kSegStateFloats + 2 * kD;
 
 // ---- kernel 3: per-segment output sweep -------------------------------------------------------
 
-// One chunk of one direction.  O accumulates this chunk's output tile (rows 16w + 4g + e,
-// column 16*jt + r); S is this wave's 16 rows of the carried fp32 state.
+// One chunk of one direction.  O accumulates this chunk's output tile, token-per-lane (token
+// 16w + r, columns 16*jt + 4g + e); S is this wave's 16 rows of the carried fp32 state (rows
+// 16w + 4g + e, column 16*jt + r).
 template <int DIR>
 __device__ __forceinline__ void out_chunk_step(OutLds &sm, const int w, const int r, const int g, const Row16 &qraw,
                                                const Row16 &kraw, const Row16 &graw, const Row16 &vraw, f32x4 (&O)[4],
@@ -406,22 +407,24 @@ __device__ __forceinline__ void out_chunk_step(OutLds &sm, const int w, const in
                               lds_read_tr(&sm.v[16 * s1 + tr_row][16 * jt + tr_col]));
     }
 
-    // ---- O += P.V (visible sub-blocks only) + readout of the incoming state ---------------------
+    // ---- O^T += V^T.P^T (visible sub-blocks only) + readout S^T.q^T of the incoming state --------
+    // computed transposed so that the accumulator layout is token-per-lane: lane (r, g) ends up
+    // with columns 16*jt + 4g .. +3 of its own token 16w + r
     {
         const bf16x8 pa0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0].x, pk[0].y, pk[1].x, pk[1].y));
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(pa0, vop[0][jt], O[jt]);
+        for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(vop[0][jt], pa0, O[jt]);
         if (ord.nb >= 2) {
             const bf16x8 pa1 = __builtin_bit_cast(bf16x8, make_uint4(pk[2].x, pk[2].y, pk[3].x, pk[3].y));
 #pragma unroll
-            for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(pa1, vop[1][jt], O[jt]);
+            for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(vop[1][jt], pa1, O[jt]);
         }
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) {
             const bf16x8 b0 = *reinterpret_cast<const bf16x8 *>(&sm.st[16 * jt + r][8 * g]);
             const bf16x8 b1 = *reinterpret_cast<const bf16x8 *>(&sm.st[16 * jt + r][32 + 8 * g]);
-            O[jt] = mfma(qr0, b0, O[jt]);
-            O[jt] = mfma(qr1, b1, O[jt]);
+            O[jt] = mfma(b0, qr0, O[jt]);
+            O[jt] = mfma(b1, qr1, O[jt]);
         }
     }
 
@@ -472,7 +475,7 @@ __device__ __forceinline__ void publish_state(OutLds &sm, int w, int r, int g, c
             make_uint2(pack2(S[jt][0], S[jt][1]), pack2(S[jt][2], S[jt][3]));
 }
 
-__global__ __launch_bounds__(kThreads) void bigla_segment_out_kernel(
+__global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     const uint16_t *__restrict__ g_fwd, const uint16_t *__restrict__ g_bwd, uint16_t *__restrict__ out,
     const float *__restrict__ seg_states /* states entering each segment, or nullptr when one segment */, int L,
@@ -491,32 +494,54 @@ __global__ __launch_bounds__(kThreads) void bigla_segment_out_kernel(
     const int nch = min(kSegChunks, n_chunks_total - chunk0);
     const float *st_in = seg_states ? seg_states + (slab * n_seg + seg) * kSegFloats : nullptr;
 
-    // ring of output tiles: ring[0] is always the tile of the chunk being processed
-    f32x4 ring[kSegChunks][4];
+    // forward-direction output tiles of the segment's chunks, parked between the two sweeps
+    f32x4 parked[kSegChunks][4];
+    auto park = [&](int m, const f32x4 (&O)[4]) {
 #pragma unroll
-    for (int m = 0; m < kSegChunks; ++m)
+        for (int p = 0; p < kSegChunks; ++p)
+            if (p == m) {
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) ring[m][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int jt = 0; jt < 4; ++jt) parked[p][jt] = O[jt];
+            }
+    };
+    auto unpark = [&](int m, f32x4 (&O)[4]) {
+#pragma unroll
+        for (int p = 0; p < kSegChunks; ++p)
+            if (p == m) {
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt) O[jt] = parked[p][jt];
+            }
+    };
 
     f32x4 S[4];
 
+    // rows of the next chunk are fetched while the current chunk is being processed
+    struct ChunkRows {
+        Row16 q, k, g, v;
+    };
+    auto fetch = [&](int m, const uint16_t *gate) {
+        const long tok = long(chunk0 + m) * kC + 16 * w + r;
+        const bool valid = tok < L;
+        ChunkRows c;
+        c.q = load_row16(q, tok, valid, g);
+        c.k = load_row16(k, tok, valid, g);
+        c.g = load_row16(gate, tok, valid, g);
+        c.v = load_row16(v, tok, valid, g);
+        return c;
+    };
+
     // ---------------- forward sweep: chunks ascending ----------------
+    ChunkRows next = fetch(0, g_fwd);
     load_state(st_in, st_in == nullptr, w, r, g, S);
     publish_state(sm, w, r, g, S);  // made visible by the first barrier inside the step
     for (int m = 0; m < nch; ++m) {
-        const long tok = long(chunk0 + m) * kC + 16 * w + r;
-        const bool valid = tok < L;
-        const Row16 qraw = load_row16(q, tok, valid, g), kraw = load_row16(k, tok, valid, g);
-        const Row16 graw = load_row16(g_fwd, tok, valid, g), vraw = load_row16(v, tok, valid, g);
-        out_chunk_step<0>(sm, w, r, g, qraw, kraw, graw, vraw, ring[0], S);
-        // rotate left: the next chunk's tile moves to ring[0]
+        const ChunkRows cur = next;
+        next = m + 1 < nch ? fetch(m + 1, g_fwd) : fetch(nch - 1, g_bwd);
+        f32x4 O[4];
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) {
-            const f32x4 first = ring[0][jt];
-#pragma unroll
-            for (int p = 0; p + 1 < kSegChunks; ++p) ring[p][jt] = ring[p + 1][jt];
-            ring[kSegChunks - 1][jt] = first;
-        }
+        for (int jt = 0; jt < 4; ++jt) O[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        out_chunk_step<0>(sm, w, r, g, cur.q, cur.k, cur.g, cur.v, O, S);
+        park(m, O);
     }
 
     // ---------------- backward sweep: chunks descending ----------------
@@ -524,27 +549,19 @@ __global__ __launch_bounds__(kThreads) void bigla_segment_out_kernel(
     load_state(st_in ? st_in + size_t(kD) * kD : nullptr, st_in == nullptr, w, r, g, S);
     publish_state(sm, w, r, g, S);
     for (int m = nch - 1; m >= 0; --m) {
-        // rotate right: chunk m's forward tile moves to ring[0]
-#pragma unroll
-        for (int jt = 0; jt < 4; ++jt) {
-            const f32x4 last = ring[kSegChunks - 1][jt];
-#pragma unroll
-            for (int p = kSegChunks - 1; p > 0; --p) ring[p][jt] = ring[p - 1][jt];
-            ring[0][jt] = last;
-        }
+        const ChunkRows cur = next;
+        if (m > 0) next = fetch(m - 1, g_bwd);
+        f32x4 O[4];
+        unpark(m, O);
+        out_chunk_step<1>(sm, w, r, g, cur.q, cur.k, cur.g, cur.v, O, S);
+        // o_t = (o_fwd_t + o_bwd_t) / 2 for token 16w + r, columns 16*jt + 4g .. +3
         const long tok = long(chunk0 + m) * kC + 16 * w + r;
-        const bool valid = tok < L;
-        const Row16 qraw = load_row16(q, tok, valid, g), kraw = load_row16(k, tok, valid, g);
-        const Row16 graw = load_row16(g_bwd, tok, valid, g), vraw = load_row16(v, tok, valid, g);
-        out_chunk_step<1>(sm, w, r, g, qraw, kraw, graw, vraw, ring[0], S);
-        // o_t = (o_fwd_t + o_bwd_t) / 2, rows 16w + 4g + e, column 16*jt + r
-        const long t0 = long(chunk0 + m) * kC + 16 * w + 4 * g;
+        if (tok < L) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (t0 + e < L) {
-#pragma unroll
-                for (int jt = 0; jt < 4; ++jt)
-                    out[(t0 + e) * kD + 16 * jt + r] = uint16_t(f32_to_bf16_bits(0.5f * ring[0][jt][e]));
+            for (int jt = 0; jt < 4; ++jt) {
+                const f32x4 o = O[jt];
+                *reinterpret_cast<uint2 *>(out + tok * kD + 16 * jt + 4 * g) =
+                    make_uint2(pack2(0.5f * o[0], 0.5f * o[1]), pack2(0.5f * o[2], 0.5f * o[3]));
             }
         }
     }
@@ -585,11 +602,26 @@ __global__ __launch_bounds__(kThreads) void bigla_segment_state_kernel(
     for (int e = 0; e < 16; ++e) bcum[e] = 1.f;
     float4 dtot_f = make_float4(1.f, 1.f, 1.f, 1.f), dtot_b = dtot_f;  // rows 16w + 4g + e
 
-    for (int m = 0; m < nch; ++m) {
+    // rows of the next chunk are fetched while the current chunk is being processed
+    struct ChunkRows {
+        Row16 k, v, gf, gb;
+    };
+    auto fetch = [&](int m) {
         const long tok = long(chunk0 + m) * kC + row;
         const bool valid = tok < L;
-        const Row16 kraw = load_row16(k, tok, valid, g), vraw = load_row16(v, tok, valid, g);
-        const Row16 gfraw = load_row16(g_fwd, tok, valid, g), gbraw = load_row16(g_bwd, tok, valid, g);
+        ChunkRows c;
+        c.k = load_row16(k, tok, valid, g);
+        c.v = load_row16(v, tok, valid, g);
+        c.gf = load_row16(g_fwd, tok, valid, g);
+        c.gb = load_row16(g_bwd, tok, valid, g);
+        return c;
+    };
+    ChunkRows next = fetch(0);
+
+    for (int m = 0; m < nch; ++m) {
+        const ChunkRows cur = next;
+        if (m + 1 < nch) next = fetch(m + 1);
+        const Row16 &kraw = cur.k, &vraw = cur.v, &gfraw = cur.gf, &gbraw = cur.gb;
 
         float kf[16], EB[16], Ff[16], Fb[16];
         unpack16(kraw, kf);
