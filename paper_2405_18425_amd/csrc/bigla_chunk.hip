@@ -10,15 +10,22 @@
 // contraction runs on v_mfma_f32_16x16x32_bf16 with fp32 accumulation; the carried state stays
 // fp32 in accumulator registers and only its readout copy is rounded to bf16.
 //
-// Numerical range.  exp(b_t - b_i) is never formed as exp(b_t) * exp(-b_i) across a whole
-// chunk.  A chunk is cut into four sub-blocks of 16 tokens; cumulative gates are local to a
-// sub-block (DPP row scans inside one wavefront).  Off-diagonal 16x16 tiles scale keys by the
-// decay to the END of the key's own sub-block and queries by the decay from the START of the
-// query's sub-block times the whole-sub-block factors in between, so every factor is <= 1 and
-// underflow to 0 is the correct limit.  The diagonal tile refers both sides to the MIDDLE of
-// the sub-block, so its factors span at most 8 steps of decay in either sense; with the
-// per-step log-gate floored at -8 (alpha >= 3.4e-4; anything smaller is a hard reset whose
-// leak is far below the bf16 tolerance) they stay within e^(+-64), inside fp32 and bf16 range.
+// Numerical range -- two evaluations of a chunk, chosen per chunk from the gates themselves.
+//   FAST.  With b_t the cumulative log-gate since the chunk edge, queries are scaled by
+//   exp(b_t) and keys by exp(-b_i); one key tile then serves the masked scores AND the state
+//   update, S_out = diag(exp(b_end)) (S_in + sum_i (k_i exp(-b_i))^T v_i), and one query tile
+//   serves the scores AND the readout.  exp(-b_i) grows with the decay accumulated over the
+//   chunk, so this form is used only when the chunk's total log-decay provably stays within
+//   60 nats in every channel (the sum over its four 16-token sub-blocks of the largest
+//   per-channel sub-block total is checked).  Gates of the paper's form, sigmoid(z)^(1/16),
+//   stay far inside: 64 steps reach 60 nats only for z < -15 throughout.
+//   RANGE-SAFE.  Otherwise cumulative gates stay local to a sub-block: off-diagonal 16x16 tiles
+//   scale keys by the decay to the END of the key's own sub-block and queries by the decay from
+//   the START of the query's sub-block times the whole-sub-block factors in between, so every
+//   factor is <= 1 and underflow to 0 is the correct limit.  The diagonal tile refers both
+//   sides to the MIDDLE of the sub-block, so its factors span at most 8 steps in either sense;
+//   the per-step log-gate is floored at -8 there (alpha >= 3.4e-4; anything smaller is a hard
+//   reset whose leak is far below the bf16 tolerance), which keeps them within e^(+-64).
 // Masking is by select, never by multiplying with 0.
 //
 // Parallel decomposition.  A sequence is cut into segments of kSegChunks chunks.
@@ -57,7 +64,8 @@ constexpr int kPitch = 72;      // LDS row pitch in bf16 elements (64 + 8: 16-by
 constexpr int kSegChunks = 4;   // chunks per segment (ring of output tiles held in registers)
 constexpr int kThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kGateFloorLog2 = -8.0f * kLog2e;  // per-step floor of the log-gate, log2 domain
+constexpr float kGateFloorLog2 = -8.0f * kLog2e;  // per-step floor of the log-gate (range-safe form), log2 domain
+constexpr float kFastRangeLog2 = 60.0f * kLog2e;  // largest chunk log-decay the fast form accepts, log2 domain
 
 // ---- small device helpers ------------------------------------------------------------------
 
@@ -222,14 +230,34 @@ struct SubOrder {
 };
 
 // Cumulative log2-gates of the lane's 16 channels inside its sub-block, inclusive of the lane's
-// own token, in scan order (prefix for DIR 0, suffix for DIR 1).  Floored per step, capped at 0.
-template <int DIR>
+// own token, in scan order (prefix for DIR 0, suffix for DIR 1), capped at 0 (alpha <= 1).
+// FLOOR additionally floors every step at kGateFloorLog2 (range-safe form only).
+template <int DIR, bool FLOOR>
 __device__ __forceinline__ void gate_scan(const Row16 &graw, float (&b)[16])
 {
     unpack16(graw, b);
 #pragma unroll
-    for (int e = 0; e < 16; ++e)
-        b[e] = row_scan<DIR>(__builtin_amdgcn_fmed3f(b[e] * kLog2e, kGateFloorLog2, 0.f));
+    for (int e = 0; e < 16; ++e) {
+        const float step = FLOOR ? __builtin_amdgcn_fmed3f(b[e] * kLog2e, kGateFloorLog2, 0.f)
+                                 : fminf(b[e] * kLog2e, 0.f);
+        b[e] = row_scan<DIR>(step);
+    }
+}
+
+// Largest |value| over the wave's far-edge lanes (the four lanes that hold sub-block totals),
+// identical in every lane of the wave.  Totals are <= 0, so this is -min.
+template <int DIR>
+__device__ __forceinline__ float subblock_decay_max(const float (&b)[16])
+{
+    float m = b[0];
+#pragma unroll
+    for (int e = 1; e < 16; ++e) m = fminf(m, b[e]);
+    constexpr int far = DIR == 0 ? 15 : 0;
+    float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), far));
+    float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), far + 16));
+    float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), far + 32));
+    float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), far + 48));
+    return -fminf(fminf(r0, r1), fminf(r2, r3));
 }
 
 // Gate factors of the output sweep for the lane's token t and 16 channels, with B_mid the
@@ -245,7 +273,7 @@ __device__ __forceinline__ void gate_factors(const Row16 &graw, int r, float (&X
                                              float (&F)[16], float (&Emid)[16], float (&EB)[16])
 {
     float b[16];
-    gate_scan<DIR>(graw, b);
+    gate_scan<DIR, true>(graw, b);
     const bool is_mid = r == (DIR == 0 ? 7 : 8);
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
@@ -265,7 +293,7 @@ template <int DIR>
 __device__ __forceinline__ void gate_factors_state(const Row16 &graw, float (&F)[16], float (&EB)[16])
 {
     float b[16];
-    gate_scan<DIR>(graw, b);
+    gate_scan<DIR, true>(graw, b);
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
         const float btot = bcast_far<DIR>(b[e]);
@@ -277,40 +305,186 @@ __device__ __forceinline__ void gate_factors_state(const Row16 &graw, float (&F)
 // ---- shared memory ---------------------------------------------------------------------------
 
 struct __align__(16) OutLds {
-    uint16_t khat[kC][kPitch];  // k * F                     [token][channel]  (intra-chunk keys)
-    uint16_t ks[kC][kPitch];    // k * exp(decay to chunk edge) [token][channel]  (state update keys)
-    uint16_t v[kC][kPitch];     // values                    [token][column]
-    uint16_t st[kD][kPitch];    // carried state, bf16 copy  [column][channel]  (readout operand)
-    float eb[4][kD];            // whole-sub-block decay factor per channel
+    uint16_t kt[kC][kPitch];   // scaled keys                  [token][channel]
+    uint16_t ks[kC][kPitch];   // range-safe form only: keys scaled for the state update [token][channel]
+    uint16_t v[kC][kPitch];    // values                       [token][column]
+    uint16_t st[kD][kPitch];   // carried state, bf16 copy     [column][channel]  (readout operand)
+    float bt[4][kD];           // log2 sub-block totals per channel (fast form)
+    float eb[4][kD];           // whole-sub-block decay factors per channel (range-safe form)
+    float bmax[4];             // largest per-channel log2 decay of each sub-block
 };
 
 struct __align__(16) StateLds {
     uint16_t ks[2][kC][kPitch];
     uint16_t v[kC][kPitch];
+    float bt[2][4][kD];
     float eb[2][4][kD];
+    float bmax[2][4];
 };
 
 // Workspace layout per (slab, segment): two fp32 64x64 states then two fp32 decay vectors.
 constexpr size_t kSegStateFloats = 2 * size_t(kD) * kD;
 constexpr size_t kSegFloats = kSegStateFloats + 2 * kD;
 
+// Token-major MFMA operands of a 64-token tile for contractions over tokens.  k-slot layout:
+// slots 0..3 = tokens 4g..4g+3 of sub-block s0, slots 4..7 = the same tokens of sub-block s1.
+__device__ __forceinline__ bf16x8 token_operand(const uint16_t (*tile)[kPitch], int s0, int s1, int col0, int r,
+                                                int g)
+{
+    const int tr_row = 4 * g + (r >> 2), tr_col = col0 + 4 * (r & 3);
+    return join(lds_read_tr(&tile[16 * s0 + tr_row][tr_col]), lds_read_tr(&tile[16 * s1 + tr_row][tr_col]));
+}
+
+__device__ __forceinline__ uint2 pack4(const f32x4 &p) { return make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3])); }
+
+// Diagonal 16x16 score tile, transposed (lane: keys 4g..4g+3, query r): keep key <= query for
+// the forward direction, key >= query for the backward one (own token in both).
+template <int DIR>
+__device__ __forceinline__ uint2 masked_diag(f32x4 p, int r, int g)
+{
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int i = 4 * g + e;
+        const bool keep = DIR == 0 ? (i <= r) : (i >= r);
+        p[e] = keep ? p[e] : 0.f;
+    }
+    return pack4(p);
+}
+
+// O^T += V^T.P^T over the visible sub-blocks, then the readout S^T.q^T of the incoming state.
+// Computed transposed so that the accumulators are token-per-lane: lane (r, g) ends up with
+// columns 16*jt + 4g .. +3 of its own token 16w + r.
+__device__ __forceinline__ void accumulate_output(const OutLds &sm, const uint2 (&pk)[4], bool second_pair,
+                                                  const bf16x8 (&vop)[2][4], bf16x8 qr0, bf16x8 qr1, int r, int g,
+                                                  f32x4 (&O)[4])
+{
+    const bf16x8 pa0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0].x, pk[0].y, pk[1].x, pk[1].y));
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(vop[0][jt], pa0, O[jt]);
+    if (second_pair) {
+        const bf16x8 pa1 = __builtin_bit_cast(bf16x8, make_uint4(pk[2].x, pk[2].y, pk[3].x, pk[3].y));
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(vop[1][jt], pa1, O[jt]);
+    }
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) {
+        const bf16x8 b0 = *reinterpret_cast<const bf16x8 *>(&sm.st[16 * jt + r][8 * g]);
+        const bf16x8 b1 = *reinterpret_cast<const bf16x8 *>(&sm.st[16 * jt + r][32 + 8 * g]);
+        O[jt] = mfma(b0, qr0, O[jt]);
+        O[jt] = mfma(b1, qr1, O[jt]);
+    }
+}
+
+// bf16 copy of the carried state for the next readout, [column][channel]
+__device__ __forceinline__ void publish_state(OutLds &sm, int w, int r, int g, const f32x4 (&S)[4])
+{
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt)
+        *reinterpret_cast<uint2 *>(&sm.st[16 * jt + r][16 * w + 4 * g]) = pack4(S[jt]);
+}
+
 // ---- kernel 3: per-segment output sweep -------------------------------------------------------
 
-// One chunk of one direction.  O accumulates this chunk's output tile, token-per-lane (token
-// 16w + r, columns 16*jt + 4g + e); S is this wave's 16 rows of the carried fp32 state (rows
-// 16w + 4g + e, column 16*jt + r).
+// FAST form of one chunk of one direction (see the header).  `b` is the lane's sub-block-local
+// cumulative log2-gate; sm.bt holds every sub-block's total and sm.v the chunk's values.
 template <int DIR>
-__device__ __forceinline__ void out_chunk_step(OutLds &sm, const int w, const int r, const int g, const Row16 &qraw,
-                                               const Row16 &kraw, const Row16 &graw, const Row16 &vraw, f32x4 (&O)[4],
-                                               f32x4 (&S)[4])
+__device__ __forceinline__ void out_chunk_fast(OutLds &sm, const SubOrder<DIR> &ord, const int w, const int r,
+                                               const int g, float (&b)[16], const Row16 &qraw, const Row16 &kraw,
+                                               f32x4 (&O)[4], f32x4 (&S)[4])
 {
-    const SubOrder<DIR> ord(w);
+    const int row = 16 * w + r;
+    float tmp[16];
+    // cumulative gate since the chunk edge: add the totals of the sub-blocks before this one
+#pragma unroll
+    for (int d = 1; d <= 3; ++d) {
+        if (d <= ord.nb) {
+            load_chan16(sm.bt[ord.before(d)], g, tmp);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) b[e] += tmp[e];
+        }
+    }
+    float qf[16], kf[16];
+    unpack16(qraw, qf);
+    unpack16(kraw, kf);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        qf[e] *= fast_exp2(b[e]);   // q * exp(b_t)
+        kf[e] *= fast_exp2(-b[e]);  // k * exp(-b_i)
+    }
+    const bf16x8 q0 = pack8(qf), q1 = pack8(qf + 8);
+    const bf16x8 k0 = pack8(kf), k1 = pack8(kf + 8);
+    *reinterpret_cast<bf16x8 *>(&sm.kt[row][8 * g]) = k0;
+    *reinterpret_cast<bf16x8 *>(&sm.kt[row][32 + 8 * g]) = k1;
+
+    __syncthreads();  // kt visible
+
+    // intra-chunk scores, transposed: P^T[i][t] = sum_c kt[i][c] * qt[t][c]
+    uint2 pk[4];
+    {
+        f32x4 p = {0.f, 0.f, 0.f, 0.f};
+        p = mfma(k0, q0, p);
+        p = mfma(k1, q1, p);
+        pk[0] = masked_diag<DIR>(p, r, g);
+    }
+#pragma unroll
+    for (int d = 1; d <= 3; ++d) {
+        if (d <= ord.nb) {
+            const int kb = ord.before(d);
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kt[16 * kb + r][8 * g]);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kt[16 * kb + r][32 + 8 * g]);
+            f32x4 p = {0.f, 0.f, 0.f, 0.f};
+            p = mfma(a0, q0, p);
+            p = mfma(a1, q1, p);
+            pk[d] = pack4(p);
+        } else {
+            pk[d] = make_uint2(0u, 0u);
+        }
+    }
+    bf16x8 vop[2][4];
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) vop[p][jt] = token_operand(sm.v, ord.slot(2 * p), ord.slot(2 * p + 1), 16 * jt, r, g);
+
+    accumulate_output(sm, pk, ord.nb >= 2, vop, q0, q1, r, g, O);
+
+    // state: S = diag(exp(b_end)) (S + kt^T V), rows c = 16w + 4g + e
+    {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const bf16x8 a = token_operand(sm.kt, ord.slot(2 * p), ord.slot(2 * p + 1), 16 * w, r, g);
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) S[jt] = mfma(a, vop[p][jt], S[jt]);
+        }
+        float4 t = *reinterpret_cast<const float4 *>(&sm.bt[0][16 * w + 4 * g]);
+#pragma unroll
+        for (int sb = 1; sb < 4; ++sb) {
+            const float4 u = *reinterpret_cast<const float4 *>(&sm.bt[sb][16 * w + 4 * g]);
+            t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
+        }
+        const float dx = fast_exp2(t.x), dy = fast_exp2(t.y), dz = fast_exp2(t.z), dw = fast_exp2(t.w);
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            S[jt][0] *= dx; S[jt][1] *= dy; S[jt][2] *= dz; S[jt][3] *= dw;
+        }
+    }
+
+    __syncthreads();  // every read of st / kt / v / bt of this step is done
+    publish_state(sm, w, r, g, S);
+}
+
+// RANGE-SAFE form of one chunk of one direction (see the header); recomputes the gate scan with
+// the per-step floor.  sm.v already holds the chunk's values.
+template <int DIR>
+__device__ __forceinline__ void out_chunk_safe(OutLds &sm, const SubOrder<DIR> &ord, const int w, const int r,
+                                               const int g, const Row16 &qraw, const Row16 &kraw, const Row16 &graw,
+                                               f32x4 (&O)[4], f32x4 (&S)[4])
+{
     const int row = 16 * w + r;
 
     float X[16], Y[16], F[16], Emid[16], EB[16];
     gate_factors<DIR>(graw, r, X, Y, F, Emid, EB);
     if (r == 0) store_chan16(sm.eb[w], g, EB);  // whole-sub-block decay exp(B_w)
-    store_row16_raw(sm.v, row, g, vraw);
 
     float qf[16], kf[16];
     unpack16(qraw, qf);
@@ -318,7 +492,7 @@ __device__ __forceinline__ void out_chunk_step(OutLds &sm, const int w, const in
     float khat[16], tmp[16], cum[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) khat[e] = kf[e] * F[e];
-    store_row16(sm.khat, row, g, khat);
+    store_row16(sm.kt, row, g, khat);
     // diagonal tile operands, both referred to the middle of the sub-block
 #pragma unroll
     for (int e = 0; e < 16; ++e) tmp[e] = kf[e] * Y[e];
@@ -327,7 +501,7 @@ __device__ __forceinline__ void out_chunk_step(OutLds &sm, const int w, const in
     for (int e = 0; e < 16; ++e) cum[e] = qf[e] * X[e];
     const bf16x8 qd0 = pack8(cum), qd1 = pack8(cum + 8);
 
-    __syncthreads();  // eb, v, khat visible
+    __syncthreads();  // eb, kt visible
 
     // query variants: qv[d] pairs with the keys of before(d+1); readout uses the full product.
     // q * exp(b_t) = (q * X) * Emid is the decay since the near edge of the query's sub-block.
@@ -363,72 +537,37 @@ __device__ __forceinline__ void out_chunk_step(OutLds &sm, const int w, const in
 
     __syncthreads();  // ks visible
 
-    // ---- intra-chunk scores, transposed: P^T[i][t] = sum_c khat[i][c] * qv[t][c] ----------------
-    // result layout: lane holds keys i = 4g..4g+3 of the tile for query t = r
-    uint2 pk[4];  // bf16 scores per logical slot
+    // intra-chunk scores, transposed: P^T[i][t] = sum_c khat[i][c] * qv[t][c]
+    uint2 pk[4];
     {
         f32x4 p = {0.f, 0.f, 0.f, 0.f};
         p = mfma(kd0, qd0, p);
         p = mfma(kd1, qd1, p);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int i = 4 * g + e;
-            const bool keep = DIR == 0 ? (i <= r) : (i >= r);  // own token included in both directions
-            p[e] = keep ? p[e] : 0.f;
-        }
-        pk[0] = make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3]));
+        pk[0] = masked_diag<DIR>(p, r, g);
     }
 #pragma unroll
     for (int d = 1; d <= 3; ++d) {
         if (d <= ord.nb) {
             const int kb = ord.before(d);
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.khat[16 * kb + r][8 * g]);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.khat[16 * kb + r][32 + 8 * g]);
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kt[16 * kb + r][8 * g]);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kt[16 * kb + r][32 + 8 * g]);
             f32x4 p = {0.f, 0.f, 0.f, 0.f};
             p = mfma(a0, qv[d - 1][0], p);
             p = mfma(a1, qv[d - 1][1], p);
-            pk[d] = make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3]));
+            pk[d] = pack4(p);
         } else {
             pk[d] = make_uint2(0u, 0u);
         }
     }
-
-    // ---- token-major operands: values (shared by P.V and the state update) ---------------------
-    // k-slot layout of a token contraction: slots 0..3 = tokens 4g..4g+3 of sub-block slot(2p),
-    // slots 4..7 = the same tokens of sub-block slot(2p+1)
-    const int tr_row = 4 * g + (r >> 2), tr_col = 4 * (r & 3);
     bf16x8 vop[2][4];
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        const int s0 = ord.slot(2 * p), s1 = ord.slot(2 * p + 1);
+    for (int p = 0; p < 2; ++p)
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt)
-            vop[p][jt] = join(lds_read_tr(&sm.v[16 * s0 + tr_row][16 * jt + tr_col]),
-                              lds_read_tr(&sm.v[16 * s1 + tr_row][16 * jt + tr_col]));
-    }
+        for (int jt = 0; jt < 4; ++jt) vop[p][jt] = token_operand(sm.v, ord.slot(2 * p), ord.slot(2 * p + 1), 16 * jt, r, g);
 
-    // ---- O^T += V^T.P^T (visible sub-blocks only) + readout S^T.q^T of the incoming state --------
-    // computed transposed so that the accumulator layout is token-per-lane: lane (r, g) ends up
-    // with columns 16*jt + 4g .. +3 of its own token 16w + r
-    {
-        const bf16x8 pa0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0].x, pk[0].y, pk[1].x, pk[1].y));
-#pragma unroll
-        for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(vop[0][jt], pa0, O[jt]);
-        if (ord.nb >= 2) {
-            const bf16x8 pa1 = __builtin_bit_cast(bf16x8, make_uint4(pk[2].x, pk[2].y, pk[3].x, pk[3].y));
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(vop[1][jt], pa1, O[jt]);
-        }
-#pragma unroll
-        for (int jt = 0; jt < 4; ++jt) {
-            const bf16x8 b0 = *reinterpret_cast<const bf16x8 *>(&sm.st[16 * jt + r][8 * g]);
-            const bf16x8 b1 = *reinterpret_cast<const bf16x8 *>(&sm.st[16 * jt + r][32 + 8 * g]);
-            O[jt] = mfma(b0, qr0, O[jt]);
-            O[jt] = mfma(b1, qr1, O[jt]);
-        }
-    }
+    accumulate_output(sm, pk, ord.nb >= 2, vop, qr0, qr1, r, g, O);
 
-    // ---- state update: S = diag(chunk decay) S + ks^T V  (rows c = 16w + 4g + e) ---------------
+    // state update: S = diag(chunk decay) S + ks^T V  (rows c = 16w + 4g + e)
     {
         float4 dch = *reinterpret_cast<const float4 *>(&sm.eb[0][16 * w + 4 * g]);
 #pragma unroll
@@ -442,21 +581,39 @@ __device__ __forceinline__ void out_chunk_step(OutLds &sm, const int w, const in
         }
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
-            const int s0 = ord.slot(2 * p), s1 = ord.slot(2 * p + 1);
-            const bf16x8 a = join(lds_read_tr(&sm.ks[16 * s0 + tr_row][16 * w + tr_col]),
-                                  lds_read_tr(&sm.ks[16 * s1 + tr_row][16 * w + tr_col]));
+            const bf16x8 a = token_operand(sm.ks, ord.slot(2 * p), ord.slot(2 * p + 1), 16 * w, r, g);
 #pragma unroll
             for (int jt = 0; jt < 4; ++jt) S[jt] = mfma(a, vop[p][jt], S[jt]);
         }
     }
 
-    __syncthreads();  // every read of st / khat / ks / v / eb of this step is done
+    __syncthreads();  // every read of st / kt / ks / v / eb of this step is done
+    publish_state(sm, w, r, g, S);
+}
 
-    // bf16 copy of the new state for the next chunk's readout, [column][channel]
-#pragma unroll
-    for (int jt = 0; jt < 4; ++jt)
-        *reinterpret_cast<uint2 *>(&sm.st[16 * jt + r][16 * w + 4 * g]) =
-            make_uint2(pack2(S[jt][0], S[jt][1]), pack2(S[jt][2], S[jt][3]));
+// One chunk of one direction.  O accumulates this chunk's output tile, token-per-lane (token
+// 16w + r, columns 16*jt + 4g + e); S is this wave's 16 rows of the carried fp32 state (rows
+// 16w + 4g + e, column 16*jt + r).
+template <int DIR>
+__device__ __forceinline__ void out_chunk_step(OutLds &sm, const int w, const int r, const int g, const Row16 &qraw,
+                                               const Row16 &kraw, const Row16 &graw, const Row16 &vraw, f32x4 (&O)[4],
+                                               f32x4 (&S)[4])
+{
+    const SubOrder<DIR> ord(w);
+    float b[16];
+    gate_scan<DIR, false>(graw, b);
+    const float wave_max = subblock_decay_max<DIR>(b);
+    if (r == (DIR == 0 ? 15 : 0)) store_chan16(sm.bt[w], g, b);  // this lane holds the sub-block totals
+    if ((threadIdx.x & 63) == 0) sm.bmax[w] = wave_max;
+    store_row16_raw(sm.v, 16 * w + r, g, vraw);
+
+    __syncthreads();  // bt, bmax, v visible
+
+    const float4 m = *reinterpret_cast<const float4 *>(sm.bmax);
+    if (m.x + m.y + m.z + m.w <= kFastRangeLog2)  // uniform over the workgroup
+        out_chunk_fast<DIR>(sm, ord, w, r, g, b, qraw, kraw, O, S);
+    else
+        out_chunk_safe<DIR>(sm, ord, w, r, g, qraw, kraw, graw, O, S);
 }
 
 __device__ __forceinline__ void load_state(const float *src, bool zero, int w, int r, int g, f32x4 (&S)[4])
@@ -465,14 +622,6 @@ __device__ __forceinline__ void load_state(const float *src, bool zero, int w, i
     for (int jt = 0; jt < 4; ++jt)
 #pragma unroll
         for (int e = 0; e < 4; ++e) S[jt][e] = zero ? 0.f : src[(16 * w + 4 * g + e) * kD + 16 * jt + r];
-}
-
-__device__ __forceinline__ void publish_state(OutLds &sm, int w, int r, int g, const f32x4 (&S)[4])
-{
-#pragma unroll
-    for (int jt = 0; jt < 4; ++jt)
-        *reinterpret_cast<uint2 *>(&sm.st[16 * jt + r][16 * w + 4 * g]) =
-            make_uint2(pack2(S[jt][0], S[jt][1]), pack2(S[jt][2], S[jt][3]));
 }
 
 __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
@@ -569,7 +718,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
 
 // ---- kernel 1: per-segment local end states, both directions in one pass ----------------------
 
-__global__ __launch_bounds__(kThreads) void bigla_segment_state_kernel(
+__global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, const uint16_t *__restrict__ g_fwd,
     const uint16_t *__restrict__ g_bwd, float *__restrict__ seg_states, int L, int n_seg)
 {
@@ -586,7 +735,6 @@ __global__ __launch_bounds__(kThreads) void bigla_segment_state_kernel(
     const int n_chunks_total = (L + kC - 1) / kC;
     const int nch = min(kSegChunks, n_chunks_total - chunk0);
     const int row = 16 * w + r;
-    const int tr_row = 4 * g + (r >> 2), tr_col = 4 * (r & 3);
 
     f32x4 Sf[4], Sb[4];
 #pragma unroll
@@ -594,13 +742,11 @@ __global__ __launch_bounds__(kThreads) void bigla_segment_state_kernel(
         Sf[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
         Sb[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    // backward direction, walked left to right: the state at the segment's LEFT edge is
-    // sum_n (product of the chunk decays of chunks left of n) * (chunk n's local state), so the
-    // running product is folded into chunk n's keys and nothing accumulated ever decays again.
-    float bcum[16];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) bcum[e] = 1.f;
-    float4 dtot_f = make_float4(1.f, 1.f, 1.f, 1.f), dtot_b = dtot_f;  // rows 16w + 4g + e
+    // Total decay of the chunks seen so far, rows 16w + 4g + e.  The backward state is walked left
+    // to right: the state at the segment's LEFT edge is sum_n (decay of the chunks left of n) *
+    // (chunk n's state at its own left edge), so chunk n's contribution is scaled by the running
+    // product once and nothing accumulated ever decays again.
+    float4 dtot_f = make_float4(1.f, 1.f, 1.f, 1.f), dtot_b = dtot_f;
 
     // rows of the next chunk are fetched while the current chunk is being processed
     struct ChunkRows {
@@ -621,79 +767,136 @@ __global__ __launch_bounds__(kThreads) void bigla_segment_state_kernel(
     for (int m = 0; m < nch; ++m) {
         const ChunkRows cur = next;
         if (m + 1 < nch) next = fetch(m + 1);
-        const Row16 &kraw = cur.k, &vraw = cur.v, &gfraw = cur.gf, &gbraw = cur.gb;
 
-        float kf[16], EB[16], Ff[16], Fb[16];
-        unpack16(kraw, kf);
-        gate_factors_state<0>(gfraw, Ff, EB);
-        if (r == 0) store_chan16(sm.eb[0][w], g, EB);
-        gate_factors_state<1>(gbraw, Fb, EB);
-        if (r == 0) store_chan16(sm.eb[1][w], g, EB);
-        store_row16_raw(sm.v, row, g, vraw);
-        __syncthreads();
-
-        float tmp[16];
-        // forward keys: decay to the chunk's right edge = F * (sub-blocks to the right)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) Ff[e] *= kf[e];
-#pragma unroll
-        for (int sb = 1; sb < 4; ++sb) {
-            if (sb > w) {
-                load_chan16(sm.eb[0][sb], g, tmp);
-#pragma unroll
-                for (int e = 0; e < 16; ++e) Ff[e] *= tmp[e];
-            }
+        float kf[16], bf[16], bb[16];
+        unpack16(cur.k, kf);
+        gate_scan<0, false>(cur.gf, bf);
+        gate_scan<1, false>(cur.gb, bb);
+        const float max_f = subblock_decay_max<0>(bf), max_b = subblock_decay_max<1>(bb);
+        if (r == 15) store_chan16(sm.bt[0][w], g, bf);
+        if (r == 0) store_chan16(sm.bt[1][w], g, bb);
+        if (lane == 0) {
+            sm.bmax[0][w] = max_f;
+            sm.bmax[1][w] = max_b;
         }
-        store_row16(sm.ks[0], row, g, Ff);
-        // backward keys: decay to the chunk's left edge = F * (sub-blocks to the left) * running product
+        store_row16_raw(sm.v, row, g, cur.v);
+        __syncthreads();  // bt, bmax, v visible
+
+        const float4 mf = *reinterpret_cast<const float4 *>(sm.bmax[0]);
+        const float4 mb = *reinterpret_cast<const float4 *>(sm.bmax[1]);
+        const bool fast = fmaxf(mf.x + mf.y + mf.z + mf.w, mb.x + mb.y + mb.z + mb.w) <= kFastRangeLog2;  // uniform
+        float4 df, db;  // this chunk's decay, rows 16w + 4g + e
+        float tmp[16];
+        if (fast) {
+            // keys k * exp(-b_i), b_i cumulative since the chunk edge of each direction
 #pragma unroll
-        for (int e = 0; e < 16; ++e) Fb[e] *= kf[e] * bcum[e];
+            for (int sb = 0; sb < 4; ++sb) {
+                if (sb < w) {
+                    load_chan16(sm.bt[0][sb], g, tmp);
 #pragma unroll
-        for (int sb = 0; sb < 3; ++sb) {
-            load_chan16(sm.eb[1][sb], g, tmp);
+                    for (int e = 0; e < 16; ++e) bf[e] += tmp[e];
+                }
+                if (sb > w) {
+                    load_chan16(sm.bt[1][sb], g, tmp);
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) bb[e] += tmp[e];
+                }
+            }
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                if (sb < w) Fb[e] *= tmp[e];
-                bcum[e] *= tmp[e];
+                bf[e] = kf[e] * fast_exp2(-bf[e]);
+                bb[e] = kf[e] * fast_exp2(-bb[e]);
+            }
+            store_row16(sm.ks[0], row, g, bf);
+            store_row16(sm.ks[1], row, g, bb);
+            float4 tf = *reinterpret_cast<const float4 *>(&sm.bt[0][0][16 * w + 4 * g]);
+            float4 tb = *reinterpret_cast<const float4 *>(&sm.bt[1][0][16 * w + 4 * g]);
+#pragma unroll
+            for (int sb = 1; sb < 4; ++sb) {
+                const float4 a = *reinterpret_cast<const float4 *>(&sm.bt[0][sb][16 * w + 4 * g]);
+                const float4 b = *reinterpret_cast<const float4 *>(&sm.bt[1][sb][16 * w + 4 * g]);
+                tf.x += a.x; tf.y += a.y; tf.z += a.z; tf.w += a.w;
+                tb.x += b.x; tb.y += b.y; tb.z += b.z; tb.w += b.w;
+            }
+            df = make_float4(fast_exp2(tf.x), fast_exp2(tf.y), fast_exp2(tf.z), fast_exp2(tf.w));
+            db = make_float4(fast_exp2(tb.x), fast_exp2(tb.y), fast_exp2(tb.z), fast_exp2(tb.w));
+        } else {
+            // range-safe keys: decay from the token to the chunk edge, every factor <= 1
+            float EB[16], Ff[16], Fb[16];
+            gate_factors_state<0>(cur.gf, Ff, EB);
+            if (r == 0) store_chan16(sm.eb[0][w], g, EB);
+            gate_factors_state<1>(cur.gb, Fb, EB);
+            if (r == 0) store_chan16(sm.eb[1][w], g, EB);
+            __syncthreads();  // eb visible
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                Ff[e] *= kf[e];
+                Fb[e] *= kf[e];
+            }
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb) {
+                if (sb > w) {  // forward: the sub-blocks to the right
+                    load_chan16(sm.eb[0][sb], g, tmp);
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) Ff[e] *= tmp[e];
+                }
+                if (sb < w) {  // backward: the sub-blocks to the left
+                    load_chan16(sm.eb[1][sb], g, tmp);
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) Fb[e] *= tmp[e];
+                }
+            }
+            store_row16(sm.ks[0], row, g, Ff);
+            store_row16(sm.ks[1], row, g, Fb);
+            df = *reinterpret_cast<const float4 *>(&sm.eb[0][0][16 * w + 4 * g]);
+            db = *reinterpret_cast<const float4 *>(&sm.eb[1][0][16 * w + 4 * g]);
+#pragma unroll
+            for (int sb = 1; sb < 4; ++sb) {
+                const float4 a = *reinterpret_cast<const float4 *>(&sm.eb[0][sb][16 * w + 4 * g]);
+                const float4 b = *reinterpret_cast<const float4 *>(&sm.eb[1][sb][16 * w + 4 * g]);
+                df.x *= a.x; df.y *= a.y; df.z *= a.z; df.w *= a.w;
+                db.x *= b.x; db.y *= b.y; db.z *= b.z; db.w *= b.w;
             }
         }
-        load_chan16(sm.eb[1][3], g, tmp);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) bcum[e] *= tmp[e];
-        store_row16(sm.ks[1], row, g, Fb);
-        __syncthreads();
+        __syncthreads();  // ks visible
 
-        // chunk decay of this wave's state rows, both directions
-        float4 df = *reinterpret_cast<const float4 *>(&sm.eb[0][0][16 * w + 4 * g]);
-        float4 db = *reinterpret_cast<const float4 *>(&sm.eb[1][0][16 * w + 4 * g]);
-#pragma unroll
-        for (int sb = 1; sb < 4; ++sb) {
-            const float4 a = *reinterpret_cast<const float4 *>(&sm.eb[0][sb][16 * w + 4 * g]);
-            const float4 b = *reinterpret_cast<const float4 *>(&sm.eb[1][sb][16 * w + 4 * g]);
-            df.x *= a.x; df.y *= a.y; df.z *= a.z; df.w *= a.w;
-            db.x *= b.x; db.y *= b.y; db.z *= b.z; db.w *= b.w;
-        }
-        dtot_f.x *= df.x; dtot_f.y *= df.y; dtot_f.z *= df.z; dtot_f.w *= df.w;
-        dtot_b.x *= db.x; dtot_b.y *= db.y; dtot_b.z *= db.z; dtot_b.w *= db.w;
+        // chunk contributions K^T V of both directions, rows c = 16w + 4g + e
+        f32x4 Cf[4], Cb[4];
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) {
-            Sf[jt][0] *= df.x; Sf[jt][1] *= df.y; Sf[jt][2] *= df.z; Sf[jt][3] *= df.w;
+            // fast: S_f = df * (S_f + Kf^T V) accumulates onto the state; safe: S_f = df * S_f + Kf^T V
+            Cf[jt] = fast ? Sf[jt] : f32x4{0.f, 0.f, 0.f, 0.f};
+            Cb[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
-            const bf16x8 af = join(lds_read_tr(&sm.ks[0][32 * p + tr_row][16 * w + tr_col]),
-                                   lds_read_tr(&sm.ks[0][32 * p + 16 + tr_row][16 * w + tr_col]));
-            const bf16x8 ab = join(lds_read_tr(&sm.ks[1][32 * p + tr_row][16 * w + tr_col]),
-                                   lds_read_tr(&sm.ks[1][32 * p + 16 + tr_row][16 * w + tr_col]));
+            const bf16x8 af = token_operand(sm.ks[0], 2 * p, 2 * p + 1, 16 * w, r, g);
+            const bf16x8 ab = token_operand(sm.ks[1], 2 * p, 2 * p + 1, 16 * w, r, g);
 #pragma unroll
             for (int jt = 0; jt < 4; ++jt) {
-                const bf16x8 vb = join(lds_read_tr(&sm.v[32 * p + tr_row][16 * jt + tr_col]),
-                                       lds_read_tr(&sm.v[32 * p + 16 + tr_row][16 * jt + tr_col]));
-                Sf[jt] = mfma(af, vb, Sf[jt]);
-                Sb[jt] = mfma(ab, vb, Sb[jt]);
+                const bf16x8 vb = token_operand(sm.v, 2 * p, 2 * p + 1, 16 * jt, r, g);
+                Cf[jt] = mfma(af, vb, Cf[jt]);
+                Cb[jt] = mfma(ab, vb, Cb[jt]);
             }
         }
-        __syncthreads();
+        // backward: chunk state at its own left edge is db * Cb (fast) or Cb (safe); scale by the
+        // decay of the chunks to its left
+        const float4 sb4 = fast ? make_float4(dtot_b.x * db.x, dtot_b.y * db.y, dtot_b.z * db.z, dtot_b.w * db.w) : dtot_b;
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            if (fast) {
+                Sf[jt][0] = Cf[jt][0] * df.x; Sf[jt][1] = Cf[jt][1] * df.y;
+                Sf[jt][2] = Cf[jt][2] * df.z; Sf[jt][3] = Cf[jt][3] * df.w;
+            } else {
+                Sf[jt][0] = fmaf(Sf[jt][0], df.x, Cf[jt][0]); Sf[jt][1] = fmaf(Sf[jt][1], df.y, Cf[jt][1]);
+                Sf[jt][2] = fmaf(Sf[jt][2], df.z, Cf[jt][2]); Sf[jt][3] = fmaf(Sf[jt][3], df.w, Cf[jt][3]);
+            }
+            Sb[jt][0] = fmaf(Cb[jt][0], sb4.x, Sb[jt][0]); Sb[jt][1] = fmaf(Cb[jt][1], sb4.y, Sb[jt][1]);
+            Sb[jt][2] = fmaf(Cb[jt][2], sb4.z, Sb[jt][2]); Sb[jt][3] = fmaf(Cb[jt][3], sb4.w, Sb[jt][3]);
+        }
+        dtot_f.x *= df.x; dtot_f.y *= df.y; dtot_f.z *= df.z; dtot_f.w *= df.w;
+        dtot_b.x *= db.x; dtot_b.y *= db.y; dtot_b.z *= db.z; dtot_b.w *= db.w;
+        __syncthreads();  // every read of this chunk's LDS tiles is done
     }
 
 #pragma unroll
