@@ -40,10 +40,23 @@
 // Nothing is reversed or copied in HBM; both directions read the same q, k, v.
 //
 // Wavefront mapping (256 threads = 4 waves).  Wave w owns tokens [16w, 16w+16) of the chunk;
-// lane (r = lane%16, g = lane/16) holds channels {8g..8g+7} and {32+8g..32+8g+7} of token
-// 16w + r, which is exactly the A/B operand layout of the 16x16x32 MFMA (row r, k-slots
-// 8g..8g+7) for contractions over channels.  Contractions over tokens (P.V and the state
-// update) take their token-major operands from row-major LDS tiles through ds_read_b64_tr_b16.
+// lane (r = lane%16, g = lane/16) holds 16 channels of token 16w + r.  Slot n = 4*ct + e of the
+// lane is channel 16*ct + 4g + e: that is the accumulator layout in which the cumulative gates
+// leave the matrix cores (below), and slots 8kk..8kk+7 are the lane's k-slots of K-step kk of
+// every contraction over channels (A and B operands of the 16x16x32 MFMA only have to agree on
+// the channel of each k-slot).  LDS tiles of scaled keys and states keep channels in that
+// operand order (position 32kk + 8g + slot%8), as does the segment-state workspace; only the
+// global loads of q and k see the permutation.  Contractions over tokens (P.V, the state
+// update, the gate scan) take their token-major operands from row-major LDS tiles through
+// ds_read_b64_tr_b16.
+//
+// Cumulative gates on the matrix cores.  The chunk-level cumulative log-gate is a product with
+// a triangular 0/1 matrix, B^T[c][t] = sum_i g[i][c] * [i <= t] (or [i >= t] backward), which
+// is exact in bf16 x bf16 -> fp32.  Two K-steps of the MFMA per 16-channel tile replace the
+// wavefront prefix scans, the cross-sub-block offsets and every unpack of g on the vector
+// ALUs, which are the scarce unit on this path; a second product with the all-ones matrix gives
+// every lane the chunk totals of its channels (state decay, choice of the form).  The
+// range-safe form still scans its sub-block-local, floored gates with DPP row operations.
 #include "vig_common.hpp"
 #include "vig_kernels.hpp"
 #include "vig_timing.hpp"
@@ -65,7 +78,7 @@ constexpr int kSegChunks = 4;   // chunks per segment (ring of output tiles held
 constexpr int kThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kGateFloorLog2 = -8.0f * kLog2e;  // per-step floor of the log-gate (range-safe form), log2 domain
-constexpr float kFastRangeLog2 = 60.0f * kLog2e;  // largest chunk log-decay the fast form accepts, log2 domain
+constexpr float kFastRange = 60.0f;  // largest chunk log-decay (nats, any channel) the fast form accepts
 
 // ---- small device helpers ------------------------------------------------------------------
 
@@ -155,12 +168,13 @@ __device__ __forceinline__ bf16x8 join(s16x4 lo, s16x4 hi)
     return __builtin_bit_cast(bf16x8, v);
 }
 
-// 16 channels of one token: two 16-byte pieces at channel offsets 8g and 32+8g
+// 16 bf16 values of one token held by a lane, packed two per dword
 struct Row16 {
     uint4 p[2];
 };
 
-__device__ __forceinline__ Row16 load_row16(const uint16_t *slab_base, long token, bool valid, int g)
+// Natural order: two 16-byte pieces at channel offsets 8g and 32+8g (tiles that are only staged)
+__device__ __forceinline__ Row16 load_row_natural(const uint16_t *slab_base, long token, bool valid, int g)
 {
     Row16 r;
     if (valid) {
@@ -171,6 +185,35 @@ __device__ __forceinline__ Row16 load_row16(const uint16_t *slab_base, long toke
         r.p[0] = make_uint4(0, 0, 0, 0);
         r.p[1] = make_uint4(0, 0, 0, 0);
     }
+    return r;
+}
+
+// Operand order: slot n = 4*ct + e holds channel 16*ct + 4g + e (four 8-byte pieces)
+__device__ __forceinline__ Row16 load_row_operand(const uint16_t *slab_base, long token, bool valid, int g)
+{
+    Row16 r;
+    if (valid) {
+        const uint2 *p = reinterpret_cast<const uint2 *>(slab_base + token * kD + 4 * g);
+        const uint2 a = p[0], b = p[4], c = p[8], d = p[12];  // +16 elements each
+        r.p[0] = make_uint4(a.x, a.y, b.x, b.y);
+        r.p[1] = make_uint4(c.x, c.y, d.x, d.y);
+    } else {
+        r.p[0] = make_uint4(0, 0, 0, 0);
+        r.p[1] = make_uint4(0, 0, 0, 0);
+    }
+    return r;
+}
+
+// The same 16 slots of one token out of a natural-order LDS tile
+__device__ __forceinline__ Row16 lds_row_operand(const uint16_t (*tile)[kPitch], int row, int g)
+{
+    const uint2 a = *reinterpret_cast<const uint2 *>(&tile[row][4 * g]);
+    const uint2 b = *reinterpret_cast<const uint2 *>(&tile[row][16 + 4 * g]);
+    const uint2 c = *reinterpret_cast<const uint2 *>(&tile[row][32 + 4 * g]);
+    const uint2 d = *reinterpret_cast<const uint2 *>(&tile[row][48 + 4 * g]);
+    Row16 r;
+    r.p[0] = make_uint4(a.x, a.y, b.x, b.y);
+    r.p[1] = make_uint4(c.x, c.y, d.x, d.y);
     return r;
 }
 
@@ -229,35 +272,16 @@ struct SubOrder {
     __device__ __forceinline__ int slot(int s) const { return s == 0 ? w : (s <= nb ? before(s) : after(s - nb)); }
 };
 
-// Cumulative log2-gates of the lane's 16 channels inside its sub-block, inclusive of the lane's
-// own token, in scan order (prefix for DIR 0, suffix for DIR 1), capped at 0 (alpha <= 1).
-// FLOOR additionally floors every step at kGateFloorLog2 (range-safe form only).
-template <int DIR, bool FLOOR>
+// Range-safe form: cumulative log2-gates of the lane's 16 channels inside its sub-block,
+// inclusive of the lane's own token, in scan order (prefix for DIR 0, suffix for DIR 1); every
+// step floored at kGateFloorLog2 and capped at 0 (alpha <= 1).
+template <int DIR>
 __device__ __forceinline__ void gate_scan(const Row16 &graw, float (&b)[16])
 {
     unpack16(graw, b);
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        const float step = FLOOR ? __builtin_amdgcn_fmed3f(b[e] * kLog2e, kGateFloorLog2, 0.f)
-                                 : fminf(b[e] * kLog2e, 0.f);
-        b[e] = row_scan<DIR>(step);
-    }
-}
-
-// Largest |value| over the wave's far-edge lanes (the four lanes that hold sub-block totals),
-// identical in every lane of the wave.  Totals are <= 0, so this is -min.
-template <int DIR>
-__device__ __forceinline__ float subblock_decay_max(const float (&b)[16])
-{
-    float m = b[0];
-#pragma unroll
-    for (int e = 1; e < 16; ++e) m = fminf(m, b[e]);
-    constexpr int far = DIR == 0 ? 15 : 0;
-    float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), far));
-    float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), far + 16));
-    float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), far + 32));
-    float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), far + 48));
-    return -fminf(fminf(r0, r1), fminf(r2, r3));
+    for (int e = 0; e < 16; ++e)
+        b[e] = row_scan<DIR>(__builtin_amdgcn_fmed3f(b[e] * kLog2e, kGateFloorLog2, 0.f));
 }
 
 // Gate factors of the output sweep for the lane's token t and 16 channels, with B_mid the
@@ -273,7 +297,7 @@ __device__ __forceinline__ void gate_factors(const Row16 &graw, int r, float (&X
                                              float (&F)[16], float (&Emid)[16], float (&EB)[16])
 {
     float b[16];
-    gate_scan<DIR, true>(graw, b);
+    gate_scan<DIR>(graw, b);
     const bool is_mid = r == (DIR == 0 ? 7 : 8);
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
@@ -293,7 +317,7 @@ template <int DIR>
 __device__ __forceinline__ void gate_factors_state(const Row16 &graw, float (&F)[16], float (&EB)[16])
 {
     float b[16];
-    gate_scan<DIR, true>(graw, b);
+    gate_scan<DIR>(graw, b);
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
         const float btot = bcast_far<DIR>(b[e]);
@@ -305,21 +329,21 @@ __device__ __forceinline__ void gate_factors_state(const Row16 &graw, float (&F)
 // ---- shared memory ---------------------------------------------------------------------------
 
 struct __align__(16) OutLds {
-    uint16_t kt[kC][kPitch];   // scaled keys                  [token][channel]
-    uint16_t ks[kC][kPitch];   // range-safe form only: keys scaled for the state update [token][channel]
+    uint16_t kt[kC][kPitch];   // scaled keys                  [token][channel, operand order]
+    uint16_t ks[kC][kPitch];   // range-safe form only: keys scaled for the state update, same layout
+    uint16_t g[kC][kPitch];    // raw log-gates of the sweep's direction [token][channel, natural order]
     uint16_t v[kC][kPitch];    // values                       [token][column]
-    uint16_t st[kD][kPitch];   // carried state, bf16 copy     [column][channel]  (readout operand)
-    float bt[4][kD];           // log2 sub-block totals per channel (fast form)
+    uint16_t st[kD][kPitch];   // carried state, bf16 copy     [column][channel, operand order]
+    float tot[kD];             // chunk total log-gate per channel (fast form), operand order
     float eb[4][kD];           // whole-sub-block decay factors per channel (range-safe form)
-    float bmax[4];             // largest per-channel log2 decay of each sub-block
 };
 
 struct __align__(16) StateLds {
     uint16_t ks[2][kC][kPitch];
+    uint16_t g[2][kC][kPitch];
     uint16_t v[kC][kPitch];
-    float bt[2][4][kD];
+    float tot[2][kD];
     float eb[2][4][kD];
-    float bmax[2][4];
 };
 
 // Workspace layout per (slab, segment): two fp32 64x64 states then two fp32 decay vectors.
@@ -336,6 +360,66 @@ __device__ __forceinline__ bf16x8 token_operand(const uint16_t (*tile)[kPitch], 
 }
 
 __device__ __forceinline__ uint2 pack4(const f32x4 &p) { return make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3])); }
+
+// The lane's column of the triangular 0/1 matrix of the gate scan, as the B operand of the two
+// K-steps over the chunk's tokens: slot s of step p is token i = 16*(2p + s/4) + 4g + s%4 and
+// holds 1 when token i contributes to the cumulative gate of the lane's own token t = 16w + r,
+// i.e. i <= t forward, i >= t backward.
+template <int DIR>
+__device__ __forceinline__ void scan_triangle(int w, int r, int g, bf16x8 (&tri)[2])
+{
+    const int t = 16 * w + r;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        uint32_t word[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t bits = 0;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int slot = 2 * j + half;
+                const int i = 16 * (2 * p + slot / 4) + 4 * g + slot % 4;
+                const bool one = DIR == 0 ? (i <= t) : (i >= t);
+                bits |= (one ? 0x3F80u : 0u) << (16 * half);
+            }
+            word[j] = bits;
+        }
+        tri[p] = __builtin_bit_cast(bf16x8, make_uint4(word[0], word[1], word[2], word[3]));
+    }
+}
+
+// Cumulative log-gates of the chunk on the matrix cores (natural-log units): B[ct][e] is the
+// inclusive cumulative gate, since the chunk edge of the direction, of channel 16ct + 4g + e
+// (slot 4ct + e) at the lane's own token; T[ct][e] is the chunk total of the same channel.
+__device__ __forceinline__ void chunk_gate_scan(const uint16_t (*gtile)[kPitch], const bf16x8 (&tri)[2], int r, int g,
+                                                f32x4 (&B)[4], f32x4 (&T)[4])
+{
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+        const bf16x8 a0 = token_operand(gtile, 0, 1, 16 * ct, r, g);
+        const bf16x8 a1 = token_operand(gtile, 2, 3, 16 * ct, r, g);
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        B[ct] = mfma(a1, tri[1], mfma(a0, tri[0], zero));
+        T[ct] = mfma(a1, ones, mfma(a0, ones, zero));
+    }
+}
+
+// Largest chunk log-decay (nats) over all 64 channels, identical in every lane of the wave: the
+// four lanes 0, 16, 32, 48 together hold the totals of every channel.
+__device__ __forceinline__ float chunk_decay_max(const f32x4 (&T)[4])
+{
+    float m = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) m = fminf(m, T[ct][e]);
+    const float m0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), 0));
+    const float m1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), 16));
+    const float m2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), 32));
+    const float m3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), 48));
+    return -fminf(fminf(m0, m1), fminf(m2, m3));
+}
 
 // Diagonal 16x16 score tile, transposed (lane: keys 4g..4g+3, query r): keep key <= query for
 // the forward direction, key >= query for the backward one (own token in both).
@@ -385,38 +469,35 @@ __device__ __forceinline__ void publish_state(OutLds &sm, int w, int r, int g, c
 
 // ---- kernel 3: per-segment output sweep -------------------------------------------------------
 
-// FAST form of one chunk of one direction (see the header).  `b` is the lane's sub-block-local
-// cumulative log2-gate; sm.bt holds every sub-block's total and sm.v the chunk's values.
+// FAST form of one chunk of one direction (see the header).  B / T are the lane's cumulative and
+// total log-gates from chunk_gate_scan; sm.v holds the chunk's values.
 template <int DIR>
 __device__ __forceinline__ void out_chunk_fast(OutLds &sm, const SubOrder<DIR> &ord, const int w, const int r,
-                                               const int g, float (&b)[16], const Row16 &qraw, const Row16 &kraw,
-                                               f32x4 (&O)[4], f32x4 (&S)[4])
+                                               const int g, const f32x4 (&B)[4], const f32x4 (&T)[4],
+                                               const Row16 &qraw, const Row16 &kraw, f32x4 (&O)[4], f32x4 (&S)[4])
 {
     const int row = 16 * w + r;
-    float tmp[16];
-    // cumulative gate since the chunk edge: add the totals of the sub-blocks before this one
+    if (r == 0) {  // chunk totals per channel, operand order, for the state decay below
+        float t[16];
 #pragma unroll
-    for (int d = 1; d <= 3; ++d) {
-        if (d <= ord.nb) {
-            load_chan16(sm.bt[ord.before(d)], g, tmp);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) b[e] += tmp[e];
-        }
+        for (int n = 0; n < 16; ++n) t[n] = T[n >> 2][n & 3];
+        store_chan16(sm.tot, g, t);
     }
     float qf[16], kf[16];
     unpack16(qraw, qf);
     unpack16(kraw, kf);
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        qf[e] *= fast_exp2(b[e]);   // q * exp(b_t)
-        kf[e] *= fast_exp2(-b[e]);  // k * exp(-b_i)
+    for (int n = 0; n < 16; ++n) {
+        const float x = B[n >> 2][n & 3] * kLog2e;
+        qf[n] *= fast_exp2(x);   // q * exp(b_t)
+        kf[n] *= fast_exp2(-x);  // k * exp(-b_i)
     }
     const bf16x8 q0 = pack8(qf), q1 = pack8(qf + 8);
     const bf16x8 k0 = pack8(kf), k1 = pack8(kf + 8);
     *reinterpret_cast<bf16x8 *>(&sm.kt[row][8 * g]) = k0;
     *reinterpret_cast<bf16x8 *>(&sm.kt[row][32 + 8 * g]) = k1;
 
-    __syncthreads();  // kt visible
+    __syncthreads();  // kt, tot visible
 
     // intra-chunk scores, transposed: P^T[i][t] = sum_c kt[i][c] * qt[t][c]
     uint2 pk[4];
@@ -448,7 +529,7 @@ __device__ __forceinline__ void out_chunk_fast(OutLds &sm, const SubOrder<DIR> &
 
     accumulate_output(sm, pk, ord.nb >= 2, vop, q0, q1, r, g, O);
 
-    // state: S = diag(exp(b_end)) (S + kt^T V), rows c = 16w + 4g + e
+    // state: S = diag(exp(b_end)) (S + kt^T V), rows at LDS positions 16w + 4g + e
     {
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
@@ -456,31 +537,28 @@ __device__ __forceinline__ void out_chunk_fast(OutLds &sm, const SubOrder<DIR> &
 #pragma unroll
             for (int jt = 0; jt < 4; ++jt) S[jt] = mfma(a, vop[p][jt], S[jt]);
         }
-        float4 t = *reinterpret_cast<const float4 *>(&sm.bt[0][16 * w + 4 * g]);
-#pragma unroll
-        for (int sb = 1; sb < 4; ++sb) {
-            const float4 u = *reinterpret_cast<const float4 *>(&sm.bt[sb][16 * w + 4 * g]);
-            t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
-        }
-        const float dx = fast_exp2(t.x), dy = fast_exp2(t.y), dz = fast_exp2(t.z), dw = fast_exp2(t.w);
+        const float4 t = *reinterpret_cast<const float4 *>(&sm.tot[16 * w + 4 * g]);
+        const float dx = fast_exp2(t.x * kLog2e), dy = fast_exp2(t.y * kLog2e);
+        const float dz = fast_exp2(t.z * kLog2e), dw = fast_exp2(t.w * kLog2e);
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) {
             S[jt][0] *= dx; S[jt][1] *= dy; S[jt][2] *= dz; S[jt][3] *= dw;
         }
     }
 
-    __syncthreads();  // every read of st / kt / v / bt of this step is done
+    __syncthreads();  // every read of st / kt / v / g / tot of this step is done
     publish_state(sm, w, r, g, S);
 }
 
-// RANGE-SAFE form of one chunk of one direction (see the header); recomputes the gate scan with
-// the per-step floor.  sm.v already holds the chunk's values.
+// RANGE-SAFE form of one chunk of one direction (see the header); scans the sub-block-local,
+// floored gates itself.  sm.g / sm.v hold the chunk's raw gates and values.
 template <int DIR>
 __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const SubOrder<DIR> &ord, const int w, const int r,
-                                               const int g, const Row16 &qraw, const Row16 &kraw, const Row16 &graw,
-                                               f32x4 (&O)[4], f32x4 (&S)[4])
+                                               const int g, const Row16 &qraw, const Row16 &kraw, f32x4 (&O)[4],
+                                               f32x4 (&S)[4])
 {
     const int row = 16 * w + r;
+    const Row16 graw = lds_row_operand(sm.g, row, g);
 
     float X[16], Y[16], F[16], Emid[16], EB[16];
     gate_factors<DIR>(graw, r, X, Y, F, Emid, EB);
@@ -592,28 +670,26 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const SubOrder<DIR> &
 }
 
 // One chunk of one direction.  O accumulates this chunk's output tile, token-per-lane (token
-// 16w + r, columns 16*jt + 4g + e); S is this wave's 16 rows of the carried fp32 state (rows
-// 16w + 4g + e, column 16*jt + r).
+// 16w + r, columns 16*jt + 4g + e); S is this wave's 16 rows of the carried fp32 state (rows at
+// LDS positions 16w + 4g + e, column 16*jt + r).  graw / vraw are natural-order rows that are
+// only staged; qraw / kraw are in operand order.
 template <int DIR>
-__device__ __forceinline__ void out_chunk_step(OutLds &sm, const int w, const int r, const int g, const Row16 &qraw,
-                                               const Row16 &kraw, const Row16 &graw, const Row16 &vraw, f32x4 (&O)[4],
-                                               f32x4 (&S)[4])
+__device__ __forceinline__ void out_chunk_step(OutLds &sm, const bf16x8 (&tri)[2], const int w, const int r,
+                                               const int g, const Row16 &qraw, const Row16 &kraw, const Row16 &graw,
+                                               const Row16 &vraw, f32x4 (&O)[4], f32x4 (&S)[4])
 {
     const SubOrder<DIR> ord(w);
-    float b[16];
-    gate_scan<DIR, false>(graw, b);
-    const float wave_max = subblock_decay_max<DIR>(b);
-    if (r == (DIR == 0 ? 15 : 0)) store_chan16(sm.bt[w], g, b);  // this lane holds the sub-block totals
-    if ((threadIdx.x & 63) == 0) sm.bmax[w] = wave_max;
+    store_row16_raw(sm.g, 16 * w + r, g, graw);
     store_row16_raw(sm.v, 16 * w + r, g, vraw);
 
-    __syncthreads();  // bt, bmax, v visible
+    __syncthreads();  // g, v visible
 
-    const float4 m = *reinterpret_cast<const float4 *>(sm.bmax);
-    if (m.x + m.y + m.z + m.w <= kFastRangeLog2)  // uniform over the workgroup
-        out_chunk_fast<DIR>(sm, ord, w, r, g, b, qraw, kraw, O, S);
+    f32x4 B[4], T[4];
+    chunk_gate_scan(sm.g, tri, r, g, B, T);
+    if (chunk_decay_max(T) <= kFastRange)  // same totals in every wave: uniform over the workgroup
+        out_chunk_fast<DIR>(sm, ord, w, r, g, B, T, qraw, kraw, O, S);
     else
-        out_chunk_safe<DIR>(sm, ord, w, r, g, qraw, kraw, graw, O, S);
+        out_chunk_safe<DIR>(sm, ord, w, r, g, qraw, kraw, O, S);
 }
 
 __device__ __forceinline__ void load_state(const float *src, bool zero, int w, int r, int g, f32x4 (&S)[4])
@@ -672,15 +748,17 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
         const long tok = long(chunk0 + m) * kC + 16 * w + r;
         const bool valid = tok < L;
         ChunkRows c;
-        c.q = load_row16(q, tok, valid, g);
-        c.k = load_row16(k, tok, valid, g);
-        c.g = load_row16(gate, tok, valid, g);
-        c.v = load_row16(v, tok, valid, g);
+        c.q = load_row_operand(q, tok, valid, g);
+        c.k = load_row_operand(k, tok, valid, g);
+        c.g = load_row_natural(gate, tok, valid, g);
+        c.v = load_row_natural(v, tok, valid, g);
         return c;
     };
+    bf16x8 tri[2];
 
     // ---------------- forward sweep: chunks ascending ----------------
     ChunkRows next = fetch(0, g_fwd);
+    scan_triangle<0>(w, r, g, tri);
     load_state(st_in, st_in == nullptr, w, r, g, S);
     publish_state(sm, w, r, g, S);  // made visible by the first barrier inside the step
     for (int m = 0; m < nch; ++m) {
@@ -689,7 +767,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
         f32x4 O[4];
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) O[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        out_chunk_step<0>(sm, w, r, g, cur.q, cur.k, cur.g, cur.v, O, S);
+        out_chunk_step<0>(sm, tri, w, r, g, cur.q, cur.k, cur.g, cur.v, O, S);
         park(m, O);
     }
 
@@ -697,12 +775,15 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
     __syncthreads();  // the forward sweep's last state copy is no longer read
     load_state(st_in ? st_in + size_t(kD) * kD : nullptr, st_in == nullptr, w, r, g, S);
     publish_state(sm, w, r, g, S);
+    scan_triangle<1>(w, r, g, tri);
     for (int m = nch - 1; m >= 0; --m) {
-        const ChunkRows cur = next;
-        if (m > 0) next = fetch(m - 1, g_bwd);
+        // the parked tile comes back before the next prefetch is issued: vector-memory results
+        // return in order, so a later wait for it must not sit behind the prefetch
         f32x4 O[4];
         unpark(m, O);
-        out_chunk_step<1>(sm, w, r, g, cur.q, cur.k, cur.g, cur.v, O, S);
+        const ChunkRows cur = next;
+        if (m > 0) next = fetch(m - 1, g_bwd);
+        out_chunk_step<1>(sm, tri, w, r, g, cur.q, cur.k, cur.g, cur.v, O, S);
         // o_t = (o_fwd_t + o_bwd_t) / 2 for token 16w + r, columns 16*jt + 4g .. +3
         const long tok = long(chunk0 + m) * kC + 16 * w + r;
         if (tok < L) {
@@ -756,76 +837,70 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         const long tok = long(chunk0 + m) * kC + row;
         const bool valid = tok < L;
         ChunkRows c;
-        c.k = load_row16(k, tok, valid, g);
-        c.v = load_row16(v, tok, valid, g);
-        c.gf = load_row16(g_fwd, tok, valid, g);
-        c.gb = load_row16(g_bwd, tok, valid, g);
+        c.k = load_row_operand(k, tok, valid, g);
+        c.v = load_row_natural(v, tok, valid, g);
+        c.gf = load_row_natural(g_fwd, tok, valid, g);
+        c.gb = load_row_natural(g_bwd, tok, valid, g);
         return c;
     };
     ChunkRows next = fetch(0);
+    bf16x8 tri_f[2], tri_b[2];
+    scan_triangle<0>(w, r, g, tri_f);
+    scan_triangle<1>(w, r, g, tri_b);
 
     for (int m = 0; m < nch; ++m) {
         const ChunkRows cur = next;
         if (m + 1 < nch) next = fetch(m + 1);
 
-        float kf[16], bf[16], bb[16];
-        unpack16(cur.k, kf);
-        gate_scan<0, false>(cur.gf, bf);
-        gate_scan<1, false>(cur.gb, bb);
-        const float max_f = subblock_decay_max<0>(bf), max_b = subblock_decay_max<1>(bb);
-        if (r == 15) store_chan16(sm.bt[0][w], g, bf);
-        if (r == 0) store_chan16(sm.bt[1][w], g, bb);
-        if (lane == 0) {
-            sm.bmax[0][w] = max_f;
-            sm.bmax[1][w] = max_b;
-        }
+        store_row16_raw(sm.g[0], row, g, cur.gf);
+        store_row16_raw(sm.g[1], row, g, cur.gb);
         store_row16_raw(sm.v, row, g, cur.v);
-        __syncthreads();  // bt, bmax, v visible
+        __syncthreads();  // g, v visible
 
-        const float4 mf = *reinterpret_cast<const float4 *>(sm.bmax[0]);
-        const float4 mb = *reinterpret_cast<const float4 *>(sm.bmax[1]);
-        const bool fast = fmaxf(mf.x + mf.y + mf.z + mf.w, mb.x + mb.y + mb.z + mb.w) <= kFastRangeLog2;  // uniform
-        float4 df, db;  // this chunk's decay, rows 16w + 4g + e
+        float kf[16];
+        unpack16(cur.k, kf);
+        f32x4 Bf[4], Bb[4];
+        float max_f, max_b;
+        {
+            f32x4 T[4];
+            float t[16];
+            chunk_gate_scan(sm.g[0], tri_f, r, g, Bf, T);
+            max_f = chunk_decay_max(T);
+#pragma unroll
+            for (int n = 0; n < 16; ++n) t[n] = T[n >> 2][n & 3];
+            if (r == 0) store_chan16(sm.tot[0], g, t);  // chunk totals per channel, operand order
+            chunk_gate_scan(sm.g[1], tri_b, r, g, Bb, T);
+            max_b = chunk_decay_max(T);
+#pragma unroll
+            for (int n = 0; n < 16; ++n) t[n] = T[n >> 2][n & 3];
+            if (r == 0) store_chan16(sm.tot[1], g, t);
+        }
+        const bool fast = fmaxf(max_f, max_b) <= kFastRange;  // uniform over the workgroup
+        float4 df, db;  // this chunk's decay, rows at LDS positions 16w + 4g + e
         float tmp[16];
         if (fast) {
             // keys k * exp(-b_i), b_i cumulative since the chunk edge of each direction
+            float kb[16];
 #pragma unroll
-            for (int sb = 0; sb < 4; ++sb) {
-                if (sb < w) {
-                    load_chan16(sm.bt[0][sb], g, tmp);
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) bf[e] += tmp[e];
-                }
-                if (sb > w) {
-                    load_chan16(sm.bt[1][sb], g, tmp);
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) bb[e] += tmp[e];
-                }
+            for (int n = 0; n < 16; ++n) {
+                kb[n] = kf[n] * fast_exp2(-kLog2e * Bb[n >> 2][n & 3]);
+                kf[n] = kf[n] * fast_exp2(-kLog2e * Bf[n >> 2][n & 3]);
             }
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                bf[e] = kf[e] * fast_exp2(-bf[e]);
-                bb[e] = kf[e] * fast_exp2(-bb[e]);
-            }
-            store_row16(sm.ks[0], row, g, bf);
-            store_row16(sm.ks[1], row, g, bb);
-            float4 tf = *reinterpret_cast<const float4 *>(&sm.bt[0][0][16 * w + 4 * g]);
-            float4 tb = *reinterpret_cast<const float4 *>(&sm.bt[1][0][16 * w + 4 * g]);
-#pragma unroll
-            for (int sb = 1; sb < 4; ++sb) {
-                const float4 a = *reinterpret_cast<const float4 *>(&sm.bt[0][sb][16 * w + 4 * g]);
-                const float4 b = *reinterpret_cast<const float4 *>(&sm.bt[1][sb][16 * w + 4 * g]);
-                tf.x += a.x; tf.y += a.y; tf.z += a.z; tf.w += a.w;
-                tb.x += b.x; tb.y += b.y; tb.z += b.z; tb.w += b.w;
-            }
-            df = make_float4(fast_exp2(tf.x), fast_exp2(tf.y), fast_exp2(tf.z), fast_exp2(tf.w));
-            db = make_float4(fast_exp2(tb.x), fast_exp2(tb.y), fast_exp2(tb.z), fast_exp2(tb.w));
+            store_row16(sm.ks[0], row, g, kf);
+            store_row16(sm.ks[1], row, g, kb);
+            __syncthreads();  // ks, tot visible
+            const float4 tf = *reinterpret_cast<const float4 *>(&sm.tot[0][16 * w + 4 * g]);
+            const float4 tb = *reinterpret_cast<const float4 *>(&sm.tot[1][16 * w + 4 * g]);
+            df = make_float4(fast_exp2(tf.x * kLog2e), fast_exp2(tf.y * kLog2e), fast_exp2(tf.z * kLog2e),
+                             fast_exp2(tf.w * kLog2e));
+            db = make_float4(fast_exp2(tb.x * kLog2e), fast_exp2(tb.y * kLog2e), fast_exp2(tb.z * kLog2e),
+                             fast_exp2(tb.w * kLog2e));
         } else {
             // range-safe keys: decay from the token to the chunk edge, every factor <= 1
             float EB[16], Ff[16], Fb[16];
-            gate_factors_state<0>(cur.gf, Ff, EB);
+            gate_factors_state<0>(lds_row_operand(sm.g[0], row, g), Ff, EB);
             if (r == 0) store_chan16(sm.eb[0][w], g, EB);
-            gate_factors_state<1>(cur.gb, Fb, EB);
+            gate_factors_state<1>(lds_row_operand(sm.g[1], row, g), Fb, EB);
             if (r == 0) store_chan16(sm.eb[1][w], g, EB);
             __syncthreads();  // eb visible
 #pragma unroll
@@ -857,8 +932,8 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
                 df.x *= a.x; df.y *= a.y; df.z *= a.z; df.w *= a.w;
                 db.x *= b.x; db.y *= b.y; db.z *= b.z; db.w *= b.w;
             }
+            __syncthreads();  // ks visible
         }
-        __syncthreads();  // ks visible
 
         // chunk contributions K^T V of both directions, rows c = 16w + 4g + e
         f32x4 Cf[4], Cb[4];
