@@ -1,0 +1,36 @@
+"""Driver for rocprofv3 counter runs: a few passes of the BiGLA + locality-gate path on one
+workload, plus one plain device-to-device copy of known size that calibrates FETCH_SIZE /
+WRITE_SIZE (bytes = counter * factor, factor = known copy bytes / counter of the copy kernel).
+
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir> -o p -- python3 -m paper_2405_18425_amd.profile_path 4 3
+"""
+from __future__ import annotations
+
+import sys
+
+import torch
+
+from . import binding as vb
+from . import workloads as wl
+
+COPY_BYTES = 256 << 20  # calibration copy: reads 256 MiB, writes 256 MiB
+
+
+def main(cfg: int = 4, passes: int = 3) -> None:
+    w = wl.CONFIGS[cfg]
+    dev = "cuda:0"
+    t = {n: wl.to_torch(a, w.dtype, dev) for n, a in wl.generate(w, seed=0).items()}
+    src = torch.empty(COPY_BYTES // 4, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    dst.copy_(src)  # the calibration kernel (an elementwise copy of COPY_BYTES)
+    og = out = None
+    for _ in range(passes):
+        og = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"])
+        out = vb.locality_gate_fwd(t["v"], t["conv_w"], t["gate_logits"], og, w.Hg, w.Wg)
+    torch.cuda.synchronize()
+    print("profile_path done", w.name, passes, float(out.float().abs().mean()), flush=True)
+
+
+if __name__ == "__main__":
+    main(*(int(a) for a in sys.argv[1:3]))
