@@ -99,11 +99,12 @@ int locality_gate_fwd(const void *x, const void *w, const void *bias, const void
  * Host pointers; VIG_ERR_SHAPE for an unknown id.
  */
 typedef enum {
-    VIG_KERNEL_SEGMENT_STATE = 0, /* chunkwise path, launch 1: per-segment local end states   */
+    VIG_KERNEL_SEGMENT_STATE = 0, /* chunkwise path, launch 1: segment end states + stash     */
     VIG_KERNEL_STATE_SCAN = 1,    /* chunkwise path, launch 2: scan over segment states       */
-    VIG_KERNEL_SEGMENT_OUT = 2,   /* chunkwise path, launch 3: per-segment output sweep       */
+    VIG_KERNEL_SEGMENT_OUT = 2,   /* chunkwise path, launch 3: output pass, fast-form segments */
     VIG_KERNEL_RECURRENT = 3,     /* exact fp32 recurrence                                    */
-    VIG_KERNEL_LOCALITY_GATE = 4  /* depthwise conv + gate                                    */
+    VIG_KERNEL_LOCALITY_GATE = 4, /* depthwise conv + gate                                    */
+    VIG_KERNEL_SEGMENT_OUT_GENERAL = 5 /* chunkwise path, launch 4: output pass, other segments */
 } vig_kernel;
 int vig_timing_enable(int on);
 int vig_timing_collect(int kernel, double *total_ms, long *launches);

@@ -23,7 +23,8 @@ VIG_F32, VIG_BF16 = 0, 1
 # every symbol include/vig_bigla.h declares
 EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "locality_gate_fwd", "vig_status_str", "vig_last_hip_error",
            "vig_timing_enable", "vig_timing_collect")
-KERNELS = {"segment_state": 0, "state_scan": 1, "segment_out": 2, "recurrent": 3, "locality_gate": 4}
+KERNELS = {"segment_state": 0, "state_scan": 1, "segment_out": 2, "recurrent": 3, "locality_gate": 4,
+           "segment_out_general": 5}
 
 _lib = None
 

@@ -28,15 +28,24 @@
 //   reset whose leak is far below the bf16 tolerance), which keeps them within e^(+-64).
 // Masking is by select, never by multiplying with 0.
 //
-// Parallel decomposition.  A sequence is cut into segments of kSegChunks chunks.
-//   1. bigla_segment_state_kernel : one workgroup per (slab, segment) computes, for BOTH
-//      directions in one pass over k, v, g, the segment's local end state and total decay.
+// Parallel decomposition.  A sequence is cut into segments of consecutive chunks (the segment
+// length is chosen at launch so that the workgroups about fill the chip once).
+//   1. bigla_segment_state_kernel : one workgroup per (slab, segment) walks its chunks right to
+//      left, once, for BOTH directions: it carries the backward state and, before each chunk,
+//      stashes it (bf16, state entering the chunk from the right, local to the segment)
+//      together with the decay from that chunk's right edge to the segment's right edge; it
+//      also accumulates the segment's forward end state, the backward state at the segment's
+//      left edge and both total decays.
 //   2. bigla_state_scan_kernel    : per state element, the sequential scan over segments in
-//      both directions turns local states into the states ENTERING each segment (in place).
-//   3. bigla_segment_out_kernel   : one workgroup per (slab, segment) sweeps its chunks
-//      left-to-right for the forward direction and right-to-left for the backward direction,
-//      holding the fp32 output tiles in registers between the sweeps, and writes
-//      (o_fwd + o_bwd)/2 once.  Sequences of at most one segment need only this launch.
+//      both directions turns segment-local end states into the states ENTERING each segment
+//      (in place).  Skipped for a single segment.
+//   3. bigla_segment_out_kernel   : one workgroup per (slab, segment) walks its chunks left to
+//      right, once.  Each chunk is finished in a single step for both directions: one merged
+//      64x64 score tile (lower triangle forward, upper triangle backward, the diagonal from
+//      both), ONE P.V contraction, the forward state readout from the state carried in
+//      registers, the backward readout from the stash plus the segment's entering state
+//      (scaled per channel by the stashed decay), then the forward state update.
+//      out = (o_fwd + o_bwd)/2 is written once; q, k, v, g_fwd, g_bwd are read once here.
 // Nothing is reversed or copied in HBM; both directions read the same q, k, v.
 //
 // Wavefront mapping (256 threads = 4 waves).  Wave w owns tokens [16w, 16w+16) of the chunk;
@@ -57,6 +66,8 @@
 // ALUs, which are the scarce unit on this path; a second product with the all-ones matrix gives
 // every lane the chunk totals of its channels (state decay, choice of the form).  The
 // range-safe form still scans its sub-block-local, floored gates with DPP row operations.
+#include <type_traits>
+
 #include "vig_common.hpp"
 #include "vig_kernels.hpp"
 #include "vig_timing.hpp"
@@ -74,7 +85,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 constexpr int kC = 64;          // chunk length (tokens)
 constexpr int kD = 64;          // dk = dv
 constexpr int kPitch = 72;      // LDS row pitch in bf16 elements (64 + 8: 16-byte aligned, bank-staggered)
-constexpr int kSegChunks = 4;   // chunks per segment (ring of output tiles held in registers)
+constexpr int kTargetWorkgroups = 512;  // segments are sized so that about this many workgroups are launched
 constexpr int kThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kGateFloorLog2 = -8.0f * kLog2e;  // per-step floor of the log-gate (range-safe form), log2 domain
@@ -329,13 +340,18 @@ __device__ __forceinline__ void gate_factors_state(const Row16 &graw, float (&F)
 // ---- shared memory ---------------------------------------------------------------------------
 
 struct __align__(16) OutLds {
-    uint16_t kt[kC][kPitch];   // scaled keys                  [token][channel, operand order]
-    uint16_t ks[kC][kPitch];   // range-safe form only: keys scaled for the state update, same layout
-    uint16_t g[kC][kPitch];    // raw log-gates of the sweep's direction [token][channel, natural order]
-    uint16_t v[kC][kPitch];    // values                       [token][column]
-    uint16_t st[kD][kPitch];   // carried state, bf16 copy     [column][channel, operand order]
-    float tot[kD];             // chunk total log-gate per channel (fast form), operand order
-    float eb[4][kD];           // whole-sub-block decay factors per channel (range-safe form)
+    uint16_t kf[kC][kPitch];    // forward-scaled keys           [token][channel, operand order]
+    uint16_t kb[kC][kPitch];    // backward-scaled keys          [token][channel, operand order]
+    uint16_t gf[kC][kPitch];    // raw forward log-gates         [token][channel, natural order]
+    uint16_t gb[kC][kPitch];    // raw backward log-gates        [token][channel, natural order];
+                                // the range-safe form reuses it for the forward state-update keys
+    uint16_t v[kC][kPitch];     // values                        [token][column]
+    uint16_t st[kD][kPitch];    // forward state, bf16 copy      [column][channel, operand order]
+    uint16_t sb[kD][kPitch];    // stashed backward state entering the chunk, same layout
+    uint16_t sseg[kD][kPitch];  // backward state entering the segment, same layout
+    float tot[kD];              // forward chunk total log-gate per channel (fast form), operand order
+    float dr[kD];               // decay from the chunk's right edge to the segment's right edge
+    float eb[2][4][kD];         // whole-sub-block decay factors per channel (range-safe form)
 };
 
 struct __align__(16) StateLds {
@@ -346,9 +362,33 @@ struct __align__(16) StateLds {
     float eb[2][4][kD];
 };
 
-// Workspace layout per (slab, segment): two fp32 64x64 states then two fp32 decay vectors.
+// Workspace: [segment region][segment flags][stash region].
+//   segment region, per (slab, segment): two fp32 64x64 states (forward, backward) then two
+//     fp32 decay vectors; rows in operand order.
+//   segment flags, per (slab, segment): one int, non-zero when every chunk of the segment
+//     admits the fast form (written by the state kernel); padded to a multiple of 16 bytes.
+//   stash region, per (slab, chunk): one bf16 64x64 state in accumulator order (thread t of
+//     the workgroup owns 16 consecutive values: columns 16*jt + r of rows 16w + 4g + e), then
+//     one fp32 decay vector.
 constexpr size_t kSegStateFloats = 2 * size_t(kD) * kD;
 constexpr size_t kSegFloats = kSegStateFloats + 2 * kD;
+constexpr size_t kStashBytes = size_t(kD) * kD * sizeof(uint16_t) + kD * sizeof(float);
+
+struct Plan {
+    int n_chunks, seg_chunks, n_seg;
+};
+
+inline Plan make_plan(long BH, int L)
+{
+    Plan p;
+    p.n_chunks = (L + kC - 1) / kC;
+    long want = kTargetWorkgroups / (BH > 0 ? BH : 1);
+    if (want < 1) want = 1;
+    if (want > p.n_chunks) want = p.n_chunks;
+    p.seg_chunks = int((p.n_chunks + want - 1) / want);
+    p.n_seg = (p.n_chunks + p.seg_chunks - 1) / p.seg_chunks;
+    return p;
+}
 
 // Token-major MFMA operands of a 64-token tile for contractions over tokens.  k-slot layout:
 // slots 0..3 = tokens 4g..4g+3 of sub-block s0, slots 4..7 = the same tokens of sub-block s1.
@@ -405,6 +445,19 @@ __device__ __forceinline__ void chunk_gate_scan(const uint16_t (*gtile)[kPitch],
     }
 }
 
+// The cumulative gates alone
+__device__ __forceinline__ void chunk_gate_scan(const uint16_t (*gtile)[kPitch], const bf16x8 (&tri)[2], int r, int g,
+                                                f32x4 (&B)[4])
+{
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+        const bf16x8 a0 = token_operand(gtile, 0, 1, 16 * ct, r, g);
+        const bf16x8 a1 = token_operand(gtile, 2, 3, 16 * ct, r, g);
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        B[ct] = mfma(a1, tri[1], mfma(a0, tri[0], zero));
+    }
+}
+
 // Largest chunk log-decay (nats) over all 64 channels, identical in every lane of the wave: the
 // four lanes 0, 16, 32, 48 together hold the totals of every channel.
 __device__ __forceinline__ float chunk_decay_max(const f32x4 (&T)[4])
@@ -435,261 +488,12 @@ __device__ __forceinline__ uint2 masked_diag(f32x4 p, int r, int g)
     return pack4(p);
 }
 
-// O^T += V^T.P^T over the visible sub-blocks, then the readout S^T.q^T of the incoming state.
-// Computed transposed so that the accumulators are token-per-lane: lane (r, g) ends up with
-// columns 16*jt + 4g .. +3 of its own token 16w + r.
-__device__ __forceinline__ void accumulate_output(const OutLds &sm, const uint2 (&pk)[4], bool second_pair,
-                                                  const bf16x8 (&vop)[2][4], bf16x8 qr0, bf16x8 qr1, int r, int g,
-                                                  f32x4 (&O)[4])
-{
-    const bf16x8 pa0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0].x, pk[0].y, pk[1].x, pk[1].y));
-#pragma unroll
-    for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(vop[0][jt], pa0, O[jt]);
-    if (second_pair) {
-        const bf16x8 pa1 = __builtin_bit_cast(bf16x8, make_uint4(pk[2].x, pk[2].y, pk[3].x, pk[3].y));
-#pragma unroll
-        for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(vop[1][jt], pa1, O[jt]);
-    }
-#pragma unroll
-    for (int jt = 0; jt < 4; ++jt) {
-        const bf16x8 b0 = *reinterpret_cast<const bf16x8 *>(&sm.st[16 * jt + r][8 * g]);
-        const bf16x8 b1 = *reinterpret_cast<const bf16x8 *>(&sm.st[16 * jt + r][32 + 8 * g]);
-        O[jt] = mfma(b0, qr0, O[jt]);
-        O[jt] = mfma(b1, qr1, O[jt]);
-    }
-}
-
-// bf16 copy of the carried state for the next readout, [column][channel]
-__device__ __forceinline__ void publish_state(OutLds &sm, int w, int r, int g, const f32x4 (&S)[4])
+// bf16 copy of an fp32 state tile held in accumulator layout (rows at positions 16w + 4g + e,
+// column 16*jt + r) into a [column][channel] tile
+__device__ __forceinline__ void publish_state(uint16_t (*tile)[kPitch], int w, int r, int g, const f32x4 (&S)[4])
 {
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt)
-        *reinterpret_cast<uint2 *>(&sm.st[16 * jt + r][16 * w + 4 * g]) = pack4(S[jt]);
-}
-
-// ---- kernel 3: per-segment output sweep -------------------------------------------------------
-
-// FAST form of one chunk of one direction (see the header).  B / T are the lane's cumulative and
-// total log-gates from chunk_gate_scan; sm.v holds the chunk's values.
-template <int DIR>
-__device__ __forceinline__ void out_chunk_fast(OutLds &sm, const SubOrder<DIR> &ord, const int w, const int r,
-                                               const int g, const f32x4 (&B)[4], const f32x4 (&T)[4],
-                                               const Row16 &qraw, const Row16 &kraw, f32x4 (&O)[4], f32x4 (&S)[4])
-{
-    const int row = 16 * w + r;
-    if (r == 0) {  // chunk totals per channel, operand order, for the state decay below
-        float t[16];
-#pragma unroll
-        for (int n = 0; n < 16; ++n) t[n] = T[n >> 2][n & 3];
-        store_chan16(sm.tot, g, t);
-    }
-    float qf[16], kf[16];
-    unpack16(qraw, qf);
-    unpack16(kraw, kf);
-#pragma unroll
-    for (int n = 0; n < 16; ++n) {
-        const float x = B[n >> 2][n & 3] * kLog2e;
-        qf[n] *= fast_exp2(x);   // q * exp(b_t)
-        kf[n] *= fast_exp2(-x);  // k * exp(-b_i)
-    }
-    const bf16x8 q0 = pack8(qf), q1 = pack8(qf + 8);
-    const bf16x8 k0 = pack8(kf), k1 = pack8(kf + 8);
-    *reinterpret_cast<bf16x8 *>(&sm.kt[row][8 * g]) = k0;
-    *reinterpret_cast<bf16x8 *>(&sm.kt[row][32 + 8 * g]) = k1;
-
-    __syncthreads();  // kt, tot visible
-
-    // intra-chunk scores, transposed: P^T[i][t] = sum_c kt[i][c] * qt[t][c]
-    uint2 pk[4];
-    {
-        f32x4 p = {0.f, 0.f, 0.f, 0.f};
-        p = mfma(k0, q0, p);
-        p = mfma(k1, q1, p);
-        pk[0] = masked_diag<DIR>(p, r, g);
-    }
-#pragma unroll
-    for (int d = 1; d <= 3; ++d) {
-        if (d <= ord.nb) {
-            const int kb = ord.before(d);
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kt[16 * kb + r][8 * g]);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kt[16 * kb + r][32 + 8 * g]);
-            f32x4 p = {0.f, 0.f, 0.f, 0.f};
-            p = mfma(a0, q0, p);
-            p = mfma(a1, q1, p);
-            pk[d] = pack4(p);
-        } else {
-            pk[d] = make_uint2(0u, 0u);
-        }
-    }
-    bf16x8 vop[2][4];
-#pragma unroll
-    for (int p = 0; p < 2; ++p)
-#pragma unroll
-        for (int jt = 0; jt < 4; ++jt) vop[p][jt] = token_operand(sm.v, ord.slot(2 * p), ord.slot(2 * p + 1), 16 * jt, r, g);
-
-    accumulate_output(sm, pk, ord.nb >= 2, vop, q0, q1, r, g, O);
-
-    // state: S = diag(exp(b_end)) (S + kt^T V), rows at LDS positions 16w + 4g + e
-    {
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const bf16x8 a = token_operand(sm.kt, ord.slot(2 * p), ord.slot(2 * p + 1), 16 * w, r, g);
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt) S[jt] = mfma(a, vop[p][jt], S[jt]);
-        }
-        const float4 t = *reinterpret_cast<const float4 *>(&sm.tot[16 * w + 4 * g]);
-        const float dx = fast_exp2(t.x * kLog2e), dy = fast_exp2(t.y * kLog2e);
-        const float dz = fast_exp2(t.z * kLog2e), dw = fast_exp2(t.w * kLog2e);
-#pragma unroll
-        for (int jt = 0; jt < 4; ++jt) {
-            S[jt][0] *= dx; S[jt][1] *= dy; S[jt][2] *= dz; S[jt][3] *= dw;
-        }
-    }
-
-    __syncthreads();  // every read of st / kt / v / g / tot of this step is done
-    publish_state(sm, w, r, g, S);
-}
-
-// RANGE-SAFE form of one chunk of one direction (see the header); scans the sub-block-local,
-// floored gates itself.  sm.g / sm.v hold the chunk's raw gates and values.
-template <int DIR>
-__device__ __forceinline__ void out_chunk_safe(OutLds &sm, const SubOrder<DIR> &ord, const int w, const int r,
-                                               const int g, const Row16 &qraw, const Row16 &kraw, f32x4 (&O)[4],
-                                               f32x4 (&S)[4])
-{
-    const int row = 16 * w + r;
-    const Row16 graw = lds_row_operand(sm.g, row, g);
-
-    float X[16], Y[16], F[16], Emid[16], EB[16];
-    gate_factors<DIR>(graw, r, X, Y, F, Emid, EB);
-    if (r == 0) store_chan16(sm.eb[w], g, EB);  // whole-sub-block decay exp(B_w)
-
-    float qf[16], kf[16];
-    unpack16(qraw, qf);
-    unpack16(kraw, kf);
-    float khat[16], tmp[16], cum[16];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) khat[e] = kf[e] * F[e];
-    store_row16(sm.kt, row, g, khat);
-    // diagonal tile operands, both referred to the middle of the sub-block
-#pragma unroll
-    for (int e = 0; e < 16; ++e) tmp[e] = kf[e] * Y[e];
-    const bf16x8 kd0 = pack8(tmp), kd1 = pack8(tmp + 8);
-#pragma unroll
-    for (int e = 0; e < 16; ++e) cum[e] = qf[e] * X[e];
-    const bf16x8 qd0 = pack8(cum), qd1 = pack8(cum + 8);
-
-    __syncthreads();  // eb, kt visible
-
-    // query variants: qv[d] pairs with the keys of before(d+1); readout uses the full product.
-    // q * exp(b_t) = (q * X) * Emid is the decay since the near edge of the query's sub-block.
-#pragma unroll
-    for (int e = 0; e < 16; ++e) cum[e] *= Emid[e];
-    bf16x8 qv[3][2];
-    qv[0][0] = pack8(cum);
-    qv[0][1] = pack8(cum + 8);
-#pragma unroll
-    for (int d = 1; d <= 3; ++d) {
-        if (d <= ord.nb) {
-            load_chan16(sm.eb[ord.before(d)], g, tmp);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) cum[e] *= tmp[e];
-            if (d < 3) {
-                qv[d][0] = pack8(cum);
-                qv[d][1] = pack8(cum + 8);
-            }
-        }
-    }
-    const bf16x8 qr0 = pack8(cum), qr1 = pack8(cum + 8);  // readout queries: q * exp(decay since chunk edge)
-
-    // state-update keys: khat times the whole sub-blocks after this one
-#pragma unroll
-    for (int a = 1; a <= 3; ++a) {
-        if (a <= 3 - ord.nb) {
-            load_chan16(sm.eb[ord.after(a)], g, tmp);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) khat[e] *= tmp[e];
-        }
-    }
-    store_row16(sm.ks, row, g, khat);
-
-    __syncthreads();  // ks visible
-
-    // intra-chunk scores, transposed: P^T[i][t] = sum_c khat[i][c] * qv[t][c]
-    uint2 pk[4];
-    {
-        f32x4 p = {0.f, 0.f, 0.f, 0.f};
-        p = mfma(kd0, qd0, p);
-        p = mfma(kd1, qd1, p);
-        pk[0] = masked_diag<DIR>(p, r, g);
-    }
-#pragma unroll
-    for (int d = 1; d <= 3; ++d) {
-        if (d <= ord.nb) {
-            const int kb = ord.before(d);
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kt[16 * kb + r][8 * g]);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kt[16 * kb + r][32 + 8 * g]);
-            f32x4 p = {0.f, 0.f, 0.f, 0.f};
-            p = mfma(a0, qv[d - 1][0], p);
-            p = mfma(a1, qv[d - 1][1], p);
-            pk[d] = pack4(p);
-        } else {
-            pk[d] = make_uint2(0u, 0u);
-        }
-    }
-    bf16x8 vop[2][4];
-#pragma unroll
-    for (int p = 0; p < 2; ++p)
-#pragma unroll
-        for (int jt = 0; jt < 4; ++jt) vop[p][jt] = token_operand(sm.v, ord.slot(2 * p), ord.slot(2 * p + 1), 16 * jt, r, g);
-
-    accumulate_output(sm, pk, ord.nb >= 2, vop, qr0, qr1, r, g, O);
-
-    // state update: S = diag(chunk decay) S + ks^T V  (rows c = 16w + 4g + e)
-    {
-        float4 dch = *reinterpret_cast<const float4 *>(&sm.eb[0][16 * w + 4 * g]);
-#pragma unroll
-        for (int sb = 1; sb < 4; ++sb) {
-            const float4 t = *reinterpret_cast<const float4 *>(&sm.eb[sb][16 * w + 4 * g]);
-            dch.x *= t.x; dch.y *= t.y; dch.z *= t.z; dch.w *= t.w;
-        }
-#pragma unroll
-        for (int jt = 0; jt < 4; ++jt) {
-            S[jt][0] *= dch.x; S[jt][1] *= dch.y; S[jt][2] *= dch.z; S[jt][3] *= dch.w;
-        }
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const bf16x8 a = token_operand(sm.ks, ord.slot(2 * p), ord.slot(2 * p + 1), 16 * w, r, g);
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt) S[jt] = mfma(a, vop[p][jt], S[jt]);
-        }
-    }
-
-    __syncthreads();  // every read of st / kt / ks / v / eb of this step is done
-    publish_state(sm, w, r, g, S);
-}
-
-// One chunk of one direction.  O accumulates this chunk's output tile, token-per-lane (token
-// 16w + r, columns 16*jt + 4g + e); S is this wave's 16 rows of the carried fp32 state (rows at
-// LDS positions 16w + 4g + e, column 16*jt + r).  graw / vraw are natural-order rows that are
-// only staged; qraw / kraw are in operand order.
-template <int DIR>
-__device__ __forceinline__ void out_chunk_step(OutLds &sm, const bf16x8 (&tri)[2], const int w, const int r,
-                                               const int g, const Row16 &qraw, const Row16 &kraw, const Row16 &graw,
-                                               const Row16 &vraw, f32x4 (&O)[4], f32x4 (&S)[4])
-{
-    const SubOrder<DIR> ord(w);
-    store_row16_raw(sm.g, 16 * w + r, g, graw);
-    store_row16_raw(sm.v, 16 * w + r, g, vraw);
-
-    __syncthreads();  // g, v visible
-
-    f32x4 B[4], T[4];
-    chunk_gate_scan(sm.g, tri, r, g, B, T);
-    if (chunk_decay_max(T) <= kFastRange)  // same totals in every wave: uniform over the workgroup
-        out_chunk_fast<DIR>(sm, ord, w, r, g, B, T, qraw, kraw, O, S);
-    else
-        out_chunk_safe<DIR>(sm, ord, w, r, g, qraw, kraw, O, S);
+    for (int jt = 0; jt < 4; ++jt) *reinterpret_cast<uint2 *>(&tile[16 * jt + r][16 * w + 4 * g]) = pack4(S[jt]);
 }
 
 __device__ __forceinline__ void load_state(const float *src, bool zero, int w, int r, int g, f32x4 (&S)[4])
@@ -700,108 +504,421 @@ __device__ __forceinline__ void load_state(const float *src, bool zero, int w, i
         for (int e = 0; e < 4; ++e) S[jt][e] = zero ? 0.f : src[(16 * w + 4 * g + e) * kD + 16 * jt + r];
 }
 
+// O^T += S^T q^T for one [column][channel] state tile (readout of a state by scaled queries)
+__device__ __forceinline__ void readout(const uint16_t (*tile)[kPitch], bf16x8 q0, bf16x8 q1, int r, int g,
+                                        f32x4 (&O)[4])
+{
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) {
+        const bf16x8 s0 = *reinterpret_cast<const bf16x8 *>(&tile[16 * jt + r][8 * g]);
+        const bf16x8 s1 = *reinterpret_cast<const bf16x8 *>(&tile[16 * jt + r][32 + 8 * g]);
+        O[jt] = mfma(s0, q0, O[jt]);
+        O[jt] = mfma(s1, q1, O[jt]);
+    }
+}
+
+// ---- kernel 3: per-segment output pass --------------------------------------------------------
+
+// What the first half of a chunk step (scores) hands to the second half (finish_chunk)
+struct ChunkOperands {
+    uint2 pk[4];                       // merged masked score tile, bf16, per key sub-block
+    bf16x8 qf0, qf1, qb0, qb1, qs0, qs1;  // readout queries: forward, backward (stash), backward (segment)
+};
+
+struct ChunkFlags {
+    bool stash;  // a backward state stashed for this chunk exists (not the segment's last chunk)
+    bool seg;    // a backward state enters the segment from the right
+};
+
+// Everything after the score tiles, common to both forms: O^T = V^T P^T + the three readouts,
+// out = O/2, then the forward state update with the keys in `ktile`.
+// fast_update: S = d (S + K^T V) with d = exp(tot); otherwise S = d S + K^T V with d = prod(eb).
+__device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)[kPitch], const ChunkOperands &op,
+                                             const ChunkFlags fl, const bool fast_update, const int w, const int r,
+                                             const int g, uint16_t *out_row, f32x4 (&S)[4])
+{
+    const uint2(&pk)[4] = op.pk;
+    bf16x8 vop[2][4];
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) vop[p][jt] = token_operand(sm.v, 2 * p, 2 * p + 1, 16 * jt, r, g);
+
+    // token-per-lane accumulators: lane (r, g) gets columns 16*jt + 4g .. +3 of its own token
+    f32x4 O[4];
+    {
+        const bf16x8 pa0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0].x, pk[0].y, pk[1].x, pk[1].y));
+        const bf16x8 pa1 = __builtin_bit_cast(bf16x8, make_uint4(pk[2].x, pk[2].y, pk[3].x, pk[3].y));
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(vop[1][jt], pa1, mfma(vop[0][jt], pa0, zero));
+    }
+    readout(sm.st, op.qf0, op.qf1, r, g, O);
+    if (fl.stash) readout(sm.sb, op.qb0, op.qb1, r, g, O);
+    if (fl.seg) readout(sm.sseg, op.qs0, op.qs1, r, g, O);
+    if (out_row) {  // o_t = (o_fwd_t + o_bwd_t) / 2
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt)
+            *reinterpret_cast<uint2 *>(out_row + 16 * jt + 4 * g) =
+                make_uint2(pack2(0.5f * O[jt][0], 0.5f * O[jt][1]), pack2(0.5f * O[jt][2], 0.5f * O[jt][3]));
+    }
+
+    // forward state, rows at LDS positions 16w + 4g + e
+    float4 d;
+    if (fast_update) {
+        const float4 t = *reinterpret_cast<const float4 *>(&sm.tot[16 * w + 4 * g]);
+        d = make_float4(fast_exp2(t.x * kLog2e), fast_exp2(t.y * kLog2e), fast_exp2(t.z * kLog2e),
+                        fast_exp2(t.w * kLog2e));
+    } else {
+        d = *reinterpret_cast<const float4 *>(&sm.eb[0][0][16 * w + 4 * g]);
+#pragma unroll
+        for (int sb = 1; sb < 4; ++sb) {
+            const float4 t = *reinterpret_cast<const float4 *>(&sm.eb[0][sb][16 * w + 4 * g]);
+            d.x *= t.x; d.y *= t.y; d.z *= t.z; d.w *= t.w;
+        }
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            S[jt][0] *= d.x; S[jt][1] *= d.y; S[jt][2] *= d.z; S[jt][3] *= d.w;
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const bf16x8 a = token_operand(ktile, 2 * p, 2 * p + 1, 16 * w, r, g);
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) S[jt] = mfma(a, vop[p][jt], S[jt]);
+    }
+    if (fast_update) {
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            S[jt][0] *= d.x; S[jt][1] *= d.y; S[jt][2] *= d.z; S[jt][3] *= d.w;
+        }
+    }
+
+    __syncthreads();  // every LDS read of this step is done
+    publish_state(sm.st, w, r, g, S);
+}
+
+// FAST form of one chunk, both directions (see the header).  Bf / Bb are the lane's cumulative
+// log-gates of the two directions, Tf the forward chunk totals.
+__device__ __forceinline__ void out_chunk_fast(OutLds &sm, const int w, const int r, const int g, const f32x4 (&Bf)[4],
+                                               const f32x4 (&Bb)[4], const f32x4 (&Tf)[4], const Row16 &qraw,
+                                               const Row16 &kraw, const ChunkFlags fl, ChunkOperands &op)
+{
+    const int row = 16 * w + r;
+    if (r == 0) {  // forward chunk totals per channel, operand order, for the state decay
+        float t[16];
+#pragma unroll
+        for (int n = 0; n < 16; ++n) t[n] = Tf[n >> 2][n & 3];
+        store_chan16(sm.tot, g, t);
+    }
+    float qf[16], kf[16], qb[16], kb[16];
+    unpack16(qraw, qf);
+    unpack16(kraw, kf);
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+        const float xf = Bf[n >> 2][n & 3] * kLog2e, xb = Bb[n >> 2][n & 3] * kLog2e;
+        qb[n] = qf[n] * fast_exp2(xb);   // q * exp(c_t)    backward
+        kb[n] = kf[n] * fast_exp2(-xb);  // k * exp(-c_i)
+        qf[n] *= fast_exp2(xf);          // q * exp(b_t)    forward
+        kf[n] *= fast_exp2(-xf);         // k * exp(-b_i)
+    }
+    const bf16x8 qf0 = pack8(qf), qf1 = pack8(qf + 8), qb0 = pack8(qb), qb1 = pack8(qb + 8);
+    const bf16x8 kf0 = pack8(kf), kf1 = pack8(kf + 8), kb0 = pack8(kb), kb1 = pack8(kb + 8);
+    *reinterpret_cast<bf16x8 *>(&sm.kf[row][8 * g]) = kf0;
+    *reinterpret_cast<bf16x8 *>(&sm.kf[row][32 + 8 * g]) = kf1;
+    *reinterpret_cast<bf16x8 *>(&sm.kb[row][8 * g]) = kb0;
+    *reinterpret_cast<bf16x8 *>(&sm.kb[row][32 + 8 * g]) = kb1;
+    // queries that read the state entering the SEGMENT: further decay from the chunk's right edge
+    bf16x8 qs0 = qb0, qs1 = qb1;
+    if (fl.seg) {
+        float dr[16];
+        load_chan16(sm.dr, g, dr);
+#pragma unroll
+        for (int n = 0; n < 16; ++n) qb[n] *= dr[n];
+        qs0 = pack8(qb);
+        qs1 = pack8(qb + 8);
+    }
+
+    __syncthreads();  // kf, kb, tot visible
+
+    // merged score tile, transposed: P^T[i][t]; key sub-block I < w forward, I > w backward,
+    // I = w the masked sum of both (own token counted by both directions)
+#pragma unroll
+    for (int I = 0; I < 4; ++I) {
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        if (I == w) {
+            f32x4 pf = mfma(kf1, qf1, mfma(kf0, qf0, zero));
+            f32x4 pb = mfma(kb1, qb1, mfma(kb0, qb0, zero));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = 4 * g + e;
+                pf[e] = (i <= r ? pf[e] : 0.f) + (i >= r ? pb[e] : 0.f);
+            }
+            op.pk[I] = pack4(pf);
+        } else if (I < w) {
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kf[16 * I + r][8 * g]);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kf[16 * I + r][32 + 8 * g]);
+            op.pk[I] = pack4(mfma(a1, qf1, mfma(a0, qf0, zero)));
+        } else {
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][8 * g]);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][32 + 8 * g]);
+            op.pk[I] = pack4(mfma(a1, qb1, mfma(a0, qb0, zero)));
+        }
+    }
+    op.qf0 = qf0; op.qf1 = qf1; op.qb0 = qb0; op.qb1 = qb1; op.qs0 = qs0; op.qs1 = qs1;
+}
+
+// RANGE-SAFE form of one chunk, both directions (see the header); scans the sub-block-local,
+// floored gates itself from the staged raw gates.
+__device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const int r, const int g, const Row16 &qraw,
+                                               const Row16 &kraw, const ChunkFlags fl, ChunkOperands &op)
+{
+    const int row = 16 * w + r;
+    float qf[16], kf[16], tmp[16];
+    unpack16(qraw, qf);
+    unpack16(kraw, kf);
+
+    // per direction: diagonal-tile operands (referred to the middle of the sub-block), the keys
+    // for off-diagonal tiles (decay to the far edge of their sub-block) and the running query
+    bf16x8 kd[2][2], qd[2][2];
+    float cum[2][16], khat_f[16];
+    {
+        float X[16], Y[16], F[16], Emid[16], EB[16];
+        gate_factors<0>(lds_row_operand(sm.gf, row, g), r, X, Y, F, Emid, EB);
+        if (r == 0) store_chan16(sm.eb[0][w], g, EB);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) khat_f[e] = kf[e] * F[e];
+        store_row16(sm.kf, row, g, khat_f);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tmp[e] = kf[e] * Y[e];
+        kd[0][0] = pack8(tmp); kd[0][1] = pack8(tmp + 8);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tmp[e] = qf[e] * X[e];
+        qd[0][0] = pack8(tmp); qd[0][1] = pack8(tmp + 8);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) cum[0][e] = tmp[e] * Emid[e];  // q * exp(decay since the sub-block's near edge)
+    }
+    {
+        float X[16], Y[16], F[16], Emid[16], EB[16];
+        gate_factors<1>(lds_row_operand(sm.gb, row, g), r, X, Y, F, Emid, EB);
+        if (r == 0) store_chan16(sm.eb[1][w], g, EB);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tmp[e] = kf[e] * F[e];
+        store_row16(sm.kb, row, g, tmp);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tmp[e] = kf[e] * Y[e];
+        kd[1][0] = pack8(tmp); kd[1][1] = pack8(tmp + 8);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tmp[e] = qf[e] * X[e];
+        qd[1][0] = pack8(tmp); qd[1][1] = pack8(tmp + 8);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) cum[1][e] = tmp[e] * Emid[e];
+    }
+
+    __syncthreads();  // eb, kf, kb visible; the raw gate tiles are no longer read
+
+    // query variants: qv[dir][d] pairs with the keys d+1 sub-blocks away in that direction's
+    // past; after the last one the running query is the readout query (decay since the chunk edge)
+    bf16x8 qv[2][3][2];
+#pragma unroll
+    for (int dir = 0; dir < 2; ++dir) {
+        const int nb = dir == 0 ? w : 3 - w;
+        qv[dir][0][0] = pack8(cum[dir]);
+        qv[dir][0][1] = pack8(cum[dir] + 8);
+#pragma unroll
+        for (int d = 1; d <= 3; ++d) {
+            if (d <= nb) {
+                load_chan16(sm.eb[dir][dir == 0 ? w - d : w + d], g, tmp);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) cum[dir][e] *= tmp[e];
+                if (d < 3) {
+                    qv[dir][d][0] = pack8(cum[dir]);
+                    qv[dir][d][1] = pack8(cum[dir] + 8);
+                }
+            }
+        }
+    }
+    const bf16x8 qf0 = pack8(cum[0]), qf1 = pack8(cum[0] + 8), qb0 = pack8(cum[1]), qb1 = pack8(cum[1] + 8);
+    bf16x8 qs0 = qb0, qs1 = qb1;
+    if (fl.seg) {
+        load_chan16(sm.dr, g, tmp);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) cum[1][e] *= tmp[e];
+        qs0 = pack8(cum[1]);
+        qs1 = pack8(cum[1] + 8);
+    }
+    // forward state-update keys: decay to the chunk's right edge = khat times the sub-blocks to
+    // the right; they take the place of the raw backward gates in LDS
+#pragma unroll
+    for (int sb = 1; sb < 4; ++sb) {
+        if (sb > w) {
+            load_chan16(sm.eb[0][sb], g, tmp);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) khat_f[e] *= tmp[e];
+        }
+    }
+    store_row16(sm.gb, row, g, khat_f);
+
+    __syncthreads();  // state-update keys visible
+
+#pragma unroll
+    for (int I = 0; I < 4; ++I) {
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        if (I == w) {
+            f32x4 pf = mfma(kd[0][1], qd[0][1], mfma(kd[0][0], qd[0][0], zero));
+            f32x4 pb = mfma(kd[1][1], qd[1][1], mfma(kd[1][0], qd[1][0], zero));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = 4 * g + e;
+                pf[e] = (i <= r ? pf[e] : 0.f) + (i >= r ? pb[e] : 0.f);
+            }
+            op.pk[I] = pack4(pf);
+        } else {
+            const bool fwd = I < w;
+            const uint16_t(*kt)[kPitch] = fwd ? sm.kf : sm.kb;
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&kt[16 * I + r][8 * g]);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&kt[16 * I + r][32 + 8 * g]);
+            f32x4 p = zero;
+#pragma unroll
+            for (int d = 1; d <= 3; ++d) {
+                if ((fwd ? w - I : I - w) == d) {
+                    const int dir = fwd ? 0 : 1;
+                    // compile-time variant index, uniform run-time choice of the direction
+                    const bf16x8 b0 = dir == 0 ? qv[0][d - 1][0] : qv[1][d - 1][0];
+                    const bf16x8 b1 = dir == 0 ? qv[0][d - 1][1] : qv[1][d - 1][1];
+                    p = mfma(a1, b1, mfma(a0, b0, zero));
+                }
+            }
+            op.pk[I] = pack4(p);
+        }
+    }
+    op.qf0 = qf0; op.qf1 = qf1; op.qb0 = qb0; op.qb1 = qb1; op.qs0 = qs0; op.qs1 = qs1;
+}
+
+// kFastOnly = true : handles the segments the state kernel has flagged as entirely within the
+//                     fast form's range, and contains no range-safe code (whose register
+//                     footprint would otherwise spill into the fast path); other segments exit.
+// kFastOnly = false: handles the remaining segments (all of them when seg_mild is nullptr), each
+//                     chunk choosing its form.
+template <bool kFastOnly>
 __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     const uint16_t *__restrict__ g_fwd, const uint16_t *__restrict__ g_bwd, uint16_t *__restrict__ out,
-    const float *__restrict__ seg_states /* states entering each segment, or nullptr when one segment */, int L,
-    int n_seg)
+    const float *__restrict__ seg_states /* states entering each segment, nullptr when one segment */,
+    const int *__restrict__ seg_mild /* per (slab, segment): every chunk admits the fast form; may be nullptr */,
+    const unsigned char *__restrict__ stash, int L, int n_chunks, int seg_chunks, int n_seg)
 {
     __shared__ OutLds sm;
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
     const long slab = blockIdx.x / n_seg;
     const int seg = blockIdx.x % n_seg;
+    {
+        const bool mild = seg_mild != nullptr && seg_mild[slab * n_seg + seg] != 0;  // uniform over the workgroup
+        if (mild != kFastOnly) return;
+    }
     const long base = slab * L * kD;
     q += base; k += base; v += base; g_fwd += base; g_bwd += base; out += base;
+    stash += size_t(slab) * n_chunks * kStashBytes;
 
-    const int chunk0 = seg * kSegChunks;
-    const int n_chunks_total = (L + kC - 1) / kC;
-    const int nch = min(kSegChunks, n_chunks_total - chunk0);
+    const int chunk0 = seg * seg_chunks;
+    const int nch = min(seg_chunks, n_chunks - chunk0);
     const float *st_in = seg_states ? seg_states + (slab * n_seg + seg) * kSegFloats : nullptr;
-
-    // forward-direction output tiles of the segment's chunks, parked between the two sweeps
-    f32x4 parked[kSegChunks][4];
-    auto park = [&](int m, const f32x4 (&O)[4]) {
-#pragma unroll
-        for (int p = 0; p < kSegChunks; ++p)
-            if (p == m) {
-#pragma unroll
-                for (int jt = 0; jt < 4; ++jt) parked[p][jt] = O[jt];
-            }
-    };
-    auto unpark = [&](int m, f32x4 (&O)[4]) {
-#pragma unroll
-        for (int p = 0; p < kSegChunks; ++p)
-            if (p == m) {
-#pragma unroll
-                for (int jt = 0; jt < 4; ++jt) O[jt] = parked[p][jt];
-            }
-    };
-
-    f32x4 S[4];
+    const bool seg_in = st_in != nullptr && seg + 1 < n_seg;  // the last segment's entering backward state is zero
+    const int row = 16 * w + r;
 
     // rows of the next chunk are fetched while the current chunk is being processed
     struct ChunkRows {
-        Row16 q, k, g, v;
+        Row16 q, k, gf, gb, v, sb;
     };
-    auto fetch = [&](int m, const uint16_t *gate) {
-        const long tok = long(chunk0 + m) * kC + 16 * w + r;
+    auto fetch = [&](int m) {
+        const long tok = long(chunk0 + m) * kC + row;
         const bool valid = tok < L;
         ChunkRows c;
         c.q = load_row_operand(q, tok, valid, g);
         c.k = load_row_operand(k, tok, valid, g);
-        c.g = load_row_natural(gate, tok, valid, g);
+        c.gf = load_row_natural(g_fwd, tok, valid, g);
+        c.gb = load_row_natural(g_bwd, tok, valid, g);
         c.v = load_row_natural(v, tok, valid, g);
+        // this lane's 16 values of the chunk's stashed state (absent for the segment's last chunk)
+        if (m + 1 < nch) {
+            const uint4 *p = reinterpret_cast<const uint4 *>(stash + size_t(chunk0 + m) * kStashBytes) + 2 * tid;
+            c.sb.p[0] = p[0];
+            c.sb.p[1] = p[1];
+        } else {
+            c.sb.p[0] = make_uint4(0, 0, 0, 0);
+            c.sb.p[1] = make_uint4(0, 0, 0, 0);
+        }
         return c;
     };
-    bf16x8 tri[2];
+    ChunkRows next = fetch(0);
 
-    // ---------------- forward sweep: chunks ascending ----------------
-    ChunkRows next = fetch(0, g_fwd);
-    scan_triangle<0>(w, r, g, tri);
+    f32x4 S[4];
     load_state(st_in, st_in == nullptr, w, r, g, S);
-    publish_state(sm, w, r, g, S);  // made visible by the first barrier inside the step
+    publish_state(sm.st, w, r, g, S);  // made visible by the first barrier of the first step
+    if (seg_in) {
+        f32x4 Sb[4];
+        load_state(st_in + size_t(kD) * kD, false, w, r, g, Sb);
+        publish_state(sm.sseg, w, r, g, Sb);
+    }
+    bf16x8 tri_f[2], tri_b[2];
+    scan_triangle<0>(w, r, g, tri_f);
+    scan_triangle<1>(w, r, g, tri_b);
+
     for (int m = 0; m < nch; ++m) {
         const ChunkRows cur = next;
-        next = m + 1 < nch ? fetch(m + 1, g_fwd) : fetch(nch - 1, g_bwd);
-        f32x4 O[4];
-#pragma unroll
-        for (int jt = 0; jt < 4; ++jt) O[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        out_chunk_step<0>(sm, tri, w, r, g, cur.q, cur.k, cur.g, cur.v, O, S);
-        park(m, O);
-    }
+        ChunkFlags fl;
+        fl.stash = m + 1 < nch;
+        fl.seg = seg_in;
 
-    // ---------------- backward sweep: chunks descending ----------------
-    __syncthreads();  // the forward sweep's last state copy is no longer read
-    load_state(st_in ? st_in + size_t(kD) * kD : nullptr, st_in == nullptr, w, r, g, S);
-    publish_state(sm, w, r, g, S);
-    scan_triangle<1>(w, r, g, tri);
-    for (int m = nch - 1; m >= 0; --m) {
-        // the parked tile comes back before the next prefetch is issued: vector-memory results
-        // return in order, so a later wait for it must not sit behind the prefetch
-        f32x4 O[4];
-        unpark(m, O);
-        const ChunkRows cur = next;
-        if (m > 0) next = fetch(m - 1, g_bwd);
-        out_chunk_step<1>(sm, tri, w, r, g, cur.q, cur.k, cur.g, cur.v, O, S);
-        // o_t = (o_fwd_t + o_bwd_t) / 2 for token 16w + r, columns 16*jt + 4g .. +3
-        const long tok = long(chunk0 + m) * kC + 16 * w + r;
-        if (tok < L) {
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt) {
-                const f32x4 o = O[jt];
-                *reinterpret_cast<uint2 *>(out + tok * kD + 16 * jt + 4 * g) =
-                    make_uint2(pack2(0.5f * o[0], 0.5f * o[1]), pack2(0.5f * o[2], 0.5f * o[3]));
-            }
+        store_row16_raw(sm.gf, row, g, cur.gf);
+        store_row16_raw(sm.gb, row, g, cur.gb);
+        store_row16_raw(sm.v, row, g, cur.v);
+        if (fl.stash) {  // accumulator order -> [column][channel] tile
+            *reinterpret_cast<uint2 *>(&sm.sb[r][16 * w + 4 * g]) = make_uint2(cur.sb.p[0].x, cur.sb.p[0].y);
+            *reinterpret_cast<uint2 *>(&sm.sb[16 + r][16 * w + 4 * g]) = make_uint2(cur.sb.p[0].z, cur.sb.p[0].w);
+            *reinterpret_cast<uint2 *>(&sm.sb[32 + r][16 * w + 4 * g]) = make_uint2(cur.sb.p[1].x, cur.sb.p[1].y);
+            *reinterpret_cast<uint2 *>(&sm.sb[48 + r][16 * w + 4 * g]) = make_uint2(cur.sb.p[1].z, cur.sb.p[1].w);
         }
+        if (fl.seg && tid < kD / 4) {
+            const float *dr = reinterpret_cast<const float *>(stash + size_t(chunk0 + m) * kStashBytes +
+                                                              size_t(kD) * kD * sizeof(uint16_t));
+            reinterpret_cast<float4 *>(sm.dr)[tid] = reinterpret_cast<const float4 *>(dr)[tid];
+        }
+        __syncthreads();  // staged tiles visible
+
+        const long tok = long(chunk0 + m) * kC + row;
+        uint16_t *out_row = tok < L ? out + tok * kD : nullptr;
+        f32x4 Bf[4], Tf[4], Bb[4];
+        ChunkOperands op;
+        bool fast = true;
+        chunk_gate_scan(sm.gf, tri_f, r, g, Bf, Tf);
+        if (kFastOnly) {
+            chunk_gate_scan(sm.gb, tri_b, r, g, Bb);
+            out_chunk_fast(sm, w, r, g, Bf, Bb, Tf, cur.q, cur.k, fl, op);
+        } else {
+            f32x4 Tb[4];
+            chunk_gate_scan(sm.gb, tri_b, r, g, Bb, Tb);
+            // same totals in every wave: the choice is uniform over the workgroup
+            fast = fmaxf(chunk_decay_max(Tf), chunk_decay_max(Tb)) <= kFastRange;
+            if (fast)
+                out_chunk_fast(sm, w, r, g, Bf, Bb, Tf, cur.q, cur.k, fl, op);
+            else
+                out_chunk_safe(sm, w, r, g, cur.q, cur.k, fl, op);
+        }
+        // the next chunk's rows travel while the matrix cores finish this one: issued here, after
+        // the element-wise half, so that they do not occupy registers during it
+        if (m + 1 < nch) next = fetch(m + 1);
+        finish_chunk(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out_row, S);
     }
 }
 
-// ---- kernel 1: per-segment local end states, both directions in one pass ----------------------
+// ---- kernel 1: per-segment end states and per-chunk backward stash -----------------------------
 
 __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, const uint16_t *__restrict__ g_fwd,
-    const uint16_t *__restrict__ g_bwd, float *__restrict__ seg_states, int L, int n_seg)
+    const uint16_t *__restrict__ g_bwd, float *__restrict__ seg_states, int *__restrict__ seg_mild,
+    unsigned char *__restrict__ stash, int L, int n_chunks, int seg_chunks, int n_seg)
 {
     __shared__ StateLds sm;
     const int tid = threadIdx.x;
@@ -811,25 +928,26 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     const long base = slab * L * kD;
     k += base; v += base; g_fwd += base; g_bwd += base;
     float *dst = seg_states + (slab * n_seg + seg) * kSegFloats;
+    stash += size_t(slab) * n_chunks * kStashBytes;
 
-    const int chunk0 = seg * kSegChunks;
-    const int n_chunks_total = (L + kC - 1) / kC;
-    const int nch = min(kSegChunks, n_chunks_total - chunk0);
+    const int chunk0 = seg * seg_chunks;
+    const int nch = min(seg_chunks, n_chunks - chunk0);
     const int row = 16 * w + r;
 
+    // Sb: backward state, carried right to left (plain recurrence).  Sf: forward state at the
+    // segment's RIGHT edge = sum_n (decay of the chunks right of n) * (chunk n's state at its own
+    // right edge); walking right to left, chunk n's contribution is scaled once by the running
+    // product rf and nothing accumulated ever decays again.  rf / rb: decay of the chunks seen
+    // so far (rows at positions 16w + 4g + e).
     f32x4 Sf[4], Sb[4];
 #pragma unroll
     for (int jt = 0; jt < 4; ++jt) {
         Sf[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
         Sb[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    // Total decay of the chunks seen so far, rows 16w + 4g + e.  The backward state is walked left
-    // to right: the state at the segment's LEFT edge is sum_n (decay of the chunks left of n) *
-    // (chunk n's state at its own left edge), so chunk n's contribution is scaled by the running
-    // product once and nothing accumulated ever decays again.
-    float4 dtot_f = make_float4(1.f, 1.f, 1.f, 1.f), dtot_b = dtot_f;
+    float4 rf = make_float4(1.f, 1.f, 1.f, 1.f), rb = rf;
+    bool all_fast = true;  // every chunk of the segment within the fast form's range
 
-    // rows of the next chunk are fetched while the current chunk is being processed
     struct ChunkRows {
         Row16 k, v, gf, gb;
     };
@@ -843,14 +961,29 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         c.gb = load_row_natural(g_bwd, tok, valid, g);
         return c;
     };
-    ChunkRows next = fetch(0);
+    ChunkRows next = fetch(nch - 1);
     bf16x8 tri_f[2], tri_b[2];
     scan_triangle<0>(w, r, g, tri_f);
     scan_triangle<1>(w, r, g, tri_b);
 
-    for (int m = 0; m < nch; ++m) {
+    for (int m = nch - 1; m >= 0; --m) {
         const ChunkRows cur = next;
-        if (m + 1 < nch) next = fetch(m + 1);
+        if (m > 0) next = fetch(m - 1);
+
+        // stash for chunk m: the backward state entering it from the right (zero, and not
+        // stored, for the segment's last chunk) and the decay from its right edge to the
+        // segment's right edge
+        {
+            unsigned char *dstm = stash + size_t(chunk0 + m) * kStashBytes;
+            if (m + 1 < nch) {  // accumulator order: 32 contiguous bytes per lane, 2 KB per wave
+                uint4 *sdst = reinterpret_cast<uint4 *>(dstm) + 2 * tid;
+                const uint2 a = pack4(Sb[0]), b = pack4(Sb[1]), c = pack4(Sb[2]), d = pack4(Sb[3]);
+                sdst[0] = make_uint4(a.x, a.y, b.x, b.y);
+                sdst[1] = make_uint4(c.x, c.y, d.x, d.y);
+            }
+            if (r == 0)
+                *reinterpret_cast<float4 *>(dstm + size_t(kD) * kD * sizeof(uint16_t) + (16 * w + 4 * g) * sizeof(float)) = rb;
+        }
 
         store_row16_raw(sm.g[0], row, g, cur.gf);
         store_row16_raw(sm.g[1], row, g, cur.gb);
@@ -876,6 +1009,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
             if (r == 0) store_chan16(sm.tot[1], g, t);
         }
         const bool fast = fmaxf(max_f, max_b) <= kFastRange;  // uniform over the workgroup
+        all_fast = all_fast && fast;
         float4 df, db;  // this chunk's decay, rows at LDS positions 16w + 4g + e
         float tmp[16];
         if (fast) {
@@ -935,13 +1069,13 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
             __syncthreads();  // ks visible
         }
 
-        // chunk contributions K^T V of both directions, rows c = 16w + 4g + e
+        // chunk contributions K^T V of both directions, rows at positions 16w + 4g + e
         f32x4 Cf[4], Cb[4];
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) {
-            // fast: S_f = df * (S_f + Kf^T V) accumulates onto the state; safe: S_f = df * S_f + Kf^T V
-            Cf[jt] = fast ? Sf[jt] : f32x4{0.f, 0.f, 0.f, 0.f};
-            Cb[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            Cf[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            // fast: S_b = db * (S_b + Kb^T V) accumulates onto the state; safe: S_b = db * S_b + Kb^T V
+            Cb[jt] = fast ? Sb[jt] : f32x4{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
@@ -954,23 +1088,23 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
                 Cb[jt] = mfma(ab, vb, Cb[jt]);
             }
         }
-        // backward: chunk state at its own left edge is db * Cb (fast) or Cb (safe); scale by the
-        // decay of the chunks to its left
-        const float4 sb4 = fast ? make_float4(dtot_b.x * db.x, dtot_b.y * db.y, dtot_b.z * db.z, dtot_b.w * db.w) : dtot_b;
+        // forward: chunk state at its own right edge is df * Cf (fast) or Cf (safe); scale by the
+        // decay of the chunks to its right
+        const float4 sf4 = fast ? make_float4(rf.x * df.x, rf.y * df.y, rf.z * df.z, rf.w * df.w) : rf;
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) {
             if (fast) {
-                Sf[jt][0] = Cf[jt][0] * df.x; Sf[jt][1] = Cf[jt][1] * df.y;
-                Sf[jt][2] = Cf[jt][2] * df.z; Sf[jt][3] = Cf[jt][3] * df.w;
+                Sb[jt][0] = Cb[jt][0] * db.x; Sb[jt][1] = Cb[jt][1] * db.y;
+                Sb[jt][2] = Cb[jt][2] * db.z; Sb[jt][3] = Cb[jt][3] * db.w;
             } else {
-                Sf[jt][0] = fmaf(Sf[jt][0], df.x, Cf[jt][0]); Sf[jt][1] = fmaf(Sf[jt][1], df.y, Cf[jt][1]);
-                Sf[jt][2] = fmaf(Sf[jt][2], df.z, Cf[jt][2]); Sf[jt][3] = fmaf(Sf[jt][3], df.w, Cf[jt][3]);
+                Sb[jt][0] = fmaf(Sb[jt][0], db.x, Cb[jt][0]); Sb[jt][1] = fmaf(Sb[jt][1], db.y, Cb[jt][1]);
+                Sb[jt][2] = fmaf(Sb[jt][2], db.z, Cb[jt][2]); Sb[jt][3] = fmaf(Sb[jt][3], db.w, Cb[jt][3]);
             }
-            Sb[jt][0] = fmaf(Cb[jt][0], sb4.x, Sb[jt][0]); Sb[jt][1] = fmaf(Cb[jt][1], sb4.y, Sb[jt][1]);
-            Sb[jt][2] = fmaf(Cb[jt][2], sb4.z, Sb[jt][2]); Sb[jt][3] = fmaf(Cb[jt][3], sb4.w, Sb[jt][3]);
+            Sf[jt][0] = fmaf(Cf[jt][0], sf4.x, Sf[jt][0]); Sf[jt][1] = fmaf(Cf[jt][1], sf4.y, Sf[jt][1]);
+            Sf[jt][2] = fmaf(Cf[jt][2], sf4.z, Sf[jt][2]); Sf[jt][3] = fmaf(Cf[jt][3], sf4.w, Sf[jt][3]);
         }
-        dtot_f.x *= df.x; dtot_f.y *= df.y; dtot_f.z *= df.z; dtot_f.w *= df.w;
-        dtot_b.x *= db.x; dtot_b.y *= db.y; dtot_b.z *= db.z; dtot_b.w *= db.w;
+        rf.x *= df.x; rf.y *= df.y; rf.z *= df.z; rf.w *= df.w;
+        rb.x *= db.x; rb.y *= db.y; rb.z *= db.z; rb.w *= db.w;
         __syncthreads();  // every read of this chunk's LDS tiles is done
     }
 
@@ -983,9 +1117,10 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
             dst[size_t(kD) * kD + idx] = Sb[jt][e];
         }
     if (r == 0) {
-        *reinterpret_cast<float4 *>(dst + kSegStateFloats + 16 * w + 4 * g) = dtot_f;
-        *reinterpret_cast<float4 *>(dst + kSegStateFloats + kD + 16 * w + 4 * g) = dtot_b;
+        *reinterpret_cast<float4 *>(dst + kSegStateFloats + 16 * w + 4 * g) = rf;
+        *reinterpret_cast<float4 *>(dst + kSegStateFloats + kD + 16 * w + 4 * g) = rb;
     }
+    if (tid == 0) seg_mild[slab * n_seg + seg] = all_fast ? 1 : 0;
 }
 
 // ---- kernel 2: scan of segment states, in place ------------------------------------------------
@@ -1015,45 +1150,62 @@ __global__ __launch_bounds__(kThreads) void bigla_state_scan_kernel(float *__res
 
 bool bigla_chunk_supported(int dk, int dv, bool is_bf16) { return is_bf16 && dk == kD && dv == kD; }
 
+namespace {
+size_t seg_region_bytes(long BH, const Plan &p) { return size_t(BH) * p.n_seg * kSegFloats * sizeof(float); }
+size_t flag_region_bytes(long BH, const Plan &p) { return (size_t(BH) * p.n_seg * sizeof(int) + 15) / 16 * 16; }
+}  // namespace
+
 size_t bigla_chunk_workspace_bytes(long BH, int L)
 {
-    const long n_chunks = (L + kC - 1) / kC;
-    const long n_seg = (n_chunks + kSegChunks - 1) / kSegChunks;
-    // always non-zero so that callers can size one buffer per problem; unused when n_seg == 1
-    return size_t(BH) * n_seg * kSegFloats * sizeof(float);
+    const Plan p = make_plan(BH, L);
+    return seg_region_bytes(BH, p) + flag_region_bytes(BH, p) + size_t(BH) * p.n_chunks * kStashBytes;
 }
 
 hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
                               void *out, long BH, int L, void *workspace, hipStream_t stream)
 {
-    const long n_chunks = (L + kC - 1) / kC;
-    const int n_seg = int((n_chunks + kSegChunks - 1) / kSegChunks);
-    const long blocks = BH * n_seg;
+    const Plan p = make_plan(BH, L);
+    const long blocks = BH * p.n_seg;
     if (blocks > 0x7fffffffL || BH * 2 * (kD * kD / kThreads) > 0x7fffffffL) return hipErrorInvalidValue;
     const uint16_t *qq = static_cast<const uint16_t *>(q), *kk = static_cast<const uint16_t *>(k);
     const uint16_t *vv = static_cast<const uint16_t *>(v);
     const uint16_t *gf = static_cast<const uint16_t *>(g_fwd), *gb = static_cast<const uint16_t *>(g_bwd);
-    float *ws = static_cast<float *>(workspace);
-    if (n_seg > 1) {
+    float *seg_states = static_cast<float *>(workspace);
+    int *seg_mild = reinterpret_cast<int *>(static_cast<unsigned char *>(workspace) + seg_region_bytes(BH, p));
+    unsigned char *stash = reinterpret_cast<unsigned char *>(seg_mild) + flag_region_bytes(BH, p);
+    hipError_t e = hipSuccess;
+    if (p.n_chunks > 1) {  // a single chunk has neither a stash nor entering states
         {
             LaunchTimer timer(kKernelSegmentState, stream);
             hipLaunchKernelGGL(bigla_segment_state_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, kk, vv,
-                               gf, gb, ws, L, n_seg);
-        }
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        {
-            LaunchTimer timer(kKernelStateScan, stream);
-            hipLaunchKernelGGL(bigla_state_scan_kernel, dim3((unsigned)(BH * 2 * (kD * kD / kThreads))),
-                               dim3(kThreads), 0, stream, ws, n_seg);
+                               gf, gb, seg_states, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg);
         }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    {
+    if (p.n_seg > 1) {
+        {
+            LaunchTimer timer(kKernelStateScan, stream);
+            hipLaunchKernelGGL(bigla_state_scan_kernel, dim3((unsigned)(BH * 2 * (kD * kD / kThreads))),
+                               dim3(kThreads), 0, stream, seg_states, p.n_seg);
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const float *seg_in = p.n_seg > 1 ? seg_states : nullptr;
+    const int *flags = p.n_chunks > 1 ? seg_mild : nullptr;
+    uint16_t *oo = static_cast<uint16_t *>(out);
+    if (flags) {  // segments the state kernel flagged as entirely within the fast form's range
         LaunchTimer timer(kKernelSegmentOut, stream);
-        hipLaunchKernelGGL(bigla_segment_out_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk, vv, gf,
-                           gb, static_cast<uint16_t *>(out), n_seg > 1 ? ws : nullptr, L, n_seg);
+        hipLaunchKernelGGL(bigla_segment_out_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk, vv,
+                           gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks, p.n_seg);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    {  // every other segment; its workgroups leave at once where the launch above did the work
+        LaunchTimer timer(kKernelSegmentOutGeneral, stream);
+        hipLaunchKernelGGL(bigla_segment_out_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk,
+                           vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks, p.n_seg);
     }
     return hipGetLastError();
 }

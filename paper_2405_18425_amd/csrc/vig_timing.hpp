@@ -12,7 +12,8 @@ enum KernelId {
     kKernelSegmentOut = 2,
     kKernelRecurrent = 3,
     kKernelLocalityGate = 4,
-    kKernelCount = 5
+    kKernelSegmentOutGeneral = 5,
+    kKernelCount = 6
 };
 
 // Brackets one launch when timing is enabled on the calling thread.
