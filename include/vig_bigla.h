@@ -38,9 +38,10 @@ typedef enum { VIG_F32 = 0, VIG_BF16 = 1 } vig_dtype;
 
 /*
  * Bytes of device scratch that bigla_fwd needs for this problem (0 if none).  The scratch
- * holds the per-segment boundary states of the chunkwise evaluation; its contents before
- * the call are ignored and after the call are unspecified.  Returns 0 for invalid sizes
- * (bigla_fwd reports those).
+ * holds the boundary states of the chunkwise evaluation (per segment and per chunk), or the
+ * forward partial outputs of the fp32-arithmetic recurrence on bf16 storage; its contents
+ * before the call are ignored and after the call are unspecified.  Returns 0 for invalid
+ * sizes (bigla_fwd reports those).
  */
 size_t bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype);
 
@@ -63,10 +64,11 @@ size_t bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype);
  *   workspace / workspace_bytes: device scratch of at least bigla_workspace_bytes(...);
  *   may be NULL/0 when that function returns 0.
  *
- * Numerics: VIG_BF16 with dk = dv = 64 runs the chunkwise MFMA path; per-step log gates
- * below -8 are treated as -8 there (alpha < 3.4e-4 acts as a hard reset either way; the
- * difference is far below the bf16 tolerance).  Every other case runs the exact fp32
- * recurrence.
+ * Numerics: VIG_BF16 with dk = dv = 64 runs the chunkwise MFMA path (bf16 operands, fp32
+ * accumulation, fp32 carried state).  A 64-token chunk in which some channel decays by more
+ * than 60 nats is evaluated in a range-safe form that treats per-step log gates below -8 as
+ * -8 (alpha < 3.4e-4 acts as a hard reset either way; the difference is far below the bf16
+ * tolerance).  Every other case runs the exact recurrence in fp32 arithmetic.
  */
 int bigla_fwd(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
               void *out, int B, int H, int L, int dk, int dv, int dtype, void *workspace,
