@@ -802,24 +802,33 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
 //                     chunk choosing its form.
 template <bool kFastOnly>
 __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
-    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
-    const uint16_t *__restrict__ g_fwd, const uint16_t *__restrict__ g_bwd, uint16_t *__restrict__ out,
+    const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
+    const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
     const float *__restrict__ seg_states /* states entering each segment, nullptr when one segment */,
     const int *__restrict__ seg_mild /* per (slab, segment): every chunk admits the fast form; may be nullptr */,
-    const unsigned char *__restrict__ stash, int L, int n_chunks, int seg_chunks, int n_seg)
+    const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg, long total_units,
+    int units_per_block)
 {
     __shared__ OutLds sm;
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
-    const long slab = blockIdx.x / n_seg;
-    const int seg = blockIdx.x % n_seg;
+    // A workgroup walks `units_per_block` consecutive (slab, segment) units and skips those of the
+    // other kernel.  The fast kernel takes one unit per workgroup; the general kernel, whose
+    // units are normally all skipped, takes several so that an idle launch drains quickly.
+    for (long unit = long(blockIdx.x) * units_per_block;
+         unit < min(long(blockIdx.x + 1) * units_per_block, total_units); ++unit) {
+    const long slab = unit / n_seg;
+    const int seg = int(unit % n_seg);
     {
-        const bool mild = seg_mild != nullptr && seg_mild[slab * n_seg + seg] != 0;  // uniform over the workgroup
-        if (mild != kFastOnly) return;
+        const bool mild = seg_mild != nullptr && seg_mild[unit] != 0;  // uniform over the workgroup
+        if (mild != kFastOnly) continue;
     }
+    __syncthreads();  // LDS of a previous unit is no longer read
     const long base = slab * L * kD;
-    q += base; k += base; v += base; g_fwd += base; g_bwd += base; out += base;
-    stash += size_t(slab) * n_chunks * kStashBytes;
+    const uint16_t *q = q_all + base, *k = k_all + base, *v = v_all + base;
+    const uint16_t *g_fwd = gf_all + base, *g_bwd = gb_all + base;
+    uint16_t *out = out_all + base;
+    const unsigned char *stash = stash_all + size_t(slab) * n_chunks * kStashBytes;
 
     const int chunk0 = seg * seg_chunks;
     const int nch = min(seg_chunks, n_chunks - chunk0);
@@ -911,6 +920,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
         if (m + 1 < nch) next = fetch(m + 1);
         finish_chunk(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out_row, S);
     }
+    }  // units
 }
 
 // ---- kernel 1: per-segment end states and per-chunk backward stash -----------------------------
@@ -1198,14 +1208,16 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
     if (flags) {  // segments the state kernel flagged as entirely within the fast form's range
         LaunchTimer timer(kKernelSegmentOut, stream);
         hipLaunchKernelGGL(bigla_segment_out_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk, vv,
-                           gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks, p.n_seg);
+                           gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, blocks, 1);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     {  // every other segment; its workgroups leave at once where the launch above did the work
         LaunchTimer timer(kKernelSegmentOutGeneral, stream);
-        hipLaunchKernelGGL(bigla_segment_out_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk,
-                           vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks, p.n_seg);
+        const int per_block = flags ? 8 : 1;
+        hipLaunchKernelGGL(bigla_segment_out_kernel<false>, dim3((unsigned)((blocks + per_block - 1) / per_block)),
+                           dim3(kThreads), 0, stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks,
+                           p.seg_chunks, p.n_seg, blocks, per_block);
     }
     return hipGetLastError();
 }

@@ -85,6 +85,22 @@ def test_bigla_adversarial_gates(dtype, gate):
     assert_close(run_bigla_gpu(s, dtype), run_bigla_oracle(s, dtype), TOL[dtype], gate)
 
 
+@pytest.mark.parametrize("B,H,L", [(2, 3, 1000), (24, 4, 1500), (3, 2, 4096)])
+def test_bigla_mixed_forms_in_one_call(B, H, L):
+    """Only a few stretches of the sequence decay too fast for the fast form: fast-form and
+    range-safe segments (and chunks) meet in one call, for several segment lengths."""
+    w = wl.Workload("mixed", B=B, H=H, Hg=1, Wg=L, dk=64, dv=64, dtype="bf16", gate_mu=-1.0)
+    _say(f"bigla mixed forms B{B} H{H} L{L}")
+    s = wl.generate(w, seed=17, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+    gf = wl.widen(s["g_fwd"], "bf16")
+    gb = wl.widen(s["g_bwd"], "bf16")
+    gf[:, :, L // 2:L // 2 + 40, ::3] = -3.0      # one stretch, a third of the channels, forward only
+    gb[0, :, 70:75, :] = -20.0                     # a hard reset in one batch element, backward only
+    gf[-1, -1, L - 30:, 5] = -2.5                  # the ragged tail of the last slab
+    s["g_fwd"], s["g_bwd"] = wl.store(gf, "bf16"), wl.store(gb, "bf16")
+    assert_close(run_bigla_gpu(s, "bf16"), run_bigla_oracle(s, "bf16"), TOL["bf16"], "mixed forms")
+
+
 @pytest.mark.parametrize("dtype", ("bf16", "f32"))
 def test_bigla_deterministic_and_stream(dtype):
     import torch
