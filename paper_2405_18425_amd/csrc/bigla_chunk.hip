@@ -184,34 +184,36 @@ struct Row16 {
     uint4 p[2];
 };
 
-// Natural order: two 16-byte pieces at channel offsets 8g and 32+8g (tiles that are only staged)
-__device__ __forceinline__ Row16 load_row_natural(const uint16_t *slab_base, long token, bool valid, int g)
+// Global row loads are branch-free: an out-of-range token reads the (valid) row `token_clamped`
+// and is zeroed afterwards.  With no control flow around the loads the compiler can count the
+// outstanding ones exactly, so waiting for one chunk's rows does not also wait for the prefetch
+// issued after them.
+__device__ __forceinline__ void zero_unless(Row16 &r, bool valid)
 {
-    Row16 r;
-    if (valid) {
-        const uint4 *p = reinterpret_cast<const uint4 *>(slab_base + token * kD + 8 * g);
-        r.p[0] = p[0];
-        r.p[1] = p[4];  // +32 elements
-    } else {
+    if (!valid) {  // selects, not a branch around memory operations
         r.p[0] = make_uint4(0, 0, 0, 0);
         r.p[1] = make_uint4(0, 0, 0, 0);
     }
+}
+
+// Natural order: two 16-byte pieces at channel offsets 8g and 32+8g (tiles that are only staged)
+__device__ __forceinline__ Row16 load_row_natural(const uint16_t *slab_base, long token_clamped, int g)
+{
+    Row16 r;
+    const uint4 *p = reinterpret_cast<const uint4 *>(slab_base + token_clamped * kD + 8 * g);
+    r.p[0] = p[0];
+    r.p[1] = p[4];  // +32 elements
     return r;
 }
 
 // Operand order: slot n = 4*ct + e holds channel 16*ct + 4g + e (four 8-byte pieces)
-__device__ __forceinline__ Row16 load_row_operand(const uint16_t *slab_base, long token, bool valid, int g)
+__device__ __forceinline__ Row16 load_row_operand(const uint16_t *slab_base, long token_clamped, int g)
 {
     Row16 r;
-    if (valid) {
-        const uint2 *p = reinterpret_cast<const uint2 *>(slab_base + token * kD + 4 * g);
-        const uint2 a = p[0], b = p[4], c = p[8], d = p[12];  // +16 elements each
-        r.p[0] = make_uint4(a.x, a.y, b.x, b.y);
-        r.p[1] = make_uint4(c.x, c.y, d.x, d.y);
-    } else {
-        r.p[0] = make_uint4(0, 0, 0, 0);
-        r.p[1] = make_uint4(0, 0, 0, 0);
-    }
+    const uint2 *p = reinterpret_cast<const uint2 *>(slab_base + token_clamped * kD + 4 * g);
+    const uint2 a = p[0], b = p[4], c = p[8], d = p[12];  // +16 elements each
+    r.p[0] = make_uint4(a.x, a.y, b.x, b.y);
+    r.p[1] = make_uint4(c.x, c.y, d.x, d.y);
     return r;
 }
 
@@ -840,24 +842,27 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
     struct ChunkRows {
         Row16 q, k, gf, gb, v, sb;
     };
-    auto fetch = [&](int m) {
-        const long tok = long(chunk0 + m) * kC + row;
+    auto fetch = [&](int m) {  // m may run one past the segment: clamped, the rows are then unused
+        const int mc = min(m, nch - 1);
+        const long tok = long(chunk0 + mc) * kC + row;
         const bool valid = tok < L;
+        const long tc = min(tok, long(L) - 1);
         ChunkRows c;
-        c.q = load_row_operand(q, tok, valid, g);
-        c.k = load_row_operand(k, tok, valid, g);
-        c.gf = load_row_natural(g_fwd, tok, valid, g);
-        c.gb = load_row_natural(g_bwd, tok, valid, g);
-        c.v = load_row_natural(v, tok, valid, g);
-        // this lane's 16 values of the chunk's stashed state (absent for the segment's last chunk)
-        if (m + 1 < nch) {
-            const uint4 *p = reinterpret_cast<const uint4 *>(stash + size_t(chunk0 + m) * kStashBytes) + 2 * tid;
-            c.sb.p[0] = p[0];
-            c.sb.p[1] = p[1];
-        } else {
-            c.sb.p[0] = make_uint4(0, 0, 0, 0);
-            c.sb.p[1] = make_uint4(0, 0, 0, 0);
-        }
+        c.q = load_row_operand(q, tc, g);
+        c.k = load_row_operand(k, tc, g);
+        c.gf = load_row_natural(g_fwd, tc, g);
+        c.gb = load_row_natural(g_bwd, tc, g);
+        c.v = load_row_natural(v, tc, g);
+        // this lane's 16 values of the chunk's stashed state (unwritten, and unused, for the
+        // segment's last chunk)
+        const uint4 *p = reinterpret_cast<const uint4 *>(stash + size_t(chunk0 + mc) * kStashBytes) + 2 * tid;
+        c.sb.p[0] = p[0];
+        c.sb.p[1] = p[1];
+        zero_unless(c.q, valid);
+        zero_unless(c.k, valid);
+        zero_unless(c.gf, valid);
+        zero_unless(c.gb, valid);
+        zero_unless(c.v, valid);
         return c;
     };
     ChunkRows next = fetch(0);
@@ -917,7 +922,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
         }
         // the next chunk's rows travel while the matrix cores finish this one: issued here, after
         // the element-wise half, so that they do not occupy registers during it
-        if (m + 1 < nch) next = fetch(m + 1);
+        next = fetch(m + 1);
         finish_chunk(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out_row, S);
     }
     }  // units
@@ -961,14 +966,19 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     struct ChunkRows {
         Row16 k, v, gf, gb;
     };
-    auto fetch = [&](int m) {
-        const long tok = long(chunk0 + m) * kC + row;
+    auto fetch = [&](int m) {  // m may run one before the segment: clamped, the rows are then unused
+        const long tok = long(chunk0 + max(m, 0)) * kC + row;
         const bool valid = tok < L;
+        const long tc = min(tok, long(L) - 1);
         ChunkRows c;
-        c.k = load_row_operand(k, tok, valid, g);
-        c.v = load_row_natural(v, tok, valid, g);
-        c.gf = load_row_natural(g_fwd, tok, valid, g);
-        c.gb = load_row_natural(g_bwd, tok, valid, g);
+        c.k = load_row_operand(k, tc, g);
+        c.v = load_row_natural(v, tc, g);
+        c.gf = load_row_natural(g_fwd, tc, g);
+        c.gb = load_row_natural(g_bwd, tc, g);
+        zero_unless(c.k, valid);
+        zero_unless(c.v, valid);
+        zero_unless(c.gf, valid);
+        zero_unless(c.gb, valid);
         return c;
     };
     ChunkRows next = fetch(nch - 1);
@@ -978,7 +988,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
 
     for (int m = nch - 1; m >= 0; --m) {
         const ChunkRows cur = next;
-        if (m > 0) next = fetch(m - 1);
+        next = fetch(m - 1);
 
         // stash for chunk m: the backward state entering it from the right (zero, and not
         // stored, for the segment's last chunk) and the decay from its right edge to the
@@ -1146,13 +1156,28 @@ __global__ __launch_bounds__(kThreads) void bigla_state_scan_kernel(float *__res
     float *base = seg_states + slab * n_seg * kSegFloats;
     const int c = elem / kD;
     float run = 0.f;
-    for (int i = 0; i < n_seg; ++i) {
-        const int n = dir == 0 ? i : n_seg - 1 - i;
-        float *s = base + n * kSegFloats;
-        const float local = s[dir * kD * kD + elem];
-        const float decay = s[kSegStateFloats + dir * kD + c];
-        s[dir * kD * kD + elem] = run;
-        run = fmaf(run, decay, local);
+    // batches of 8 segments: all loads of a batch are issued before its first store, so that the
+    // in-place update does not serialise one memory round trip per segment
+    constexpr int kBatch = 8;
+    for (int i0 = 0; i0 < n_seg; i0 += kBatch) {
+        float local[kBatch], decay[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int i = min(i0 + u, n_seg - 1);
+            const int n = dir == 0 ? i : n_seg - 1 - i;
+            const float *s = base + n * kSegFloats;
+            local[u] = s[dir * kD * kD + elem];
+            decay[u] = s[kSegStateFloats + dir * kD + c];
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            if (i0 + u < n_seg) {
+                const int i = i0 + u;
+                const int n = dir == 0 ? i : n_seg - 1 - i;
+                base[n * kSegFloats + dir * kD * kD + elem] = run;
+                run = fmaf(run, decay[u], local[u]);
+            }
+        }
     }
 }
 
