@@ -31,9 +31,15 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA peak
 CACHE_BYTES = 256 << 20        # Infinity Cache; buffer sets rotate over more than this
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/), keyed by (kernel, workload); None until measured for that pair.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/bigla_path_vig_s_1024.md (read + written, calibrated with a plain copy), keyed by
+# (kernel, workload); None for pairs that were not profiled.
+MEASURED_TRAFFIC_BYTES = {
+    ("segment_out", "vig_s_1024"): 194.0e6,
+    ("segment_state", "vig_s_1024"): 138.9e6,
+    ("state_scan", "vig_s_1024"): 33.5e6,
+    ("locality_gate", "vig_s_1024"): 116.1e6,
+}
 
 
 def parse_args():
