@@ -49,13 +49,14 @@
 // Nothing is reversed or copied in HBM; both directions read the same q, k, v.
 //
 // Wavefront mapping (256 threads = 4 waves).  Wave w owns tokens [16w, 16w+16) of the chunk;
-// lane (r = lane%16, g = lane/16) holds 16 channels of token 16w + r.  Slot n = 4*ct + e of the
-// lane is channel 16*ct + 4g + e: that is the accumulator layout in which the cumulative gates
-// leave the matrix cores (below), and slots 8kk..8kk+7 are the lane's k-slots of K-step kk of
-// every contraction over channels (A and B operands of the 16x16x32 MFMA only have to agree on
-// the channel of each k-slot).  LDS tiles of scaled keys and states keep channels in that
-// operand order (position 32kk + 8g + slot%8), as does the segment-state workspace; only the
-// global loads of q and k see the permutation.  Contractions over tokens (P.V, the state
+// lane (r = lane%16, g = lane/16) holds 16 channels of token 16w + r: slot n of the lane is
+// channel 32*(n/8) + 8g + n%8, i.e. two 16-byte pieces of the token row, and slots 8kk..8kk+7
+// are the lane's k-slots of K-step kk of every contraction over channels.  The cumulative
+// gates leave the matrix cores (below) in accumulator layout, lane (r, g) holding rows
+// 4g..4g+3 of each 16-row tile; the staged gate tiles therefore keep their columns permuted
+// (channel 32kk + 8g + 4h + e at column 16(2kk+h) + 4g + e) so that tile ct, row 4g+e is the
+// lane's slot 4ct + e.  Rows that are only staged (v, both gates) are fetched with fully
+// contiguous wave loads, 8 whole 128-byte rows per instruction.  Contractions over tokens (P.V, the state
 // update, the gate scan) take their token-major operands from row-major LDS tiles through
 // ds_read_b64_tr_b16.
 //
@@ -196,8 +197,9 @@ __device__ __forceinline__ void zero_unless(Row16 &r, bool valid)
     }
 }
 
-// Natural order: two 16-byte pieces at channel offsets 8g and 32+8g (tiles that are only staged)
-__device__ __forceinline__ Row16 load_row_natural(const uint16_t *slab_base, long token_clamped, int g)
+// Operand rows (q, k): lane (r, g) takes the two 16-byte pieces of its token at channel offsets
+// 8g and 32+8g; slot n of the lane is channel 32*(n/8) + 8g + n%8.
+__device__ __forceinline__ Row16 load_row_operand(const uint16_t *slab_base, long token_clamped, int g)
 {
     Row16 r;
     const uint4 *p = reinterpret_cast<const uint4 *>(slab_base + token_clamped * kD + 8 * g);
@@ -206,18 +208,50 @@ __device__ __forceinline__ Row16 load_row_natural(const uint16_t *slab_base, lon
     return r;
 }
 
-// Operand order: slot n = 4*ct + e holds channel 16*ct + 4g + e (four 8-byte pieces)
-__device__ __forceinline__ Row16 load_row_operand(const uint16_t *slab_base, long token_clamped, int g)
+// Rows that are only staged into LDS (v, g_fwd, g_bwd): fully contiguous wave loads, 8 whole
+// 128-byte rows per instruction.  Lane i of wave w takes 16-byte piece i%8 of rows
+// 16w + i/8 and 16w + 8 + i/8 of the chunk.
+struct StagedRows {
+    uint4 p[2];
+};
+
+__device__ __forceinline__ StagedRows load_rows_staged(const uint16_t *slab_base, long chunk_token0, int w, int lane,
+                                                       int L)
 {
-    Row16 r;
-    const uint2 *p = reinterpret_cast<const uint2 *>(slab_base + token_clamped * kD + 4 * g);
-    const uint2 a = p[0], b = p[4], c = p[8], d = p[12];  // +16 elements each
-    r.p[0] = make_uint4(a.x, a.y, b.x, b.y);
-    r.p[1] = make_uint4(c.x, c.y, d.x, d.y);
-    return r;
+    StagedRows s;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const long tok = chunk_token0 + 16 * w + 8 * t + (lane >> 3);
+        const long tc = tok < L ? tok : long(L) - 1;
+        s.p[t] = *reinterpret_cast<const uint4 *>(slab_base + tc * kD + 8 * (lane & 7));
+        if (tok >= L) s.p[t] = make_uint4(0, 0, 0, 0);  // a select, not a branch around the load
+    }
+    return s;
 }
 
-// The same 16 slots of one token out of a natural-order LDS tile
+// values: natural column order
+__device__ __forceinline__ void stage_values(uint16_t (*tile)[kPitch], int w, int lane, const StagedRows &s)
+{
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+        *reinterpret_cast<uint4 *>(&tile[16 * w + 8 * t + (lane >> 3)][8 * (lane & 7)]) = s.p[t];
+}
+
+// log-gates: columns permuted so that the gate scan's 16-channel tiles come out in operand
+// order.  Channel 32kk + 8g + 4h + e is stored at column 16*(2kk + h) + 4g + e: the piece with
+// channels 8p..8p+7 (p = 4kk + g) is split into its two 8-byte halves.
+__device__ __forceinline__ void stage_gates(uint16_t (*tile)[kPitch], int w, int lane, const StagedRows &s)
+{
+    const int piece = lane & 7, kk = piece >> 2, gg = piece & 3;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int row = 16 * w + 8 * t + (lane >> 3);
+        *reinterpret_cast<uint2 *>(&tile[row][32 * kk + 4 * gg]) = make_uint2(s.p[t].x, s.p[t].y);
+        *reinterpret_cast<uint2 *>(&tile[row][32 * kk + 16 + 4 * gg]) = make_uint2(s.p[t].z, s.p[t].w);
+    }
+}
+
+// The lane's 16 slots of one token out of a staged gate tile (column order of stage_gates)
 __device__ __forceinline__ Row16 lds_row_operand(const uint16_t (*tile)[kPitch], int row, int g)
 {
     const uint2 a = *reinterpret_cast<const uint2 *>(&tile[row][4 * g]);
@@ -840,7 +874,8 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
 
     // rows of the next chunk are fetched while the current chunk is being processed
     struct ChunkRows {
-        Row16 q, k, gf, gb, v, sb;
+        Row16 q, k, sb;
+        StagedRows gf, gb, v;
     };
     auto fetch = [&](int m) {  // m may run one past the segment: clamped, the rows are then unused
         const int mc = min(m, nch - 1);
@@ -850,9 +885,9 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
         ChunkRows c;
         c.q = load_row_operand(q, tc, g);
         c.k = load_row_operand(k, tc, g);
-        c.gf = load_row_natural(g_fwd, tc, g);
-        c.gb = load_row_natural(g_bwd, tc, g);
-        c.v = load_row_natural(v, tc, g);
+        c.gf = load_rows_staged(g_fwd, long(chunk0 + mc) * kC, w, lane, L);
+        c.gb = load_rows_staged(g_bwd, long(chunk0 + mc) * kC, w, lane, L);
+        c.v = load_rows_staged(v, long(chunk0 + mc) * kC, w, lane, L);
         // this lane's 16 values of the chunk's stashed state (unwritten, and unused, for the
         // segment's last chunk)
         const uint4 *p = reinterpret_cast<const uint4 *>(stash + size_t(chunk0 + mc) * kStashBytes) + 2 * tid;
@@ -860,9 +895,6 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
         c.sb.p[1] = p[1];
         zero_unless(c.q, valid);
         zero_unless(c.k, valid);
-        zero_unless(c.gf, valid);
-        zero_unless(c.gb, valid);
-        zero_unless(c.v, valid);
         return c;
     };
     ChunkRows next = fetch(0);
@@ -885,9 +917,9 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
         fl.stash = m + 1 < nch;
         fl.seg = seg_in;
 
-        store_row16_raw(sm.gf, row, g, cur.gf);
-        store_row16_raw(sm.gb, row, g, cur.gb);
-        store_row16_raw(sm.v, row, g, cur.v);
+        stage_gates(sm.gf, w, lane, cur.gf);
+        stage_gates(sm.gb, w, lane, cur.gb);
+        stage_values(sm.v, w, lane, cur.v);
         if (fl.stash) {  // accumulator order -> [column][channel] tile
             *reinterpret_cast<uint2 *>(&sm.sb[r][16 * w + 4 * g]) = make_uint2(cur.sb.p[0].x, cur.sb.p[0].y);
             *reinterpret_cast<uint2 *>(&sm.sb[16 + r][16 * w + 4 * g]) = make_uint2(cur.sb.p[0].z, cur.sb.p[0].w);
@@ -964,7 +996,8 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     bool all_fast = true;  // every chunk of the segment within the fast form's range
 
     struct ChunkRows {
-        Row16 k, v, gf, gb;
+        Row16 k;
+        StagedRows v, gf, gb;
     };
     auto fetch = [&](int m) {  // m may run one before the segment: clamped, the rows are then unused
         const long tok = long(chunk0 + max(m, 0)) * kC + row;
@@ -972,23 +1005,29 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         const long tc = min(tok, long(L) - 1);
         ChunkRows c;
         c.k = load_row_operand(k, tc, g);
-        c.v = load_row_natural(v, tc, g);
-        c.gf = load_row_natural(g_fwd, tc, g);
-        c.gb = load_row_natural(g_bwd, tc, g);
+        c.v = load_rows_staged(v, long(chunk0 + max(m, 0)) * kC, w, lane, L);
+        c.gf = load_rows_staged(g_fwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
+        c.gb = load_rows_staged(g_bwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
         zero_unless(c.k, valid);
-        zero_unless(c.v, valid);
-        zero_unless(c.gf, valid);
-        zero_unless(c.gb, valid);
         return c;
     };
-    ChunkRows next = fetch(nch - 1);
-    bf16x8 tri_f[2], tri_b[2];
-    scan_triangle<0>(w, r, g, tri_f);
-    scan_triangle<1>(w, r, g, tri_b);
+    // two chunks of rows are kept in flight: at the bandwidth this kernel runs at, a load takes
+    // about as long as one chunk step
+    ChunkRows next = fetch(nch - 1), after_next = fetch(nch - 2);
 
     for (int m = nch - 1; m >= 0; --m) {
         const ChunkRows cur = next;
-        next = fetch(m - 1);
+        next = after_next;
+        after_next = fetch(m - 2);
+        // the scan's triangular operands are rebuilt every step (a few dozen selects) rather than
+        // kept in 16 registers across the loop; the opaque copy keeps them from being hoisted
+        bf16x8 tri_f[2], tri_b[2];
+        {
+            int rr = r;
+            asm volatile("" : "+v"(rr));
+            scan_triangle<0>(w, rr, g, tri_f);
+            scan_triangle<1>(w, rr, g, tri_b);
+        }
 
         // stash for chunk m: the backward state entering it from the right (zero, and not
         // stored, for the segment's last chunk) and the decay from its right edge to the
@@ -1005,9 +1044,9 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
                 *reinterpret_cast<float4 *>(dstm + size_t(kD) * kD * sizeof(uint16_t) + (16 * w + 4 * g) * sizeof(float)) = rb;
         }
 
-        store_row16_raw(sm.g[0], row, g, cur.gf);
-        store_row16_raw(sm.g[1], row, g, cur.gb);
-        store_row16_raw(sm.v, row, g, cur.v);
+        stage_gates(sm.g[0], w, lane, cur.gf);
+        stage_gates(sm.g[1], w, lane, cur.gb);
+        stage_values(sm.v, w, lane, cur.v);
         __syncthreads();  // g, v visible
 
         float kf[16];
@@ -1050,33 +1089,37 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
             db = make_float4(fast_exp2(tb.x * kLog2e), fast_exp2(tb.y * kLog2e), fast_exp2(tb.z * kLog2e),
                              fast_exp2(tb.w * kLog2e));
         } else {
-            // range-safe keys: decay from the token to the chunk edge, every factor <= 1
-            float EB[16], Ff[16], Fb[16];
-            gate_factors_state<0>(lds_row_operand(sm.g[0], row, g), Ff, EB);
+            // range-safe keys: decay from the token to the chunk edge, every factor <= 1.  One
+            // direction at a time (this form is rare; fewer live registers matter more than a barrier)
+            float F[16], EB[16];
+            gate_factors_state<0>(lds_row_operand(sm.g[0], row, g), F, EB);
             if (r == 0) store_chan16(sm.eb[0][w], g, EB);
-            gate_factors_state<1>(lds_row_operand(sm.g[1], row, g), Fb, EB);
-            if (r == 0) store_chan16(sm.eb[1][w], g, EB);
-            __syncthreads();  // eb visible
+            __syncthreads();  // eb[0] visible
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                Ff[e] *= kf[e];
-                Fb[e] *= kf[e];
-            }
+            for (int e = 0; e < 16; ++e) F[e] *= kf[e];
 #pragma unroll
-            for (int sb = 0; sb < 4; ++sb) {
+            for (int sb = 1; sb < 4; ++sb) {
                 if (sb > w) {  // forward: the sub-blocks to the right
                     load_chan16(sm.eb[0][sb], g, tmp);
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) Ff[e] *= tmp[e];
+                    for (int e = 0; e < 16; ++e) F[e] *= tmp[e];
                 }
+            }
+            store_row16(sm.ks[0], row, g, F);
+            gate_factors_state<1>(lds_row_operand(sm.g[1], row, g), F, EB);
+            if (r == 0) store_chan16(sm.eb[1][w], g, EB);
+            __syncthreads();  // eb[1] visible
+#pragma unroll
+            for (int e = 0; e < 16; ++e) F[e] *= kf[e];
+#pragma unroll
+            for (int sb = 0; sb < 3; ++sb) {
                 if (sb < w) {  // backward: the sub-blocks to the left
                     load_chan16(sm.eb[1][sb], g, tmp);
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) Fb[e] *= tmp[e];
+                    for (int e = 0; e < 16; ++e) F[e] *= tmp[e];
                 }
             }
-            store_row16(sm.ks[0], row, g, Ff);
-            store_row16(sm.ks[1], row, g, Fb);
+            store_row16(sm.ks[1], row, g, F);
             df = *reinterpret_cast<const float4 *>(&sm.eb[0][0][16 * w + 4 * g]);
             db = *reinterpret_cast<const float4 *>(&sm.eb[1][0][16 * w + 4 * g]);
 #pragma unroll
