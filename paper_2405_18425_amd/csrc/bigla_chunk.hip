@@ -185,32 +185,12 @@ struct Row16 {
     uint4 p[2];
 };
 
-// Global row loads are branch-free: an out-of-range token reads the (valid) row `token_clamped`
-// and is zeroed afterwards.  With no control flow around the loads the compiler can count the
-// outstanding ones exactly, so waiting for one chunk's rows does not also wait for the prefetch
-// issued after them.
-__device__ __forceinline__ void zero_unless(Row16 &r, bool valid)
-{
-    if (!valid) {  // selects, not a branch around memory operations
-        r.p[0] = make_uint4(0, 0, 0, 0);
-        r.p[1] = make_uint4(0, 0, 0, 0);
-    }
-}
-
-// Operand rows (q, k): lane (r, g) takes the two 16-byte pieces of its token at channel offsets
-// 8g and 32+8g; slot n of the lane is channel 32*(n/8) + 8g + n%8.
-__device__ __forceinline__ Row16 load_row_operand(const uint16_t *slab_base, long token_clamped, int g)
-{
-    Row16 r;
-    const uint4 *p = reinterpret_cast<const uint4 *>(slab_base + token_clamped * kD + 8 * g);
-    r.p[0] = p[0];
-    r.p[1] = p[4];  // +32 elements
-    return r;
-}
-
-// Rows that are only staged into LDS (v, g_fwd, g_bwd): fully contiguous wave loads, 8 whole
-// 128-byte rows per instruction.  Lane i of wave w takes 16-byte piece i%8 of rows
-// 16w + i/8 and 16w + 8 + i/8 of the chunk.
+// Every global row load is a fully contiguous wave load, 8 whole 128-byte rows per instruction:
+// lane i of wave w takes 16-byte piece i%8 of rows 16w + i/8 and 16w + 8 + i/8 of the chunk.
+// The loads are branch-free: an out-of-range token reads the last valid row and is zeroed
+// afterwards.  With no control flow around the loads the compiler can count the outstanding
+// ones exactly, so waiting for one chunk's rows does not also wait for the prefetch issued
+// after them.
 struct StagedRows {
     uint4 p[2];
 };
@@ -227,6 +207,33 @@ __device__ __forceinline__ StagedRows load_rows_staged(const uint16_t *slab_base
         if (tok >= L) s.p[t] = make_uint4(0, 0, 0, 0);  // a select, not a branch around the load
     }
     return s;
+}
+
+// Orders this wave's earlier LDS writes before its later LDS reads of what other lanes of the
+// same wave wrote (the LDS executes one wave's accesses in order; this keeps the compiler from
+// moving them across each other).
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Operand rows (q, k) arrive as contiguous rows too; the wave turns its own 16 rows into the
+// operand layout through 16 tile rows that no other wave touches at that point.
+__device__ __forceinline__ void bounce_store(uint16_t (*tile)[kPitch], int w, int lane, const StagedRows &s)
+{
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+        *reinterpret_cast<uint4 *>(&tile[16 * w + 8 * t + (lane >> 3)][8 * (lane & 7)]) = s.p[t];
+}
+
+__device__ __forceinline__ Row16 bounce_load(const uint16_t (*tile)[kPitch], int row, int g)
+{
+    Row16 r;
+    r.p[0] = *reinterpret_cast<const uint4 *>(&tile[row][8 * g]);
+    r.p[1] = *reinterpret_cast<const uint4 *>(&tile[row][32 + 8 * g]);
+    return r;
 }
 
 // values: natural column order
@@ -571,7 +578,8 @@ struct ChunkFlags {
 // fast_update: S = d (S + K^T V) with d = exp(tot); otherwise S = d S + K^T V with d = prod(eb).
 __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)[kPitch], const ChunkOperands &op,
                                              const ChunkFlags fl, const bool fast_update, const int w, const int r,
-                                             const int g, uint16_t *out_row, f32x4 (&S)[4])
+                                             const int g, uint16_t *out_slab, const long chunk_token0, const int L,
+                                             f32x4 (&S)[4])
 {
     const uint2(&pk)[4] = op.pk;
     bf16x8 vop[2][4];
@@ -592,11 +600,21 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
     readout(sm.st, op.qf0, op.qf1, r, g, O);
     if (fl.stash) readout(sm.sb, op.qb0, op.qb1, r, g, O);
     if (fl.seg) readout(sm.sseg, op.qs0, op.qs1, r, g, O);
-    if (out_row) {  // o_t = (o_fwd_t + o_bwd_t) / 2
+    {  // o_t = (o_fwd_t + o_bwd_t) / 2, turned into whole rows through the wave's own rows of the
+       // forward gate tile (last read before the score tiles), then written 8 rows per store
+        const int lane = 16 * g + r;
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt)
-            *reinterpret_cast<uint2 *>(out_row + 16 * jt + 4 * g) =
+            *reinterpret_cast<uint2 *>(&sm.gf[16 * w + r][16 * jt + 4 * g]) =
                 make_uint2(pack2(0.5f * O[jt][0], 0.5f * O[jt][1]), pack2(0.5f * O[jt][2], 0.5f * O[jt][3]));
+        wave_lds_fence();
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int rr = 16 * w + 8 * t + (lane >> 3);
+            const uint4 o = *reinterpret_cast<const uint4 *>(&sm.gf[rr][8 * (lane & 7)]);
+            if (chunk_token0 + rr < L)
+                *reinterpret_cast<uint4 *>(out_slab + (chunk_token0 + rr) * kD + 8 * (lane & 7)) = o;
+        }
     }
 
     // forward state, rows at LDS positions 16w + 4g + e
@@ -874,27 +892,22 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
 
     // rows of the next chunk are fetched while the current chunk is being processed
     struct ChunkRows {
-        Row16 q, k, sb;
-        StagedRows gf, gb, v;
+        Row16 sb;
+        StagedRows q, k, gf, gb, v;
     };
     auto fetch = [&](int m) {  // m may run one past the segment: clamped, the rows are then unused
         const int mc = min(m, nch - 1);
-        const long tok = long(chunk0 + mc) * kC + row;
-        const bool valid = tok < L;
-        const long tc = min(tok, long(L) - 1);
         ChunkRows c;
-        c.q = load_row_operand(q, tc, g);
-        c.k = load_row_operand(k, tc, g);
+        c.q = load_rows_staged(q, long(chunk0 + mc) * kC, w, lane, L);
+        c.k = load_rows_staged(k, long(chunk0 + mc) * kC, w, lane, L);
         c.gf = load_rows_staged(g_fwd, long(chunk0 + mc) * kC, w, lane, L);
         c.gb = load_rows_staged(g_bwd, long(chunk0 + mc) * kC, w, lane, L);
         c.v = load_rows_staged(v, long(chunk0 + mc) * kC, w, lane, L);
         // this lane's 16 values of the chunk's stashed state (unwritten, and unused, for the
         // segment's last chunk)
-        const uint4 *p = reinterpret_cast<const uint4 *>(stash + size_t(chunk0 + mc) * kStashBytes) + 2 * tid;
+        const uint4 *p = reinterpret_cast<const uint4 *>(stash + size_t(chunk0 + mc) * kStashBytes) + tid;
         c.sb.p[0] = p[0];
-        c.sb.p[1] = p[1];
-        zero_unless(c.q, valid);
-        zero_unless(c.k, valid);
+        c.sb.p[1] = p[kThreads];
         return c;
     };
     ChunkRows next = fetch(0);
@@ -917,9 +930,15 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
         fl.stash = m + 1 < nch;
         fl.seg = seg_in;
 
+        // kf / kb are idle until this step's scaled keys are written: the wave's own rows of
+        // them carry q and k from row order into operand order
+        bounce_store(sm.kf, w, lane, cur.q);
+        bounce_store(sm.kb, w, lane, cur.k);
         stage_gates(sm.gf, w, lane, cur.gf);
         stage_gates(sm.gb, w, lane, cur.gb);
         stage_values(sm.v, w, lane, cur.v);
+        wave_lds_fence();
+        const Row16 q_row = bounce_load(sm.kf, row, g), k_row = bounce_load(sm.kb, row, g);
         if (fl.stash) {  // accumulator order -> [column][channel] tile
             *reinterpret_cast<uint2 *>(&sm.sb[r][16 * w + 4 * g]) = make_uint2(cur.sb.p[0].x, cur.sb.p[0].y);
             *reinterpret_cast<uint2 *>(&sm.sb[16 + r][16 * w + 4 * g]) = make_uint2(cur.sb.p[0].z, cur.sb.p[0].w);
@@ -933,29 +952,27 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
         }
         __syncthreads();  // staged tiles visible
 
-        const long tok = long(chunk0 + m) * kC + row;
-        uint16_t *out_row = tok < L ? out + tok * kD : nullptr;
         f32x4 Bf[4], Tf[4], Bb[4];
         ChunkOperands op;
         bool fast = true;
         chunk_gate_scan(sm.gf, tri_f, r, g, Bf, Tf);
         if (kFastOnly) {
             chunk_gate_scan(sm.gb, tri_b, r, g, Bb);
-            out_chunk_fast(sm, w, r, g, Bf, Bb, Tf, cur.q, cur.k, fl, op);
+            out_chunk_fast(sm, w, r, g, Bf, Bb, Tf, q_row, k_row, fl, op);
         } else {
             f32x4 Tb[4];
             chunk_gate_scan(sm.gb, tri_b, r, g, Bb, Tb);
             // same totals in every wave: the choice is uniform over the workgroup
             fast = fmaxf(chunk_decay_max(Tf), chunk_decay_max(Tb)) <= kFastRange;
             if (fast)
-                out_chunk_fast(sm, w, r, g, Bf, Bb, Tf, cur.q, cur.k, fl, op);
+                out_chunk_fast(sm, w, r, g, Bf, Bb, Tf, q_row, k_row, fl, op);
             else
-                out_chunk_safe(sm, w, r, g, cur.q, cur.k, fl, op);
+                out_chunk_safe(sm, w, r, g, q_row, k_row, fl, op);
         }
         // the next chunk's rows travel while the matrix cores finish this one: issued here, after
         // the element-wise half, so that they do not occupy registers during it
         next = fetch(m + 1);
-        finish_chunk(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out_row, S);
+        finish_chunk(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L, S);
     }
     }  // units
 }
@@ -996,19 +1013,14 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     bool all_fast = true;  // every chunk of the segment within the fast form's range
 
     struct ChunkRows {
-        Row16 k;
-        StagedRows v, gf, gb;
+        StagedRows k, v, gf, gb;
     };
     auto fetch = [&](int m) {  // m may run one before the segment: clamped, the rows are then unused
-        const long tok = long(chunk0 + max(m, 0)) * kC + row;
-        const bool valid = tok < L;
-        const long tc = min(tok, long(L) - 1);
         ChunkRows c;
-        c.k = load_row_operand(k, tc, g);
+        c.k = load_rows_staged(k, long(chunk0 + max(m, 0)) * kC, w, lane, L);
         c.v = load_rows_staged(v, long(chunk0 + max(m, 0)) * kC, w, lane, L);
         c.gf = load_rows_staged(g_fwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
         c.gb = load_rows_staged(g_bwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
-        zero_unless(c.k, valid);
         return c;
     };
     // two chunks of rows are kept in flight: at the bandwidth this kernel runs at, a load takes
@@ -1034,23 +1046,27 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         // segment's right edge
         {
             unsigned char *dstm = stash + size_t(chunk0 + m) * kStashBytes;
-            if (m + 1 < nch) {  // accumulator order: 32 contiguous bytes per lane, 2 KB per wave
-                uint4 *sdst = reinterpret_cast<uint4 *>(dstm) + 2 * tid;
+            if (m + 1 < nch) {  // accumulator order, two halves of 4 KB, each store contiguous over the wave
+                uint4 *sdst = reinterpret_cast<uint4 *>(dstm) + tid;
                 const uint2 a = pack4(Sb[0]), b = pack4(Sb[1]), c = pack4(Sb[2]), d = pack4(Sb[3]);
                 sdst[0] = make_uint4(a.x, a.y, b.x, b.y);
-                sdst[1] = make_uint4(c.x, c.y, d.x, d.y);
+                sdst[kThreads] = make_uint4(c.x, c.y, d.x, d.y);
             }
             if (r == 0)
                 *reinterpret_cast<float4 *>(dstm + size_t(kD) * kD * sizeof(uint16_t) + (16 * w + 4 * g) * sizeof(float)) = rb;
         }
 
+        // ks[0] is idle until this step's scaled keys are written: the wave's own rows of it
+        // carry k from row order into operand order
+        bounce_store(sm.ks[0], w, lane, cur.k);
         stage_gates(sm.g[0], w, lane, cur.gf);
         stage_gates(sm.g[1], w, lane, cur.gb);
         stage_values(sm.v, w, lane, cur.v);
+        wave_lds_fence();
+        float kf[16];
+        unpack16(bounce_load(sm.ks[0], row, g), kf);
         __syncthreads();  // g, v visible
 
-        float kf[16];
-        unpack16(cur.k, kf);
         f32x4 Bf[4], Bb[4];
         float max_f, max_b;
         {
