@@ -406,8 +406,9 @@ struct __align__(16) StateLds {
 };
 
 // Workspace: [segment region][segment flags][stash region].
-//   segment region, per (slab, segment): two fp32 64x64 states (forward, backward) then two
-//     fp32 decay vectors; rows in operand order.
+//   segment region, per (slab, segment): two fp32 64x64 states (forward, backward) in
+//     accumulator order (float4 number 256*jt + t belongs to thread t of the workgroup:
+//     column 16*jt + r of rows 16w + 4g + e), then two fp32 decay vectors indexed by row.
 //   segment flags, per (slab, segment): one int, non-zero when every chunk of the segment
 //     admits the fast form (written by the state kernel); padded to a multiple of 16 bytes.
 //   stash region, per (slab, chunk): one bf16 64x64 state in accumulator order (thread t of
@@ -539,12 +540,13 @@ __device__ __forceinline__ void publish_state(uint16_t (*tile)[kPitch], int w, i
     for (int jt = 0; jt < 4; ++jt) *reinterpret_cast<uint2 *>(&tile[16 * jt + r][16 * w + 4 * g]) = pack4(S[jt]);
 }
 
-__device__ __forceinline__ void load_state(const float *src, bool zero, int w, int r, int g, f32x4 (&S)[4])
+__device__ __forceinline__ void load_state(const float *src, bool zero, int tid, f32x4 (&S)[4])
 {
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) S[jt][e] = zero ? 0.f : src[(16 * w + 4 * g + e) * kD + 16 * jt + r];
+    for (int jt = 0; jt < 4; ++jt) {
+        S[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (!zero) S[jt] = reinterpret_cast<const f32x4 *>(src)[kThreads * jt + tid];
+    }
 }
 
 // O^T += S^T q^T for one [column][channel] state tile (readout of a state by scaled queries)
@@ -913,11 +915,11 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
     ChunkRows next = fetch(0);
 
     f32x4 S[4];
-    load_state(st_in, st_in == nullptr, w, r, g, S);
+    load_state(st_in, st_in == nullptr, tid, S);
     publish_state(sm.st, w, r, g, S);  // made visible by the first barrier of the first step
     if (seg_in) {
         f32x4 Sb[4];
-        load_state(st_in + size_t(kD) * kD, false, w, r, g, Sb);
+        load_state(st_in + size_t(kD) * kD, false, tid, Sb);
         publish_state(sm.sseg, w, r, g, Sb);
     }
     bf16x8 tri_f[2], tri_b[2];
@@ -1188,13 +1190,10 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     }
 
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int idx = (16 * w + 4 * g + e) * kD + 16 * jt + r;
-            dst[idx] = Sf[jt][e];
-            dst[size_t(kD) * kD + idx] = Sb[jt][e];
-        }
+    for (int jt = 0; jt < 4; ++jt) {
+        reinterpret_cast<f32x4 *>(dst)[kThreads * jt + tid] = Sf[jt];
+        reinterpret_cast<f32x4 *>(dst + size_t(kD) * kD)[kThreads * jt + tid] = Sb[jt];
+    }
     if (r == 0) {
         *reinterpret_cast<float4 *>(dst + kSegStateFloats + 16 * w + 4 * g) = rf;
         *reinterpret_cast<float4 *>(dst + kSegStateFloats + kD + 16 * w + 4 * g) = rb;
@@ -1205,36 +1204,41 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
 // ---- kernel 2: scan of segment states, in place ------------------------------------------------
 // On entry seg_states[slab][n] holds segment n's local end states and decays; on exit it holds the
 // states ENTERING segment n: from the left for the forward direction, from the right for the
-// backward direction.  One thread per (slab, direction, state element).
+// backward direction.  One thread per (slab, direction, float4 of the state): the four values
+// are rows 4g..4g+3 of one 16-row block, so they share one float4 of the decay vector.
 __global__ __launch_bounds__(kThreads) void bigla_state_scan_kernel(float *__restrict__ seg_states, int n_seg)
 {
-    constexpr int kBlocksPerState = kD * kD / kThreads;
-    const int elem = (blockIdx.x % kBlocksPerState) * kThreads + threadIdx.x;  // 0 .. 4095
+    constexpr int kBlocksPerState = kD * kD / 4 / kThreads;
+    const int quad = (blockIdx.x % kBlocksPerState) * kThreads + threadIdx.x;  // 0 .. 1023
     const int dir = (blockIdx.x / kBlocksPerState) & 1;
     const long slab = blockIdx.x / (2 * kBlocksPerState);
     float *base = seg_states + slab * n_seg * kSegFloats;
-    const int c = elem / kD;
-    float run = 0.f;
+    const int owner = quad % kThreads;                                  // thread of the producing workgroup
+    const int row0 = 16 * (owner / 64) + 4 * ((owner % 64) / 16);       // 16w + 4g
+    float4 run = make_float4(0.f, 0.f, 0.f, 0.f);
     // batches of 8 segments: all loads of a batch are issued before its first store, so that the
     // in-place update does not serialise one memory round trip per segment
     constexpr int kBatch = 8;
     for (int i0 = 0; i0 < n_seg; i0 += kBatch) {
-        float local[kBatch], decay[kBatch];
+        float4 local[kBatch], decay[kBatch];
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             const int i = min(i0 + u, n_seg - 1);
             const int n = dir == 0 ? i : n_seg - 1 - i;
             const float *s = base + n * kSegFloats;
-            local[u] = s[dir * kD * kD + elem];
-            decay[u] = s[kSegStateFloats + dir * kD + c];
+            local[u] = reinterpret_cast<const float4 *>(s + dir * kD * kD)[quad];
+            decay[u] = *reinterpret_cast<const float4 *>(s + kSegStateFloats + dir * kD + row0);
         }
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             if (i0 + u < n_seg) {
                 const int i = i0 + u;
                 const int n = dir == 0 ? i : n_seg - 1 - i;
-                base[n * kSegFloats + dir * kD * kD + elem] = run;
-                run = fmaf(run, decay[u], local[u]);
+                reinterpret_cast<float4 *>(base + n * kSegFloats + dir * kD * kD)[quad] = run;
+                run.x = fmaf(run.x, decay[u].x, local[u].x);
+                run.y = fmaf(run.y, decay[u].y, local[u].y);
+                run.z = fmaf(run.z, decay[u].z, local[u].z);
+                run.w = fmaf(run.w, decay[u].w, local[u].w);
             }
         }
     }
@@ -1280,7 +1284,7 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
     if (p.n_seg > 1) {
         {
             LaunchTimer timer(kKernelStateScan, stream);
-            hipLaunchKernelGGL(bigla_state_scan_kernel, dim3((unsigned)(BH * 2 * (kD * kD / kThreads))),
+            hipLaunchKernelGGL(bigla_state_scan_kernel, dim3((unsigned)(BH * 2 * (kD * kD / 4 / kThreads))),
                                dim3(kThreads), 0, stream, seg_states, p.n_seg);
         }
         e = hipGetLastError();
