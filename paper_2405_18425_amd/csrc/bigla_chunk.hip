@@ -578,10 +578,11 @@ struct ChunkFlags {
 // Everything after the score tiles, common to both forms: O^T = V^T P^T + the three readouts,
 // out = O/2, then the forward state update with the keys in `ktile`.
 // fast_update: S = d (S + K^T V) with d = exp(tot); otherwise S = d S + K^T V with d = prod(eb).
+template <class Prefetch>
 __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)[kPitch], const ChunkOperands &op,
                                              const ChunkFlags fl, const bool fast_update, const int w, const int r,
                                              const int g, uint16_t *out_slab, const long chunk_token0, const int L,
-                                             f32x4 (&S)[4])
+                                             f32x4 (&S)[4], Prefetch &&prefetch_last)
 {
     const uint2(&pk)[4] = op.pk;
     bf16x8 vop[2][4];
@@ -602,6 +603,7 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
     readout(sm.st, op.qf0, op.qf1, r, g, O);
     if (fl.stash) readout(sm.sb, op.qb0, op.qb1, r, g, O);
     if (fl.seg) readout(sm.sseg, op.qs0, op.qs1, r, g, O);
+    prefetch_last();
     {  // o_t = (o_fwd_t + o_bwd_t) / 2, turned into whole rows through the wave's own rows of the
        // forward gate tile (last read before the score tiles), then written 8 rows per store
         const int lane = 16 * g + r;
@@ -656,9 +658,11 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
 
 // FAST form of one chunk, both directions (see the header).  Bf / Bb are the lane's cumulative
 // log-gates of the two directions, Tf the forward chunk totals.
+template <class Prefetch>
 __device__ __forceinline__ void out_chunk_fast(OutLds &sm, const int w, const int r, const int g, const f32x4 (&Bf)[4],
                                                const f32x4 (&Bb)[4], const f32x4 (&Tf)[4], const Row16 &qraw,
-                                               const Row16 &kraw, const ChunkFlags fl, ChunkOperands &op)
+                                               const Row16 &kraw, const ChunkFlags fl, ChunkOperands &op,
+                                               Prefetch &&prefetch_first)
 {
     const int row = 16 * w + r;
     if (r == 0) {  // forward chunk totals per channel, operand order, for the state decay
@@ -696,6 +700,7 @@ __device__ __forceinline__ void out_chunk_fast(OutLds &sm, const int w, const in
     }
 
     __syncthreads();  // kf, kb, tot visible
+    prefetch_first();
 
     // merged score tile, transposed: P^T[i][t]; key sub-block I < w forward, I > w backward,
     // I = w the masked sum of both (own token counted by both directions)
@@ -726,8 +731,10 @@ __device__ __forceinline__ void out_chunk_fast(OutLds &sm, const int w, const in
 
 // RANGE-SAFE form of one chunk, both directions (see the header); scans the sub-block-local,
 // floored gates itself from the staged raw gates.
+template <class Prefetch>
 __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const int r, const int g, const Row16 &qraw,
-                                               const Row16 &kraw, const ChunkFlags fl, ChunkOperands &op)
+                                               const Row16 &kraw, const ChunkFlags fl, ChunkOperands &op,
+                                               Prefetch &&prefetch_first)
 {
     const int row = 16 * w + r;
     float qf[16], kf[16], tmp[16];
@@ -772,6 +779,7 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
     }
 
     __syncthreads();  // eb, kf, kb visible; the raw gate tiles are no longer read
+    prefetch_first();
 
     // query variants: qv[dir][d] pairs with the keys d+1 sub-blocks away in that direction's
     // past; after the last one the running query is the readout query (decay since the chunk edge)
@@ -897,22 +905,31 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
         Row16 sb;
         StagedRows q, k, gf, gb, v;
     };
-    auto fetch = [&](int m) {  // m may run one past the segment: clamped, the rows are then unused
-        const int mc = min(m, nch - 1);
-        ChunkRows c;
-        c.q = load_rows_staged(q, long(chunk0 + mc) * kC, w, lane, L);
-        c.k = load_rows_staged(k, long(chunk0 + mc) * kC, w, lane, L);
-        c.gf = load_rows_staged(g_fwd, long(chunk0 + mc) * kC, w, lane, L);
-        c.gb = load_rows_staged(g_bwd, long(chunk0 + mc) * kC, w, lane, L);
-        c.v = load_rows_staged(v, long(chunk0 + mc) * kC, w, lane, L);
+    // The rows of the next chunk are requested in three groups between the phases of a step (a
+    // burst of all twelve loads would stall the wave at issue while the memory pipeline is
+    // full).  m may run one past the segment: clamped, the rows are then unused.
+    auto chunk_token0 = [&](int m) { return long(chunk0 + min(m, nch - 1)) * kC; };
+    auto fetch_qk = [&](ChunkRows &c, int m) {
+        c.q = load_rows_staged(q, chunk_token0(m), w, lane, L);
+        c.k = load_rows_staged(k, chunk_token0(m), w, lane, L);
+    };
+    auto fetch_gates = [&](ChunkRows &c, int m) {
+        c.gf = load_rows_staged(g_fwd, chunk_token0(m), w, lane, L);
+        c.gb = load_rows_staged(g_bwd, chunk_token0(m), w, lane, L);
+    };
+    auto fetch_v_stash = [&](ChunkRows &c, int m) {
+        c.v = load_rows_staged(v, chunk_token0(m), w, lane, L);
         // this lane's 16 values of the chunk's stashed state (unwritten, and unused, for the
         // segment's last chunk)
-        const uint4 *p = reinterpret_cast<const uint4 *>(stash + size_t(chunk0 + mc) * kStashBytes) + tid;
+        const uint4 *p =
+            reinterpret_cast<const uint4 *>(stash + size_t(chunk0 + min(m, nch - 1)) * kStashBytes) + tid;
         c.sb.p[0] = p[0];
         c.sb.p[1] = p[kThreads];
-        return c;
     };
-    ChunkRows next = fetch(0);
+    ChunkRows next;
+    fetch_qk(next, 0);
+    fetch_gates(next, 0);
+    fetch_v_stash(next, 0);
 
     f32x4 S[4];
     load_state(st_in, st_in == nullptr, tid, S);
@@ -957,24 +974,31 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
         f32x4 Bf[4], Tf[4], Bb[4];
         ChunkOperands op;
         bool fast = true;
+        // (the general kernel, short of registers, requests everything at the middle point)
+        auto prefetch_first = [&]() {
+            if (kFastOnly) fetch_qk(next, m + 1);
+        };
+        auto prefetch_last = [&]() {
+            if (kFastOnly) fetch_v_stash(next, m + 1);
+        };
         chunk_gate_scan(sm.gf, tri_f, r, g, Bf, Tf);
         if (kFastOnly) {
             chunk_gate_scan(sm.gb, tri_b, r, g, Bb);
-            out_chunk_fast(sm, w, r, g, Bf, Bb, Tf, q_row, k_row, fl, op);
+            out_chunk_fast(sm, w, r, g, Bf, Bb, Tf, q_row, k_row, fl, op, prefetch_first);
         } else {
             f32x4 Tb[4];
             chunk_gate_scan(sm.gb, tri_b, r, g, Bb, Tb);
             // same totals in every wave: the choice is uniform over the workgroup
             fast = fmaxf(chunk_decay_max(Tf), chunk_decay_max(Tb)) <= kFastRange;
             if (fast)
-                out_chunk_fast(sm, w, r, g, Bf, Bb, Tf, q_row, k_row, fl, op);
+                out_chunk_fast(sm, w, r, g, Bf, Bb, Tf, q_row, k_row, fl, op, prefetch_first);
             else
-                out_chunk_safe(sm, w, r, g, q_row, k_row, fl, op);
+                out_chunk_safe(sm, w, r, g, q_row, k_row, fl, op, prefetch_first);
         }
-        // the next chunk's rows travel while the matrix cores finish this one: issued here, after
-        // the element-wise half, so that they do not occupy registers during it
-        next = fetch(m + 1);
-        finish_chunk(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L, S);
+        if (!kFastOnly) fetch_qk(next, m + 1);
+        fetch_gates(next, m + 1);
+        if (!kFastOnly) fetch_v_stash(next, m + 1);
+        finish_chunk(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L, S, prefetch_last);
     }
     }  // units
 }
@@ -1032,7 +1056,10 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     for (int m = nch - 1; m >= 0; --m) {
         const ChunkRows cur = next;
         next = after_next;
-        after_next = fetch(m - 2);
+        // the rows of chunk m-2 are requested a tile at a time between the phases of this step:
+        // a burst of all of them would stall this wave at issue while the memory pipeline is full
+        const long far_token0 = long(chunk0 + max(m - 2, 0)) * kC;
+        after_next.k = load_rows_staged(k, far_token0, w, lane, L);
         // the scan's triangular operands are rebuilt every step (a few dozen selects) rather than
         // kept in 16 registers across the loop; the opaque copy keeps them from being hoisted
         bf16x8 tri_f[2], tri_b[2];
@@ -1068,6 +1095,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         float kf[16];
         unpack16(bounce_load(sm.ks[0], row, g), kf);
         __syncthreads();  // g, v visible
+        after_next.v = load_rows_staged(v, far_token0, w, lane, L);
 
         f32x4 Bf[4], Bb[4];
         float max_f, max_b;
@@ -1087,6 +1115,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         }
         const bool fast = fmaxf(max_f, max_b) <= kFastRange;  // uniform over the workgroup
         all_fast = all_fast && fast;
+        after_next.gf = load_rows_staged(g_fwd, far_token0, w, lane, L);
         float4 df, db;  // this chunk's decay, rows at LDS positions 16w + 4g + e
         float tmp[16];
         if (fast) {
@@ -1150,6 +1179,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
             __syncthreads();  // ks visible
         }
 
+        after_next.gb = load_rows_staged(g_bwd, far_token0, w, lane, L);
         // chunk contributions K^T V of both directions, rows at positions 16w + 4g + e
         f32x4 Cf[4], Cb[4];
 #pragma unroll
