@@ -187,10 +187,10 @@ struct Row16 {
 
 // Every global row load is a fully contiguous wave load, 8 whole 128-byte rows per instruction:
 // lane i of wave w takes 16-byte piece i%8 of rows 16w + i/8 and 16w + 8 + i/8 of the chunk.
-// The loads are branch-free: an out-of-range token reads the last valid row and is zeroed
-// afterwards.  With no control flow around the loads the compiler can count the outstanding
-// ones exactly, so waiting for one chunk's rows does not also wait for the prefetch issued
-// after them.
+// The loads are branch-free: an out-of-range token reads the last valid row, and the rows of a
+// ragged final chunk are zeroed when they are consumed (zero_past_end).  With no control flow
+// around the loads the compiler can count the outstanding ones exactly, so waiting for one
+// chunk's rows does not also wait for the prefetch issued after them.
 struct StagedRows {
     uint4 p[2];
 };
@@ -204,9 +204,16 @@ __device__ __forceinline__ StagedRows load_rows_staged(const uint16_t *slab_base
         const long tok = chunk_token0 + 16 * w + 8 * t + (lane >> 3);
         const long tc = tok < L ? tok : long(L) - 1;
         s.p[t] = *reinterpret_cast<const uint4 *>(slab_base + tc * kD + 8 * (lane & 7));
-        if (tok >= L) s.p[t] = make_uint4(0, 0, 0, 0);  // a select, not a branch around the load
     }
     return s;
+}
+
+// Zero the rows of tokens >= L (k = v = 0 and log-gate 0 make such a token a no-op).
+__device__ __forceinline__ void zero_past_end(StagedRows &s, long chunk_token0, int w, int lane, int L)
+{
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+        if (chunk_token0 + 16 * w + 8 * t + (lane >> 3) >= L) s.p[t] = make_uint4(0, 0, 0, 0);
 }
 
 // Orders this wave's earlier LDS writes before its later LDS reads of what other lanes of the
@@ -391,9 +398,7 @@ struct __align__(16) OutLds {
     uint16_t v[kC][kPitch];     // values                        [token][column]
     uint16_t st[kD][kPitch];    // forward state, bf16 copy      [column][channel, operand order]
     uint16_t sb[kD][kPitch];    // stashed backward state entering the chunk, same layout
-    uint16_t sseg[kD][kPitch];  // backward state entering the segment, same layout
     float tot[kD];              // forward chunk total log-gate per channel (fast form), operand order
-    float dr[kD];               // decay from the chunk's right edge to the segment's right edge
     float eb[2][4][kD];         // whole-sub-block decay factors per channel (range-safe form)
 };
 
@@ -567,7 +572,7 @@ __device__ __forceinline__ void readout(const uint16_t (*tile)[kPitch], bf16x8 q
 // What the first half of a chunk step (scores) hands to the second half (finish_chunk)
 struct ChunkOperands {
     uint2 pk[4];                       // merged masked score tile, bf16, per key sub-block
-    bf16x8 qf0, qf1, qb0, qb1, qs0, qs1;  // readout queries: forward, backward (stash), backward (segment)
+    bf16x8 qf0, qf1, qb0, qb1;  // readout queries: forward, backward
 };
 
 struct ChunkFlags {
@@ -601,8 +606,7 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
         for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(vop[1][jt], pa1, mfma(vop[0][jt], pa0, zero));
     }
     readout(sm.st, op.qf0, op.qf1, r, g, O);
-    if (fl.stash) readout(sm.sb, op.qb0, op.qb1, r, g, O);
-    if (fl.seg) readout(sm.sseg, op.qs0, op.qs1, r, g, O);
+    if (fl.stash || fl.seg) readout(sm.sb, op.qb0, op.qb1, r, g, O);
     prefetch_last();
     {  // o_t = (o_fwd_t + o_bwd_t) / 2, turned into whole rows through the wave's own rows of the
        // forward gate tile (last read before the score tiles), then written 8 rows per store
@@ -688,17 +692,6 @@ __device__ __forceinline__ void out_chunk_fast(OutLds &sm, const int w, const in
     *reinterpret_cast<bf16x8 *>(&sm.kf[row][32 + 8 * g]) = kf1;
     *reinterpret_cast<bf16x8 *>(&sm.kb[row][8 * g]) = kb0;
     *reinterpret_cast<bf16x8 *>(&sm.kb[row][32 + 8 * g]) = kb1;
-    // queries that read the state entering the SEGMENT: further decay from the chunk's right edge
-    bf16x8 qs0 = qb0, qs1 = qb1;
-    if (fl.seg) {
-        float dr[16];
-        load_chan16(sm.dr, g, dr);
-#pragma unroll
-        for (int n = 0; n < 16; ++n) qb[n] *= dr[n];
-        qs0 = pack8(qb);
-        qs1 = pack8(qb + 8);
-    }
-
     __syncthreads();  // kf, kb, tot visible
     prefetch_first();
 
@@ -726,7 +719,7 @@ __device__ __forceinline__ void out_chunk_fast(OutLds &sm, const int w, const in
             op.pk[I] = pack4(mfma(a1, qb1, mfma(a0, qb0, zero)));
         }
     }
-    op.qf0 = qf0; op.qf1 = qf1; op.qb0 = qb0; op.qb1 = qb1; op.qs0 = qs0; op.qs1 = qs1;
+    op.qf0 = qf0; op.qf1 = qf1; op.qb0 = qb0; op.qb1 = qb1;
 }
 
 // RANGE-SAFE form of one chunk, both directions (see the header); scans the sub-block-local,
@@ -803,14 +796,6 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
         }
     }
     const bf16x8 qf0 = pack8(cum[0]), qf1 = pack8(cum[0] + 8), qb0 = pack8(cum[1]), qb1 = pack8(cum[1] + 8);
-    bf16x8 qs0 = qb0, qs1 = qb1;
-    if (fl.seg) {
-        load_chan16(sm.dr, g, tmp);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) cum[1][e] *= tmp[e];
-        qs0 = pack8(cum[1]);
-        qs1 = pack8(cum[1] + 8);
-    }
     // forward state-update keys: decay to the chunk's right edge = khat times the sub-blocks to
     // the right; they take the place of the raw backward gates in LDS
 #pragma unroll
@@ -856,7 +841,7 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
             op.pk[I] = pack4(p);
         }
     }
-    op.qf0 = qf0; op.qf1 = qf1; op.qb0 = qb0; op.qb1 = qb1; op.qs0 = qs0; op.qs1 = qs1;
+    op.qf0 = qf0; op.qf1 = qf1; op.qb0 = qb0; op.qb1 = qb1;
 }
 
 // kFastOnly = true : handles the segments the state kernel has flagged as entirely within the
@@ -903,6 +888,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
     // rows of the next chunk are fetched while the current chunk is being processed
     struct ChunkRows {
         Row16 sb;
+        float4 dr;  // decay of the lane's state rows from the chunk's right edge to the segment's
         StagedRows q, k, gf, gb, v;
     };
     // The rows of the next chunk are requested in three groups between the phases of a step (a
@@ -925,6 +911,8 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
             reinterpret_cast<const uint4 *>(stash + size_t(chunk0 + min(m, nch - 1)) * kStashBytes) + tid;
         c.sb.p[0] = p[0];
         c.sb.p[1] = p[kThreads];
+        c.dr = *reinterpret_cast<const float4 *>(reinterpret_cast<const unsigned char *>(p - tid) +
+                                                 size_t(kD) * kD * sizeof(uint16_t) + (16 * w + 4 * g) * sizeof(float));
     };
     ChunkRows next;
     fetch_qk(next, 0);
@@ -934,17 +922,24 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
     f32x4 S[4];
     load_state(st_in, st_in == nullptr, tid, S);
     publish_state(sm.st, w, r, g, S);  // made visible by the first barrier of the first step
-    if (seg_in) {
-        f32x4 Sb[4];
-        load_state(st_in + size_t(kD) * kD, false, tid, Sb);
-        publish_state(sm.sseg, w, r, g, Sb);
-    }
+    // backward state entering the segment from the right, kept in registers: each step adds its
+    // decayed copy to the chunk's stashed state, so that one readout serves both
+    f32x4 Sseg[4];
+    load_state(st_in + size_t(kD) * kD, !seg_in, tid, Sseg);
     bf16x8 tri_f[2], tri_b[2];
     scan_triangle<0>(w, r, g, tri_f);
     scan_triangle<1>(w, r, g, tri_b);
 
     for (int m = 0; m < nch; ++m) {
-        const ChunkRows cur = next;
+        ChunkRows cur = next;
+        if (long(chunk0 + m + 1) * kC > L) {  // ragged final chunk of the sequence (uniform branch)
+            const long t0 = long(chunk0 + m) * kC;
+            zero_past_end(cur.q, t0, w, lane, L);
+            zero_past_end(cur.k, t0, w, lane, L);
+            zero_past_end(cur.gf, t0, w, lane, L);
+            zero_past_end(cur.gb, t0, w, lane, L);
+            zero_past_end(cur.v, t0, w, lane, L);
+        }
         ChunkFlags fl;
         fl.stash = m + 1 < nch;
         fl.seg = seg_in;
@@ -958,16 +953,28 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
         stage_values(sm.v, w, lane, cur.v);
         wave_lds_fence();
         const Row16 q_row = bounce_load(sm.kf, row, g), k_row = bounce_load(sm.kb, row, g);
-        if (fl.stash) {  // accumulator order -> [column][channel] tile
-            *reinterpret_cast<uint2 *>(&sm.sb[r][16 * w + 4 * g]) = make_uint2(cur.sb.p[0].x, cur.sb.p[0].y);
-            *reinterpret_cast<uint2 *>(&sm.sb[16 + r][16 * w + 4 * g]) = make_uint2(cur.sb.p[0].z, cur.sb.p[0].w);
-            *reinterpret_cast<uint2 *>(&sm.sb[32 + r][16 * w + 4 * g]) = make_uint2(cur.sb.p[1].x, cur.sb.p[1].y);
-            *reinterpret_cast<uint2 *>(&sm.sb[48 + r][16 * w + 4 * g]) = make_uint2(cur.sb.p[1].z, cur.sb.p[1].w);
-        }
-        if (fl.seg && tid < kD / 4) {
-            const float *dr = reinterpret_cast<const float *>(stash + size_t(chunk0 + m) * kStashBytes +
-                                                              size_t(kD) * kD * sizeof(uint16_t));
-            reinterpret_cast<float4 *>(sm.dr)[tid] = reinterpret_cast<const float4 *>(dr)[tid];
+        if (fl.stash || fl.seg) {
+            // backward state entering the chunk from the right: the stash (accumulator order, zero
+            // for the segment's last chunk) plus the segment's entering state decayed from the
+            // segment's right edge to the chunk's; stored as a [column][channel] tile
+            uint2 t[4] = {make_uint2(cur.sb.p[0].x, cur.sb.p[0].y), make_uint2(cur.sb.p[0].z, cur.sb.p[0].w),
+                          make_uint2(cur.sb.p[1].x, cur.sb.p[1].y), make_uint2(cur.sb.p[1].z, cur.sb.p[1].w)};
+            if (fl.seg) {
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt) {
+                    f32x4 x = {0.f, 0.f, 0.f, 0.f};
+                    if (fl.stash)
+                        x = f32x4{bf16_lo_to_f32(t[jt].x), bf16_hi_to_f32(t[jt].x), bf16_lo_to_f32(t[jt].y),
+                                  bf16_hi_to_f32(t[jt].y)};
+                    x[0] = fmaf(cur.dr.x, Sseg[jt][0], x[0]);
+                    x[1] = fmaf(cur.dr.y, Sseg[jt][1], x[1]);
+                    x[2] = fmaf(cur.dr.z, Sseg[jt][2], x[2]);
+                    x[3] = fmaf(cur.dr.w, Sseg[jt][3], x[3]);
+                    t[jt] = pack4(x);
+                }
+            }
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) *reinterpret_cast<uint2 *>(&sm.sb[16 * jt + r][16 * w + 4 * g]) = t[jt];
         }
         __syncthreads();  // staged tiles visible
 
@@ -1054,7 +1061,14 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     ChunkRows next = fetch(nch - 1), after_next = fetch(nch - 2);
 
     for (int m = nch - 1; m >= 0; --m) {
-        const ChunkRows cur = next;
+        ChunkRows cur = next;
+        if (long(chunk0 + m + 1) * kC > L) {  // ragged final chunk of the sequence (uniform branch)
+            const long t0 = long(chunk0 + m) * kC;
+            zero_past_end(cur.k, t0, w, lane, L);
+            zero_past_end(cur.v, t0, w, lane, L);
+            zero_past_end(cur.gf, t0, w, lane, L);
+            zero_past_end(cur.gb, t0, w, lane, L);
+        }
         next = after_next;
         // the rows of chunk m-2 are requested a tile at a time between the phases of this step:
         // a burst of all of them would stall this wave at issue while the memory pipeline is full
