@@ -187,14 +187,14 @@ struct Row16 {
 
 // Every global row load is a fully contiguous wave load, 8 whole 128-byte rows per instruction:
 // lane i of wave w takes 16-byte piece i%8 of rows 16w + i/8 and 16w + 8 + i/8 of the chunk.
-// The loads are branch-free: an out-of-range token reads the last valid row, and the rows of a
-// ragged final chunk are zeroed when they are consumed (zero_past_end).  With no control flow
-// around the loads the compiler can count the outstanding ones exactly, so waiting for one
-// chunk's rows does not also wait for the prefetch issued after them.
+// An out-of-range token reads the last valid row and is zeroed, either right here (kZeroHere;
+// compiled as a skipped branch unless the chunk is ragged) or when the rows are consumed
+// (zero_past_end).  Which of the two a kernel uses was settled by timing it.
 struct StagedRows {
     uint4 p[2];
 };
 
+template <bool kZeroHere = false>
 __device__ __forceinline__ StagedRows load_rows_staged(const uint16_t *slab_base, long chunk_token0, int w, int lane,
                                                        int L)
 {
@@ -204,6 +204,7 @@ __device__ __forceinline__ StagedRows load_rows_staged(const uint16_t *slab_base
         const long tok = chunk_token0 + 16 * w + 8 * t + (lane >> 3);
         const long tc = tok < L ? tok : long(L) - 1;
         s.p[t] = *reinterpret_cast<const uint4 *>(slab_base + tc * kD + 8 * (lane & 7));
+        if (kZeroHere && tok >= L) s.p[t] = make_uint4(0, 0, 0, 0);
     }
     return s;
 }
@@ -1050,10 +1051,10 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     };
     auto fetch = [&](int m) {  // m may run one before the segment: clamped, the rows are then unused
         ChunkRows c;
-        c.k = load_rows_staged(k, long(chunk0 + max(m, 0)) * kC, w, lane, L);
-        c.v = load_rows_staged(v, long(chunk0 + max(m, 0)) * kC, w, lane, L);
-        c.gf = load_rows_staged(g_fwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
-        c.gb = load_rows_staged(g_bwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
+        c.k = load_rows_staged<true>(k, long(chunk0 + max(m, 0)) * kC, w, lane, L);
+        c.v = load_rows_staged<true>(v, long(chunk0 + max(m, 0)) * kC, w, lane, L);
+        c.gf = load_rows_staged<true>(g_fwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
+        c.gb = load_rows_staged<true>(g_bwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
         return c;
     };
     // two chunks of rows are kept in flight: at the bandwidth this kernel runs at, a load takes
@@ -1061,19 +1062,12 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     ChunkRows next = fetch(nch - 1), after_next = fetch(nch - 2);
 
     for (int m = nch - 1; m >= 0; --m) {
-        ChunkRows cur = next;
-        if (long(chunk0 + m + 1) * kC > L) {  // ragged final chunk of the sequence (uniform branch)
-            const long t0 = long(chunk0 + m) * kC;
-            zero_past_end(cur.k, t0, w, lane, L);
-            zero_past_end(cur.v, t0, w, lane, L);
-            zero_past_end(cur.gf, t0, w, lane, L);
-            zero_past_end(cur.gb, t0, w, lane, L);
-        }
+        const ChunkRows cur = next;
         next = after_next;
         // the rows of chunk m-2 are requested a tile at a time between the phases of this step:
         // a burst of all of them would stall this wave at issue while the memory pipeline is full
         const long far_token0 = long(chunk0 + max(m - 2, 0)) * kC;
-        after_next.k = load_rows_staged(k, far_token0, w, lane, L);
+        after_next.k = load_rows_staged<true>(k, far_token0, w, lane, L);
         // the scan's triangular operands are rebuilt every step (a few dozen selects) rather than
         // kept in 16 registers across the loop; the opaque copy keeps them from being hoisted
         bf16x8 tri_f[2], tri_b[2];
@@ -1109,7 +1103,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         float kf[16];
         unpack16(bounce_load(sm.ks[0], row, g), kf);
         __syncthreads();  // g, v visible
-        after_next.v = load_rows_staged(v, far_token0, w, lane, L);
+        after_next.v = load_rows_staged<true>(v, far_token0, w, lane, L);
 
         f32x4 Bf[4], Bb[4];
         float max_f, max_b;
@@ -1129,7 +1123,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         }
         const bool fast = fmaxf(max_f, max_b) <= kFastRange;  // uniform over the workgroup
         all_fast = all_fast && fast;
-        after_next.gf = load_rows_staged(g_fwd, far_token0, w, lane, L);
+        after_next.gf = load_rows_staged<true>(g_fwd, far_token0, w, lane, L);
         float4 df, db;  // this chunk's decay, rows at LDS positions 16w + 4g + e
         float tmp[16];
         if (fast) {
@@ -1193,7 +1187,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
             __syncthreads();  // ks visible
         }
 
-        after_next.gb = load_rows_staged(g_bwd, far_token0, w, lane, L);
+        after_next.gb = load_rows_staged<true>(g_bwd, far_token0, w, lane, L);
         // chunk contributions K^T V of both directions, rows at positions 16w + 4g + e
         f32x4 Cf[4], Cb[4];
 #pragma unroll
