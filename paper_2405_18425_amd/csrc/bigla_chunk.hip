@@ -851,7 +851,7 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
 // kFastOnly = false: handles the remaining segments (all of them when seg_mild is nullptr), each
 //                     chunk choosing its form.
 template <bool kFastOnly>
-__global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
+__global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out_kernel(
     const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
     const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
     const float *__restrict__ seg_states /* states entering each segment, nullptr when one segment */,
