@@ -862,17 +862,26 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
     __shared__ OutLds sm;
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
-    // A workgroup walks `units_per_block` consecutive (slab, segment) units and skips those of the
-    // other kernel.  The fast kernel takes one unit per workgroup; the general kernel, whose
-    // units are normally all skipped, takes several so that an idle launch drains quickly.
-    for (long unit = long(blockIdx.x) * units_per_block;
-         unit < min(long(blockIdx.x + 1) * units_per_block, total_units); ++unit) {
+    // A workgroup owns `units_per_block` (at most 64) consecutive (slab, segment) units and
+    // skips those of the other kernel.  The fast kernel takes one unit per workgroup; the
+    // general kernel, whose units are normally all skipped, takes several, and reads all their
+    // flags with one load per lane so that an idle launch drains after a single memory round trip.
+    const long first_unit = long(blockIdx.x) * units_per_block;
+    unsigned long long todo;
+    {
+        const long u = first_unit + lane;
+        bool mine = false;
+        if (lane < units_per_block && u < total_units) {
+            const bool mild = seg_mild != nullptr && seg_mild[u] != 0;
+            mine = mild == kFastOnly;
+        }
+        todo = __ballot(mine);  // the same in every wave of the workgroup
+    }
+    while (todo != 0) {
+    const long unit = first_unit + __builtin_ctzll(todo);
+    todo &= todo - 1;
     const long slab = unit / n_seg;
     const int seg = int(unit % n_seg);
-    {
-        const bool mild = seg_mild != nullptr && seg_mild[unit] != 0;  // uniform over the workgroup
-        if (mild != kFastOnly) continue;
-    }
     __syncthreads();  // LDS of a previous unit is no longer read
     const long base = slab * L * kD;
     const uint16_t *q = q_all + base, *k = k_all + base, *v = v_all + base;
@@ -1340,10 +1349,12 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
     }
     {  // every other segment; its workgroups leave at once where the launch above did the work
         LaunchTimer timer(kKernelSegmentOutGeneral, stream);
-        const int per_block = flags ? 8 : 1;
+        // about one workgroup per CU (this kernel runs one per CU), at most 64 units each
+        long per_block = flags ? (blocks + 255) / 256 : 1;
+        if (per_block > 64) per_block = 64;
         hipLaunchKernelGGL(bigla_segment_out_kernel<false>, dim3((unsigned)((blocks + per_block - 1) / per_block)),
                            dim3(kThreads), 0, stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks,
-                           p.seg_chunks, p.n_seg, blocks, per_block);
+                           p.seg_chunks, p.n_seg, blocks, int(per_block));
     }
     return hipGetLastError();
 }
