@@ -588,7 +588,7 @@ template <class Prefetch>
 __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)[kPitch], const ChunkOperands &op,
                                              const ChunkFlags fl, const bool fast_update, const int w, const int r,
                                              const int g, uint16_t *out_slab, const long chunk_token0, const int L,
-                                             f32x4 (&S)[4], Prefetch &&prefetch_last)
+                                             f32x4 (&S)[4], Prefetch &&prefetch)
 {
     const uint2(&pk)[4] = op.pk;
     bf16x8 vop[2][4];
@@ -596,6 +596,7 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
     for (int p = 0; p < 2; ++p)
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) vop[p][jt] = token_operand(sm.v, 2 * p, 2 * p + 1, 16 * jt, r, g);
+    prefetch(0);
 
     // token-per-lane accumulators: lane (r, g) gets columns 16*jt + 4g .. +3 of its own token
     f32x4 O[4];
@@ -606,9 +607,11 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(vop[1][jt], pa1, mfma(vop[0][jt], pa0, zero));
     }
+    prefetch(1);
     readout(sm.st, op.qf0, op.qf1, r, g, O);
+    prefetch(2);
     if (fl.stash || fl.seg) readout(sm.sb, op.qb0, op.qb1, r, g, O);
-    prefetch_last();
+    prefetch(3);
     {  // o_t = (o_fwd_t + o_bwd_t) / 2, turned into whole rows through the wave's own rows of the
        // forward gate tile (last read before the score tiles), then written 8 rows per store
         const int lane = 16 * g + r;
@@ -901,33 +904,33 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
         float4 dr;  // decay of the lane's state rows from the chunk's right edge to the segment's
         StagedRows q, k, gf, gb, v;
     };
-    // The rows of the next chunk are requested in three groups between the phases of a step (a
-    // burst of all twelve loads would stall the wave at issue while the memory pipeline is
+    // The rows of the next chunk are requested a tile at a time between the phases of a step (a
+    // burst of all thirteen loads would stall the wave at issue while the memory pipeline is
     // full).  m may run one past the segment: clamped, the rows are then unused.
     auto chunk_token0 = [&](int m) { return long(chunk0 + min(m, nch - 1)) * kC; };
-    auto fetch_qk = [&](ChunkRows &c, int m) {
-        c.q = load_rows_staged(q, chunk_token0(m), w, lane, L);
-        c.k = load_rows_staged(k, chunk_token0(m), w, lane, L);
-    };
-    auto fetch_gates = [&](ChunkRows &c, int m) {
-        c.gf = load_rows_staged(g_fwd, chunk_token0(m), w, lane, L);
-        c.gb = load_rows_staged(g_bwd, chunk_token0(m), w, lane, L);
-    };
-    auto fetch_v_stash = [&](ChunkRows &c, int m) {
-        c.v = load_rows_staged(v, chunk_token0(m), w, lane, L);
+    auto fetch_stash = [&](ChunkRows &c, int m) {
         // this lane's 16 values of the chunk's stashed state (unwritten, and unused, for the
-        // segment's last chunk)
-        const uint4 *p =
-            reinterpret_cast<const uint4 *>(stash + size_t(chunk0 + min(m, nch - 1)) * kStashBytes) + tid;
+        // segment's last chunk) and the decay of its rows
+        const unsigned char *base = stash + size_t(chunk0 + min(m, nch - 1)) * kStashBytes;
+        const uint4 *p = reinterpret_cast<const uint4 *>(base) + tid;
         c.sb.p[0] = p[0];
         c.sb.p[1] = p[kThreads];
-        c.dr = *reinterpret_cast<const float4 *>(reinterpret_cast<const unsigned char *>(p - tid) +
-                                                 size_t(kD) * kD * sizeof(uint16_t) + (16 * w + 4 * g) * sizeof(float));
+        c.dr = *reinterpret_cast<const float4 *>(base + size_t(kD) * kD * sizeof(uint16_t) +
+                                                 (16 * w + 4 * g) * sizeof(float));
+    };
+    // part 0..5: q, k, g_fwd, g_bwd, v, stash
+    auto fetch_part = [&](ChunkRows &c, int m, int part) {
+        const long t0 = chunk_token0(m);
+        if (part == 0) c.q = load_rows_staged(q, t0, w, lane, L);
+        if (part == 1) c.k = load_rows_staged(k, t0, w, lane, L);
+        if (part == 2) c.gf = load_rows_staged(g_fwd, t0, w, lane, L);
+        if (part == 3) c.gb = load_rows_staged(g_bwd, t0, w, lane, L);
+        if (part == 4) c.v = load_rows_staged(v, t0, w, lane, L);
+        if (part == 5) fetch_stash(c, m);
     };
     ChunkRows next;
-    fetch_qk(next, 0);
-    fetch_gates(next, 0);
-    fetch_v_stash(next, 0);
+#pragma unroll
+    for (int part = 0; part < 6; ++part) fetch_part(next, 0, part);
 
     f32x4 S[4];
     load_state(st_in, st_in == nullptr, tid, S);
@@ -991,12 +994,20 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
         f32x4 Bf[4], Tf[4], Bb[4];
         ChunkOperands op;
         bool fast = true;
-        // (the general kernel, short of registers, requests everything at the middle point)
+        // fast kernel: q and k after the barrier of the first half, both gates after the score
+        // tiles, v and the stash after the readouts (finer splits measured slower); the general
+        // kernel requests everything between the halves
         auto prefetch_first = [&]() {
-            if (kFastOnly) fetch_qk(next, m + 1);
+            if (kFastOnly) {
+                fetch_part(next, m + 1, 0);
+                fetch_part(next, m + 1, 1);
+            }
         };
-        auto prefetch_last = [&]() {
-            if (kFastOnly) fetch_v_stash(next, m + 1);
+        auto prefetch_second_half = [&](int point) {
+            if (kFastOnly && point == 3) {
+                fetch_part(next, m + 1, 4);
+                fetch_part(next, m + 1, 5);
+            }
         };
         chunk_gate_scan(sm.gf, tri_f, r, g, Bf, Tf);
         if (kFastOnly) {
@@ -1012,10 +1023,15 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
             else
                 out_chunk_safe(sm, w, r, g, q_row, k_row, fl, op, prefetch_first);
         }
-        if (!kFastOnly) fetch_qk(next, m + 1);
-        fetch_gates(next, m + 1);
-        if (!kFastOnly) fetch_v_stash(next, m + 1);
-        finish_chunk(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L, S, prefetch_last);
+        if (kFastOnly) {
+            fetch_part(next, m + 1, 2);
+            fetch_part(next, m + 1, 3);
+        } else {
+#pragma unroll
+            for (int part = 0; part < 6; ++part) fetch_part(next, m + 1, part);
+        }
+        finish_chunk(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L, S,
+                     prefetch_second_half);
     }
     }  // units
 }
@@ -1066,26 +1082,17 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         c.gb = load_rows_staged<true>(g_bwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
         return c;
     };
-    // two chunks of rows are kept in flight: at the bandwidth this kernel runs at, a load takes
-    // about as long as one chunk step
-    ChunkRows next = fetch(nch - 1), after_next = fetch(nch - 2);
+    ChunkRows next = fetch(nch - 1);
+    bf16x8 tri_f[2], tri_b[2];
+    scan_triangle<0>(w, r, g, tri_f);
+    scan_triangle<1>(w, r, g, tri_b);
 
     for (int m = nch - 1; m >= 0; --m) {
         const ChunkRows cur = next;
-        next = after_next;
-        // the rows of chunk m-2 are requested a tile at a time between the phases of this step:
+        // the rows of chunk m-1 are requested a tile at a time between the phases of this step:
         // a burst of all of them would stall this wave at issue while the memory pipeline is full
-        const long far_token0 = long(chunk0 + max(m - 2, 0)) * kC;
-        after_next.k = load_rows_staged<true>(k, far_token0, w, lane, L);
-        // the scan's triangular operands are rebuilt every step (a few dozen selects) rather than
-        // kept in 16 registers across the loop; the opaque copy keeps them from being hoisted
-        bf16x8 tri_f[2], tri_b[2];
-        {
-            int rr = r;
-            asm volatile("" : "+v"(rr));
-            scan_triangle<0>(w, rr, g, tri_f);
-            scan_triangle<1>(w, rr, g, tri_b);
-        }
+        const long far_token0 = long(chunk0 + max(m - 1, 0)) * kC;
+        next.k = load_rows_staged<true>(k, far_token0, w, lane, L);
 
         // stash for chunk m: the backward state entering it from the right (zero, and not
         // stored, for the segment's last chunk) and the decay from its right edge to the
@@ -1112,7 +1119,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         float kf[16];
         unpack16(bounce_load(sm.ks[0], row, g), kf);
         __syncthreads();  // g, v visible
-        after_next.v = load_rows_staged<true>(v, far_token0, w, lane, L);
+        next.v = load_rows_staged<true>(v, far_token0, w, lane, L);
 
         f32x4 Bf[4], Bb[4];
         float max_f, max_b;
@@ -1132,7 +1139,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         }
         const bool fast = fmaxf(max_f, max_b) <= kFastRange;  // uniform over the workgroup
         all_fast = all_fast && fast;
-        after_next.gf = load_rows_staged<true>(g_fwd, far_token0, w, lane, L);
+        next.gf = load_rows_staged<true>(g_fwd, far_token0, w, lane, L);
         float4 df, db;  // this chunk's decay, rows at LDS positions 16w + 4g + e
         float tmp[16];
         if (fast) {
@@ -1196,7 +1203,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
             __syncthreads();  // ks visible
         }
 
-        after_next.gb = load_rows_staged<true>(g_bwd, far_token0, w, lane, L);
+        next.gb = load_rows_staged<true>(g_bwd, far_token0, w, lane, L);
         // chunk contributions K^T V of both directions, rows at positions 16w + 4g + e
         f32x4 Cf[4], Cb[4];
 #pragma unroll
