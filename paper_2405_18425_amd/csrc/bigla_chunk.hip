@@ -664,6 +664,39 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
     publish_state(sm.st, w, r, g, S);
 }
 
+// Merged score tiles of the fast form and the readout queries, from this lane's scaled operands
+// and the key tiles in LDS.
+__device__ __forceinline__ void score_tiles(OutLds &sm, const int w, const int r, const int g, const bf16x8 qf0,
+                                            const bf16x8 qf1, const bf16x8 qb0, const bf16x8 qb1, const bf16x8 kf0,
+                                            const bf16x8 kf1, const bf16x8 kb0, const bf16x8 kb1, ChunkOperands &op)
+{
+    // merged score tile, transposed: P^T[i][t]; key sub-block I < w forward, I > w backward,
+    // I = w the masked sum of both (own token counted by both directions)
+#pragma unroll
+    for (int I = 0; I < 4; ++I) {
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        if (I == w) {
+            f32x4 pf = mfma(kf1, qf1, mfma(kf0, qf0, zero));
+            f32x4 pb = mfma(kb1, qb1, mfma(kb0, qb0, zero));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = 4 * g + e;
+                pf[e] = (i <= r ? pf[e] : 0.f) + (i >= r ? pb[e] : 0.f);
+            }
+            op.pk[I] = pack4(pf);
+        } else if (I < w) {
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kf[16 * I + r][8 * g]);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kf[16 * I + r][32 + 8 * g]);
+            op.pk[I] = pack4(mfma(a1, qf1, mfma(a0, qf0, zero)));
+        } else {
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][8 * g]);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][32 + 8 * g]);
+            op.pk[I] = pack4(mfma(a1, qb1, mfma(a0, qb0, zero)));
+        }
+    }
+    op.qf0 = qf0; op.qf1 = qf1; op.qb0 = qb0; op.qb1 = qb1;
+}
+
 // FAST form of one chunk, both directions (see the header).  Bf / Bb are the lane's cumulative
 // log-gates of the two directions, Tf the forward chunk totals.
 template <class Prefetch>
@@ -699,31 +732,53 @@ __device__ __forceinline__ void out_chunk_fast(OutLds &sm, const int w, const in
     __syncthreads();  // kf, kb, tot visible
     prefetch_first();
 
-    // merged score tile, transposed: P^T[i][t]; key sub-block I < w forward, I > w backward,
-    // I = w the masked sum of both (own token counted by both directions)
+    score_tiles(sm, w, r, g, qf0, qf1, qb0, qb1, kf0, kf1, kb0, kb1, op);
+}
+
+// FAST form with the gate scans folded in, for the kernel that runs nothing else: per 16-channel
+// tile the two directions' cumulative gates come off the matrix cores and are consumed by the
+// exponentials and scalings of that tile's four slots right away, so that the vector ALU work
+// of one tile can overlap the LDS reads and MFMAs of the next (one basic block, no branch
+// between the scan and its use).  The forward chunk totals are the cumulative gates of the
+// chunk's last token (wave 3, r = 15).
+template <class Prefetch>
+__device__ __forceinline__ void out_chunk_fast_fused(OutLds &sm, const bf16x8 (&tri_f)[2], const bf16x8 (&tri_b)[2],
+                                                     const int w, const int r, const int g, const Row16 &qraw,
+                                                     const Row16 &kraw, ChunkOperands &op, Prefetch &&prefetch_first)
+{
+    const int row = 16 * w + r;
+    float qf[16], kf[16], qb[16], kb[16], tot[16];
+    unpack16(qraw, qf);
+    unpack16(kraw, kf);
 #pragma unroll
-    for (int I = 0; I < 4; ++I) {
+    for (int ct = 0; ct < 4; ++ct) {
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-        if (I == w) {
-            f32x4 pf = mfma(kf1, qf1, mfma(kf0, qf0, zero));
-            f32x4 pb = mfma(kb1, qb1, mfma(kb0, qb0, zero));
+        const bf16x8 f0 = token_operand(sm.gf, 0, 1, 16 * ct, r, g), f1 = token_operand(sm.gf, 2, 3, 16 * ct, r, g);
+        const bf16x8 b0 = token_operand(sm.gb, 0, 1, 16 * ct, r, g), b1 = token_operand(sm.gb, 2, 3, 16 * ct, r, g);
+        const f32x4 Bf = mfma(f1, tri_f[1], mfma(f0, tri_f[0], zero));
+        const f32x4 Bb = mfma(b1, tri_b[1], mfma(b0, tri_b[0], zero));
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int i = 4 * g + e;
-                pf[e] = (i <= r ? pf[e] : 0.f) + (i >= r ? pb[e] : 0.f);
-            }
-            op.pk[I] = pack4(pf);
-        } else if (I < w) {
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kf[16 * I + r][8 * g]);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kf[16 * I + r][32 + 8 * g]);
-            op.pk[I] = pack4(mfma(a1, qf1, mfma(a0, qf0, zero)));
-        } else {
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][8 * g]);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][32 + 8 * g]);
-            op.pk[I] = pack4(mfma(a1, qb1, mfma(a0, qb0, zero)));
+        for (int e = 0; e < 4; ++e) {
+            const int n = 4 * ct + e;
+            const float xf = Bf[e] * kLog2e, xb = Bb[e] * kLog2e;
+            tot[n] = Bf[e];
+            qb[n] = qf[n] * fast_exp2(xb);   // q * exp(c_t)    backward
+            kb[n] = kf[n] * fast_exp2(-xb);  // k * exp(-c_i)
+            qf[n] *= fast_exp2(xf);          // q * exp(b_t)    forward
+            kf[n] *= fast_exp2(-xf);         // k * exp(-b_i)
         }
     }
-    op.qf0 = qf0; op.qf1 = qf1; op.qb0 = qb0; op.qb1 = qb1;
+    const bf16x8 qf0 = pack8(qf), qf1 = pack8(qf + 8), qb0 = pack8(qb), qb1 = pack8(qb + 8);
+    const bf16x8 kf0 = pack8(kf), kf1 = pack8(kf + 8), kb0 = pack8(kb), kb1 = pack8(kb + 8);
+    *reinterpret_cast<bf16x8 *>(&sm.kf[row][8 * g]) = kf0;
+    *reinterpret_cast<bf16x8 *>(&sm.kf[row][32 + 8 * g]) = kf1;
+    *reinterpret_cast<bf16x8 *>(&sm.kb[row][8 * g]) = kb0;
+    *reinterpret_cast<bf16x8 *>(&sm.kb[row][32 + 8 * g]) = kb1;
+    if (w == 3 && r == 15) store_chan16(sm.tot, g, tot);  // for the state decay
+
+    __syncthreads();  // kf, kb, tot visible
+    prefetch_first();
+    score_tiles(sm, w, r, g, qf0, qf1, qb0, qb1, kf0, kf1, kb0, kb1, op);
 }
 
 // RANGE-SAFE form of one chunk, both directions (see the header); scans the sub-block-local,
@@ -1009,12 +1064,11 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
                 fetch_part(next, m + 1, 5);
             }
         };
-        chunk_gate_scan(sm.gf, tri_f, r, g, Bf, Tf);
         if (kFastOnly) {
-            chunk_gate_scan(sm.gb, tri_b, r, g, Bb);
-            out_chunk_fast(sm, w, r, g, Bf, Bb, Tf, q_row, k_row, fl, op, prefetch_first);
+            out_chunk_fast_fused(sm, tri_f, tri_b, w, r, g, q_row, k_row, op, prefetch_first);
         } else {
             f32x4 Tb[4];
+            chunk_gate_scan(sm.gf, tri_f, r, g, Bf, Tf);
             chunk_gate_scan(sm.gb, tri_b, r, g, Bb, Tb);
             // same totals in every wave: the choice is uniform over the workgroup
             fast = fmaxf(chunk_decay_max(Tf), chunk_decay_max(Tb)) <= kFastRange;
