@@ -64,8 +64,9 @@ size_t bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype);
  *   workspace / workspace_bytes: device scratch of at least bigla_workspace_bytes(...);
  *   may be NULL/0 when that function returns 0.
  *
- * Numerics: VIG_BF16 with dk = dv = 64 runs the chunkwise MFMA path (bf16 operands, fp32
- * accumulation, fp32 carried state).  A 64-token chunk in which some channel decays by more
+ * Numerics: VIG_BF16 with dv = 64 and dk = 64 or 32 runs the chunkwise MFMA path (bf16 operands,
+ * fp32 accumulation, fp32 carried state; dk = 32 is widened to 64 key channels with zeros
+ * inside the kernels).  A 64-token chunk in which some channel decays by more
  * than 60 nats is evaluated in a range-safe form that treats per-step log gates below -8 as
  * -8 (alpha < 3.4e-4 acts as a hard reset either way; the difference is far below the bf16
  * tolerance).  Every other case runs the exact recurrence in fp32 arithmetic.

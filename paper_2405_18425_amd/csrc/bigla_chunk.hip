@@ -194,17 +194,25 @@ struct StagedRows {
     uint4 p[2];
 };
 
-template <bool kZeroHere = false>
+//
+// kRow is the tensor's row length in elements.  Rows of 32 (keys, queries and gates of a 32-wide
+// head) are widened to the kernels' 64 channels with zeros: channels 32..63 then carry q = k = 0
+// and log-gate 0 through every later step, which leaves the result unchanged.  The lanes of the
+// zero half repeat the addresses of the other half, so the instruction still touches whole rows.
+template <bool kZeroHere = false, int kRow = kD>
 __device__ __forceinline__ StagedRows load_rows_staged(const uint16_t *slab_base, long chunk_token0, int w, int lane,
                                                        int L)
 {
+    static_assert(kRow == kD || kRow == kD / 2, "row length");
+    constexpr int kPieces = kRow / 8;
     StagedRows s;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         const long tok = chunk_token0 + 16 * w + 8 * t + (lane >> 3);
         const long tc = tok < L ? tok : long(L) - 1;
-        s.p[t] = *reinterpret_cast<const uint4 *>(slab_base + tc * kD + 8 * (lane & 7));
+        s.p[t] = *reinterpret_cast<const uint4 *>(slab_base + tc * kRow + 8 * ((lane & 7) % kPieces));
         if (kZeroHere && tok >= L) s.p[t] = make_uint4(0, 0, 0, 0);
+        if (kRow < kD && (lane & 7) >= kPieces) s.p[t] = make_uint4(0, 0, 0, 0);
     }
     return s;
 }
@@ -908,7 +916,7 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
 //                     footprint would otherwise spill into the fast path); other segments exit.
 // kFastOnly = false: handles the remaining segments (all of them when seg_mild is nullptr), each
 //                     chunk choosing its form.
-template <bool kFastOnly>
+template <bool kFastOnly, int kDk>
 __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out_kernel(
     const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
     const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
@@ -941,9 +949,9 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
     const long slab = unit / n_seg;
     const int seg = int(unit % n_seg);
     __syncthreads();  // LDS of a previous unit is no longer read
-    const long base = slab * L * kD;
-    const uint16_t *q = q_all + base, *k = k_all + base, *v = v_all + base;
-    const uint16_t *g_fwd = gf_all + base, *g_bwd = gb_all + base;
+    const long base = slab * L * kD, key_base = slab * L * kDk;
+    const uint16_t *q = q_all + key_base, *k = k_all + key_base, *v = v_all + base;
+    const uint16_t *g_fwd = gf_all + key_base, *g_bwd = gb_all + key_base;
     uint16_t *out = out_all + base;
     const unsigned char *stash = stash_all + size_t(slab) * n_chunks * kStashBytes;
 
@@ -976,10 +984,10 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
     // part 0..5: q, k, g_fwd, g_bwd, v, stash
     auto fetch_part = [&](ChunkRows &c, int m, int part) {
         const long t0 = chunk_token0(m);
-        if (part == 0) c.q = load_rows_staged(q, t0, w, lane, L);
-        if (part == 1) c.k = load_rows_staged(k, t0, w, lane, L);
-        if (part == 2) c.gf = load_rows_staged(g_fwd, t0, w, lane, L);
-        if (part == 3) c.gb = load_rows_staged(g_bwd, t0, w, lane, L);
+        if (part == 0) c.q = load_rows_staged<false, kDk>(q, t0, w, lane, L);
+        if (part == 1) c.k = load_rows_staged<false, kDk>(k, t0, w, lane, L);
+        if (part == 2) c.gf = load_rows_staged<false, kDk>(g_fwd, t0, w, lane, L);
+        if (part == 3) c.gb = load_rows_staged<false, kDk>(g_bwd, t0, w, lane, L);
         if (part == 4) c.v = load_rows_staged(v, t0, w, lane, L);
         if (part == 5) fetch_stash(c, m);
     };
@@ -1092,6 +1100,7 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
 
 // ---- kernel 1: per-segment end states and per-chunk backward stash -----------------------------
 
+template <int kDk>
 __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, const uint16_t *__restrict__ g_fwd,
     const uint16_t *__restrict__ g_bwd, float *__restrict__ seg_states, int *__restrict__ seg_mild,
@@ -1102,8 +1111,8 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
     const long slab = blockIdx.x / n_seg;
     const int seg = blockIdx.x % n_seg;
-    const long base = slab * L * kD;
-    k += base; v += base; g_fwd += base; g_bwd += base;
+    const long base = slab * L * kD, key_base = slab * L * kDk;
+    k += key_base; v += base; g_fwd += key_base; g_bwd += key_base;
     float *dst = seg_states + (slab * n_seg + seg) * kSegFloats;
     stash += size_t(slab) * n_chunks * kStashBytes;
 
@@ -1130,10 +1139,10 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     };
     auto fetch = [&](int m) {  // m may run one before the segment: clamped, the rows are then unused
         ChunkRows c;
-        c.k = load_rows_staged<true>(k, long(chunk0 + max(m, 0)) * kC, w, lane, L);
+        c.k = load_rows_staged<true, kDk>(k, long(chunk0 + max(m, 0)) * kC, w, lane, L);
         c.v = load_rows_staged<true>(v, long(chunk0 + max(m, 0)) * kC, w, lane, L);
-        c.gf = load_rows_staged<true>(g_fwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
-        c.gb = load_rows_staged<true>(g_bwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
+        c.gf = load_rows_staged<true, kDk>(g_fwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
+        c.gb = load_rows_staged<true, kDk>(g_bwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
         return c;
     };
     ChunkRows next = fetch(nch - 1);
@@ -1146,7 +1155,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         // the rows of chunk m-1 are requested a tile at a time between the phases of this step:
         // a burst of all of them would stall this wave at issue while the memory pipeline is full
         const long far_token0 = long(chunk0 + max(m - 1, 0)) * kC;
-        next.k = load_rows_staged<true>(k, far_token0, w, lane, L);
+        next.k = load_rows_staged<true, kDk>(k, far_token0, w, lane, L);
 
         // stash for chunk m: the backward state entering it from the right (zero, and not
         // stored, for the segment's last chunk) and the decay from its right edge to the
@@ -1193,7 +1202,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         }
         const bool fast = fmaxf(max_f, max_b) <= kFastRange;  // uniform over the workgroup
         all_fast = all_fast && fast;
-        next.gf = load_rows_staged<true>(g_fwd, far_token0, w, lane, L);
+        next.gf = load_rows_staged<true, kDk>(g_fwd, far_token0, w, lane, L);
         float4 df, db;  // this chunk's decay, rows at LDS positions 16w + 4g + e
         float tmp[16];
         if (fast) {
@@ -1257,7 +1266,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
             __syncthreads();  // ks visible
         }
 
-        next.gb = load_rows_staged<true>(g_bwd, far_token0, w, lane, L);
+        next.gb = load_rows_staged<true, kDk>(g_bwd, far_token0, w, lane, L);
         // chunk contributions K^T V of both directions, rows at positions 16w + 4g + e
         f32x4 Cf[4], Cb[4];
 #pragma unroll
@@ -1354,7 +1363,7 @@ __global__ __launch_bounds__(kThreads) void bigla_state_scan_kernel(float *__res
 
 }  // namespace
 
-bool bigla_chunk_supported(int dk, int dv, bool is_bf16) { return is_bf16 && dk == kD && dv == kD; }
+bool bigla_chunk_supported(int dk, int dv, bool is_bf16) { return is_bf16 && dv == kD && (dk == kD || dk == kD / 2); }
 
 namespace {
 size_t seg_region_bytes(long BH, const Plan &p) { return size_t(BH) * p.n_seg * kSegFloats * sizeof(float); }
@@ -1367,8 +1376,10 @@ size_t bigla_chunk_workspace_bytes(long BH, int L)
     return seg_region_bytes(BH, p) + flag_region_bytes(BH, p) + size_t(BH) * p.n_chunks * kStashBytes;
 }
 
-hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
-                              void *out, long BH, int L, void *workspace, hipStream_t stream)
+namespace {
+template <int kDk>
+hipError_t chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd, void *out,
+                        long BH, int L, void *workspace, hipStream_t stream)
 {
     const Plan p = make_plan(BH, L);
     const long blocks = BH * p.n_seg;
@@ -1383,7 +1394,7 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
     if (p.n_chunks > 1) {  // a single chunk has neither a stash nor entering states
         {
             LaunchTimer timer(kKernelSegmentState, stream);
-            hipLaunchKernelGGL(bigla_segment_state_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, kk, vv,
+            hipLaunchKernelGGL(bigla_segment_state_kernel<kDk>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, kk, vv,
                                gf, gb, seg_states, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg);
         }
         e = hipGetLastError();
@@ -1403,7 +1414,7 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
     uint16_t *oo = static_cast<uint16_t *>(out);
     if (flags) {  // segments the state kernel flagged as entirely within the fast form's range
         LaunchTimer timer(kKernelSegmentOut, stream);
-        hipLaunchKernelGGL(bigla_segment_out_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk, vv,
+        hipLaunchKernelGGL((bigla_segment_out_kernel<true, kDk>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk, vv,
                            gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, blocks, 1);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -1413,11 +1424,20 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
         // about one workgroup per CU (this kernel runs one per CU), at most 64 units each
         long per_block = flags ? (blocks + 255) / 256 : 1;
         if (per_block > 64) per_block = 64;
-        hipLaunchKernelGGL(bigla_segment_out_kernel<false>, dim3((unsigned)((blocks + per_block - 1) / per_block)),
+        hipLaunchKernelGGL((bigla_segment_out_kernel<false, kDk>), dim3((unsigned)((blocks + per_block - 1) / per_block)),
                            dim3(kThreads), 0, stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks,
                            p.seg_chunks, p.n_seg, blocks, int(per_block));
     }
     return hipGetLastError();
+}
+}  // namespace
+
+hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                              void *out, long BH, int L, int dk, void *workspace, hipStream_t stream)
+{
+    if (dk == kD) return chunk_launch<kD>(q, k, v, g_fwd, g_bwd, out, BH, L, workspace, stream);
+    if (dk == kD / 2) return chunk_launch<kD / 2>(q, k, v, g_fwd, g_bwd, out, BH, L, workspace, stream);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace vig

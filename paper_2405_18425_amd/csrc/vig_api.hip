@@ -66,7 +66,7 @@ int bigla_fwd(const void *q, const void *k, const void *v, const void *g_fwd, co
     const long BH = long(B) * H;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (vig::bigla_chunk_supported(dk, dv, bf16))
-        return hip_status(vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, workspace, s));
+        return hip_status(vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, workspace, s));
     return hip_status(vig::bigla_recurrent_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, dv, bf16, workspace, s));
 }
 

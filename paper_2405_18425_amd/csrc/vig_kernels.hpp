@@ -12,11 +12,11 @@ hipError_t bigla_recurrent_launch(const void *q, const void *k, const void *v, c
                                   const void *g_bwd, void *out, long BH, int L, int dk, int dv, bool is_bf16,
                                   void *workspace, hipStream_t stream);
 
-// ---- chunkwise bf16 MFMA path (dk = dv = 64) -------------------------------------------------
+// ---- chunkwise bf16 MFMA path (dv = 64, dk = 64 or 32) ----------------------------------------
 bool bigla_chunk_supported(int dk, int dv, bool is_bf16);
 size_t bigla_chunk_workspace_bytes(long BH, int L);
 hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
-                              void *out, long BH, int L, void *workspace, hipStream_t stream);
+                              void *out, long BH, int L, int dk, void *workspace, hipStream_t stream);
 
 // ---- depthwise 3x3 conv + sigmoid-gated blend -------------------------------------------------
 hipError_t locality_gate_launch(const void *x, const void *w, const void *bias, const void *gate_logits,

@@ -47,6 +47,18 @@ def test_bigla_full_size_sampled_slabs(cfg):
     _say(f"  max|err|/max|ref| = {rel:.3e}")
 
 
+@pytest.mark.parametrize("B,H,grid,mu", [(2, 6, 64, -2.0), (3, 6, 14, 0.0), (2, 12, 32, 2.0)])
+def test_bigla_head_shape_32_64(B, H, grid, mu):
+    """The head shape the paper's parameter count implies (keys and queries half as wide as the
+    values: dk = 32, dv = 64), at the sequence lengths and gate statistics of the benchmark
+    configurations; runs the chunkwise MFMA kernels."""
+    w = wl.Workload(f"head32_{grid}", B=B, H=H, Hg=grid, Wg=grid, dk=32, dv=64, dtype="bf16", gate_mu=mu)
+    _say(f"bigla {w}")
+    s = wl.generate(w, seed=3, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+    rel = assert_close(run_bigla_gpu(s, "bf16"), run_bigla_oracle(s, "bf16"), TOL["bf16"], w.name)
+    _say(f"  max|err|/max|ref| = {rel:.3e}")
+
+
 EDGE_L = (1, 2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 196, 255, 256, 257, 300, 513, 1000)
 
 
@@ -60,12 +72,12 @@ def test_bigla_ragged_lengths(dtype, dk, dv):
         assert_close(run_bigla_gpu(s, dtype), run_bigla_oracle(s, dtype), TOL[dtype], f"L={L}")
 
 
-@pytest.mark.parametrize("dtype", ("bf16", "f32"))
+@pytest.mark.parametrize("dtype,dk", (("bf16", 64), ("f32", 64), ("bf16", 32)))
 @pytest.mark.parametrize("gate", ("zero", "minus4", "minus40", "mixed_spikes", "tiny"))
-def test_bigla_adversarial_gates(dtype, gate):
+def test_bigla_adversarial_gates(dtype, dk, gate):
     """Degenerate gates: alpha = 1 everywhere, very fast decay, isolated hard resets, near-one."""
-    w = wl.Workload("adv", B=2, H=2, Hg=1, Wg=333, dk=64, dv=64, dtype=dtype, gate_mu=0.0)
-    _say(f"bigla adversarial {dtype} {gate}")
+    w = wl.Workload("adv", B=2, H=2, Hg=1, Wg=333, dk=dk, dv=64, dtype=dtype, gate_mu=0.0)
+    _say(f"bigla adversarial {dtype} dk{dk} {gate}")
     s = wl.generate(w, seed=11, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
     shape = (w.B, w.H, w.L, w.dk)
     if gate == "zero":
@@ -85,12 +97,12 @@ def test_bigla_adversarial_gates(dtype, gate):
     assert_close(run_bigla_gpu(s, dtype), run_bigla_oracle(s, dtype), TOL[dtype], gate)
 
 
-@pytest.mark.parametrize("B,H,L", [(2, 3, 1000), (24, 4, 1500), (3, 2, 4096)])
-def test_bigla_mixed_forms_in_one_call(B, H, L):
+@pytest.mark.parametrize("B,H,L,dk", [(2, 3, 1000, 64), (24, 4, 1500, 64), (3, 2, 4096, 64), (5, 3, 1500, 32)])
+def test_bigla_mixed_forms_in_one_call(B, H, L, dk):
     """Only a few stretches of the sequence decay too fast for the fast form: fast-form and
     range-safe segments (and chunks) meet in one call, for several segment lengths."""
-    w = wl.Workload("mixed", B=B, H=H, Hg=1, Wg=L, dk=64, dv=64, dtype="bf16", gate_mu=-1.0)
-    _say(f"bigla mixed forms B{B} H{H} L{L}")
+    w = wl.Workload("mixed", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=64, dtype="bf16", gate_mu=-1.0)
+    _say(f"bigla mixed forms B{B} H{H} L{L} dk{dk}")
     s = wl.generate(w, seed=17, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
     gf = wl.widen(s["g_fwd"], "bf16")
     gb = wl.widen(s["g_bwd"], "bf16")
@@ -177,3 +189,36 @@ def test_path_end_to_end_config0():
     ref_og = oracle.bigla(wd["q"], wd["k"], wd["v"], wd["g_fwd"], wd["g_bwd"])
     ref = oracle.locality_gate(wd["v"], wd["conv_w"], wd["gate_logits"], ref_og, w.Hg, w.Wg)
     assert_close(wl.widen(wl.from_torch(out, w.dtype), w.dtype), ref, TOL[w.dtype], "end to end")
+
+
+@pytest.mark.parametrize("grid,H", [(56, 2), (28, 4), (14, 8), (7, 16)])
+def test_path_end_to_end_hierarchical_stage_shapes(grid, H):
+    """The chained path on the sequence lengths of a four-stage hierarchical variant (Table of
+    architectures: 56x56, 28x28, 14x14 and 7x7 token grids, more heads at the coarser stages),
+    bf16, head size 64."""
+    import torch
+    from paper_2405_18425_amd import binding as vb
+    import oracle
+
+    w = wl.Workload(f"stage_{grid}", B=2, H=H, Hg=grid, Wg=grid, dk=64, dv=64, dtype="bf16", gate_mu=0.0)
+    _say(f"end to end {w}")
+    s = wl.generate(w, seed=grid)
+    t = {n: wl.to_torch(a, w.dtype, "cuda:0") for n, a in s.items()}
+    og = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"])
+    out = vb.locality_gate_fwd(t["v"], t["conv_w"], t["gate_logits"], og, w.Hg, w.Wg)
+    torch.cuda.synchronize()
+    wd = {n: wl.widen(a, w.dtype) for n, a in s.items()}
+    ref_og = oracle.bigla(wd["q"], wd["k"], wd["v"], wd["g_fwd"], wd["g_bwd"])
+    ref = oracle.locality_gate(wd["v"], wd["conv_w"], wd["gate_logits"], ref_og, w.Hg, w.Wg)
+    og64 = wl.widen(wl.from_torch(og, w.dtype), w.dtype)
+    out64 = wl.widen(wl.from_torch(out, w.dtype), w.dtype)
+    assert_close(og64, ref_og, TOL[w.dtype], "bigla")
+    # second stage on the intermediate the GPU actually produced: its own error only
+    ref_stage2 = oracle.locality_gate(wd["v"], wd["conv_w"], wd["gate_logits"], og64, w.Hg, w.Wg)
+    assert_close(out64, ref_stage2, 8e-3, "locality on the GPU's o_global")
+    # whole chain against the oracle's chain: the first stage's error (bounded relative to the
+    # scale of o_global, which can exceed that of the blended output) passes through (1 - G) <= 1
+    tol = TOL[w.dtype]
+    rms = lambda a: np.sqrt(np.mean(a ** 2, axis=(2, 3), keepdims=True))
+    bound = tol * (np.abs(ref) + rms(ref) + np.abs(ref_og) + rms(ref_og))
+    assert np.all(np.abs(out64 - ref) <= bound), float(np.max(np.abs(out64 - ref) - bound))
