@@ -198,7 +198,8 @@ struct StagedRows {
 // kRow is the tensor's row length in elements.  Rows of 32 (keys, queries and gates of a 32-wide
 // head) are widened to the kernels' 64 channels with zeros: channels 32..63 then carry q = k = 0
 // and log-gate 0 through every later step, which leaves the result unchanged.  The lanes of the
-// zero half repeat the addresses of the other half, so the instruction still touches whole rows.
+// zero half repeat the addresses of the other half (the instruction still touches whole rows)
+// and are cleared by zero_widened_half when the rows are consumed.
 template <bool kZeroHere = false, int kRow = kD>
 __device__ __forceinline__ StagedRows load_rows_staged(const uint16_t *slab_base, long chunk_token0, int w, int lane,
                                                        int L)
@@ -212,9 +213,16 @@ __device__ __forceinline__ StagedRows load_rows_staged(const uint16_t *slab_base
         const long tc = tok < L ? tok : long(L) - 1;
         s.p[t] = *reinterpret_cast<const uint4 *>(slab_base + tc * kRow + 8 * ((lane & 7) % kPieces));
         if (kZeroHere && tok >= L) s.p[t] = make_uint4(0, 0, 0, 0);
-        if (kRow < kD && (lane & 7) >= kPieces) s.p[t] = make_uint4(0, 0, 0, 0);
     }
     return s;
+}
+
+// The zero half of a widened 32-wide row, applied when the rows are consumed (a select right
+// after the load would make the wave wait for it at once).
+template <int kRow>
+__device__ __forceinline__ void zero_widened_half(StagedRows &s, int lane)
+{
+    if (kRow < kD && (lane & 7) >= kRow / 8) s.p[0] = s.p[1] = make_uint4(0, 0, 0, 0);
 }
 
 // Zero the rows of tokens >= L (k = v = 0 and log-gate 0 make such a token a no-op).
@@ -1016,6 +1024,10 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
             zero_past_end(cur.gb, t0, w, lane, L);
             zero_past_end(cur.v, t0, w, lane, L);
         }
+        zero_widened_half<kDk>(cur.q, lane);
+        zero_widened_half<kDk>(cur.k, lane);
+        zero_widened_half<kDk>(cur.gf, lane);
+        zero_widened_half<kDk>(cur.gb, lane);
         ChunkFlags fl;
         fl.stash = m + 1 < nch;
         fl.seg = seg_in;
@@ -1151,7 +1163,10 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     scan_triangle<1>(w, r, g, tri_b);
 
     for (int m = nch - 1; m >= 0; --m) {
-        const ChunkRows cur = next;
+        ChunkRows cur = next;
+        zero_widened_half<kDk>(cur.k, lane);
+        zero_widened_half<kDk>(cur.gf, lane);
+        zero_widened_half<kDk>(cur.gb, lane);
         // the rows of chunk m-1 are requested a tile at a time between the phases of this step:
         // a burst of all of them would stall this wave at issue while the memory pipeline is full
         const long far_token0 = long(chunk0 + max(m - 1, 0)) * kC;
