@@ -31,10 +31,20 @@ typedef enum {
     VIG_ERR_UNSUPPORTED = -4, /* dk or dv outside {16, 32, 64}                           */
     VIG_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned                        */
     VIG_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than bigla_workspace_bytes()  */
-    VIG_ERR_HIP = -7          /* a HIP call failed; see vig_last_hip_error()             */
+    VIG_ERR_HIP = -7,         /* a HIP call failed; see vig_last_hip_error()             */
+    VIG_ERR_LAYOUT = -8       /* layout is not a vig_layout                              */
 } vig_status;
 
 typedef enum { VIG_F32 = 0, VIG_BF16 = 1 } vig_dtype;
+
+/*
+ * Placement of heads and tokens in the activations.  VIG_LAYOUT_BHLD, [B, H, L, d], is what
+ * bigla_fwd / locality_gate_fwd take.  VIG_LAYOUT_BLHD, [B, L, H, d] (token-major: a token's H*d
+ * features are contiguous, the form in which the projections of a block emit q, k, v and the
+ * gates, so that no transpose is needed around the token mixer -- Section 4.2.1 treats heads as
+ * independent slices of the feature dimension), is accepted by the *_layout entry points.
+ */
+typedef enum { VIG_LAYOUT_BHLD = 0, VIG_LAYOUT_BLHD = 1 } vig_layout;
 
 /*
  * Bytes of device scratch that bigla_fwd needs for this problem (0 if none).  The scratch
@@ -76,6 +86,15 @@ int bigla_fwd(const void *q, const void *k, const void *v, const void *g_fwd, co
               size_t workspace_bytes, void *stream);
 
 /*
+ * bigla_fwd with the activations q, k, v, g_fwd, g_bwd and out all in `layout` (a vig_layout);
+ * everything else as for bigla_fwd (same workspace size).  With VIG_LAYOUT_BLHD, L * H * max(dk, dv)
+ * must stay below 2^31 and L below 2^24 (VIG_ERR_SHAPE otherwise).
+ */
+int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                     void *out, int B, int H, int L, int dk, int dv, int dtype, int layout,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * 2D gating locality injection forward -- Section 4.2.2.  Token t of the flattened
  * sequence is patch (y, xp) of the Hg x Wg grid, t = y*Wg + xp; channel c = h*dv + j.
  *     O_local[y,xp,c] = bias[c] + sum_{dy,dx in {-1,0,1}} w[c,dy+1,dx+1] * x[y+dy, xp+dx, c]
@@ -92,6 +111,15 @@ int bigla_fwd(const void *q, const void *k, const void *v, const void *g_fwd, co
 int locality_gate_fwd(const void *x, const void *w, const void *bias, const void *gate_logits,
                       const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv,
                       int dtype, void *stream);
+
+/*
+ * locality_gate_fwd with x, gate_logits, o_global and out in `layout` (a vig_layout): with
+ * VIG_LAYOUT_BLHD they are [B, Hg*Wg, H, dv], i.e. channel c = h*dv + j of a pixel is contiguous.
+ * w and bias as for locality_gate_fwd.
+ */
+int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, const void *gate_logits,
+                             const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv,
+                             int dtype, int layout, void *stream);
 
 /*
  * Measurement aid (no part of the method): per-kernel timing with HIP events recorded on the

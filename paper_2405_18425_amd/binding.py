@@ -17,12 +17,15 @@ LIB_PATH = os.path.join(_HERE, "libvig_bigla.so")
 
 VIG_OK = 0
 VIG_ERR_NULL, VIG_ERR_SHAPE, VIG_ERR_DTYPE, VIG_ERR_UNSUPPORTED = -1, -2, -3, -4
-VIG_ERR_ALIGN, VIG_ERR_WORKSPACE, VIG_ERR_HIP = -5, -6, -7
+VIG_ERR_ALIGN, VIG_ERR_WORKSPACE, VIG_ERR_HIP, VIG_ERR_LAYOUT = -5, -6, -7, -8
 VIG_F32, VIG_BF16 = 0, 1
+VIG_LAYOUT_BHLD, VIG_LAYOUT_BLHD = 0, 1
+LAYOUTS = {"bhld": VIG_LAYOUT_BHLD, "blhd": VIG_LAYOUT_BLHD}
 
 # every symbol include/vig_bigla.h declares
-EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "locality_gate_fwd", "vig_status_str", "vig_last_hip_error",
-           "vig_timing_enable", "vig_timing_collect")
+EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "locality_gate_fwd",
+           "locality_gate_fwd_layout", "vig_status_str", "vig_last_hip_error", "vig_timing_enable",
+           "vig_timing_collect")
 KERNELS = {"segment_state": 0, "state_scan": 1, "segment_out": 2, "recurrent": 3, "locality_gate": 4,
            "segment_out_general": 5}
 
@@ -48,8 +51,12 @@ def lib() -> ctypes.CDLL:
         L.bigla_workspace_bytes.restype = sz
         L.bigla_fwd.argtypes = [vp] * 6 + [ci] * 6 + [vp, sz, vp]
         L.bigla_fwd.restype = ci
+        L.bigla_fwd_layout.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
+        L.bigla_fwd_layout.restype = ci
         L.locality_gate_fwd.argtypes = [vp] * 6 + [ci] * 6 + [vp]
         L.locality_gate_fwd.restype = ci
+        L.locality_gate_fwd_layout.argtypes = [vp] * 6 + [ci] * 7 + [vp]
+        L.locality_gate_fwd_layout.restype = ci
         L.vig_status_str.argtypes = [ci]
         L.vig_status_str.restype = ctypes.c_char_p
         L.vig_last_hip_error.argtypes = []
@@ -102,26 +109,37 @@ def bigla_workspace_bytes(B: int, H: int, L: int, dk: int, dv: int, dtype: int) 
     return int(lib().bigla_workspace_bytes(B, H, L, dk, dv, dtype))
 
 
-def bigla_fwd(q, k, v, g_fwd, g_bwd, out=None, workspace=None):
-    """BiGLA forward (Section 4.2.1).  q,k,g_fwd,g_bwd: [B,H,L,dk]; v: [B,H,L,dv] -> out [B,H,L,dv].
+def _layout_code(layout) -> int:
+    if layout not in LAYOUTS:
+        raise VigError(VIG_ERR_LAYOUT, f"layout must be one of {sorted(LAYOUTS)}")
+    return LAYOUTS[layout]
+
+
+def bigla_fwd(q, k, v, g_fwd, g_bwd, out=None, workspace=None, layout="bhld"):
+    """BiGLA forward (Section 4.2.1).  q,k,g_fwd,g_bwd: [B,H,L,dk]; v: [B,H,L,dv] -> out [B,H,L,dv]
+    (layout "bhld"), or all of them token-major, [B,L,H,d] (layout "blhd").
 
     g_* are LOG forget gates (<= 0).  `workspace` is an optional uint8 GPU tensor of at least
     bigla_workspace_bytes(...) bytes; one is allocated with torch when absent.
     """
+    lay = _layout_code(layout)
     q = _dev(q, "q")
     if q.dim() != 4:
-        raise VigError(VIG_ERR_SHAPE, "q must be [B,H,L,dk]")
-    B, H, L, dk = q.shape
+        raise VigError(VIG_ERR_SHAPE, "q must be 4-dimensional")
+    if lay == VIG_LAYOUT_BHLD:
+        B, H, L, dk = q.shape
+    else:
+        B, L, H, dk = q.shape
     k = _dev(k, "k", q.shape, q)
     g_fwd = _dev(g_fwd, "g_fwd", q.shape, q)
     g_bwd = _dev(g_bwd, "g_bwd", q.shape, q)
     v = _dev(v, "v", like=q)
-    if v.dim() != 4 or tuple(v.shape[:3]) != (B, H, L):
-        raise VigError(VIG_ERR_SHAPE, "v must be [B,H,L,dv]")
+    if v.dim() != 4 or tuple(v.shape[:3]) != tuple(q.shape[:3]):
+        raise VigError(VIG_ERR_SHAPE, "v must have the leading dimensions of q")
     dv = v.shape[3]
     if out is None:
-        out = torch.empty((B, H, L, dv), dtype=q.dtype, device=q.device)
-    out = _dev(out, "out", (B, H, L, dv), q)
+        out = torch.empty(tuple(v.shape), dtype=q.dtype, device=q.device)
+    out = _dev(out, "out", tuple(v.shape), q)
     code = _dtype_code(q)
     need = bigla_workspace_bytes(B, H, L, dk, dv, code)
     if workspace is None and need > 0:
@@ -129,21 +147,31 @@ def bigla_fwd(q, k, v, g_fwd, g_bwd, out=None, workspace=None):
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     with torch.cuda.device(q.device):
-        st = lib().bigla_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), g_fwd.data_ptr(), g_bwd.data_ptr(),
-                             out.data_ptr(), B, H, L, dk, dv, code, ws_ptr, ws_bytes, _stream_ptr(q.device))
+        if lay == VIG_LAYOUT_BHLD:
+            st = lib().bigla_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), g_fwd.data_ptr(), g_bwd.data_ptr(),
+                                 out.data_ptr(), B, H, L, dk, dv, code, ws_ptr, ws_bytes, _stream_ptr(q.device))
+        else:
+            st = lib().bigla_fwd_layout(q.data_ptr(), k.data_ptr(), v.data_ptr(), g_fwd.data_ptr(),
+                                        g_bwd.data_ptr(), out.data_ptr(), B, H, L, dk, dv, code, lay, ws_ptr,
+                                        ws_bytes, _stream_ptr(q.device))
     _check(st, "bigla_fwd")
     return out
 
 
-def locality_gate_fwd(x, w, gate_logits, o_global, Hg: int, Wg: int, bias=None, out=None):
+def locality_gate_fwd(x, w, gate_logits, o_global, Hg: int, Wg: int, bias=None, out=None, layout="bhld"):
     """2D gating locality injection (Section 4.2.2).
 
-    x, gate_logits, o_global: [B,H,Hg*Wg,dv]; w: [H*dv,3,3]; bias: [H*dv] or None -> out like x.
+    x, gate_logits, o_global: [B,H,Hg*Wg,dv] (layout "bhld") or [B,Hg*Wg,H,dv] (layout "blhd");
+    w: [H*dv,3,3]; bias: [H*dv] or None -> out like x.
     """
+    lay = _layout_code(layout)
     x = _dev(x, "x")
     if x.dim() != 4:
-        raise VigError(VIG_ERR_SHAPE, "x must be [B,H,L,dv]")
-    B, H, L, dv = x.shape
+        raise VigError(VIG_ERR_SHAPE, "x must be 4-dimensional")
+    if lay == VIG_LAYOUT_BHLD:
+        B, H, L, dv = x.shape
+    else:
+        B, L, H, dv = x.shape
     if L != Hg * Wg:
         raise VigError(VIG_ERR_SHAPE, "x.shape[2] must equal Hg*Wg")
     w = _dev(w, "w", (H * dv, 3, 3), x)
@@ -155,9 +183,15 @@ def locality_gate_fwd(x, w, gate_logits, o_global, Hg: int, Wg: int, bias=None, 
         out = torch.empty_like(x)
     out = _dev(out, "out", x.shape, x)
     with torch.cuda.device(x.device):
-        st = lib().locality_gate_fwd(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None,
-                                     gate_logits.data_ptr(), o_global.data_ptr(), out.data_ptr(), B, H, Hg, Wg, dv,
-                                     _dtype_code(x), _stream_ptr(x.device))
+        bias_ptr = bias.data_ptr() if bias is not None else None
+        if lay == VIG_LAYOUT_BHLD:
+            st = lib().locality_gate_fwd(x.data_ptr(), w.data_ptr(), bias_ptr, gate_logits.data_ptr(),
+                                         o_global.data_ptr(), out.data_ptr(), B, H, Hg, Wg, dv, _dtype_code(x),
+                                         _stream_ptr(x.device))
+        else:
+            st = lib().locality_gate_fwd_layout(x.data_ptr(), w.data_ptr(), bias_ptr, gate_logits.data_ptr(),
+                                                o_global.data_ptr(), out.data_ptr(), B, H, Hg, Wg, dv,
+                                                _dtype_code(x), lay, _stream_ptr(x.device))
     _check(st, "locality_gate_fwd")
     return out
 

@@ -200,9 +200,13 @@ struct StagedRows {
 // and log-gate 0 through every later step, which leaves the result unchanged.  The lanes of the
 // zero half repeat the addresses of the other half (the instruction still touches whole rows)
 // and are cleared by zero_widened_half when the rows are consumed.
-template <bool kZeroHere = false, int kRow = kD>
+//
+// kTm selects the token-major layout ([B, L, H, d]): consecutive tokens of the slab are then
+// tok_stride = H * kRow elements apart; offsets stay below 2^31 (checked on the host) and are
+// formed with a 24-bit multiply.  Head-major ([B, H, L, d]) rows are kRow apart, a shift.
+template <bool kZeroHere = false, int kRow = kD, bool kTm = false>
 __device__ __forceinline__ StagedRows load_rows_staged(const uint16_t *slab_base, long chunk_token0, int w, int lane,
-                                                       int L)
+                                                       int L, unsigned tok_stride = 0)
 {
     static_assert(kRow == kD || kRow == kD / 2, "row length");
     constexpr int kPieces = kRow / 8;
@@ -211,7 +215,8 @@ __device__ __forceinline__ StagedRows load_rows_staged(const uint16_t *slab_base
     for (int t = 0; t < 2; ++t) {
         const long tok = chunk_token0 + 16 * w + 8 * t + (lane >> 3);
         const long tc = tok < L ? tok : long(L) - 1;
-        s.p[t] = *reinterpret_cast<const uint4 *>(slab_base + tc * kRow + 8 * ((lane & 7) % kPieces));
+        const size_t row_off = kTm ? size_t(__umul24(unsigned(tc), tok_stride)) : size_t(tc) * kRow;
+        s.p[t] = *reinterpret_cast<const uint4 *>(slab_base + row_off + 8 * ((lane & 7) % kPieces));
         if (kZeroHere && tok >= L) s.p[t] = make_uint4(0, 0, 0, 0);
     }
     return s;
@@ -600,11 +605,11 @@ struct ChunkFlags {
 // Everything after the score tiles, common to both forms: O^T = V^T P^T + the three readouts,
 // out = O/2, then the forward state update with the keys in `ktile`.
 // fast_update: S = d (S + K^T V) with d = exp(tot); otherwise S = d S + K^T V with d = prod(eb).
-template <class Prefetch>
+template <bool kTm, class Prefetch>
 __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)[kPitch], const ChunkOperands &op,
                                              const ChunkFlags fl, const bool fast_update, const int w, const int r,
                                              const int g, uint16_t *out_slab, const long chunk_token0, const int L,
-                                             f32x4 (&S)[4], Prefetch &&prefetch)
+                                             const unsigned out_tok_stride, f32x4 (&S)[4], Prefetch &&prefetch)
 {
     const uint2(&pk)[4] = op.pk;
     bf16x8 vop[2][4];
@@ -640,8 +645,9 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
         for (int t = 0; t < 2; ++t) {
             const int rr = 16 * w + 8 * t + (lane >> 3);
             const uint4 o = *reinterpret_cast<const uint4 *>(&sm.gf[rr][8 * (lane & 7)]);
-            if (chunk_token0 + rr < L)
-                *reinterpret_cast<uint4 *>(out_slab + (chunk_token0 + rr) * kD + 8 * (lane & 7)) = o;
+            const long tok = chunk_token0 + rr;
+            const size_t row_off = kTm ? size_t(__umul24(unsigned(tok), out_tok_stride)) : size_t(tok) * kD;
+            if (tok < L) *reinterpret_cast<uint4 *>(out_slab + row_off + 8 * (lane & 7)) = o;
         }
     }
 
@@ -924,14 +930,14 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
 //                     footprint would otherwise spill into the fast path); other segments exit.
 // kFastOnly = false: handles the remaining segments (all of them when seg_mild is nullptr), each
 //                     chunk choosing its form.
-template <bool kFastOnly, int kDk>
+template <bool kFastOnly, int kDk, bool kTm>
 __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out_kernel(
     const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
     const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
     const float *__restrict__ seg_states /* states entering each segment, nullptr when one segment */,
     const int *__restrict__ seg_mild /* per (slab, segment): every chunk admits the fast form; may be nullptr */,
     const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg, long total_units,
-    int units_per_block)
+    int units_per_block, int heads /* used when kTm: activations are [B,L,H,d] */)
 {
     __shared__ OutLds sm;
     const int tid = threadIdx.x;
@@ -957,7 +963,10 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
     const long slab = unit / n_seg;
     const int seg = int(unit % n_seg);
     __syncthreads();  // LDS of a previous unit is no longer read
-    const long base = slab * L * kD, key_base = slab * L * kDk;
+    // first row of the slab and distance between its tokens, in rows of the tensor
+    const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
+    const unsigned key_stride = unsigned(heads) * kDk, val_stride = unsigned(heads) * kD;
+    const long base = row0 * kD, key_base = row0 * kDk;
     const uint16_t *q = q_all + key_base, *k = k_all + key_base, *v = v_all + base;
     const uint16_t *g_fwd = gf_all + key_base, *g_bwd = gb_all + key_base;
     uint16_t *out = out_all + base;
@@ -992,11 +1001,11 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
     // part 0..5: q, k, g_fwd, g_bwd, v, stash
     auto fetch_part = [&](ChunkRows &c, int m, int part) {
         const long t0 = chunk_token0(m);
-        if (part == 0) c.q = load_rows_staged<false, kDk>(q, t0, w, lane, L);
-        if (part == 1) c.k = load_rows_staged<false, kDk>(k, t0, w, lane, L);
-        if (part == 2) c.gf = load_rows_staged<false, kDk>(g_fwd, t0, w, lane, L);
-        if (part == 3) c.gb = load_rows_staged<false, kDk>(g_bwd, t0, w, lane, L);
-        if (part == 4) c.v = load_rows_staged(v, t0, w, lane, L);
+        if (part == 0) c.q = load_rows_staged<false, kDk, kTm>(q, t0, w, lane, L, key_stride);
+        if (part == 1) c.k = load_rows_staged<false, kDk, kTm>(k, t0, w, lane, L, key_stride);
+        if (part == 2) c.gf = load_rows_staged<false, kDk, kTm>(g_fwd, t0, w, lane, L, key_stride);
+        if (part == 3) c.gb = load_rows_staged<false, kDk, kTm>(g_bwd, t0, w, lane, L, key_stride);
+        if (part == 4) c.v = load_rows_staged<false, kD, kTm>(v, t0, w, lane, L, val_stride);
         if (part == 5) fetch_stash(c, m);
     };
     ChunkRows next;
@@ -1104,7 +1113,7 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
 #pragma unroll
             for (int part = 0; part < 6; ++part) fetch_part(next, m + 1, part);
         }
-        finish_chunk(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L, S,
+        finish_chunk<kTm>(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L, val_stride, S,
                      prefetch_second_half);
     }
     }  // units
@@ -1112,19 +1121,21 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
 
 // ---- kernel 1: per-segment end states and per-chunk backward stash -----------------------------
 
-template <int kDk>
+template <int kDk, bool kTm>
 __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, const uint16_t *__restrict__ g_fwd,
     const uint16_t *__restrict__ g_bwd, float *__restrict__ seg_states, int *__restrict__ seg_mild,
-    unsigned char *__restrict__ stash, int L, int n_chunks, int seg_chunks, int n_seg)
+    unsigned char *__restrict__ stash, int L, int n_chunks, int seg_chunks, int n_seg,
+    int heads /* used when kTm: activations are [B,L,H,d] */)
 {
     __shared__ StateLds sm;
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
     const long slab = blockIdx.x / n_seg;
     const int seg = blockIdx.x % n_seg;
-    const long base = slab * L * kD, key_base = slab * L * kDk;
-    k += key_base; v += base; g_fwd += key_base; g_bwd += key_base;
+    const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
+    const unsigned key_stride = unsigned(heads) * kDk, val_stride = unsigned(heads) * kD;
+    k += row0 * kDk; v += row0 * kD; g_fwd += row0 * kDk; g_bwd += row0 * kDk;
     float *dst = seg_states + (slab * n_seg + seg) * kSegFloats;
     stash += size_t(slab) * n_chunks * kStashBytes;
 
@@ -1151,10 +1162,10 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     };
     auto fetch = [&](int m) {  // m may run one before the segment: clamped, the rows are then unused
         ChunkRows c;
-        c.k = load_rows_staged<true, kDk>(k, long(chunk0 + max(m, 0)) * kC, w, lane, L);
-        c.v = load_rows_staged<true>(v, long(chunk0 + max(m, 0)) * kC, w, lane, L);
-        c.gf = load_rows_staged<true, kDk>(g_fwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
-        c.gb = load_rows_staged<true, kDk>(g_bwd, long(chunk0 + max(m, 0)) * kC, w, lane, L);
+        c.k = load_rows_staged<true, kDk, kTm>(k, long(chunk0 + max(m, 0)) * kC, w, lane, L, key_stride);
+        c.v = load_rows_staged<true, kD, kTm>(v, long(chunk0 + max(m, 0)) * kC, w, lane, L, val_stride);
+        c.gf = load_rows_staged<true, kDk, kTm>(g_fwd, long(chunk0 + max(m, 0)) * kC, w, lane, L, key_stride);
+        c.gb = load_rows_staged<true, kDk, kTm>(g_bwd, long(chunk0 + max(m, 0)) * kC, w, lane, L, key_stride);
         return c;
     };
     ChunkRows next = fetch(nch - 1);
@@ -1170,7 +1181,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         // the rows of chunk m-1 are requested a tile at a time between the phases of this step:
         // a burst of all of them would stall this wave at issue while the memory pipeline is full
         const long far_token0 = long(chunk0 + max(m - 1, 0)) * kC;
-        next.k = load_rows_staged<true, kDk>(k, far_token0, w, lane, L);
+        next.k = load_rows_staged<true, kDk, kTm>(k, far_token0, w, lane, L, key_stride);
 
         // stash for chunk m: the backward state entering it from the right (zero, and not
         // stored, for the segment's last chunk) and the decay from its right edge to the
@@ -1197,7 +1208,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         float kf[16];
         unpack16(bounce_load(sm.ks[0], row, g), kf);
         __syncthreads();  // g, v visible
-        next.v = load_rows_staged<true>(v, far_token0, w, lane, L);
+        next.v = load_rows_staged<true, kD, kTm>(v, far_token0, w, lane, L, val_stride);
 
         f32x4 Bf[4], Bb[4];
         float max_f, max_b;
@@ -1217,7 +1228,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         }
         const bool fast = fmaxf(max_f, max_b) <= kFastRange;  // uniform over the workgroup
         all_fast = all_fast && fast;
-        next.gf = load_rows_staged<true, kDk>(g_fwd, far_token0, w, lane, L);
+        next.gf = load_rows_staged<true, kDk, kTm>(g_fwd, far_token0, w, lane, L, key_stride);
         float4 df, db;  // this chunk's decay, rows at LDS positions 16w + 4g + e
         float tmp[16];
         if (fast) {
@@ -1281,7 +1292,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
             __syncthreads();  // ks visible
         }
 
-        next.gb = load_rows_staged<true, kDk>(g_bwd, far_token0, w, lane, L);
+        next.gb = load_rows_staged<true, kDk, kTm>(g_bwd, far_token0, w, lane, L, key_stride);
         // chunk contributions K^T V of both directions, rows at positions 16w + 4g + e
         f32x4 Cf[4], Cb[4];
 #pragma unroll
@@ -1392,9 +1403,9 @@ size_t bigla_chunk_workspace_bytes(long BH, int L)
 }
 
 namespace {
-template <int kDk>
+template <int kDk, bool kTm>
 hipError_t chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd, void *out,
-                        long BH, int L, void *workspace, hipStream_t stream)
+                        long BH, int L, int heads_token_major, void *workspace, hipStream_t stream)
 {
     const Plan p = make_plan(BH, L);
     const long blocks = BH * p.n_seg;
@@ -1409,8 +1420,9 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
     if (p.n_chunks > 1) {  // a single chunk has neither a stash nor entering states
         {
             LaunchTimer timer(kKernelSegmentState, stream);
-            hipLaunchKernelGGL(bigla_segment_state_kernel<kDk>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, kk, vv,
-                               gf, gb, seg_states, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg);
+            hipLaunchKernelGGL((bigla_segment_state_kernel<kDk, kTm>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, kk, vv,
+                               gf, gb, seg_states, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg,
+                               heads_token_major);
         }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -1429,8 +1441,9 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
     uint16_t *oo = static_cast<uint16_t *>(out);
     if (flags) {  // segments the state kernel flagged as entirely within the fast form's range
         LaunchTimer timer(kKernelSegmentOut, stream);
-        hipLaunchKernelGGL((bigla_segment_out_kernel<true, kDk>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk, vv,
-                           gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, blocks, 1);
+        hipLaunchKernelGGL((bigla_segment_out_kernel<true, kDk, kTm>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk, vv,
+                           gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, blocks, 1,
+                           heads_token_major);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -1439,19 +1452,26 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
         // about one workgroup per CU (this kernel runs one per CU), at most 64 units each
         long per_block = flags ? (blocks + 255) / 256 : 1;
         if (per_block > 64) per_block = 64;
-        hipLaunchKernelGGL((bigla_segment_out_kernel<false, kDk>), dim3((unsigned)((blocks + per_block - 1) / per_block)),
+        hipLaunchKernelGGL((bigla_segment_out_kernel<false, kDk, kTm>), dim3((unsigned)((blocks + per_block - 1) / per_block)),
                            dim3(kThreads), 0, stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks,
-                           p.seg_chunks, p.n_seg, blocks, int(per_block));
+                           p.seg_chunks, p.n_seg, blocks, int(per_block), heads_token_major);
     }
     return hipGetLastError();
 }
 }  // namespace
 
 hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
-                              void *out, long BH, int L, int dk, void *workspace, hipStream_t stream)
+                              void *out, long BH, int L, int dk, int heads_token_major, void *workspace,
+                              hipStream_t stream)
 {
-    if (dk == kD) return chunk_launch<kD>(q, k, v, g_fwd, g_bwd, out, BH, L, workspace, stream);
-    if (dk == kD / 2) return chunk_launch<kD / 2>(q, k, v, g_fwd, g_bwd, out, BH, L, workspace, stream);
+    const bool tm = heads_token_major > 0;
+    if (dk == kD && !tm) return chunk_launch<kD, false>(q, k, v, g_fwd, g_bwd, out, BH, L, 1, workspace, stream);
+    if (dk == kD && tm)
+        return chunk_launch<kD, true>(q, k, v, g_fwd, g_bwd, out, BH, L, heads_token_major, workspace, stream);
+    if (dk == kD / 2 && !tm)
+        return chunk_launch<kD / 2, false>(q, k, v, g_fwd, g_bwd, out, BH, L, 1, workspace, stream);
+    if (dk == kD / 2 && tm)
+        return chunk_launch<kD / 2, true>(q, k, v, g_fwd, g_bwd, out, BH, L, heads_token_major, workspace, stream);
     return hipErrorInvalidValue;
 }
 

@@ -67,7 +67,7 @@ struct vec4<bf16_t> {
 
 constexpr int kThreads = 256;
 
-template <typename T, int DV, int RS>
+template <typename T, int DV, int RS, bool kTm /* [B,L,H,dv] instead of [B,H,L,dv] */>
 __global__ __launch_bounds__(kThreads) void locality_gate_kernel(
     const T *__restrict__ x, const T *__restrict__ w, const T *__restrict__ bias, const T *__restrict__ z,
     const T *__restrict__ og, T *__restrict__ out, int H, int Hg, int Wg, int n_strips, long total_threads)
@@ -87,7 +87,10 @@ __global__ __launch_bounds__(kThreads) void locality_gate_kernel(
     const long slab = rest / n_strips;
     const int h = int(slab % H);
     const int c0 = h * DV + cg * N;
-    const size_t slab_off = size_t(slab) * Hg * Wg * DV + size_t(cg) * N;
+    // first pixel of the slab and distance between pixels, in rows of DV channels
+    const size_t row0 = kTm ? size_t(slab / H) * Hg * Wg * H + h : size_t(slab) * Hg * Wg;
+    const size_t px = kTm ? size_t(H) * DV : size_t(DV);
+    const size_t slab_off = row0 * DV + size_t(cg) * N;
     const int y0 = strip * RS;
 
     // ---- every load of the strip is issued before any arithmetic: (RS+2)*3 input vectors (rows
@@ -101,13 +104,13 @@ __global__ __launch_bounds__(kThreads) void locality_gate_kernel(
         for (int kx = 0; kx < 3; ++kx) {
             const int xx = xp + kx - 1;
             const bool in = yy >= 0 && yy < Hg && xx >= 0 && xx < Wg;
-            xr[i][kx] = in ? *reinterpret_cast<const raw_t *>(x + slab_off + (size_t(yy) * Wg + xx) * DV) : V::zero();
+            xr[i][kx] = in ? *reinterpret_cast<const raw_t *>(x + slab_off + (size_t(yy) * Wg + xx) * px) : V::zero();
         }
     }
 #pragma unroll
     for (int i = 0; i < RS; ++i) {
         const bool in = y0 + i < Hg;
-        const size_t o = slab_off + (size_t(y0 + i) * Wg + xp) * DV;
+        const size_t o = slab_off + (size_t(y0 + i) * Wg + xp) * px;
         zr[i] = in ? *reinterpret_cast<const raw_t *>(z + o) : V::zero();
         gr[i] = in ? *reinterpret_cast<const raw_t *>(og + o) : V::zero();
     }
@@ -160,14 +163,14 @@ __global__ __launch_bounds__(kThreads) void locality_gate_kernel(
                 // G * O_local + (1 - G) * O_global
                 res[e] = fmaf(gate, res[e] - gf[e], gf[e]);
             }
-            V::store(out + slab_off + (size_t(y0 + i) * Wg + xp) * DV, res);
+            V::store(out + slab_off + (size_t(y0 + i) * Wg + xp) * px, res);
         }
     }
 }
 
 template <typename T, int DV, int RS>
 hipError_t launch_rs(const void *x, const void *w, const void *bias, const void *z, const void *og, void *out,
-                     long slabs, int H, int Hg, int Wg, hipStream_t stream)
+                     long slabs, int H, int Hg, int Wg, int token_major, hipStream_t stream)
 {
     constexpr int CG = DV / vec4<T>::N;
     const int n_strips = (Hg + RS - 1) / RS;
@@ -175,34 +178,40 @@ hipError_t launch_rs(const void *x, const void *w, const void *bias, const void 
     const long blocks = (total + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
     LaunchTimer timer(kKernelLocalityGate, stream);
-    hipLaunchKernelGGL((locality_gate_kernel<T, DV, RS>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
-                       static_cast<const T *>(x), static_cast<const T *>(w), static_cast<const T *>(bias),
-                       static_cast<const T *>(z), static_cast<const T *>(og), static_cast<T *>(out), H, Hg, Wg,
-                       n_strips, total);
+    if (token_major)
+        hipLaunchKernelGGL((locality_gate_kernel<T, DV, RS, true>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+                           static_cast<const T *>(x), static_cast<const T *>(w), static_cast<const T *>(bias),
+                           static_cast<const T *>(z), static_cast<const T *>(og), static_cast<T *>(out), H, Hg, Wg,
+                           n_strips, total);
+    else
+        hipLaunchKernelGGL((locality_gate_kernel<T, DV, RS, false>), dim3((unsigned)blocks), dim3(kThreads), 0,
+                           stream, static_cast<const T *>(x), static_cast<const T *>(w),
+                           static_cast<const T *>(bias), static_cast<const T *>(z), static_cast<const T *>(og),
+                           static_cast<T *>(out), H, Hg, Wg, n_strips, total);
     return hipGetLastError();
 }
 
 template <typename T, int DV>
 hipError_t launch(const void *x, const void *w, const void *bias, const void *z, const void *og, void *out, int B,
-                  int H, int Hg, int Wg, hipStream_t stream)
+                  int H, int Hg, int Wg, int token_major, hipStream_t stream)
 {
     constexpr int CG = DV / vec4<T>::N;
     // strips of 4 rows (1.5x input reads, the halo rows come from L2) when that still fills the
     // chip several times over, else strips of 2 rows
     const long slabs = long(B) * H;
     const long blocks4 = (slabs * ((Hg + 3) / 4) * Wg * CG + kThreads - 1) / kThreads;
-    if (blocks4 >= 2048) return launch_rs<T, DV, 4>(x, w, bias, z, og, out, slabs, H, Hg, Wg, stream);
-    return launch_rs<T, DV, 2>(x, w, bias, z, og, out, slabs, H, Hg, Wg, stream);
+    if (blocks4 >= 2048) return launch_rs<T, DV, 4>(x, w, bias, z, og, out, slabs, H, Hg, Wg, token_major, stream);
+    return launch_rs<T, DV, 2>(x, w, bias, z, og, out, slabs, H, Hg, Wg, token_major, stream);
 }
 
 template <typename T>
 hipError_t launch_dv(int dv, const void *x, const void *w, const void *bias, const void *z, const void *og,
-                     void *out, int B, int H, int Hg, int Wg, hipStream_t stream)
+                     void *out, int B, int H, int Hg, int Wg, int token_major, hipStream_t stream)
 {
     switch (dv) {
-        case 16: return launch<T, 16>(x, w, bias, z, og, out, B, H, Hg, Wg, stream);
-        case 32: return launch<T, 32>(x, w, bias, z, og, out, B, H, Hg, Wg, stream);
-        case 64: return launch<T, 64>(x, w, bias, z, og, out, B, H, Hg, Wg, stream);
+        case 16: return launch<T, 16>(x, w, bias, z, og, out, B, H, Hg, Wg, token_major, stream);
+        case 32: return launch<T, 32>(x, w, bias, z, og, out, B, H, Hg, Wg, token_major, stream);
+        case 64: return launch<T, 64>(x, w, bias, z, og, out, B, H, Hg, Wg, token_major, stream);
     }
     return hipErrorInvalidValue;
 }
@@ -211,10 +220,10 @@ hipError_t launch_dv(int dv, const void *x, const void *w, const void *bias, con
 
 hipError_t locality_gate_launch(const void *x, const void *w, const void *bias, const void *gate_logits,
                                 const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv,
-                                bool is_bf16, hipStream_t stream)
+                                bool is_bf16, int token_major, hipStream_t stream)
 {
-    if (is_bf16) return launch_dv<bf16_t>(dv, x, w, bias, gate_logits, o_global, out, B, H, Hg, Wg, stream);
-    return launch_dv<float>(dv, x, w, bias, gate_logits, o_global, out, B, H, Hg, Wg, stream);
+    if (is_bf16) return launch_dv<bf16_t>(dv, x, w, bias, gate_logits, o_global, out, B, H, Hg, Wg, token_major, stream);
+    return launch_dv<float>(dv, x, w, bias, gate_logits, o_global, out, B, H, Hg, Wg, token_major, stream);
 }
 
 }  // namespace vig

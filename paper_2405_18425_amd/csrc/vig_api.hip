@@ -51,11 +51,24 @@ int bigla_fwd(const void *q, const void *k, const void *v, const void *g_fwd, co
               int B, int H, int L, int dk, int dv, int dtype, void *workspace, size_t workspace_bytes,
               void *stream)
 {
+    return bigla_fwd_layout(q, k, v, g_fwd, g_bwd, out, B, H, L, dk, dv, dtype, VIG_LAYOUT_BHLD, workspace,
+                            workspace_bytes, stream);
+}
+
+int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd, void *out,
+                     int B, int H, int L, int dk, int dv, int dtype, int layout, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
     if (!q || !k || !v || !g_fwd || !g_bwd || !out) return VIG_ERR_NULL;
+    if (layout != VIG_LAYOUT_BHLD && layout != VIG_LAYOUT_BLHD) return VIG_ERR_LAYOUT;
     if (B <= 0 || H <= 0 || L <= 0 || dk <= 0 || dv <= 0) return VIG_ERR_SHAPE;
     if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
     if (!head_dim_ok(dk) || !head_dim_ok(dv)) return VIG_ERR_UNSUPPORTED;
     if (!sizes_ok(B, H, L, dk > dv ? dk : dv) || long(B) * H > 0x7fffffffL) return VIG_ERR_SHAPE;
+    // token-major offsets inside one batch element are formed in 32 bits (24-bit factors)
+    if (layout == VIG_LAYOUT_BLHD &&
+        (L >= (1 << 24) || long(H) * 64 >= (1 << 24) || long(L) * H * (dk > dv ? dk : dv) >= (1L << 31)))
+        return VIG_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g_fwd) || !aligned16(g_bwd) ||
         !aligned16(out) || !aligned16(workspace))
         return VIG_ERR_ALIGN;
@@ -65,16 +78,28 @@ int bigla_fwd(const void *q, const void *k, const void *v, const void *g_fwd, co
     const bool bf16 = dtype == VIG_BF16;
     const long BH = long(B) * H;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const int heads_token_major = layout == VIG_LAYOUT_BLHD ? H : 0;
     if (vig::bigla_chunk_supported(dk, dv, bf16))
-        return hip_status(vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, workspace, s));
-    return hip_status(vig::bigla_recurrent_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, dv, bf16, workspace, s));
+        return hip_status(
+            vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, heads_token_major, workspace, s));
+    return hip_status(vig::bigla_recurrent_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, dv, bf16,
+                                                  heads_token_major, workspace, s));
 }
 
 int locality_gate_fwd(const void *x, const void *w, const void *bias, const void *gate_logits,
                       const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv, int dtype,
                       void *stream)
 {
+    return locality_gate_fwd_layout(x, w, bias, gate_logits, o_global, out, B, H, Hg, Wg, dv, dtype,
+                                    VIG_LAYOUT_BHLD, stream);
+}
+
+int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, const void *gate_logits,
+                             const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv, int dtype,
+                             int layout, void *stream)
+{
     if (!x || !w || !gate_logits || !o_global || !out) return VIG_ERR_NULL;
+    if (layout != VIG_LAYOUT_BHLD && layout != VIG_LAYOUT_BLHD) return VIG_ERR_LAYOUT;
     if (B <= 0 || H <= 0 || Hg <= 0 || Wg <= 0 || dv <= 0) return VIG_ERR_SHAPE;
     if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
     if (!head_dim_ok(dv)) return VIG_ERR_UNSUPPORTED;
@@ -83,7 +108,8 @@ int locality_gate_fwd(const void *x, const void *w, const void *bias, const void
         !aligned16(out))
         return VIG_ERR_ALIGN;
     return hip_status(vig::locality_gate_launch(x, w, bias, gate_logits, o_global, out, B, H, Hg, Wg, dv,
-                                                dtype == VIG_BF16, static_cast<hipStream_t>(stream)));
+                                                dtype == VIG_BF16, layout == VIG_LAYOUT_BLHD ? 1 : 0,
+                                                static_cast<hipStream_t>(stream)));
 }
 
 const char *vig_status_str(int status)
@@ -97,6 +123,7 @@ const char *vig_status_str(int status)
         case VIG_ERR_ALIGN: return "VIG_ERR_ALIGN: a pointer is not 16-byte aligned";
         case VIG_ERR_WORKSPACE: return "VIG_ERR_WORKSPACE: workspace missing or too small";
         case VIG_ERR_HIP: return "VIG_ERR_HIP: a HIP call failed (see vig_last_hip_error)";
+        case VIG_ERR_LAYOUT: return "VIG_ERR_LAYOUT: layout is not a vig_layout";
     }
     return "unknown vig_status";
 }

@@ -6,21 +6,26 @@
 
 namespace vig {
 
+// Tensor layouts.  Head-major [B, H, L, d] is the default.  Token-major [B, L, H, d] (what the
+// projection GEMMs of a block emit) is passed to the BiGLA launches as `heads_token_major` = H
+// (0 selects head-major) and to the locality launch as a flag.
+
 // ---- exact fp32 recurrence (any supported head shape, both dtypes) --------------------------
 size_t bigla_recurrent_workspace_bytes(long BH, int L, int dv, bool is_bf16);
 hipError_t bigla_recurrent_launch(const void *q, const void *k, const void *v, const void *g_fwd,
                                   const void *g_bwd, void *out, long BH, int L, int dk, int dv, bool is_bf16,
-                                  void *workspace, hipStream_t stream);
+                                  int heads_token_major, void *workspace, hipStream_t stream);
 
 // ---- chunkwise bf16 MFMA path (dv = 64, dk = 64 or 32) ----------------------------------------
 bool bigla_chunk_supported(int dk, int dv, bool is_bf16);
 size_t bigla_chunk_workspace_bytes(long BH, int L);
 hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
-                              void *out, long BH, int L, int dk, void *workspace, hipStream_t stream);
+                              void *out, long BH, int L, int dk, int heads_token_major, void *workspace,
+                              hipStream_t stream);
 
 // ---- depthwise 3x3 conv + sigmoid-gated blend -------------------------------------------------
 hipError_t locality_gate_launch(const void *x, const void *w, const void *bias, const void *gate_logits,
                                 const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv,
-                                bool is_bf16, hipStream_t stream);
+                                bool is_bf16, int token_major, hipStream_t stream);
 
 }  // namespace vig

@@ -29,7 +29,7 @@ def test_header_and_exports_agree():
 
 
 def test_status_strings():
-    for code in range(-7, 1):
+    for code in range(-8, 1):
         s = vb.status_str(code)
         assert s and "unknown" not in s
     assert "unknown" in vb.status_str(5)
@@ -86,6 +86,21 @@ def test_locality_validation_codes():
     assert call_loc(dv=24) == vb.VIG_ERR_UNSUPPORTED
     assert call_loc(bias=PTR + 6) == vb.VIG_ERR_ALIGN
     assert call_loc(w=PTR + 1) == vb.VIG_ERR_ALIGN
+
+
+def test_layout_entry_points_validate():
+    L = vb.lib()
+    args = (PTR,) * 6 + (1, 1, 8, 16, 16, vb.VIG_F32)
+    assert L.bigla_fwd_layout(*args, 2, None, 0, None) == vb.VIG_ERR_LAYOUT
+    assert L.bigla_fwd_layout(*args, -1, None, 0, None) == vb.VIG_ERR_LAYOUT
+    assert L.bigla_fwd_layout(None, *args[1:], vb.VIG_LAYOUT_BLHD, None, 0, None) == vb.VIG_ERR_NULL
+    # token-major offsets are 32-bit inside a batch element
+    big = (PTR,) * 6 + (1, 64, 1 << 23, 64, 64, vb.VIG_BF16)
+    assert L.bigla_fwd_layout(*big, vb.VIG_LAYOUT_BLHD, None, 0, None) == vb.VIG_ERR_SHAPE
+    largs = (PTR, PTR, None, PTR, PTR, PTR, 1, 1, 4, 4, 16, vb.VIG_BF16)
+    assert L.locality_gate_fwd_layout(*largs, 3, None) == vb.VIG_ERR_LAYOUT
+    assert L.locality_gate_fwd_layout(PTR, PTR, None, PTR, PTR, PTR, 1, 1, 4, 4, 24, vb.VIG_BF16,
+                                      vb.VIG_LAYOUT_BLHD, None) == vb.VIG_ERR_UNSUPPORTED
 
 
 def test_binding_rejects_cpu_tensors():

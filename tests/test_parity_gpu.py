@@ -222,3 +222,48 @@ def test_path_end_to_end_hierarchical_stage_shapes(grid, H):
     rms = lambda a: np.sqrt(np.mean(a ** 2, axis=(2, 3), keepdims=True))
     bound = tol * (np.abs(ref) + rms(ref) + np.abs(ref_og) + rms(ref_og))
     assert np.all(np.abs(out64 - ref) <= bound), float(np.max(np.abs(out64 - ref) - bound))
+
+
+@pytest.mark.parametrize("dtype,dk,dv,B,H,L", [("bf16", 64, 64, 2, 6, 1024), ("bf16", 32, 64, 3, 3, 333),
+                                               ("bf16", 64, 64, 2, 5, 64), ("f32", 16, 16, 2, 3, 100),
+                                               ("bf16", 16, 32, 2, 2, 70)])
+def test_bigla_token_major_layout(dtype, dk, dv, B, H, L):
+    """[B, L, H, d] activations (what the projections of a block emit): same result as the
+    head-major call, element for element, and equal to the oracle."""
+    import torch
+    from paper_2405_18425_amd import binding as vb
+
+    w = wl.Workload("tm", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=dv, dtype=dtype, gate_mu=-1.0)
+    _say(f"bigla token-major {w}")
+    s = wl.generate(w, seed=23, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+    t = {n: wl.to_torch(a, dtype, "cuda:0") for n, a in s.items()}
+    tm = {n: a.permute(0, 2, 1, 3).contiguous() for n, a in t.items()}
+    out_tm = vb.bigla_fwd(tm["q"], tm["k"], tm["v"], tm["g_fwd"], tm["g_bwd"], layout="blhd")
+    out_hm = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"])
+    torch.cuda.synchronize()
+    assert tuple(out_tm.shape) == (B, L, H, dv)
+    assert torch.equal(out_tm.permute(0, 2, 1, 3), out_hm)
+    got = wl.widen(wl.from_torch(out_tm.permute(0, 2, 1, 3).contiguous(), dtype), dtype)
+    assert_close(got, run_bigla_oracle(s, dtype), TOL[dtype], "token-major")
+
+
+@pytest.mark.parametrize("dtype", ("bf16", "f32"))
+@pytest.mark.parametrize("Hg,Wg,H,dv", [(14, 14, 3, 64), (5, 9, 4, 16), (32, 32, 2, 64), (1, 7, 2, 32)])
+def test_locality_token_major_layout(dtype, Hg, Wg, H, dv):
+    import torch
+    from paper_2405_18425_amd import binding as vb
+
+    w = wl.Workload("tm", B=2, H=H, Hg=Hg, Wg=Wg, dk=16, dv=dv, dtype=dtype, gate_mu=0.0)
+    _say(f"locality token-major {w}")
+    s = wl.generate(w, seed=29)
+    t = {n: wl.to_torch(a, dtype, "cuda:0") for n, a in s.items()}
+    og = torch.flip(t["v"], dims=(2,)).contiguous()  # any tensor of the right shape
+    tm = lambda a: a.permute(0, 2, 1, 3).contiguous()
+    out_tm = vb.locality_gate_fwd(tm(t["v"]), t["conv_w"], tm(t["gate_logits"]), tm(og), Hg, Wg, layout="blhd")
+    out_hm = vb.locality_gate_fwd(t["v"], t["conv_w"], t["gate_logits"], og, Hg, Wg)
+    torch.cuda.synchronize()
+    assert torch.equal(out_tm.permute(0, 2, 1, 3), out_hm)
+    import oracle
+    ref = oracle.locality_gate(wl.widen(s["v"], dtype), wl.widen(s["conv_w"], dtype), wl.widen(s["gate_logits"], dtype),
+                               wl.widen(wl.from_torch(og, dtype), dtype), Hg, Wg)
+    assert_close(wl.widen(wl.from_torch(out_hm, dtype), dtype), ref, 8e-3 if dtype == "bf16" else 1e-5, "tm")
