@@ -52,6 +52,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget-s", type=float, default=12.0)
     ap.add_argument("--single-set", action="store_true", help="reuse one buffer set (cache-warm timing)")
+    ap.add_argument("--dk", type=int, default=0, help="override the key/query head width of the workload (side measurement)")
+    ap.add_argument("--layout", choices=("bhld", "blhd"), default="bhld",
+                    help="activation layout: head-major (default) or token-major [B,L,H,d] (side measurement)")
     return ap.parse_args()
 
 
@@ -74,6 +77,8 @@ def main():
     vb.lib()  # fail loudly if the HIP library is not built
     dev = torch.device("cuda:0")
     w = wl.CONFIGS[args.config]
+    if args.dk:
+        w = w.replace(name=f"{w.name}_dk{args.dk}", dk=args.dk)
     esize = 2 if w.dtype == "bf16" else 4
 
     # ---- inputs: one seeded set on the host, further sets are batch-rotated copies on the device
@@ -85,6 +90,8 @@ def main():
     for i in range(n_sets):
         s = {n: (t if i == 0 or n == "conv_w" else torch.roll(t, shifts=i, dims=0).contiguous())
              for n, t in base.items()}
+        if args.layout == "blhd":
+            s = {n: (t if n == "conv_w" else t.permute(0, 2, 1, 3).contiguous()) for n, t in s.items()}
         s["o_global"] = torch.empty_like(s["v"])
         s["out"] = torch.empty_like(s["v"])
         sets.append(s)
@@ -94,8 +101,10 @@ def main():
 
     def step(i):
         s = sets[i % n_sets]
-        vb.bigla_fwd(s["q"], s["k"], s["v"], s["g_fwd"], s["g_bwd"], out=s["o_global"], workspace=workspace)
-        vb.locality_gate_fwd(s["v"], s["conv_w"], s["gate_logits"], s["o_global"], w.Hg, w.Wg, out=s["out"])
+        vb.bigla_fwd(s["q"], s["k"], s["v"], s["g_fwd"], s["g_bwd"], out=s["o_global"], workspace=workspace,
+                     layout=args.layout)
+        vb.locality_gate_fwd(s["v"], s["conv_w"], s["gate_logits"], s["o_global"], w.Hg, w.Wg, out=s["out"],
+                             layout=args.layout)
 
     for i in range(args.warmup):
         step(i)
@@ -182,7 +191,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": w.L, "grid": [w.Hg, w.Wg], "dk": w.dk, "dv": w.dv,
-                   "gate_logit_mean": w.gate_mu, "buffer_sets": n_sets, "set_bytes": set_bytes},
+                   "gate_logit_mean": w.gate_mu, "layout": args.layout, "buffer_sets": n_sets, "set_bytes": set_bytes},
         "roofline": roofline, "cpu_baseline": cpu, "detail": extra,
     }
     print(json.dumps(line), flush=True)
