@@ -1,4 +1,5 @@
-// Chunkwise bf16 MFMA evaluation of BiGLA (Section 4.2.1, Eq. (BiGLA)) for dk = dv = 64.
+// Chunkwise bf16 MFMA evaluation of BiGLA (Section 4.2.1, Eq. (BiGLA)) for dv = 64 and dk = 64
+// (or 32, widened to 64 with zero channels).
 //
 // The recurrence S_t = diag(alpha_t) S_{t-1} + k_t^T v_t, o_t = q_t S_t is regrouped exactly
 // (no approximation beyond bf16 operand rounding) over chunks of 64 tokens.  With b_t the
@@ -43,9 +44,11 @@
 //      right, once.  Each chunk is finished in a single step for both directions: one merged
 //      64x64 score tile (lower triangle forward, upper triangle backward, the diagonal from
 //      both), ONE P.V contraction, the forward state readout from the state carried in
-//      registers, the backward readout from the stash plus the segment's entering state
-//      (scaled per channel by the stashed decay), then the forward state update.
-//      out = (o_fwd + o_bwd)/2 is written once; q, k, v, g_fwd, g_bwd are read once here.
+//      registers, ONE backward readout from the stash tile to which the segment's entering
+//      state (scaled per channel by the stashed decay) has been added, then the forward state
+//      update.  out = (o_fwd + o_bwd)/2 is written once; q, k, v, g_fwd, g_bwd are read once
+//      here.  Two instantiations: the fast form alone for the segments the state kernel flagged
+//      as mild, and the general one (both forms) for the rest.
 // Nothing is reversed or copied in HBM; both directions read the same q, k, v.
 //
 // Wavefront mapping (256 threads = 4 waves).  Wave w owns tokens [16w, 16w+16) of the chunk;
@@ -55,10 +58,11 @@
 // gates leave the matrix cores (below) in accumulator layout, lane (r, g) holding rows
 // 4g..4g+3 of each 16-row tile; the staged gate tiles therefore keep their columns permuted
 // (channel 32kk + 8g + 4h + e at column 16(2kk+h) + 4g + e) so that tile ct, row 4g+e is the
-// lane's slot 4ct + e.  Rows that are only staged (v, both gates) are fetched with fully
-// contiguous wave loads, 8 whole 128-byte rows per instruction.  Contractions over tokens (P.V, the state
-// update, the gate scan) take their token-major operands from row-major LDS tiles through
-// ds_read_b64_tr_b16.
+// lane's slot 4ct + e.  Every row tensor moves between HBM and the chip in fully contiguous
+// wave accesses, 8 whole 128-byte rows per instruction; q, k and out change between row order
+// and operand order through the wave's own rows of an idle LDS tile.  Contractions over tokens
+// (P.V, the state update, the gate scan) take their token-major operands from row-major LDS
+// tiles through ds_read_b64_tr_b16.
 //
 // Cumulative gates on the matrix cores.  The chunk-level cumulative log-gate is a product with
 // a triangular 0/1 matrix, B^T[c][t] = sum_i g[i][c] * [i <= t] (or [i >= t] backward), which
@@ -315,12 +319,6 @@ __device__ __forceinline__ void store_row16(uint16_t (*tile)[kPitch], int row, i
     *reinterpret_cast<uint4 *>(&tile[row][32 + 8 * g]) = b;
 }
 
-__device__ __forceinline__ void store_row16_raw(uint16_t (*tile)[kPitch], int row, int g, const Row16 &r)
-{
-    *reinterpret_cast<uint4 *>(&tile[row][8 * g]) = r.p[0];
-    *reinterpret_cast<uint4 *>(&tile[row][32 + 8 * g]) = r.p[1];
-}
-
 // the lane's 16 channels of a per-channel fp32 vector in LDS
 __device__ __forceinline__ void load_chan16(const float *vec, int g, float (&f)[16])
 {
@@ -342,18 +340,6 @@ __device__ __forceinline__ void store_chan16(float *vec, int g, const float (&f)
     b[0] = make_float4(f[8], f[9], f[10], f[11]);
     b[1] = make_float4(f[12], f[13], f[14], f[15]);
 }
-
-// Logical order of the four sub-blocks as seen from sub-block w in direction DIR:
-// slot 0 = w itself, slots 1..nb = the sub-blocks whose keys w's queries see (nearest first),
-// remaining slots = the sub-blocks after w (nearest first).
-template <int DIR>
-struct SubOrder {
-    int w, nb;
-    __device__ __forceinline__ explicit SubOrder(int w_) : w(w_), nb(DIR == 0 ? w_ : 3 - w_) {}
-    __device__ __forceinline__ int before(int d) const { return DIR == 0 ? w - d : w + d; }  // 1 <= d <= nb
-    __device__ __forceinline__ int after(int a) const { return DIR == 0 ? w + a : w - a; }   // 1 <= a <= 3-nb
-    __device__ __forceinline__ int slot(int s) const { return s == 0 ? w : (s <= nb ? before(s) : after(s - nb)); }
-};
 
 // Range-safe form: cumulative log2-gates of the lane's 16 channels inside its sub-block,
 // inclusive of the lane's own token, in scan order (prefix for DIR 0, suffix for DIR 1); every
@@ -513,19 +499,6 @@ __device__ __forceinline__ void chunk_gate_scan(const uint16_t (*gtile)[kPitch],
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
         B[ct] = mfma(a1, tri[1], mfma(a0, tri[0], zero));
         T[ct] = mfma(a1, ones, mfma(a0, ones, zero));
-    }
-}
-
-// The cumulative gates alone
-__device__ __forceinline__ void chunk_gate_scan(const uint16_t (*gtile)[kPitch], const bf16x8 (&tri)[2], int r, int g,
-                                                f32x4 (&B)[4])
-{
-#pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
-        const bf16x8 a0 = token_operand(gtile, 0, 1, 16 * ct, r, g);
-        const bf16x8 a1 = token_operand(gtile, 2, 3, 16 * ct, r, g);
-        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-        B[ct] = mfma(a1, tri[1], mfma(a0, tri[0], zero));
     }
 }
 
@@ -724,7 +697,7 @@ __device__ __forceinline__ void score_tiles(OutLds &sm, const int w, const int r
 template <class Prefetch>
 __device__ __forceinline__ void out_chunk_fast(OutLds &sm, const int w, const int r, const int g, const f32x4 (&Bf)[4],
                                                const f32x4 (&Bb)[4], const f32x4 (&Tf)[4], const Row16 &qraw,
-                                               const Row16 &kraw, const ChunkFlags fl, ChunkOperands &op,
+                                               const Row16 &kraw, const ChunkFlags /*fl*/, ChunkOperands &op,
                                                Prefetch &&prefetch_first)
 {
     const int row = 16 * w + r;
@@ -807,7 +780,7 @@ __device__ __forceinline__ void out_chunk_fast_fused(OutLds &sm, const bf16x8 (&
 // floored gates itself from the staged raw gates.
 template <class Prefetch>
 __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const int r, const int g, const Row16 &qraw,
-                                               const Row16 &kraw, const ChunkFlags fl, ChunkOperands &op,
+                                               const Row16 &kraw, const ChunkFlags /*fl*/, ChunkOperands &op,
                                                Prefetch &&prefetch_first)
 {
     const int row = 16 * w + r;
