@@ -550,15 +550,20 @@ __device__ __forceinline__ void load_state(const float *src, bool zero, int tid,
 }
 
 // O^T += S^T q^T for one [column][channel] state tile (readout of a state by scaled queries)
+// kKs = 1: only channels 0..31 carry data (a 32-wide head widened with zeros), the second K-step
+// is skipped.
+template <int kKs = 2>
 __device__ __forceinline__ void readout(const uint16_t (*tile)[kPitch], bf16x8 q0, bf16x8 q1, int r, int g,
                                         f32x4 (&O)[4])
 {
 #pragma unroll
     for (int jt = 0; jt < 4; ++jt) {
         const bf16x8 s0 = *reinterpret_cast<const bf16x8 *>(&tile[16 * jt + r][8 * g]);
-        const bf16x8 s1 = *reinterpret_cast<const bf16x8 *>(&tile[16 * jt + r][32 + 8 * g]);
         O[jt] = mfma(s0, q0, O[jt]);
-        O[jt] = mfma(s1, q1, O[jt]);
+        if (kKs > 1) {
+            const bf16x8 s1 = *reinterpret_cast<const bf16x8 *>(&tile[16 * jt + r][32 + 8 * g]);
+            O[jt] = mfma(s1, q1, O[jt]);
+        }
     }
 }
 
@@ -578,7 +583,9 @@ struct ChunkFlags {
 // Everything after the score tiles, common to both forms: O^T = V^T P^T + the three readouts,
 // out = O/2, then the forward state update with the keys in `ktile`.
 // fast_update: S = d (S + K^T V) with d = exp(tot); otherwise S = d S + K^T V with d = prod(eb).
-template <bool kTm, class Prefetch>
+// kKs = 1 (32-wide head, fast kernel only): state rows 32..63 are identically zero, so the waves
+// that own them (w >= 2) skip the state update and nobody reads the upper K-step of a state tile.
+template <bool kTm, int kKs, class Prefetch>
 __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)[kPitch], const ChunkOperands &op,
                                              const ChunkFlags fl, const bool fast_update, const int w, const int r,
                                              const int g, uint16_t *out_slab, const long chunk_token0, const int L,
@@ -602,9 +609,9 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
         for (int jt = 0; jt < 4; ++jt) O[jt] = mfma(vop[1][jt], pa1, mfma(vop[0][jt], pa0, zero));
     }
     prefetch(1);
-    readout(sm.st, op.qf0, op.qf1, r, g, O);
+    readout<kKs>(sm.st, op.qf0, op.qf1, r, g, O);
     prefetch(2);
-    if (fl.stash || fl.seg) readout(sm.sb, op.qb0, op.qb1, r, g, O);
+    if (fl.stash || fl.seg) readout<kKs>(sm.sb, op.qb0, op.qb1, r, g, O);
     prefetch(3);
     {  // o_t = (o_fwd_t + o_bwd_t) / 2, turned into whole rows through the wave's own rows of the
        // forward gate tile (last read before the score tiles), then written 8 rows per store
@@ -625,8 +632,11 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
     }
 
     // forward state, rows at LDS positions 16w + 4g + e
-    float4 d;
-    if (fast_update) {
+    const bool owns_rows = kKs > 1 || w < 2;
+    float4 d = make_float4(1.f, 1.f, 1.f, 1.f);
+    if (!owns_rows) {
+        // nothing to update
+    } else if (fast_update) {
         const float4 t = *reinterpret_cast<const float4 *>(&sm.tot[16 * w + 4 * g]);
         d = make_float4(fast_exp2(t.x * kLog2e), fast_exp2(t.y * kLog2e), fast_exp2(t.z * kLog2e),
                         fast_exp2(t.w * kLog2e));
@@ -642,13 +652,15 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
             S[jt][0] *= d.x; S[jt][1] *= d.y; S[jt][2] *= d.z; S[jt][3] *= d.w;
         }
     }
+    if (owns_rows) {
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        const bf16x8 a = token_operand(ktile, 2 * p, 2 * p + 1, 16 * w, r, g);
+        for (int p = 0; p < 2; ++p) {
+            const bf16x8 a = token_operand(ktile, 2 * p, 2 * p + 1, 16 * w, r, g);
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) S[jt] = mfma(a, vop[p][jt], S[jt]);
+            for (int jt = 0; jt < 4; ++jt) S[jt] = mfma(a, vop[p][jt], S[jt]);
+        }
     }
-    if (fast_update) {
+    if (fast_update && owns_rows) {
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) {
             S[jt][0] *= d.x; S[jt][1] *= d.y; S[jt][2] *= d.z; S[jt][3] *= d.w;
@@ -656,11 +668,12 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
     }
 
     __syncthreads();  // every LDS read of this step is done
-    publish_state(sm.st, w, r, g, S);
+    if (owns_rows) publish_state(sm.st, w, r, g, S);
 }
 
 // Merged score tiles of the fast form and the readout queries, from this lane's scaled operands
 // and the key tiles in LDS.
+template <int kKs = 2>
 __device__ __forceinline__ void score_tiles(OutLds &sm, const int w, const int r, const int g, const bf16x8 qf0,
                                             const bf16x8 qf1, const bf16x8 qb0, const bf16x8 qb1, const bf16x8 kf0,
                                             const bf16x8 kf1, const bf16x8 kb0, const bf16x8 kb1, ChunkOperands &op)
@@ -671,8 +684,11 @@ __device__ __forceinline__ void score_tiles(OutLds &sm, const int w, const int r
     for (int I = 0; I < 4; ++I) {
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
         if (I == w) {
-            f32x4 pf = mfma(kf1, qf1, mfma(kf0, qf0, zero));
-            f32x4 pb = mfma(kb1, qb1, mfma(kb0, qb0, zero));
+            f32x4 pf = mfma(kf0, qf0, zero), pb = mfma(kb0, qb0, zero);
+            if (kKs > 1) {
+                pf = mfma(kf1, qf1, pf);
+                pb = mfma(kb1, qb1, pb);
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int i = 4 * g + e;
@@ -681,12 +697,14 @@ __device__ __forceinline__ void score_tiles(OutLds &sm, const int w, const int r
             op.pk[I] = pack4(pf);
         } else if (I < w) {
             const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kf[16 * I + r][8 * g]);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kf[16 * I + r][32 + 8 * g]);
-            op.pk[I] = pack4(mfma(a1, qf1, mfma(a0, qf0, zero)));
+            f32x4 p = mfma(a0, qf0, zero);
+            if (kKs > 1) p = mfma(*reinterpret_cast<const bf16x8 *>(&sm.kf[16 * I + r][32 + 8 * g]), qf1, p);
+            op.pk[I] = pack4(p);
         } else {
             const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][8 * g]);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][32 + 8 * g]);
-            op.pk[I] = pack4(mfma(a1, qb1, mfma(a0, qb0, zero)));
+            f32x4 p = mfma(a0, qb0, zero);
+            if (kKs > 1) p = mfma(*reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][32 + 8 * g]), qb1, p);
+            op.pk[I] = pack4(p);
         }
     }
     op.qf0 = qf0; op.qf1 = qf1; op.qb0 = qb0; op.qb1 = qb1;
@@ -736,17 +754,20 @@ __device__ __forceinline__ void out_chunk_fast(OutLds &sm, const int w, const in
 // of one tile can overlap the LDS reads and MFMAs of the next (one basic block, no branch
 // between the scan and its use).  The forward chunk totals are the cumulative gates of the
 // chunk's last token (wave 3, r = 15).
-template <class Prefetch>
+template <int kKs, class Prefetch>
 __device__ __forceinline__ void out_chunk_fast_fused(OutLds &sm, const bf16x8 (&tri_f)[2], const bf16x8 (&tri_b)[2],
                                                      const int w, const int r, const int g, const Row16 &qraw,
                                                      const Row16 &kraw, ChunkOperands &op, Prefetch &&prefetch_first)
 {
     const int row = 16 * w + r;
+    constexpr int kCt = 2 * kKs;  // 16-channel tiles that carry data
     float qf[16], kf[16], qb[16], kb[16], tot[16];
     unpack16(qraw, qf);
     unpack16(kraw, kf);
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
+    for (int n = 4 * kCt; n < 16; ++n) qf[n] = kf[n] = qb[n] = kb[n] = tot[n] = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < kCt; ++ct) {
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
         const bf16x8 f0 = token_operand(sm.gf, 0, 1, 16 * ct, r, g), f1 = token_operand(sm.gf, 2, 3, 16 * ct, r, g);
         const bf16x8 b0 = token_operand(sm.gb, 0, 1, 16 * ct, r, g), b1 = token_operand(sm.gb, 2, 3, 16 * ct, r, g);
@@ -766,14 +787,16 @@ __device__ __forceinline__ void out_chunk_fast_fused(OutLds &sm, const bf16x8 (&
     const bf16x8 qf0 = pack8(qf), qf1 = pack8(qf + 8), qb0 = pack8(qb), qb1 = pack8(qb + 8);
     const bf16x8 kf0 = pack8(kf), kf1 = pack8(kf + 8), kb0 = pack8(kb), kb1 = pack8(kb + 8);
     *reinterpret_cast<bf16x8 *>(&sm.kf[row][8 * g]) = kf0;
-    *reinterpret_cast<bf16x8 *>(&sm.kf[row][32 + 8 * g]) = kf1;
     *reinterpret_cast<bf16x8 *>(&sm.kb[row][8 * g]) = kb0;
-    *reinterpret_cast<bf16x8 *>(&sm.kb[row][32 + 8 * g]) = kb1;
+    if (kKs > 1) {  // the upper K-step of the key tiles is never read otherwise
+        *reinterpret_cast<bf16x8 *>(&sm.kf[row][32 + 8 * g]) = kf1;
+        *reinterpret_cast<bf16x8 *>(&sm.kb[row][32 + 8 * g]) = kb1;
+    }
     if (w == 3 && r == 15) store_chan16(sm.tot, g, tot);  // for the state decay
 
     __syncthreads();  // kf, kb, tot visible
     prefetch_first();
-    score_tiles(sm, w, r, g, qf0, qf1, qb0, qb1, kf0, kf1, kb0, kb1, op);
+    score_tiles<kKs>(sm, w, r, g, qf0, qf1, qb0, qb1, kf0, kf1, kb0, kb1, op);
 }
 
 // RANGE-SAFE form of one chunk, both directions (see the header); scans the sub-block-local,
@@ -915,6 +938,11 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
     __shared__ OutLds sm;
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    // The fast kernel of a 32-wide head skips the zero half of the key dimension: one K-step per
+    // contraction over channels, no state rows (and no stash) for the waves that would own rows
+    // 32..63.  The general kernel keeps the widened form throughout.
+    constexpr int kKs = (kFastOnly && kDk == kD / 2) ? 1 : 2;
+    const bool owns_rows = kKs > 1 || w < 2;
     // A workgroup owns `units_per_block` (at most 64) consecutive (slab, segment) units and
     // skips those of the other kernel.  The fast kernel takes one unit per workgroup; the
     // general kernel, whose units are normally all skipped, takes several, and reads all their
@@ -964,12 +992,13 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
     auto fetch_stash = [&](ChunkRows &c, int m) {
         // this lane's 16 values of the chunk's stashed state (unwritten, and unused, for the
         // segment's last chunk) and the decay of its rows
+        // (waves without state rows read their first row's values instead: same cache lines, unused)
         const unsigned char *base = stash + size_t(chunk0 + min(m, nch - 1)) * kStashBytes;
-        const uint4 *p = reinterpret_cast<const uint4 *>(base) + tid;
+        const uint4 *p = reinterpret_cast<const uint4 *>(base) + (owns_rows ? tid : (tid & 127));
         c.sb.p[0] = p[0];
         c.sb.p[1] = p[kThreads];
         c.dr = *reinterpret_cast<const float4 *>(base + size_t(kD) * kD * sizeof(uint16_t) +
-                                                 (16 * w + 4 * g) * sizeof(float));
+                                                 (16 * (owns_rows ? w : (w & 1)) + 4 * g) * sizeof(float));
     };
     // part 0..5: q, k, g_fwd, g_bwd, v, stash
     auto fetch_part = [&](ChunkRows &c, int m, int part) {
@@ -986,12 +1015,12 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
     for (int part = 0; part < 6; ++part) fetch_part(next, 0, part);
 
     f32x4 S[4];
-    load_state(st_in, st_in == nullptr, tid, S);
-    publish_state(sm.st, w, r, g, S);  // made visible by the first barrier of the first step
+    load_state(st_in, st_in == nullptr || !owns_rows, tid, S);
+    if (owns_rows) publish_state(sm.st, w, r, g, S);  // made visible by the first barrier of the first step
     // backward state entering the segment from the right, kept in registers: each step adds its
     // decayed copy to the chunk's stashed state, so that one readout serves both
     f32x4 Sseg[4];
-    load_state(st_in + size_t(kD) * kD, !seg_in, tid, Sseg);
+    load_state(st_in + size_t(kD) * kD, !seg_in || !owns_rows, tid, Sseg);
     bf16x8 tri_f[2], tri_b[2];
     scan_triangle<0>(w, r, g, tri_f);
     scan_triangle<1>(w, r, g, tri_b);
@@ -1023,7 +1052,7 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
         stage_values(sm.v, w, lane, cur.v);
         wave_lds_fence();
         const Row16 q_row = bounce_load(sm.kf, row, g), k_row = bounce_load(sm.kb, row, g);
-        if (fl.stash || fl.seg) {
+        if ((fl.stash || fl.seg) && owns_rows) {
             // backward state entering the chunk from the right: the stash (accumulator order, zero
             // for the segment's last chunk) plus the segment's entering state decayed from the
             // segment's right edge to the chunk's; stored as a [column][channel] tile
@@ -1067,7 +1096,7 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
             }
         };
         if (kFastOnly) {
-            out_chunk_fast_fused(sm, tri_f, tri_b, w, r, g, q_row, k_row, op, prefetch_first);
+            out_chunk_fast_fused<kKs>(sm, tri_f, tri_b, w, r, g, q_row, k_row, op, prefetch_first);
         } else {
             f32x4 Tb[4];
             chunk_gate_scan(sm.gf, tri_f, r, g, Bf, Tf);
@@ -1086,7 +1115,7 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
 #pragma unroll
             for (int part = 0; part < 6; ++part) fetch_part(next, m + 1, part);
         }
-        finish_chunk<kTm>(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L, val_stride, S,
+        finish_chunk<kTm, kKs>(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L, val_stride, S,
                      prefetch_second_half);
     }
     }  // units
