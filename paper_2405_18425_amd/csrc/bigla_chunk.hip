@@ -488,12 +488,16 @@ __device__ __forceinline__ void scan_triangle(int w, int r, int g, bf16x8 (&tri)
 // Cumulative log-gates of the chunk on the matrix cores (natural-log units): B[ct][e] is the
 // inclusive cumulative gate, since the chunk edge of the direction, of channel 16ct + 4g + e
 // (slot 4ct + e) at the lane's own token; T[ct][e] is the chunk total of the same channel.
+// kCt < 4: only the first kCt channel tiles carry data (a 32-wide head), the others are zero.
+template <int kCt = 4>
 __device__ __forceinline__ void chunk_gate_scan(const uint16_t (*gtile)[kPitch], const bf16x8 (&tri)[2], int r, int g,
                                                 f32x4 (&B)[4], f32x4 (&T)[4])
 {
     const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
+    for (int ct = kCt; ct < 4; ++ct) B[ct] = T[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ct = 0; ct < kCt; ++ct) {
         const bf16x8 a0 = token_operand(gtile, 0, 1, 16 * ct, r, g);
         const bf16x8 a1 = token_operand(gtile, 2, 3, 16 * ct, r, g);
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -1174,6 +1178,11 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     bf16x8 tri_f[2], tri_b[2];
     scan_triangle<0>(w, r, g, tri_f);
     scan_triangle<1>(w, r, g, tri_b);
+    // A 32-wide head: channels 32..63 are zero padding.  The fast form skips them (half the
+    // channel tiles in the scans, half the slots in the scalings, no K^T V for the waves that
+    // own state rows 32..63, which stay zero); the range-safe form keeps the widened arithmetic.
+    constexpr int kCt = kDk / 16, kSlots = kDk / 4;
+    const bool owns_rows = 16 * w < kDk;
 
     for (int m = nch - 1; m >= 0; --m) {
         ChunkRows cur = next;
@@ -1217,12 +1226,12 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         {
             f32x4 T[4];
             float t[16];
-            chunk_gate_scan(sm.g[0], tri_f, r, g, Bf, T);
+            chunk_gate_scan<kCt>(sm.g[0], tri_f, r, g, Bf, T);
             max_f = chunk_decay_max(T);
 #pragma unroll
             for (int n = 0; n < 16; ++n) t[n] = T[n >> 2][n & 3];
             if (r == 0) store_chan16(sm.tot[0], g, t);  // chunk totals per channel, operand order
-            chunk_gate_scan(sm.g[1], tri_b, r, g, Bb, T);
+            chunk_gate_scan<kCt>(sm.g[1], tri_b, r, g, Bb, T);
             max_b = chunk_decay_max(T);
 #pragma unroll
             for (int n = 0; n < 16; ++n) t[n] = T[n >> 2][n & 3];
@@ -1237,7 +1246,9 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
             // keys k * exp(-b_i), b_i cumulative since the chunk edge of each direction
             float kb[16];
 #pragma unroll
-            for (int n = 0; n < 16; ++n) {
+            for (int n = kSlots; n < 16; ++n) kb[n] = kf[n] = 0.f;
+#pragma unroll
+            for (int n = 0; n < kSlots; ++n) {
                 kb[n] = kf[n] * fast_exp2(-kLog2e * Bb[n >> 2][n & 3]);
                 kf[n] = kf[n] * fast_exp2(-kLog2e * Bf[n >> 2][n & 3]);
             }
@@ -1303,15 +1314,17 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
             // fast: S_b = db * (S_b + Kb^T V) accumulates onto the state; safe: S_b = db * S_b + Kb^T V
             Cb[jt] = fast ? Sb[jt] : f32x4{0.f, 0.f, 0.f, 0.f};
         }
+        if (owns_rows) {
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const bf16x8 af = token_operand(sm.ks[0], 2 * p, 2 * p + 1, 16 * w, r, g);
-            const bf16x8 ab = token_operand(sm.ks[1], 2 * p, 2 * p + 1, 16 * w, r, g);
+            for (int p = 0; p < 2; ++p) {
+                const bf16x8 af = token_operand(sm.ks[0], 2 * p, 2 * p + 1, 16 * w, r, g);
+                const bf16x8 ab = token_operand(sm.ks[1], 2 * p, 2 * p + 1, 16 * w, r, g);
 #pragma unroll
-            for (int jt = 0; jt < 4; ++jt) {
-                const bf16x8 vb = token_operand(sm.v, 2 * p, 2 * p + 1, 16 * jt, r, g);
-                Cf[jt] = mfma(af, vb, Cf[jt]);
-                Cb[jt] = mfma(ab, vb, Cb[jt]);
+                for (int jt = 0; jt < 4; ++jt) {
+                    const bf16x8 vb = token_operand(sm.v, 2 * p, 2 * p + 1, 16 * jt, r, g);
+                    Cf[jt] = mfma(af, vb, Cf[jt]);
+                    Cb[jt] = mfma(ab, vb, Cb[jt]);
+                }
             }
         }
         // forward: chunk state at its own right edge is df * Cf (fast) or Cf (safe); scale by the
