@@ -267,3 +267,40 @@ def test_locality_token_major_layout(dtype, Hg, Wg, H, dv):
     ref = oracle.locality_gate(wl.widen(s["v"], dtype), wl.widen(s["conv_w"], dtype), wl.widen(s["gate_logits"], dtype),
                                wl.widen(wl.from_torch(og, dtype), dtype), Hg, Wg)
     assert_close(wl.widen(wl.from_torch(out_hm, dtype), dtype), ref, 8e-3 if dtype == "bf16" else 1e-5, "tm")
+
+
+def test_bigla_seeded_random_shapes():
+    """A seeded sweep over shapes, head widths, layouts, dtypes and gate regimes (mild, mixed,
+    harsh), each case against the oracle."""
+    import torch
+    from paper_2405_18425_amd import binding as vb
+
+    rng = np.random.default_rng(2024)
+    for case in range(36):
+        dtype = "bf16" if case % 4 else "f32"
+        dk, dv = ((64, 64), (32, 64), (16, 16), (32, 32), (64, 32), (16, 64))[int(rng.integers(6))]
+        if dtype == "bf16" and case % 3:
+            dk, dv = ((64, 64), (32, 64))[case % 2]          # mostly the MFMA path
+        B, H = int(rng.integers(1, 5)), int(rng.integers(1, 8))
+        L = int(rng.choice([1, 3, 31, 64, 65, 100, 192, 200, 449, 777, 1024, 1300]))
+        layout = "blhd" if rng.random() < 0.4 else "bhld"
+        regime = ("mild", "mixed", "harsh")[int(rng.integers(3))]
+        w = wl.Workload(f"rand{case}", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=dv, dtype=dtype,
+                        gate_mu={"mild": 1.0, "mixed": -1.0, "harsh": -3.0}[regime])
+        _say(f"random case {case}: {w} layout={layout} regime={regime}")
+        s_ = wl.generate(w, seed=1000 + case, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+        if regime != "mild":
+            for name in ("g_fwd", "g_bwd"):
+                g = wl.widen(s_[name], dtype)
+                spikes = rng.random(g.shape) < (0.01 if regime == "mixed" else 0.2)
+                g[spikes] = -float(rng.choice([2.0, 6.0, 25.0]))
+                s_[name] = wl.store(g, dtype)
+        t = {n: wl.to_torch(a, dtype, "cuda:0") for n, a in s_.items()}
+        if layout == "blhd":
+            t = {n: a.permute(0, 2, 1, 3).contiguous() for n, a in t.items()}
+        out = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], layout=layout)
+        torch.cuda.synchronize()
+        if layout == "blhd":
+            out = out.permute(0, 2, 1, 3).contiguous()
+        got = wl.widen(wl.from_torch(out, dtype), dtype)
+        assert_close(got, run_bigla_oracle(s_, dtype), TOL[dtype], f"random case {case}")
