@@ -442,6 +442,9 @@ inline Plan make_plan(long BH, int L)
     long want = kTargetWorkgroups / (BH > 0 ? BH : 1);
     if (want < 1) want = 1;
     if (want > p.n_chunks) want = p.n_chunks;
+    // short sequences with at least half a chip of slabs: one segment per slab saves the scan
+    // launch and the segment states, which outweighs the longer walk (measured at L = 196)
+    if (BH >= 128 && p.n_chunks <= 4) want = 1;
     p.seg_chunks = int((p.n_chunks + want - 1) / want);
     p.n_seg = (p.n_chunks + p.seg_chunks - 1) / p.seg_chunks;
     return p;
