@@ -132,10 +132,10 @@ int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, con
 typedef enum {
     VIG_KERNEL_SEGMENT_STATE = 0, /* chunkwise path, launch 1: segment end states + stash     */
     VIG_KERNEL_STATE_SCAN = 1,    /* chunkwise path, launch 2: scan over segment states       */
-    VIG_KERNEL_SEGMENT_OUT = 2,   /* chunkwise path, launch 3: output pass, fast-form segments */
+    VIG_KERNEL_SEGMENT_OUT = 2,   /* chunkwise path, launch 3: output pass                    */
     VIG_KERNEL_RECURRENT = 3,     /* exact fp32 recurrence                                    */
     VIG_KERNEL_LOCALITY_GATE = 4, /* depthwise conv + gate                                    */
-    VIG_KERNEL_SEGMENT_OUT_GENERAL = 5 /* chunkwise path, launch 4: output pass, other segments */
+    VIG_KERNEL_SEGMENT_OUT_GENERAL = 5 /* chunkwise path, output pass of single-chunk sequences  */
 } vig_kernel;
 int vig_timing_enable(int on);
 int vig_timing_collect(int kernel, double *total_ms, long *launches);

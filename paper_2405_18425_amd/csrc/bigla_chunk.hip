@@ -47,8 +47,8 @@
 //      registers, ONE backward readout from the stash tile to which the segment's entering
 //      state (scaled per channel by the stashed decay) has been added, then the forward state
 //      update.  out = (o_fwd + o_bwd)/2 is written once; q, k, v, g_fwd, g_bwd are read once
-//      here.  Two instantiations: the fast form alone for the segments the state kernel flagged
-//      as mild, and the general one (both forms) for the rest.
+//      here.  Segments the state kernel flagged as mild run fast-form-only code inlined in the
+//      kernel; the others call the general code (both forms) as a separate function.
 // Nothing is reversed or copied in HBM; both directions read the same q, k, v.
 //
 // Wavefront mapping (256 threads = 4 waves).  Wave w owns tokens [16w, 16w+16) of the chunk;
@@ -590,7 +590,7 @@ struct ChunkFlags {
 // Everything after the score tiles, common to both forms: O^T = V^T P^T + the three readouts,
 // out = O/2, then the forward state update with the keys in `ktile`.
 // fast_update: S = d (S + K^T V) with d = exp(tot); otherwise S = d S + K^T V with d = prod(eb).
-// kKs = 1 (32-wide head, fast kernel only): state rows 32..63 are identically zero, so the waves
+// kKs = 1 (32-wide head, fast-form code only): state rows 32..63 are identically zero, so the waves
 // that own them (w >= 2) skip the state update and nobody reads the upper K-step of a state tile.
 template <bool kTm, int kKs, class Prefetch>
 __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)[kPitch], const ChunkOperands &op,
@@ -933,44 +933,28 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
 //                     footprint would otherwise spill into the fast path); other segments exit.
 // kFastOnly = false: handles the remaining segments (all of them when seg_mild is nullptr), each
 //                     chunk choosing its form.
+// The output kernel's LDS, at namespace scope so that the inlined fast-form code and the
+// separately compiled general code address the same allocation as LDS (not through a generic
+// reference).
+__shared__ OutLds g_out_lds;
+
 template <bool kFastOnly, int kDk, bool kTm>
-__global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out_kernel(
+__device__ __forceinline__ void out_unit(
     const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
     const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
-    const float *__restrict__ seg_states /* states entering each segment, nullptr when one segment */,
-    const int *__restrict__ seg_mild /* per (slab, segment): every chunk admits the fast form; may be nullptr */,
-    const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg, long total_units,
-    int units_per_block, int heads /* used when kTm: activations are [B,L,H,d] */)
+    const float *__restrict__ seg_states, const unsigned char *__restrict__ stash_all, int L, int n_chunks,
+    int seg_chunks, int n_seg, const long unit, int heads)
 {
-    __shared__ OutLds sm;
+    OutLds &sm = g_out_lds;
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
-    // The fast kernel of a 32-wide head skips the zero half of the key dimension: one K-step per
+    // The fast-form code of a 32-wide head skips the zero half of the key dimension: one K-step per
     // contraction over channels, no state rows (and no stash) for the waves that would own rows
-    // 32..63.  The general kernel keeps the widened form throughout.
+    // 32..63.  The general code keeps the widened form throughout.
     constexpr int kKs = (kFastOnly && kDk == kD / 2) ? 1 : 2;
     const bool owns_rows = kKs > 1 || w < 2;
-    // A workgroup owns `units_per_block` (at most 64) consecutive (slab, segment) units and
-    // skips those of the other kernel.  The fast kernel takes one unit per workgroup; the
-    // general kernel, whose units are normally all skipped, takes several, and reads all their
-    // flags with one load per lane so that an idle launch drains after a single memory round trip.
-    const long first_unit = long(blockIdx.x) * units_per_block;
-    unsigned long long todo;
-    {
-        const long u = first_unit + lane;
-        bool mine = false;
-        if (lane < units_per_block && u < total_units) {
-            const bool mild = seg_mild != nullptr && seg_mild[u] != 0;
-            mine = mild == kFastOnly;
-        }
-        todo = __ballot(mine);  // the same in every wave of the workgroup
-    }
-    while (todo != 0) {
-    const long unit = first_unit + __builtin_ctzll(todo);
-    todo &= todo - 1;
     const long slab = unit / n_seg;
     const int seg = int(unit % n_seg);
-    __syncthreads();  // LDS of a previous unit is no longer read
     // first row of the slab and distance between its tokens, in rows of the tensor
     const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
     const unsigned key_stride = unsigned(heads) * kDk, val_stride = unsigned(heads) * kD;
@@ -1017,9 +1001,13 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
         if (part == 4) c.v = load_rows_staged<false, kD, kTm>(v, t0, w, lane, L, val_stride);
         if (part == 5) fetch_stash(c, m);
     };
+    // The general code, short of registers, fetches a chunk's rows at the start of its step
+    // instead of one step ahead (measured faster there).
     ChunkRows next;
+    if (kFastOnly) {
 #pragma unroll
-    for (int part = 0; part < 6; ++part) fetch_part(next, 0, part);
+        for (int part = 0; part < 6; ++part) fetch_part(next, 0, part);
+    }
 
     f32x4 S[4];
     load_state(st_in, st_in == nullptr || !owns_rows, tid, S);
@@ -1033,6 +1021,10 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
     scan_triangle<1>(w, r, g, tri_b);
 
     for (int m = 0; m < nch; ++m) {
+        if (!kFastOnly) {
+#pragma unroll
+            for (int part = 0; part < 6; ++part) fetch_part(next, m, part);
+        }
         ChunkRows cur = next;
         if (long(chunk0 + m + 1) * kC > L) {  // ragged final chunk of the sequence (uniform branch)
             const long t0 = long(chunk0 + m) * kC;
@@ -1087,9 +1079,8 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
         f32x4 Bf[4], Tf[4], Bb[4];
         ChunkOperands op;
         bool fast = true;
-        // fast kernel: q and k after the barrier of the first half, both gates after the score
-        // tiles, v and the stash after the readouts (finer splits measured slower); the general
-        // kernel requests everything between the halves
+        // fast code: q and k after the barrier of the first half, both gates after the score
+        // tiles, v and the stash after the readouts (finer splits measured slower)
         auto prefetch_first = [&]() {
             if (kFastOnly) {
                 fetch_part(next, m + 1, 0);
@@ -1118,14 +1109,42 @@ __global__ __launch_bounds__(kThreads, kFastOnly ? 2 : 1) void bigla_segment_out
         if (kFastOnly) {
             fetch_part(next, m + 1, 2);
             fetch_part(next, m + 1, 3);
-        } else {
-#pragma unroll
-            for (int part = 0; part < 6; ++part) fetch_part(next, m + 1, part);
         }
         finish_chunk<kTm, kKs>(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L, val_stride, S,
                      prefetch_second_half);
     }
-    }  // units
+}
+
+template <int kDk, bool kTm>
+__device__ __attribute__((noinline)) void out_unit_general(
+    const uint16_t *q_all, const uint16_t *k_all, const uint16_t *v_all, const uint16_t *gf_all, const uint16_t *gb_all,
+    uint16_t *out_all, const float *seg_states, const unsigned char *stash_all, int L, int n_chunks, int seg_chunks,
+    int n_seg, const long unit, int heads)
+{
+    out_unit<false, kDk, kTm>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L, n_chunks,
+                              seg_chunks, n_seg, unit, heads);
+}
+
+// One workgroup per (slab, segment) unit.  kByFlag: units the state kernel flagged as mild run the
+// fast-form code inline; the others call the general code as a real function, so that its
+// register appetite (spilled to its own stack frame) does not touch the fast path's allocation
+// and one launch serves both.  !kByFlag (single-chunk sequences, no flags): general code only.
+template <bool kByFlag, int kDk, bool kTm>
+__global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
+    const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
+    const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
+    const float *__restrict__ seg_states /* states entering each segment, nullptr when one segment */,
+    const int *__restrict__ seg_mild /* per unit: every chunk admits the fast form (kByFlag) */,
+    const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg,
+    int heads /* used when kTm: activations are [B,L,H,d] */)
+{
+    const long unit = blockIdx.x;
+    if (kByFlag && seg_mild[unit] != 0)  // uniform over the workgroup
+        out_unit<true, kDk, kTm>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L, n_chunks,
+                                 seg_chunks, n_seg, unit, heads);
+    else
+        out_unit_general<kDk, kTm>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
+                                   n_chunks, seg_chunks, n_seg, unit, heads);
 }
 
 // ---- kernel 1: per-segment end states and per-chunk backward stash -----------------------------
@@ -1457,22 +1476,16 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
     const float *seg_in = p.n_seg > 1 ? seg_states : nullptr;
     const int *flags = p.n_chunks > 1 ? seg_mild : nullptr;
     uint16_t *oo = static_cast<uint16_t *>(out);
-    if (flags) {  // segments the state kernel flagged as entirely within the fast form's range
-        LaunchTimer timer(kKernelSegmentOut, stream);
-        hipLaunchKernelGGL((bigla_segment_out_kernel<true, kDk, kTm>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk, vv,
-                           gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, blocks, 1,
-                           heads_token_major);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    {  // every other segment; its workgroups leave at once where the launch above did the work
-        LaunchTimer timer(kKernelSegmentOutGeneral, stream);
-        // about one workgroup per CU (this kernel runs one per CU), at most 64 units each
-        long per_block = flags ? (blocks + 255) / 256 : 1;
-        if (per_block > 64) per_block = 64;
-        hipLaunchKernelGGL((bigla_segment_out_kernel<false, kDk, kTm>), dim3((unsigned)((blocks + per_block - 1) / per_block)),
-                           dim3(kThreads), 0, stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks,
-                           p.seg_chunks, p.n_seg, blocks, int(per_block), heads_token_major);
+    {
+        LaunchTimer timer(flags ? kKernelSegmentOut : kKernelSegmentOutGeneral, stream);
+        if (flags)
+            hipLaunchKernelGGL((bigla_segment_out_kernel<true, kDk, kTm>), dim3((unsigned)blocks), dim3(kThreads), 0,
+                               stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks,
+                               p.n_seg, heads_token_major);
+        else  // a single chunk per sequence: no state kernel has run, no flags exist
+            hipLaunchKernelGGL((bigla_segment_out_kernel<false, kDk, kTm>), dim3((unsigned)blocks), dim3(kThreads), 0,
+                               stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks,
+                               p.n_seg, heads_token_major);
     }
     return hipGetLastError();
 }
