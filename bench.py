@@ -35,7 +35,7 @@ CACHE_BYTES = 256 << 20        # Infinity Cache; buffer sets rotate over more th
 # profiles/bigla_path_vig_s_1024.md (read + written, calibrated with a plain copy), keyed by
 # (kernel, workload); None for pairs that were not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("segment_out", "vig_s_1024"): 194.6e6,
+    ("segment_out", "vig_s_1024"): 195.1e6,
     ("segment_state", "vig_s_1024"): 138.9e6,
     ("state_scan", "vig_s_1024"): 32.5e6,
     ("locality_gate", "vig_s_1024"): 116.2e6,
