@@ -49,6 +49,8 @@ class Oracle:
         lib.bigla_ref_f64.restype = ctypes.c_int
         lib.locality_gate_ref_f64.argtypes = [dp] * 6 + [ctypes.c_int] * 6
         lib.locality_gate_ref_f64.restype = ctypes.c_int
+        lib.gate_producer_ref_f64.argtypes = [dp] * 6 + [ctypes.c_int] * 6 + [ctypes.c_double, ctypes.c_int]
+        lib.gate_producer_ref_f64.restype = ctypes.c_int
         lib.oracle_max_threads.restype = ctypes.c_int
         self._lib = lib
 
@@ -106,6 +108,33 @@ class Oracle:
             raise RuntimeError(f"locality_gate_ref_f64 failed ({rc})")
         return out
 
+    def gate_producer(self, x, w1, w2, H: int, dk: int, bias=None, tau: float = 16.0, nthreads: int = 0):
+        """(g_fwd, g_bwd), each [B,H,L,dk]: log forget gates log(sigmoid((x W1) W2 + b)) / tau
+        (Section 3 and Eq. (BiGLA) lines 1-2), float64.
+
+        x: [B,L,D]; w1: [D,rank]; w2: [rank, 2*H*dk] (forward half first, heads in order);
+        bias: [2*H*dk] or None.
+        """
+        x = _c64(x)
+        if x.ndim != 3:
+            raise ValueError("x must be [B,L,D]")
+        B, L, D = x.shape
+        w1 = _c64(w1)
+        if w1.ndim != 2 or w1.shape[0] != D:
+            raise ValueError("w1 must be [D,rank]")
+        rank = w1.shape[1]
+        w2 = _c64(w2, (rank, 2 * H * dk))
+        b = None if bias is None else _c64(bias, (2 * H * dk,))
+        gf = np.empty((B, H, L, dk), dtype=np.float64)
+        gb = np.empty_like(gf)
+        if gf.size == 0:
+            return gf, gb
+        rc = self._lib.gate_producer_ref_f64(_ptr(x), _ptr(w1), _ptr(w2), _ptr(b) if b is not None else None,
+                                             _ptr(gf), _ptr(gb), B, H, L, D, rank, dk, float(tau), int(nthreads))
+        if rc != 0:
+            raise RuntimeError(f"gate_producer_ref_f64 failed ({rc})")
+        return gf, gb
+
 
 def default() -> Oracle:
     global _default
@@ -124,3 +153,7 @@ def bigla(q, k, v, g_fwd, g_bwd, nthreads: int = 0) -> np.ndarray:
 
 def locality_gate(x, w, gate_logits, o_global, Hg: int, Wg: int, bias=None, nthreads: int = 0) -> np.ndarray:
     return default().locality_gate(x, w, gate_logits, o_global, Hg, Wg, bias, nthreads)
+
+
+def gate_producer(x, w1, w2, H: int, dk: int, bias=None, tau: float = 16.0, nthreads: int = 0):
+    return default().gate_producer(x, w1, w2, H, dk, bias, tau, nthreads)

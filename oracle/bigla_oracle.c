@@ -11,6 +11,9 @@
  *                             run token by token, then averaged.
  *   - locality_gate_ref_f64 : Section 4.2.2 (depthwise 3x3 convolution on the
  *                             patch grid, sigmoid gate, convex blend).
+ *   - gate_producer_ref_f64 : the direction-wise forget gates, first two lines
+ *                             of Eq. (BiGLA) with the low-rank gate of Section 3,
+ *                             returned as log-gates.
  * No blocking, chunking, fusion or reordering is applied.
  *
  * Pins (tests/test_oracle_pins.py): explicit-product quadratic form by brute
@@ -164,4 +167,70 @@ int locality_gate_ref_f64(const double *x, const double *w, const double *bias,
                 }
     }
     return 0;
+}
+
+/* log(sigmoid(z)) without overflow: min(z, 0) - log(1 + exp(-|z|)), the same function. */
+static double log_sigmoid(double z)
+{
+    return (z < 0.0 ? z : 0.0) - log1p(exp(-fabs(z)));
+}
+
+/*
+ * Direction-wise forget gates, Eq. (BiGLA) lines 1-2 (Section 4.2.1) with the low-rank gate of
+ * Section 3:
+ *   z_t     = (x_t W1) W2 + b               in R^{2*H*dk}
+ *   alpha_t = sigmoid(z_t)^(1/tau)
+ *   split   : entries [0, H*dk) are the forward gates, [H*dk, 2*H*dk) the backward gates;
+ *             inside each half head h owns entries [h*dk, (h+1)*dk)
+ * Returned as LOG gates g = log(alpha) = log(sigmoid(z)) / tau  (<= 0).
+ *   x : [B, L, D]   w1 : [D, rank]   w2 : [rank, 2*H*dk]   bias : [2*H*dk] or NULL
+ *   g_fwd, g_bwd : [B, H, L, dk]
+ * The product is evaluated in the printed order: first the rank-wide x_t W1, then times W2.
+ */
+int gate_producer_ref_f64(const double *x, const double *w1, const double *w2, const double *bias,
+                          double *g_fwd, double *g_bwd, int B, int H, int L, int D, int rank, int dk,
+                          double tau, int nthreads)
+{
+    if (!x || !w1 || !w2 || !g_fwd || !g_bwd) return -1;
+    if (B <= 0 || H <= 0 || L <= 0 || D <= 0 || rank <= 0 || dk <= 0 || !(tau > 0.0)) return -1;
+    const long tokens = (long)B * L;
+    const int half = H * dk, width = 2 * half;
+    int failed = 0;
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#pragma omp parallel
+#else
+    (void)nthreads;
+#endif
+    {
+        double *low = (double *)malloc(sizeof(double) * (size_t)rank);
+        if (!low) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        } else {
+#ifdef _OPENMP
+#pragma omp for schedule(static)
+#endif
+            for (long n = 0; n < tokens; ++n) {
+                const long b = n / L, t = n % L;
+                const double *xt = x + (size_t)n * D;
+                for (int r = 0; r < rank; ++r) {
+                    double acc = 0.0;
+                    for (int i = 0; i < D; ++i) acc += xt[i] * w1[(size_t)i * rank + r];
+                    low[r] = acc;
+                }
+                for (int c = 0; c < width; ++c) {
+                    double z = bias ? bias[c] : 0.0;
+                    for (int r = 0; r < rank; ++r) z += low[r] * w2[(size_t)r * width + c];
+                    const int dir = c / half, h = (c % half) / dk, j = c % dk;
+                    double *g = dir == 0 ? g_fwd : g_bwd;
+                    g[(((size_t)b * H + h) * L + t) * dk + j] = log_sigmoid(z) / tau;
+                }
+            }
+        }
+        free(low);
+    }
+    return failed ? -1 : 0;
 }

@@ -284,3 +284,108 @@ def pin_loc_channel_mapping(loc):
 
 LOC_PINS = (pin_loc_library_conv, pin_loc_centre_delta_and_gate_limits, pin_loc_single_tap_shifts,
             pin_loc_ones_kernel_counts, pin_loc_channel_mapping)
+
+
+# --------------------------------------------------------------------------- #
+# Gate producer (Section 3 gate; Eq. (BiGLA) lines 1-2).  gp(x, w1, w2, H, dk, bias, tau) ->
+# (g_fwd, g_bwd), each [B,H,L,dk], log gates.
+# --------------------------------------------------------------------------- #
+def _gp_draw(seed, B=2, L=7, D=10, rank=4, H=3, dk=5):
+    r = _rng(seed)
+    return (r.standard_normal((B, L, D)), r.standard_normal((D, rank)) / 2, r.standard_normal((rank, 2 * H * dk)),
+            r.standard_normal(2 * H * dk), H, dk)
+
+
+def _gp_split(z, H, dk):
+    """[B,L,2*H*dk] -> two [B,H,L,dk]: forward half first, heads in order inside each half."""
+    B, L, _ = z.shape
+    f = z[..., :H * dk].reshape(B, L, H, dk).transpose(0, 2, 1, 3)
+    b = z[..., H * dk:].reshape(B, L, H, dk).transpose(0, 2, 1, 3)
+    return f, b
+
+
+def pin_gp_library_matmul(gp):
+    """alpha = sigmoid((x W1) W2 + b)^(1/tau) with library matmuls and the formula as printed
+    (valid where exp does not overflow); checked as alpha, i.e. through exp of the log gate."""
+    x, w1, w2, b, H, dk = _gp_draw(1)
+    for tau in (16.0, 1.0, 3.5):
+        gf, gb = gp(x, w1, w2, H, dk, b, tau)
+        alpha = (1.0 / (1.0 + np.exp(-((x @ w1) @ w2 + b)))) ** (1.0 / tau)
+        af, ab = _gp_split(alpha, H, dk)
+        _close(np.exp(gf), af)
+        _close(np.exp(gb), ab)
+        assert np.all(gf <= 0) and np.all(gb <= 0)
+
+
+def pin_gp_zero_projection_gives_bias_gate(gp):
+    """W2 = 0 (or x = 0): every token gets log(sigmoid(b))/tau; no bias at all: log(1/2)/tau."""
+    x, w1, w2, b, H, dk = _gp_draw(2)
+    gf, gb = gp(x, w1, np.zeros_like(w2), H, dk, b, 16.0)
+    ref = np.log(1.0 / (1.0 + np.exp(-b))) / 16.0
+    _close(gf, np.broadcast_to(ref[:H * dk].reshape(1, H, 1, dk), gf.shape))
+    _close(gb, np.broadcast_to(ref[H * dk:].reshape(1, H, 1, dk), gb.shape))
+    gf, gb = gp(np.zeros_like(x), w1, w2, H, dk, None, 16.0)
+    _close(gf, np.full(gf.shape, np.log(0.5) / 16.0))
+    _close(gb, np.full(gb.shape, np.log(0.5) / 16.0))
+
+
+def pin_gp_split_and_head_mapping(gp):
+    """One non-zero column of W2 (bias 0) moves exactly one (direction, head, channel) away from
+    log(1/2)/tau: column c < H*dk is forward head c // dk channel c % dk, the rest backward."""
+    x, w1, w2, b, H, dk = _gp_draw(3)
+    base = np.log(0.5) / 16.0
+    for c in (0, dk - 1, dk, H * dk - 1, H * dk, H * dk + dk + 2, 2 * H * dk - 1):
+        w = np.zeros_like(w2)
+        w[:, c] = w2[:, c]
+        gf, gb = gp(x, w1, w, H, dk, None, 16.0)
+        moved_f = np.abs(gf - base) > 1e-9
+        moved_b = np.abs(gb - base) > 1e-9
+        d, h, j = c // (H * dk), (c % (H * dk)) // dk, c % dk
+        want = np.zeros(gf.shape, dtype=bool)
+        want[:, h, :, j] = True
+        if d == 0:
+            assert np.array_equal(moved_f, want) and not moved_b.any()
+        else:
+            assert np.array_equal(moved_b, want) and not moved_f.any()
+
+
+def pin_gp_low_rank_null_space(gp):
+    """Whatever lies in the null space of W1^T cannot change the gates (the gate sees x only
+    through the rank-wide product x W1), and the pre-activation is linear in x."""
+    x, w1, w2, b, H, dk = _gp_draw(4, D=10, rank=3)
+    qmat, _ = np.linalg.qr(w1, mode="complete")
+    null = qmat[:, 3:]                                    # D x (D - rank), orthogonal to span(W1)
+    r = _rng(40)
+    x2 = x + r.standard_normal(x.shape[:2] + (null.shape[1],)) @ null.T
+    a = gp(x, w1, w2, H, dk, b, 16.0)
+    c = gp(x2, w1, w2, H, dk, b, 16.0)
+    _close(c[0], a[0], 1e-10)
+    _close(c[1], a[1], 1e-10)
+    # logit(alpha^tau) is affine in x: second difference vanishes
+    def logit(g):  # log(p / (1 - p)) with p = exp(16 g), 1 - p taken as -expm1 to keep its digits
+        return 16.0 * g - np.log(-np.expm1(16.0 * g))
+    y = r.standard_normal(x.shape)
+    l0, l1, l2 = (logit(gp(x + s * y, w1, w2, H, dk, b, 16.0)[0]) for s in (0.0, 1.0, 2.0))
+    _close(l2 - 2 * l1 + l0, np.zeros_like(l0), 1e-8)
+
+
+def pin_gp_saturation(gp):
+    """Far into either tail the log gate is z/tau (z << 0) or -exp(-z)/tau (z >> 0): no overflow,
+    no -inf, and the tau-th power of alpha is still the sigmoid."""
+    B, L, D, rank, H, dk = 1, 4, 2, 1, 1, 2
+    x = np.array([[[1.0, 0.0], [-1.0, 0.0], [50.0, 0.0], [-50.0, 0.0]]])
+    w1 = np.array([[1.0], [0.0]])
+    w2 = np.array([[20.0, -20.0, 20.0, -20.0]])           # z = +-20 x[.,0]
+    gf, gb = gp(x, w1, w2, H, dk, None, 16.0)
+    z = 20.0 * x[0, :, 0]
+    for t in range(L):
+        for j, sgn in enumerate((1.0, -1.0)):
+            zz = sgn * z[t]
+            want = zz / 16.0 if zz < -30 else (-np.exp(-zz) / 16.0 if zz > 30 else np.log(1 / (1 + np.exp(-zz))) / 16.0)
+            assert np.isfinite(gf[0, 0, t, j])
+            assert abs(gf[0, 0, t, j] - want) <= 1e-12 * max(1.0, abs(want)), (t, j, gf[0, 0, t, j], want)
+            assert gb[0, 0, t, j] == gf[0, 0, t, j]
+
+
+GP_PINS = (pin_gp_library_matmul, pin_gp_zero_projection_gives_bias_gate, pin_gp_split_and_head_mapping,
+           pin_gp_low_rank_null_space, pin_gp_saturation)

@@ -10,7 +10,7 @@ import subprocess
 import pytest
 
 import oracle
-from oracle_pins import BIGLA_PINS, LOC_PINS
+from oracle_pins import BIGLA_PINS, GP_PINS, LOC_PINS
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "bigla_oracle.c")
 
@@ -44,6 +44,17 @@ MUTANTS = [
     ("gate_sign", "exp(-z[o])", "exp(z[o])", None, "loc"),
     ("channel_ignores_head", "const int c = h * dv + j;", "const int c = j;", None, "loc"),
     ("bias_outside_gate", "double local = bias ? bias[c] : 0.0;", "double local = 0.0;", None, "loc"),
+    ("gp_halves_swapped", "double *g = dir == 0 ? g_fwd : g_bwd;", "double *g = dir == 0 ? g_bwd : g_fwd;", None, "gp"),
+    ("gp_heads_interleaved", "const int dir = c / half, h = (c % half) / dk, j = c % dk;",
+     "const int dir = c / half, h = (c % half) % H, j = (c % half) / H;", None, "gp"),
+    ("gp_w1_transposed", "acc += xt[i] * w1[(size_t)i * rank + r];", "acc += xt[i] * w1[(size_t)r * D + i];", None, "gp"),
+    ("gp_w2_transposed", "z += low[r] * w2[(size_t)r * width + c];", "z += low[r] * w2[(size_t)c * rank + r];", None, "gp"),
+    ("gp_no_temperature", "log_sigmoid(z) / tau;", "log_sigmoid(z);", None, "gp"),
+    ("gp_temperature_inside", "log_sigmoid(z) / tau;", "log_sigmoid(z / tau);", None, "gp"),
+    ("gp_bias_dropped", "double z = bias ? bias[c] : 0.0;", "double z = 0.0;", None, "gp"),
+    ("gp_sigmoid_sign", "return (z < 0.0 ? z : 0.0) - log1p(exp(-fabs(z)));", "return (z > 0.0 ? -z : 0.0) - log1p(exp(-fabs(z)));", None, "gp"),
+    ("gp_naive_log_sigmoid", "return (z < 0.0 ? z : 0.0) - log1p(exp(-fabs(z)));", "return log(1.0 / (1.0 + exp(-z)));", None, "gp"),
+    ("gp_token_batch_swapped", "const long b = n / L, t = n % L;", "const long b = n % B, t = n / B;", None, "gp"),
 ]
 
 
@@ -89,8 +100,8 @@ def test_mutant_is_caught(tmp_path, name, old, new, occ, which):
     subprocess.run(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-w", "-o", str(so_path),
                     str(c_path), "-lm"], check=True)
     mutant = oracle.Oracle(str(so_path))
-    pins = BIGLA_PINS if which == "bigla" else LOC_PINS
-    fn = mutant.bigla if which == "bigla" else mutant.locality_gate
+    pins = {"bigla": BIGLA_PINS, "loc": LOC_PINS, "gp": GP_PINS}[which]
+    fn = {"bigla": mutant.bigla, "loc": mutant.locality_gate, "gp": mutant.gate_producer}[which]
     tripped = []
     for pin in pins:
         try:

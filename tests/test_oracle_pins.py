@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle_pins import BIGLA_PINS, LOC_PINS
+from oracle_pins import BIGLA_PINS, GP_PINS, LOC_PINS
 
 
 @pytest.mark.parametrize("pin", BIGLA_PINS, ids=lambda p: p.__name__)
@@ -14,6 +14,29 @@ def test_bigla_pin(pin):
 @pytest.mark.parametrize("pin", LOC_PINS, ids=lambda p: p.__name__)
 def test_locality_pin(pin):
     pin(oracle.locality_gate)
+
+
+@pytest.mark.parametrize("pin", GP_PINS, ids=lambda p: p.__name__)
+def test_gate_producer_pin(pin):
+    pin(oracle.gate_producer)
+
+
+def test_gate_producer_feeds_bigla():
+    """The produced log gates are valid inputs of the token mixer: <= 0, and with huge negative
+    pre-activations in one direction that direction dies (only the own-token term survives)."""
+    r = np.random.default_rng(5)
+    B, L, D, H, dk, dv = 1, 6, 8, 2, 4, 3
+    x = r.standard_normal((B, L, D))
+    w1 = r.standard_normal((D, 16)) / 3
+    w2 = r.standard_normal((16, 2 * H * dk))
+    bias = np.concatenate([np.zeros(H * dk), np.full(H * dk, -1e5)])      # backward gates ~ 0
+    gf, gb = oracle.gate_producer(x, w1, w2, H, dk, bias)
+    assert np.all(gf <= 0) and np.all(gb < -1e3)
+    q, k = r.standard_normal((2, B, H, L, dk))
+    v = r.standard_normal((B, H, L, dv))
+    out = oracle.bigla(q, k, v, gf, gb)
+    only_fwd = oracle.bigla(q, k, v, gf, np.full_like(gb, -1e9))
+    assert np.allclose(out, only_fwd, rtol=0, atol=1e-12)
 
 
 def test_thread_count_does_not_change_result():
