@@ -28,7 +28,7 @@ typedef enum {
     VIG_ERR_NULL = -1,        /* a required pointer is NULL                              */
     VIG_ERR_SHAPE = -2,       /* a size is <= 0 or the product of sizes overflows        */
     VIG_ERR_DTYPE = -3,       /* dtype is not a vig_dtype                                */
-    VIG_ERR_UNSUPPORTED = -4, /* dk or dv outside {16, 32, 64}                           */
+    VIG_ERR_UNSUPPORTED = -4, /* dk or dv outside {16, 32, 64}; D not a multiple of 32   */
     VIG_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned                        */
     VIG_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than bigla_workspace_bytes()  */
     VIG_ERR_HIP = -7,         /* a HIP call failed; see vig_last_hip_error()             */
@@ -122,6 +122,30 @@ int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, con
                              int dtype, int layout, void *stream);
 
 /*
+ * Direction-wise forget gates -- Section 3 (low-rank gate, temperature tau) and the first two
+ * lines of Eq. (BiGLA), Section 4.2.1.  For every token t of every batch element, with x_t the
+ * block input of width D:
+ *     z_t     = (x_t W1) W2 + b                in R^{2*H*dk}     (W1: D x 16, W2: 16 x 2*H*dk)
+ *     alpha_t = sigmoid(z_t)^(1/tau)
+ *     entries [0, H*dk) of alpha_t are the forward gates, [H*dk, 2*H*dk) the backward gates;
+ *     inside each half head h owns entries [h*dk, (h+1)*dk)
+ * and the outputs are the LOG gates log(alpha) = log(sigmoid(z)) / tau (<= 0, finite for every
+ * finite z) in the form bigla_fwd takes.
+ *
+ *   x            [B, L, D]            in    D a multiple of 32
+ *   w1           [16, D]              in    W1 transposed (how a linear layer D -> 16 stores its weight)
+ *   w2           [2*H*dk, 16]         in    W2 transposed (linear layer 16 -> 2*H*dk)
+ *   bias         [2*H*dk] or NULL     in
+ *   g_fwd, g_bwd [B, H, L, dk] (VIG_LAYOUT_BHLD) or [B, L, H, dk] (VIG_LAYOUT_BLHD)   out
+ *   dk in {16, 32, 64}; tau > 0 (16 in the paper); layout a vig_layout (of the outputs).
+ * VIG_BF16: both products on the matrix cores with fp32 accumulation (x W1 rounded to bf16 in
+ * between), fp32 log-sigmoid, bf16 out.  VIG_F32: fp32 throughout.
+ */
+int gate_producer_fwd(const void *x, const void *w1, const void *w2, const void *bias, void *g_fwd,
+                      void *g_bwd, int B, int H, int L, int D, int dk, float tau, int dtype, int layout,
+                      void *stream);
+
+/*
  * Measurement aid (no part of the method): per-kernel timing with HIP events recorded on the
  * stream each kernel is launched on.  vig_timing_enable(1) clears the records and makes every
  * later launch of this library from the calling thread record a start/stop event pair;
@@ -135,7 +159,8 @@ typedef enum {
     VIG_KERNEL_SEGMENT_OUT = 2,   /* chunkwise path, launch 3: output pass                    */
     VIG_KERNEL_RECURRENT = 3,     /* exact fp32 recurrence                                    */
     VIG_KERNEL_LOCALITY_GATE = 4, /* depthwise conv + gate                                    */
-    VIG_KERNEL_SEGMENT_OUT_GENERAL = 5 /* chunkwise path, output pass of single-chunk sequences  */
+    VIG_KERNEL_SEGMENT_OUT_GENERAL = 5, /* chunkwise path, output pass of single-chunk sequences */
+    VIG_KERNEL_GATE_PRODUCER = 6  /* forget-gate producer                                     */
 } vig_kernel;
 int vig_timing_enable(int on);
 int vig_timing_collect(int kernel, double *total_ms, long *launches);

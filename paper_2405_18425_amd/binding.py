@@ -24,10 +24,10 @@ LAYOUTS = {"bhld": VIG_LAYOUT_BHLD, "blhd": VIG_LAYOUT_BLHD}
 
 # every symbol include/vig_bigla.h declares
 EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "locality_gate_fwd",
-           "locality_gate_fwd_layout", "vig_status_str", "vig_last_hip_error", "vig_timing_enable",
+           "locality_gate_fwd_layout", "gate_producer_fwd", "vig_status_str", "vig_last_hip_error", "vig_timing_enable",
            "vig_timing_collect")
 KERNELS = {"segment_state": 0, "state_scan": 1, "segment_out": 2, "recurrent": 3, "locality_gate": 4,
-           "segment_out_general": 5}
+           "segment_out_general": 5, "gate_producer": 6}
 
 _lib = None
 
@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.locality_gate_fwd.restype = ci
         L.locality_gate_fwd_layout.argtypes = [vp] * 6 + [ci] * 7 + [vp]
         L.locality_gate_fwd_layout.restype = ci
+        L.gate_producer_fwd.argtypes = [vp] * 6 + [ci] * 5 + [ctypes.c_float, ci, ci, vp]
+        L.gate_producer_fwd.restype = ci
         L.vig_status_str.argtypes = [ci]
         L.vig_status_str.restype = ctypes.c_char_p
         L.vig_last_hip_error.argtypes = []
@@ -194,6 +196,38 @@ def locality_gate_fwd(x, w, gate_logits, o_global, Hg: int, Wg: int, bias=None, 
                                                 _dtype_code(x), lay, _stream_ptr(x.device))
     _check(st, "locality_gate_fwd")
     return out
+
+
+def gate_producer_fwd(x, w1, w2, H: int, dk: int, bias=None, tau: float = 16.0, layout="bhld", g_fwd=None,
+                      g_bwd=None):
+    """Direction-wise log forget gates (Section 3 gate; Eq. (BiGLA) lines 1-2).
+
+    x: [B,L,D]; w1: [16,D] and w2: [2*H*dk,16] (linear-layer weight layout); bias: [2*H*dk] or None
+    -> (g_fwd, g_bwd), each [B,H,L,dk] (layout "bhld") or [B,L,H,dk] ("blhd").
+    """
+    lay = _layout_code(layout)
+    x = _dev(x, "x")
+    if x.dim() != 3:
+        raise VigError(VIG_ERR_SHAPE, "x must be [B,L,D]")
+    B, L, D = x.shape
+    w1 = _dev(w1, "w1", (16, D), x)
+    w2 = _dev(w2, "w2", (2 * H * dk, 16), x)
+    if bias is not None:
+        bias = _dev(bias, "bias", (2 * H * dk,), x)
+    shape = (B, H, L, dk) if lay == VIG_LAYOUT_BHLD else (B, L, H, dk)
+    if g_fwd is None:
+        g_fwd = torch.empty(shape, dtype=x.dtype, device=x.device)
+    if g_bwd is None:
+        g_bwd = torch.empty(shape, dtype=x.dtype, device=x.device)
+    g_fwd = _dev(g_fwd, "g_fwd", shape, x)
+    g_bwd = _dev(g_bwd, "g_bwd", shape, x)
+    with torch.cuda.device(x.device):
+        st = lib().gate_producer_fwd(x.data_ptr(), w1.data_ptr(), w2.data_ptr(),
+                                     bias.data_ptr() if bias is not None else None, g_fwd.data_ptr(),
+                                     g_bwd.data_ptr(), B, H, L, D, dk, float(tau), _dtype_code(x), lay,
+                                     _stream_ptr(x.device))
+    _check(st, "gate_producer_fwd")
+    return g_fwd, g_bwd
 
 
 def timing_enable(on: bool) -> None:

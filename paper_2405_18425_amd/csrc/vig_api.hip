@@ -112,6 +112,23 @@ int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, con
                                                 static_cast<hipStream_t>(stream)));
 }
 
+int gate_producer_fwd(const void *x, const void *w1, const void *w2, const void *bias, void *g_fwd, void *g_bwd,
+                      int B, int H, int L, int D, int dk, float tau, int dtype, int layout, void *stream)
+{
+    if (!x || !w1 || !w2 || !g_fwd || !g_bwd) return VIG_ERR_NULL;
+    if (layout != VIG_LAYOUT_BHLD && layout != VIG_LAYOUT_BLHD) return VIG_ERR_LAYOUT;
+    if (B <= 0 || H <= 0 || L <= 0 || D <= 0 || dk <= 0 || !(tau > 0.f)) return VIG_ERR_SHAPE;
+    if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
+    if (!head_dim_ok(dk) || D % 32 != 0) return VIG_ERR_UNSUPPORTED;
+    if (!sizes_ok(B, L, D, 1) || !sizes_ok(B, L, H, 2 * dk) || long(H) * dk > (1 << 20)) return VIG_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(w1) || !aligned16(w2) || !aligned16(bias) || !aligned16(g_fwd) ||
+        !aligned16(g_bwd))
+        return VIG_ERR_ALIGN;
+    return hip_status(vig::gate_producer_launch(x, w1, w2, bias, g_fwd, g_bwd, B, H, L, D, dk, tau,
+                                                dtype == VIG_BF16, layout == VIG_LAYOUT_BLHD ? 1 : 0,
+                                                static_cast<hipStream_t>(stream)));
+}
+
 const char *vig_status_str(int status)
 {
     switch (status) {
@@ -119,7 +136,7 @@ const char *vig_status_str(int status)
         case VIG_ERR_NULL: return "VIG_ERR_NULL: a required pointer is NULL";
         case VIG_ERR_SHAPE: return "VIG_ERR_SHAPE: a size is <= 0 or too large";
         case VIG_ERR_DTYPE: return "VIG_ERR_DTYPE: dtype is not VIG_F32 or VIG_BF16";
-        case VIG_ERR_UNSUPPORTED: return "VIG_ERR_UNSUPPORTED: dk and dv must be 16, 32 or 64";
+        case VIG_ERR_UNSUPPORTED: return "VIG_ERR_UNSUPPORTED: head widths must be 16, 32 or 64 (model width a multiple of 32)";
         case VIG_ERR_ALIGN: return "VIG_ERR_ALIGN: a pointer is not 16-byte aligned";
         case VIG_ERR_WORKSPACE: return "VIG_ERR_WORKSPACE: workspace missing or too small";
         case VIG_ERR_HIP: return "VIG_ERR_HIP: a HIP call failed (see vig_last_hip_error)";

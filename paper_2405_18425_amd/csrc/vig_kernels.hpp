@@ -28,4 +28,9 @@ hipError_t locality_gate_launch(const void *x, const void *w, const void *bias, 
                                 const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv,
                                 bool is_bf16, int token_major, hipStream_t stream);
 
+// ---- direction-wise forget-gate producer (low-rank projection + log-sigmoid / tau) -----------
+hipError_t gate_producer_launch(const void *x, const void *w1, const void *w2, const void *bias, void *g_fwd,
+                                void *g_bwd, int B, int H, int L, int D, int dk, float tau, bool is_bf16,
+                                int token_major, hipStream_t stream);
+
 }  // namespace vig

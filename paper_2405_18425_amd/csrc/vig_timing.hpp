@@ -13,7 +13,8 @@ enum KernelId {
     kKernelRecurrent = 3,
     kKernelLocalityGate = 4,
     kKernelSegmentOutGeneral = 5,
-    kKernelCount = 6
+    kKernelGateProducer = 6,
+    kKernelCount = 7
 };
 
 // Brackets one launch when timing is enabled on the calling thread.

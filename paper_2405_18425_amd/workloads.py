@@ -190,3 +190,18 @@ def generate(w: Workload, seed: int = 0, tensors=None) -> dict:
     }
     names = list(spec) if tensors is None else list(tensors)
     return {n: store(spec[n](), w.dtype) for n in names}
+
+
+def generate_gate_inputs(B: int, L: int, D: int, H: int, dk: int, dtype: str, seed: int = 0, bias_mu: float = 0.0,
+                         rank: int = 16) -> dict:
+    """Stored inputs of the forget-gate producer, in the mathematical orientation of Section 3:
+    x : [B,L,D] ~ N(0,1) (a normalised block input), w1 : [D,rank] ~ N(0,1)/sqrt(D),
+    w2 : [rank, 2*H*dk] ~ N(0,1)/sqrt(rank), bias : [2*H*dk] ~ N(bias_mu, 1).  The pre-activation
+    then has unit-order spread around bias_mu, like the gate logits of the BiGLA configurations."""
+    spec = {
+        "x": normal(seed, "gate_x", (B, L, D)),
+        "w1": normal(seed, "gate_w1", (D, rank)) / np.sqrt(D),
+        "w2": normal(seed, "gate_w2", (rank, 2 * H * dk)) / np.sqrt(rank),
+        "bias": normal(seed, "gate_bias", (2 * H * dk,), mu=bias_mu),
+    }
+    return {n: store(a, dtype) for n, a in spec.items()}

@@ -103,6 +103,27 @@ def test_layout_entry_points_validate():
                                       vb.VIG_LAYOUT_BLHD, None) == vb.VIG_ERR_UNSUPPORTED
 
 
+def test_gate_producer_validation_codes():
+    L = vb.lib()
+
+    def call(x=PTR, w1=PTR, w2=PTR, bias=None, gf=PTR, gb=PTR, B=1, H=1, Ln=8, D=32, dk=16, tau=16.0,
+             dtype=vb.VIG_BF16, layout=vb.VIG_LAYOUT_BHLD):
+        return L.gate_producer_fwd(x, w1, w2, bias, gf, gb, B, H, Ln, D, dk, tau, dtype, layout, None)
+
+    for name in ("x", "w1", "w2", "gf", "gb"):
+        assert call(**{name: None}) == vb.VIG_ERR_NULL
+    for name in ("B", "H", "Ln", "D", "dk"):
+        assert call(**{name: 0}) == vb.VIG_ERR_SHAPE
+    assert call(tau=0.0) == vb.VIG_ERR_SHAPE
+    assert call(tau=-1.0) == vb.VIG_ERR_SHAPE
+    assert call(dtype=5) == vb.VIG_ERR_DTYPE
+    assert call(layout=9) == vb.VIG_ERR_LAYOUT
+    assert call(dk=48) == vb.VIG_ERR_UNSUPPORTED
+    assert call(D=40) == vb.VIG_ERR_UNSUPPORTED
+    assert call(bias=PTR + 4) == vb.VIG_ERR_ALIGN
+    assert call(x=PTR + 8) == vb.VIG_ERR_ALIGN
+
+
 def test_binding_rejects_cpu_tensors():
     import torch
 

@@ -304,3 +304,76 @@ def test_bigla_seeded_random_shapes():
             out = out.permute(0, 2, 1, 3).contiguous()
         got = wl.widen(wl.from_torch(out, dtype), dtype)
         assert_close(got, run_bigla_oracle(s_, dtype), TOL[dtype], f"random case {case}")
+
+
+# --------------------------------------------------------------------------- #
+# Forget-gate producer
+# --------------------------------------------------------------------------- #
+def _run_gate_producer(st, H, dk, dtype, layout, tau=16.0, with_bias=True):
+    import torch
+    from paper_2405_18425_amd import binding as vb
+
+    t = {n: wl.to_torch(a, dtype, "cuda:0") for n, a in st.items()}
+    gf, gb = vb.gate_producer_fwd(t["x"], t["w1"].t().contiguous(), t["w2"].t().contiguous(), H, dk,
+                                  bias=t["bias"] if with_bias else None, tau=tau, layout=layout)
+    torch.cuda.synchronize()
+    if layout == "blhd":
+        gf, gb = gf.permute(0, 2, 1, 3).contiguous(), gb.permute(0, 2, 1, 3).contiguous()
+    return wl.widen(wl.from_torch(gf, dtype), dtype), wl.widen(wl.from_torch(gb, dtype), dtype)
+
+
+@pytest.mark.parametrize("dtype", ("bf16", "f32"))
+@pytest.mark.parametrize("B,L,D,H,dk,layout,mu", [
+    (4, 196, 192, 3, 64, "bhld", 0.0),      # ViG-T-like block at 224 px
+    (2, 1024, 384, 6, 64, "bhld", -2.0),    # ViG-S-like at 512 px, strong decay
+    (2, 777, 384, 6, 32, "blhd", 2.0),      # paper head shape, token-major, ragged token count
+    (1, 5, 32, 1, 16, "bhld", 0.0),         # fewer tokens than one tile
+    (3, 49, 768, 12, 64, "blhd", 0.0),      # ViG-B width
+])
+def test_gate_producer_parity(dtype, B, L, D, H, dk, layout, mu):
+    import oracle
+
+    _say(f"gate producer {dtype} B{B} L{L} D{D} H{H} dk{dk} {layout} mu{mu}")
+    st = wl.generate_gate_inputs(B, L, D, H, dk, dtype, seed=7, bias_mu=mu)
+    wd = {n: wl.widen(a, dtype) for n, a in st.items()}
+    for with_bias in (True, False):
+        gf, gb = _run_gate_producer(st, H, dk, dtype, layout, with_bias=with_bias)
+        rf, rb = oracle.gate_producer(wd["x"], wd["w1"], wd["w2"], H, dk, wd["bias"] if with_bias else None, 16.0)
+        assert np.all(gf <= 0) and np.all(gb <= 0)
+        assert_close(gf, rf, TOL[dtype], "g_fwd")
+        assert_close(gb, rb, TOL[dtype], "g_bwd")
+
+
+def test_gate_producer_saturated_logits_stay_finite():
+    import oracle
+
+    st = wl.generate_gate_inputs(2, 100, 64, 2, 16, "bf16", seed=9)
+    w2 = wl.widen(st["w2"], "bf16") * 300.0          # pre-activations of several hundred either way
+    st["w2"] = wl.store(w2, "bf16")
+    wd = {n: wl.widen(a, "bf16") for n, a in st.items()}
+    for tau in (16.0, 1.0):
+        gf, gb = _run_gate_producer(st, 2, 16, "bf16", "bhld", tau=tau)
+        rf, rb = oracle.gate_producer(wd["x"], wd["w1"], wd["w2"], 2, 16, wd["bias"], tau)
+        assert np.all(np.isfinite(gf)) and np.all(np.isfinite(gb))
+        assert_close(gf, rf, TOL["bf16"], "g_fwd")
+        assert_close(gb, rb, TOL["bf16"], "g_bwd")
+
+
+def test_gate_producer_into_bigla_chain():
+    """Gates made on the GPU feed bigla_fwd directly (same layout, no copy in between)."""
+    import torch
+    import oracle
+    from paper_2405_18425_amd import binding as vb
+
+    B, L, D, H, dk, dv = 2, 300, 192, 3, 64, 64
+    st = wl.generate_gate_inputs(B, L, D, H, dk, "bf16", seed=11, bias_mu=-1.0)
+    w = wl.Workload("chain", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=dv, dtype="bf16", gate_mu=0.0)
+    s = wl.generate(w, seed=11, tensors=("q", "k", "v"))
+    t = {n: wl.to_torch(a, "bf16", "cuda:0") for n, a in {**st, **s}.items()}
+    gf, gb = vb.gate_producer_fwd(t["x"], t["w1"].t().contiguous(), t["w2"].t().contiguous(), H, dk, bias=t["bias"])
+    out = vb.bigla_fwd(t["q"], t["k"], t["v"], gf, gb)
+    torch.cuda.synchronize()
+    gf64 = wl.widen(wl.from_torch(gf, "bf16"), "bf16")
+    gb64 = wl.widen(wl.from_torch(gb, "bf16"), "bf16")
+    ref = oracle.bigla(wl.widen(s["q"], "bf16"), wl.widen(s["k"], "bf16"), wl.widen(s["v"], "bf16"), gf64, gb64)
+    assert_close(wl.widen(wl.from_torch(out, "bf16"), "bf16"), ref, TOL["bf16"], "bigla on produced gates")
