@@ -132,7 +132,8 @@ int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, con
  * and the outputs are the LOG gates log(alpha) = log(sigmoid(z)) / tau (<= 0, finite for every
  * finite z) in the form bigla_fwd takes.
  *
- *   x            [B, L, D]            in    D a multiple of 32
+ *   x            [B, L, D]            in    D a multiple of 32; VIG_BF16: one of 32, 64, ..., 256,
+ *                                           320, 384, 512, 576, 640, 768, 1024
  *   w1           [16, D]              in    W1 transposed (how a linear layer D -> 16 stores its weight)
  *   w2           [2*H*dk, 16]         in    W2 transposed (linear layer 16 -> 2*H*dk)
  *   bias         [2*H*dk] or NULL     in

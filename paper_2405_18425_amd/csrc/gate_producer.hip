@@ -17,8 +17,9 @@
 //           the same 8 inputs); the accumulator leaves lane (token l%16, ranks 4g..4g+3)
 //   GEMM 2  Z^T[channel][token] = w2[channel][:] . H1^T[:][token]   v_mfma_f32_16x16x16_bf16, K = 16
 //           B is the bf16 copy of GEMM 1's accumulator as it stands (lane: token l%16, ranks
-//           4g..4g+3), A = w2 rows (lane: channel l%16 of the tile, ranks 4g..4g+3); the result
-//           leaves lane (token l%16, channels 4g..4g+3 of the tile): 8 bytes per lane to store.
+//           4g..4g+3), A = w2 rows (lane: one channel, ranks 4g..4g+3); the result leaves lane
+//           (token l%16, the channels of A rows 4g..4g+3).  The A rows of four consecutive tiles
+//           are chosen so that the lane ends up with 16 consecutive channels: whole-row stores.
 // fp32: plain fp32 FMAs, one workgroup per 16 tokens (low-rank products through LDS).
 #include "vig_common.hpp"
 #include "vig_kernels.hpp"
@@ -31,6 +32,7 @@ namespace {
 constexpr int kRank = 16;  // width of the low-rank bottleneck (Section 3)
 constexpr int kThreads = 256;
 constexpr int kTokensPerWave = 16;
+constexpr int kPersistentBlocks = 768;  // three workgroups per CU walk the token tiles
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -51,59 +53,140 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, b);
 }
 
-template <int kDummy = 0>
+// Copy w2 ([width][16] bf16, 2 x 16 bytes per row) and the bias into LDS, eight loads in flight per
+// thread and batch (a load-store-load-store loop would pay one memory round trip per 16 bytes).
+__device__ __forceinline__ void stage_weights(const uint16_t *w2, const uint16_t *bias, uint16_t *s_w2,
+                                              uint16_t *s_bias, int width)
+{
+    const uint4 *src = reinterpret_cast<const uint4 *>(w2);
+    uint4 *dst = reinterpret_cast<uint4 *>(s_w2);
+    const int n = width * 2;
+    for (int i0 = threadIdx.x; i0 < n; i0 += 8 * kThreads) {
+        uint4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[min(i0 + u * kThreads, n - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (i0 + u * kThreads < n) dst[i0 + u * kThreads] = v[u];
+    }
+    for (int i = threadIdx.x; i < width / 8; i += kThreads)
+        reinterpret_cast<uint4 *>(s_bias)[i] = bias ? reinterpret_cast<const uint4 *>(bias)[i] : make_uint4(0u, 0u, 0u, 0u);
+}
+
+// Persistent workgroups: w2 and the bias are copied into LDS once (rows of 32 bytes, read back 8
+// bytes per lane, so that the loop over channel tiles waits on LDS, not on global memory), each
+// wave keeps its A operands of GEMM 1 (all of w1) in registers, and then walks token tiles with a
+// grid stride.  The x rows of a wave's NEXT tile are requested as soon as GEMM 1 has consumed the
+// current ones, so they travel during the long channel loop.
+// kSteps = D / 32 (every load of the low-rank product is unrolled); kLdsW2 = false reads w2 and
+// the bias from global memory (when they do not fit the LDS budget).
+template <int kSteps, bool kLdsW2>
 __global__ __launch_bounds__(kThreads) void gate_producer_bf16_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ w1, const uint16_t *__restrict__ w2,
     const uint16_t *__restrict__ bias, uint16_t *__restrict__ g_fwd, uint16_t *__restrict__ g_bwd, long tokens,
     int H, int L, int D, int dk, float inv_tau, int token_major)
 {
-    const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
-    const long tile = long(blockIdx.x) * (kThreads / 64) + (threadIdx.x >> 6);
-    const long tok0 = tile * kTokensPerWave;
-    if (tok0 >= tokens) return;  // whole wave
-    const long tok = tok0 + r;
-    const long tok_c = tok < tokens ? tok : tokens - 1;  // rows past the end repeat the last one, not stored
-
-    // ---- GEMM 1: H1^T = w1 . x^T, two accumulators so that consecutive MFMAs do not wait on each other
-    f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-    const uint4 *xrow = reinterpret_cast<const uint4 *>(x + size_t(tok_c) * D) + g;
-    const uint4 *wrow = reinterpret_cast<const uint4 *>(w1 + size_t(r) * D) + g;
-    const int ksteps = D / 32;
-#pragma unroll 4
-    for (int kk = 0; kk < ksteps; ++kk) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, wrow[4 * kk]);
-        const bf16x8 b = __builtin_bit_cast(bf16x8, xrow[4 * kk]);
-        acc[kk & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[kk & 1], 0, 0, 0);
-    }
-    // lane (token r, ranks 4g..4g+3) -> bf16 B operand of the K = 16 MFMA
-    const uint2 hb = make_uint2(pack2(acc[0][0] + acc[1][0], acc[0][1] + acc[1][1]),
-                                pack2(acc[0][2] + acc[1][2], acc[0][3] + acc[1][3]));
-    const s16x4 hop = __builtin_bit_cast(s16x4, hb);
-
-    // ---- GEMM 2 per 16-channel tile, then bias, log-sigmoid, 1/tau, store
+    extern __shared__ __align__(16) unsigned char dyn_lds[];
     const int width = 2 * H * dk, half = H * dk;
-    const long b_idx = tok_c / L;
-    const int t_idx = int(tok_c % L);
-    for (int c0 = 0; c0 < width; c0 += 16) {
-        const uint2 wa = *reinterpret_cast<const uint2 *>(w2 + size_t(c0 + r) * kRank + 4 * g);
-        f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        z = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, wa), hop, z, 0, 0, 0);
-        float bv[4] = {0.f, 0.f, 0.f, 0.f};
-        if (bias) {
-            const uint2 braw = *reinterpret_cast<const uint2 *>(bias + c0 + 4 * g);
-            bv[0] = bf16_lo_to_f32(braw.x); bv[1] = bf16_hi_to_f32(braw.x);
-            bv[2] = bf16_lo_to_f32(braw.y); bv[3] = bf16_hi_to_f32(braw.y);
-        }
-        float o[4];
+    uint16_t *s_w2 = reinterpret_cast<uint16_t *>(dyn_lds);       // [width][16]
+    uint16_t *s_bias = s_w2 + size_t(width) * kRank;              // [width] (zeros when there is no bias)
+    const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    const long n_tiles = (tokens + kTokensPerWave - 1) / kTokensPerWave;
+    const long tile_step = long(gridDim.x) * (kThreads / 64);
+    long tile = long(blockIdx.x) * (kThreads / 64) + (threadIdx.x >> 6);
+
+    // lane (r, g): A operand = w1 row r (rank), B operand = x row of token r; 16 bytes at 32kk + 8g
+    auto x_row = [&](long t) {
+        const long tok = t * kTokensPerWave + r;
+        return reinterpret_cast<const uint4 *>(x + size_t(tok < tokens ? tok : tokens - 1) * D) + g;
+    };
+    uint4 wa[kSteps], xa[kSteps];
+    {
+        const uint4 *wrow = reinterpret_cast<const uint4 *>(w1 + size_t(r) * D) + g;
+        const uint4 *xrow = x_row(tile < n_tiles ? tile : n_tiles - 1);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = log_sigmoid(z[e] + bv[e]) * inv_tau;
-        if (tok < tokens) {
-            // a 16-channel tile lies inside one head of one direction (dk is a multiple of 16)
-            uint16_t *gbase = c0 < half ? g_fwd : g_bwd;
-            const int cc = (c0 < half ? c0 : c0 - half) + 4 * g;
-            const int h = cc / dk, j = cc % dk;
-            const size_t row = token_major ? (size_t(b_idx) * L + t_idx) * H + h : (size_t(b_idx) * H + h) * L + t_idx;
-            *reinterpret_cast<uint2 *>(gbase + row * dk + j) = make_uint2(pack2(o[0], o[1]), pack2(o[2], o[3]));
+        for (int kk = 0; kk < kSteps; ++kk) {
+            xa[kk] = xrow[4 * kk];
+            wa[kk] = wrow[4 * kk];
+        }
+    }
+    if (kLdsW2) {
+        stage_weights(w2, bias, s_w2, s_bias, width);
+        __syncthreads();
+    }
+    const uint16_t *w2src = kLdsW2 ? s_w2 : w2;
+    const uint16_t *bsrc = kLdsW2 ? s_bias : bias;
+    const int dk_shift = dk == 64 ? 6 : (dk == 32 ? 5 : 4);
+    const int arow = 16 * (r >> 2) + (r & 3);  // channel of this lane's A row inside a group, tile 0
+
+    for (; tile < n_tiles; tile += tile_step) {
+        // ---- GEMM 1: H1^T = w1 . x^T, two accumulators so that consecutive MFMAs do not wait on each other
+        f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int kk = 0; kk < kSteps; ++kk)
+            acc[kk & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wa[kk]),
+                                                                  __builtin_bit_cast(bf16x8, xa[kk]), acc[kk & 1], 0, 0, 0);
+        // lane (token r, ranks 4g..4g+3) -> bf16 B operand of the K = 16 MFMA
+        const uint2 hb = make_uint2(pack2(acc[0][0] + acc[1][0], acc[0][1] + acc[1][1]),
+                                    pack2(acc[0][2] + acc[1][2], acc[0][3] + acc[1][3]));
+        const s16x4 hop = __builtin_bit_cast(s16x4, hb);
+        {  // the next tile's rows (clamped past the end: loaded, never used)
+            const long next = tile + tile_step;
+            const uint4 *xrow = x_row(next < n_tiles ? next : n_tiles - 1);
+#pragma unroll
+            for (int kk = 0; kk < kSteps; ++kk) xa[kk] = xrow[4 * kk];
+        }
+
+        // ---- GEMM 2 in groups of 64 channels (four MFMA tiles), then bias, log-sigmoid, 1/tau, store.
+        // Row 4g'+e of tile i of a group is given channel 16g' + 4i + e, so that after the four tiles
+        // lane (r, g) holds the 16 CONSECUTIVE channels 16g .. 16g+15 of its token: 32 contiguous
+        // bytes per lane, whole 128-byte rows per store instruction.  Those 16 channels lie inside
+        // one head of one direction (dk is 16, 32 or 64: shifts, no division).
+        const long tok = tile * kTokensPerWave + r;
+        const long tok_c = tok < tokens ? tok : tokens - 1;
+        const long b_idx = tok_c / L;
+        const int t_idx = int(tok_c % L);
+        for (int cb = 0; cb < width; cb += 64) {
+            f32x4 z[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int ch = min(cb + arow + 4 * i, width - 1);  // a ragged last group repeats a row, unused
+                const uint2 a2 = *reinterpret_cast<const uint2 *>(w2src + size_t(ch) * kRank + 4 * g);
+                const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                z[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a2), hop, zero, 0, 0, 0);
+            }
+            const int c = cb + 16 * g;  // first of this lane's 16 channels
+            if (c >= width) continue;
+            float bv[16];
+            if (bsrc) {
+                const uint4 b0 = *reinterpret_cast<const uint4 *>(bsrc + c), b1 = *reinterpret_cast<const uint4 *>(bsrc + c + 8);
+                const uint32_t raw[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+                for (int n = 0; n < 8; ++n) {
+                    bv[2 * n] = bf16_lo_to_f32(raw[n]);
+                    bv[2 * n + 1] = bf16_hi_to_f32(raw[n]);
+                }
+            } else {
+#pragma unroll
+                for (int n = 0; n < 16; ++n) bv[n] = 0.f;
+            }
+            uint32_t packed[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {  // channel c + 4i + e
+                const float o0 = log_sigmoid(z[i][0] + bv[4 * i + 0]) * inv_tau, o1 = log_sigmoid(z[i][1] + bv[4 * i + 1]) * inv_tau;
+                const float o2 = log_sigmoid(z[i][2] + bv[4 * i + 2]) * inv_tau, o3 = log_sigmoid(z[i][3] + bv[4 * i + 3]) * inv_tau;
+                packed[2 * i] = pack2(o0, o1);
+                packed[2 * i + 1] = pack2(o2, o3);
+            }
+            if (tok < tokens) {
+                const bool bwd = c >= half;
+                const int cc = bwd ? c - half : c;
+                const int h = cc >> dk_shift, j = cc & (dk - 1);
+                const size_t row = token_major ? (size_t(b_idx) * L + t_idx) * H + h : (size_t(b_idx) * H + h) * L + t_idx;
+                uint4 *dst = reinterpret_cast<uint4 *>((bwd ? g_bwd : g_fwd) + row * dk + j);
+                dst[0] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+                dst[1] = make_uint4(packed[4], packed[5], packed[6], packed[7]);
+            }
         }
     }
 }
@@ -154,6 +237,17 @@ __global__ __launch_bounds__(kThreads) void gate_producer_f32_kernel(
 
 }  // namespace
 
+bool gate_producer_width_ok(int D, bool is_bf16)
+{
+    if (D <= 0 || D % 32 != 0) return false;
+    if (!is_bf16) return true;
+    switch (D / 32) {  // the unrolled instantiations of the bf16 kernel
+        case 1: case 2: case 3: case 4: case 5: case 6: case 7: case 8: case 10: case 12: case 16: case 18: case 20:
+        case 24: case 32: return true;
+    }
+    return false;
+}
+
 hipError_t gate_producer_launch(const void *x, const void *w1, const void *w2, const void *bias, void *g_fwd,
                                 void *g_bwd, int B, int H, int L, int D, int dk, float tau, bool is_bf16,
                                 int token_major, hipStream_t stream)
@@ -163,13 +257,31 @@ hipError_t gate_producer_launch(const void *x, const void *w1, const void *w2, c
     LaunchTimer timer(kKernelGateProducer, stream);
     if (is_bf16) {
         const long tiles = (tokens + kTokensPerWave - 1) / kTokensPerWave;
-        const long blocks = (tiles + kThreads / 64 - 1) / (kThreads / 64);
-        if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(gate_producer_bf16_kernel<0>, dim3((unsigned)blocks), dim3(kThreads), 0, stream,
-                           static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w1),
-                           static_cast<const uint16_t *>(w2), static_cast<const uint16_t *>(bias),
-                           static_cast<uint16_t *>(g_fwd), static_cast<uint16_t *>(g_bwd), tokens, H, L, D, dk,
-                           inv_tau, token_major);
+        long blocks = (tiles + kThreads / 64 - 1) / (kThreads / 64);
+        if (blocks > kPersistentBlocks) blocks = kPersistentBlocks;
+        const size_t w2_bytes = size_t(2) * H * dk * (kRank + 1) * sizeof(uint16_t);  // w2 and the bias
+        const bool lds = w2_bytes <= 52 * 1024;
+#define VIG_GP_LAUNCH(KS, LDS)                                                                                     \
+    hipLaunchKernelGGL((gate_producer_bf16_kernel<KS, LDS>), dim3((unsigned)blocks), dim3(kThreads),               \
+                       (LDS) ? w2_bytes : 0, stream, static_cast<const uint16_t *>(x),                            \
+                       static_cast<const uint16_t *>(w1), static_cast<const uint16_t *>(w2),                      \
+                       static_cast<const uint16_t *>(bias), static_cast<uint16_t *>(g_fwd),                       \
+                       static_cast<uint16_t *>(g_bwd), tokens, H, L, D, dk, inv_tau, token_major)
+#define VIG_GP_CASE(KS)                                                                                            \
+    case KS:                                                                                                       \
+        if (lds)                                                                                                   \
+            VIG_GP_LAUNCH(KS, true);                                                                               \
+        else                                                                                                       \
+            VIG_GP_LAUNCH(KS, false);                                                                              \
+        break
+        switch (D / 32) {  // model widths 32 .. 1024 in steps of 32 up to 256, then the common larger ones
+            VIG_GP_CASE(1); VIG_GP_CASE(2); VIG_GP_CASE(3); VIG_GP_CASE(4); VIG_GP_CASE(5); VIG_GP_CASE(6);
+            VIG_GP_CASE(7); VIG_GP_CASE(8); VIG_GP_CASE(10); VIG_GP_CASE(12); VIG_GP_CASE(16); VIG_GP_CASE(18);
+            VIG_GP_CASE(20); VIG_GP_CASE(24); VIG_GP_CASE(32);
+            default: return hipErrorInvalidValue;
+        }
+#undef VIG_GP_CASE
+#undef VIG_GP_LAUNCH
     } else {
         const long blocks = (tokens + kTokensPerWave - 1) / kTokensPerWave;
         if (blocks > 0x7fffffffL) return hipErrorInvalidValue;

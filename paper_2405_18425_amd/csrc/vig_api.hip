@@ -119,7 +119,7 @@ int gate_producer_fwd(const void *x, const void *w1, const void *w2, const void 
     if (layout != VIG_LAYOUT_BHLD && layout != VIG_LAYOUT_BLHD) return VIG_ERR_LAYOUT;
     if (B <= 0 || H <= 0 || L <= 0 || D <= 0 || dk <= 0 || !(tau > 0.f)) return VIG_ERR_SHAPE;
     if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
-    if (!head_dim_ok(dk) || D % 32 != 0) return VIG_ERR_UNSUPPORTED;
+    if (!head_dim_ok(dk) || !vig::gate_producer_width_ok(D, dtype == VIG_BF16)) return VIG_ERR_UNSUPPORTED;
     if (!sizes_ok(B, L, D, 1) || !sizes_ok(B, L, H, 2 * dk) || long(H) * dk > (1 << 20)) return VIG_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(w1) || !aligned16(w2) || !aligned16(bias) || !aligned16(g_fwd) ||
         !aligned16(g_bwd))

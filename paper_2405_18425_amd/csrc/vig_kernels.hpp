@@ -29,6 +29,7 @@ hipError_t locality_gate_launch(const void *x, const void *w, const void *bias, 
                                 bool is_bf16, int token_major, hipStream_t stream);
 
 // ---- direction-wise forget-gate producer (low-rank projection + log-sigmoid / tau) -----------
+bool gate_producer_width_ok(int D, bool is_bf16);
 hipError_t gate_producer_launch(const void *x, const void *w1, const void *w2, const void *bias, void *g_fwd,
                                 void *g_bwd, int B, int H, int L, int D, int dk, float tau, bool is_bf16,
                                 int token_major, hipStream_t stream);
