@@ -3,6 +3,9 @@ workload, plus one plain device-to-device copy of known size that calibrates FET
 WRITE_SIZE (bytes = counter * factor, factor = known copy bytes / counter of the copy kernel).
 
     rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir> -o p -- python3 -m paper_2405_18425_amd.profile_path 4 3
+
+A third argument D > 0 adds the forget-gate producer in front of every pass (block input of width D
+for the same B, L, H, dk), feeding the gates it makes to bigla_fwd.
 """
 from __future__ import annotations
 
@@ -16,16 +19,24 @@ from . import workloads as wl
 COPY_BYTES = 256 << 20  # calibration copy: reads 256 MiB, writes 256 MiB
 
 
-def main(cfg: int = 4, passes: int = 3) -> None:
+def main(cfg: int = 4, passes: int = 3, gate_width: int = 0) -> None:
     w = wl.CONFIGS[cfg]
     dev = "cuda:0"
     t = {n: wl.to_torch(a, w.dtype, dev) for n, a in wl.generate(w, seed=0).items()}
+    gp = None
+    if gate_width > 0:
+        g = wl.generate_gate_inputs(w.B, w.L, gate_width, w.H, w.dk, w.dtype, seed=0, bias_mu=w.gate_mu)
+        gp = {n: wl.to_torch(a, w.dtype, dev) for n, a in g.items()}
+        gp["w1"], gp["w2"] = gp["w1"].t().contiguous(), gp["w2"].t().contiguous()
     src = torch.empty(COPY_BYTES // 4, dtype=torch.float32, device=dev).normal_()
     dst = torch.empty_like(src)
     torch.cuda.synchronize()
     dst.copy_(src)  # the calibration kernel (an elementwise copy of COPY_BYTES)
     og = out = None
     for _ in range(passes):
+        if gp is not None:
+            vb.gate_producer_fwd(gp["x"], gp["w1"], gp["w2"], w.H, w.dk, bias=gp["bias"], g_fwd=t["g_fwd"],
+                                 g_bwd=t["g_bwd"])
         og = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"])
         out = vb.locality_gate_fwd(t["v"], t["conv_w"], t["gate_logits"], og, w.Hg, w.Wg)
     torch.cuda.synchronize()
@@ -33,4 +44,4 @@ def main(cfg: int = 4, passes: int = 3) -> None:
 
 
 if __name__ == "__main__":
-    main(*(int(a) for a in sys.argv[1:3]))
+    main(*(int(a) for a in sys.argv[1:4]))
