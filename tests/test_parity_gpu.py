@@ -377,3 +377,41 @@ def test_gate_producer_into_bigla_chain():
     gb64 = wl.widen(wl.from_torch(gb, "bf16"), "bf16")
     ref = oracle.bigla(wl.widen(s["q"], "bf16"), wl.widen(s["k"], "bf16"), wl.widen(s["v"], "bf16"), gf64, gb64)
     assert_close(wl.widen(wl.from_torch(out, "bf16"), "bf16"), ref, TOL["bf16"], "bigla on produced gates")
+
+
+def test_path_captured_in_a_hip_graph():
+    """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a step can be captured in a HIP graph.  Every replay -- with eager work
+    and synchronisations in between, and with the inputs changed in place -- must equal the
+    eager result bit for bit."""
+    import torch
+    from paper_2405_18425_amd import binding as vb
+
+    w = wl.Workload("graph", B=2, H=3, Hg=20, Wg=20, dk=64, dv=64, dtype="bf16", gate_mu=-1.0)
+    t = {n: wl.to_torch(a, w.dtype, "cuda:0") for n, a in wl.generate(w, seed=31).items()}
+    ws = torch.empty(vb.bigla_workspace_bytes(w.B, w.H, w.L, w.dk, w.dv, vb.VIG_BF16), dtype=torch.uint8, device="cuda:0")
+    og, out = torch.empty_like(t["v"]), torch.empty_like(t["v"])
+
+    def step():
+        vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], out=og, workspace=ws)
+        vb.locality_gate_fwd(t["v"], t["conv_w"], t["gate_logits"], og, w.Hg, w.Wg, out=out)
+
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+        step()
+    for rep in range(4):
+        if rep:  # new inputs in the same buffers
+            t["q"].copy_(torch.roll(t["q"], shifts=rep, dims=2))
+            t["g_bwd"].mul_(0.5)
+        step()
+        torch.cuda.synchronize()
+        want = out.clone()
+        out.zero_()
+        og.zero_()
+        ws.random_(0, 255)               # eager work between replays, dirty scratch
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {rep}"
