@@ -150,7 +150,8 @@ def main():
         "avg_us": round(dom_us, 2), "algorithmic_bytes": alg_bytes,
     }
     bigla_us = sum(kern[n]["avg_us"] * kern[n]["launches_per_step"]
-                   for n in ("segment_state", "state_scan", "segment_out", "segment_out_general", "recurrent") if n in kern)
+                   for n in ("segment_state", "state_scan", "segment_out", "segment_out_general", "slab", "recurrent")
+                   if n in kern)
     extra = {
         "kernels_us": {n: round(k["avg_us"] * k["launches_per_step"], 2) for n, k in kern.items()},
         "bigla_us": round(bigla_us, 2),

@@ -161,7 +161,8 @@ typedef enum {
     VIG_KERNEL_RECURRENT = 3,     /* exact fp32 recurrence                                    */
     VIG_KERNEL_LOCALITY_GATE = 4, /* depthwise conv + gate                                    */
     VIG_KERNEL_SEGMENT_OUT_GENERAL = 5, /* chunkwise path, output pass of single-chunk sequences */
-    VIG_KERNEL_GATE_PRODUCER = 6  /* forget-gate producer                                     */
+    VIG_KERNEL_GATE_PRODUCER = 6, /* forget-gate producer                                     */
+    VIG_KERNEL_SLAB = 7           /* chunkwise path, one-segment plans: both passes, one launch */
 } vig_kernel;
 int vig_timing_enable(int on);
 int vig_timing_collect(int kernel, double *total_ms, long *launches);

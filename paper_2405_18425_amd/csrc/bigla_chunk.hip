@@ -49,6 +49,8 @@
 //      update.  out = (o_fwd + o_bwd)/2 is written once; q, k, v, g_fwd, g_bwd are read once
 //      here.  Segments the state kernel flagged as mild run fast-form-only code inlined in the
 //      kernel; the others call the general code (both forms) as a separate function.
+//   When a plan has one segment per slab, bigla_slab_kernel runs passes 1 and 3 in a single launch
+//   (a workgroup per slab; no segment states, no flags).
 // Nothing is reversed or copied in HBM; both directions read the same q, k, v.
 //
 // Wavefront mapping (256 threads = 4 waves).  Wave w owns tokens [16w, 16w+16) of the chunk;
@@ -933,10 +935,15 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
 //                     footprint would otherwise spill into the fast path); other segments exit.
 // kFastOnly = false: handles the remaining segments (all of them when seg_mild is nullptr), each
 //                     chunk choosing its form.
-// The output kernel's LDS, at namespace scope so that the inlined fast-form code and the
-// separately compiled general code address the same allocation as LDS (not through a generic
-// reference).
-__shared__ OutLds g_out_lds;
+// The kernels' LDS, at namespace scope so that the inlined fast-form code and the separately
+// compiled general code address the same allocation as LDS (not through a generic reference).
+// The state pass and the output pass use it one after the other (the single-launch kernel for
+// one-segment plans runs both).
+union PathLds {
+    OutLds out;
+    StateLds state;
+};
+__shared__ PathLds g_lds;
 
 template <bool kFastOnly, int kDk, bool kTm>
 __device__ __forceinline__ void out_unit(
@@ -945,7 +952,7 @@ __device__ __forceinline__ void out_unit(
     const float *__restrict__ seg_states, const unsigned char *__restrict__ stash_all, int L, int n_chunks,
     int seg_chunks, int n_seg, const long unit, int heads)
 {
-    OutLds &sm = g_out_lds;
+    OutLds &sm = g_lds.out;
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
     // The fast-form code of a 32-wide head skips the zero half of the key dimension: one K-step per
@@ -1149,22 +1156,23 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
 
 // ---- kernel 1: per-segment end states and per-chunk backward stash -----------------------------
 
+// One (slab, segment) unit of the state pass.  Returns whether every chunk admitted the fast form.
+// seg_states == nullptr (one segment per slab): the end states are not needed and not stored.
 template <int kDk, bool kTm>
-__global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
+__device__ __forceinline__ bool state_unit(
     const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, const uint16_t *__restrict__ g_fwd,
-    const uint16_t *__restrict__ g_bwd, float *__restrict__ seg_states, int *__restrict__ seg_mild,
-    unsigned char *__restrict__ stash, int L, int n_chunks, int seg_chunks, int n_seg,
-    int heads /* used when kTm: activations are [B,L,H,d] */)
+    const uint16_t *__restrict__ g_bwd, float *__restrict__ seg_states, unsigned char *__restrict__ stash, int L,
+    int n_chunks, int seg_chunks, int n_seg, const long unit, int heads)
 {
-    __shared__ StateLds sm;
+    StateLds &sm = g_lds.state;
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
-    const long slab = blockIdx.x / n_seg;
-    const int seg = blockIdx.x % n_seg;
+    const long slab = unit / n_seg;
+    const int seg = int(unit % n_seg);
     const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
     const unsigned key_stride = unsigned(heads) * kDk, val_stride = unsigned(heads) * kD;
     k += row0 * kDk; v += row0 * kD; g_fwd += row0 * kDk; g_bwd += row0 * kDk;
-    float *dst = seg_states + (slab * n_seg + seg) * kSegFloats;
+    float *dst = seg_states ? seg_states + (slab * n_seg + seg) * kSegFloats : nullptr;
     stash += size_t(slab) * n_chunks * kStashBytes;
 
     const int chunk0 = seg * seg_chunks;
@@ -1369,16 +1377,49 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
         __syncthreads();  // every read of this chunk's LDS tiles is done
     }
 
+    if (seg_states) {
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt) {
-        reinterpret_cast<f32x4 *>(dst)[kThreads * jt + tid] = Sf[jt];
-        reinterpret_cast<f32x4 *>(dst + size_t(kD) * kD)[kThreads * jt + tid] = Sb[jt];
+        for (int jt = 0; jt < 4; ++jt) {
+            reinterpret_cast<f32x4 *>(dst)[kThreads * jt + tid] = Sf[jt];
+            reinterpret_cast<f32x4 *>(dst + size_t(kD) * kD)[kThreads * jt + tid] = Sb[jt];
+        }
+        if (r == 0) {
+            *reinterpret_cast<float4 *>(dst + kSegStateFloats + 16 * w + 4 * g) = rf;
+            *reinterpret_cast<float4 *>(dst + kSegStateFloats + kD + 16 * w + 4 * g) = rb;
+        }
     }
-    if (r == 0) {
-        *reinterpret_cast<float4 *>(dst + kSegStateFloats + 16 * w + 4 * g) = rf;
-        *reinterpret_cast<float4 *>(dst + kSegStateFloats + kD + 16 * w + 4 * g) = rb;
-    }
-    if (tid == 0) seg_mild[slab * n_seg + seg] = all_fast ? 1 : 0;
+    return all_fast;
+}
+
+template <int kDk, bool kTm>
+__global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
+    const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, const uint16_t *__restrict__ g_fwd,
+    const uint16_t *__restrict__ g_bwd, float *__restrict__ seg_states, int *__restrict__ seg_mild,
+    unsigned char *__restrict__ stash, int L, int n_chunks, int seg_chunks, int n_seg,
+    int heads /* used when kTm: activations are [B,L,H,d] */)
+{
+    const bool all_fast =
+        state_unit<kDk, kTm>(k, v, g_fwd, g_bwd, seg_states, stash, L, n_chunks, seg_chunks, n_seg, blockIdx.x, heads);
+    if (threadIdx.x == 0) seg_mild[blockIdx.x] = all_fast ? 1 : 0;
+}
+
+// One-segment plans (a workgroup per slab): state pass and output pass in ONE launch.  The stash
+// the state pass writes is read back by the same workgroup (the barrier between the passes orders
+// the global writes before the reads), no segment states or flags go through memory, and the
+// second read of k, v and the gates finds them in L2.
+template <int kDk, bool kTm>
+__global__ __launch_bounds__(kThreads, 2) void bigla_slab_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
+    const uint16_t *__restrict__ g_fwd, const uint16_t *__restrict__ g_bwd, uint16_t *__restrict__ out,
+    unsigned char *__restrict__ stash, int L, int n_chunks, int heads)
+{
+    const long unit = blockIdx.x;
+    const bool all_fast = state_unit<kDk, kTm>(k, v, g_fwd, g_bwd, nullptr, stash, L, n_chunks, n_chunks, 1, unit, heads);
+    __syncthreads();  // stash written (and complete), the state pass's LDS no longer read
+    if (all_fast)     // uniform over the workgroup
+        out_unit<true, kDk, kTm>(q, k, v, g_fwd, g_bwd, out, nullptr, stash, L, n_chunks, n_chunks, 1, unit, heads);
+    else
+        out_unit_general<kDk, kTm>(q, k, v, g_fwd, g_bwd, out, nullptr, stash, L, n_chunks, n_chunks, 1, unit, heads);
 }
 
 // ---- kernel 2: scan of segment states, in place ------------------------------------------------
@@ -1454,6 +1495,13 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
     int *seg_mild = reinterpret_cast<int *>(static_cast<unsigned char *>(workspace) + seg_region_bytes(BH, p));
     unsigned char *stash = reinterpret_cast<unsigned char *>(seg_mild) + flag_region_bytes(BH, p);
     hipError_t e = hipSuccess;
+    uint16_t *oo = static_cast<uint16_t *>(out);
+    if (p.n_seg == 1 && p.n_chunks > 1) {  // one workgroup per slab does both passes in one launch
+        LaunchTimer timer(kKernelSlab, stream);
+        hipLaunchKernelGGL((bigla_slab_kernel<kDk, kTm>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk, vv,
+                           gf, gb, oo, stash, L, p.n_chunks, heads_token_major);
+        return hipGetLastError();
+    }
     if (p.n_chunks > 1) {  // a single chunk has neither a stash nor entering states
         {
             LaunchTimer timer(kKernelSegmentState, stream);
@@ -1475,7 +1523,6 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
     }
     const float *seg_in = p.n_seg > 1 ? seg_states : nullptr;
     const int *flags = p.n_chunks > 1 ? seg_mild : nullptr;
-    uint16_t *oo = static_cast<uint16_t *>(out);
     {
         LaunchTimer timer(flags ? kKernelSegmentOut : kKernelSegmentOutGeneral, stream);
         if (flags)

@@ -14,7 +14,8 @@ enum KernelId {
     kKernelLocalityGate = 4,
     kKernelSegmentOutGeneral = 5,
     kKernelGateProducer = 6,
-    kKernelCount = 7
+    kKernelSlab = 7,
+    kKernelCount = 8
 };
 
 // Brackets one launch when timing is enabled on the calling thread.
