@@ -28,7 +28,8 @@ typedef enum {
     VIG_ERR_NULL = -1,        /* a required pointer is NULL                              */
     VIG_ERR_SHAPE = -2,       /* a size is <= 0 or the product of sizes overflows        */
     VIG_ERR_DTYPE = -3,       /* dtype is not a vig_dtype                                */
-    VIG_ERR_UNSUPPORTED = -4, /* dk or dv outside {16, 32, 64}; D not a multiple of 32   */
+    VIG_ERR_UNSUPPORTED = -4, /* dk or dv outside {16, 32, 64}; D not a multiple of 32;
+                                 a plan the shape does not admit                         */
     VIG_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned                        */
     VIG_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than bigla_workspace_bytes()  */
     VIG_ERR_HIP = -7,         /* a HIP call failed; see vig_last_hip_error()             */
@@ -120,6 +121,32 @@ int locality_gate_fwd(const void *x, const void *w, const void *bias, const void
 int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, const void *gate_logits,
                              const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv,
                              int dtype, int layout, void *stream);
+
+/*
+ * The two steps above as one call -- Section 4.2.2, Eq. (2D gating), lines 2 and 4, with the
+ * gate logits given:
+ *     out = G * DWConv3x3(x) + (1 - G) * BiGLA(q, k, v, g_fwd, g_bwd),   G = sigmoid(gate_logits)
+ * for L = Hg * Wg tokens in raster order.  Arguments as for bigla_fwd_layout and
+ * locality_gate_fwd_layout (all activations in `layout`; Hg * Wg below 2^24).  `plan` (a vig_plan):
+ *   VIG_PLAN_TWO_LAUNCHES     the token mixer writes its output into the workspace and the locality
+ *                             kernel reads it back (any supported shape and dtype);
+ *   VIG_PLAN_FUSED_EPILOGUE   the output pass of the chunkwise path applies the blend to each chunk's
+ *                             rows before writing them, so the token mixer's output (rounded to bf16
+ *                             as bigla_fwd would store it) never goes through memory.  VIG_BF16 with
+ *                             dv = 64 and dk = 64 or 32 only (VIG_ERR_UNSUPPORTED otherwise);
+ *   VIG_PLAN_AUTO             the faster of the two for the shape: at present always two launches
+ *                             (the output pass is bound by its vector arithmetic, and the blend's
+ *                             arithmetic costs more there than a second pass over memory).
+ * Either plan returns bit for bit what bigla_fwd_layout followed by locality_gate_fwd_layout returns.
+ * workspace: at least bigla_locality_workspace_bytes(B, H, Hg*Wg, dk, dv, dtype, plan) bytes
+ * (that function returns 0 for invalid or unsupported arguments).
+ */
+typedef enum { VIG_PLAN_AUTO = 0, VIG_PLAN_TWO_LAUNCHES = 1, VIG_PLAN_FUSED_EPILOGUE = 2 } vig_plan;
+size_t bigla_locality_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype, int plan);
+int bigla_locality_fwd(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                       const void *x, const void *w, const void *bias, const void *gate_logits, void *out,
+                       int B, int H, int Hg, int Wg, int dk, int dv, int dtype, int layout, int plan,
+                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Direction-wise forget gates -- Section 3 (low-rank gate, temperature tau) and the first two

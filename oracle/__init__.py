@@ -157,3 +157,11 @@ def locality_gate(x, w, gate_logits, o_global, Hg: int, Wg: int, bias=None, nthr
 
 def gate_producer(x, w1, w2, H: int, dk: int, bias=None, tau: float = 16.0, nthreads: int = 0):
     return default().gate_producer(x, w1, w2, H, dk, bias, tau, nthreads)
+
+
+def bigla_locality(q, k, v, g_fwd, g_bwd, x, w, gate_logits, Hg: int, Wg: int, bias=None,
+                   nthreads: int = 0) -> np.ndarray:
+    """The block's two steps chained (Section 4.2.2, the gating equation with O_global taken from
+    Section 4.2.1): the token mixer's output, unrounded, is the global branch of the blend."""
+    o_global = bigla(q, k, v, g_fwd, g_bwd, nthreads)
+    return locality_gate(x, w, gate_logits, o_global, Hg, Wg, bias, nthreads)

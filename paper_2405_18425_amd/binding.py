@@ -21,10 +21,12 @@ VIG_ERR_ALIGN, VIG_ERR_WORKSPACE, VIG_ERR_HIP, VIG_ERR_LAYOUT = -5, -6, -7, -8
 VIG_F32, VIG_BF16 = 0, 1
 VIG_LAYOUT_BHLD, VIG_LAYOUT_BLHD = 0, 1
 LAYOUTS = {"bhld": VIG_LAYOUT_BHLD, "blhd": VIG_LAYOUT_BLHD}
+PLANS = {"auto": 0, "two_launches": 1, "fused_epilogue": 2}
 
 # every symbol include/vig_bigla.h declares
 EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "locality_gate_fwd",
-           "locality_gate_fwd_layout", "gate_producer_fwd", "vig_status_str", "vig_last_hip_error", "vig_timing_enable",
+           "locality_gate_fwd_layout", "bigla_locality_workspace_bytes", "bigla_locality_fwd", "gate_producer_fwd",
+           "vig_status_str", "vig_last_hip_error", "vig_timing_enable",
            "vig_timing_collect")
 KERNELS = {"segment_state": 0, "state_scan": 1, "segment_out": 2, "recurrent": 3, "locality_gate": 4,
            "segment_out_general": 5, "gate_producer": 6, "slab": 7}
@@ -57,6 +59,10 @@ def lib() -> ctypes.CDLL:
         L.locality_gate_fwd.restype = ci
         L.locality_gate_fwd_layout.argtypes = [vp] * 6 + [ci] * 7 + [vp]
         L.locality_gate_fwd_layout.restype = ci
+        L.bigla_locality_workspace_bytes.argtypes = [ci] * 7
+        L.bigla_locality_workspace_bytes.restype = sz
+        L.bigla_locality_fwd.argtypes = [vp] * 10 + [ci] * 9 + [vp, sz, vp]
+        L.bigla_locality_fwd.restype = ci
         L.gate_producer_fwd.argtypes = [vp] * 6 + [ci] * 5 + [ctypes.c_float, ci, ci, vp]
         L.gate_producer_fwd.restype = ci
         L.vig_status_str.argtypes = [ci]
@@ -195,6 +201,55 @@ def locality_gate_fwd(x, w, gate_logits, o_global, Hg: int, Wg: int, bias=None, 
                                                 o_global.data_ptr(), out.data_ptr(), B, H, Hg, Wg, dv,
                                                 _dtype_code(x), lay, _stream_ptr(x.device))
     _check(st, "locality_gate_fwd")
+    return out
+
+
+def bigla_locality_fwd(q, k, v, g_fwd, g_bwd, x, w, gate_logits, Hg: int, Wg: int, bias=None, out=None,
+                       workspace=None, layout="bhld", plan="auto"):
+    """Token mixer and locality blend in one call (Sections 4.2.1 and 4.2.2):
+    out = G * DWConv3x3(x) + (1 - G) * BiGLA(q, k, v, g_fwd, g_bwd), G = sigmoid(gate_logits).
+    Tensors as for bigla_fwd and locality_gate_fwd, L = Hg*Wg.  plan: "auto", "two_launches" or
+    "fused_epilogue" (the blend inside the chunkwise output pass; bf16, dv = 64, dk = 64 or 32).
+    """
+    lay = _layout_code(layout)
+    if plan not in PLANS:
+        raise VigError(VIG_ERR_UNSUPPORTED, f"plan must be one of {sorted(PLANS)}")
+    q = _dev(q, "q")
+    if q.dim() != 4:
+        raise VigError(VIG_ERR_SHAPE, "q must be 4-dimensional")
+    if lay == VIG_LAYOUT_BHLD:
+        B, H, L, dk = q.shape
+    else:
+        B, L, H, dk = q.shape
+    if L != Hg * Wg:
+        raise VigError(VIG_ERR_SHAPE, "the sequence length must equal Hg*Wg")
+    k = _dev(k, "k", q.shape, q)
+    g_fwd = _dev(g_fwd, "g_fwd", q.shape, q)
+    g_bwd = _dev(g_bwd, "g_bwd", q.shape, q)
+    v = _dev(v, "v", like=q)
+    if v.dim() != 4 or tuple(v.shape[:3]) != tuple(q.shape[:3]):
+        raise VigError(VIG_ERR_SHAPE, "v must have the leading dimensions of q")
+    dv = v.shape[3]
+    x = _dev(x, "x", v.shape, q)
+    gate_logits = _dev(gate_logits, "gate_logits", v.shape, q)
+    w = _dev(w, "w", (H * dv, 3, 3), q)
+    if bias is not None:
+        bias = _dev(bias, "bias", (H * dv,), q)
+    if out is None:
+        out = torch.empty(tuple(v.shape), dtype=q.dtype, device=q.device)
+    out = _dev(out, "out", tuple(v.shape), q)
+    code = _dtype_code(q)
+    need = int(lib().bigla_locality_workspace_bytes(B, H, L, dk, dv, code, PLANS[plan]))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(q.device):
+        st = lib().bigla_locality_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), g_fwd.data_ptr(), g_bwd.data_ptr(),
+                                      x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None,
+                                      gate_logits.data_ptr(), out.data_ptr(), B, H, Hg, Wg, dk, dv, code, lay,
+                                      PLANS[plan], ws_ptr, ws_bytes, _stream_ptr(q.device))
+    _check(st, "bigla_locality_fwd")
     return out
 
 

@@ -410,6 +410,8 @@ struct __align__(16) OutLds {
     uint16_t sb[kD][kPitch];    // stashed backward state entering the chunk, same layout
     float tot[kD];              // forward chunk total log-gate per channel (fast form), operand order
     float eb[2][4][kD];         // whole-sub-block decay factors per channel (range-safe form)
+    float cw[9][kD];            // fused locality epilogue: the head's 3x3 taps, [tap][channel]
+    float cb[kD];               //                          and its conv bias
 };
 
 struct __align__(16) StateLds {
@@ -589,16 +591,29 @@ struct ChunkFlags {
     bool seg;    // a backward state enters the segment from the right
 };
 
+// One slab's inputs of the fused 2D gating locality injection (Section 4.2.2): the conv input and
+// the gate logits as buffer resources whose rows sit at the activations' token pitch.  Taps that
+// fall off the grid, and rows past the sequence, are requested at kOffGrid, which is beyond the
+// resource's extent: the bounds check of the load returns zeros for them, the conv's zero padding.
+struct LocalitySlab {
+    __amdgpu_buffer_rsrc_t x, z;
+    int Hg, Wg;
+};
+constexpr unsigned kOffGrid = 0xfffffff0u;
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
 // Everything after the score tiles, common to both forms: O^T = V^T P^T + the three readouts,
 // out = O/2, then the forward state update with the keys in `ktile`.
 // fast_update: S = d (S + K^T V) with d = exp(tot); otherwise S = d S + K^T V with d = prod(eb).
 // kKs = 1 (32-wide head, fast-form code only): state rows 32..63 are identically zero, so the waves
 // that own them (w >= 2) skip the state update and nobody reads the upper K-step of a state tile.
-template <bool kTm, int kKs, class Prefetch>
+// kLoc: the locality blend is applied to the chunk's rows before they are written (below).
+template <bool kTm, int kKs, bool kLoc, class Prefetch>
 __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)[kPitch], const ChunkOperands &op,
                                              const ChunkFlags fl, const bool fast_update, const int w, const int r,
                                              const int g, uint16_t *out_slab, const long chunk_token0, const int L,
-                                             const unsigned out_tok_stride, f32x4 (&S)[4], Prefetch &&prefetch)
+                                             const unsigned out_tok_stride, f32x4 (&S)[4], const LocalitySlab &ls,
+                                             Prefetch &&prefetch)
 {
     const uint2(&pk)[4] = op.pk;
     bf16x8 vop[2][4];
@@ -622,9 +637,9 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
     prefetch(2);
     if (fl.stash || fl.seg) readout<kKs>(sm.sb, op.qb0, op.qb1, r, g, O);
     prefetch(3);
+    const int lane = 16 * g + r;
     {  // o_t = (o_fwd_t + o_bwd_t) / 2, turned into whole rows through the wave's own rows of the
        // forward gate tile (last read before the score tiles), then written 8 rows per store
-        const int lane = 16 * g + r;
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt)
             *reinterpret_cast<uint2 *>(&sm.gf[16 * w + r][16 * jt + 4 * g]) =
@@ -636,7 +651,9 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
             const uint4 o = *reinterpret_cast<const uint4 *>(&sm.gf[rr][8 * (lane & 7)]);
             const long tok = chunk_token0 + rr;
             const size_t row_off = kTm ? size_t(__umul24(unsigned(tok), out_tok_stride)) : size_t(tok) * kD;
-            if (tok < L) *reinterpret_cast<uint4 *>(out_slab + row_off + 8 * (lane & 7)) = o;
+            if (!kLoc) {
+                if (tok < L) *reinterpret_cast<uint4 *>(out_slab + row_off + 8 * (lane & 7)) = o;
+            }
         }
     }
 
@@ -678,6 +695,62 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
 
     __syncthreads();  // every LDS read of this step is done
     if (owns_rows) publish_state(sm.st, w, r, g, S);
+
+    if (kLoc) {
+        // out = G * (bias + sum_taps w * x) + (1 - G) * o, G = sigmoid(z): the arithmetic (fp32,
+        // taps in row-major order) of the stand-alone locality kernel, on the o rounded to bf16.
+        // One token row at a time (the lane's piece, 8 channels, of its 3x3 neighbourhood is ten
+        // 16-byte loads); o is still in the wave's rows of the gate tile.
+        const int c0 = 8 * (lane & 7);
+        const unsigned pitch_b = (kTm ? out_tok_stride : unsigned(kD)) * 2u;
+#pragma unroll 1
+        for (int t = 0; t < 2; ++t) {
+            const int rr = 16 * w + 8 * t + (lane >> 3);
+            const long tok = chunk_token0 + rr;
+            const unsigned row_off = kTm ? __umul24(unsigned(tok), out_tok_stride) : unsigned(tok) * kD;
+            const unsigned own = (row_off + c0) * 2u;
+            const int y = int(tok) / ls.Wg, xp = int(tok) - y * ls.Wg;
+            u32x4 x_nb[9];
+#pragma unroll
+            for (int ky = -1; ky <= 1; ++ky)
+#pragma unroll
+                for (int kx = -1; kx <= 1; ++kx) {
+                    const bool in = unsigned(y + ky) < unsigned(ls.Hg) && unsigned(xp + kx) < unsigned(ls.Wg);
+                    const unsigned off = own + unsigned(ky * ls.Wg + kx) * pitch_b;
+                    x_nb[3 * (ky + 1) + kx + 1] = __builtin_amdgcn_raw_buffer_load_b128(ls.x, in ? off : kOffGrid, 0, 0);
+                }
+            const u32x4 z_row = __builtin_amdgcn_raw_buffer_load_b128(ls.z, tok < L ? own : kOffGrid, 0, 0);
+            float acc[8];
+            {
+                const float4 b0 = *reinterpret_cast<const float4 *>(&sm.cb[c0]);
+                const float4 b1 = *reinterpret_cast<const float4 *>(&sm.cb[c0 + 4]);
+                acc[0] = b0.x; acc[1] = b0.y; acc[2] = b0.z; acc[3] = b0.w;
+                acc[4] = b1.x; acc[5] = b1.y; acc[6] = b1.z; acc[7] = b1.w;
+            }
+#pragma unroll
+            for (int tap = 0; tap < 9; ++tap) {
+                const float4 w0 = *reinterpret_cast<const float4 *>(&sm.cw[tap][c0]);
+                const float4 w1 = *reinterpret_cast<const float4 *>(&sm.cw[tap][c0 + 4]);
+                const float wt[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+                float xf[8];
+                unpack8(make_uint4(x_nb[tap].x, x_nb[tap].y, x_nb[tap].z, x_nb[tap].w), xf);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] = fmaf(wt[e], xf[e], acc[e]);
+            }
+            float zf[8], of[8];
+            unpack8(make_uint4(z_row.x, z_row.y, z_row.z, z_row.w), zf);
+            unpack8(*reinterpret_cast<const uint4 *>(&sm.gf[rr][c0]), of);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float gate = __builtin_amdgcn_rcpf(1.f + __expf(-zf[e]));
+                acc[e] = fmaf(gate, acc[e] - of[e], of[e]);
+            }
+            if (tok < L)
+                *reinterpret_cast<uint4 *>(out_slab + row_off + c0) =
+                    make_uint4(pack2(acc[0], acc[1]), pack2(acc[2], acc[3]), pack2(acc[4], acc[5]),
+                               pack2(acc[6], acc[7]));
+        }
+    }
 }
 
 // Merged score tiles of the fast form and the readout queries, from this lane's scaled operands
@@ -945,12 +1018,14 @@ union PathLds {
 };
 __shared__ PathLds g_lds;
 
-template <bool kFastOnly, int kDk, bool kTm>
+// kLoc: the 2D gating locality injection of `lf` is applied to every chunk's rows before they are
+// written, so that `out_all` receives the block output instead of the token mixer's.
+template <bool kFastOnly, int kDk, bool kTm, bool kLoc>
 __device__ __forceinline__ void out_unit(
     const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
     const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
     const float *__restrict__ seg_states, const unsigned char *__restrict__ stash_all, int L, int n_chunks,
-    int seg_chunks, int n_seg, const long unit, int heads)
+    int seg_chunks, int n_seg, const long unit, int heads, const LocalityFusion &lf)
 {
     OutLds &sm = g_lds.out;
     const int tid = threadIdx.x;
@@ -976,6 +1051,33 @@ __device__ __forceinline__ void out_unit(
     const float *st_in = seg_states ? seg_states + (slab * n_seg + seg) * kSegFloats : nullptr;
     const bool seg_in = st_in != nullptr && seg + 1 < n_seg;  // the last segment's entering backward state is zero
     const int row = 16 * w + r;
+
+    LocalitySlab ls;
+    if (kLoc) {
+        // the head's taps and bias as fp32 in LDS (read after the first barrier of the first step)
+        const int head = int(slab % lf.H);
+        const uint16_t *taps = static_cast<const uint16_t *>(lf.w) + size_t(head) * kD * 9;
+        for (int i = tid; i < kD * 9; i += kThreads) sm.cw[i % 9][i / 9] = bf16_lo_to_f32(taps[i]);
+        if (tid < kD)
+            sm.cb[tid] = lf.bias ? bf16_lo_to_f32(static_cast<const uint16_t *>(lf.bias)[head * kD + tid]) : 0.f;
+        // the slab's rows from its first token to the end of its last token's row
+        const unsigned extent = unsigned(L - 1) * (kTm ? val_stride : unsigned(kD)) * 2u + unsigned(kD) * 2u;
+        const unsigned kRawDwords = 0x00020000u;  // untyped 32-bit data, bounds check on the byte offset
+        // (the addresses are the same in every lane; saying so keeps the resources in scalar registers)
+        auto slab_rows = [&](const void *all) {
+            const uintptr_t a = reinterpret_cast<uintptr_t>(static_cast<const uint16_t *>(all) + base);
+            // (the builtin returns a signed int: widen through unsigned, not by sign extension)
+            const uintptr_t lo = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a))));
+            const uintptr_t hi = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a >> 32))));
+            return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(lo | (hi << 32)), 0,
+                                                     int(unsigned(__builtin_amdgcn_readfirstlane(int(extent)))),
+                                                     int(kRawDwords));
+        };
+        ls.x = slab_rows(lf.x);
+        ls.z = slab_rows(lf.gate_logits);
+        ls.Hg = lf.Hg;
+        ls.Wg = lf.Wg;
+    }
 
     // rows of the next chunk are fetched while the current chunk is being processed
     struct ChunkRows {
@@ -1117,41 +1219,41 @@ __device__ __forceinline__ void out_unit(
             fetch_part(next, m + 1, 2);
             fetch_part(next, m + 1, 3);
         }
-        finish_chunk<kTm, kKs>(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L, val_stride, S,
-                     prefetch_second_half);
+        finish_chunk<kTm, kKs, kLoc>(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L,
+                                     val_stride, S, ls, prefetch_second_half);
     }
 }
 
-template <int kDk, bool kTm>
+template <int kDk, bool kTm, bool kLoc>
 __device__ __attribute__((noinline)) void out_unit_general(
     const uint16_t *q_all, const uint16_t *k_all, const uint16_t *v_all, const uint16_t *gf_all, const uint16_t *gb_all,
     uint16_t *out_all, const float *seg_states, const unsigned char *stash_all, int L, int n_chunks, int seg_chunks,
-    int n_seg, const long unit, int heads)
+    int n_seg, const long unit, int heads, const LocalityFusion &lf)
 {
-    out_unit<false, kDk, kTm>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L, n_chunks,
-                              seg_chunks, n_seg, unit, heads);
+    out_unit<false, kDk, kTm, kLoc>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L, n_chunks,
+                                    seg_chunks, n_seg, unit, heads, lf);
 }
 
 // One workgroup per (slab, segment) unit.  kByFlag: units the state kernel flagged as mild run the
 // fast-form code inline; the others call the general code as a real function, so that its
 // register appetite (spilled to its own stack frame) does not touch the fast path's allocation
 // and one launch serves both.  !kByFlag (single-chunk sequences, no flags): general code only.
-template <bool kByFlag, int kDk, bool kTm>
+template <bool kByFlag, int kDk, bool kTm, bool kLoc>
 __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
     const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
     const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
     const float *__restrict__ seg_states /* states entering each segment, nullptr when one segment */,
     const int *__restrict__ seg_mild /* per unit: every chunk admits the fast form (kByFlag) */,
     const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg,
-    int heads /* used when kTm: activations are [B,L,H,d] */)
+    int heads /* used when kTm: activations are [B,L,H,d] */, const LocalityFusion lf /* used when kLoc */)
 {
     const long unit = blockIdx.x;
     if (kByFlag && seg_mild[unit] != 0)  // uniform over the workgroup
-        out_unit<true, kDk, kTm>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L, n_chunks,
-                                 seg_chunks, n_seg, unit, heads);
+        out_unit<true, kDk, kTm, kLoc>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
+                                       n_chunks, seg_chunks, n_seg, unit, heads, lf);
     else
-        out_unit_general<kDk, kTm>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
-                                   n_chunks, seg_chunks, n_seg, unit, heads);
+        out_unit_general<kDk, kTm, kLoc>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
+                                         n_chunks, seg_chunks, n_seg, unit, heads, lf);
 }
 
 // ---- kernel 1: per-segment end states and per-chunk backward stash -----------------------------
@@ -1407,19 +1509,21 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
 // the state pass writes is read back by the same workgroup (the barrier between the passes orders
 // the global writes before the reads), no segment states or flags go through memory, and the
 // second read of k, v and the gates finds them in L2.
-template <int kDk, bool kTm>
+template <int kDk, bool kTm, bool kLoc>
 __global__ __launch_bounds__(kThreads, 2) void bigla_slab_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     const uint16_t *__restrict__ g_fwd, const uint16_t *__restrict__ g_bwd, uint16_t *__restrict__ out,
-    unsigned char *__restrict__ stash, int L, int n_chunks, int heads)
+    unsigned char *__restrict__ stash, int L, int n_chunks, int heads, const LocalityFusion lf)
 {
     const long unit = blockIdx.x;
     const bool all_fast = state_unit<kDk, kTm>(k, v, g_fwd, g_bwd, nullptr, stash, L, n_chunks, n_chunks, 1, unit, heads);
     __syncthreads();  // stash written (and complete), the state pass's LDS no longer read
     if (all_fast)     // uniform over the workgroup
-        out_unit<true, kDk, kTm>(q, k, v, g_fwd, g_bwd, out, nullptr, stash, L, n_chunks, n_chunks, 1, unit, heads);
+        out_unit<true, kDk, kTm, kLoc>(q, k, v, g_fwd, g_bwd, out, nullptr, stash, L, n_chunks, n_chunks, 1, unit,
+                                       heads, lf);
     else
-        out_unit_general<kDk, kTm>(q, k, v, g_fwd, g_bwd, out, nullptr, stash, L, n_chunks, n_chunks, 1, unit, heads);
+        out_unit_general<kDk, kTm, kLoc>(q, k, v, g_fwd, g_bwd, out, nullptr, stash, L, n_chunks, n_chunks, 1, unit,
+                                         heads, lf);
 }
 
 // ---- kernel 2: scan of segment states, in place ------------------------------------------------
@@ -1481,9 +1585,10 @@ size_t bigla_chunk_workspace_bytes(long BH, int L)
 }
 
 namespace {
-template <int kDk, bool kTm>
+template <int kDk, bool kTm, bool kLoc>
 hipError_t chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd, void *out,
-                        long BH, int L, int heads_token_major, void *workspace, hipStream_t stream)
+                        long BH, int L, int heads_token_major, const LocalityFusion &lf, void *workspace,
+                        hipStream_t stream)
 {
     const Plan p = make_plan(BH, L);
     const long blocks = BH * p.n_seg;
@@ -1498,8 +1603,8 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
     uint16_t *oo = static_cast<uint16_t *>(out);
     if (p.n_seg == 1 && p.n_chunks > 1) {  // one workgroup per slab does both passes in one launch
         LaunchTimer timer(kKernelSlab, stream);
-        hipLaunchKernelGGL((bigla_slab_kernel<kDk, kTm>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq, kk, vv,
-                           gf, gb, oo, stash, L, p.n_chunks, heads_token_major);
+        hipLaunchKernelGGL((bigla_slab_kernel<kDk, kTm, kLoc>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq,
+                           kk, vv, gf, gb, oo, stash, L, p.n_chunks, heads_token_major, lf);
         return hipGetLastError();
     }
     if (p.n_chunks > 1) {  // a single chunk has neither a stash nor entering states
@@ -1526,31 +1631,42 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
     {
         LaunchTimer timer(flags ? kKernelSegmentOut : kKernelSegmentOutGeneral, stream);
         if (flags)
-            hipLaunchKernelGGL((bigla_segment_out_kernel<true, kDk, kTm>), dim3((unsigned)blocks), dim3(kThreads), 0,
-                               stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks,
-                               p.n_seg, heads_token_major);
+            hipLaunchKernelGGL((bigla_segment_out_kernel<true, kDk, kTm, kLoc>), dim3((unsigned)blocks),
+                               dim3(kThreads), 0, stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks,
+                               p.seg_chunks, p.n_seg, heads_token_major, lf);
         else  // a single chunk per sequence: no state kernel has run, no flags exist
-            hipLaunchKernelGGL((bigla_segment_out_kernel<false, kDk, kTm>), dim3((unsigned)blocks), dim3(kThreads), 0,
-                               stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks, p.seg_chunks,
-                               p.n_seg, heads_token_major);
+            hipLaunchKernelGGL((bigla_segment_out_kernel<false, kDk, kTm, kLoc>), dim3((unsigned)blocks),
+                               dim3(kThreads), 0, stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks,
+                               p.seg_chunks, p.n_seg, heads_token_major, lf);
     }
     return hipGetLastError();
 }
 }  // namespace
 
 hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
-                              void *out, long BH, int L, int dk, int heads_token_major, void *workspace,
-                              hipStream_t stream)
+                              void *out, long BH, int L, int dk, int heads_token_major, const LocalityFusion *fusion,
+                              void *workspace, hipStream_t stream)
 {
     const bool tm = heads_token_major > 0;
-    if (dk == kD && !tm) return chunk_launch<kD, false>(q, k, v, g_fwd, g_bwd, out, BH, L, 1, workspace, stream);
-    if (dk == kD && tm)
-        return chunk_launch<kD, true>(q, k, v, g_fwd, g_bwd, out, BH, L, heads_token_major, workspace, stream);
-    if (dk == kD / 2 && !tm)
-        return chunk_launch<kD / 2, false>(q, k, v, g_fwd, g_bwd, out, BH, L, 1, workspace, stream);
-    if (dk == kD / 2 && tm)
-        return chunk_launch<kD / 2, true>(q, k, v, g_fwd, g_bwd, out, BH, L, heads_token_major, workspace, stream);
-    return hipErrorInvalidValue;
+    const int heads = tm ? heads_token_major : 1;
+    if (dk != kD && dk != kD / 2) return hipErrorInvalidValue;
+    const LocalityFusion none = {};
+    // (key width, layout, fused epilogue) pick the instantiation
+    auto go = [&](auto dk_c, auto tm_c, auto loc_c) {
+        return chunk_launch<decltype(dk_c)::value, decltype(tm_c)::value, decltype(loc_c)::value>(
+            q, k, v, g_fwd, g_bwd, out, BH, L, heads, fusion ? *fusion : none, workspace, stream);
+    };
+    using std::integral_constant;
+    using std::true_type;
+    using std::false_type;
+    typedef integral_constant<int, kD> wide;
+    typedef integral_constant<int, kD / 2> half;
+    if (fusion) {
+        if (dk == kD) return tm ? go(wide{}, true_type{}, true_type{}) : go(wide{}, false_type{}, true_type{});
+        return tm ? go(half{}, true_type{}, true_type{}) : go(half{}, false_type{}, true_type{});
+    }
+    if (dk == kD) return tm ? go(wide{}, true_type{}, false_type{}) : go(wide{}, false_type{}, false_type{});
+    return tm ? go(half{}, true_type{}, false_type{}) : go(half{}, false_type{}, false_type{});
 }
 
 }  // namespace vig

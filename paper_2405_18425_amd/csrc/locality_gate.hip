@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void locality_gate_kernel(
                 }
 #pragma unroll
             for (int e = 0; e < N; ++e) {
-                const float gate = __frcp_rn(1.f + __expf(-zf[e]));
+                const float gate = __builtin_amdgcn_rcpf(1.f + __expf(-zf[e]));
                 // G * O_local + (1 - G) * O_global
                 res[e] = fmaf(gate, res[e] - gf[e], gf[e]);
             }

@@ -81,7 +81,7 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
     const int heads_token_major = layout == VIG_LAYOUT_BLHD ? H : 0;
     if (vig::bigla_chunk_supported(dk, dv, bf16))
         return hip_status(
-            vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, heads_token_major, workspace, s));
+            vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, heads_token_major, nullptr, workspace, s));
     return hip_status(vig::bigla_recurrent_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, dv, bf16,
                                                   heads_token_major, workspace, s));
 }
@@ -112,6 +112,68 @@ int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, con
                                                 static_cast<hipStream_t>(stream)));
 }
 
+namespace {
+size_t align256(size_t n) { return (n + 255) / 256 * 256; }
+}  // namespace
+
+size_t bigla_locality_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype, int plan)
+{
+    if (B <= 0 || H <= 0 || L <= 0 || !head_dim_ok(dk) || !head_dim_ok(dv)) return 0;
+    if (dtype != VIG_F32 && dtype != VIG_BF16) return 0;
+    if (plan != VIG_PLAN_AUTO && plan != VIG_PLAN_TWO_LAUNCHES && plan != VIG_PLAN_FUSED_EPILOGUE) return 0;
+    const size_t mixer = bigla_workspace_bytes(B, H, L, dk, dv, dtype);
+    if (plan == VIG_PLAN_FUSED_EPILOGUE) return vig::bigla_chunk_supported(dk, dv, dtype == VIG_BF16) ? mixer : 0;
+    if (!sizes_ok(B, H, L, dv)) return 0;
+    // the token mixer's output goes through the workspace
+    return align256(mixer) + size_t(B) * H * L * dv * (dtype == VIG_BF16 ? 2 : 4);
+}
+
+int bigla_locality_fwd(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                       const void *x, const void *w, const void *bias, const void *gate_logits, void *out, int B,
+                       int H, int Hg, int Wg, int dk, int dv, int dtype, int layout, int plan, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    if (!q || !k || !v || !g_fwd || !g_bwd || !x || !w || !gate_logits || !out) return VIG_ERR_NULL;
+    if (layout != VIG_LAYOUT_BHLD && layout != VIG_LAYOUT_BLHD) return VIG_ERR_LAYOUT;
+    if (plan != VIG_PLAN_AUTO && plan != VIG_PLAN_TWO_LAUNCHES && plan != VIG_PLAN_FUSED_EPILOGUE)
+        return VIG_ERR_UNSUPPORTED;
+    if (B <= 0 || H <= 0 || Hg <= 0 || Wg <= 0 || dk <= 0 || dv <= 0) return VIG_ERR_SHAPE;
+    if (long(Hg) * Wg >= (1L << 24)) return VIG_ERR_SHAPE;
+    const int L = Hg * Wg;
+    if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
+    if (!head_dim_ok(dk) || !head_dim_ok(dv)) return VIG_ERR_UNSUPPORTED;
+    const bool bf16 = dtype == VIG_BF16;
+    if (plan != VIG_PLAN_FUSED_EPILOGUE) {
+        // the token mixer into the workspace, then the locality kernel (both validate their arguments)
+        const size_t mixer = align256(bigla_workspace_bytes(B, H, L, dk, dv, dtype));
+        const size_t need = bigla_locality_workspace_bytes(B, H, L, dk, dv, dtype, plan);
+        if (need == 0) return VIG_ERR_SHAPE;
+        if (!workspace || workspace_bytes < need) return VIG_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return VIG_ERR_ALIGN;
+        void *o_global = static_cast<unsigned char *>(workspace) + mixer;
+        const int st = bigla_fwd_layout(q, k, v, g_fwd, g_bwd, o_global, B, H, L, dk, dv, dtype, layout, workspace,
+                                        mixer, stream);
+        if (st != VIG_OK) return st;
+        return locality_gate_fwd_layout(x, w, bias, gate_logits, o_global, out, B, H, Hg, Wg, dv, dtype, layout,
+                                        stream);
+    }
+    if (!vig::bigla_chunk_supported(dk, dv, bf16)) return VIG_ERR_UNSUPPORTED;
+    if (!sizes_ok(B, H, L, dk > dv ? dk : dv) || long(B) * H > 0x7fffffffL) return VIG_ERR_SHAPE;
+    // rows of a slab are addressed with 32-bit byte offsets (token-major: over one batch element)
+    if (layout == VIG_LAYOUT_BLHD && (long(H) * 64 >= (1 << 24) || long(L) * H * 64 * 2 >= 0xffffff00L))
+        return VIG_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g_fwd) || !aligned16(g_bwd) ||
+        !aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(gate_logits) || !aligned16(out) ||
+        !aligned16(workspace))
+        return VIG_ERR_ALIGN;
+    const size_t need = bigla_workspace_bytes(B, H, L, dk, dv, dtype);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return VIG_ERR_WORKSPACE;
+    const vig::LocalityFusion fusion = {x, w, bias, gate_logits, H, Hg, Wg};
+    return hip_status(vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, long(B) * H, L, dk,
+                                              layout == VIG_LAYOUT_BLHD ? H : 0, &fusion, workspace,
+                                              static_cast<hipStream_t>(stream)));
+}
+
 int gate_producer_fwd(const void *x, const void *w1, const void *w2, const void *bias, void *g_fwd, void *g_bwd,
                       int B, int H, int L, int D, int dk, float tau, int dtype, int layout, void *stream)
 {
@@ -136,7 +198,9 @@ const char *vig_status_str(int status)
         case VIG_ERR_NULL: return "VIG_ERR_NULL: a required pointer is NULL";
         case VIG_ERR_SHAPE: return "VIG_ERR_SHAPE: a size is <= 0 or too large";
         case VIG_ERR_DTYPE: return "VIG_ERR_DTYPE: dtype is not VIG_F32 or VIG_BF16";
-        case VIG_ERR_UNSUPPORTED: return "VIG_ERR_UNSUPPORTED: head widths must be 16, 32 or 64 (model width a multiple of 32)";
+        case VIG_ERR_UNSUPPORTED:
+            return "VIG_ERR_UNSUPPORTED: head widths must be 16, 32 or 64 (model width a multiple of 32); plan a vig_plan "
+                   "the shape admits";
         case VIG_ERR_ALIGN: return "VIG_ERR_ALIGN: a pointer is not 16-byte aligned";
         case VIG_ERR_WORKSPACE: return "VIG_ERR_WORKSPACE: workspace missing or too small";
         case VIG_ERR_HIP: return "VIG_ERR_HIP: a HIP call failed (see vig_last_hip_error)";

@@ -19,9 +19,16 @@ hipError_t bigla_recurrent_launch(const void *q, const void *k, const void *v, c
 // ---- chunkwise bf16 MFMA path (dv = 64, dk = 64 or 32) ----------------------------------------
 bool bigla_chunk_supported(int dk, int dv, bool is_bf16);
 size_t bigla_chunk_workspace_bytes(long BH, int L);
+// Inputs of the 2D gating locality injection when the chunkwise output pass applies it to its rows
+// before writing them (x and gate_logits in the activations' layout, L = Hg * Wg).
+struct LocalityFusion {
+    const void *x, *w, *bias /* may be null */, *gate_logits;
+    int H, Hg, Wg;
+};
+// fusion == nullptr: out receives the token mixer's output; otherwise the block output
 hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
-                              void *out, long BH, int L, int dk, int heads_token_major, void *workspace,
-                              hipStream_t stream);
+                              void *out, long BH, int L, int dk, int heads_token_major, const LocalityFusion *fusion,
+                              void *workspace, hipStream_t stream);
 
 // ---- depthwise 3x3 conv + sigmoid-gated blend -------------------------------------------------
 hipError_t locality_gate_launch(const void *x, const void *w, const void *bias, const void *gate_logits,

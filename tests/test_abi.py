@@ -124,6 +124,48 @@ def test_gate_producer_validation_codes():
     assert call(x=PTR + 8) == vb.VIG_ERR_ALIGN
 
 
+def test_bigla_locality_validation_codes():
+    L = vb.lib()
+
+    def call(q=PTR, k=PTR, v=PTR, gf=PTR, gb=PTR, x=PTR, w=PTR, bias=None, z=PTR, out=PTR, B=1, H=1, Hg=4, Wg=4,
+             dk=64, dv=64, dtype=vb.VIG_BF16, layout=vb.VIG_LAYOUT_BHLD, plan=0, ws=None, ws_bytes=0):
+        return L.bigla_locality_fwd(q, k, v, gf, gb, x, w, bias, z, out, B, H, Hg, Wg, dk, dv, dtype, layout, plan, ws,
+                                    ws_bytes, None)
+
+    for name in ("q", "k", "v", "gf", "gb", "x", "w", "z", "out"):
+        assert call(**{name: None}) == vb.VIG_ERR_NULL
+    for name in ("B", "H", "Hg", "Wg", "dk", "dv"):
+        assert call(**{name: 0}) == vb.VIG_ERR_SHAPE
+    assert call(Hg=1 << 12, Wg=1 << 12) == vb.VIG_ERR_SHAPE
+    assert call(dtype=9) == vb.VIG_ERR_DTYPE
+    assert call(layout=4) == vb.VIG_ERR_LAYOUT
+    assert call(plan=3) == vb.VIG_ERR_UNSUPPORTED
+    assert call(plan=-1) == vb.VIG_ERR_UNSUPPORTED
+    assert call(dk=48) == vb.VIG_ERR_UNSUPPORTED
+    for plan in vb.PLANS.values():
+        need = L.bigla_locality_workspace_bytes(2, 3, 100, 64, 64, vb.VIG_BF16, plan)
+        assert need > 0
+        kw = dict(B=2, H=3, Hg=10, Wg=10, plan=plan)
+        assert call(**kw) == vb.VIG_ERR_WORKSPACE
+        assert call(ws=PTR, ws_bytes=need - 1, **kw) == vb.VIG_ERR_WORKSPACE
+        assert call(ws=PTR + 4, ws_bytes=need, **kw) == vb.VIG_ERR_ALIGN
+    # the fused plan exists for the chunkwise bf16 shapes only; the others keep the intermediate
+    fused, two = vb.PLANS["fused_epilogue"], vb.PLANS["two_launches"]
+    assert call(dtype=vb.VIG_F32, plan=fused) == vb.VIG_ERR_UNSUPPORTED
+    assert call(dk=16, dv=16, plan=fused) == vb.VIG_ERR_UNSUPPORTED
+    assert L.bigla_locality_workspace_bytes(1, 1, 64, 16, 16, vb.VIG_F32, fused) == 0
+    assert L.bigla_locality_workspace_bytes(1, 1, 64, 16, 16, vb.VIG_F32, two) == 64 * 16 * 4
+    a = L.bigla_locality_workspace_bytes(8, 6, 4096, 64, 64, vb.VIG_BF16, fused)
+    b = L.bigla_locality_workspace_bytes(8, 6, 4096, 64, 64, vb.VIG_BF16, two)
+    assert a == vb.bigla_workspace_bytes(8, 6, 4096, 64, 64, vb.VIG_BF16)
+    assert b >= a + 8 * 6 * 4096 * 64 * 2
+    assert L.bigla_locality_workspace_bytes(8, 6, 4096, 64, 64, vb.VIG_BF16, 0) in (a, b)
+    assert call(x=PTR + 8, plan=fused, ws=PTR, ws_bytes=1 << 30) == vb.VIG_ERR_ALIGN
+    # token-major rows of one batch element are addressed with 32-bit byte offsets
+    assert call(B=1, H=64, Hg=1 << 10, Wg=1 << 10, layout=vb.VIG_LAYOUT_BLHD, plan=fused, ws=PTR,
+                ws_bytes=1 << 40) == vb.VIG_ERR_SHAPE
+
+
 def test_binding_rejects_cpu_tensors():
     import torch
 

@@ -39,6 +39,32 @@ def test_gate_producer_feeds_bigla():
     assert np.allclose(out, only_fwd, rtol=0, atol=1e-12)
 
 
+def test_block_chain_limits():
+    """The chained block output against what its definition fixes: with the gate closed
+    (logits -> -inf) it is the token mixer's output, with the gate open the convolution's, and in
+    between it moves along the segment between the two by exactly G (Section 4.2.2)."""
+    r = np.random.default_rng(11)
+    B, H, Hg, Wg, dk, dv = 2, 2, 3, 4, 3, 5
+    L = Hg * Wg
+    q, k = r.standard_normal((2, B, H, L, dk))
+    gf, gb = -np.abs(r.standard_normal((2, B, H, L, dk))) / 4
+    v, x, z = r.standard_normal((3, B, H, L, dv))
+    w = r.standard_normal((H * dv, 3, 3))
+    bias = r.standard_normal(H * dv)
+    mixer = oracle.bigla(q, k, v, gf, gb)
+    conv = oracle.locality_gate(x, w, np.full_like(z, 800.0), np.zeros_like(x), Hg, Wg, bias)
+    closed = oracle.bigla_locality(q, k, v, gf, gb, x, w, np.full_like(z, -800.0), Hg, Wg, bias)
+    opened = oracle.bigla_locality(q, k, v, gf, gb, x, w, np.full_like(z, 800.0), Hg, Wg, bias)
+    assert np.array_equal(closed, mixer)
+    assert np.array_equal(opened, conv)
+    out = oracle.bigla_locality(q, k, v, gf, gb, x, w, z, Hg, Wg, bias)
+    G = 1.0 / (1.0 + np.exp(-z))
+    assert np.allclose(out - mixer, G * (conv - mixer), rtol=0, atol=1e-12)
+    # the conv input is x, not the mixer's value tensor
+    other = oracle.bigla_locality(q, k, v, gf, gb, x + 1.0, w, z, Hg, Wg, bias)
+    assert not np.allclose(other, out)
+
+
 def test_thread_count_does_not_change_result():
     r = np.random.default_rng(0)
     q, k, gf, gb = (r.standard_normal((3, 2, 33, 8)) for _ in range(4))

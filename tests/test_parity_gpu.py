@@ -224,6 +224,83 @@ def test_path_end_to_end_hierarchical_stage_shapes(grid, H):
     assert np.all(np.abs(out64 - ref) <= bound), float(np.max(np.abs(out64 - ref) - bound))
 
 
+@pytest.mark.parametrize("B,H,Hg,Wg,dk,layout,mu,with_bias", [
+    (2, 3, 8, 8, 64, "bhld", 0.0, False),       # one chunk per sequence: the general output kernel
+    (3, 3, 14, 14, 64, "bhld", 0.0, True),      # ragged final chunk, three-launch plan
+    (64, 2, 14, 14, 64, "bhld", 0.0, False),    # one-segment plan: state and output pass in one launch
+    (2, 6, 32, 32, 64, "blhd", 2.0, True),
+    (2, 3, 64, 64, 32, "bhld", -2.0, False),    # the benchmark grid, 32-wide keys
+    (1, 3, 20, 13, 32, "blhd", -40.0, True),    # strong decay: range-safe form
+    (1, 2, 5, 100, 64, "bhld", 0.0, True),      # grid rows longer than a chunk
+    (1, 2, 100, 3, 64, "bhld", 0.0, True),      # many grid rows per chunk
+    (1, 1, 1, 70, 64, "bhld", 0.0, True),       # degenerate grids: a single row, a single column
+    (1, 1, 70, 1, 64, "bhld", 0.0, True),
+])
+def test_bigla_locality_plans(B, H, Hg, Wg, dk, layout, mu, with_bias):
+    """Token mixer + locality blend as one call: the fused-epilogue plan (the blend inside the chunkwise
+    output pass) and the two-launch plan return the same bits as the two separate entry points, and
+    the result is the oracle's chain within the path's tolerance.  The conv input is a tensor of
+    its own (not the mixer's v)."""
+    import torch
+    from paper_2405_18425_amd import binding as vb
+    import oracle
+
+    w = wl.Workload("plans", B=B, H=H, Hg=Hg, Wg=Wg, dk=dk, dv=64, dtype="bf16", gate_mu=mu)
+    _say(f"bigla_locality {w} {layout} bias={with_bias}")
+    s = wl.generate(w, seed=Hg * 131 + Wg)
+    s["x"] = wl.generate(w, seed=Hg * 131 + Wg + 7)["v"]
+    bias = wl.generate(w.replace(B=1), seed=3)["gate_logits"][0, :, 0, :].reshape(H * 64).copy() if with_bias else None
+    wd = {n: wl.widen(a, w.dtype) for n, a in s.items()}
+    bias64 = wl.widen(bias, w.dtype) if with_bias else None
+    t = {n: wl.to_torch(a, w.dtype, "cuda:0") for n, a in s.items()}
+    tb = wl.to_torch(bias, w.dtype, "cuda:0") if with_bias else None
+    if layout == "blhd":
+        for n in ("q", "k", "v", "g_fwd", "g_bwd", "gate_logits", "x"):
+            t[n] = t[n].transpose(1, 2).contiguous()
+    og = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], layout=layout)
+    separate = vb.locality_gate_fwd(t["x"], t["conv_w"], t["gate_logits"], og, Hg, Wg, bias=tb, layout=layout)
+    outs = {}
+    for plan in ("fused_epilogue", "two_launches", "auto"):
+        outs[plan] = vb.bigla_locality_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], t["x"], t["conv_w"],
+                                           t["gate_logits"], Hg, Wg, bias=tb, layout=layout, plan=plan)
+    torch.cuda.synchronize()
+    for plan, o in outs.items():
+        assert torch.equal(o, separate), f"{plan}: {(o != separate).sum().item()} elements differ from the separate calls"
+    got = outs["fused_epilogue"].transpose(1, 2) if layout == "blhd" else outs["fused_epilogue"]
+    got64 = wl.widen(wl.from_torch(got.contiguous(), w.dtype), w.dtype)
+    ref_og = oracle.bigla(wd["q"], wd["k"], wd["v"], wd["g_fwd"], wd["g_bwd"])
+    ref = oracle.locality_gate(wd["x"], wd["conv_w"], wd["gate_logits"], ref_og, Hg, Wg, bias64)
+    assert np.array_equal(ref, oracle.bigla_locality(wd["q"], wd["k"], wd["v"], wd["g_fwd"], wd["g_bwd"], wd["x"],
+                                                     wd["conv_w"], wd["gate_logits"], Hg, Wg, bias64))
+    # the mixer's error (bounded relative to the scale of o_global) passes through (1 - G) <= 1
+    tol = TOL[w.dtype]
+    rms = lambda a: np.sqrt(np.mean(a ** 2, axis=(2, 3), keepdims=True))
+    bound = tol * (np.abs(ref) + rms(ref) + np.abs(ref_og) + rms(ref_og))
+    assert np.all(np.abs(got64 - ref) <= bound), float(np.max(np.abs(got64 - ref) - bound))
+
+
+def test_bigla_locality_other_shapes_take_two_launches():
+    """fp32 and the narrow heads have no fused plan (a clear error); "auto" serves them."""
+    import torch
+    from paper_2405_18425_amd import binding as vb
+    import oracle
+
+    w = wl.CONFIGS[0]
+    s = wl.generate(w, seed=0)
+    t = {n: wl.to_torch(a, w.dtype, "cuda:0") for n, a in s.items()}
+    with pytest.raises(vb.VigError) as e:
+        vb.bigla_locality_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], t["v"], t["conv_w"], t["gate_logits"],
+                              w.Hg, w.Wg, plan="fused_epilogue")
+    assert e.value.status == vb.VIG_ERR_UNSUPPORTED
+    out = vb.bigla_locality_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], t["v"], t["conv_w"], t["gate_logits"],
+                                w.Hg, w.Wg)
+    torch.cuda.synchronize()
+    wd = {n: wl.widen(a, w.dtype) for n, a in s.items()}
+    ref = oracle.bigla_locality(wd["q"], wd["k"], wd["v"], wd["g_fwd"], wd["g_bwd"], wd["v"], wd["conv_w"],
+                                wd["gate_logits"], w.Hg, w.Wg)
+    assert_close(wl.widen(wl.from_torch(out, w.dtype), w.dtype), ref, TOL[w.dtype], "two launches, fp32")
+
+
 @pytest.mark.parametrize("dtype,dk,dv,B,H,L", [("bf16", 64, 64, 2, 6, 1024), ("bf16", 32, 64, 3, 3, 333),
                                                ("bf16", 64, 64, 2, 5, 64), ("f32", 16, 16, 2, 3, 100),
                                                ("bf16", 16, 32, 2, 2, 70)])
