@@ -104,6 +104,9 @@ int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, con
     if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
     if (!head_dim_ok(dv)) return VIG_ERR_UNSUPPORTED;
     if (!sizes_ok(B, H, Hg, long(Wg) * dv) || long(Hg) * Wg > 0x7fffffffL) return VIG_ERR_SHAPE;
+    // the pixels of one slab (token-major: of one batch element) are addressed with 32-bit byte offsets
+    if (long(Hg) * Wg * (layout == VIG_LAYOUT_BLHD ? H : 1) * dv * (dtype == VIG_BF16 ? 2 : 4) >= 0xffffff00L)
+        return VIG_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(gate_logits) || !aligned16(o_global) ||
         !aligned16(out))
         return VIG_ERR_ALIGN;

@@ -5,7 +5,9 @@ WRITE_SIZE (bytes = counter * factor, factor = known copy bytes / counter of the
     rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir> -o p -- python3 -m paper_2405_18425_amd.profile_path 4 3
 
 A third argument D > 0 adds the forget-gate producer in front of every pass (block input of width D
-for the same B, L, H, dk), feeding the gates it makes to bigla_fwd.
+for the same B, L, H, dk), feeding the gates it makes to bigla_fwd.  A fourth argument 1 or 2 runs
+each pass through bigla_locality_fwd with the two-launch plan (1) or the fused-epilogue plan (2)
+instead of the two separate entry points.
 """
 from __future__ import annotations
 
@@ -19,7 +21,7 @@ from . import workloads as wl
 COPY_BYTES = 256 << 20  # calibration copy: reads 256 MiB, writes 256 MiB
 
 
-def main(cfg: int = 4, passes: int = 3, gate_width: int = 0) -> None:
+def main(cfg: int = 4, passes: int = 3, gate_width: int = 0, plan: int = 0) -> None:
     w = wl.CONFIGS[cfg]
     dev = "cuda:0"
     t = {n: wl.to_torch(a, w.dtype, dev) for n, a in wl.generate(w, seed=0).items()}
@@ -37,6 +39,11 @@ def main(cfg: int = 4, passes: int = 3, gate_width: int = 0) -> None:
         if gp is not None:
             vb.gate_producer_fwd(gp["x"], gp["w1"], gp["w2"], w.H, w.dk, bias=gp["bias"], g_fwd=t["g_fwd"],
                                  g_bwd=t["g_bwd"])
+        if plan:
+            out = vb.bigla_locality_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], t["v"], t["conv_w"],
+                                        t["gate_logits"], w.Hg, w.Wg,
+                                        plan={1: "two_launches", 2: "fused_epilogue"}[plan])
+            continue
         og = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"])
         out = vb.locality_gate_fwd(t["v"], t["conv_w"], t["gate_logits"], og, w.Hg, w.Wg)
     torch.cuda.synchronize()
@@ -44,4 +51,4 @@ def main(cfg: int = 4, passes: int = 3, gate_width: int = 0) -> None:
 
 
 if __name__ == "__main__":
-    main(*(int(a) for a in sys.argv[1:4]))
+    main(*(int(a) for a in sys.argv[1:5]))
