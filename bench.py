@@ -38,7 +38,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("segment_out", "vig_s_1024"): 195.1e6,
     ("segment_state", "vig_s_1024"): 138.9e6,
     ("state_scan", "vig_s_1024"): 32.5e6,
-    ("locality_gate", "vig_s_1024"): 116.2e6,
+    ("locality_gate", "vig_s_1024"): 109.2e6,
 }
 
 
