@@ -71,7 +71,8 @@ size_t bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype);
  *                                     (log alpha = logsigmoid(.)/tau for the paper's gate);
  *                                     positive or NaN values are outside the contract
  *   out          [B, H, L, dv]   out
- *   L >= 1 is arbitrary (ragged final chunk handled inside); dk, dv in {16, 32, 64}.
+ *   L >= 1 is arbitrary (ragged final chunk handled inside); dk, dv in {16, 32, 64}.  On the
+ *   chunkwise path (below) L must stay below 2^24 (VIG_ERR_SHAPE otherwise).
  *   workspace / workspace_bytes: device scratch of at least bigla_workspace_bytes(...);
  *   may be NULL/0 when that function returns 0.
  *
@@ -107,7 +108,7 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
  *   w                         [H*dv, 3, 3]        in
  *   bias                      [H*dv] or NULL      in
  *   out                       [B, H, Hg*Wg, dv]   out
- *   dv in {16, 32, 64}.
+ *   dv in {16, 32, 64}.  One (batch element, head) slab must stay below 4 GiB (VIG_ERR_SHAPE).
  */
 int locality_gate_fwd(const void *x, const void *w, const void *bias, const void *gate_logits,
                       const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv,
@@ -116,7 +117,7 @@ int locality_gate_fwd(const void *x, const void *w, const void *bias, const void
 /*
  * locality_gate_fwd with x, gate_logits, o_global and out in `layout` (a vig_layout): with
  * VIG_LAYOUT_BLHD they are [B, Hg*Wg, H, dv], i.e. channel c = h*dv + j of a pixel is contiguous.
- * w and bias as for locality_gate_fwd.
+ * w and bias as for locality_gate_fwd.  With VIG_LAYOUT_BLHD one batch element must stay below 4 GiB.
  */
 int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, const void *gate_logits,
                              const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv,

@@ -191,39 +191,64 @@ struct Row16 {
     uint4 p[2];
 };
 
-// Every global row load is a fully contiguous wave load, 8 whole 128-byte rows per instruction:
+// Every global row access is a fully contiguous wave access, 8 whole 128-byte rows per instruction:
 // lane i of wave w takes 16-byte piece i%8 of rows 16w + i/8 and 16w + 8 + i/8 of the chunk.
-// An out-of-range token reads the last valid row and is zeroed, either right here (kZeroHere;
-// compiled as a skipped branch unless the chunk is ragged) or when the rows are consumed
-// (zero_past_end).  Which of the two a kernel uses was settled by timing it.
 struct StagedRows {
     uint4 p[2];
 };
 
-//
-// kRow is the tensor's row length in elements.  Rows of 32 (keys, queries and gates of a 32-wide
-// head) are widened to the kernels' 64 channels with zeros: channels 32..63 then carry q = k = 0
-// and log-gate 0 through every later step, which leaves the result unchanged.  The lanes of the
-// zero half repeat the addresses of the other half (the instruction still touches whole rows)
-// and are cleared by zero_widened_half when the rows are consumed.
-//
-// kTm selects the token-major layout ([B, L, H, d]): consecutive tokens of the slab are then
-// tok_stride = H * kRow elements apart; offsets stay below 2^31 (checked on the host) and are
-// formed with a 24-bit multiply.  Head-major ([B, H, L, d]) rows are kRow apart, a shift.
-template <bool kZeroHere = false, int kRow = kD, bool kTm = false>
-__device__ __forceinline__ StagedRows load_rows_staged(const uint16_t *slab_base, long chunk_token0, int w, int lane,
-                                                       int L, unsigned tok_stride = 0)
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// One slab's rows of a tensor, reached through a buffer resource whose extent ends with the slab's
+// last token: the byte offset of a row is 32 bits wide, and a token past the sequence lies beyond
+// the extent, where the bounds check of the access returns zeros for a load (k = v = 0 and
+// log-gate 0 make such a token a no-op) and drops a store -- no clamp, no branch, no select.
+// The resource is the same in every lane; saying so keeps it in scalar registers.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const void *first_row, unsigned extent_bytes)
+{
+    const uintptr_t a = reinterpret_cast<uintptr_t>(first_row);
+    // (readfirstlane returns a signed int: widen through unsigned, not by sign extension)
+    const uintptr_t lo = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a))));
+    const uintptr_t hi = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a >> 32))));
+    const unsigned kRawDwords = 0x00020000u;  // untyped 32-bit data, bounds check on the byte offset
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(lo | (hi << 32)), 0,
+                                             int(unsigned(__builtin_amdgcn_readfirstlane(int(extent_bytes)))),
+                                             int(kRawDwords));
+}
+
+// Byte offsets of a lane's two pieces inside a chunk, for rows of kRow elements `pitch` bytes apart
+// (head-major [B, H, L, d]: pitch = 2 * kRow; token-major [B, L, H, d]: pitch = 2 * H * kRow).
+// Rows of 32 (keys, queries and gates of a 32-wide head) are widened to the kernels' 64 channels
+// with zeros: channels 32..63 then carry q = k = 0 and log-gate 0 through every later step, which
+// leaves the result unchanged.  The lanes of the zero half repeat the addresses of the other half
+// (the instruction still touches whole rows) and are cleared by zero_widened_half when the rows
+// are consumed.
+struct LaneRows {
+    unsigned off[2];
+    unsigned pitch;
+};
+
+template <int kRow>
+__device__ __forceinline__ LaneRows lane_rows(int w, int lane, unsigned pitch)
 {
     static_assert(kRow == kD || kRow == kD / 2, "row length");
     constexpr int kPieces = kRow / 8;
+    LaneRows r;
+    r.pitch = pitch;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) r.off[t] = unsigned(16 * w + 8 * t + (lane >> 3)) * pitch + 16u * ((lane & 7) % kPieces);
+    return r;
+}
+
+// The lane's pieces of the chunk that starts at token chunk_token0 (below 2^24)
+__device__ __forceinline__ StagedRows load_rows(__amdgpu_buffer_rsrc_t rows, const LaneRows &lr, unsigned chunk_token0)
+{
+    const unsigned chunk_off = chunk_token0 * lr.pitch;
     StagedRows s;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-        const long tok = chunk_token0 + 16 * w + 8 * t + (lane >> 3);
-        const long tc = tok < L ? tok : long(L) - 1;
-        const size_t row_off = kTm ? size_t(__umul24(unsigned(tc), tok_stride)) : size_t(tc) * kRow;
-        s.p[t] = *reinterpret_cast<const uint4 *>(slab_base + row_off + 8 * ((lane & 7) % kPieces));
-        if (kZeroHere && tok >= L) s.p[t] = make_uint4(0, 0, 0, 0);
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rows, lr.off[t] + chunk_off, 0, 0);
+        s.p[t] = make_uint4(v.x, v.y, v.z, v.w);
     }
     return s;
 }
@@ -234,14 +259,6 @@ template <int kRow>
 __device__ __forceinline__ void zero_widened_half(StagedRows &s, int lane)
 {
     if (kRow < kD && (lane & 7) >= kRow / 8) s.p[0] = s.p[1] = make_uint4(0, 0, 0, 0);
-}
-
-// Zero the rows of tokens >= L (k = v = 0 and log-gate 0 make such a token a no-op).
-__device__ __forceinline__ void zero_past_end(StagedRows &s, long chunk_token0, int w, int lane, int L)
-{
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-        if (chunk_token0 + 16 * w + 8 * t + (lane >> 3) >= L) s.p[t] = make_uint4(0, 0, 0, 0);
 }
 
 // Orders this wave's earlier LDS writes before its later LDS reads of what other lanes of the
@@ -600,7 +617,6 @@ struct LocalitySlab {
     int Hg, Wg;
 };
 constexpr unsigned kOffGrid = 0xfffffff0u;
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 // Everything after the score tiles, common to both forms: O^T = V^T P^T + the three readouts,
 // out = O/2, then the forward state update with the keys in `ktile`.
@@ -611,8 +627,8 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 template <bool kTm, int kKs, bool kLoc, class Prefetch>
 __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)[kPitch], const ChunkOperands &op,
                                              const ChunkFlags fl, const bool fast_update, const int w, const int r,
-                                             const int g, uint16_t *out_slab, const long chunk_token0, const int L,
-                                             const unsigned out_tok_stride, f32x4 (&S)[4], const LocalitySlab &ls,
+                                             const int g, __amdgpu_buffer_rsrc_t out_rows, const LaneRows &vr,
+                                             const unsigned chunk_token0, f32x4 (&S)[4], const LocalitySlab &ls,
                                              Prefetch &&prefetch)
 {
     const uint2(&pk)[4] = op.pk;
@@ -645,14 +661,13 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
             *reinterpret_cast<uint2 *>(&sm.gf[16 * w + r][16 * jt + 4 * g]) =
                 make_uint2(pack2(0.5f * O[jt][0], 0.5f * O[jt][1]), pack2(0.5f * O[jt][2], 0.5f * O[jt][3]));
         wave_lds_fence();
+        if (!kLoc) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int rr = 16 * w + 8 * t + (lane >> 3);
-            const uint4 o = *reinterpret_cast<const uint4 *>(&sm.gf[rr][8 * (lane & 7)]);
-            const long tok = chunk_token0 + rr;
-            const size_t row_off = kTm ? size_t(__umul24(unsigned(tok), out_tok_stride)) : size_t(tok) * kD;
-            if (!kLoc) {
-                if (tok < L) *reinterpret_cast<uint4 *>(out_slab + row_off + 8 * (lane & 7)) = o;
+            for (int t = 0; t < 2; ++t) {
+                const int rr = 16 * w + 8 * t + (lane >> 3);
+                const uint4 o = *reinterpret_cast<const uint4 *>(&sm.gf[rr][8 * (lane & 7)]);
+                __builtin_amdgcn_raw_buffer_store_b128(u32x4{o.x, o.y, o.z, o.w}, out_rows,
+                                                       vr.off[t] + chunk_token0 * vr.pitch, 0, 0);
             }
         }
     }
@@ -702,14 +717,13 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
         // One token row at a time (the lane's piece, 8 channels, of its 3x3 neighbourhood is ten
         // 16-byte loads); o is still in the wave's rows of the gate tile.
         const int c0 = 8 * (lane & 7);
-        const unsigned pitch_b = (kTm ? out_tok_stride : unsigned(kD)) * 2u;
+        const unsigned pitch_b = vr.pitch;
 #pragma unroll 1
         for (int t = 0; t < 2; ++t) {
             const int rr = 16 * w + 8 * t + (lane >> 3);
-            const long tok = chunk_token0 + rr;
-            const unsigned row_off = kTm ? __umul24(unsigned(tok), out_tok_stride) : unsigned(tok) * kD;
-            const unsigned own = (row_off + c0) * 2u;
-            const int y = int(tok) / ls.Wg, xp = int(tok) - y * ls.Wg;
+            const int tok = int(chunk_token0) + rr;
+            const unsigned own = vr.off[t] + chunk_token0 * vr.pitch;
+            const int y = tok / ls.Wg, xp = tok - y * ls.Wg;
             u32x4 x_nb[9];
 #pragma unroll
             for (int ky = -1; ky <= 1; ++ky)
@@ -719,7 +733,7 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
                     const unsigned off = own + unsigned(ky * ls.Wg + kx) * pitch_b;
                     x_nb[3 * (ky + 1) + kx + 1] = __builtin_amdgcn_raw_buffer_load_b128(ls.x, in ? off : kOffGrid, 0, 0);
                 }
-            const u32x4 z_row = __builtin_amdgcn_raw_buffer_load_b128(ls.z, tok < L ? own : kOffGrid, 0, 0);
+            const u32x4 z_row = __builtin_amdgcn_raw_buffer_load_b128(ls.z, own, 0, 0);
             float acc[8];
             {
                 const float4 b0 = *reinterpret_cast<const float4 *>(&sm.cb[c0]);
@@ -745,10 +759,9 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
                 const float gate = __builtin_amdgcn_rcpf(1.f + __expf(-zf[e]));
                 acc[e] = fmaf(gate, acc[e] - of[e], of[e]);
             }
-            if (tok < L)
-                *reinterpret_cast<uint4 *>(out_slab + row_off + c0) =
-                    make_uint4(pack2(acc[0], acc[1]), pack2(acc[2], acc[3]), pack2(acc[4], acc[5]),
-                               pack2(acc[6], acc[7]));
+            __builtin_amdgcn_raw_buffer_store_b128(
+                u32x4{pack2(acc[0], acc[1]), pack2(acc[2], acc[3]), pack2(acc[4], acc[5]), pack2(acc[6], acc[7])},
+                out_rows, own, 0, 0);
         }
     }
 }
@@ -1039,11 +1052,16 @@ __device__ __forceinline__ void out_unit(
     const int seg = int(unit % n_seg);
     // first row of the slab and distance between its tokens, in rows of the tensor
     const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
-    const unsigned key_stride = unsigned(heads) * kDk, val_stride = unsigned(heads) * kD;
     const long base = row0 * kD, key_base = row0 * kDk;
-    const uint16_t *q = q_all + key_base, *k = k_all + key_base, *v = v_all + base;
-    const uint16_t *g_fwd = gf_all + key_base, *g_bwd = gb_all + key_base;
-    uint16_t *out = out_all + base;
+    // bytes between consecutive tokens of the slab, and the slab's extent from its first row
+    const unsigned key_pitch = unsigned(heads) * kDk * 2u, val_pitch = unsigned(heads) * kD * 2u;
+    const unsigned key_extent = unsigned(L - 1) * key_pitch + kDk * 2u, val_extent = unsigned(L - 1) * val_pitch + kD * 2u;
+    const __amdgpu_buffer_rsrc_t q = slab_resource(q_all + key_base, key_extent);
+    const __amdgpu_buffer_rsrc_t k = slab_resource(k_all + key_base, key_extent);
+    const __amdgpu_buffer_rsrc_t g_fwd = slab_resource(gf_all + key_base, key_extent);
+    const __amdgpu_buffer_rsrc_t g_bwd = slab_resource(gb_all + key_base, key_extent);
+    const __amdgpu_buffer_rsrc_t v = slab_resource(v_all + base, val_extent);
+    const __amdgpu_buffer_rsrc_t out = slab_resource(out_all + base, val_extent);
     const unsigned char *stash = stash_all + size_t(slab) * n_chunks * kStashBytes;
 
     const int chunk0 = seg * seg_chunks;
@@ -1060,21 +1078,8 @@ __device__ __forceinline__ void out_unit(
         for (int i = tid; i < kD * 9; i += kThreads) sm.cw[i % 9][i / 9] = bf16_lo_to_f32(taps[i]);
         if (tid < kD)
             sm.cb[tid] = lf.bias ? bf16_lo_to_f32(static_cast<const uint16_t *>(lf.bias)[head * kD + tid]) : 0.f;
-        // the slab's rows from its first token to the end of its last token's row
-        const unsigned extent = unsigned(L - 1) * (kTm ? val_stride : unsigned(kD)) * 2u + unsigned(kD) * 2u;
-        const unsigned kRawDwords = 0x00020000u;  // untyped 32-bit data, bounds check on the byte offset
-        // (the addresses are the same in every lane; saying so keeps the resources in scalar registers)
-        auto slab_rows = [&](const void *all) {
-            const uintptr_t a = reinterpret_cast<uintptr_t>(static_cast<const uint16_t *>(all) + base);
-            // (the builtin returns a signed int: widen through unsigned, not by sign extension)
-            const uintptr_t lo = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a))));
-            const uintptr_t hi = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a >> 32))));
-            return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(lo | (hi << 32)), 0,
-                                                     int(unsigned(__builtin_amdgcn_readfirstlane(int(extent)))),
-                                                     int(kRawDwords));
-        };
-        ls.x = slab_rows(lf.x);
-        ls.z = slab_rows(lf.gate_logits);
+        ls.x = slab_resource(static_cast<const uint16_t *>(lf.x) + base, val_extent);
+        ls.z = slab_resource(static_cast<const uint16_t *>(lf.gate_logits) + base, val_extent);
         ls.Hg = lf.Hg;
         ls.Wg = lf.Wg;
     }
@@ -1088,7 +1093,8 @@ __device__ __forceinline__ void out_unit(
     // The rows of the next chunk are requested a tile at a time between the phases of a step (a
     // burst of all thirteen loads would stall the wave at issue while the memory pipeline is
     // full).  m may run one past the segment: clamped, the rows are then unused.
-    auto chunk_token0 = [&](int m) { return long(chunk0 + min(m, nch - 1)) * kC; };
+    const LaneRows kr = lane_rows<kDk>(w, lane, key_pitch), vr = lane_rows<kD>(w, lane, val_pitch);
+    auto chunk_token0 = [&](int m) { return unsigned(chunk0 + min(m, nch - 1)) * kC; };
     auto fetch_stash = [&](ChunkRows &c, int m) {
         // this lane's 16 values of the chunk's stashed state (unwritten, and unused, for the
         // segment's last chunk) and the decay of its rows
@@ -1102,12 +1108,12 @@ __device__ __forceinline__ void out_unit(
     };
     // part 0..5: q, k, g_fwd, g_bwd, v, stash
     auto fetch_part = [&](ChunkRows &c, int m, int part) {
-        const long t0 = chunk_token0(m);
-        if (part == 0) c.q = load_rows_staged<false, kDk, kTm>(q, t0, w, lane, L, key_stride);
-        if (part == 1) c.k = load_rows_staged<false, kDk, kTm>(k, t0, w, lane, L, key_stride);
-        if (part == 2) c.gf = load_rows_staged<false, kDk, kTm>(g_fwd, t0, w, lane, L, key_stride);
-        if (part == 3) c.gb = load_rows_staged<false, kDk, kTm>(g_bwd, t0, w, lane, L, key_stride);
-        if (part == 4) c.v = load_rows_staged<false, kD, kTm>(v, t0, w, lane, L, val_stride);
+        const unsigned t0 = chunk_token0(m);
+        if (part == 0) c.q = load_rows(q, kr, t0);
+        if (part == 1) c.k = load_rows(k, kr, t0);
+        if (part == 2) c.gf = load_rows(g_fwd, kr, t0);
+        if (part == 3) c.gb = load_rows(g_bwd, kr, t0);
+        if (part == 4) c.v = load_rows(v, vr, t0);
         if (part == 5) fetch_stash(c, m);
     };
     // The general code, short of registers, fetches a chunk's rows at the start of its step
@@ -1135,14 +1141,6 @@ __device__ __forceinline__ void out_unit(
             for (int part = 0; part < 6; ++part) fetch_part(next, m, part);
         }
         ChunkRows cur = next;
-        if (long(chunk0 + m + 1) * kC > L) {  // ragged final chunk of the sequence (uniform branch)
-            const long t0 = long(chunk0 + m) * kC;
-            zero_past_end(cur.q, t0, w, lane, L);
-            zero_past_end(cur.k, t0, w, lane, L);
-            zero_past_end(cur.gf, t0, w, lane, L);
-            zero_past_end(cur.gb, t0, w, lane, L);
-            zero_past_end(cur.v, t0, w, lane, L);
-        }
         zero_widened_half<kDk>(cur.q, lane);
         zero_widened_half<kDk>(cur.k, lane);
         zero_widened_half<kDk>(cur.gf, lane);
@@ -1219,8 +1217,8 @@ __device__ __forceinline__ void out_unit(
             fetch_part(next, m + 1, 2);
             fetch_part(next, m + 1, 3);
         }
-        finish_chunk<kTm, kKs, kLoc>(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, long(chunk0 + m) * kC, L,
-                                     val_stride, S, ls, prefetch_second_half);
+        finish_chunk<kTm, kKs, kLoc>(sm, fast ? sm.kf : sm.gb, op, fl, fast, w, r, g, out, vr, unsigned(chunk0 + m) * kC,
+                                     S, ls, prefetch_second_half);
     }
 }
 
@@ -1262,8 +1260,8 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
 // seg_states == nullptr (one segment per slab): the end states are not needed and not stored.
 template <int kDk, bool kTm>
 __device__ __forceinline__ bool state_unit(
-    const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, const uint16_t *__restrict__ g_fwd,
-    const uint16_t *__restrict__ g_bwd, float *__restrict__ seg_states, unsigned char *__restrict__ stash, int L,
+    const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all, const uint16_t *__restrict__ gf_all,
+    const uint16_t *__restrict__ gb_all, float *__restrict__ seg_states, unsigned char *__restrict__ stash, int L,
     int n_chunks, int seg_chunks, int n_seg, const long unit, int heads)
 {
     StateLds &sm = g_lds.state;
@@ -1272,8 +1270,13 @@ __device__ __forceinline__ bool state_unit(
     const long slab = unit / n_seg;
     const int seg = int(unit % n_seg);
     const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
-    const unsigned key_stride = unsigned(heads) * kDk, val_stride = unsigned(heads) * kD;
-    k += row0 * kDk; v += row0 * kD; g_fwd += row0 * kDk; g_bwd += row0 * kDk;
+    // bytes between consecutive tokens of the slab, and the slab's extent from its first row
+    const unsigned key_pitch = unsigned(heads) * kDk * 2u, val_pitch = unsigned(heads) * kD * 2u;
+    const unsigned key_extent = unsigned(L - 1) * key_pitch + kDk * 2u, val_extent = unsigned(L - 1) * val_pitch + kD * 2u;
+    const __amdgpu_buffer_rsrc_t k = slab_resource(k_all + row0 * kDk, key_extent);
+    const __amdgpu_buffer_rsrc_t g_fwd = slab_resource(gf_all + row0 * kDk, key_extent);
+    const __amdgpu_buffer_rsrc_t g_bwd = slab_resource(gb_all + row0 * kDk, key_extent);
+    const __amdgpu_buffer_rsrc_t v = slab_resource(v_all + row0 * kD, val_extent);
     float *dst = seg_states ? seg_states + (slab * n_seg + seg) * kSegFloats : nullptr;
     stash += size_t(slab) * n_chunks * kStashBytes;
 
@@ -1298,12 +1301,14 @@ __device__ __forceinline__ bool state_unit(
     struct ChunkRows {
         StagedRows k, v, gf, gb;
     };
+    const LaneRows kr = lane_rows<kDk>(w, lane, key_pitch), vr = lane_rows<kD>(w, lane, val_pitch);
     auto fetch = [&](int m) {  // m may run one before the segment: clamped, the rows are then unused
         ChunkRows c;
-        c.k = load_rows_staged<true, kDk, kTm>(k, long(chunk0 + max(m, 0)) * kC, w, lane, L, key_stride);
-        c.v = load_rows_staged<true, kD, kTm>(v, long(chunk0 + max(m, 0)) * kC, w, lane, L, val_stride);
-        c.gf = load_rows_staged<true, kDk, kTm>(g_fwd, long(chunk0 + max(m, 0)) * kC, w, lane, L, key_stride);
-        c.gb = load_rows_staged<true, kDk, kTm>(g_bwd, long(chunk0 + max(m, 0)) * kC, w, lane, L, key_stride);
+        const unsigned t0 = unsigned(chunk0 + max(m, 0)) * kC;
+        c.k = load_rows(k, kr, t0);
+        c.v = load_rows(v, vr, t0);
+        c.gf = load_rows(g_fwd, kr, t0);
+        c.gb = load_rows(g_bwd, kr, t0);
         return c;
     };
     ChunkRows next = fetch(nch - 1);
@@ -1323,8 +1328,8 @@ __device__ __forceinline__ bool state_unit(
         zero_widened_half<kDk>(cur.gb, lane);
         // the rows of chunk m-1 are requested a tile at a time between the phases of this step:
         // a burst of all of them would stall this wave at issue while the memory pipeline is full
-        const long far_token0 = long(chunk0 + max(m - 1, 0)) * kC;
-        next.k = load_rows_staged<true, kDk, kTm>(k, far_token0, w, lane, L, key_stride);
+        const unsigned far_token0 = unsigned(chunk0 + max(m - 1, 0)) * kC;
+        next.k = load_rows(k, kr, far_token0);
 
         // stash for chunk m: the backward state entering it from the right (zero, and not
         // stored, for the segment's last chunk) and the decay from its right edge to the
@@ -1351,7 +1356,7 @@ __device__ __forceinline__ bool state_unit(
         float kf[16];
         unpack16(bounce_load(sm.ks[0], row, g), kf);
         __syncthreads();  // g, v visible
-        next.v = load_rows_staged<true, kD, kTm>(v, far_token0, w, lane, L, val_stride);
+        next.v = load_rows(v, vr, far_token0);
 
         f32x4 Bf[4], Bb[4];
         float max_f, max_b;
@@ -1371,7 +1376,7 @@ __device__ __forceinline__ bool state_unit(
         }
         const bool fast = fmaxf(max_f, max_b) <= kFastRange;  // uniform over the workgroup
         all_fast = all_fast && fast;
-        next.gf = load_rows_staged<true, kDk, kTm>(g_fwd, far_token0, w, lane, L, key_stride);
+        next.gf = load_rows(g_fwd, kr, far_token0);
         float4 df, db;  // this chunk's decay, rows at LDS positions 16w + 4g + e
         float tmp[16];
         if (fast) {
@@ -1437,7 +1442,7 @@ __device__ __forceinline__ bool state_unit(
             __syncthreads();  // ks visible
         }
 
-        next.gb = load_rows_staged<true, kDk, kTm>(g_bwd, far_token0, w, lane, L, key_stride);
+        next.gb = load_rows(g_bwd, kr, far_token0);
         // chunk contributions K^T V of both directions, rows at positions 16w + 4g + e
         f32x4 Cf[4], Cb[4];
 #pragma unroll

@@ -25,6 +25,13 @@ bool sizes_ok(long a, long b, long c, long d)
     return true;
 }
 
+// rows of 64 bf16 values, pitch 128 bytes (times H when token-major), L + 64 of them
+bool chunk_offsets_ok(int L, int H, int layout)
+{
+    const long pitch = 128L * (layout == VIG_LAYOUT_BLHD ? H : 1);
+    return L < (1 << 24) && (long(L) + 64) * pitch <= 0xfffffff0L;
+}
+
 int hip_status(hipError_t e)
 {
     if (e == hipSuccess) return VIG_OK;
@@ -79,6 +86,9 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
     const long BH = long(B) * H;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int heads_token_major = layout == VIG_LAYOUT_BLHD ? H : 0;
+    // the chunkwise kernels address the rows of a slab (token-major: of a batch element) with 32-bit
+    // byte offsets, up to one chunk past the sequence
+    if (vig::bigla_chunk_supported(dk, dv, bf16) && !chunk_offsets_ok(L, H, layout)) return VIG_ERR_SHAPE;
     if (vig::bigla_chunk_supported(dk, dv, bf16))
         return hip_status(
             vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, heads_token_major, nullptr, workspace, s));
@@ -162,9 +172,7 @@ int bigla_locality_fwd(const void *q, const void *k, const void *v, const void *
     }
     if (!vig::bigla_chunk_supported(dk, dv, bf16)) return VIG_ERR_UNSUPPORTED;
     if (!sizes_ok(B, H, L, dk > dv ? dk : dv) || long(B) * H > 0x7fffffffL) return VIG_ERR_SHAPE;
-    // rows of a slab are addressed with 32-bit byte offsets (token-major: over one batch element)
-    if (layout == VIG_LAYOUT_BLHD && (long(H) * 64 >= (1 << 24) || long(L) * H * 64 * 2 >= 0xffffff00L))
-        return VIG_ERR_SHAPE;
+    if (!chunk_offsets_ok(L, H, layout)) return VIG_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g_fwd) || !aligned16(g_bwd) ||
         !aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(gate_logits) || !aligned16(out) ||
         !aligned16(workspace))
