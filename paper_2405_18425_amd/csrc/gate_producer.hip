@@ -40,10 +40,15 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-// log(sigmoid(z)) = min(z, 0) - log(1 + exp(-|z|)), finite for every finite z
+// log(sigmoid(z)) = min(z, 0) - log(1 + exp(-|z|)), finite for every finite z.  The bare hardware
+// exp2 / log2 serve: the exponential's argument is <= 0 (an underflow to 0 is the right limit) and
+// the logarithm's lies in [1, 2], so neither needs the range handling of the library functions,
+// which costs more vector instructions than the two transcendentals themselves.
 __device__ __forceinline__ float log_sigmoid(float z)
 {
-    return fminf(z, 0.f) - __logf(1.f + __expf(-fabsf(z)));
+    const float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+    const float e = __builtin_amdgcn_exp2f(-kLog2e * fabsf(z));
+    return fmaf(-kLn2, __builtin_amdgcn_logf(1.f + e), fminf(z, 0.f));
 }
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)
@@ -184,8 +189,12 @@ __global__ __launch_bounds__(kThreads) void gate_producer_bf16_kernel(
                 const int h = cc >> dk_shift, j = cc & (dk - 1);
                 const size_t row = token_major ? (size_t(b_idx) * L + t_idx) * H + h : (size_t(b_idx) * H + h) * L + t_idx;
                 uint4 *dst = reinterpret_cast<uint4 *>((bwd ? g_bwd : g_fwd) + row * dk + j);
-                dst[0] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
-                dst[1] = make_uint4(packed[4], packed[5], packed[6], packed[7]);
+                // streaming stores (nothing here reads the gates back): measured 2 us faster
+                typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+                __builtin_nontemporal_store(u32x4{packed[0], packed[1], packed[2], packed[3]},
+                                            reinterpret_cast<u32x4 *>(dst));
+                __builtin_nontemporal_store(u32x4{packed[4], packed[5], packed[6], packed[7]},
+                                            reinterpret_cast<u32x4 *>(dst) + 1);
             }
         }
     }
