@@ -619,7 +619,8 @@ struct LocalitySlab {
 constexpr unsigned kOffGrid = 0xfffffff0u;
 
 // Everything after the score tiles, common to both forms: O^T = V^T P^T + the three readouts,
-// out = O/2, then the forward state update with the keys in `ktile`.
+// out = O (the score and readout queries carry the 1/2 of the average), then the forward state
+// update with the keys in `ktile`.
 // fast_update: S = d (S + K^T V) with d = exp(tot); otherwise S = d S + K^T V with d = prod(eb).
 // kKs = 1 (32-wide head, fast-form code only): state rows 32..63 are identically zero, so the waves
 // that own them (w >= 2) skip the state update and nobody reads the upper K-step of a state tile.
@@ -654,12 +655,12 @@ __device__ __forceinline__ void finish_chunk(OutLds &sm, const uint16_t (*ktile)
     if (fl.stash || fl.seg) readout<kKs>(sm.sb, op.qb0, op.qb1, r, g, O);
     prefetch(3);
     const int lane = 16 * g + r;
-    {  // o_t = (o_fwd_t + o_bwd_t) / 2, turned into whole rows through the wave's own rows of the
+    {  // o_t = (o_fwd_t + o_bwd_t) / 2 (the queries arrive halved), turned into whole rows through the wave's own rows of the
        // forward gate tile (last read before the score tiles), then written 8 rows per store
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt)
             *reinterpret_cast<uint2 *>(&sm.gf[16 * w + r][16 * jt + 4 * g]) =
-                make_uint2(pack2(0.5f * O[jt][0], 0.5f * O[jt][1]), pack2(0.5f * O[jt][2], 0.5f * O[jt][3]));
+                make_uint2(pack2(O[jt][0], O[jt][1]), pack2(O[jt][2], O[jt][3]));
         wave_lds_fence();
         if (!kLoc) {
 #pragma unroll
@@ -826,10 +827,10 @@ __device__ __forceinline__ void out_chunk_fast(OutLds &sm, const int w, const in
 #pragma unroll
     for (int n = 0; n < 16; ++n) {
         const float xf = Bf[n >> 2][n & 3] * kLog2e, xb = Bb[n >> 2][n & 3] * kLog2e;
-        qb[n] = qf[n] * fast_exp2(xb);   // q * exp(c_t)    backward
-        kb[n] = kf[n] * fast_exp2(-xb);  // k * exp(-c_i)
-        qf[n] *= fast_exp2(xf);          // q * exp(b_t)    forward
-        kf[n] *= fast_exp2(-xf);         // k * exp(-b_i)
+        qb[n] = qf[n] * fast_exp2(xb - 1.f);  // q * exp(c_t) / 2   backward
+        kb[n] = kf[n] * fast_exp2(-xb);       // k * exp(-c_i)
+        qf[n] *= fast_exp2(xf - 1.f);         // q * exp(b_t) / 2   forward
+        kf[n] *= fast_exp2(-xf);              // k * exp(-b_i)
     }
     const bf16x8 qf0 = pack8(qf), qf1 = pack8(qf + 8), qb0 = pack8(qb), qb1 = pack8(qb + 8);
     const bf16x8 kf0 = pack8(kf), kf1 = pack8(kf + 8), kb0 = pack8(kb), kb1 = pack8(kb + 8);
@@ -873,10 +874,10 @@ __device__ __forceinline__ void out_chunk_fast_fused(OutLds &sm, const bf16x8 (&
             const int n = 4 * ct + e;
             const float xf = Bf[e] * kLog2e, xb = Bb[e] * kLog2e;
             tot[n] = Bf[e];
-            qb[n] = qf[n] * fast_exp2(xb);   // q * exp(c_t)    backward
-            kb[n] = kf[n] * fast_exp2(-xb);  // k * exp(-c_i)
-            qf[n] *= fast_exp2(xf);          // q * exp(b_t)    forward
-            kf[n] *= fast_exp2(-xf);         // k * exp(-b_i)
+            qb[n] = qf[n] * fast_exp2(xb - 1.f);  // q * exp(c_t) / 2   backward
+            kb[n] = kf[n] * fast_exp2(-xb);       // k * exp(-c_i)
+            qf[n] *= fast_exp2(xf - 1.f);         // q * exp(b_t) / 2   forward
+            kf[n] *= fast_exp2(-xf);              // k * exp(-b_i)
         }
     }
     const bf16x8 qf0 = pack8(qf), qf1 = pack8(qf + 8), qb0 = pack8(qb), qb1 = pack8(qb + 8);
@@ -905,6 +906,8 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
     float qf[16], kf[16], tmp[16];
     unpack16(qraw, qf);
     unpack16(kraw, kf);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) qf[e] *= 0.5f;  // the 1/2 of the output, carried by every query variant
 
     // per direction: diagonal-tile operands (referred to the middle of the sub-block), the keys
     // for off-diagonal tiles (decay to the far edge of their sub-block) and the running query
