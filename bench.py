@@ -45,8 +45,8 @@ MEASURED_TRAFFIC_BYTES = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=300)  # the first few hundred steps after idling run ~5 % slower
     ap.add_argument("--config", type=int, default=4, help="workload index (paper_2405_18425_amd.workloads.CONFIGS)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
