@@ -532,6 +532,21 @@ __device__ __forceinline__ void chunk_gate_scan(const uint16_t (*gtile)[kPitch],
 
 // Largest chunk log-decay (nats) over all 64 channels, identical in every lane of the wave: the
 // four lanes 0, 16, 32, 48 together hold the totals of every channel.
+// Chunk totals alone (where the cumulative gates of a direction are not needed)
+template <int kCt = 4>
+__device__ __forceinline__ void chunk_gate_totals(const uint16_t (*gtile)[kPitch], int r, int g, f32x4 (&T)[4])
+{
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
+#pragma unroll
+    for (int ct = kCt; ct < 4; ++ct) T[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ct = 0; ct < kCt; ++ct) {
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        T[ct] = mfma(token_operand(gtile, 2, 3, 16 * ct, r, g), ones,
+                     mfma(token_operand(gtile, 0, 1, 16 * ct, r, g), ones, zero));
+    }
+}
+
 __device__ __forceinline__ float chunk_decay_max(const f32x4 (&T)[4])
 {
     float m = 0.f;
@@ -1261,7 +1276,10 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
 
 // One (slab, segment) unit of the state pass.  Returns whether every chunk admitted the fast form.
 // seg_states == nullptr (one segment per slab): the end states are not needed and not stored.
-template <int kDk, bool kTm>
+// kFwd = false (only with seg_states == nullptr): nothing reads the forward end state, so the fast
+// form skips the forward direction altogether (its cumulative gates, scaled keys and K^T V); the
+// forward chunk totals are still formed, for the choice of the form.
+template <int kDk, bool kTm, bool kFwd = true>
 __device__ __forceinline__ bool state_unit(
     const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all, const uint16_t *__restrict__ gf_all,
     const uint16_t *__restrict__ gb_all, float *__restrict__ seg_states, unsigned char *__restrict__ stash, int L,
@@ -1366,11 +1384,15 @@ __device__ __forceinline__ bool state_unit(
         {
             f32x4 T[4];
             float t[16];
-            chunk_gate_scan<kCt>(sm.g[0], tri_f, r, g, Bf, T);
+            if (kFwd) {
+                chunk_gate_scan<kCt>(sm.g[0], tri_f, r, g, Bf, T);
+            } else {
+                chunk_gate_totals<kCt>(sm.g[0], r, g, T);
+            }
             max_f = chunk_decay_max(T);
 #pragma unroll
             for (int n = 0; n < 16; ++n) t[n] = T[n >> 2][n & 3];
-            if (r == 0) store_chan16(sm.tot[0], g, t);  // chunk totals per channel, operand order
+            if (kFwd && r == 0) store_chan16(sm.tot[0], g, t);  // chunk totals per channel, operand order
             chunk_gate_scan<kCt>(sm.g[1], tri_b, r, g, Bb, T);
             max_b = chunk_decay_max(T);
 #pragma unroll
@@ -1390,15 +1412,18 @@ __device__ __forceinline__ bool state_unit(
 #pragma unroll
             for (int n = 0; n < kSlots; ++n) {
                 kb[n] = kf[n] * fast_exp2(-kLog2e * Bb[n >> 2][n & 3]);
-                kf[n] = kf[n] * fast_exp2(-kLog2e * Bf[n >> 2][n & 3]);
+                if (kFwd) kf[n] = kf[n] * fast_exp2(-kLog2e * Bf[n >> 2][n & 3]);
             }
-            store_row16(sm.ks[0], row, g, kf);
+            if (kFwd) store_row16(sm.ks[0], row, g, kf);
             store_row16(sm.ks[1], row, g, kb);
             __syncthreads();  // ks, tot visible
-            const float4 tf = *reinterpret_cast<const float4 *>(&sm.tot[0][16 * w + 4 * g]);
             const float4 tb = *reinterpret_cast<const float4 *>(&sm.tot[1][16 * w + 4 * g]);
-            df = make_float4(fast_exp2(tf.x * kLog2e), fast_exp2(tf.y * kLog2e), fast_exp2(tf.z * kLog2e),
-                             fast_exp2(tf.w * kLog2e));
+            df = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (kFwd) {
+                const float4 tf = *reinterpret_cast<const float4 *>(&sm.tot[0][16 * w + 4 * g]);
+                df = make_float4(fast_exp2(tf.x * kLog2e), fast_exp2(tf.y * kLog2e), fast_exp2(tf.z * kLog2e),
+                                 fast_exp2(tf.w * kLog2e));
+            }
             db = make_float4(fast_exp2(tb.x * kLog2e), fast_exp2(tb.y * kLog2e), fast_exp2(tb.z * kLog2e),
                              fast_exp2(tb.w * kLog2e));
         } else {
@@ -1457,12 +1482,13 @@ __device__ __forceinline__ bool state_unit(
         if (owns_rows) {
 #pragma unroll
             for (int p = 0; p < 2; ++p) {
-                const bf16x8 af = token_operand(sm.ks[0], 2 * p, 2 * p + 1, 16 * w, r, g);
                 const bf16x8 ab = token_operand(sm.ks[1], 2 * p, 2 * p + 1, 16 * w, r, g);
+                bf16x8 af = ab;
+                if (kFwd) af = token_operand(sm.ks[0], 2 * p, 2 * p + 1, 16 * w, r, g);
 #pragma unroll
                 for (int jt = 0; jt < 4; ++jt) {
                     const bf16x8 vb = token_operand(sm.v, 2 * p, 2 * p + 1, 16 * jt, r, g);
-                    Cf[jt] = mfma(af, vb, Cf[jt]);
+                    if (kFwd) Cf[jt] = mfma(af, vb, Cf[jt]);
                     Cb[jt] = mfma(ab, vb, Cb[jt]);
                 }
             }
@@ -1479,10 +1505,14 @@ __device__ __forceinline__ bool state_unit(
                 Sb[jt][0] = fmaf(Sb[jt][0], db.x, Cb[jt][0]); Sb[jt][1] = fmaf(Sb[jt][1], db.y, Cb[jt][1]);
                 Sb[jt][2] = fmaf(Sb[jt][2], db.z, Cb[jt][2]); Sb[jt][3] = fmaf(Sb[jt][3], db.w, Cb[jt][3]);
             }
-            Sf[jt][0] = fmaf(Cf[jt][0], sf4.x, Sf[jt][0]); Sf[jt][1] = fmaf(Cf[jt][1], sf4.y, Sf[jt][1]);
-            Sf[jt][2] = fmaf(Cf[jt][2], sf4.z, Sf[jt][2]); Sf[jt][3] = fmaf(Cf[jt][3], sf4.w, Sf[jt][3]);
+            if (kFwd) {
+                Sf[jt][0] = fmaf(Cf[jt][0], sf4.x, Sf[jt][0]); Sf[jt][1] = fmaf(Cf[jt][1], sf4.y, Sf[jt][1]);
+                Sf[jt][2] = fmaf(Cf[jt][2], sf4.z, Sf[jt][2]); Sf[jt][3] = fmaf(Cf[jt][3], sf4.w, Sf[jt][3]);
+            }
         }
-        rf.x *= df.x; rf.y *= df.y; rf.z *= df.z; rf.w *= df.w;
+        if (kFwd) {
+            rf.x *= df.x; rf.y *= df.y; rf.z *= df.z; rf.w *= df.w;
+        }
         rb.x *= db.x; rb.y *= db.y; rb.z *= db.z; rb.w *= db.w;
         __syncthreads();  // every read of this chunk's LDS tiles is done
     }
@@ -1524,7 +1554,8 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_slab_kernel(
     unsigned char *__restrict__ stash, int L, int n_chunks, int heads, const LocalityFusion lf)
 {
     const long unit = blockIdx.x;
-    const bool all_fast = state_unit<kDk, kTm>(k, v, g_fwd, g_bwd, nullptr, stash, L, n_chunks, n_chunks, 1, unit, heads);
+    const bool all_fast =
+        state_unit<kDk, kTm, false>(k, v, g_fwd, g_bwd, nullptr, stash, L, n_chunks, n_chunks, 1, unit, heads);
     __syncthreads();  // stash written (and complete), the state pass's LDS no longer read
     if (all_fast)     // uniform over the workgroup
         out_unit<true, kDk, kTm, kLoc>(q, k, v, g_fwd, g_bwd, out, nullptr, stash, L, n_chunks, n_chunks, 1, unit,

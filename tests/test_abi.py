@@ -64,6 +64,26 @@ def test_bigla_validation_codes():
                           ws_bytes=need) == vb.VIG_ERR_ALIGN
 
 
+def test_offset_range_limits():
+    """The kernels address one slab's rows (token-major: one batch element's) with 32-bit byte
+    offsets; shapes beyond that are refused on the host."""
+    L = vb.lib()
+    big = 1 << 40
+    # chunkwise path: sequence length below 2^24, and (L + 64) rows of 128 bytes (times H when token-major)
+    args = (PTR,) * 6 + (1, 1, 1 << 24, 64, 64, vb.VIG_BF16)
+    assert L.bigla_fwd_layout(*args, vb.VIG_LAYOUT_BHLD, PTR, big, None) == vb.VIG_ERR_SHAPE
+    args = (PTR,) * 6 + (1, 8, (1 << 22) - 32, 64, 64, vb.VIG_BF16)
+    assert L.bigla_fwd_layout(*args, vb.VIG_LAYOUT_BLHD, PTR, big, None) == vb.VIG_ERR_SHAPE
+    # the exact recurrence has no such limit on L (it is refused for the workspace here, not the shape)
+    args = (PTR,) * 6 + (1, 1, 1 << 24, 16, 16, vb.VIG_BF16)
+    assert L.bigla_fwd_layout(*args, vb.VIG_LAYOUT_BHLD, None, 0, None) == vb.VIG_ERR_WORKSPACE
+    # locality kernel: one slab (one batch element when token-major) below 4 GiB
+    assert L.locality_gate_fwd_layout(PTR, PTR, None, PTR, PTR, PTR, 1, 1, 1 << 13, 1 << 13, 64, vb.VIG_F32,
+                                      vb.VIG_LAYOUT_BHLD, None) == vb.VIG_ERR_SHAPE
+    assert L.locality_gate_fwd_layout(PTR, PTR, None, PTR, PTR, PTR, 1, 64, 1 << 10, 1 << 10, 64, vb.VIG_BF16,
+                                      vb.VIG_LAYOUT_BLHD, None) == vb.VIG_ERR_SHAPE
+
+
 def test_workspace_query():
     assert vb.bigla_workspace_bytes(1, 1, 64, 16, 16, vb.VIG_F32) == 0
     assert vb.bigla_workspace_bytes(0, 1, 64, 16, 16, vb.VIG_F32) == 0
