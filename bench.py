@@ -37,7 +37,6 @@ CACHE_BYTES = 256 << 20        # Infinity Cache; buffer sets rotate over more th
 MEASURED_TRAFFIC_BYTES = {
     ("segment_out", "vig_s_1024"): 195.1e6,
     ("segment_state", "vig_s_1024"): 138.9e6,
-    ("state_scan", "vig_s_1024"): 32.5e6,
     ("locality_gate", "vig_s_1024"): 109.2e6,
 }
 
@@ -150,7 +149,7 @@ def main():
         "avg_us": round(dom_us, 2), "algorithmic_bytes": alg_bytes,
     }
     bigla_us = sum(kern[n]["avg_us"] * kern[n]["launches_per_step"]
-                   for n in ("segment_state", "state_scan", "segment_out", "segment_out_general", "slab", "recurrent")
+                   for n in ("segment_state", "segment_out", "segment_out_general", "slab", "recurrent")
                    if n in kern)
     extra = {
         "kernels_us": {n: round(k["avg_us"] * k["launches_per_step"], 2) for n, k in kern.items()},

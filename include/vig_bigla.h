@@ -184,8 +184,8 @@ int gate_producer_fwd(const void *x, const void *w1, const void *w2, const void 
  */
 typedef enum {
     VIG_KERNEL_SEGMENT_STATE = 0, /* chunkwise path, launch 1: segment end states + stash     */
-    VIG_KERNEL_STATE_SCAN = 1,    /* chunkwise path, launch 2: scan over segment states       */
-    VIG_KERNEL_SEGMENT_OUT = 2,   /* chunkwise path, launch 3: output pass                    */
+    /* 1 is not in use */
+    VIG_KERNEL_SEGMENT_OUT = 2,   /* chunkwise path, launch 2: output pass                    */
     VIG_KERNEL_RECURRENT = 3,     /* exact fp32 recurrence                                    */
     VIG_KERNEL_LOCALITY_GATE = 4, /* depthwise conv + gate                                    */
     VIG_KERNEL_SEGMENT_OUT_GENERAL = 5, /* chunkwise path, output pass of single-chunk sequences */

@@ -28,7 +28,7 @@ EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "locality_g
            "locality_gate_fwd_layout", "bigla_locality_workspace_bytes", "bigla_locality_fwd", "gate_producer_fwd",
            "vig_status_str", "vig_last_hip_error", "vig_timing_enable",
            "vig_timing_collect")
-KERNELS = {"segment_state": 0, "state_scan": 1, "segment_out": 2, "recurrent": 3, "locality_gate": 4,
+KERNELS = {"segment_state": 0, "segment_out": 2, "recurrent": 3, "locality_gate": 4,
            "segment_out_general": 5, "gate_producer": 6, "slab": 7}
 
 _lib = None

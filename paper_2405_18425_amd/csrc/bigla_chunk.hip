@@ -37,10 +37,11 @@
 //      together with the decay from that chunk's right edge to the segment's right edge; it
 //      also accumulates the segment's forward end state, the backward state at the segment's
 //      left edge and both total decays.
-//   2. bigla_state_scan_kernel    : per state element, the sequential scan over segments in
-//      both directions turns segment-local end states into the states ENTERING each segment
-//      (in place).  Skipped for a single segment.
-//   3. bigla_segment_out_kernel   : one workgroup per (slab, segment) walks its chunks left to
+//   2. bigla_segment_out_kernel   : one workgroup per (slab, segment).  It first folds the
+//      segment-local end states and decays of the slab's other segments into the two states
+//      ENTERING its own segment (forward from the left, backward from the right: a short
+//      sequential scan per state element, E <- D_n E + S_n, whose operands sit in the L2 of the
+//      XCD that all segments of a slab are assigned to), then walks its chunks left to
 //      right, once.  Each chunk is finished in a single step for both directions: one merged
 //      64x64 score tile (lower triangle forward, upper triangle backward, the diagonal from
 //      both), ONE P.V contraction, the forward state readout from the state carried in
@@ -49,7 +50,7 @@
 //      update.  out = (o_fwd + o_bwd)/2 is written once; q, k, v, g_fwd, g_bwd are read once
 //      here.  Segments the state kernel flagged as mild run fast-form-only code inlined in the
 //      kernel; the others call the general code (both forms) as a separate function.
-//   When a plan has one segment per slab, bigla_slab_kernel runs passes 1 and 3 in a single launch
+//   When a plan has one segment per slab, bigla_slab_kernel runs both passes in a single launch
 //   (a workgroup per slab; no segment states, no flags).
 // Nothing is reversed or copied in HBM; both directions read the same q, k, v.
 //
@@ -442,7 +443,9 @@ struct __align__(16) StateLds {
 // Workspace: [segment region][segment flags][stash region].
 //   segment region, per (slab, segment): two fp32 64x64 states (forward, backward) in
 //     accumulator order (float4 number 256*jt + t belongs to thread t of the workgroup:
-//     column 16*jt + r of rows 16w + 4g + e), then two fp32 decay vectors indexed by row.
+//     column 16*jt + r of rows 16w + 4g + e), then two fp32 decay vectors indexed by row: the
+//     segment's LOCAL end states (forward at its right edge, backward at its left edge, both
+//     from a zero start) and total decays, written by the state pass, folded by the output pass.
 //   segment flags, per (slab, segment): one int, non-zero when every chunk of the segment
 //     admits the fast form (written by the state kernel); padded to a multiple of 16 bytes.
 //   stash region, per (slab, chunk): one bf16 64x64 state in accumulator order (thread t of
@@ -1043,6 +1046,24 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
 // compiled general code address the same allocation as LDS (not through a generic reference).
 // The state pass and the output pass use it one after the other (the single-launch kernel for
 // one-segment plans runs both).
+// Which (slab, segment) a workgroup handles.  Workgroups go to the eight XCDs round-robin by index
+// and each XCD has an L2 of its own: when the slab count divides by eight, all segments of a slab
+// are given to workgroups of one XCD, so that the segment states the state pass leaves behind are
+// found in that L2 when the output pass folds them (and the stash of a chunk is read where it was
+// written in either case: both passes use the same mapping).
+__device__ __forceinline__ void unit_slab_segment(long unit, int n_seg, long &slab, int &seg)
+{
+    const long n_slabs = gridDim.x / unsigned(n_seg);
+    if (n_slabs % 8 == 0) {
+        const long j = unit / 8;
+        slab = unit % 8 + 8 * (j / n_seg);
+        seg = int(j % n_seg);
+    } else {
+        slab = unit / n_seg;
+        seg = int(unit % n_seg);
+    }
+}
+
 union PathLds {
     OutLds out;
     StateLds state;
@@ -1066,8 +1087,9 @@ __device__ __forceinline__ void out_unit(
     // 32..63.  The general code keeps the widened form throughout.
     constexpr int kKs = (kFastOnly && kDk == kD / 2) ? 1 : 2;
     const bool owns_rows = kKs > 1 || w < 2;
-    const long slab = unit / n_seg;
-    const int seg = int(unit % n_seg);
+    long slab;
+    int seg;
+    unit_slab_segment(unit, n_seg, slab, seg);
     // first row of the slab and distance between its tokens, in rows of the tensor
     const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
     const long base = row0 * kD, key_base = row0 * kDk;
@@ -1084,8 +1106,7 @@ __device__ __forceinline__ void out_unit(
 
     const int chunk0 = seg * seg_chunks;
     const int nch = min(seg_chunks, n_chunks - chunk0);
-    const float *st_in = seg_states ? seg_states + (slab * n_seg + seg) * kSegFloats : nullptr;
-    const bool seg_in = st_in != nullptr && seg + 1 < n_seg;  // the last segment's entering backward state is zero
+    const bool seg_in = seg_states != nullptr && seg + 1 < n_seg;  // the last segment's entering backward state is zero
     const int row = 16 * w + r;
 
     LocalitySlab ls;
@@ -1142,13 +1163,47 @@ __device__ __forceinline__ void out_unit(
         for (int part = 0; part < 6; ++part) fetch_part(next, 0, part);
     }
 
-    f32x4 S[4];
-    load_state(st_in, st_in == nullptr || !owns_rows, tid, S);
+    // States entering the segment, folded here from the segments' LOCAL end states and decays that
+    // the state pass left in the workspace: forward from the left, E <- D_n * E + S_n over the
+    // segments n < seg; backward from the right over n > seg (kept in registers: each step adds
+    // its decayed copy to the chunk's stashed state, so that one readout serves both).  The loads
+    // of up to four segments are in flight together.
+    f32x4 S[4], Sseg[4];
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) S[jt] = Sseg[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (seg_states != nullptr && owns_rows) {
+        const float *slab_states = seg_states + slab * n_seg * kSegFloats;
+        auto fold = [&](f32x4 (&E)[4], int dir, int first, int count, int step) {
+            constexpr int kBatch = 4;
+            for (int i0 = 0; i0 < count; i0 += kBatch) {
+                f32x4 local[kBatch][4];
+                float4 decay[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const float *sp = slab_states + size_t(first + step * min(i0 + u, count - 1)) * kSegFloats;
+#pragma unroll
+                    for (int jt = 0; jt < 4; ++jt)
+                        local[u][jt] = reinterpret_cast<const f32x4 *>(sp + dir * kD * kD)[kThreads * jt + tid];
+                    decay[u] = *reinterpret_cast<const float4 *>(sp + kSegStateFloats + dir * kD + 16 * w + 4 * g);
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    if (i0 + u < count) {
+#pragma unroll
+                        for (int jt = 0; jt < 4; ++jt) {
+                            E[jt][0] = fmaf(E[jt][0], decay[u].x, local[u][jt][0]);
+                            E[jt][1] = fmaf(E[jt][1], decay[u].y, local[u][jt][1]);
+                            E[jt][2] = fmaf(E[jt][2], decay[u].z, local[u][jt][2]);
+                            E[jt][3] = fmaf(E[jt][3], decay[u].w, local[u][jt][3]);
+                        }
+                    }
+                }
+            }
+        };
+        fold(S, 0, 0, seg, 1);
+        fold(Sseg, 1, n_seg - 1, n_seg - 1 - seg, -1);
+    }
     if (owns_rows) publish_state(sm.st, w, r, g, S);  // made visible by the first barrier of the first step
-    // backward state entering the segment from the right, kept in registers: each step adds its
-    // decayed copy to the chunk's stashed state, so that one readout serves both
-    f32x4 Sseg[4];
-    load_state(st_in + size_t(kD) * kD, !seg_in || !owns_rows, tid, Sseg);
     bf16x8 tri_f[2], tri_b[2];
     scan_triangle<0>(w, r, g, tri_f);
     scan_triangle<1>(w, r, g, tri_b);
@@ -1288,8 +1343,9 @@ __device__ __forceinline__ bool state_unit(
     StateLds &sm = g_lds.state;
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
-    const long slab = unit / n_seg;
-    const int seg = int(unit % n_seg);
+    long slab;
+    int seg;
+    unit_slab_segment(unit, n_seg, slab, seg);
     const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
     // bytes between consecutive tokens of the slab, and the slab's extent from its first row
     const unsigned key_pitch = unsigned(heads) * kDk * 2u, val_pitch = unsigned(heads) * kD * 2u;
@@ -1565,49 +1621,6 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_slab_kernel(
                                          heads, lf);
 }
 
-// ---- kernel 2: scan of segment states, in place ------------------------------------------------
-// On entry seg_states[slab][n] holds segment n's local end states and decays; on exit it holds the
-// states ENTERING segment n: from the left for the forward direction, from the right for the
-// backward direction.  One thread per (slab, direction, float4 of the state): the four values
-// are rows 4g..4g+3 of one 16-row block, so they share one float4 of the decay vector.
-__global__ __launch_bounds__(kThreads) void bigla_state_scan_kernel(float *__restrict__ seg_states, int n_seg)
-{
-    constexpr int kBlocksPerState = kD * kD / 4 / kThreads;
-    const int quad = (blockIdx.x % kBlocksPerState) * kThreads + threadIdx.x;  // 0 .. 1023
-    const int dir = (blockIdx.x / kBlocksPerState) & 1;
-    const long slab = blockIdx.x / (2 * kBlocksPerState);
-    float *base = seg_states + slab * n_seg * kSegFloats;
-    const int owner = quad % kThreads;                                  // thread of the producing workgroup
-    const int row0 = 16 * (owner / 64) + 4 * ((owner % 64) / 16);       // 16w + 4g
-    float4 run = make_float4(0.f, 0.f, 0.f, 0.f);
-    // batches of 8 segments: all loads of a batch are issued before its first store, so that the
-    // in-place update does not serialise one memory round trip per segment
-    constexpr int kBatch = 8;
-    for (int i0 = 0; i0 < n_seg; i0 += kBatch) {
-        float4 local[kBatch], decay[kBatch];
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            const int i = min(i0 + u, n_seg - 1);
-            const int n = dir == 0 ? i : n_seg - 1 - i;
-            const float *s = base + n * kSegFloats;
-            local[u] = reinterpret_cast<const float4 *>(s + dir * kD * kD)[quad];
-            decay[u] = *reinterpret_cast<const float4 *>(s + kSegStateFloats + dir * kD + row0);
-        }
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            if (i0 + u < n_seg) {
-                const int i = i0 + u;
-                const int n = dir == 0 ? i : n_seg - 1 - i;
-                reinterpret_cast<float4 *>(base + n * kSegFloats + dir * kD * kD)[quad] = run;
-                run.x = fmaf(run.x, decay[u].x, local[u].x);
-                run.y = fmaf(run.y, decay[u].y, local[u].y);
-                run.z = fmaf(run.z, decay[u].z, local[u].z);
-                run.w = fmaf(run.w, decay[u].w, local[u].w);
-            }
-        }
-    }
-}
-
 }  // namespace
 
 bool bigla_chunk_supported(int dk, int dv, bool is_bf16) { return is_bf16 && dv == kD && (dk == kD || dk == kD / 2); }
@@ -1631,7 +1644,7 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
 {
     const Plan p = make_plan(BH, L);
     const long blocks = BH * p.n_seg;
-    if (blocks > 0x7fffffffL || BH * 2 * (kD * kD / kThreads) > 0x7fffffffL) return hipErrorInvalidValue;
+    if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
     const uint16_t *qq = static_cast<const uint16_t *>(q), *kk = static_cast<const uint16_t *>(k);
     const uint16_t *vv = static_cast<const uint16_t *>(v);
     const uint16_t *gf = static_cast<const uint16_t *>(g_fwd), *gb = static_cast<const uint16_t *>(g_bwd);
@@ -1652,15 +1665,6 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
             hipLaunchKernelGGL((bigla_segment_state_kernel<kDk, kTm>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, kk, vv,
                                gf, gb, seg_states, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg,
                                heads_token_major);
-        }
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    if (p.n_seg > 1) {
-        {
-            LaunchTimer timer(kKernelStateScan, stream);
-            hipLaunchKernelGGL(bigla_state_scan_kernel, dim3((unsigned)(BH * 2 * (kD * kD / 4 / kThreads))),
-                               dim3(kThreads), 0, stream, seg_states, p.n_seg);
         }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
