@@ -35,8 +35,8 @@ CACHE_BYTES = 256 << 20        # Infinity Cache; buffer sets rotate over more th
 # profiles/bigla_path_vig_s_1024.md (read + written, calibrated with a plain copy), keyed by
 # (kernel, workload); None for pairs that were not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("segment_out", "vig_s_1024"): 195.1e6,
-    ("segment_state", "vig_s_1024"): 138.9e6,
+    ("segment_out", "vig_s_1024"): 193.6e6,
+    ("segment_state", "vig_s_1024"): 138.8e6,
     ("locality_gate", "vig_s_1024"): 109.2e6,
 }
 

@@ -226,7 +226,7 @@ def test_path_end_to_end_hierarchical_stage_shapes(grid, H):
 
 @pytest.mark.parametrize("B,H,Hg,Wg,dk,layout,mu,with_bias", [
     (2, 3, 8, 8, 64, "bhld", 0.0, False),       # one chunk per sequence: the general output kernel
-    (3, 3, 14, 14, 64, "bhld", 0.0, True),      # ragged final chunk, three-launch plan
+    (3, 3, 14, 14, 64, "bhld", 0.0, True),      # ragged final chunk, several segments per slab
     (64, 2, 14, 14, 64, "bhld", 0.0, False),    # one-segment plan: state and output pass in one launch
     (2, 6, 32, 32, 64, "blhd", 2.0, True),
     (2, 3, 64, 64, 32, "bhld", -2.0, False),    # the benchmark grid, 32-wide keys
