@@ -51,6 +51,8 @@ class Oracle:
         lib.locality_gate_ref_f64.restype = ctypes.c_int
         lib.gate_producer_ref_f64.argtypes = [dp] * 6 + [ctypes.c_int] * 6 + [ctypes.c_double, ctypes.c_int]
         lib.gate_producer_ref_f64.restype = ctypes.c_int
+        lib.bigla_bwd_ref_f64.argtypes = [dp] * 11 + [ctypes.c_int] * 6
+        lib.bigla_bwd_ref_f64.restype = ctypes.c_int
         lib.oracle_max_threads.restype = ctypes.c_int
         self._lib = lib
 
@@ -81,6 +83,31 @@ class Oracle:
         if rc != 0:
             raise RuntimeError(f"bigla_ref_f64 failed ({rc})")
         return out
+
+    def bigla_bwd(self, q, k, v, g_fwd, g_bwd, d_out, nthreads: int = 0):
+        """(dq, dk, dv, dg_fwd, dg_bwd): the gradient of `bigla` for the output gradient d_out
+        [B,H,L,dv] (chain rule on the recurrences of Section 4.2.1), float64."""
+        q = _c64(q)
+        if q.ndim != 4:
+            raise ValueError("q must be [B,H,L,dk]")
+        B, H, L, dk = q.shape
+        k = _c64(k, q.shape)
+        g_fwd = _c64(g_fwd, q.shape)
+        g_bwd = _c64(g_bwd, q.shape)
+        v = _c64(v)
+        if v.ndim != 4 or v.shape[:3] != (B, H, L):
+            raise ValueError("v must be [B,H,L,dv]")
+        dv = v.shape[3]
+        d_out = _c64(d_out, v.shape)
+        dq, dk_, dgf, dgb = (np.zeros(q.shape, dtype=np.float64) for _ in range(4))
+        dv_ = np.zeros(v.shape, dtype=np.float64)
+        if q.size == 0 or v.size == 0:
+            return dq, dk_, dv_, dgf, dgb
+        rc = self._lib.bigla_bwd_ref_f64(_ptr(q), _ptr(k), _ptr(v), _ptr(g_fwd), _ptr(g_bwd), _ptr(d_out), _ptr(dq),
+                                         _ptr(dk_), _ptr(dv_), _ptr(dgf), _ptr(dgb), B, H, L, dk, dv, int(nthreads))
+        if rc != 0:
+            raise RuntimeError(f"bigla_bwd_ref_f64 failed ({rc})")
+        return dq, dk_, dv_, dgf, dgb
 
     def locality_gate(self, x, w, gate_logits, o_global, Hg: int, Wg: int, bias=None,
                       nthreads: int = 0) -> np.ndarray:
@@ -149,6 +176,10 @@ def max_threads() -> int:
 
 def bigla(q, k, v, g_fwd, g_bwd, nthreads: int = 0) -> np.ndarray:
     return default().bigla(q, k, v, g_fwd, g_bwd, nthreads)
+
+
+def bigla_bwd(q, k, v, g_fwd, g_bwd, d_out, nthreads: int = 0):
+    return default().bigla_bwd(q, k, v, g_fwd, g_bwd, d_out, nthreads)
 
 
 def locality_gate(x, w, gate_logits, o_global, Hg: int, Wg: int, bias=None, nthreads: int = 0) -> np.ndarray:

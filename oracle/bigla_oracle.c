@@ -14,13 +14,20 @@
  *   - gate_producer_ref_f64 : the direction-wise forget gates, first two lines
  *                             of Eq. (BiGLA) with the low-rank gate of Section 3,
  *                             returned as log-gates.
+ *   - bigla_bwd_ref_f64     : the gradient of bigla_ref_f64 with respect to all five
+ *                             inputs, by the chain rule on the same two recurrences
+ *                             (the paper trains through them, Section 5, but prints no
+ *                             gradient formulas): adjoint states run against each
+ *                             recurrence's direction.
  * No blocking, chunking, fusion or reordering is applied.
  *
  * Pins (tests/test_oracle_pins.py): explicit-product quadratic form by brute
  * force, the all-gates-one reduction to plain bidirectional linear attention,
  * the closed forms for vanishing and constant gates, the reversal symmetry,
  * the kill-one-direction causal check, trilinearity, a hand-worked L=2 case,
- * and for the convolution a library conv2d plus closed-form kernels.
+ * and for the convolution a library conv2d plus closed-form kernels; for the
+ * gradient, central finite differences of bigla_ref_f64 in all five inputs and the
+ * closed forms of the gates-closed and gates-open limits.
  *
  * Layout everywhere: dense row-major, innermost index = feature.
  *   q, k, g_fwd, g_bwd : [B, H, L, dk]      v, out : [B, H, L, dv]
@@ -111,6 +118,100 @@ int bigla_ref_f64(const double *q, const double *k, const double *v,
         }
         free(S);
         free(of);
+    }
+    return failed ? -1 : 0;
+}
+
+/*
+ * Gradient of one direction of one slab.  With s_t the state column of value dimension j
+ * (s_t = alpha_t * s_{t-1} + k_t v_t[j], walking in direction `step` = +1 or -1 from the
+ * direction's first token) and o_t[j] = q_t . s_t, the adjoint of s_t is
+ *     a_t = q_t do_t[j] + alpha_{t+step} * a_{t+step}        (zero beyond the last token)
+ * and the chain rule gives
+ *     dq_t += s_t do_t[j],  dk_t += a_t v_t[j],  dv_t[j] += k_t . a_t,
+ *     dalpha_t += a_t * s_{t-step}  (nothing before the first token),  dg_t = alpha_t dalpha_t.
+ * do = d_out / 2 (the average of the two directions).  Columns j are independent, so the states
+ * of one column at every token (L x dk) are kept and the adjoint runs back over them.
+ */
+static void bigla_bwd_direction(const double *q, const double *k, const double *v, const double *g,
+                                const double *d_out, double *dq, double *dk_, double *dv_, double *dg,
+                                int L, int dk, int dv, int step, double *states, double *a, double *dalpha)
+{
+    const int first = step > 0 ? 0 : L - 1;
+    memset(dalpha, 0, sizeof(double) * (size_t)L * dk);
+    for (int j = 0; j < dv; ++j) {
+        /* states of column j at every token */
+        for (int n = 0; n < L; ++n) {
+            const int t = first + n * step;
+            for (int c = 0; c < dk; ++c) {
+                const double prev = n == 0 ? 0.0 : states[(size_t)(t - step) * dk + c];
+                states[(size_t)t * dk + c] = exp(g[(size_t)t * dk + c]) * prev + k[(size_t)t * dk + c] * v[(size_t)t * dv + j];
+            }
+        }
+        /* adjoint, from the direction's last token back to its first */
+        for (int c = 0; c < dk; ++c) a[c] = 0.0;
+        for (int n = L - 1; n >= 0; --n) {
+            const int t = first + n * step;
+            const double dot = 0.5 * d_out[(size_t)t * dv + j];
+            double kv = 0.0;
+            for (int c = 0; c < dk; ++c) {
+                const double decay = n == L - 1 ? 0.0 : exp(g[(size_t)(t + step) * dk + c]);
+                a[c] = q[(size_t)t * dk + c] * dot + decay * a[c];
+                dq[(size_t)t * dk + c] += states[(size_t)t * dk + c] * dot;
+                dk_[(size_t)t * dk + c] += a[c] * v[(size_t)t * dv + j];
+                kv += k[(size_t)t * dk + c] * a[c];
+                if (n > 0) dalpha[(size_t)t * dk + c] += a[c] * states[(size_t)(t - step) * dk + c];
+            }
+            dv_[(size_t)t * dv + j] += kv;
+        }
+    }
+    for (size_t i = 0; i < (size_t)L * dk; ++i) dg[i] = exp(g[i]) * dalpha[i];
+}
+
+/*
+ * BiGLA backward: given d_out = dLoss/d_out [B,H,L,dv], the gradients of the loss with respect
+ * to q, k, g_fwd, g_bwd [B,H,L,dk] and v [B,H,L,dv] of bigla_ref_f64.  Returns 0, or -1 on a bad
+ * argument / allocation failure.
+ */
+int bigla_bwd_ref_f64(const double *q, const double *k, const double *v, const double *g_fwd,
+                      const double *g_bwd, const double *d_out, double *dq, double *dk_, double *dv_,
+                      double *dg_fwd, double *dg_bwd, int B, int H, int L, int dk, int dv, int nthreads)
+{
+    if (!q || !k || !v || !g_fwd || !g_bwd || !d_out || !dq || !dk_ || !dv_ || !dg_fwd || !dg_bwd) return -1;
+    if (B <= 0 || H <= 0 || L <= 0 || dk <= 0 || dv <= 0) return -1;
+    const long slabs = (long)B * H;
+    int failed = 0;
+#ifdef _OPENMP
+    if (nthreads <= 0) nthreads = omp_get_max_threads();
+#pragma omp parallel num_threads(nthreads)
+#endif
+    {
+        double *states = (double *)malloc(sizeof(double) * (size_t)L * dk);
+        double *dalpha = (double *)malloc(sizeof(double) * (size_t)L * dk);
+        double *a = (double *)malloc(sizeof(double) * (size_t)dk);
+        if (!states || !dalpha || !a) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        } else {
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1)
+#endif
+            for (long s = 0; s < slabs; ++s) {
+                const size_t ok = (size_t)s * L * dk, ov = (size_t)s * L * dv;
+                memset(dq + ok, 0, sizeof(double) * (size_t)L * dk);
+                memset(dk_ + ok, 0, sizeof(double) * (size_t)L * dk);
+                memset(dv_ + ov, 0, sizeof(double) * (size_t)L * dv);
+                bigla_bwd_direction(q + ok, k + ok, v + ov, g_fwd + ok, d_out + ov, dq + ok, dk_ + ok, dv_ + ov,
+                                    dg_fwd + ok, L, dk, dv, +1, states, a, dalpha);
+                bigla_bwd_direction(q + ok, k + ok, v + ov, g_bwd + ok, d_out + ov, dq + ok, dk_ + ok, dv_ + ov,
+                                    dg_bwd + ok, L, dk, dv, -1, states, a, dalpha);
+            }
+        }
+        free(states);
+        free(dalpha);
+        free(a);
     }
     return failed ? -1 : 0;
 }

@@ -389,3 +389,89 @@ def pin_gp_saturation(gp):
 
 GP_PINS = (pin_gp_library_matmul, pin_gp_zero_projection_gives_bias_gate, pin_gp_split_and_head_mapping,
            pin_gp_low_rank_null_space, pin_gp_saturation)
+
+
+# --------------------------------------------------------------------------- #
+# BiGLA backward (gradient of the token mixer): pins take bwd(q, k, v, gf, gb, d_out)
+# -> (dq, dk, dv, dgf, dgb)
+# --------------------------------------------------------------------------- #
+def pin_bwd_finite_differences(bwd):
+    """Central differences of the O(L^2) explicit-product form (no recurrence, no oracle code)
+    in every element of all five inputs, loss = sum(out * d_out)."""
+    q, k, v, gf, gb = _draw(21, B=1, H=2, L=5, dk=2, dv=3, gate_scale=1.5)
+    d_out = _rng(22).standard_normal(v.shape)
+    got = bwd(q, k, v, gf, gb, d_out)
+    args = [q, k, v, gf, gb]
+    h = 1e-6
+    for idx in range(5):
+        fd = np.zeros_like(args[idx])
+        for i in np.ndindex(*args[idx].shape):
+            plus = [a.copy() for a in args]
+            minus = [a.copy() for a in args]
+            plus[idx][i] += h
+            minus[idx][i] -= h
+            fd[i] = (np.sum(quadratic_form(*plus) * d_out) - np.sum(quadratic_form(*minus) * d_out)) / (2 * h)
+        _close(got[idx], fd, 1e-7)
+
+
+def pin_bwd_gates_closed(bwd):
+    """Gates -> 0: out_t = (q_t . k_t) v_t, whose gradients are immediate; the gates get none."""
+    q, k, v, _, _ = _draw(23, L=6)
+    closed = np.full(q.shape, -800.0)
+    d_out = _rng(24).standard_normal(v.shape)
+    dq, dk, dv, dgf, dgb = bwd(q, k, v, closed, closed, d_out)
+    dov = np.sum(d_out * v, axis=-1, keepdims=True)
+    _close(dq, dov * k)
+    _close(dk, dov * q)
+    _close(dv, np.sum(q * k, axis=-1, keepdims=True) * d_out)
+    assert np.all(dgf == 0.0) and np.all(dgb == 0.0)
+
+
+def pin_bwd_gates_open(bwd):
+    """All log-gates 0: out = W V with W = (tril(QK^T) + triu(QK^T)) / 2, plain matrix calculus."""
+    q, k, v, _, _ = _draw(25, L=7)
+    zero = np.zeros(q.shape)
+    d_out = _rng(26).standard_normal(v.shape)
+    dq, dk, dv, _, _ = bwd(q, k, v, zero, zero, d_out)
+    L = q.shape[2]
+    mask = 0.5 * (np.tril(np.ones((L, L))) + np.triu(np.ones((L, L))))
+    P = np.einsum("bhtc,bhic->bhti", q, k)
+    dP = np.einsum("bhtj,bhij->bhti", d_out, v) * mask
+    _close(dv, np.einsum("bhti,bhtj->bhij", P * mask, d_out))
+    _close(dq, np.einsum("bhti,bhic->bhtc", dP, k))
+    _close(dk, np.einsum("bhti,bhtc->bhic", dP, q))
+
+
+def pin_bwd_reversal_symmetry(bwd):
+    """Reversing the sequence and swapping the gate streams reverses every gradient and swaps the
+    two gate gradients."""
+    q, k, v, gf, gb = _draw(27, L=8)
+    d_out = _rng(28).standard_normal(v.shape)
+    a = bwd(q, k, v, gf, gb, d_out)
+    rev = lambda x: np.ascontiguousarray(x[:, :, ::-1])
+    b = bwd(rev(q), rev(k), rev(v), rev(gb), rev(gf), rev(d_out))
+    for x, y in zip(a, (b[0], b[1], b[2], b[4], b[3])):
+        _close(rev(y), x)
+
+
+def pin_bwd_inert_gates_linearity_slabs(bwd):
+    """g_fwd[0] and g_bwd[L-1] multiply zero states: no gradient.  The map d_out -> gradients is
+    linear, and a slab whose d_out is zero receives none while the others are unchanged."""
+    q, k, v, gf, gb = _draw(29, L=6)
+    r = _rng(30)
+    d1, d2 = r.standard_normal((2,) + v.shape)
+    g1, g2, g12 = bwd(q, k, v, gf, gb, d1), bwd(q, k, v, gf, gb, d2), bwd(q, k, v, gf, gb, 2.0 * d1 - 3.0 * d2)
+    assert np.all(g1[3][:, :, 0] == 0.0) and np.all(g1[4][:, :, -1] == 0.0)
+    assert np.any(g1[3][:, :, 1] != 0.0) and np.any(g1[4][:, :, 0] != 0.0)
+    for a, b, c in zip(g1, g2, g12):
+        _close(c, 2.0 * a - 3.0 * b)
+    d3 = d1.copy()
+    d3[0, 1] = 0.0
+    g3 = bwd(q, k, v, gf, gb, d3)
+    for a, b in zip(g1, g3):
+        assert np.all(b[0, 1] == 0.0)
+        assert np.array_equal(b[1], a[1]) and np.array_equal(b[0, 0], a[0, 0])
+
+
+BWD_PINS = (pin_bwd_finite_differences, pin_bwd_gates_closed, pin_bwd_gates_open, pin_bwd_reversal_symmetry,
+            pin_bwd_inert_gates_linearity_slabs)

@@ -10,7 +10,7 @@ import subprocess
 import pytest
 
 import oracle
-from oracle_pins import BIGLA_PINS, GP_PINS, LOC_PINS
+from oracle_pins import BIGLA_PINS, BWD_PINS, GP_PINS, LOC_PINS
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "bigla_oracle.c")
 
@@ -55,6 +55,22 @@ MUTANTS = [
     ("gp_sigmoid_sign", "return (z < 0.0 ? z : 0.0) - log1p(exp(-fabs(z)));", "return (z > 0.0 ? -z : 0.0) - log1p(exp(-fabs(z)));", None, "gp"),
     ("gp_naive_log_sigmoid", "return (z < 0.0 ? z : 0.0) - log1p(exp(-fabs(z)));", "return log(1.0 / (1.0 + exp(-z)));", None, "gp"),
     ("gp_token_batch_swapped", "const long b = n / L, t = n % L;", "const long b = n % B, t = n / B;", None, "gp"),
+    ("bwd_no_half", "const double dot = 0.5 * d_out[(size_t)t * dv + j];", "const double dot = d_out[(size_t)t * dv + j];",
+     None, "bwd"),
+    ("bwd_adjoint_decays_by_own_gate", "const double decay = n == L - 1 ? 0.0 : exp(g[(size_t)(t + step) * dk + c]);",
+     "const double decay = n == L - 1 ? 0.0 : exp(g[(size_t)t * dk + c]);", None, "bwd"),
+    ("bwd_dalpha_from_current_state", "dalpha[(size_t)t * dk + c] += a[c] * states[(size_t)(t - step) * dk + c];",
+     "dalpha[(size_t)t * dk + c] += a[c] * states[(size_t)t * dk + c];", None, "bwd"),
+    ("bwd_dg_without_alpha", "dg[i] = exp(g[i]) * dalpha[i];", "dg[i] = dalpha[i];", None, "bwd"),
+    ("bwd_directions_swapped", "dg_fwd + ok, L, dk, dv, +1, states, a, dalpha);",
+     "dg_fwd + ok, L, dk, dv, -1, states, a, dalpha);", None, "bwd"),
+    ("bwd_gate_streams_swapped", "bigla_bwd_direction(q + ok, k + ok, v + ov, g_bwd + ok,",
+     "bigla_bwd_direction(q + ok, k + ok, v + ov, g_fwd + ok,", None, "bwd"),
+    ("bwd_dq_from_adjoint", "dq[(size_t)t * dk + c] += states[(size_t)t * dk + c] * dot;",
+     "dq[(size_t)t * dk + c] += a[c] * dot;", None, "bwd"),
+    ("bwd_dv_from_q", "kv += k[(size_t)t * dk + c] * a[c];", "kv += q[(size_t)t * dk + c] * a[c];", None, "bwd"),
+    ("bwd_dk_without_v", "dk_[(size_t)t * dk + c] += a[c] * v[(size_t)t * dv + j];", "dk_[(size_t)t * dk + c] += a[c];",
+     None, "bwd"),
 ]
 
 
@@ -100,8 +116,8 @@ def test_mutant_is_caught(tmp_path, name, old, new, occ, which):
     subprocess.run(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-w", "-o", str(so_path),
                     str(c_path), "-lm"], check=True)
     mutant = oracle.Oracle(str(so_path))
-    pins = {"bigla": BIGLA_PINS, "loc": LOC_PINS, "gp": GP_PINS}[which]
-    fn = {"bigla": mutant.bigla, "loc": mutant.locality_gate, "gp": mutant.gate_producer}[which]
+    pins = {"bigla": BIGLA_PINS, "loc": LOC_PINS, "gp": GP_PINS, "bwd": BWD_PINS}[which]
+    fn = {"bigla": mutant.bigla, "loc": mutant.locality_gate, "gp": mutant.gate_producer, "bwd": mutant.bigla_bwd}[which]
     tripped = []
     for pin in pins:
         try:

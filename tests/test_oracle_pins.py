@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle_pins import BIGLA_PINS, GP_PINS, LOC_PINS
+from oracle_pins import BIGLA_PINS, BWD_PINS, GP_PINS, LOC_PINS
 
 
 @pytest.mark.parametrize("pin", BIGLA_PINS, ids=lambda p: p.__name__)
@@ -19,6 +19,11 @@ def test_locality_pin(pin):
 @pytest.mark.parametrize("pin", GP_PINS, ids=lambda p: p.__name__)
 def test_gate_producer_pin(pin):
     pin(oracle.gate_producer)
+
+
+@pytest.mark.parametrize("pin", BWD_PINS, ids=lambda p: p.__name__)
+def test_bigla_bwd_pin(pin):
+    pin(oracle.bigla_bwd)
 
 
 def test_gate_producer_feeds_bigla():
