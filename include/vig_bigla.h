@@ -97,6 +97,31 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * BiGLA backward -- the gradient of bigla_fwd (Section 4.2.1, Eq. (BiGLA); the paper trains
+ * through the token mixer, Section 5, and prints no gradient formulas, so this is the chain rule
+ * on the two recurrences).  Given d_out = dLoss/d_out it returns dLoss/d(q, k, v, g_fwd, g_bwd):
+ * with do_t = d_out_t / 2 and, per direction, the adjoint of the state
+ *     A_t = q_t^T do_t + diag(alpha_{t+1}) A_{t+1}   (forward direction; mirrored for backward),
+ *     dq_t = S_t do_t^T ,  dk_t = A_t v_t^T ,  dv_t = k_t A_t     (summed over both directions),
+ *     dg_fwd_t = alpha_fwd_t * sum_j A_fwd_t[., j] S_fwd_{t-1}[., j]   (likewise dg_bwd with t+1).
+ *
+ *   q, k, v, g_fwd, g_bwd   as for bigla_fwd_layout            in
+ *   d_out                   [B, H, L, dv]                      in
+ *   dq, dk, dg_fwd, dg_bwd  [B, H, L, dk]                      out
+ *   dv                      [B, H, L, dv]                      out
+ *   (all in `layout`; dk, dv in {16, 32, 64}; any L >= 1)
+ *   workspace: at least bigla_bwd_workspace_bytes(...) bytes (fp32 partial gradients).
+ * Numerics: fp32 arithmetic token by token for either dtype (bf16 in and out, rounded to nearest
+ * even); the gate gradients are formed as running sums of q * dq - k * dk per direction, which is
+ * the same quantity.  A chunkwise matrix-core version does not exist yet.
+ */
+size_t bigla_bwd_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype);
+int bigla_bwd(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+              const void *d_out, void *dq, void *dk, void *dv, void *dg_fwd, void *dg_bwd, int B, int H,
+              int L, int dk_, int dv_, int dtype, int layout, void *workspace, size_t workspace_bytes,
+              void *stream);
+
+/*
  * 2D gating locality injection forward -- Section 4.2.2.  Token t of the flattened
  * sequence is patch (y, xp) of the Hg x Wg grid, t = y*Wg + xp; channel c = h*dv + j.
  *     O_local[y,xp,c] = bias[c] + sum_{dy,dx in {-1,0,1}} w[c,dy+1,dx+1] * x[y+dy, xp+dx, c]
@@ -190,7 +215,8 @@ typedef enum {
     VIG_KERNEL_LOCALITY_GATE = 4, /* depthwise conv + gate                                    */
     VIG_KERNEL_SEGMENT_OUT_GENERAL = 5, /* chunkwise path, output pass of single-chunk sequences */
     VIG_KERNEL_GATE_PRODUCER = 6, /* forget-gate producer                                     */
-    VIG_KERNEL_SLAB = 7           /* chunkwise path, one-segment plans: both passes, one launch */
+    VIG_KERNEL_SLAB = 7,          /* chunkwise path, one-segment plans: both passes, one launch */
+    VIG_KERNEL_BACKWARD = 8       /* the two launches of bigla_bwd together                   */
 } vig_kernel;
 int vig_timing_enable(int on);
 int vig_timing_collect(int kernel, double *total_ms, long *launches);

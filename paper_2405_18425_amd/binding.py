@@ -26,10 +26,11 @@ PLANS = {"auto": 0, "two_launches": 1, "fused_epilogue": 2}
 # every symbol include/vig_bigla.h declares
 EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "locality_gate_fwd",
            "locality_gate_fwd_layout", "bigla_locality_workspace_bytes", "bigla_locality_fwd", "gate_producer_fwd",
+           "bigla_bwd_workspace_bytes", "bigla_bwd",
            "vig_status_str", "vig_last_hip_error", "vig_timing_enable",
            "vig_timing_collect")
 KERNELS = {"segment_state": 0, "segment_out": 2, "recurrent": 3, "locality_gate": 4,
-           "segment_out_general": 5, "gate_producer": 6, "slab": 7}
+           "segment_out_general": 5, "gate_producer": 6, "slab": 7, "backward": 8}
 
 _lib = None
 
@@ -63,6 +64,10 @@ def lib() -> ctypes.CDLL:
         L.bigla_locality_workspace_bytes.restype = sz
         L.bigla_locality_fwd.argtypes = [vp] * 10 + [ci] * 9 + [vp, sz, vp]
         L.bigla_locality_fwd.restype = ci
+        L.bigla_bwd_workspace_bytes.argtypes = [ci] * 6
+        L.bigla_bwd_workspace_bytes.restype = sz
+        L.bigla_bwd.argtypes = [vp] * 11 + [ci] * 7 + [vp, sz, vp]
+        L.bigla_bwd.restype = ci
         L.gate_producer_fwd.argtypes = [vp] * 6 + [ci] * 5 + [ctypes.c_float, ci, ci, vp]
         L.gate_producer_fwd.restype = ci
         L.vig_status_str.argtypes = [ci]
@@ -251,6 +256,42 @@ def bigla_locality_fwd(q, k, v, g_fwd, g_bwd, x, w, gate_logits, Hg: int, Wg: in
                                       PLANS[plan], ws_ptr, ws_bytes, _stream_ptr(q.device))
     _check(st, "bigla_locality_fwd")
     return out
+
+
+def bigla_bwd(q, k, v, g_fwd, g_bwd, d_out, workspace=None, layout="bhld"):
+    """Gradient of bigla_fwd (Section 4.2.1): returns (dq, dk, dv, dg_fwd, dg_bwd) for the output
+    gradient d_out (shaped like v); tensors as for bigla_fwd."""
+    lay = _layout_code(layout)
+    q = _dev(q, "q")
+    if q.dim() != 4:
+        raise VigError(VIG_ERR_SHAPE, "q must be 4-dimensional")
+    if lay == VIG_LAYOUT_BHLD:
+        B, H, L, dk = q.shape
+    else:
+        B, L, H, dk = q.shape
+    k = _dev(k, "k", q.shape, q)
+    g_fwd = _dev(g_fwd, "g_fwd", q.shape, q)
+    g_bwd = _dev(g_bwd, "g_bwd", q.shape, q)
+    v = _dev(v, "v", like=q)
+    if v.dim() != 4 or tuple(v.shape[:3]) != tuple(q.shape[:3]):
+        raise VigError(VIG_ERR_SHAPE, "v must have the leading dimensions of q")
+    dv = v.shape[3]
+    d_out = _dev(d_out, "d_out", v.shape, q)
+    dq, dk_, dgf, dgb = (torch.empty_like(q) for _ in range(4))
+    dv_ = torch.empty_like(v)
+    code = _dtype_code(q)
+    need = int(lib().bigla_bwd_workspace_bytes(B, H, L, dk, dv, code))
+    if need == 0:
+        raise VigError(VIG_ERR_UNSUPPORTED, "unsupported shape for bigla_bwd")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    with torch.cuda.device(q.device):
+        st = lib().bigla_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), g_fwd.data_ptr(), g_bwd.data_ptr(),
+                             d_out.data_ptr(), dq.data_ptr(), dk_.data_ptr(), dv_.data_ptr(), dgf.data_ptr(),
+                             dgb.data_ptr(), B, H, L, dk, dv, code, lay, workspace.data_ptr(),
+                             workspace.numel() * workspace.element_size(), _stream_ptr(q.device))
+    _check(st, "bigla_bwd")
+    return dq, dk_, dv_, dgf, dgb
 
 
 def gate_producer_fwd(x, w1, w2, H: int, dk: int, bias=None, tau: float = 16.0, layout="bhld", g_fwd=None,

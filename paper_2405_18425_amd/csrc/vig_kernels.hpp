@@ -30,6 +30,12 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
                               void *out, long BH, int L, int dk, int heads_token_major, const LocalityFusion *fusion,
                               void *workspace, hipStream_t stream);
 
+// ---- gradient of the token mixer, exact fp32 recurrences (any supported head shape, both dtypes) ----
+size_t bigla_bwd_workspace_bytes(long BH, int L, int dk, int dv);
+hipError_t bigla_bwd_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                            const void *d_out, void *dq, void *dk, void *dv, void *dg_fwd, void *dg_bwd, long BH, int L,
+                            int dk_, int dv_, bool is_bf16, int heads_token_major, void *workspace, hipStream_t stream);
+
 // ---- depthwise 3x3 conv + sigmoid-gated blend -------------------------------------------------
 hipError_t locality_gate_launch(const void *x, const void *w, const void *bias, const void *gate_logits,
                                 const void *o_global, void *out, int B, int H, int Hg, int Wg, int dv,

@@ -15,7 +15,8 @@ enum KernelId {
     kKernelSegmentOutGeneral = 5,
     kKernelGateProducer = 6,
     kKernelSlab = 7,
-    kKernelCount = 8
+    kKernelBackward = 8,
+    kKernelCount = 9
 };
 
 // Brackets one launch when timing is enabled on the calling thread.

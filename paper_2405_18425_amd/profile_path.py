@@ -7,7 +7,8 @@ WRITE_SIZE (bytes = counter * factor, factor = known copy bytes / counter of the
 A third argument D > 0 adds the forget-gate producer in front of every pass (block input of width D
 for the same B, L, H, dk), feeding the gates it makes to bigla_fwd.  A fourth argument 1 or 2 runs
 each pass through bigla_locality_fwd with the two-launch plan (1) or the fused-epilogue plan (2)
-instead of the two separate entry points.
+instead of the two separate entry points; 3 runs bigla_bwd (the gradient of the token mixer, with
+the locality step's input as output gradient) after each forward pass.
 """
 from __future__ import annotations
 
@@ -39,13 +40,15 @@ def main(cfg: int = 4, passes: int = 3, gate_width: int = 0, plan: int = 0) -> N
         if gp is not None:
             vb.gate_producer_fwd(gp["x"], gp["w1"], gp["w2"], w.H, w.dk, bias=gp["bias"], g_fwd=t["g_fwd"],
                                  g_bwd=t["g_bwd"])
-        if plan:
+        if plan in (1, 2):
             out = vb.bigla_locality_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], t["v"], t["conv_w"],
                                         t["gate_logits"], w.Hg, w.Wg,
                                         plan={1: "two_launches", 2: "fused_epilogue"}[plan])
             continue
         og = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"])
         out = vb.locality_gate_fwd(t["v"], t["conv_w"], t["gate_logits"], og, w.Hg, w.Wg)
+        if plan == 3:
+            vb.bigla_bwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], t["gate_logits"])
     torch.cuda.synchronize()
     print("profile_path done", w.name, passes, float(out.float().abs().mean()), flush=True)
 

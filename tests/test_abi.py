@@ -186,6 +186,28 @@ def test_bigla_locality_validation_codes():
                 ws_bytes=1 << 40) == vb.VIG_ERR_SHAPE
 
 
+def test_bigla_bwd_validation_codes():
+    L = vb.lib()
+
+    def call(q=PTR, k=PTR, v=PTR, gf=PTR, gb=PTR, do=PTR, dq=PTR, dk_=PTR, dv_=PTR, dgf=PTR, dgb=PTR, B=1, H=1, Ln=8,
+             dk=16, dv=16, dtype=vb.VIG_F32, layout=vb.VIG_LAYOUT_BHLD, ws=PTR, ws_bytes=1 << 40):
+        return L.bigla_bwd(q, k, v, gf, gb, do, dq, dk_, dv_, dgf, dgb, B, H, Ln, dk, dv, dtype, layout, ws, ws_bytes, None)
+
+    for name in ("q", "k", "v", "gf", "gb", "do", "dq", "dk_", "dv_", "dgf", "dgb"):
+        assert call(**{name: None}) == vb.VIG_ERR_NULL
+    for name in ("B", "H", "Ln", "dk", "dv"):
+        assert call(**{name: 0}) == vb.VIG_ERR_SHAPE
+    assert call(dtype=2) == vb.VIG_ERR_DTYPE
+    assert call(layout=-1) == vb.VIG_ERR_LAYOUT
+    assert call(dk=24) == vb.VIG_ERR_UNSUPPORTED
+    assert call(dq=PTR + 4) == vb.VIG_ERR_ALIGN
+    need = L.bigla_bwd_workspace_bytes(2, 3, 100, 32, 64, vb.VIG_BF16)
+    assert need == 2 * 3 * 100 * (3 * 32 + 64) * 4
+    assert call(B=2, H=3, Ln=100, dk=32, dv=64, dtype=vb.VIG_BF16, ws=None, ws_bytes=0) == vb.VIG_ERR_WORKSPACE
+    assert call(B=2, H=3, Ln=100, dk=32, dv=64, dtype=vb.VIG_BF16, ws_bytes=need - 1) == vb.VIG_ERR_WORKSPACE
+    assert L.bigla_bwd_workspace_bytes(2, 3, 100, 48, 64, vb.VIG_BF16) == 0
+
+
 def test_binding_rejects_cpu_tensors():
     import torch
 

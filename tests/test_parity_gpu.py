@@ -492,3 +492,80 @@ def test_path_captured_in_a_hip_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out, want), f"replay {rep}"
+
+
+# --------------------------------------------------------------------------- #
+# BiGLA backward
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("dtype,B,H,L,dk,dv,layout,mu", [
+    ("f32", 1, 2, 37, 16, 16, "bhld", 0.0),
+    ("f32", 2, 2, 100, 32, 64, "blhd", 0.0),
+    ("f32", 1, 1, 1, 16, 16, "bhld", 0.0),        # a single token: only the self term
+    ("f32", 2, 2, 16, 32, 32, "bhld", 0.0),       # exactly one staged tile: the second sweep starts where the first ended
+    ("bf16", 3, 2, 20, 64, 64, "blhd", 0.0),      # two tiles, the last one ragged
+    ("f32", 1, 2, 130, 64, 64, "bhld", -6.0),     # strong decay
+    ("bf16", 2, 3, 196, 64, 64, "bhld", 0.0),     # the 14 x 14 grid
+    ("bf16", 1, 2, 333, 32, 64, "blhd", 2.0),     # the paper's head shape, gates near one
+    ("bf16", 2, 2, 64, 16, 32, "bhld", 0.0),
+    ("bf16", 1, 6, 1024, 64, 64, "bhld", -2.0),   # one batch element of the 32 x 32 grid
+])
+def test_bigla_bwd_parity(dtype, B, H, L, dk, dv, layout, mu):
+    """bigla_bwd against the oracle's gradient, all five gradients, same stored inputs."""
+    import torch
+    from paper_2405_18425_amd import binding as vb
+    import oracle
+
+    w = wl.Workload("bwd", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=dv, dtype=dtype, gate_mu=mu)
+    _say(f"bigla_bwd {w} {layout}")
+    s = wl.generate(w, seed=L + dk)
+    s["d_out"] = wl.generate(w, seed=L + dk + 1)["v"]
+    names = ("q", "k", "v", "g_fwd", "g_bwd", "d_out")
+    wd = {n: wl.widen(s[n], dtype) for n in names}
+    t = {n: wl.to_torch(s[n], dtype, "cuda:0") for n in names}
+    if layout == "blhd":
+        t = {n: a.transpose(1, 2).contiguous() for n, a in t.items()}
+    got = vb.bigla_bwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], t["d_out"], layout=layout)
+    torch.cuda.synchronize()
+    ref = oracle.bigla_bwd(wd["q"], wd["k"], wd["v"], wd["g_fwd"], wd["g_bwd"], wd["d_out"])
+    # The gate gradients are running sums of q * dq - k * dk (Section 4.2.1 differentiated): their
+    # rounding error scales with those summands, not with the result, which is exactly zero where
+    # a gate is inert (g_fwd of the first token, g_bwd of the last) and can be small elsewhere.
+    rms = lambda a: np.sqrt(np.mean(a ** 2, axis=(2, 3), keepdims=True))
+    summand = rms(wd["q"] * ref[0]) + rms(wd["k"] * ref[1])
+    for name, g, r in zip(("dq", "dk", "dv", "dg_fwd", "dg_bwd"), got, ref):
+        if layout == "blhd":
+            g = g.transpose(1, 2).contiguous()
+        g64 = wl.widen(wl.from_torch(g, dtype), dtype)
+        if name.startswith("dg"):
+            assert np.all(np.isfinite(g64))
+            bound = TOL[dtype] * (np.abs(r) + rms(r) + summand)
+            assert np.all(np.abs(g64 - r) <= bound), f"{name}: {float(np.max(np.abs(g64 - r) - bound)):.3e} over the bound"
+        else:
+            assert_close(g64, r, TOL[dtype], f"{name}")
+
+
+def test_bigla_bwd_is_the_gradient_of_the_forward_kernels():
+    """Directional derivative of the library's own forward (fp32) along a random direction in all
+    five inputs against <gradient, direction>: the two entry points agree with each other, not
+    only each with the oracle."""
+    import torch
+    from paper_2405_18425_amd import binding as vb
+
+    w = wl.Workload("fd", B=1, H=2, Hg=1, Wg=48, dk=16, dv=16, dtype="f32", gate_mu=0.0)
+    s = wl.generate(w, seed=5)
+    names = ("q", "k", "v", "g_fwd", "g_bwd")
+    x = {n: wl.to_torch(s[n], "f32", "cuda:0").double() for n in names}
+    d_out = wl.to_torch(wl.generate(w, seed=6)["v"], "f32", "cuda:0")
+    u = {n: wl.to_torch(wl.generate(w, seed=7 + i)[n], "f32", "cuda:0").double() for i, n in enumerate(names)}
+    u["g_fwd"], u["g_bwd"] = -u["g_fwd"].abs(), u["g_bwd"].abs() * 0.5   # any direction will do
+    grads = vb.bigla_bwd(*(x[n].float() for n in names), d_out)
+    lhs = sum(float((g.double() * u[n]).sum()) for g, n in zip((grads[0], grads[1], grads[2], grads[3], grads[4]), names))
+    h = 1e-2   # fp32 forward: a large step, the loss is smooth
+    def loss(sign):
+        args = [(x[n] + sign * h * u[n]).float() for n in names]
+        args[3], args[4] = args[3].clamp(max=0.0), args[4].clamp(max=0.0)
+        return float((vb.bigla_fwd(*args).double() * d_out.double()).sum())
+    torch.cuda.synchronize()
+    rhs = (loss(+1.0) - loss(-1.0)) / (2 * h)
+    _say(f"<grad, u> = {lhs:.6f}, central difference of the forward = {rhs:.6f}")
+    assert abs(lhs - rhs) <= 2e-3 * max(1.0, abs(rhs))
