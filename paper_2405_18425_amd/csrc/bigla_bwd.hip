@@ -73,6 +73,50 @@ __device__ __forceinline__ float share_scan(float x, int s)
     return x;
 }
 
+// A [16 tokens][NC columns] piece of a row tensor moves as 16-byte chunks, one per thread:
+// chunk = (token, 16-byte part of the token's NC columns); tokens past the sequence repeat the last
+// one (always a valid address) and are replaced by `pad` when the piece is put into LDS.
+template <typename E, int NC>
+struct Piece {
+    static constexpr int kVals = 16 / int(sizeof(E));   // values per chunk
+    static constexpr int kPerRow = NC / kVals;           // chunks per token
+    static constexpr int kChunks = kTile * kPerRow;      // <= 256 for NC <= 64
+    static_assert(NC % kVals == 0 && kChunks <= kShare * kBlock, "piece fits one chunk per thread");
+
+    static __device__ __forceinline__ uint4 load(const E *base, size_t pitch, int t0, int col0, int L, int tid)
+    {
+        uint4 r = make_uint4(0u, 0u, 0u, 0u);
+        if (tid < kChunks) {
+            const int tok = min(t0 + tid / kPerRow, L - 1);
+            r = *reinterpret_cast<const uint4 *>(base + size_t(tok) * pitch + col0 + (tid % kPerRow) * kVals);
+        }
+        return r;
+    }
+
+    // dst[token][column] = f(value) (f: scale, or exp for log-gates), `pad` for tokens >= n
+    template <bool kExp>
+    static __device__ __forceinline__ void put(float (*dst)[NC], const uint4 &raw, int n, float scale, float pad, int tid)
+    {
+        if (tid >= kChunks) return;
+        const int tt = tid / kPerRow, c = (tid % kPerRow) * kVals;
+        float f[kVals];
+        if (sizeof(E) == 2) {
+            f[0] = bf16_lo_to_f32(raw.x); f[1] = bf16_hi_to_f32(raw.x);
+            f[2 % kVals] = bf16_lo_to_f32(raw.y); f[3 % kVals] = bf16_hi_to_f32(raw.y);
+            f[4 % kVals] = bf16_lo_to_f32(raw.z); f[5 % kVals] = bf16_hi_to_f32(raw.z);
+            f[6 % kVals] = bf16_lo_to_f32(raw.w); f[7 % kVals] = bf16_hi_to_f32(raw.w);
+        } else {
+            f[0] = __uint_as_float(raw.x); f[1] = __uint_as_float(raw.y);
+            f[2] = __uint_as_float(raw.z); f[3] = __uint_as_float(raw.w);
+        }
+#pragma unroll
+        for (int j = 0; j < kVals; ++j) {
+            const float x = kExp ? __expf(f[j]) : scale * f[j];
+            dst[tt][c + j] = tt < n ? x : pad;
+        }
+    }
+};
+
 // Rows of one slab of a tensor: element (t, c) of a [.., L, D] slab sits at base[t * pitch + c]
 template <typename T>
 struct Rows {
@@ -117,7 +161,7 @@ __device__ __forceinline__ void bwd_block(
     // result; whole rows of the operands along the shared dimension
     __shared__ float s_own[kTile][kBlock], s_alpha[kTile][kBlock], s_k[kTile][kBlock], s_dq[kTile][kBlock],
         s_first[kTile][kBlock];
-    __shared__ __align__(16) float s_a[kTile][D_SPLIT], s_b[kTile][D_SPLIT], s_gate[kTile][kRowsRole ? 1 : D_SPLIT];
+    __shared__ __align__(16) float s_a[kTile][D_SPLIT], s_b[kTile][D_SPLIT], s_gate[kRowsRole ? 1 : kTile][D_SPLIT];
 
     for (int sweep = 0; sweep < 2; ++sweep) {
         if (sweep == 1) {
@@ -139,75 +183,64 @@ __device__ __forceinline__ void bwd_block(
 
         // A tile's operands are requested one tile ahead, all loads issued together from clamped
         // (always valid) addresses, and put into LDS (zeroed past the sequence) when their turn comes.
-        constexpr int kPer = kTile * D_SPLIT / kThreads;  // elements per thread of a [16][D_SPLIT] piece
         struct TileRegs {
-            float own, gate_own, k, dq, first;
-            float a[kPer], b[kPer], gate[kPer];
+            uint4 own, gate_own, k, dq, first, a, b, gate;
         };
-        const int st_tt = tid / kBlock, st_c = tid % kBlock;  // this thread's element of the 16 x 16 pieces
+        typedef Piece<T, kBlock> Own;        // the block's 16 columns of a row tensor
+        typedef Piece<float, kBlock> OwnF;   // ... of an fp32 workspace array
+        typedef Piece<T, D_SPLIT> Full;      // whole rows along the shared dimension
         auto fetch = [&](int tile) {
             TileRegs r;
             const int t0 = tile * kTile;
-            const int tok = min(t0 + st_tt, L - 1);
-            r.k = r.dq = r.first = r.gate_own = 0.f;
+            r.gate_own = r.k = r.dq = r.first = r.gate = make_uint4(0u, 0u, 0u, 0u);
             if (kRowsRole) {
-                r.own = ROLE == kRoleDq ? k.at(tok, i0 + st_c) : q.at(tok, i0 + st_c);
-                r.gate_own = g.at(tok, i0 + st_c);
+                r.own = Own::load((ROLE == kRoleDq ? k : q).base, k.pitch, t0, i0, L, tid);
+                r.gate_own = Own::load(g.base, g.pitch, t0, i0, L, tid);
                 if (ROLE == kRoleDk) {
-                    r.k = k.at(tok, i0 + st_c);
-                    r.dq = (sweep == 0 ? dqf : dqb)[size_t(tok) * DK + i0 + st_c];
+                    r.k = Own::load(k.base, k.pitch, t0, i0, L, tid);
+                    r.dq = OwnF::load(sweep == 0 ? dqf : dqb, DK, t0, i0, L, tid);
                 }
             } else {
-                r.own = dout.at(tok, i0 + st_c);
+                r.own = Own::load(dout.base, dout.pitch, t0, i0, L, tid);
             }
-            if (sweep == 1) r.first = (ROLE == kRoleDq ? dqf : part)[size_t(tok) * D_OWN + i0 + st_c];
-#pragma unroll
-            for (int u = 0; u < kPer; ++u) {
-                const int e = tid + u * kThreads, t2 = min(t0 + e / D_SPLIT, L - 1), c2 = e % D_SPLIT;
-                if (ROLE == kRoleDq) {
-                    r.a[u] = v.at(t2, c2);
-                    r.b[u] = dout.at(t2, c2);
-                } else if (ROLE == kRoleDk) {
-                    r.a[u] = dout.at(t2, c2);
-                    r.b[u] = v.at(t2, c2);
-                } else {
-                    r.a[u] = q.at(t2, c2);
-                    r.b[u] = k.at(t2, c2);
-                    r.gate[u] = g.at(t2, c2);
-                }
+            if (sweep == 1) r.first = OwnF::load(ROLE == kRoleDq ? dqf : part, D_OWN, t0, i0, L, tid);
+            if (ROLE == kRoleDq) {
+                r.a = Full::load(v.base, v.pitch, t0, 0, L, tid);
+                r.b = Full::load(dout.base, dout.pitch, t0, 0, L, tid);
+            } else if (ROLE == kRoleDk) {
+                r.a = Full::load(dout.base, dout.pitch, t0, 0, L, tid);
+                r.b = Full::load(v.base, v.pitch, t0, 0, L, tid);
+            } else {
+                r.a = Full::load(q.base, q.pitch, t0, 0, L, tid);
+                r.b = Full::load(k.base, k.pitch, t0, 0, L, tid);
+                r.gate = Full::load(g.base, g.pitch, t0, 0, L, tid);
             }
             return r;
         };
         // rows past the sequence are zero (a gate of 1 there is harmless: an ascending sweep visits
         // nothing after them, a descending sweep meets them first, with a zero matrix)
         auto stash = [&](const TileRegs &r, int n) {
-            const bool in = st_tt < n;
             if (kRowsRole) {
-                s_own[st_tt][st_c] = in ? r.own : 0.f;
-                s_alpha[st_tt][st_c] = in ? __expf(r.gate_own) : 1.f;
+                Own::template put<false>(s_own, r.own, n, 1.f, 0.f, tid);
+                Own::template put<true>(s_alpha, r.gate_own, n, 1.f, 1.f, tid);
                 if (ROLE == kRoleDk) {
-                    s_k[st_tt][st_c] = in ? r.k : 0.f;
-                    s_dq[st_tt][st_c] = in ? r.dq : 0.f;
+                    Own::template put<false>(s_k, r.k, n, 1.f, 0.f, tid);
+                    OwnF::template put<false>(s_dq, r.dq, n, 1.f, 0.f, tid);
                 }
             } else {
-                s_own[st_tt][st_c] = in ? 0.5f * r.own : 0.f;  // do of the block's columns
+                Own::template put<false>(s_own, r.own, n, 0.5f, 0.f, tid);  // do of the block's columns
             }
-            if (sweep == 1) s_first[st_tt][st_c] = r.first;
-#pragma unroll
-            for (int u = 0; u < kPer; ++u) {
-                const int e = tid + u * kThreads, t2 = e / D_SPLIT, c2 = e % D_SPLIT;
-                const bool in2 = t2 < n;
-                if (ROLE == kRoleDq) {
-                    s_a[t2][c2] = in2 ? r.a[u] : 0.f;
-                    s_b[t2][c2] = in2 ? 0.5f * r.b[u] : 0.f;
-                } else if (ROLE == kRoleDk) {
-                    s_a[t2][c2] = in2 ? 0.5f * r.a[u] : 0.f;
-                    s_b[t2][c2] = in2 ? r.b[u] : 0.f;
-                } else {
-                    s_a[t2][c2] = in2 ? r.a[u] : 0.f;
-                    s_b[t2][c2] = in2 ? r.b[u] : 0.f;
-                    s_gate[t2][c2] = in2 ? __expf(r.gate[u]) : 1.f;
-                }
+            if (sweep == 1) OwnF::template put<false>(s_first, r.first, n, 1.f, 0.f, tid);
+            if (ROLE == kRoleDq) {
+                Full::template put<false>(s_a, r.a, n, 1.f, 0.f, tid);
+                Full::template put<false>(s_b, r.b, n, 0.5f, 0.f, tid);
+            } else if (ROLE == kRoleDk) {
+                Full::template put<false>(s_a, r.a, n, 0.5f, 0.f, tid);
+                Full::template put<false>(s_b, r.b, n, 1.f, 0.f, tid);
+            } else {
+                Full::template put<false>(s_a, r.a, n, 1.f, 0.f, tid);
+                Full::template put<false>(s_b, r.b, n, 1.f, 0.f, tid);
+                Full::template put<true>(s_gate, r.gate, n, 1.f, 1.f, tid);
             }
         };
 
