@@ -72,6 +72,33 @@ def test_bigla_ragged_lengths(dtype, dk, dv):
         assert_close(run_bigla_gpu(s, dtype), run_bigla_oracle(s, dtype), TOL[dtype], f"L={L}")
 
 
+@pytest.mark.parametrize("B,H,L,dk,layout", [
+    (8, 1, 1000, 64, "bhld"),    # 8 slabs, 16 one-chunk segments each: the longest fold, slabs pinned to XCDs
+    (2, 4, 700, 64, "blhd"),     # 8 slabs again, token-major, ragged last segment
+    (3, 3, 700, 64, "bhld"),     # 9 slabs: the plain (slab, segment) order
+    (16, 1, 330, 32, "bhld"),    # 16 slabs, 32-wide keys (only two waves own state rows)
+    (1, 1, 4096, 64, "bhld"),    # a single slab cut into 64 segments
+    (5, 8, 130, 64, "blhd"),     # 40 slabs, three chunks in two or three segments
+])
+def test_bigla_segment_plans(B, H, L, dk, layout):
+    """Plans with several segments per slab: the output pass folds the other segments' end states
+    itself, and the workgroup -> (slab, segment) assignment depends on the slab count."""
+    w = wl.Workload("plan", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=64, dtype="bf16", gate_mu=1.0)
+    _say(f"bigla plan {w} {layout}")
+    s = wl.generate(w, seed=B * 100 + H, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+    ref = run_bigla_oracle(s, "bf16")
+    if layout == "bhld":
+        got = run_bigla_gpu(s, "bf16")
+    else:
+        import torch
+        from paper_2405_18425_amd import binding as vb
+        t = {n: wl.to_torch(s[n], "bf16", "cuda:0").transpose(1, 2).contiguous() for n in s}
+        out = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], layout="blhd")
+        torch.cuda.synchronize()
+        got = wl.widen(wl.from_torch(out.transpose(1, 2).contiguous(), "bf16"), "bf16")
+    assert_close(got, ref, TOL["bf16"], "segment plan")
+
+
 @pytest.mark.parametrize("dtype,dk", (("bf16", 64), ("f32", 64), ("bf16", 32)))
 @pytest.mark.parametrize("gate", ("zero", "minus4", "minus40", "mixed_spikes", "tiny"))
 def test_bigla_adversarial_gates(dtype, dk, gate):
