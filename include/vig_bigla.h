@@ -120,6 +120,11 @@ int bigla_bwd(const void *q, const void *k, const void *v, const void *g_fwd, co
               const void *d_out, void *dq, void *dk, void *dv, void *dg_fwd, void *dg_bwd, int B, int H,
               int L, int dk_, int dv_, int dtype, int layout, void *workspace, size_t workspace_bytes,
               void *stream);
+typedef enum { VIG_BWD_AUTO = 0, VIG_BWD_RECURRENT = 1 } vig_bwd_plan;
+int bigla_bwd_plan(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                   const void *d_out, void *dq, void *dk, void *dv, void *dg_fwd, void *dg_bwd, int B, int H,
+                   int L, int dk_, int dv_, int dtype, int layout, int plan, void *workspace,
+                   size_t workspace_bytes, void *stream);
 
 /*
  * 2D gating locality injection forward -- Section 4.2.2.  Token t of the flattened

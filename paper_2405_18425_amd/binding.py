@@ -26,7 +26,7 @@ PLANS = {"auto": 0, "two_launches": 1, "fused_epilogue": 2}
 # every symbol include/vig_bigla.h declares
 EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "locality_gate_fwd",
            "locality_gate_fwd_layout", "bigla_locality_workspace_bytes", "bigla_locality_fwd", "gate_producer_fwd",
-           "bigla_bwd_workspace_bytes", "bigla_bwd",
+           "bigla_bwd_workspace_bytes", "bigla_bwd", "bigla_bwd_plan",
            "vig_status_str", "vig_last_hip_error", "vig_timing_enable",
            "vig_timing_collect")
 KERNELS = {"segment_state": 0, "segment_out": 2, "recurrent": 3, "locality_gate": 4,
@@ -68,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.bigla_bwd_workspace_bytes.restype = sz
         L.bigla_bwd.argtypes = [vp] * 11 + [ci] * 7 + [vp, sz, vp]
         L.bigla_bwd.restype = ci
+        L.bigla_bwd_plan.argtypes = [vp] * 11 + [ci] * 8 + [vp, sz, vp]
+        L.bigla_bwd_plan.restype = ci
         L.gate_producer_fwd.argtypes = [vp] * 6 + [ci] * 5 + [ctypes.c_float, ci, ci, vp]
         L.gate_producer_fwd.restype = ci
         L.vig_status_str.argtypes = [ci]
@@ -258,9 +260,15 @@ def bigla_locality_fwd(q, k, v, g_fwd, g_bwd, x, w, gate_logits, Hg: int, Wg: in
     return out
 
 
-def bigla_bwd(q, k, v, g_fwd, g_bwd, d_out, workspace=None, layout="bhld"):
+BWD_PLANS = {"auto": 0, "recurrent": 1}
+
+
+def bigla_bwd(q, k, v, g_fwd, g_bwd, d_out, workspace=None, layout="bhld", plan="auto"):
     """Gradient of bigla_fwd (Section 4.2.1): returns (dq, dk, dv, dg_fwd, dg_bwd) for the output
-    gradient d_out (shaped like v); tensors as for bigla_fwd."""
+    gradient d_out (shaped like v); tensors as for bigla_fwd.  plan: "auto" (bigla_bwd) or
+    "recurrent" (bigla_bwd_plan with VIG_BWD_RECURRENT: the exact token-by-token kernels only)."""
+    if plan not in BWD_PLANS:
+        raise VigError(VIG_ERR_UNSUPPORTED, f"unknown plan {plan!r}")
     lay = _layout_code(layout)
     q = _dev(q, "q")
     if q.dim() != 4:
@@ -286,10 +294,13 @@ def bigla_bwd(q, k, v, g_fwd, g_bwd, d_out, workspace=None, layout="bhld"):
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     with torch.cuda.device(q.device):
-        st = lib().bigla_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), g_fwd.data_ptr(), g_bwd.data_ptr(),
-                             d_out.data_ptr(), dq.data_ptr(), dk_.data_ptr(), dv_.data_ptr(), dgf.data_ptr(),
-                             dgb.data_ptr(), B, H, L, dk, dv, code, lay, workspace.data_ptr(),
-                             workspace.numel() * workspace.element_size(), _stream_ptr(q.device))
+        args = (q.data_ptr(), k.data_ptr(), v.data_ptr(), g_fwd.data_ptr(), g_bwd.data_ptr(), d_out.data_ptr(),
+                dq.data_ptr(), dk_.data_ptr(), dv_.data_ptr(), dgf.data_ptr(), dgb.data_ptr(), B, H, L, dk, dv, code, lay)
+        tail = (workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(q.device))
+        if plan == "auto":
+            st = lib().bigla_bwd(*args, *tail)
+        else:
+            st = lib().bigla_bwd_plan(*args, BWD_PLANS[plan], *tail)
     _check(st, "bigla_bwd")
     return dq, dk_, dv_, dgf, dgb
 

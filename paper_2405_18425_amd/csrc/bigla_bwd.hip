@@ -132,7 +132,8 @@ __device__ __forceinline__ void bwd_block(
     const T *__restrict__ gf_all, const T *__restrict__ gb_all, const T *__restrict__ do_all, T *__restrict__ dq_all,
     T *__restrict__ dk_all, T *__restrict__ dv_all, T *__restrict__ dgf_all, T *__restrict__ dgb_all,
     float *__restrict__ ws_dq /* [2][slabs][L][DK]: dq^f, dq^b */, float *__restrict__ ws_part /* [slabs][L][D]: first sweep */,
-    int L, int heads_token_major /* 0: [B,H,L,d]; H: [B,L,H,d] */, long n_slabs, long block)
+    int L, int heads_token_major /* 0: [B,H,L,d]; H: [B,L,H,d] */, long n_slabs, long block,
+    const int *__restrict__ only_marked /* null: every slab; else only slabs whose entry is non-zero */)
 {
     constexpr bool kRowsRole = ROLE != kRoleDv;     // the workgroup owns rows (channels) of the matrix
     constexpr int D_OWN = kRowsRole ? DK : DV;      // the dimension the workgroup's block lies in
@@ -143,6 +144,7 @@ __device__ __forceinline__ void bwd_block(
 
     const int tid = threadIdx.x, own = tid / kShare, s = tid % kShare;
     const long slab = block / kParts;
+    if (only_marked && only_marked[slab] == 0) return;  // the chunkwise kernels have taken this slab
     const int i0 = int(block % kParts) * kBlock;  // first row (column) of the block
     const int idx = i0 + own;                          // this thread's row (column)
     const int e0 = s * E;                              // its first element along the shared dimension
@@ -332,15 +334,16 @@ template <typename T, int DK, int DV>
 __global__ __launch_bounds__(kThreads) void bigla_bwd_dq_dv_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, const T *__restrict__ gf,
     const T *__restrict__ gb, const T *__restrict__ d_out, T *__restrict__ dq, T *__restrict__ dv,
-    float *__restrict__ ws_dq, float *__restrict__ ws_dv, int L, int heads_token_major, long n_slabs)
+    float *__restrict__ ws_dq, float *__restrict__ ws_dv, int L, int heads_token_major, long n_slabs,
+    const int *__restrict__ only_marked)
 {
     const long dq_blocks = n_slabs * (DK / kBlock);
     if (long(blockIdx.x) < dq_blocks)
         bwd_block<T, DK, DV, kRoleDq>(q, k, v, gf, gb, d_out, dq, nullptr, nullptr, nullptr, nullptr, ws_dq, nullptr, L,
-                                      heads_token_major, n_slabs, blockIdx.x);
+                                      heads_token_major, n_slabs, blockIdx.x, only_marked);
     else
         bwd_block<T, DK, DV, kRoleDv>(q, k, v, gf, gb, d_out, nullptr, nullptr, dv, nullptr, nullptr, ws_dq, ws_dv, L,
-                                      heads_token_major, n_slabs, long(blockIdx.x) - dq_blocks);
+                                      heads_token_major, n_slabs, long(blockIdx.x) - dq_blocks, only_marked);
 }
 
 // dk and both gate gradients (reads dq^f, dq^b from the workspace)
@@ -349,16 +352,16 @@ __global__ __launch_bounds__(kThreads) void bigla_bwd_dk_dg_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, const T *__restrict__ gf,
     const T *__restrict__ gb, const T *__restrict__ d_out, T *__restrict__ dk, T *__restrict__ dgf,
     T *__restrict__ dgb, float *__restrict__ ws_dq, float *__restrict__ ws_dk, int L, int heads_token_major,
-    long n_slabs)
+    long n_slabs, const int *__restrict__ only_marked)
 {
     bwd_block<T, DK, DV, kRoleDk>(q, k, v, gf, gb, d_out, nullptr, dk, nullptr, dgf, dgb, ws_dq, ws_dk, L,
-                                  heads_token_major, n_slabs, blockIdx.x);
+                                  heads_token_major, n_slabs, blockIdx.x, only_marked);
 }
 
 template <typename T, int DK, int DV>
 hipError_t launch(const void *q, const void *k, const void *v, const void *gf, const void *gb, const void *d_out,
                   void *dq, void *dk, void *dv, void *dgf, void *dgb, long BH, int L, int heads_token_major,
-                  float *ws, hipStream_t stream)
+                  float *ws, const int *only_marked, hipStream_t stream)
 {
     float *ws_dq = ws;                                // dq^f, dq^b
     float *ws_dk = ws + size_t(2) * BH * L * DK;      // dk of the first sweep
@@ -367,25 +370,24 @@ hipError_t launch(const void *q, const void *k, const void *v, const void *gf, c
     if (dq_blocks + dv_blocks > 0x7fffffffL) return hipErrorInvalidValue;
     const T *qq = static_cast<const T *>(q), *kk = static_cast<const T *>(k), *vv = static_cast<const T *>(v);
     const T *f = static_cast<const T *>(gf), *b = static_cast<const T *>(gb), *dd = static_cast<const T *>(d_out);
-    LaunchTimer timer(kKernelBackward, stream);
     hipLaunchKernelGGL((bigla_bwd_dq_dv_kernel<T, DK, DV>), dim3((unsigned)(dq_blocks + dv_blocks)), dim3(kThreads), 0,
                        stream, qq, kk, vv, f, b, dd, static_cast<T *>(dq), static_cast<T *>(dv), ws_dq, ws_dv, L,
-                       heads_token_major, BH);
+                       heads_token_major, BH, only_marked);
     hipLaunchKernelGGL((bigla_bwd_dk_dg_kernel<T, DK, DV>), dim3((unsigned)dq_blocks), dim3(kThreads), 0, stream, qq, kk,
                        vv, f, b, dd, static_cast<T *>(dk), static_cast<T *>(dgf), static_cast<T *>(dgb), ws_dq, ws_dk, L,
-                       heads_token_major, BH);
+                       heads_token_major, BH, only_marked);
     return hipGetLastError();
 }
 
 template <typename T, int DK>
 hipError_t launch_dv(int dv_, const void *q, const void *k, const void *v, const void *gf, const void *gb,
                      const void *d_out, void *dq, void *dk, void *dv, void *dgf, void *dgb, long BH, int L,
-                     int heads_token_major, float *ws, hipStream_t stream)
+                     int heads_token_major, float *ws, const int *only_marked, hipStream_t stream)
 {
     switch (dv_) {
-        case 16: return launch<T, DK, 16>(q, k, v, gf, gb, d_out, dq, dk, dv, dgf, dgb, BH, L, heads_token_major, ws, stream);
-        case 32: return launch<T, DK, 32>(q, k, v, gf, gb, d_out, dq, dk, dv, dgf, dgb, BH, L, heads_token_major, ws, stream);
-        case 64: return launch<T, DK, 64>(q, k, v, gf, gb, d_out, dq, dk, dv, dgf, dgb, BH, L, heads_token_major, ws, stream);
+        case 16: return launch<T, DK, 16>(q, k, v, gf, gb, d_out, dq, dk, dv, dgf, dgb, BH, L, heads_token_major, ws, only_marked, stream);
+        case 32: return launch<T, DK, 32>(q, k, v, gf, gb, d_out, dq, dk, dv, dgf, dgb, BH, L, heads_token_major, ws, only_marked, stream);
+        case 64: return launch<T, DK, 64>(q, k, v, gf, gb, d_out, dq, dk, dv, dgf, dgb, BH, L, heads_token_major, ws, only_marked, stream);
     }
     return hipErrorInvalidValue;
 }
@@ -393,33 +395,48 @@ hipError_t launch_dv(int dv_, const void *q, const void *k, const void *v, const
 template <typename T>
 hipError_t launch_dk(int dk_, int dv_, const void *q, const void *k, const void *v, const void *gf, const void *gb,
                      const void *d_out, void *dq, void *dk, void *dv, void *dgf, void *dgb, long BH, int L,
-                     int heads_token_major, float *ws, hipStream_t stream)
+                     int heads_token_major, float *ws, const int *only_marked, hipStream_t stream)
 {
     switch (dk_) {
-        case 16: return launch_dv<T, 16>(dv_, q, k, v, gf, gb, d_out, dq, dk, dv, dgf, dgb, BH, L, heads_token_major, ws, stream);
-        case 32: return launch_dv<T, 32>(dv_, q, k, v, gf, gb, d_out, dq, dk, dv, dgf, dgb, BH, L, heads_token_major, ws, stream);
-        case 64: return launch_dv<T, 64>(dv_, q, k, v, gf, gb, d_out, dq, dk, dv, dgf, dgb, BH, L, heads_token_major, ws, stream);
+        case 16: return launch_dv<T, 16>(dv_, q, k, v, gf, gb, d_out, dq, dk, dv, dgf, dgb, BH, L, heads_token_major, ws, only_marked, stream);
+        case 32: return launch_dv<T, 32>(dv_, q, k, v, gf, gb, d_out, dq, dk, dv, dgf, dgb, BH, L, heads_token_major, ws, only_marked, stream);
+        case 64: return launch_dv<T, 64>(dv_, q, k, v, gf, gb, d_out, dq, dk, dv, dgf, dgb, BH, L, heads_token_major, ws, only_marked, stream);
     }
     return hipErrorInvalidValue;
 }
 
 }  // namespace
 
-size_t bigla_bwd_workspace_bytes(long BH, int L, int dk, int dv)
+size_t bigla_bwd_workspace_bytes(long BH, int L, int dk, int dv, bool is_bf16)
 {
-    return size_t(BH) * L * (size_t(3) * dk + dv) * sizeof(float);
+    const size_t exact = size_t(BH) * L * (size_t(3) * dk + dv) * sizeof(float);
+    return exact + (bigla_bwd_chunk_supported(dk, dv, is_bf16) ? bigla_bwd_chunk_workspace_bytes(BH, L) : 0);
 }
 
 hipError_t bigla_bwd_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
                             const void *d_out, void *dq, void *dk, void *dv, void *dg_fwd, void *dg_bwd, long BH, int L,
-                            int dk_, int dv_, bool is_bf16, int heads_token_major, void *workspace, hipStream_t stream)
+                            int dk_, int dv_, bool is_bf16, int heads_token_major, bool recurrent_only, void *workspace,
+                            hipStream_t stream)
 {
-    float *ws = static_cast<float *>(workspace);
+    LaunchTimer timer(kKernelBackward, stream);
+    char *base = static_cast<char *>(workspace);
+    const int *only_marked = nullptr;
+    if (bigla_bwd_chunk_supported(dk_, dv_, is_bf16)) {
+        // the chunkwise kernels take every slab whose gates they can carry and mark the others
+        if (!recurrent_only) {
+            const hipError_t e = bigla_bwd_chunk_launch(q, k, v, g_fwd, g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, BH, L,
+                                                        heads_token_major, base, stream);
+            if (e != hipSuccess) return e;
+            only_marked = bigla_bwd_chunk_marks(base, BH, L);
+        }
+        base += bigla_bwd_chunk_workspace_bytes(BH, L);
+    }
+    float *ws = reinterpret_cast<float *>(base);
     if (is_bf16)
         return launch_dk<bf16_t>(dk_, dv_, q, k, v, g_fwd, g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, BH, L,
-                                 heads_token_major, ws, stream);
+                                 heads_token_major, ws, only_marked, stream);
     return launch_dk<float>(dk_, dv_, q, k, v, g_fwd, g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, BH, L,
-                            heads_token_major, ws, stream);
+                            heads_token_major, ws, only_marked, stream);
 }
 
 }  // namespace vig

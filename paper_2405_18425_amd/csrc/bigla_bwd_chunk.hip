@@ -1,0 +1,668 @@
+// Chunkwise bf16 MFMA evaluation of the gradient of the BiGLA token mixer (Section 4.2.1,
+// Eq. (BiGLA); the paper trains through it, Section 5, and prints no gradient formulas) for
+// dk = dv = 64 in bf16: the counterpart of the chunkwise forward kernels.
+//
+// One direction, forward (the backward one is its mirror image: suffix sums, keys to the right).
+// Inside a chunk of 64 tokens let b_t be the inclusive cumulative log-gate since the chunk's left
+// edge, E+ = exp(b), E- = exp(-b), q~ = q * E+, k~ = k * E-, do' = d_out / 2.  With
+//   S_in : the state entering the chunk (after the previous chunk's last token), [dk][dv]
+//   A'   : diag(exp(b_end)) times the adjoint of the chunk's end state due to all later chunks
+// the regrouped chain rule is, with the masks s <= t,
+//   P  = mask(q~ k~^T)             dP = mask(do' v^T)                          [t][s]
+//   X  = dP k~ + do' S_in^T        dq = E+ * X
+//   Yi = dP^T q~   Ye = v A'^T     dk = E- * (Yi + Ye)
+//   dv = P^T do' + k~ A'
+//   dg_u = sum_{t >= u} (q~ * X - k~ * Yi)_t + sum_{t < u} (k~ * Ye)_t + rowsum(S_in * A')
+// (the three parts of dg are the token pairs (s, t), s < u <= t, that straddle u: both inside the
+// chunk or s before it; s inside and t after it; s before and t after).  Every sum of dg runs over
+// at most one chunk, so no long-range cancellation enters it; its two prefix/suffix sums are
+// products with 0/1 triangles on the matrix cores, the summands split into two bf16 halves.
+// States come from two small launches before the main one:
+//   1. bigla_bwd_chunk_local_kernel (workgroup per chunk): the chunk's own contributions
+//      U = (k * exp(b_end - b))^T v and W = q~^T do' for both directions, and the chunk totals of
+//      the log-gates;
+//   2. bigla_bwd_chunk_scan_kernel (elementwise over the 64x64 matrices, sequential over the
+//      chunks of a slab): S_in(c+1) = d_c S_in(c) + U_c and A'_c = d_c (W_{c+1} + A'_{c+1}), in
+//      place, fp32 running values, bf16 storage; it also marks the slabs in which some chunk's
+//      total log-decay exceeds 60 nats in some channel;
+//   3. bigla_bwd_chunk_main_kernel (workgroup per chunk): everything above for both directions,
+//      dq, dk, dv accumulated in registers and written once.
+// exp(-b) grows with the decay accumulated over a chunk, so marked slabs are left to the exact
+// token-by-token kernels (which skip every other slab); gates of the paper's form,
+// sigmoid(z)^(1/16), reach 60 nats in 64 steps only for z < -15 throughout.
+//
+// Wavefront mapping (256 threads = 4 waves): wave w owns tokens 16w..16w+15 of the chunk; results
+// are produced transposed, so that lane (r = lane%16, g = lane/16) holds, for token 16w + r,
+// channels 16ct + 4g + e (ct, e = 0..3) -- four 8-byte pieces of the token's row.  All tiles are
+// row-major bf16 in LDS; an operand whose contraction index runs along the tile's rows is read
+// with ds_read_b64_tr_b16.  Tokens past the sequence are read as zeros (q = k = v = do = 0,
+// log-gate 0: a no-op) and their stores are dropped, both by the bounds check of the buffer
+// resource that spans the slab.
+#include "vig_common.hpp"
+#include "vig_kernels.hpp"
+#include "vig_timing.hpp"
+
+namespace vig {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kC = 64;       // chunk length (tokens)
+constexpr int kD = 64;       // dk = dv
+constexpr int kPitch = 72;   // LDS row pitch in bf16 elements
+constexpr int kThreads = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kFastRange = 60.0f;  // largest chunk log-decay (nats, any channel) this path accepts
+constexpr size_t kMat = size_t(kD) * kD;  // elements of one state matrix
+
+typedef uint16_t Tile[kC][kPitch];
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi)
+{
+    f32x2 a = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2));
+}
+__device__ __forceinline__ uint2 pack4(const f32x4 &p) { return make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3])); }
+
+__device__ __forceinline__ f32x4 unpack4(const uint2 &u)
+{
+    return f32x4{bf16_lo_to_f32(u.x), bf16_hi_to_f32(u.x), bf16_lo_to_f32(u.y), bf16_hi_to_f32(u.y)};
+}
+
+__device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// Transposing LDS read: the 16 lanes of a row fetch a 4 (rows) x 16 (columns) bf16 patch of a
+// row-major tile; lane n of the row receives the 4 rows of column n and supplies the address of
+// row n/4, columns 4*(n%4).. of the patch.
+__device__ __forceinline__ s16x4 lds_read_tr(const uint16_t *p)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
+}
+
+__device__ __forceinline__ bf16x8 join(s16x4 lo, s16x4 hi)
+{
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// MFMA operand whose 16 rows (A) or columns (B) are tile rows row0..row0+15 and whose contraction
+// index runs along the tile's columns: k-slot j of K-step kk is column 32kk + 8g + j.
+__device__ __forceinline__ bf16x8 row_frag(const Tile &tile, int row0, int kk, int r, int g)
+{
+    return *reinterpret_cast<const bf16x8 *>(&tile[row0 + r][32 * kk + 8 * g]);
+}
+
+// MFMA operand whose 16 rows (A) or columns (B) are tile columns col0..col0+15 and whose contraction
+// index runs along the tile's rows: k-slot j of K-step kk is row 32kk + 8g + j.
+__device__ __forceinline__ bf16x8 col_frag(const Tile &tile, int col0, int kk, int r, int g)
+{
+    const int row = 32 * kk + 8 * g + (r >> 2), col = col0 + 4 * (r & 3);
+    return join(lds_read_tr(&tile[row][col]), lds_read_tr(&tile[row + 4][col]));
+}
+
+// B operand of a contraction over the chunk's tokens with a 0/1 triangle: k-slot j of K-step kk is
+// token s = 32kk + 8g + j, the lane's column is token u; 1 where s REL u holds.
+enum Rel { kLe = 0, kGe = 1, kLt = 2, kGt = 3 };
+template <int REL>
+__device__ __forceinline__ bf16x8 tri_frag(int kk, int g, int u)
+{
+    uint32_t word[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+        uint32_t bits = 0;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int s = 32 * kk + 8 * g + 2 * jj + half;
+            const bool one = REL == kLe ? s <= u : REL == kGe ? s >= u : REL == kLt ? s < u : s > u;
+            bits |= (one ? 0x3F80u : 0u) << (16 * half);
+        }
+        word[jj] = bits;
+    }
+    return __builtin_bit_cast(bf16x8, make_uint4(word[0], word[1], word[2], word[3]));
+}
+
+// One slab's rows of a [.., 64] bf16 tensor behind a buffer resource that ends with the slab's last
+// token (loads beyond it return zeros, stores beyond it are dropped).
+struct SlabRows {
+    __amdgpu_buffer_rsrc_t rsrc;
+    unsigned pitch;  // bytes between consecutive tokens
+};
+
+__device__ __forceinline__ SlabRows slab_rows(const void *base, long slab, int L, int heads_token_major)
+{
+    const size_t first = heads_token_major
+                             ? size_t(slab / heads_token_major) * size_t(L) * heads_token_major + slab % heads_token_major
+                             : size_t(slab) * L;
+    const unsigned pitch = 2u * kD * unsigned(heads_token_major ? heads_token_major : 1);
+    const unsigned extent = unsigned(L - 1) * pitch + 2u * kD;
+    const uintptr_t a = reinterpret_cast<uintptr_t>(static_cast<const char *>(base) + first * (2 * kD));
+    // (readfirstlane returns a signed int: widen through unsigned, not by sign extension)
+    const uintptr_t lo = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a))));
+    const uintptr_t hi = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a >> 32))));
+    SlabRows s;
+    s.rsrc = __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(lo | (hi << 32)), 0,
+                                               int(unsigned(__builtin_amdgcn_readfirstlane(int(extent)))),
+                                               0x00020000);
+    s.pitch = pitch;
+    return s;
+}
+
+// Whole rows of a chunk into a tile: lane i of wave w takes 16-byte piece i%8 of rows 16w + i/8 and
+// 16w + 8 + i/8.  kHalf: the values are halved on the way (exact in bf16).
+template <bool kHalf>
+__device__ __forceinline__ void stage_rows(Tile &tile, const SlabRows &rows, unsigned t0, int w, int lane)
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int row = 16 * w + 8 * h + (lane >> 3);
+        u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rows.rsrc, (t0 + row) * rows.pitch + 16u * (lane & 7), 0, 0);
+        if (kHalf) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = pack2(0.5f * bf16_lo_to_f32(x[i]), 0.5f * bf16_hi_to_f32(x[i]));
+        }
+        *reinterpret_cast<uint4 *>(&tile[row][8 * (lane & 7)]) = make_uint4(x[0], x[1], x[2], x[3]);
+    }
+}
+
+// Orders this wave's earlier LDS writes before its later LDS reads of what other lanes of the
+// same wave wrote (the LDS executes one wave's accesses in order; this keeps the compiler from
+// moving them across each other).
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// The lane's own four pieces of a token row (channels 16ct + 4g .. + 3 of token 16w + r) out of
+// rows the wave has staged itself: rows 16w..16w+15 of a tile belong to wave w alone.
+__device__ __forceinline__ void take_own(const Tile &tile, int w, int r, int g, uint2 (&x)[4])
+{
+    wave_lds_fence();
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) x[ct] = *reinterpret_cast<const uint2 *>(&tile[16 * w + r][16 * ct + 4 * g]);
+}
+
+// The wave's 16 result rows, held as the lanes' own pieces, to global memory as whole rows: through
+// the wave's rows of a tile that nobody reads at that point, then 16 bytes per lane, 8 lanes a row.
+__device__ __forceinline__ void store_own(Tile &tile, const SlabRows &rows, unsigned t0, int w, int lane, int r, int g,
+                                          const f32x4 (&x)[4])
+{
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) *reinterpret_cast<uint2 *>(&tile[16 * w + r][16 * ct + 4 * g]) = pack4(x[ct]);
+    wave_lds_fence();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int row = 16 * w + 8 * h + (lane >> 3);
+        const uint4 v = *reinterpret_cast<const uint4 *>(&tile[row][8 * (lane & 7)]);
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{v.x, v.y, v.z, v.w}, rows.rsrc,
+                                               (t0 + row) * rows.pitch + 16u * (lane & 7), 0, 0);
+    }
+    wave_lds_fence();  // the rows may be reused by this wave right away
+}
+
+// the lane's piece of tile row 16w + r
+__device__ __forceinline__ void put_own(Tile &tile, int w, int r, int g, int ct, const f32x4 &x)
+{
+    *reinterpret_cast<uint2 *>(&tile[16 * w + r][16 * ct + 4 * g]) = pack4(x);
+}
+
+// Inclusive cumulative log-gates of the chunk on the matrix cores (a product with a 0/1 triangle is
+// exact in bf16 x bf16 -> fp32): b[ct][e] for the lane's token and channel 16ct + 4g + e, prefix
+// sums for DIR 0, suffix sums for DIR 1.
+template <int DIR>
+__device__ __forceinline__ void gate_scan(const Tile &gates, int w, int r, int g, f32x4 (&b)[4])
+{
+    const bf16x8 t0 = tri_frag<DIR == 0 ? kLe : kGe>(0, g, 16 * w + r);
+    const bf16x8 t1 = tri_frag<DIR == 0 ? kLe : kGe>(1, g, 16 * w + r);
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        b[ct] = mfma(col_frag(gates, 16 * ct, 1, r, g), t1, mfma(col_frag(gates, 16 * ct, 0, r, g), t0, zero));
+    }
+}
+
+// ---- workspace ---------------------------------------------------------------------------------
+// [states][log-decays][slab marks]
+//   states, per (slab, chunk): four bf16 64x64 matrices, row-major [key channel][value column]:
+//     0: forward  state entering the chunk from the left      (pass 1 leaves U there)
+//     1: forward  A' of the chunk (decayed adjoint from the right)     (pass 1: W)
+//     2: backward state entering the chunk from the right
+//     3: backward A' of the chunk (decayed adjoint from the left)
+//   log-decays, per (slab, chunk, direction): the chunk's total log-gate per channel, fp32
+//   slab marks: one int per slab, non-zero when the slab is left to the exact kernels
+struct Workspace {
+    uint16_t *states;
+    float *logdec;
+    int *marks;
+};
+
+inline size_t align256(size_t n) { return (n + 255) / 256 * 256; }
+
+inline int chunks_of(int L) { return (L + kC - 1) / kC; }
+
+inline size_t states_bytes(long BH, int L) { return align256(size_t(BH) * chunks_of(L) * 4 * kMat * sizeof(uint16_t)); }
+inline size_t logdec_bytes(long BH, int L) { return align256(size_t(BH) * chunks_of(L) * 2 * kD * sizeof(float)); }
+inline size_t marks_bytes(long BH) { return align256(size_t(BH) * sizeof(int)); }
+
+struct LocalLds {
+    Tile v, dout, gates, qt, kh;
+};
+
+// ---- pass 1: the chunk's own contributions to the states ----------------------------------------
+__global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_local_kernel(
+    const void *__restrict__ q_all, const void *__restrict__ k_all, const void *__restrict__ v_all,
+    const void *__restrict__ gf_all, const void *__restrict__ gb_all, const void *__restrict__ do_all,
+    uint16_t *__restrict__ states, float *__restrict__ logdec, int L, int heads_token_major, int n_chunks)
+{
+    __shared__ __align__(16) LocalLds sm;
+    const long unit = blockIdx.x;
+    const long slab = unit / n_chunks;
+    const int chunk = int(unit % n_chunks);
+    const unsigned t0 = unsigned(chunk) * kC;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+
+    const SlabRows q = slab_rows(q_all, slab, L, heads_token_major), k = slab_rows(k_all, slab, L, heads_token_major);
+    const SlabRows v = slab_rows(v_all, slab, L, heads_token_major), dout = slab_rows(do_all, slab, L, heads_token_major);
+    const SlabRows gf = slab_rows(gf_all, slab, L, heads_token_major), gb = slab_rows(gb_all, slab, L, heads_token_major);
+
+    uint2 qr[4], kr[4];
+    stage_rows<false>(sm.qt, q, t0, w, lane);
+    stage_rows<false>(sm.kh, k, t0, w, lane);
+    stage_rows<false>(sm.v, v, t0, w, lane);
+    stage_rows<true>(sm.dout, dout, t0, w, lane);
+    take_own(sm.qt, w, r, g, qr);
+    take_own(sm.kh, w, r, g, kr);
+
+    uint16_t *mats = states + size_t(unit) * 4 * kMat;
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
+
+#pragma unroll
+    for (int dir = 0; dir < 2; ++dir) {
+        if (dir == 1) __syncthreads();  // the first direction's products have read the tiles
+        stage_rows<false>(sm.gates, dir == 0 ? gf : gb, t0, w, lane);
+        __syncthreads();
+        f32x4 b[4], T[4];
+        if (dir == 0)
+            gate_scan<0>(sm.gates, w, r, g, b);
+        else
+            gate_scan<1>(sm.gates, w, r, g, b);
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            T[ct] = mfma(col_frag(sm.gates, 16 * ct, 1, r, g), ones, mfma(col_frag(sm.gates, 16 * ct, 0, r, g), ones, zero));
+            const f32x4 qv = unpack4(qr[ct]), kv = unpack4(kr[ct]);
+            f32x4 qs, ks;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                qs[e] = qv[e] * fast_exp2(b[ct][e] * kLog2e);
+                ks[e] = kv[e] * fast_exp2((T[ct][e] - b[ct][e]) * kLog2e);
+            }
+            put_own(sm.qt, w, r, g, ct, qs);
+            put_own(sm.kh, w, r, g, ct, ks);
+            if (w == 0 && r == 0)
+                *reinterpret_cast<f32x4 *>(&logdec[(size_t(unit) * 2 + dir) * kD + 16 * ct + 4 * g]) = T[ct];
+        }
+        __syncthreads();
+        // U^T[j][i] = sum_t v[t][j] kh[t][i],  W^T[j][i] = sum_t do'[t][j] q~[t][i]: the wave takes rows
+        // i = 16w.., the lane ends up with four consecutive columns j of row 16w + r
+        uint16_t *U = mats + size_t(2 * dir) * kMat, *W = U + kMat;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            f32x4 u = {0.f, 0.f, 0.f, 0.f}, x = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                u = mfma(col_frag(sm.v, 16 * mt, kk, r, g), col_frag(sm.kh, 16 * w, kk, r, g), u);
+                x = mfma(col_frag(sm.dout, 16 * mt, kk, r, g), col_frag(sm.qt, 16 * w, kk, r, g), x);
+            }
+            *reinterpret_cast<uint2 *>(&U[(16 * w + r) * kD + 16 * mt + 4 * g]) = pack4(u);
+            *reinterpret_cast<uint2 *>(&W[(16 * w + r) * kD + 16 * mt + 4 * g]) = pack4(x);
+        }
+    }
+}
+
+// ---- pass 2: the chunk-to-chunk recurrences, elementwise ------------------------------------------
+// grid: 16 workgroups per slab = 4 matrices x 4 quarters; a thread owns 4 consecutive elements of a
+// row and walks the slab's chunks in the matrix's direction, its loads requested kScanAhead chunks
+// ahead (the walk is a chain of dependent fp32 operations, but the addresses are known).
+constexpr int kScanAhead = 8;
+constexpr int kScanParts = 4;
+
+__global__ __launch_bounds__(kThreads) void bigla_bwd_chunk_scan_kernel(uint16_t *__restrict__ states,
+                                                                       const float *__restrict__ logdec,
+                                                                       int *__restrict__ marks, int n_chunks)
+{
+    const long slab = blockIdx.x / (4 * kScanParts);
+    const int kind = (blockIdx.x / kScanParts) & 3, part = blockIdx.x % kScanParts;
+    const int tid = threadIdx.x;
+    const int piece = part * kThreads + tid;  // 0..1023
+    const int row = piece >> 4;
+    const int dir = kind >> 1;
+    const bool adjoint = (kind & 1) != 0;
+    const bool ascending = kind == 0 || kind == 3;
+
+    if (kind == 0 && part == 0) {
+        // mark the slab when some chunk decays by more than the fast form can carry
+        __shared__ float lowest[kThreads];
+        float m = 0.f;
+        const float *ld = logdec + size_t(slab) * n_chunks * 2 * kD;
+        for (long i = tid; i < long(n_chunks) * 2 * kD; i += kThreads) m = fminf(m, ld[i]);
+        lowest[tid] = m;
+        __syncthreads();
+        for (int s = kThreads / 2; s > 0; s >>= 1) {
+            if (tid < s) lowest[tid] = fminf(lowest[tid], lowest[tid + s]);
+            __syncthreads();
+        }
+        // (a NaN gate total compares false and leaves the slab to this path, whose outputs are then NaN too)
+        if (tid == 0) marks[slab] = (-lowest[0] > kFastRange) ? 1 : 0;
+    }
+
+    uint16_t *mat = states + (size_t(slab) * n_chunks * 4 + kind) * kMat + size_t(piece) * 4;
+    const float *ld = logdec + (size_t(slab) * n_chunks * 2 + dir) * kD + row;
+    struct Item {
+        uint2 x;
+        float logd;
+    };
+    auto fetch = [&](int n) {
+        Item it;
+        it.x = make_uint2(0u, 0u);
+        it.logd = 0.f;
+        if (n < n_chunks) {
+            const int c = ascending ? n : n_chunks - 1 - n;
+            it.x = *reinterpret_cast<const uint2 *>(mat + size_t(c) * 4 * kMat);
+            it.logd = ld[size_t(c) * 2 * kD];
+        }
+        return it;
+    };
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    Item ahead[kScanAhead];
+#pragma unroll
+    for (int j = 0; j < kScanAhead; ++j) ahead[j] = fetch(j);
+    for (int n0 = 0; n0 < n_chunks; n0 += kScanAhead) {
+#pragma unroll
+        for (int j = 0; j < kScanAhead; ++j) {
+            const int n = n0 + j;
+            if (n < n_chunks) {
+                const Item cur = ahead[j];
+                ahead[j] = fetch(n + kScanAhead);
+                const int c = ascending ? n : n_chunks - 1 - n;
+                const float d = fast_exp2(cur.logd * kLog2e);
+                const f32x4 u = unpack4(cur.x);
+                f32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (adjoint) {
+                        o[e] = d * s[e];     // A' of this chunk
+                        s[e] = u[e] + o[e];  // adjoint of the previous chunk's end state
+                    } else {
+                        o[e] = s[e];         // state entering this chunk
+                        s[e] = d * s[e] + u[e];
+                    }
+                }
+                *reinterpret_cast<uint2 *>(mat + size_t(c) * 4 * kMat) = pack4(o);
+            }
+        }
+    }
+}
+
+// ---- pass 3: the gradients of one chunk ------------------------------------------------------------
+
+struct MainLds {
+    Tile v;      // values                                   [token][column]
+    Tile dout;   // d_out / 2                                [token][column]
+    Tile gp;     // log-gates, then P; later a half of dg's summands
+    Tile qt;     // q~                                       [token][channel]
+    Tile kt;     // k~
+    Tile dp;     // masked dP                                [t][s]
+    Tile st;     // S_in                                     [channel][column]
+    Tile ad;     // A'
+    float R[kD]; // rowsum(S_in * A') per channel
+};
+
+struct Grads {
+    f32x4 dq[4], dk[4], dv[4];  // token 16w + r, channels / columns 16ct + 4g + e
+};
+
+__device__ __forceinline__ void copy_matrix(Tile &tile, const uint16_t *src, int tid)
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int p = tid + kThreads * h;
+        *reinterpret_cast<uint4 *>(&tile[p >> 3][8 * (p & 7)]) = reinterpret_cast<const uint4 *>(src)[p];
+    }
+}
+
+template <int DIR>
+__device__ __forceinline__ void chunk_direction(MainLds &sm, const SlabRows &gates, const SlabRows &dg_rows,
+                                                const uint16_t *mats, unsigned t0, int tid, int w, int lane, int r,
+                                                int g, const uint2 (&qr)[4], const uint2 (&kr)[4], Grads &acc)
+{
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    if (DIR == 1) __syncthreads();  // the first direction's last products have read the tiles
+    stage_rows<false>(sm.gp, gates, t0, w, lane);
+    copy_matrix(sm.st, mats + size_t(2 * DIR) * kMat, tid);
+    copy_matrix(sm.ad, mats + size_t(2 * DIR + 1) * kMat, tid);
+    __syncthreads();
+
+    // cumulative gates, scaled queries and keys (kept as rounded: the gate gradient below must use
+    // exactly the operands of the contractions, see there)
+    f32x4 Ep[4];
+    {
+        f32x4 b[4];
+        gate_scan<DIR>(sm.gp, w, r, g, b);
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            const f32x4 qv = unpack4(qr[ct]), kv = unpack4(kr[ct]);
+            f32x4 qs, ks;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float x = b[ct][e] * kLog2e;
+                Ep[ct][e] = fast_exp2(x);
+                qs[e] = qv[e] * Ep[ct][e];
+                ks[e] = kv[e] * fast_exp2(-x);
+            }
+            put_own(sm.qt, w, r, g, ct, qs);
+            put_own(sm.kt, w, r, g, ct, ks);
+        }
+    }
+    // rowsum(S_in * A'): four threads per row, 16 columns each
+    {
+        const int row = tid >> 2, c0 = 16 * (tid & 3);
+        float sum = 0.f;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint4 a = *reinterpret_cast<const uint4 *>(&sm.st[row][c0 + 8 * h]);
+            const uint4 b = *reinterpret_cast<const uint4 *>(&sm.ad[row][c0 + 8 * h]);
+            sum += bf16_lo_to_f32(a.x) * bf16_lo_to_f32(b.x) + bf16_hi_to_f32(a.x) * bf16_hi_to_f32(b.x);
+            sum += bf16_lo_to_f32(a.y) * bf16_lo_to_f32(b.y) + bf16_hi_to_f32(a.y) * bf16_hi_to_f32(b.y);
+            sum += bf16_lo_to_f32(a.z) * bf16_lo_to_f32(b.z) + bf16_hi_to_f32(a.z) * bf16_hi_to_f32(b.z);
+            sum += bf16_lo_to_f32(a.w) * bf16_lo_to_f32(b.w) + bf16_hi_to_f32(a.w) * bf16_hi_to_f32(b.w);
+        }
+        sum += __shfl_xor(sum, 1);
+        sum += __shfl_xor(sum, 2);
+        if ((tid & 3) == 0) sm.R[row] = sum;
+    }
+    __syncthreads();  // q~, k~ complete; every wave is done with the gates
+
+    // P^T and dP^T tiles of the wave's queries (keys 16m + 4g + e, query 16w + r), masked, stored [t][s]
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        f32x4 p = zero;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) p = mfma(row_frag(sm.kt, 16 * m, kk, r, g), row_frag(sm.qt, 16 * w, kk, r, g), p);
+        f32x4 d = zero;  // (the same for both directions up to the mask; not kept: registers are scarcer)
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) d = mfma(row_frag(sm.v, 16 * m, kk, r, g), row_frag(sm.dout, 16 * w, kk, r, g), d);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int s = 16 * m + 4 * g + e, t = 16 * w + r;
+            const bool keep = DIR == 0 ? s <= t : s >= t;
+            p[e] = keep ? p[e] : 0.f;
+            d[e] = keep ? d[e] : 0.f;
+        }
+        put_own(sm.gp, w, r, g, m, p);
+        put_own(sm.dp, w, r, g, m, d);
+    }
+    __syncthreads();
+
+    f32x4 E1[4], E2[4];
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+        // X^T[c][t] = sum_s k~[s][c] dP[t][s] + sum_j S_in[c][j] do'[t][j]
+        f32x4 X = zero, Yi = zero, Ye = zero, V = zero;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            X = mfma(col_frag(sm.kt, 16 * ct, kk, r, g), row_frag(sm.dp, 16 * w, kk, r, g), X);
+            X = mfma(row_frag(sm.st, 16 * ct, kk, r, g), row_frag(sm.dout, 16 * w, kk, r, g), X);
+            // Yi^T[c][s] = sum_t q~[t][c] dP[t][s],  Ye^T[c][s] = sum_j A'[c][j] v[s][j]
+            Yi = mfma(col_frag(sm.qt, 16 * ct, kk, r, g), col_frag(sm.dp, 16 * w, kk, r, g), Yi);
+            Ye = mfma(row_frag(sm.ad, 16 * ct, kk, r, g), row_frag(sm.v, 16 * w, kk, r, g), Ye);
+            // dv^T[j][s] = sum_t do'[t][j] P[t][s] + sum_i A'[i][j] k~[s][i]
+            V = mfma(col_frag(sm.dout, 16 * ct, kk, r, g), col_frag(sm.gp, 16 * w, kk, r, g), V);
+            V = mfma(col_frag(sm.ad, 16 * ct, kk, r, g), row_frag(sm.kt, 16 * w, kk, r, g), V);
+        }
+        // The summands of the gate gradient take q~ and k~ as the contractions saw them (rounded to
+        // bf16): sum_{t>=u} q~ * X - sum_{s>=u} k~ * Yi is then, term by term, the sum over the pairs
+        // s < u <= t of q~_t dP_ts k~_s, and the rounding of the operands perturbs each pair once
+        // instead of leaving the difference of two long sums that no longer cancel.
+        const f32x4 qv = unpack4(*reinterpret_cast<const uint2 *>(&sm.qt[16 * w + r][16 * ct + 4 * g]));
+        const f32x4 kv = unpack4(*reinterpret_cast<const uint2 *>(&sm.kt[16 * w + r][16 * ct + 4 * g]));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc.dq[ct][e] += Ep[ct][e] * X[e];
+            acc.dk[ct][e] += __builtin_amdgcn_rcpf(Ep[ct][e]) * (Yi[e] + Ye[e]);
+            acc.dv[ct][e] += V[e];
+            E1[ct][e] = qv[e] * X[e] - kv[e] * Yi[e];
+            E2[ct][e] = kv[e] * Ye[e];
+        }
+    }
+    __syncthreads();  // every wave is done with q~, k~, P and dP: their tiles take dg's summands
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+        f32x4 hi1, lo1, hi2, lo2;
+        const uint2 h1 = pack4(E1[ct]), h2 = pack4(E2[ct]);
+        hi1 = unpack4(h1);
+        hi2 = unpack4(h2);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            lo1[e] = E1[ct][e] - hi1[e];
+            lo2[e] = E2[ct][e] - hi2[e];
+        }
+        *reinterpret_cast<uint2 *>(&sm.qt[16 * w + r][16 * ct + 4 * g]) = h1;
+        put_own(sm.kt, w, r, g, ct, lo1);
+        *reinterpret_cast<uint2 *>(&sm.gp[16 * w + r][16 * ct + 4 * g]) = h2;
+        put_own(sm.dp, w, r, g, ct, lo2);
+    }
+    __syncthreads();
+    // dg^T[c][u] = sum_t E1[t][c] [t >= u] + sum_t E2[t][c] [t < u]   (forward; mirrored backward)
+    {
+        const int u = 16 * w + r;
+        const bf16x8 a0 = tri_frag<DIR == 0 ? kGe : kLe>(0, g, u), a1 = tri_frag<DIR == 0 ? kGe : kLe>(1, g, u);
+        const bf16x8 b0 = tri_frag<DIR == 0 ? kLt : kGt>(0, g, u), b1 = tri_frag<DIR == 0 ? kLt : kGt>(1, g, u);
+        f32x4 dg[4];
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            f32x4 s = *reinterpret_cast<const f32x4 *>(&sm.R[16 * ct + 4 * g]);
+            s = mfma(col_frag(sm.qt, 16 * ct, 0, r, g), a0, s);
+            s = mfma(col_frag(sm.qt, 16 * ct, 1, r, g), a1, s);
+            s = mfma(col_frag(sm.kt, 16 * ct, 0, r, g), a0, s);
+            s = mfma(col_frag(sm.kt, 16 * ct, 1, r, g), a1, s);
+            s = mfma(col_frag(sm.gp, 16 * ct, 0, r, g), b0, s);
+            s = mfma(col_frag(sm.gp, 16 * ct, 1, r, g), b1, s);
+            s = mfma(col_frag(sm.dp, 16 * ct, 0, r, g), b0, s);
+            s = mfma(col_frag(sm.dp, 16 * ct, 1, r, g), b1, s);
+            dg[ct] = s;
+        }
+        store_own(sm.st, dg_rows, t0, w, lane, r, g, dg);  // S_in is not needed any more
+    }
+}
+
+__global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_main_kernel(
+    const void *__restrict__ q_all, const void *__restrict__ k_all, const void *__restrict__ v_all,
+    const void *__restrict__ gf_all, const void *__restrict__ gb_all, const void *__restrict__ do_all,
+    void *__restrict__ dq_all, void *__restrict__ dk_all, void *__restrict__ dv_all, void *__restrict__ dgf_all,
+    void *__restrict__ dgb_all, const uint16_t *__restrict__ states, const int *__restrict__ marks, int L,
+    int heads_token_major, int n_chunks)
+{
+    __shared__ __align__(16) MainLds sm;
+    const long unit = blockIdx.x;
+    const long slab = unit / n_chunks;
+    if (marks[slab] != 0) return;  // left to the exact kernels
+    const int chunk = int(unit % n_chunks);
+    const unsigned t0 = unsigned(chunk) * kC;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+
+    const SlabRows q = slab_rows(q_all, slab, L, heads_token_major), k = slab_rows(k_all, slab, L, heads_token_major);
+    const SlabRows v = slab_rows(v_all, slab, L, heads_token_major), dout = slab_rows(do_all, slab, L, heads_token_major);
+    const SlabRows gf = slab_rows(gf_all, slab, L, heads_token_major), gb = slab_rows(gb_all, slab, L, heads_token_major);
+    const SlabRows dgf = slab_rows(dgf_all, slab, L, heads_token_major), dgb = slab_rows(dgb_all, slab, L, heads_token_major);
+
+    uint2 qr[4], kr[4];
+    stage_rows<false>(sm.qt, q, t0, w, lane);
+    stage_rows<false>(sm.kt, k, t0, w, lane);
+    stage_rows<false>(sm.v, v, t0, w, lane);
+    stage_rows<true>(sm.dout, dout, t0, w, lane);
+    take_own(sm.qt, w, r, g, qr);
+    take_own(sm.kt, w, r, g, kr);
+
+    Grads acc;
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) acc.dq[ct] = acc.dk[ct] = acc.dv[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint16_t *mats = states + size_t(unit) * 4 * kMat;
+    chunk_direction<0>(sm, gf, dgf, mats, t0, tid, w, lane, r, g, qr, kr, acc);
+    chunk_direction<1>(sm, gb, dgb, mats, t0, tid, w, lane, r, g, qr, kr, acc);
+
+    store_own(sm.st, slab_rows(dq_all, slab, L, heads_token_major), t0, w, lane, r, g, acc.dq);
+    store_own(sm.ad, slab_rows(dk_all, slab, L, heads_token_major), t0, w, lane, r, g, acc.dk);
+    store_own(sm.v, slab_rows(dv_all, slab, L, heads_token_major), t0, w, lane, r, g, acc.dv);
+}
+
+}  // namespace
+
+bool bigla_bwd_chunk_supported(int dk, int dv, bool is_bf16) { return is_bf16 && dk == kD && dv == kD; }
+
+size_t bigla_bwd_chunk_workspace_bytes(long BH, int L)
+{
+    return states_bytes(BH, L) + logdec_bytes(BH, L) + marks_bytes(BH);
+}
+
+const int *bigla_bwd_chunk_marks(void *workspace, long BH, int L)
+{
+    return reinterpret_cast<const int *>(static_cast<char *>(workspace) + states_bytes(BH, L) + logdec_bytes(BH, L));
+}
+
+hipError_t bigla_bwd_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                                  const void *d_out, void *dq, void *dk, void *dv, void *dg_fwd, void *dg_bwd, long BH,
+                                  int L, int heads_token_major, void *workspace, hipStream_t stream)
+{
+    const int n_chunks = chunks_of(L);
+    const long units = BH * n_chunks;
+    if (units > 0x7fffffffL || BH * 4 * kScanParts > 0x7fffffffL) return hipErrorInvalidValue;
+    Workspace ws;
+    char *base = static_cast<char *>(workspace);
+    ws.states = reinterpret_cast<uint16_t *>(base);
+    ws.logdec = reinterpret_cast<float *>(base + states_bytes(BH, L));
+    ws.marks = reinterpret_cast<int *>(base + states_bytes(BH, L) + logdec_bytes(BH, L));
+    hipLaunchKernelGGL(bigla_bwd_chunk_local_kernel, dim3((unsigned)units), dim3(kThreads), 0, stream, q, k, v, g_fwd,
+                       g_bwd, d_out, ws.states, ws.logdec, L, heads_token_major, n_chunks);
+    hipLaunchKernelGGL(bigla_bwd_chunk_scan_kernel, dim3((unsigned)(BH * 4 * kScanParts)), dim3(kThreads), 0, stream, ws.states,
+                       ws.logdec, ws.marks, n_chunks);
+    hipLaunchKernelGGL(bigla_bwd_chunk_main_kernel, dim3((unsigned)units), dim3(kThreads), 0, stream, q, k, v, g_fwd,
+                       g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, ws.states, ws.marks, L, heads_token_major, n_chunks);
+    return hipGetLastError();
+}
+
+}  // namespace vig

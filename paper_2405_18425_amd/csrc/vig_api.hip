@@ -101,19 +101,31 @@ size_t bigla_bwd_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype)
     if (B <= 0 || H <= 0 || L <= 0 || !head_dim_ok(dk) || !head_dim_ok(dv)) return 0;
     if (dtype != VIG_F32 && dtype != VIG_BF16) return 0;
     if (!sizes_ok(B, H, L, 3L * dk + dv)) return 0;
-    return vig::bigla_bwd_workspace_bytes(long(B) * H, L, dk, dv);
+    return vig::bigla_bwd_workspace_bytes(long(B) * H, L, dk, dv, dtype == VIG_BF16);
 }
 
 int bigla_bwd(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd, const void *d_out,
               void *dq, void *dk, void *dv, void *dg_fwd, void *dg_bwd, int B, int H, int L, int dk_, int dv_,
               int dtype, int layout, void *workspace, size_t workspace_bytes, void *stream)
 {
+    return bigla_bwd_plan(q, k, v, g_fwd, g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, B, H, L, dk_, dv_, dtype, layout,
+                          VIG_BWD_AUTO, workspace, workspace_bytes, stream);
+}
+
+int bigla_bwd_plan(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                   const void *d_out, void *dq, void *dk, void *dv, void *dg_fwd, void *dg_bwd, int B, int H, int L,
+                   int dk_, int dv_, int dtype, int layout, int plan, void *workspace, size_t workspace_bytes,
+                   void *stream)
+{
     if (!q || !k || !v || !g_fwd || !g_bwd || !d_out || !dq || !dk || !dv || !dg_fwd || !dg_bwd) return VIG_ERR_NULL;
     if (layout != VIG_LAYOUT_BHLD && layout != VIG_LAYOUT_BLHD) return VIG_ERR_LAYOUT;
     if (B <= 0 || H <= 0 || L <= 0 || dk_ <= 0 || dv_ <= 0) return VIG_ERR_SHAPE;
     if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
     if (!head_dim_ok(dk_) || !head_dim_ok(dv_)) return VIG_ERR_UNSUPPORTED;
+    if (plan != VIG_BWD_AUTO && plan != VIG_BWD_RECURRENT) return VIG_ERR_UNSUPPORTED;
     if (!sizes_ok(B, H, L, 3L * dk_ + dv_) || long(B) * H * 4 > 0x7fffffffL) return VIG_ERR_SHAPE;
+    const bool chunkwise = plan == VIG_BWD_AUTO && vig::bigla_bwd_chunk_supported(dk_, dv_, dtype == VIG_BF16);
+    if (chunkwise && !chunk_offsets_ok(L, H, layout)) return VIG_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g_fwd) || !aligned16(g_bwd) ||
         !aligned16(d_out) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(dg_fwd) ||
         !aligned16(dg_bwd) || !aligned16(workspace))
@@ -121,8 +133,8 @@ int bigla_bwd(const void *q, const void *k, const void *v, const void *g_fwd, co
     const size_t need = bigla_bwd_workspace_bytes(B, H, L, dk_, dv_, dtype);
     if (!workspace || workspace_bytes < need) return VIG_ERR_WORKSPACE;
     return hip_status(vig::bigla_bwd_launch(q, k, v, g_fwd, g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, long(B) * H, L,
-                                            dk_, dv_, dtype == VIG_BF16, layout == VIG_LAYOUT_BLHD ? H : 0, workspace,
-                                            static_cast<hipStream_t>(stream)));
+                                            dk_, dv_, dtype == VIG_BF16, layout == VIG_LAYOUT_BLHD ? H : 0,
+                                            plan == VIG_BWD_RECURRENT, workspace, static_cast<hipStream_t>(stream)));
 }
 
 int locality_gate_fwd(const void *x, const void *w, const void *bias, const void *gate_logits,

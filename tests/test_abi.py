@@ -206,6 +206,23 @@ def test_bigla_bwd_validation_codes():
     assert call(B=2, H=3, Ln=100, dk=32, dv=64, dtype=vb.VIG_BF16, ws=None, ws_bytes=0) == vb.VIG_ERR_WORKSPACE
     assert call(B=2, H=3, Ln=100, dk=32, dv=64, dtype=vb.VIG_BF16, ws_bytes=need - 1) == vb.VIG_ERR_WORKSPACE
     assert L.bigla_bwd_workspace_bytes(2, 3, 100, 48, 64, vb.VIG_BF16) == 0
+    # bf16 with 64-wide heads adds the chunkwise kernels' states (four 64 x 64 bf16 matrices per
+    # chunk), chunk log-decays and slab marks, each rounded up to 256 bytes
+    exact = 2 * 3 * 100 * (3 * 64 + 64) * 4
+    chunks = 2 * 3 * 2
+    assert L.bigla_bwd_workspace_bytes(2, 3, 100, 64, 64, vb.VIG_F32) == exact
+    assert L.bigla_bwd_workspace_bytes(2, 3, 100, 64, 64, vb.VIG_BF16) == exact + chunks * 4 * 8192 + chunks * 512 + 256
+
+    def plan_call(plan, Ln=8, H=1, layout=vb.VIG_LAYOUT_BHLD):
+        return L.bigla_bwd_plan(PTR, PTR, PTR, PTR, PTR, PTR, PTR, PTR, PTR, PTR, PTR, 1, H, Ln, 64, 64, vb.VIG_BF16,
+                                layout, plan, None, 0, None)
+
+    assert plan_call(2) == vb.VIG_ERR_UNSUPPORTED
+    assert plan_call(-1) == vb.VIG_ERR_UNSUPPORTED
+    assert plan_call(0) == vb.VIG_ERR_WORKSPACE and plan_call(1) == vb.VIG_ERR_WORKSPACE
+    # the chunkwise kernels address a slab with 32-bit byte offsets; the exact ones do not
+    assert plan_call(0, Ln=1 << 22, H=16, layout=vb.VIG_LAYOUT_BLHD) == vb.VIG_ERR_SHAPE
+    assert plan_call(1, Ln=1 << 22, H=16, layout=vb.VIG_LAYOUT_BLHD) == vb.VIG_ERR_WORKSPACE
 
 
 def test_binding_rejects_cpu_tensors():
