@@ -15,8 +15,8 @@
 //   dg_u = sum_{t >= u} (q~ * X - k~ * Yi)_t + sum_{t < u} (k~ * Ye)_t + rowsum(S_in * A')
 // (the three parts of dg are the token pairs (s, t), s < u <= t, that straddle u: both inside the
 // chunk or s before it; s inside and t after it; s before and t after).  Every sum of dg runs over
-// at most one chunk, so no long-range cancellation enters it; its two prefix/suffix sums are
-// products with 0/1 triangles on the matrix cores, the summands split into two bf16 halves.
+// at most one chunk, so no long-range cancellation enters it; its two prefix/suffix sums are fp32
+// scans over the wave's tokens (DPP row operations) plus the other waves' totals.
 // States come from two small launches before the main one:
 //   1. bigla_bwd_chunk_local_kernel (workgroup per chunk): the chunk's own contributions
 //      U = (k * exp(b_end - b))^T v and W = q~^T do' for both directions, and the chunk totals of
@@ -83,6 +83,37 @@ __device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp_or_zero(float x)
+{
+    // lanes whose DPP source falls outside the 16-lane row receive 0
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+
+// Inclusive scan over the 16 lanes of a DPP row (the 16 tokens of a wave at fixed g): prefix sums
+// (SUFFIX 0) or suffix sums (SUFFIX 1); row_total hands every lane the scan's last value.
+template <int SUFFIX>
+__device__ __forceinline__ float row_scan(float x)
+{
+    if (SUFFIX == 0) {
+        x += dpp_or_zero<0x111>(x);  // row_shr:1
+        x += dpp_or_zero<0x112>(x);
+        x += dpp_or_zero<0x114>(x);
+        x += dpp_or_zero<0x118>(x);
+    } else {
+        x += dpp_or_zero<0x101>(x);  // row_shl:1
+        x += dpp_or_zero<0x102>(x);
+        x += dpp_or_zero<0x104>(x);
+        x += dpp_or_zero<0x108>(x);
+    }
+    return x;
+}
+template <int SUFFIX>
+__device__ __forceinline__ float row_total(float scanned)
+{
+    return SUFFIX == 0 ? dpp_or_zero<0x15f>(scanned) : dpp_or_zero<0x150>(scanned);  // row_newbcast:15 / :0
+}
+
 // Transposing LDS read: the 16 lanes of a row fetch a 4 (rows) x 16 (columns) bf16 patch of a
 // row-major tile; lane n of the row receives the 4 rows of column n and supplies the address of
 // row n/4, columns 4*(n%4).. of the patch.
@@ -115,7 +146,7 @@ __device__ __forceinline__ bf16x8 col_frag(const Tile &tile, int col0, int kk, i
 
 // B operand of a contraction over the chunk's tokens with a 0/1 triangle: k-slot j of K-step kk is
 // token s = 32kk + 8g + j, the lane's column is token u; 1 where s REL u holds.
-enum Rel { kLe = 0, kGe = 1, kLt = 2, kGt = 3 };
+enum Rel { kLe = 0, kGe = 1 };
 template <int REL>
 __device__ __forceinline__ bf16x8 tri_frag(int kk, int g, int u)
 {
@@ -126,7 +157,7 @@ __device__ __forceinline__ bf16x8 tri_frag(int kk, int g, int u)
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             const int s = 32 * kk + 8 * g + 2 * jj + half;
-            const bool one = REL == kLe ? s <= u : REL == kGe ? s >= u : REL == kLt ? s < u : s > u;
+            const bool one = REL == kLe ? s <= u : s >= u;
             bits |= (one ? 0x3F80u : 0u) << (16 * half);
         }
         word[jj] = bits;
@@ -423,13 +454,14 @@ __global__ __launch_bounds__(kThreads) void bigla_bwd_chunk_scan_kernel(uint16_t
 struct MainLds {
     Tile v;      // values                                   [token][column]
     Tile dout;   // d_out / 2                                [token][column]
-    Tile gp;     // log-gates, then P; later a half of dg's summands
+    Tile gp;     // log-gates, then P
     Tile qt;     // q~                                       [token][channel]
     Tile kt;     // k~
     Tile dp;     // masked dP                                [t][s]
     Tile st;     // S_in                                     [channel][column]
     Tile ad;     // A'
     float R[kD]; // rowsum(S_in * A') per channel
+    float tot[2][4][kD];  // per wave and channel: the wave's sums of the two kinds of dg summands
 };
 
 struct Grads {
@@ -549,44 +581,43 @@ __device__ __forceinline__ void chunk_direction(MainLds &sm, const SlabRows &gat
             E2[ct][e] = kv[e] * Ye[e];
         }
     }
-    __syncthreads();  // every wave is done with q~, k~, P and dP: their tiles take dg's summands
-#pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
-        f32x4 hi1, lo1, hi2, lo2;
-        const uint2 h1 = pack4(E1[ct]), h2 = pack4(E2[ct]);
-        hi1 = unpack4(h1);
-        hi2 = unpack4(h2);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            lo1[e] = E1[ct][e] - hi1[e];
-            lo2[e] = E2[ct][e] - hi2[e];
-        }
-        *reinterpret_cast<uint2 *>(&sm.qt[16 * w + r][16 * ct + 4 * g]) = h1;
-        put_own(sm.kt, w, r, g, ct, lo1);
-        *reinterpret_cast<uint2 *>(&sm.gp[16 * w + r][16 * ct + 4 * g]) = h2;
-        put_own(sm.dp, w, r, g, ct, lo2);
-    }
-    __syncthreads();
-    // dg^T[c][u] = sum_t E1[t][c] [t >= u] + sum_t E2[t][c] [t < u]   (forward; mirrored backward)
+    // dg_u = sum_{t >= u} E1_t + sum_{t < u} E2_t + rowsum(S_in * A')   (forward; mirrored backward):
+    // scans over the wave's 16 tokens with DPP row operations, in fp32, then the other waves' totals
     {
-        const int u = 16 * w + r;
-        const bf16x8 a0 = tri_frag<DIR == 0 ? kGe : kLe>(0, g, u), a1 = tri_frag<DIR == 0 ? kGe : kLe>(1, g, u);
-        const bf16x8 b0 = tri_frag<DIR == 0 ? kLt : kGt>(0, g, u), b1 = tri_frag<DIR == 0 ? kLt : kGt>(1, g, u);
+        constexpr int kFar = DIR == 0 ? 1 : 0;  // E1 accumulates from the far side of the direction
         f32x4 dg[4];
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct) {
-            f32x4 s = *reinterpret_cast<const f32x4 *>(&sm.R[16 * ct + 4 * g]);
-            s = mfma(col_frag(sm.qt, 16 * ct, 0, r, g), a0, s);
-            s = mfma(col_frag(sm.qt, 16 * ct, 1, r, g), a1, s);
-            s = mfma(col_frag(sm.kt, 16 * ct, 0, r, g), a0, s);
-            s = mfma(col_frag(sm.kt, 16 * ct, 1, r, g), a1, s);
-            s = mfma(col_frag(sm.gp, 16 * ct, 0, r, g), b0, s);
-            s = mfma(col_frag(sm.gp, 16 * ct, 1, r, g), b1, s);
-            s = mfma(col_frag(sm.dp, 16 * ct, 0, r, g), b0, s);
-            s = mfma(col_frag(sm.dp, 16 * ct, 1, r, g), b1, s);
-            dg[ct] = s;
+            f32x4 t1, t2;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float a = row_scan<kFar>(E1[ct][e]);
+                const float b = row_scan<1 - kFar>(E2[ct][e]);
+                dg[ct][e] = a + (b - E2[ct][e]);
+                t1[e] = row_total<kFar>(a);
+                t2[e] = row_total<1 - kFar>(b);
+            }
+            if (r == 0) {
+                *reinterpret_cast<f32x4 *>(&sm.tot[0][w][16 * ct + 4 * g]) = t1;
+                *reinterpret_cast<f32x4 *>(&sm.tot[1][w][16 * ct + 4 * g]) = t2;
+            }
         }
-        store_own(sm.st, dg_rows, t0, w, lane, r, g, dg);  // S_in is not needed any more
+        __syncthreads();  // totals visible; every wave is done with S_in, whose tile carries dg out
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            f32x4 s = *reinterpret_cast<const f32x4 *>(&sm.R[16 * ct + 4 * g]);
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2) {
+                if (w2 == w) continue;
+                const bool far = DIR == 0 ? w2 > w : w2 < w;
+                const f32x4 t = *reinterpret_cast<const f32x4 *>(&sm.tot[far ? 0 : 1][w2][16 * ct + 4 * g]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s[e] += t[e];
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dg[ct][e] += s[e];
+        }
+        store_own(sm.st, dg_rows, t0, w, lane, r, g, dg);
     }
 }
 
