@@ -110,10 +110,17 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
  *   dq, dk, dg_fwd, dg_bwd  [B, H, L, dk]                      out
  *   dv                      [B, H, L, dv]                      out
  *   (all in `layout`; dk, dv in {16, 32, 64}; any L >= 1)
- *   workspace: at least bigla_bwd_workspace_bytes(...) bytes (fp32 partial gradients).
- * Numerics: fp32 arithmetic token by token for either dtype (bf16 in and out, rounded to nearest
- * even); the gate gradients are formed as running sums of q * dq - k * dk per direction, which is
- * the same quantity.  A chunkwise matrix-core version does not exist yet.
+ *   workspace: at least bigla_bwd_workspace_bytes(...) bytes (fp32 partial gradients; for bf16 with
+ *   dk = dv = 64 also four 64 x 64 bf16 state matrices per 64-token chunk).
+ * Two sets of kernels.  bigla_bwd_plan with VIG_BWD_RECURRENT runs the exact ones: fp32 arithmetic
+ * token by token for either dtype (bf16 in and out, rounded to nearest even), the gate gradients
+ * formed as running sums of q * dq - k * dk per direction, which is the same quantity.
+ * VIG_BWD_AUTO (what bigla_bwd runs) takes, for VIG_BF16 with dk = dv = 64, the chunkwise
+ * matrix-core kernels (operands rounded to bf16, fp32 accumulation, the counterpart of the
+ * forward's chunkwise path; L below 2^24 and a slab addressable with 32-bit byte offsets, else
+ * VIG_ERR_SHAPE) and leaves to the exact kernels, inside the same call, only the (b, h) slabs in
+ * which some 64-token chunk decays by more than 60 nats in a channel; for every other dtype or
+ * head shape it is the exact kernels.  Unknown plan: VIG_ERR_UNSUPPORTED.
  */
 size_t bigla_bwd_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype);
 int bigla_bwd(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
@@ -221,7 +228,7 @@ typedef enum {
     VIG_KERNEL_SEGMENT_OUT_GENERAL = 5, /* chunkwise path, output pass of single-chunk sequences */
     VIG_KERNEL_GATE_PRODUCER = 6, /* forget-gate producer                                     */
     VIG_KERNEL_SLAB = 7,          /* chunkwise path, one-segment plans: both passes, one launch */
-    VIG_KERNEL_BACKWARD = 8       /* the two launches of bigla_bwd together                   */
+    VIG_KERNEL_BACKWARD = 8       /* all launches of one bigla_bwd call together               */
 } vig_kernel;
 int vig_timing_enable(int on);
 int vig_timing_collect(int kernel, double *total_ms, long *launches);

@@ -22,7 +22,8 @@
 //   dk : adjoint rows, and the running sums that are dg_fwd (descending sweep) and dg_bwd
 //        (ascending); reads dq^f, dq^b, so it runs after the first launch.
 // This is the exact-arithmetic path for every head shape and both dtypes (bf16 storage, fp32
-// arithmetic); a chunkwise matrix-core version is not built.
+// arithmetic).  For bf16 with 64-wide heads the chunkwise matrix-core kernels run first and these
+// kernels then take only the slabs marked for them (gates beyond the chunkwise range).
 #include "vig_common.hpp"
 #include "vig_kernels.hpp"
 #include "vig_timing.hpp"

@@ -191,20 +191,34 @@ __device__ __forceinline__ SlabRows slab_rows(const void *base, long slab, int L
     return s;
 }
 
-// Whole rows of a chunk into a tile: lane i of wave w takes 16-byte piece i%8 of rows 16w + i/8 and
-// 16w + 8 + i/8.  kHalf: the values are halved on the way (exact in bf16).
+// Whole rows of a chunk: lane i of wave w takes 16-byte piece i%8 of rows 16w + i/8 and 16w + 8 + i/8.
+// Requested first (all of a phase's tensors together), put into a tile when they are needed.
+struct ChunkRows {
+    u32x4 p[2];
+};
+
+__device__ __forceinline__ ChunkRows fetch_rows(const SlabRows &rows, unsigned t0, int w, int lane)
+{
+    ChunkRows c;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+        c.p[h] = __builtin_amdgcn_raw_buffer_load_b128(
+            rows.rsrc, (t0 + 16 * w + 8 * h + (lane >> 3)) * rows.pitch + 16u * (lane & 7), 0, 0);
+    return c;
+}
+
+// kHalf: the values are halved on the way (exact in bf16).
 template <bool kHalf>
-__device__ __forceinline__ void stage_rows(Tile &tile, const SlabRows &rows, unsigned t0, int w, int lane)
+__device__ __forceinline__ void put_rows(Tile &tile, const ChunkRows &c, int w, int lane)
 {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        const int row = 16 * w + 8 * h + (lane >> 3);
-        u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rows.rsrc, (t0 + row) * rows.pitch + 16u * (lane & 7), 0, 0);
+        u32x4 x = c.p[h];
         if (kHalf) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) x[i] = pack2(0.5f * bf16_lo_to_f32(x[i]), 0.5f * bf16_hi_to_f32(x[i]));
         }
-        *reinterpret_cast<uint4 *>(&tile[row][8 * (lane & 7)]) = make_uint4(x[0], x[1], x[2], x[3]);
+        *reinterpret_cast<uint4 *>(&tile[16 * w + 8 * h + (lane >> 3)][8 * (lane & 7)]) = make_uint4(x[0], x[1], x[2], x[3]);
     }
 }
 
@@ -311,10 +325,15 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_local_kernel(
     const SlabRows gf = slab_rows(gf_all, slab, L, heads_token_major), gb = slab_rows(gb_all, slab, L, heads_token_major);
 
     uint2 qr[4], kr[4];
-    stage_rows<false>(sm.qt, q, t0, w, lane);
-    stage_rows<false>(sm.kh, k, t0, w, lane);
-    stage_rows<false>(sm.v, v, t0, w, lane);
-    stage_rows<true>(sm.dout, dout, t0, w, lane);
+    {
+        const ChunkRows cq = fetch_rows(q, t0, w, lane), ck = fetch_rows(k, t0, w, lane);
+        const ChunkRows cv = fetch_rows(v, t0, w, lane), cd = fetch_rows(dout, t0, w, lane);
+        put_rows<false>(sm.qt, cq, w, lane);
+        put_rows<false>(sm.kh, ck, w, lane);
+        put_rows<false>(sm.v, cv, w, lane);
+        put_rows<true>(sm.dout, cd, w, lane);
+    }
+    ChunkRows cg[2] = {fetch_rows(gf, t0, w, lane), fetch_rows(gb, t0, w, lane)};
     take_own(sm.qt, w, r, g, qr);
     take_own(sm.kh, w, r, g, kr);
 
@@ -324,7 +343,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_local_kernel(
 #pragma unroll
     for (int dir = 0; dir < 2; ++dir) {
         if (dir == 1) __syncthreads();  // the first direction's products have read the tiles
-        stage_rows<false>(sm.gates, dir == 0 ? gf : gb, t0, w, lane);
+        put_rows<false>(sm.gates, cg[dir], w, lane);
         __syncthreads();
         f32x4 b[4], T[4];
         if (dir == 0)
@@ -368,10 +387,12 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_local_kernel(
 // ---- pass 2: the chunk-to-chunk recurrences, elementwise ------------------------------------------
 // grid: 16 workgroups per slab = 4 matrices x 4 quarters; a thread owns 4 consecutive elements of a
 // row and walks the slab's chunks in the matrix's direction, its loads requested kScanAhead chunks
-// ahead (the walk is a chain of dependent fp32 operations, but the addresses are known).
-constexpr int kScanAhead = 8;
+// ahead (the walk is a chain of dependent fp32 operations, but the addresses are known; measured at
+// 64 chunks per slab: 69 / 66 / 62 / 56 us for 4 / 8 / 16 / 32 chunks ahead; with 4 chunks per slab
+// the deep version only pays for its longer prologue, 25 us against 17 us).
 constexpr int kScanParts = 4;
 
+template <int kScanAhead>
 __global__ __launch_bounds__(kThreads) void bigla_bwd_chunk_scan_kernel(uint16_t *__restrict__ states,
                                                                        const float *__restrict__ logdec,
                                                                        int *__restrict__ marks, int n_chunks)
@@ -468,25 +489,48 @@ struct Grads {
     f32x4 dq[4], dk[4], dv[4];  // token 16w + r, channels / columns 16ct + 4g + e
 };
 
-__device__ __forceinline__ void copy_matrix(Tile &tile, const uint16_t *src, int tid)
+// What one direction reads beside q, k, v, do: its log-gates and its two state matrices.  Requested
+// ahead of the phase that needs them (the global latency then overlaps other work).
+struct DirInputs {
+    ChunkRows gates;
+    uint4 st[2], ad[2];
+};
+
+template <int DIR>
+__device__ __forceinline__ DirInputs fetch_dir(const SlabRows &gates, const uint16_t *mats, unsigned t0, int tid, int w,
+                                               int lane)
+{
+    DirInputs in;
+    in.gates = fetch_rows(gates, t0, w, lane);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        in.st[h] = reinterpret_cast<const uint4 *>(mats + size_t(2 * DIR) * kMat)[tid + kThreads * h];
+        in.ad[h] = reinterpret_cast<const uint4 *>(mats + size_t(2 * DIR + 1) * kMat)[tid + kThreads * h];
+    }
+    return in;
+}
+
+__device__ __forceinline__ void put_matrix(Tile &tile, const uint4 (&x)[2], int tid)
 {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int p = tid + kThreads * h;
-        *reinterpret_cast<uint4 *>(&tile[p >> 3][8 * (p & 7)]) = reinterpret_cast<const uint4 *>(src)[p];
+        *reinterpret_cast<uint4 *>(&tile[p >> 3][8 * (p & 7)]) = x[h];
     }
 }
 
-template <int DIR>
-__device__ __forceinline__ void chunk_direction(MainLds &sm, const SlabRows &gates, const SlabRows &dg_rows,
-                                                const uint16_t *mats, unsigned t0, int tid, int w, int lane, int r,
-                                                int g, const uint2 (&qr)[4], const uint2 (&kr)[4], Grads &acc)
+// `in`: this direction's inputs, already requested; `next`: called once the contractions are done,
+// to request the other direction's.
+template <int DIR, class Next>
+__device__ __forceinline__ void chunk_direction(MainLds &sm, const DirInputs &in, const SlabRows &dg_rows, unsigned t0,
+                                                int tid, int w, int lane, int r, int g, const uint2 (&qr)[4],
+                                                const uint2 (&kr)[4], Grads &acc, Next next)
 {
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    if (DIR == 1) __syncthreads();  // the first direction's last products have read the tiles
-    stage_rows<false>(sm.gp, gates, t0, w, lane);
-    copy_matrix(sm.st, mats + size_t(2 * DIR) * kMat, tid);
-    copy_matrix(sm.ad, mats + size_t(2 * DIR + 1) * kMat, tid);
+    if (DIR == 1) __syncthreads();  // the first direction's last reads of the tiles are done
+    put_rows<false>(sm.gp, in.gates, w, lane);
+    put_matrix(sm.st, in.st, tid);
+    put_matrix(sm.ad, in.ad, tid);
     __syncthreads();
 
     // cumulative gates, scaled queries and keys (kept as rounded: the gate gradient below must use
@@ -581,6 +625,7 @@ __device__ __forceinline__ void chunk_direction(MainLds &sm, const SlabRows &gat
             E2[ct][e] = kv[e] * Ye[e];
         }
     }
+    next();
     // dg_u = sum_{t >= u} E1_t + sum_{t < u} E2_t + rowsum(S_in * A')   (forward; mirrored backward):
     // scans over the wave's 16 tokens with DPP row operations, in fp32, then the other waves' totals
     {
@@ -642,19 +687,26 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_main_kernel(
     const SlabRows dgf = slab_rows(dgf_all, slab, L, heads_token_major), dgb = slab_rows(dgb_all, slab, L, heads_token_major);
 
     uint2 qr[4], kr[4];
-    stage_rows<false>(sm.qt, q, t0, w, lane);
-    stage_rows<false>(sm.kt, k, t0, w, lane);
-    stage_rows<false>(sm.v, v, t0, w, lane);
-    stage_rows<true>(sm.dout, dout, t0, w, lane);
+    const uint16_t *mats = states + size_t(unit) * 4 * kMat;
+    {
+        const ChunkRows cq = fetch_rows(q, t0, w, lane), ck = fetch_rows(k, t0, w, lane);
+        const ChunkRows cv = fetch_rows(v, t0, w, lane), cd = fetch_rows(dout, t0, w, lane);
+        put_rows<false>(sm.qt, cq, w, lane);
+        put_rows<false>(sm.kt, ck, w, lane);
+        put_rows<false>(sm.v, cv, w, lane);
+        put_rows<true>(sm.dout, cd, w, lane);
+    }
+    const DirInputs in_f = fetch_dir<0>(gf, mats, t0, tid, w, lane);
     take_own(sm.qt, w, r, g, qr);
     take_own(sm.kt, w, r, g, kr);
 
     Grads acc;
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) acc.dq[ct] = acc.dk[ct] = acc.dv[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const uint16_t *mats = states + size_t(unit) * 4 * kMat;
-    chunk_direction<0>(sm, gf, dgf, mats, t0, tid, w, lane, r, g, qr, kr, acc);
-    chunk_direction<1>(sm, gb, dgb, mats, t0, tid, w, lane, r, g, qr, kr, acc);
+    DirInputs in_b;
+    chunk_direction<0>(sm, in_f, dgf, t0, tid, w, lane, r, g, qr, kr, acc,
+                       [&]() { in_b = fetch_dir<1>(gb, mats, t0, tid, w, lane); });
+    chunk_direction<1>(sm, in_b, dgb, t0, tid, w, lane, r, g, qr, kr, acc, []() {});
 
     store_own(sm.st, slab_rows(dq_all, slab, L, heads_token_major), t0, w, lane, r, g, acc.dq);
     store_own(sm.ad, slab_rows(dk_all, slab, L, heads_token_major), t0, w, lane, r, g, acc.dk);
@@ -689,8 +741,12 @@ hipError_t bigla_bwd_chunk_launch(const void *q, const void *k, const void *v, c
     ws.marks = reinterpret_cast<int *>(base + states_bytes(BH, L) + logdec_bytes(BH, L));
     hipLaunchKernelGGL(bigla_bwd_chunk_local_kernel, dim3((unsigned)units), dim3(kThreads), 0, stream, q, k, v, g_fwd,
                        g_bwd, d_out, ws.states, ws.logdec, L, heads_token_major, n_chunks);
-    hipLaunchKernelGGL(bigla_bwd_chunk_scan_kernel, dim3((unsigned)(BH * 4 * kScanParts)), dim3(kThreads), 0, stream, ws.states,
-                       ws.logdec, ws.marks, n_chunks);
+    if (n_chunks > 16)
+        hipLaunchKernelGGL(bigla_bwd_chunk_scan_kernel<32>, dim3((unsigned)(BH * 4 * kScanParts)), dim3(kThreads), 0, stream,
+                           ws.states, ws.logdec, ws.marks, n_chunks);
+    else
+        hipLaunchKernelGGL(bigla_bwd_chunk_scan_kernel<8>, dim3((unsigned)(BH * 4 * kScanParts)), dim3(kThreads), 0, stream,
+                           ws.states, ws.logdec, ws.marks, n_chunks);
     hipLaunchKernelGGL(bigla_bwd_chunk_main_kernel, dim3((unsigned)units), dim3(kThreads), 0, stream, q, k, v, g_fwd,
                        g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, ws.states, ws.marks, L, heads_token_major, n_chunks);
     return hipGetLastError();

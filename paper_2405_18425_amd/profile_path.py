@@ -8,7 +8,8 @@ A third argument D > 0 adds the forget-gate producer in front of every pass (blo
 for the same B, L, H, dk), feeding the gates it makes to bigla_fwd.  A fourth argument 1 or 2 runs
 each pass through bigla_locality_fwd with the two-launch plan (1) or the fused-epilogue plan (2)
 instead of the two separate entry points; 3 runs bigla_bwd (the gradient of the token mixer, with
-the locality step's input as output gradient) after each forward pass.
+the locality step's input as output gradient) after each forward pass, 4 the same through
+bigla_bwd_plan with the exact token-by-token kernels only.
 """
 from __future__ import annotations
 
@@ -47,8 +48,9 @@ def main(cfg: int = 4, passes: int = 3, gate_width: int = 0, plan: int = 0) -> N
             continue
         og = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"])
         out = vb.locality_gate_fwd(t["v"], t["conv_w"], t["gate_logits"], og, w.Hg, w.Wg)
-        if plan == 3:
-            vb.bigla_bwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], t["gate_logits"])
+        if plan in (3, 4):
+            vb.bigla_bwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], t["gate_logits"],
+                         plan="auto" if plan == 3 else "recurrent")
     torch.cuda.synchronize()
     print("profile_path done", w.name, passes, float(out.float().abs().mean()), flush=True)
 
