@@ -426,7 +426,7 @@ hipError_t bigla_bwd_launch(const void *q, const void *k, const void *v, const v
         // the chunkwise kernels take every slab whose gates they can carry and mark the others
         if (!recurrent_only) {
             const hipError_t e = bigla_bwd_chunk_launch(q, k, v, g_fwd, g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, BH, L,
-                                                        heads_token_major, base, stream);
+                                                        dk_, heads_token_major, base, stream);
             if (e != hipSuccess) return e;
             only_marked = bigla_bwd_chunk_marks(base, BH, L);
         }

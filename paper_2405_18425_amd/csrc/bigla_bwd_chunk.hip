@@ -1,6 +1,7 @@
 // Chunkwise bf16 MFMA evaluation of the gradient of the BiGLA token mixer (Section 4.2.1,
 // Eq. (BiGLA); the paper trains through it, Section 5, and prints no gradient formulas) for
-// dk = dv = 64 in bf16: the counterpart of the chunkwise forward kernels.
+// dv = 64 and dk = 64 (or 32, widened to 64 with zero channels) in bf16: the counterpart of the
+// chunkwise forward kernels.
 //
 // One direction, forward (the backward one is its mirror image: suffix sums, keys to the right).
 // Inside a chunk of 64 tokens let b_t be the inclusive cumulative log-gate since the chunk's left
@@ -165,21 +166,27 @@ __device__ __forceinline__ bf16x8 tri_frag(int kk, int g, int u)
     return __builtin_bit_cast(bf16x8, make_uint4(word[0], word[1], word[2], word[3]));
 }
 
-// One slab's rows of a [.., 64] bf16 tensor behind a buffer resource that ends with the slab's last
-// token (loads beyond it return zeros, stores beyond it are dropped).
+// One slab's rows of a [.., width] bf16 tensor (width 64, or 32 for the queries, keys and gates of
+// a 32-wide head) behind a buffer resource that ends with the slab's last token (loads beyond it
+// return zeros, stores beyond it are dropped).  Rows of 32 are widened to the kernels' 64 channels
+// with zeros: channels 32..63 then carry q = k = 0 and log-gate 0 through every step and their
+// results are not stored; the pieces of the missing half are requested, and stored, at an offset
+// beyond the extent.
 struct SlabRows {
     __amdgpu_buffer_rsrc_t rsrc;
-    unsigned pitch;  // bytes between consecutive tokens
+    unsigned pitch;   // bytes between consecutive tokens
+    unsigned pieces;  // 16-byte pieces per row: 8 or 4
 };
+constexpr unsigned kBeyond = 0xfffffff0u;
 
-__device__ __forceinline__ SlabRows slab_rows(const void *base, long slab, int L, int heads_token_major)
+__device__ __forceinline__ SlabRows slab_rows(const void *base, long slab, int L, int heads_token_major, int width = kD)
 {
     const size_t first = heads_token_major
                              ? size_t(slab / heads_token_major) * size_t(L) * heads_token_major + slab % heads_token_major
                              : size_t(slab) * L;
-    const unsigned pitch = 2u * kD * unsigned(heads_token_major ? heads_token_major : 1);
-    const unsigned extent = unsigned(L - 1) * pitch + 2u * kD;
-    const uintptr_t a = reinterpret_cast<uintptr_t>(static_cast<const char *>(base) + first * (2 * kD));
+    const unsigned pitch = 2u * unsigned(width) * unsigned(heads_token_major ? heads_token_major : 1);
+    const unsigned extent = unsigned(L - 1) * pitch + 2u * unsigned(width);
+    const uintptr_t a = reinterpret_cast<uintptr_t>(static_cast<const char *>(base) + first * (2 * size_t(width)));
     // (readfirstlane returns a signed int: widen through unsigned, not by sign extension)
     const uintptr_t lo = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a))));
     const uintptr_t hi = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a >> 32))));
@@ -188,6 +195,7 @@ __device__ __forceinline__ SlabRows slab_rows(const void *base, long slab, int L
                                                int(unsigned(__builtin_amdgcn_readfirstlane(int(extent)))),
                                                0x00020000);
     s.pitch = pitch;
+    s.pieces = unsigned(width) / 8u;
     return s;
 }
 
@@ -201,9 +209,10 @@ __device__ __forceinline__ ChunkRows fetch_rows(const SlabRows &rows, unsigned t
 {
     ChunkRows c;
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-        c.p[h] = __builtin_amdgcn_raw_buffer_load_b128(
-            rows.rsrc, (t0 + 16 * w + 8 * h + (lane >> 3)) * rows.pitch + 16u * (lane & 7), 0, 0);
+    for (int h = 0; h < 2; ++h) {
+        const unsigned off = (t0 + 16 * w + 8 * h + (lane >> 3)) * rows.pitch + 16u * (lane & 7);
+        c.p[h] = __builtin_amdgcn_raw_buffer_load_b128(rows.rsrc, unsigned(lane & 7) < rows.pieces ? off : kBeyond, 0, 0);
+    }
     return c;
 }
 
@@ -253,8 +262,9 @@ __device__ __forceinline__ void store_own(Tile &tile, const SlabRows &rows, unsi
     for (int h = 0; h < 2; ++h) {
         const int row = 16 * w + 8 * h + (lane >> 3);
         const uint4 v = *reinterpret_cast<const uint4 *>(&tile[row][8 * (lane & 7)]);
+        const unsigned off = (t0 + row) * rows.pitch + 16u * (lane & 7);
         __builtin_amdgcn_raw_buffer_store_b128(u32x4{v.x, v.y, v.z, v.w}, rows.rsrc,
-                                               (t0 + row) * rows.pitch + 16u * (lane & 7), 0, 0);
+                                               unsigned(lane & 7) < rows.pieces ? off : kBeyond, 0, 0);
     }
     wave_lds_fence();  // the rows may be reused by this wave right away
 }
@@ -311,7 +321,7 @@ struct LocalLds {
 __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_local_kernel(
     const void *__restrict__ q_all, const void *__restrict__ k_all, const void *__restrict__ v_all,
     const void *__restrict__ gf_all, const void *__restrict__ gb_all, const void *__restrict__ do_all,
-    uint16_t *__restrict__ states, float *__restrict__ logdec, int L, int heads_token_major, int n_chunks)
+    uint16_t *__restrict__ states, float *__restrict__ logdec, int L, int heads_token_major, int n_chunks, int dk)
 {
     __shared__ __align__(16) LocalLds sm;
     const long unit = blockIdx.x;
@@ -320,9 +330,9 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_local_kernel(
     const unsigned t0 = unsigned(chunk) * kC;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
 
-    const SlabRows q = slab_rows(q_all, slab, L, heads_token_major), k = slab_rows(k_all, slab, L, heads_token_major);
+    const SlabRows q = slab_rows(q_all, slab, L, heads_token_major, dk), k = slab_rows(k_all, slab, L, heads_token_major, dk);
     const SlabRows v = slab_rows(v_all, slab, L, heads_token_major), dout = slab_rows(do_all, slab, L, heads_token_major);
-    const SlabRows gf = slab_rows(gf_all, slab, L, heads_token_major), gb = slab_rows(gb_all, slab, L, heads_token_major);
+    const SlabRows gf = slab_rows(gf_all, slab, L, heads_token_major, dk), gb = slab_rows(gb_all, slab, L, heads_token_major, dk);
 
     uint2 qr[4], kr[4];
     {
@@ -390,17 +400,18 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_local_kernel(
 // ahead (the walk is a chain of dependent fp32 operations, but the addresses are known; measured at
 // 64 chunks per slab: 69 / 66 / 62 / 56 us for 4 / 8 / 16 / 32 chunks ahead; with 4 chunks per slab
 // the deep version only pays for its longer prologue, 25 us against 17 us).
-constexpr int kScanParts = 4;
+constexpr int kScanThreads = 256;
+constexpr int kScanParts = 1024 / kScanThreads;
 
 template <int kScanAhead>
-__global__ __launch_bounds__(kThreads) void bigla_bwd_chunk_scan_kernel(uint16_t *__restrict__ states,
+__global__ __launch_bounds__(kScanThreads) void bigla_bwd_chunk_scan_kernel(uint16_t *__restrict__ states,
                                                                        const float *__restrict__ logdec,
                                                                        int *__restrict__ marks, int n_chunks)
 {
     const long slab = blockIdx.x / (4 * kScanParts);
     const int kind = (blockIdx.x / kScanParts) & 3, part = blockIdx.x % kScanParts;
     const int tid = threadIdx.x;
-    const int piece = part * kThreads + tid;  // 0..1023
+    const int piece = part * kScanThreads + tid;  // 0..1023
     const int row = piece >> 4;
     const int dir = kind >> 1;
     const bool adjoint = (kind & 1) != 0;
@@ -408,13 +419,13 @@ __global__ __launch_bounds__(kThreads) void bigla_bwd_chunk_scan_kernel(uint16_t
 
     if (kind == 0 && part == 0) {
         // mark the slab when some chunk decays by more than the fast form can carry
-        __shared__ float lowest[kThreads];
+        __shared__ float lowest[kScanThreads];
         float m = 0.f;
         const float *ld = logdec + size_t(slab) * n_chunks * 2 * kD;
-        for (long i = tid; i < long(n_chunks) * 2 * kD; i += kThreads) m = fminf(m, ld[i]);
+        for (long i = tid; i < long(n_chunks) * 2 * kD; i += kScanThreads) m = fminf(m, ld[i]);
         lowest[tid] = m;
         __syncthreads();
-        for (int s = kThreads / 2; s > 0; s >>= 1) {
+        for (int s = kScanThreads / 2; s > 0; s >>= 1) {
             if (tid < s) lowest[tid] = fminf(lowest[tid], lowest[tid + s]);
             __syncthreads();
         }
@@ -671,7 +682,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_main_kernel(
     const void *__restrict__ gf_all, const void *__restrict__ gb_all, const void *__restrict__ do_all,
     void *__restrict__ dq_all, void *__restrict__ dk_all, void *__restrict__ dv_all, void *__restrict__ dgf_all,
     void *__restrict__ dgb_all, const uint16_t *__restrict__ states, const int *__restrict__ marks, int L,
-    int heads_token_major, int n_chunks)
+    int heads_token_major, int n_chunks, int dk)
 {
     __shared__ __align__(16) MainLds sm;
     const long unit = blockIdx.x;
@@ -681,10 +692,10 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_main_kernel(
     const unsigned t0 = unsigned(chunk) * kC;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
 
-    const SlabRows q = slab_rows(q_all, slab, L, heads_token_major), k = slab_rows(k_all, slab, L, heads_token_major);
+    const SlabRows q = slab_rows(q_all, slab, L, heads_token_major, dk), k = slab_rows(k_all, slab, L, heads_token_major, dk);
     const SlabRows v = slab_rows(v_all, slab, L, heads_token_major), dout = slab_rows(do_all, slab, L, heads_token_major);
-    const SlabRows gf = slab_rows(gf_all, slab, L, heads_token_major), gb = slab_rows(gb_all, slab, L, heads_token_major);
-    const SlabRows dgf = slab_rows(dgf_all, slab, L, heads_token_major), dgb = slab_rows(dgb_all, slab, L, heads_token_major);
+    const SlabRows gf = slab_rows(gf_all, slab, L, heads_token_major, dk), gb = slab_rows(gb_all, slab, L, heads_token_major, dk);
+    const SlabRows dgf = slab_rows(dgf_all, slab, L, heads_token_major, dk), dgb = slab_rows(dgb_all, slab, L, heads_token_major, dk);
 
     uint2 qr[4], kr[4];
     const uint16_t *mats = states + size_t(unit) * 4 * kMat;
@@ -708,14 +719,14 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_main_kernel(
                        [&]() { in_b = fetch_dir<1>(gb, mats, t0, tid, w, lane); });
     chunk_direction<1>(sm, in_b, dgb, t0, tid, w, lane, r, g, qr, kr, acc, []() {});
 
-    store_own(sm.st, slab_rows(dq_all, slab, L, heads_token_major), t0, w, lane, r, g, acc.dq);
-    store_own(sm.ad, slab_rows(dk_all, slab, L, heads_token_major), t0, w, lane, r, g, acc.dk);
+    store_own(sm.st, slab_rows(dq_all, slab, L, heads_token_major, dk), t0, w, lane, r, g, acc.dq);
+    store_own(sm.ad, slab_rows(dk_all, slab, L, heads_token_major, dk), t0, w, lane, r, g, acc.dk);
     store_own(sm.v, slab_rows(dv_all, slab, L, heads_token_major), t0, w, lane, r, g, acc.dv);
 }
 
 }  // namespace
 
-bool bigla_bwd_chunk_supported(int dk, int dv, bool is_bf16) { return is_bf16 && dk == kD && dv == kD; }
+bool bigla_bwd_chunk_supported(int dk, int dv, bool is_bf16) { return is_bf16 && (dk == kD || dk == kD / 2) && dv == kD; }
 
 size_t bigla_bwd_chunk_workspace_bytes(long BH, int L)
 {
@@ -729,7 +740,7 @@ const int *bigla_bwd_chunk_marks(void *workspace, long BH, int L)
 
 hipError_t bigla_bwd_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
                                   const void *d_out, void *dq, void *dk, void *dv, void *dg_fwd, void *dg_bwd, long BH,
-                                  int L, int heads_token_major, void *workspace, hipStream_t stream)
+                                  int L, int dk_, int heads_token_major, void *workspace, hipStream_t stream)
 {
     const int n_chunks = chunks_of(L);
     const long units = BH * n_chunks;
@@ -740,15 +751,15 @@ hipError_t bigla_bwd_chunk_launch(const void *q, const void *k, const void *v, c
     ws.logdec = reinterpret_cast<float *>(base + states_bytes(BH, L));
     ws.marks = reinterpret_cast<int *>(base + states_bytes(BH, L) + logdec_bytes(BH, L));
     hipLaunchKernelGGL(bigla_bwd_chunk_local_kernel, dim3((unsigned)units), dim3(kThreads), 0, stream, q, k, v, g_fwd,
-                       g_bwd, d_out, ws.states, ws.logdec, L, heads_token_major, n_chunks);
+                       g_bwd, d_out, ws.states, ws.logdec, L, heads_token_major, n_chunks, dk_);
     if (n_chunks > 16)
-        hipLaunchKernelGGL(bigla_bwd_chunk_scan_kernel<32>, dim3((unsigned)(BH * 4 * kScanParts)), dim3(kThreads), 0, stream,
+        hipLaunchKernelGGL(bigla_bwd_chunk_scan_kernel<32>, dim3((unsigned)(BH * 4 * kScanParts)), dim3(kScanThreads), 0, stream,
                            ws.states, ws.logdec, ws.marks, n_chunks);
     else
-        hipLaunchKernelGGL(bigla_bwd_chunk_scan_kernel<8>, dim3((unsigned)(BH * 4 * kScanParts)), dim3(kThreads), 0, stream,
+        hipLaunchKernelGGL(bigla_bwd_chunk_scan_kernel<8>, dim3((unsigned)(BH * 4 * kScanParts)), dim3(kScanThreads), 0, stream,
                            ws.states, ws.logdec, ws.marks, n_chunks);
     hipLaunchKernelGGL(bigla_bwd_chunk_main_kernel, dim3((unsigned)units), dim3(kThreads), 0, stream, q, k, v, g_fwd,
-                       g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, ws.states, ws.marks, L, heads_token_major, n_chunks);
+                       g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, ws.states, ws.marks, L, heads_token_major, n_chunks, dk_);
     return hipGetLastError();
 }
 

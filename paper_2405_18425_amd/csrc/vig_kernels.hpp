@@ -31,7 +31,7 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
                               void *workspace, hipStream_t stream);
 
 // ---- gradient of the token mixer -----------------------------------------------------------------
-// Exact fp32 recurrences for any supported head shape and both dtypes; for bf16 with dk = dv = 64 the
+// Exact fp32 recurrences for any supported head shape and both dtypes; for bf16 with dv = 64 and dk = 64 or 32 the
 // chunkwise matrix-core kernels run first and leave to the exact ones only the slabs they mark
 // (gates beyond their range).  recurrent_only: the exact kernels take everything.
 size_t bigla_bwd_workspace_bytes(long BH, int L, int dk, int dv, bool is_bf16);
@@ -45,7 +45,7 @@ size_t bigla_bwd_chunk_workspace_bytes(long BH, int L);
 const int *bigla_bwd_chunk_marks(void *workspace, long BH, int L);
 hipError_t bigla_bwd_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
                                   const void *d_out, void *dq, void *dk, void *dv, void *dg_fwd, void *dg_bwd, long BH,
-                                  int L, int heads_token_major, void *workspace, hipStream_t stream);
+                                  int L, int dk_, int heads_token_major, void *workspace, hipStream_t stream);
 
 // ---- depthwise 3x3 conv + sigmoid-gated blend -------------------------------------------------
 hipError_t locality_gate_launch(const void *x, const void *w, const void *bias, const void *gate_logits,

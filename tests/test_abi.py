@@ -201,17 +201,20 @@ def test_bigla_bwd_validation_codes():
     assert call(layout=-1) == vb.VIG_ERR_LAYOUT
     assert call(dk=24) == vb.VIG_ERR_UNSUPPORTED
     assert call(dq=PTR + 4) == vb.VIG_ERR_ALIGN
-    need = L.bigla_bwd_workspace_bytes(2, 3, 100, 32, 64, vb.VIG_BF16)
-    assert need == 2 * 3 * 100 * (3 * 32 + 64) * 4
-    assert call(B=2, H=3, Ln=100, dk=32, dv=64, dtype=vb.VIG_BF16, ws=None, ws_bytes=0) == vb.VIG_ERR_WORKSPACE
-    assert call(B=2, H=3, Ln=100, dk=32, dv=64, dtype=vb.VIG_BF16, ws_bytes=need - 1) == vb.VIG_ERR_WORKSPACE
+    need = L.bigla_bwd_workspace_bytes(2, 3, 100, 32, 32, vb.VIG_BF16)
+    assert need == 2 * 3 * 100 * (3 * 32 + 32) * 4
+    assert call(B=2, H=3, Ln=100, dk=32, dv=32, dtype=vb.VIG_BF16, ws=None, ws_bytes=0) == vb.VIG_ERR_WORKSPACE
+    assert call(B=2, H=3, Ln=100, dk=32, dv=32, dtype=vb.VIG_BF16, ws_bytes=need - 1) == vb.VIG_ERR_WORKSPACE
     assert L.bigla_bwd_workspace_bytes(2, 3, 100, 48, 64, vb.VIG_BF16) == 0
-    # bf16 with 64-wide heads adds the chunkwise kernels' states (four 64 x 64 bf16 matrices per
-    # chunk), chunk log-decays and slab marks, each rounded up to 256 bytes
+    # bf16 with 64-wide values and 64- or 32-wide keys adds the chunkwise kernels' states (four
+    # 64 x 64 bf16 matrices per chunk), chunk log-decays and slab marks, each rounded up to 256 bytes
     exact = 2 * 3 * 100 * (3 * 64 + 64) * 4
     chunks = 2 * 3 * 2
     assert L.bigla_bwd_workspace_bytes(2, 3, 100, 64, 64, vb.VIG_F32) == exact
     assert L.bigla_bwd_workspace_bytes(2, 3, 100, 64, 64, vb.VIG_BF16) == exact + chunks * 4 * 8192 + chunks * 512 + 256
+    assert L.bigla_bwd_workspace_bytes(2, 3, 100, 32, 64, vb.VIG_BF16) == (
+        2 * 3 * 100 * (3 * 32 + 64) * 4 + chunks * 4 * 8192 + chunks * 512 + 256)
+    assert L.bigla_bwd_workspace_bytes(2, 3, 100, 64, 32, vb.VIG_BF16) == 2 * 3 * 100 * (3 * 64 + 32) * 4
 
     def plan_call(plan, Ln=8, H=1, layout=vb.VIG_LAYOUT_BHLD):
         return L.bigla_bwd_plan(PTR, PTR, PTR, PTR, PTR, PTR, PTR, PTR, PTR, PTR, PTR, 1, H, Ln, 64, 64, vb.VIG_BF16,

@@ -569,7 +569,7 @@ def _check_bwd(s, dtype, layout, plan, slabs=None, what=""):
 
 
 def _bwd_plans(dtype, dk, dv):
-    return ("auto", "recurrent") if (dtype == "bf16" and dk == 64 and dv == 64) else ("auto",)
+    return ("auto", "recurrent") if (dtype == "bf16" and dk in (32, 64) and dv == 64) else ("auto",)
 
 
 @pytest.mark.parametrize("dtype,B,H,L,dk,dv,layout,mu", [
@@ -586,7 +586,7 @@ def _bwd_plans(dtype, dk, dv):
 ])
 def test_bigla_bwd_parity(dtype, B, H, L, dk, dv, layout, mu):
     """bigla_bwd against the oracle's gradient, all five gradients, same stored inputs; where the
-    chunkwise kernels apply (bf16, 64-wide heads) both plans are checked."""
+    chunkwise kernels apply (bf16, 64-wide values, 64- or 32-wide keys) both plans are checked."""
     w = wl.Workload("bwd", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=dv, dtype=dtype, gate_mu=mu)
     s = _bwd_inputs(w, seed=L + dk)
     for plan in _bwd_plans(dtype, dk, dv):
@@ -600,18 +600,19 @@ def test_bigla_bwd_chunkwise_lengths(L):
     """Chunkwise gradient kernels on lengths around the 64-token chunk: single chunks, exact
     multiples, ragged tails of 1 and 63 tokens; alternating layouts and gate strengths."""
     layout = "bhld" if L % 2 else "blhd"
-    w = wl.Workload("bwdlen", B=2, H=3, Hg=1, Wg=L, dk=64, dv=64, dtype="bf16", gate_mu=(-3.0, 0.0, 2.0)[L % 3])
-    _say(f"bigla_bwd chunkwise L={L} {layout} mu={w.gate_mu}")
+    dk = 32 if L % 4 < 2 else 64
+    w = wl.Workload("bwdlen", B=2, H=3, Hg=1, Wg=L, dk=dk, dv=64, dtype="bf16", gate_mu=(-3.0, 0.0, 2.0)[L % 3])
+    _say(f"bigla_bwd chunkwise L={L} dk={dk} {layout} mu={w.gate_mu}")
     worst = _check_bwd(_bwd_inputs(w, seed=3 * L), "bf16", layout, "auto")
     _say(f"  worst error / bound = {worst:.3f}")
 
 
-@pytest.mark.parametrize("layout", ("bhld", "blhd"))
-def test_bigla_bwd_slabs_beyond_the_chunkwise_range(layout):
+@pytest.mark.parametrize("layout,dk", (("bhld", 64), ("blhd", 64), ("blhd", 32)))
+def test_bigla_bwd_slabs_beyond_the_chunkwise_range(layout, dk):
     """Some slabs decay by more than the chunkwise kernels carry (a chunk total beyond 60 nats):
     those are left to the exact kernels, the others are not, in one call."""
     B, H, L = 2, 3, 300
-    w = wl.Workload("bwdmark", B=B, H=H, Hg=1, Wg=L, dk=64, dv=64, dtype="bf16", gate_mu=-1.0)
+    w = wl.Workload("bwdmark", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=64, dtype="bf16", gate_mu=-1.0)
     s = _bwd_inputs(w, seed=23)
     gf, gb = wl.widen(s["g_fwd"], "bf16"), wl.widen(s["g_bwd"], "bf16")
     gf[0, 1, :, :] = -3.0                           # 192 nats per chunk, every channel, forward only
@@ -625,10 +626,10 @@ def test_bigla_bwd_slabs_beyond_the_chunkwise_range(layout):
     _say(f"  worst error / bound = {worst:.3f}")
 
 
-@pytest.mark.parametrize("cfg", (2, 4))
-def test_bigla_bwd_full_size_sampled_slabs(cfg):
+@pytest.mark.parametrize("cfg,dk", ((2, 64), (4, 64), (4, 32)))
+def test_bigla_bwd_full_size_sampled_slabs(cfg, dk):
     """The gradient at full benchmark size; the oracle recomputes a sample of (b, h) slabs."""
-    w = wl.CONFIGS[cfg]
+    w = wl.CONFIGS[cfg].replace(dk=dk)
     _say(f"bigla_bwd full cfg{cfg} {w}")
     s = _bwd_inputs(w, seed=1)
     rng = np.random.default_rng(cfg)
