@@ -52,6 +52,9 @@ def parse_args():
     ap.add_argument("--cpu-budget-s", type=float, default=12.0)
     ap.add_argument("--single-set", action="store_true", help="reuse one buffer set (cache-warm timing)")
     ap.add_argument("--dk", type=int, default=0, help="override the key/query head width of the workload (side measurement)")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time bigla_bwd, the gradient of the token mixer, on the same buffers (side "
+                         "measurement in detail.backward; not part of the step or of value)")
     ap.add_argument("--layout", choices=("bhld", "blhd"), default="bhld",
                     help="activation layout: head-major (default) or token-major [B,L,H,d] (side measurement)")
     return ap.parse_args()
@@ -164,6 +167,28 @@ def main():
         lus = kern["locality_gate"]["avg_us"]
         extra["locality_hbm_gbs"] = round(loc_bytes / (lus * 1e-6) / 1e9, 1)
         extra["locality_frac_hbm_peak"] = round(loc_bytes / (lus * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+
+    # ---- side measurement: the gradient of the token mixer (d_out := the gate logits, any values do)
+    if args.backward:
+        bws = torch.empty(int(vb.lib().bigla_bwd_workspace_bytes(w.B, w.H, w.L, w.dk, w.dv, code)), dtype=torch.uint8,
+                          device=dev)
+        n_bwd = max(20, args.steps // 5)
+
+        def bwd(i):
+            s = sets[i % n_sets]
+            vb.bigla_bwd(s["q"], s["k"], s["v"], s["g_fwd"], s["g_bwd"], s["gate_logits"], workspace=bws,
+                         layout=args.layout)
+
+        for i in range(max(5, n_bwd // 5)):
+            bwd(i)
+        torch.cuda.synchronize()
+        b0 = time.perf_counter()
+        for i in range(n_bwd):
+            bwd(i)
+        torch.cuda.synchronize()
+        bwd_us = (time.perf_counter() - b0) * 1e6 / n_bwd
+        extra["backward"] = {"us": round(bwd_us, 2), "tokens_per_s": round(w.tokens / (bwd_us * 1e-6), 1),
+                             "calls": n_bwd, "vs_forward_mixer": round(bwd_us / bigla_us, 2)}
 
     # ---- CPU oracle on the host cores (reported baseline, not the target)
     cpu = None

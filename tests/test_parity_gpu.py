@@ -638,6 +638,50 @@ def test_bigla_bwd_full_size_sampled_slabs(cfg, dk):
     _say(f"  worst error / bound = {worst:.3f}")
 
 
+def test_bigla_bwd_long_sequence():
+    """256 chunks and a ragged tail per slab: the chunk scan's deep prefetch wraps many times."""
+    w = wl.Workload("bwdlong", B=1, H=2, Hg=1, Wg=16384 + 17, dk=64, dv=64, dtype="bf16", gate_mu=-2.0)
+    _say(f"bigla_bwd long {w}")
+    worst = _check_bwd(_bwd_inputs(w, seed=9), "bf16", "bhld", "auto")
+    _say(f"  worst error / bound = {worst:.3f}")
+
+
+def test_bigla_bwd_captured_in_a_hip_graph():
+    """bigla_bwd (chunkwise kernels plus the exact ones behind the slab marks) captured once and
+    replayed with new inputs in the same buffers, eager work in between: every replay equals the
+    eager call."""
+    import torch
+    from paper_2405_18425_amd import binding as vb
+
+    w = wl.Workload("bwdgraph", B=2, H=2, Hg=1, Wg=300, dk=64, dv=64, dtype="bf16", gate_mu=-1.0)
+    s = _bwd_inputs(w, seed=12)
+    gf = wl.widen(s["g_fwd"], "bf16")
+    gf[1, 1] = -2.0                                   # one slab for the exact kernels
+    s["g_fwd"] = wl.store(gf, "bf16")
+    t = [wl.to_torch(s[n], "bf16", "cuda:0") for n in BWD_NAMES]
+    need = int(vb.lib().bigla_bwd_workspace_bytes(w.B, w.H, w.L, w.dk, w.dv, 1))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    vb.bigla_bwd(*t, workspace=ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+        captured = vb.bigla_bwd(*t, workspace=ws)
+    for rep in range(3):
+        if rep:
+            t[0].copy_(torch.roll(t[0], shifts=rep, dims=2))
+            t[5].mul_(0.5)
+        want = [g.clone() for g in vb.bigla_bwd(*t, workspace=ws)]
+        torch.cuda.synchronize()
+        for g in captured:
+            g.zero_()
+        ws.random_(0, 255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(captured, want):
+            assert torch.equal(a, b), f"replay {rep}"
+
+
 def test_bigla_bwd_chunkwise_deterministic_dirty_workspace():
     """Two calls with the workspace overwritten in between return the same bits."""
     import torch
