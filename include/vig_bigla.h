@@ -111,11 +111,11 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
  *   dv                      [B, H, L, dv]                      out
  *   (all in `layout`; dk, dv in {16, 32, 64}; any L >= 1)
  *   workspace: at least bigla_bwd_workspace_bytes(...) bytes (fp32 partial gradients; for bf16 with
- *   dk = dv = 64 also four 64 x 64 bf16 state matrices per 64-token chunk).
+ *   dv = 64 and dk = 64 or 32 also four 64 x 64 bf16 state matrices per 64-token chunk).
  * Two sets of kernels.  bigla_bwd_plan with VIG_BWD_RECURRENT runs the exact ones: fp32 arithmetic
  * token by token for either dtype (bf16 in and out, rounded to nearest even), the gate gradients
  * formed as running sums of q * dq - k * dk per direction, which is the same quantity.
- * VIG_BWD_AUTO (what bigla_bwd runs) takes, for VIG_BF16 with dk = dv = 64, the chunkwise
+ * VIG_BWD_AUTO (what bigla_bwd runs) takes, for VIG_BF16 with dv = 64 and dk = 64 or 32, the chunkwise
  * matrix-core kernels (operands rounded to bf16, fp32 accumulation, the counterpart of the
  * forward's chunkwise path; L below 2^24 and a slab addressable with 32-bit byte offsets, else
  * VIG_ERR_SHAPE) and leaves to the exact kernels, inside the same call, only the (b, h) slabs in

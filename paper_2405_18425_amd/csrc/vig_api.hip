@@ -126,6 +126,7 @@ int bigla_bwd_plan(const void *q, const void *k, const void *v, const void *g_fw
     if (!sizes_ok(B, H, L, 3L * dk_ + dv_) || long(B) * H * 4 > 0x7fffffffL) return VIG_ERR_SHAPE;
     const bool chunkwise = plan == VIG_BWD_AUTO && vig::bigla_bwd_chunk_supported(dk_, dv_, dtype == VIG_BF16);
     if (chunkwise && !chunk_offsets_ok(L, H, layout)) return VIG_ERR_SHAPE;
+    if (chunkwise && long(B) * H * ((long(L) + 63) / 64) > 0x7fffffffL) return VIG_ERR_SHAPE;  // a workgroup per chunk
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g_fwd) || !aligned16(g_bwd) ||
         !aligned16(d_out) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(dg_fwd) ||
         !aligned16(dg_bwd) || !aligned16(workspace))
