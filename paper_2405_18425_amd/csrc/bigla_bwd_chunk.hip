@@ -145,6 +145,15 @@ __device__ __forceinline__ bf16x8 col_frag(const Tile &tile, int col0, int kk, i
     return join(lds_read_tr(&tile[row][col]), lds_read_tr(&tile[row + 4][col]));
 }
 
+// MFMA A operand whose 16 rows are tile columns col0..col0+15, contracted over the tile's rows
+// (tokens) in accumulator order: k-slots 0..3 of K-step kk are rows 32kk + 4g + e, slots 4..7 rows
+// 32kk + 16 + 4g + e, which is where a lane's accumulators of two stacked 16x16 tiles sit.
+__device__ __forceinline__ bf16x8 token_frag(const Tile &tile, int col0, int kk, int r, int g)
+{
+    const int row = 32 * kk + 4 * g + (r >> 2), col = col0 + 4 * (r & 3);
+    return join(lds_read_tr(&tile[row][col]), lds_read_tr(&tile[row + 16][col]));
+}
+
 // B operand of a contraction over the chunk's tokens with a 0/1 triangle: k-slot j of K-step kk is
 // token s = 32kk + 8g + j, the lane's column is token u; 1 where s REL u holds.
 enum Rel { kLe = 0, kGe = 1 };
@@ -486,10 +495,9 @@ __global__ __launch_bounds__(kScanThreads) void bigla_bwd_chunk_scan_kernel(uint
 struct MainLds {
     Tile v;      // values                                   [token][column]
     Tile dout;   // d_out / 2                                [token][column]
-    Tile gp;     // log-gates, then P
+    Tile gp;     // log-gates                                [token][channel]
     Tile qt;     // q~                                       [token][channel]
     Tile kt;     // k~
-    Tile dp;     // masked dP                                [t][s]
     Tile st;     // S_in                                     [channel][column]
     Tile ad;     // A'
     float R[kD]; // rowsum(S_in * A') per channel
@@ -584,42 +592,84 @@ __device__ __forceinline__ void chunk_direction(MainLds &sm, const DirInputs &in
     }
     __syncthreads();  // q~, k~ complete; every wave is done with the gates
 
-    // P^T and dP^T tiles of the wave's queries (keys 16m + 4g + e, query 16w + r), masked, stored [t][s]
+    // The wave's strips of the masked score matrices, straight from the accumulators into the B
+    // operands of the contractions over tokens (no trip through LDS): the row strip of dP for X
+    // (keys 16m + 4g + e, query 16w + r) and the column strips of dP and P for Yi and dv (queries
+    // 16m + 4g + e, key 16w + r).  A lane's accumulators of tiles m = 2kk, 2kk + 1 are exactly its
+    // k-slots of K-step kk when slots 0..3 are tokens 32kk + 4g + e and slots 4..7 tokens
+    // 32kk + 16 + 4g + e; the A operands (token_frag) use the same order.
+    const bf16x8 own_k[2] = {row_frag(sm.kt, 16 * w, 0, r, g), row_frag(sm.kt, 16 * w, 1, r, g)};
+    const bf16x8 own_d[2] = {row_frag(sm.dout, 16 * w, 0, r, g), row_frag(sm.dout, 16 * w, 1, r, g)};
+    const bf16x8 own_v[2] = {row_frag(sm.v, 16 * w, 0, r, g), row_frag(sm.v, 16 * w, 1, r, g)};
+    // Each strip is split into two bf16 halves (value = hi + lo to 16 bits): the scores then enter
+    // the second contraction unrounded, for one more MFMA per product and no further LDS traffic.
+    bf16x8 bX[2], bY[2], bP[2], bXl[2], bYl[2], bPl[2];
 #pragma unroll
-    for (int m = 0; m < 4; ++m) {
-        f32x4 p = zero;
+    for (int kk = 0; kk < 2; ++kk) {
+        uint2 x[2], y[2], p[2], xl[2], yl[2], pl[2];
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) p = mfma(row_frag(sm.kt, 16 * m, kk, r, g), row_frag(sm.qt, 16 * w, kk, r, g), p);
-        f32x4 d = zero;  // (the same for both directions up to the mask; not kept: registers are scarcer)
+        for (int half = 0; half < 2; ++half) {
+            const int m = 2 * kk + half;
+            f32x4 dr = zero, dc = zero, pc = zero;
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) d = mfma(row_frag(sm.v, 16 * m, kk, r, g), row_frag(sm.dout, 16 * w, kk, r, g), d);
+            for (int k2 = 0; k2 < 2; ++k2) {
+                dr = mfma(row_frag(sm.v, 16 * m, k2, r, g), own_d[k2], dr);     // dP[t own][s]
+                dc = mfma(row_frag(sm.dout, 16 * m, k2, r, g), own_v[k2], dc);  // dP[t][s own]
+                pc = mfma(row_frag(sm.qt, 16 * m, k2, r, g), own_k[k2], pc);    // P[t][s own]
+            }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int s = 16 * m + 4 * g + e, t = 16 * w + r;
-            const bool keep = DIR == 0 ? s <= t : s >= t;
-            p[e] = keep ? p[e] : 0.f;
-            d[e] = keep ? d[e] : 0.f;
+            for (int e = 0; e < 4; ++e) {
+                const int far = 16 * m + 4 * g + e, own = 16 * w + r;
+                // row strip: far is the key, own the query; column strips: the other way round
+                const bool keep_row = DIR == 0 ? far <= own : far >= own;
+                const bool keep_col = DIR == 0 ? own <= far : own >= far;
+                dr[e] = keep_row ? dr[e] : 0.f;
+                dc[e] = keep_col ? dc[e] : 0.f;
+                pc[e] = keep_col ? pc[e] : 0.f;
+            }
+            x[half] = pack4(dr);
+            y[half] = pack4(dc);
+            p[half] = pack4(pc);
+            const f32x4 xh = unpack4(x[half]), yh = unpack4(y[half]), ph = unpack4(p[half]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                dr[e] -= xh[e];
+                dc[e] -= yh[e];
+                pc[e] -= ph[e];
+            }
+            xl[half] = pack4(dr);
+            yl[half] = pack4(dc);
+            pl[half] = pack4(pc);
         }
-        put_own(sm.gp, w, r, g, m, p);
-        put_own(sm.dp, w, r, g, m, d);
+        bX[kk] = __builtin_bit_cast(bf16x8, make_uint4(x[0].x, x[0].y, x[1].x, x[1].y));
+        bY[kk] = __builtin_bit_cast(bf16x8, make_uint4(y[0].x, y[0].y, y[1].x, y[1].y));
+        bP[kk] = __builtin_bit_cast(bf16x8, make_uint4(p[0].x, p[0].y, p[1].x, p[1].y));
+        bXl[kk] = __builtin_bit_cast(bf16x8, make_uint4(xl[0].x, xl[0].y, xl[1].x, xl[1].y));
+        bYl[kk] = __builtin_bit_cast(bf16x8, make_uint4(yl[0].x, yl[0].y, yl[1].x, yl[1].y));
+        bPl[kk] = __builtin_bit_cast(bf16x8, make_uint4(pl[0].x, pl[0].y, pl[1].x, pl[1].y));
     }
-    __syncthreads();
 
     f32x4 E1[4], E2[4];
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) {
-        // X^T[c][t] = sum_s k~[s][c] dP[t][s] + sum_j S_in[c][j] do'[t][j]
         f32x4 X = zero, Yi = zero, Ye = zero, V = zero;
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
-            X = mfma(col_frag(sm.kt, 16 * ct, kk, r, g), row_frag(sm.dp, 16 * w, kk, r, g), X);
-            X = mfma(row_frag(sm.st, 16 * ct, kk, r, g), row_frag(sm.dout, 16 * w, kk, r, g), X);
+            // X^T[c][t] = sum_s k~[s][c] dP[t][s] + sum_j S_in[c][j] do'[t][j]
+            const bf16x8 ak = token_frag(sm.kt, 16 * ct, kk, r, g);
+            X = mfma(ak, bXl[kk], X);
+            X = mfma(ak, bX[kk], X);
+            X = mfma(row_frag(sm.st, 16 * ct, kk, r, g), own_d[kk], X);
             // Yi^T[c][s] = sum_t q~[t][c] dP[t][s],  Ye^T[c][s] = sum_j A'[c][j] v[s][j]
-            Yi = mfma(col_frag(sm.qt, 16 * ct, kk, r, g), col_frag(sm.dp, 16 * w, kk, r, g), Yi);
-            Ye = mfma(row_frag(sm.ad, 16 * ct, kk, r, g), row_frag(sm.v, 16 * w, kk, r, g), Ye);
+            const bf16x8 aq = token_frag(sm.qt, 16 * ct, kk, r, g);
+            Yi = mfma(aq, bYl[kk], Yi);
+            Yi = mfma(aq, bY[kk], Yi);
+            Ye = mfma(row_frag(sm.ad, 16 * ct, kk, r, g), own_v[kk], Ye);
             // dv^T[j][s] = sum_t do'[t][j] P[t][s] + sum_i A'[i][j] k~[s][i]
-            V = mfma(col_frag(sm.dout, 16 * ct, kk, r, g), col_frag(sm.gp, 16 * w, kk, r, g), V);
-            V = mfma(col_frag(sm.ad, 16 * ct, kk, r, g), row_frag(sm.kt, 16 * w, kk, r, g), V);
+            const bf16x8 ad = token_frag(sm.dout, 16 * ct, kk, r, g);
+            V = mfma(ad, bPl[kk], V);
+            V = mfma(ad, bP[kk], V);
+            V = mfma(col_frag(sm.ad, 16 * ct, kk, r, g), own_k[kk], V);
         }
         // The summands of the gate gradient take q~ and k~ as the contractions saw them (rounded to
         // bf16): sum_{t>=u} q~ * X - sum_{s>=u} k~ * Yi is then, term by term, the sum over the pairs
