@@ -638,6 +638,37 @@ def test_bigla_bwd_full_size_sampled_slabs(cfg, dk):
     _say(f"  worst error / bound = {worst:.3f}")
 
 
+def test_bigla_bwd_seeded_random_shapes():
+    """A seeded sweep over shapes, head widths, layouts, dtypes, input scales and gate regimes
+    (mild, mixed with a few strong steps, harsh: slabs beyond the chunkwise range), all five
+    gradients of each case against the oracle."""
+    rng = np.random.default_rng(4242)
+    for case in range(30):
+        dtype = "bf16" if case % 5 else "f32"
+        dk, dv = ((64, 64), (32, 64), (16, 16), (32, 32), (64, 32), (16, 64))[int(rng.integers(6))]
+        if dtype == "bf16" and case % 3:
+            dk, dv = ((64, 64), (32, 64))[case % 2]          # mostly the chunkwise kernels
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 6))
+        L = int(rng.choice([1, 3, 31, 64, 65, 100, 192, 200, 449, 777, 1024, 1300]))
+        layout = "blhd" if rng.random() < 0.4 else "bhld"
+        regime = ("mild", "mixed", "harsh")[int(rng.integers(3))]
+        scale = float(rng.choice([0.25, 1.0, 4.0]))
+        w = wl.Workload(f"bwdrand{case}", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=dv, dtype=dtype,
+                        gate_mu={"mild": 1.0, "mixed": -1.0, "harsh": -3.0}[regime])
+        _say(f"bwd random case {case}: {w} layout={layout} regime={regime} scale={scale}")
+        s_ = _bwd_inputs(w, seed=2000 + case)
+        for name in ("q", "k", "v", "d_out"):
+            s_[name] = wl.store(wl.widen(s_[name], dtype) * scale, dtype)
+        if regime != "mild":
+            for name in ("g_fwd", "g_bwd"):
+                g = wl.widen(s_[name], dtype)
+                spikes = rng.random(g.shape) < (0.01 if regime == "mixed" else 0.2)
+                g[spikes] = -float(rng.choice([2.0, 6.0, 25.0]))
+                s_[name] = wl.store(g, dtype)
+        worst = _check_bwd(s_, dtype, layout, "auto", what=f"random case {case}")
+        _say(f"  worst error / bound = {worst:.3f}")
+
+
 def test_bigla_bwd_long_sequence():
     """256 chunks and a ragged tail per slab: the chunk scan's deep prefetch wraps many times."""
     w = wl.Workload("bwdlong", B=1, H=2, Hg=1, Wg=16384 + 17, dk=64, dv=64, dtype="bf16", gate_mu=-2.0)
