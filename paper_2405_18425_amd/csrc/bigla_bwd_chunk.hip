@@ -39,6 +39,8 @@
 // with ds_read_b64_tr_b16.  Tokens past the sequence are read as zeros (q = k = v = do = 0,
 // log-gate 0: a no-op) and their stores are dropped, both by the bounds check of the buffer
 // resource that spans the slab.
+#include <type_traits>
+
 #include "vig_common.hpp"
 #include "vig_kernels.hpp"
 #include "vig_timing.hpp"
@@ -287,7 +289,7 @@ __device__ __forceinline__ void put_own(Tile &tile, int w, int r, int g, int ct,
 // Inclusive cumulative log-gates of the chunk on the matrix cores (a product with a 0/1 triangle is
 // exact in bf16 x bf16 -> fp32): b[ct][e] for the lane's token and channel 16ct + 4g + e, prefix
 // sums for DIR 0, suffix sums for DIR 1.
-template <int DIR>
+template <int DIR, int kCt>
 __device__ __forceinline__ void gate_scan(const Tile &gates, int w, int r, int g, f32x4 (&b)[4])
 {
     const bf16x8 t0 = tri_frag<DIR == 0 ? kLe : kGe>(0, g, 16 * w + r);
@@ -295,7 +297,8 @@ __device__ __forceinline__ void gate_scan(const Tile &gates, int w, int r, int g
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) {
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-        b[ct] = mfma(col_frag(gates, 16 * ct, 1, r, g), t1, mfma(col_frag(gates, 16 * ct, 0, r, g), t0, zero));
+        b[ct] = zero;
+        if (ct < kCt) b[ct] = mfma(col_frag(gates, 16 * ct, 1, r, g), t1, mfma(col_frag(gates, 16 * ct, 0, r, g), t0, zero));
     }
 }
 
@@ -327,6 +330,9 @@ struct LocalLds {
 };
 
 // ---- pass 1: the chunk's own contributions to the states ----------------------------------------
+// kCt: channel tiles of 16 that carry data (4; 2 for a 32-wide head, whose channels 32..63 are zero
+// in q, k and the gates: their rows of the matrices are neither computed, stored nor read anywhere).
+template <int kCt>
 __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_local_kernel(
     const void *__restrict__ q_all, const void *__restrict__ k_all, const void *__restrict__ v_all,
     const void *__restrict__ gf_all, const void *__restrict__ gb_all, const void *__restrict__ do_all,
@@ -366,12 +372,16 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_local_kernel(
         __syncthreads();
         f32x4 b[4], T[4];
         if (dir == 0)
-            gate_scan<0>(sm.gates, w, r, g, b);
+            gate_scan<0, kCt>(sm.gates, w, r, g, b);
         else
-            gate_scan<1>(sm.gates, w, r, g, b);
+            gate_scan<1, kCt>(sm.gates, w, r, g, b);
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct) {
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            if (ct >= kCt) {  // no data: total log-gate 0 (the scan of the marks reads every channel)
+                if (w == 0 && r == 0) *reinterpret_cast<f32x4 *>(&logdec[(size_t(unit) * 2 + dir) * kD + 16 * ct + 4 * g]) = zero;
+                continue;
+            }
             T[ct] = mfma(col_frag(sm.gates, 16 * ct, 1, r, g), ones, mfma(col_frag(sm.gates, 16 * ct, 0, r, g), ones, zero));
             const f32x4 qv = unpack4(qr[ct]), kv = unpack4(kr[ct]);
             f32x4 qs, ks;
@@ -386,19 +396,23 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_local_kernel(
                 *reinterpret_cast<f32x4 *>(&logdec[(size_t(unit) * 2 + dir) * kD + 16 * ct + 4 * g]) = T[ct];
         }
         __syncthreads();
-        // U^T[j][i] = sum_t v[t][j] kh[t][i],  W^T[j][i] = sum_t do'[t][j] q~[t][i]: the wave takes rows
-        // i = 16w.., the lane ends up with four consecutive columns j of row 16w + r
+        // U^T[j][i] = sum_t v[t][j] kh[t][i],  W^T[j][i] = sum_t do'[t][j] q~[t][i]: a wave takes 16 rows
+        // i (and, with two row tiles only, half of the column tiles), the lane ends up with four
+        // consecutive columns j of its row
         uint16_t *U = mats + size_t(2 * dir) * kMat, *W = U + kMat;
+        const int it = kCt == 4 ? w : (w & 1);          // row tile
+        const int mt0 = kCt == 4 ? 0 : 2 * (w >> 1);    // first column tile
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
+        for (int mi = 0; mi < kCt; ++mi) {
+            const int mt = mt0 + mi;
             f32x4 u = {0.f, 0.f, 0.f, 0.f}, x = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                u = mfma(col_frag(sm.v, 16 * mt, kk, r, g), col_frag(sm.kh, 16 * w, kk, r, g), u);
-                x = mfma(col_frag(sm.dout, 16 * mt, kk, r, g), col_frag(sm.qt, 16 * w, kk, r, g), x);
+                u = mfma(col_frag(sm.v, 16 * mt, kk, r, g), col_frag(sm.kh, 16 * it, kk, r, g), u);
+                x = mfma(col_frag(sm.dout, 16 * mt, kk, r, g), col_frag(sm.qt, 16 * it, kk, r, g), x);
             }
-            *reinterpret_cast<uint2 *>(&U[(16 * w + r) * kD + 16 * mt + 4 * g]) = pack4(u);
-            *reinterpret_cast<uint2 *>(&W[(16 * w + r) * kD + 16 * mt + 4 * g]) = pack4(x);
+            *reinterpret_cast<uint2 *>(&U[(16 * it + r) * kD + 16 * mt + 4 * g]) = pack4(u);
+            *reinterpret_cast<uint2 *>(&W[(16 * it + r) * kD + 16 * mt + 4 * g]) = pack4(x);
         }
     }
 }
@@ -410,17 +424,17 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_local_kernel(
 // 64 chunks per slab: 69 / 66 / 62 / 56 us for 4 / 8 / 16 / 32 chunks ahead; with 4 chunks per slab
 // the deep version only pays for its longer prologue, 25 us against 17 us).
 constexpr int kScanThreads = 256;
-constexpr int kScanParts = 1024 / kScanThreads;
 
-template <int kScanAhead>
+template <int kScanAhead, int kCt>
 __global__ __launch_bounds__(kScanThreads) void bigla_bwd_chunk_scan_kernel(uint16_t *__restrict__ states,
                                                                        const float *__restrict__ logdec,
                                                                        int *__restrict__ marks, int n_chunks)
 {
+    constexpr int kScanParts = kCt * 256 / kScanThreads;  // workgroups per matrix: 16 * kCt rows of 16 pieces
     const long slab = blockIdx.x / (4 * kScanParts);
     const int kind = (blockIdx.x / kScanParts) & 3, part = blockIdx.x % kScanParts;
     const int tid = threadIdx.x;
-    const int piece = part * kScanThreads + tid;  // 0..1023
+    const int piece = part * kScanThreads + tid;  // 0 .. 256 * kCt - 1
     const int row = piece >> 4;
     const int dir = kind >> 1;
     const bool adjoint = (kind & 1) != 0;
@@ -515,7 +529,7 @@ struct DirInputs {
     uint4 st[2], ad[2];
 };
 
-template <int DIR>
+template <int DIR, int kCt>
 __device__ __forceinline__ DirInputs fetch_dir(const SlabRows &gates, const uint16_t *mats, unsigned t0, int tid, int w,
                                                int lane)
 {
@@ -523,8 +537,11 @@ __device__ __forceinline__ DirInputs fetch_dir(const SlabRows &gates, const uint
     in.gates = fetch_rows(gates, t0, w, lane);
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        in.st[h] = reinterpret_cast<const uint4 *>(mats + size_t(2 * DIR) * kMat)[tid + kThreads * h];
-        in.ad[h] = reinterpret_cast<const uint4 *>(mats + size_t(2 * DIR + 1) * kMat)[tid + kThreads * h];
+        in.st[h] = in.ad[h] = make_uint4(0u, 0u, 0u, 0u);
+        if (2 * h < kCt) {  // piece tid + 256 h lies in rows 32h .. 32h + 31
+            in.st[h] = reinterpret_cast<const uint4 *>(mats + size_t(2 * DIR) * kMat)[tid + kThreads * h];
+            in.ad[h] = reinterpret_cast<const uint4 *>(mats + size_t(2 * DIR + 1) * kMat)[tid + kThreads * h];
+        }
     }
     return in;
 }
@@ -540,7 +557,7 @@ __device__ __forceinline__ void put_matrix(Tile &tile, const uint4 (&x)[2], int 
 
 // `in`: this direction's inputs, already requested; `next`: called once the contractions are done,
 // to request the other direction's.
-template <int DIR, class Next>
+template <int DIR, int kCt, class Next>
 __device__ __forceinline__ void chunk_direction(MainLds &sm, const DirInputs &in, const SlabRows &dg_rows, unsigned t0,
                                                 int tid, int w, int lane, int r, int g, const uint2 (&qr)[4],
                                                 const uint2 (&kr)[4], Grads &acc, Next next)
@@ -557,9 +574,9 @@ __device__ __forceinline__ void chunk_direction(MainLds &sm, const DirInputs &in
     f32x4 Ep[4];
     {
         f32x4 b[4];
-        gate_scan<DIR>(sm.gp, w, r, g, b);
+        gate_scan<DIR, kCt>(sm.gp, w, r, g, b);
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
+        for (int ct = 0; ct < kCt; ++ct) {
             const f32x4 qv = unpack4(qr[ct]), kv = unpack4(kr[ct]);
             f32x4 qs, ks;
 #pragma unroll
@@ -574,7 +591,7 @@ __device__ __forceinline__ void chunk_direction(MainLds &sm, const DirInputs &in
         }
     }
     // rowsum(S_in * A'): four threads per row, 16 columns each
-    {
+    if ((tid >> 2) < 16 * kCt) {
         const int row = tid >> 2, c0 = 16 * (tid & 3);
         float sum = 0.f;
 #pragma unroll
@@ -615,7 +632,7 @@ __device__ __forceinline__ void chunk_direction(MainLds &sm, const DirInputs &in
             for (int k2 = 0; k2 < 2; ++k2) {
                 dr = mfma(row_frag(sm.v, 16 * m, k2, r, g), own_d[k2], dr);     // dP[t own][s]
                 dc = mfma(row_frag(sm.dout, 16 * m, k2, r, g), own_v[k2], dc);  // dP[t][s own]
-                pc = mfma(row_frag(sm.qt, 16 * m, k2, r, g), own_k[k2], pc);    // P[t][s own]
+                if (2 * k2 < kCt) pc = mfma(row_frag(sm.qt, 16 * m, k2, r, g), own_k[k2], pc);  // P[t][s own]
             }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -655,21 +672,28 @@ __device__ __forceinline__ void chunk_direction(MainLds &sm, const DirInputs &in
         f32x4 X = zero, Yi = zero, Ye = zero, V = zero;
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
-            // X^T[c][t] = sum_s k~[s][c] dP[t][s] + sum_j S_in[c][j] do'[t][j]
-            const bf16x8 ak = token_frag(sm.kt, 16 * ct, kk, r, g);
-            X = mfma(ak, bXl[kk], X);
-            X = mfma(ak, bX[kk], X);
-            X = mfma(row_frag(sm.st, 16 * ct, kk, r, g), own_d[kk], X);
-            // Yi^T[c][s] = sum_t q~[t][c] dP[t][s],  Ye^T[c][s] = sum_j A'[c][j] v[s][j]
-            const bf16x8 aq = token_frag(sm.qt, 16 * ct, kk, r, g);
-            Yi = mfma(aq, bYl[kk], Yi);
-            Yi = mfma(aq, bY[kk], Yi);
-            Ye = mfma(row_frag(sm.ad, 16 * ct, kk, r, g), own_v[kk], Ye);
-            // dv^T[j][s] = sum_t do'[t][j] P[t][s] + sum_i A'[i][j] k~[s][i]
+            if (ct < kCt) {
+                // X^T[c][t] = sum_s k~[s][c] dP[t][s] + sum_j S_in[c][j] do'[t][j]
+                const bf16x8 ak = token_frag(sm.kt, 16 * ct, kk, r, g);
+                X = mfma(ak, bXl[kk], X);
+                X = mfma(ak, bX[kk], X);
+                X = mfma(row_frag(sm.st, 16 * ct, kk, r, g), own_d[kk], X);
+                // Yi^T[c][s] = sum_t q~[t][c] dP[t][s],  Ye^T[c][s] = sum_j A'[c][j] v[s][j]
+                const bf16x8 aq = token_frag(sm.qt, 16 * ct, kk, r, g);
+                Yi = mfma(aq, bYl[kk], Yi);
+                Yi = mfma(aq, bY[kk], Yi);
+                Ye = mfma(row_frag(sm.ad, 16 * ct, kk, r, g), own_v[kk], Ye);
+            }
+            // dv^T[j][s] = sum_t do'[t][j] P[t][s] + sum_i A'[i][j] k~[s][i]   (column tile j = ct)
             const bf16x8 ad = token_frag(sm.dout, 16 * ct, kk, r, g);
             V = mfma(ad, bPl[kk], V);
             V = mfma(ad, bP[kk], V);
-            V = mfma(col_frag(sm.ad, 16 * ct, kk, r, g), own_k[kk], V);
+            if (2 * kk < kCt) V = mfma(col_frag(sm.ad, 16 * ct, kk, r, g), own_k[kk], V);
+        }
+        if (ct >= kCt) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc.dv[ct][e] += V[e];
+            continue;
         }
         // The summands of the gate gradient take q~ and k~ as the contractions saw them (rounded to
         // bf16): sum_{t>=u} q~ * X - sum_{s>=u} k~ * Yi is then, term by term, the sum over the pairs
@@ -693,7 +717,9 @@ __device__ __forceinline__ void chunk_direction(MainLds &sm, const DirInputs &in
         constexpr int kFar = DIR == 0 ? 1 : 0;  // E1 accumulates from the far side of the direction
         f32x4 dg[4];
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
+        for (int ct = kCt; ct < 4; ++ct) dg[ct] = zero;
+#pragma unroll
+        for (int ct = 0; ct < kCt; ++ct) {
             f32x4 t1, t2;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -710,7 +736,7 @@ __device__ __forceinline__ void chunk_direction(MainLds &sm, const DirInputs &in
         }
         __syncthreads();  // totals visible; every wave is done with S_in, whose tile carries dg out
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
+        for (int ct = 0; ct < kCt; ++ct) {
             f32x4 s = *reinterpret_cast<const f32x4 *>(&sm.R[16 * ct + 4 * g]);
 #pragma unroll
             for (int w2 = 0; w2 < 4; ++w2) {
@@ -727,6 +753,7 @@ __device__ __forceinline__ void chunk_direction(MainLds &sm, const DirInputs &in
     }
 }
 
+template <int kCt>
 __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_main_kernel(
     const void *__restrict__ q_all, const void *__restrict__ k_all, const void *__restrict__ v_all,
     const void *__restrict__ gf_all, const void *__restrict__ gb_all, const void *__restrict__ do_all,
@@ -757,7 +784,7 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_main_kernel(
         put_rows<false>(sm.v, cv, w, lane);
         put_rows<true>(sm.dout, cd, w, lane);
     }
-    const DirInputs in_f = fetch_dir<0>(gf, mats, t0, tid, w, lane);
+    const DirInputs in_f = fetch_dir<0, kCt>(gf, mats, t0, tid, w, lane);
     take_own(sm.qt, w, r, g, qr);
     take_own(sm.kt, w, r, g, kr);
 
@@ -765,9 +792,9 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_bwd_chunk_main_kernel(
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) acc.dq[ct] = acc.dk[ct] = acc.dv[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
     DirInputs in_b;
-    chunk_direction<0>(sm, in_f, dgf, t0, tid, w, lane, r, g, qr, kr, acc,
-                       [&]() { in_b = fetch_dir<1>(gb, mats, t0, tid, w, lane); });
-    chunk_direction<1>(sm, in_b, dgb, t0, tid, w, lane, r, g, qr, kr, acc, []() {});
+    chunk_direction<0, kCt>(sm, in_f, dgf, t0, tid, w, lane, r, g, qr, kr, acc,
+                            [&]() { in_b = fetch_dir<1, kCt>(gb, mats, t0, tid, w, lane); });
+    chunk_direction<1, kCt>(sm, in_b, dgb, t0, tid, w, lane, r, g, qr, kr, acc, []() {});
 
     store_own(sm.st, slab_rows(dq_all, slab, L, heads_token_major, dk), t0, w, lane, r, g, acc.dq);
     store_own(sm.ad, slab_rows(dk_all, slab, L, heads_token_major, dk), t0, w, lane, r, g, acc.dk);
@@ -794,22 +821,31 @@ hipError_t bigla_bwd_chunk_launch(const void *q, const void *k, const void *v, c
 {
     const int n_chunks = chunks_of(L);
     const long units = BH * n_chunks;
-    if (units > 0x7fffffffL || BH * 4 * kScanParts > 0x7fffffffL) return hipErrorInvalidValue;
+    if (units > 0x7fffffffL || BH * 16 > 0x7fffffffL) return hipErrorInvalidValue;
     Workspace ws;
     char *base = static_cast<char *>(workspace);
     ws.states = reinterpret_cast<uint16_t *>(base);
     ws.logdec = reinterpret_cast<float *>(base + states_bytes(BH, L));
     ws.marks = reinterpret_cast<int *>(base + states_bytes(BH, L) + logdec_bytes(BH, L));
-    hipLaunchKernelGGL(bigla_bwd_chunk_local_kernel, dim3((unsigned)units), dim3(kThreads), 0, stream, q, k, v, g_fwd,
-                       g_bwd, d_out, ws.states, ws.logdec, L, heads_token_major, n_chunks, dk_);
-    if (n_chunks > 16)
-        hipLaunchKernelGGL(bigla_bwd_chunk_scan_kernel<32>, dim3((unsigned)(BH * 4 * kScanParts)), dim3(kScanThreads), 0, stream,
-                           ws.states, ws.logdec, ws.marks, n_chunks);
+    auto launch = [&](auto ct) {
+        constexpr int kCt = decltype(ct)::value;
+        const dim3 scan_grid((unsigned)(BH * 4 * (kCt * 256 / kScanThreads)));
+        hipLaunchKernelGGL(bigla_bwd_chunk_local_kernel<kCt>, dim3((unsigned)units), dim3(kThreads), 0, stream, q, k, v,
+                           g_fwd, g_bwd, d_out, ws.states, ws.logdec, L, heads_token_major, n_chunks, dk_);
+        if (n_chunks > 16)
+            hipLaunchKernelGGL((bigla_bwd_chunk_scan_kernel<32, kCt>), scan_grid, dim3(kScanThreads), 0, stream, ws.states,
+                               ws.logdec, ws.marks, n_chunks);
+        else
+            hipLaunchKernelGGL((bigla_bwd_chunk_scan_kernel<8, kCt>), scan_grid, dim3(kScanThreads), 0, stream, ws.states,
+                               ws.logdec, ws.marks, n_chunks);
+        hipLaunchKernelGGL(bigla_bwd_chunk_main_kernel<kCt>, dim3((unsigned)units), dim3(kThreads), 0, stream, q, k, v,
+                           g_fwd, g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, ws.states, ws.marks, L, heads_token_major,
+                           n_chunks, dk_);
+    };
+    if (dk_ == kD)
+        launch(std::integral_constant<int, 4>{});
     else
-        hipLaunchKernelGGL(bigla_bwd_chunk_scan_kernel<8>, dim3((unsigned)(BH * 4 * kScanParts)), dim3(kScanThreads), 0, stream,
-                           ws.states, ws.logdec, ws.marks, n_chunks);
-    hipLaunchKernelGGL(bigla_bwd_chunk_main_kernel, dim3((unsigned)units), dim3(kThreads), 0, stream, q, k, v, g_fwd,
-                       g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, ws.states, ws.marks, L, heads_token_major, n_chunks, dk_);
+        launch(std::integral_constant<int, 2>{});
     return hipGetLastError();
 }
 
