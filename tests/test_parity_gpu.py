@@ -565,6 +565,15 @@ def _check_bwd(s, dtype, layout, plan, slabs=None, what=""):
         ratio = float(np.max(np.abs(g64 - r) / bound))
         worst = max(worst, ratio)
         assert ratio <= 1.0, f"{what} {name} ({plan}): error {ratio:.3f} x the bound"
+        # In aggregate the error is far below the element bound: from one chunk of tokens on, its rms
+        # per slab stays under 0.5 % of the gradient's own rms (bf16: output rounding 0.17 %, operand
+        # rounding of the chunkwise kernels up to 0.33 % measured) and under 2e-6 of it in fp32.
+        # (A handful of tokens is a handful of q.k dot products whose cancellation the rounded
+        # operands do not share; only the element bound applies there.)
+        if r.shape[2] >= 64:
+            scale = rms(r) + (summand if name.startswith("dg") else 0.0)
+            agg = float(np.max(rms(g64 - r) / np.maximum(scale, 1e-30)))
+            assert agg <= (5e-3 if dtype == "bf16" else 2e-6), f"{what} {name} ({plan}): rms error {agg:.2e} of the rms"
     return worst
 
 
