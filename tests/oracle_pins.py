@@ -473,5 +473,36 @@ def pin_bwd_inert_gates_linearity_slabs(bwd):
         assert np.array_equal(b[1], a[1]) and np.array_equal(b[0, 0], a[0, 0])
 
 
+def pin_bwd_library_autodiff(bwd):
+    """Reverse-mode differentiation by a library (PyTorch autograd, CPU, fp64) of a vectorised
+    explicit-product form: weights exp(difference of cumulative log-gates) under a mask, no
+    recurrence and no code of the oracle.  The form itself is first held to the brute-force
+    expansion; its gradient then pins all five gradients at a size finite differences do not
+    reach, to rounding."""
+    import torch
+
+    q, k, v, gf, gb = _draw(29, B=1, H=2, L=9, dk=3, dv=4, gate_scale=1.2)
+    d_out = _rng(30).standard_normal(v.shape)
+    t = [torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (q, k, v, gf, gb)]
+    tq, tk, tv, tgf, tgb = t
+    L = q.shape[2]
+    cf = torch.cumsum(tgf, dim=2)                         # sum_{j<=t} gf_j
+    cb = torch.cumsum(tgb, dim=2) - tgb                   # sum_{j<t}  gb_j
+    idx = torch.arange(L)
+    lower = (idx[None, :] <= idx[:, None]).to(torch.float64)   # [t, i]: i <= t
+    upper = (idx[None, :] >= idx[:, None]).to(torch.float64)   # [t, i]: i >= t
+    # decay from i to t, forward: prod_{j=i+1..t} a_fwd_j; backward: prod_{j=t..i-1} a_bwd_j
+    df = torch.exp((cf[:, :, :, None, :] - cf[:, :, None, :, :]) * lower[None, None, :, :, None])
+    db = torch.exp((cb[:, :, None, :, :] - cb[:, :, :, None, :]) * upper[None, None, :, :, None])
+    wf = torch.einsum("bhtc,bhic,bhtic->bhti", tq, tk, df) * lower
+    wb = torch.einsum("bhtc,bhic,bhtic->bhti", tq, tk, db) * upper
+    out = 0.5 * torch.einsum("bhti,bhij->bhtj", wf + wb, tv)
+    _close(out.detach().numpy(), quadratic_form(q, k, v, gf, gb), 1e-12)
+    (out * torch.tensor(d_out)).sum().backward()
+    got = bwd(q, k, v, gf, gb, d_out)
+    for g, ref in zip(got, t):
+        _close(g, ref.grad.numpy(), 1e-11)
+
+
 BWD_PINS = (pin_bwd_finite_differences, pin_bwd_gates_closed, pin_bwd_gates_open, pin_bwd_reversal_symmetry,
-            pin_bwd_inert_gates_linearity_slabs)
+            pin_bwd_inert_gates_linearity_slabs, pin_bwd_library_autodiff)
