@@ -141,6 +141,32 @@ def test_bigla_mixed_forms_in_one_call(B, H, L, dk):
 
 
 @pytest.mark.parametrize("layout", ("bhld", "blhd"))
+def test_bigla_many_short_slabs(layout):
+    """8192 slabs of twenty tokens: one-chunk sequences, a grid of thousands of workgroups (16 times
+    what the chip holds at once), forward and gradient."""
+    import torch
+    from paper_2405_18425_amd import binding as vb
+
+    w = wl.Workload("many", B=512, H=16, Hg=1, Wg=20, dk=64, dv=64, dtype="bf16", gate_mu=0.0)
+    _say(f"bigla many slabs {w} {layout}")
+    s = _bwd_inputs(w, seed=31)
+    t = {n: wl.to_torch(a, "bf16", "cuda:0") for n, a in s.items()}
+    if layout == "blhd":
+        t = {n: a.transpose(1, 2).contiguous() for n, a in t.items()}
+    out = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], layout=layout)
+    torch.cuda.synchronize()
+    if layout == "blhd":
+        out = out.transpose(1, 2).contiguous()
+    # a slab of twenty tokens has little scale of its own (a few hundred cancelling dot products, and
+    # 8192 slabs to pick the unluckiest from): the floor of the bound is the rms over all slabs
+    flat = lambda a: a.reshape(1, 1, -1, a.shape[-1])
+    assert_close(flat(wl.widen(wl.from_torch(out, "bf16"), "bf16")), flat(run_bigla_oracle(s, "bf16")), TOL["bf16"],
+                 "many slabs")
+    worst = _check_bwd(s, "bf16", layout, "auto", what="many slabs", pool=True)
+    _say(f"  gradient: worst error / bound = {worst:.3f}")
+
+
+@pytest.mark.parametrize("layout", ("bhld", "blhd"))
 def test_bigla_very_long_sequence(layout):
     """One slab pair of 65 541 tokens (1025 chunks, a ragged tail of 5): hundreds of segments per
     slab, byte offsets beyond 2^23 inside a slab, both layouts."""
@@ -566,9 +592,11 @@ def _bwd_inputs(w, seed):
     return s
 
 
-def _check_bwd(s, dtype, layout, plan, slabs=None, what=""):
+def _check_bwd(s, dtype, layout, plan, slabs=None, what="", pool=False):
     """bigla_bwd on the stored inputs s against the oracle's gradient (on all slabs, or on a
-    sample of (b, h) slabs: a slab's gradients depend on that slab only)."""
+    sample of (b, h) slabs: a slab's gradients depend on that slab only).  pool: the rms that
+    floors the bound is taken over all slabs together (slabs of a few tokens have no scale of
+    their own: a handful of cancelling dot products)."""
     import torch
     from paper_2405_18425_amd import binding as vb
     import oracle
@@ -585,6 +613,10 @@ def _check_bwd(s, dtype, layout, plan, slabs=None, what=""):
         wd = {n: np.stack([a[b, h] for (b, h) in slabs])[None] for n, a in wd.items()}
         got = [np.stack([a[b, h] for (b, h) in slabs])[None] for a in got]
     ref = oracle.bigla_bwd(*(wd[n] for n in BWD_NAMES))
+    if pool:
+        flat = lambda a: a.reshape(1, 1, -1, a.shape[-1])
+        wd = {n: flat(a) for n, a in wd.items()}
+        got, ref = [flat(a) for a in got], [flat(a) for a in ref]
     # The gate gradients are running sums of q * dq - k * dk (Section 4.2.1 differentiated): their
     # rounding error scales with those summands, not with the result, which is exactly zero where
     # a gate is inert (g_fwd of the first token, g_bwd of the last) and can be small elsewhere.
