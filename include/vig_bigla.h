@@ -4,8 +4,10 @@
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never
- *     allocates, frees or synchronises; work is enqueued on `stream` (a hipStream_t passed
- *     as void*, NULL = the default stream) and the call returns at once.
+ *     allocates or frees device memory and never synchronises; work is enqueued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and the call returns at once.
+ *     The one exception is the measurement aid at the end of this header: vig_timing_enable(1)
+ *     creates a pool of HIP events, and vig_timing_collect waits for them.
  *   - Tensors are dense, row-major, innermost index = feature.  All tensors of one call
  *     share `dtype` (vig_dtype).  VIG_BF16: bf16 in, fp32 accumulate, bf16 out rounded to
  *     nearest even.  VIG_F32: fp32 throughout.

@@ -49,14 +49,6 @@ namespace vig {
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-
 constexpr int kC = 64;       // chunk length (tokens)
 constexpr int kD = 64;       // dk = dv
 constexpr int kPitch = 72;   // LDS row pitch in bf16 elements
@@ -67,69 +59,10 @@ constexpr size_t kMat = size_t(kD) * kD;  // elements of one state matrix
 
 typedef uint16_t Tile[kC][kPitch];
 
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-__device__ __forceinline__ uint32_t pack2(float lo, float hi)
-{
-    f32x2 a = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2));
-}
-__device__ __forceinline__ uint2 pack4(const f32x4 &p) { return make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3])); }
-
-__device__ __forceinline__ f32x4 unpack4(const uint2 &u)
-{
-    return f32x4{bf16_lo_to_f32(u.x), bf16_hi_to_f32(u.x), bf16_lo_to_f32(u.y), bf16_hi_to_f32(u.y)};
-}
-
-__device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-}
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_or_zero(float x)
-{
-    // lanes whose DPP source falls outside the 16-lane row receive 0
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
-}
-
-// Inclusive scan over the 16 lanes of a DPP row (the 16 tokens of a wave at fixed g): prefix sums
-// (SUFFIX 0) or suffix sums (SUFFIX 1); row_total hands every lane the scan's last value.
-template <int SUFFIX>
-__device__ __forceinline__ float row_scan(float x)
-{
-    if (SUFFIX == 0) {
-        x += dpp_or_zero<0x111>(x);  // row_shr:1
-        x += dpp_or_zero<0x112>(x);
-        x += dpp_or_zero<0x114>(x);
-        x += dpp_or_zero<0x118>(x);
-    } else {
-        x += dpp_or_zero<0x101>(x);  // row_shl:1
-        x += dpp_or_zero<0x102>(x);
-        x += dpp_or_zero<0x104>(x);
-        x += dpp_or_zero<0x108>(x);
-    }
-    return x;
-}
 template <int SUFFIX>
 __device__ __forceinline__ float row_total(float scanned)
 {
     return SUFFIX == 0 ? dpp_or_zero<0x15f>(scanned) : dpp_or_zero<0x150>(scanned);  // row_newbcast:15 / :0
-}
-
-// Transposing LDS read: the 16 lanes of a row fetch a 4 (rows) x 16 (columns) bf16 patch of a
-// row-major tile; lane n of the row receives the 4 rows of column n and supplies the address of
-// row n/4, columns 4*(n%4).. of the patch.
-__device__ __forceinline__ s16x4 lds_read_tr(const uint16_t *p)
-{
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
-}
-
-__device__ __forceinline__ bf16x8 join(s16x4 lo, s16x4 hi)
-{
-    typedef __attribute__((ext_vector_type(8))) short s16x8;
-    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, v);
 }
 
 // MFMA operand whose 16 rows (A) or columns (B) are tile rows row0..row0+15 and whose contraction
@@ -197,14 +130,8 @@ __device__ __forceinline__ SlabRows slab_rows(const void *base, long slab, int L
                              : size_t(slab) * L;
     const unsigned pitch = 2u * unsigned(width) * unsigned(heads_token_major ? heads_token_major : 1);
     const unsigned extent = unsigned(L - 1) * pitch + 2u * unsigned(width);
-    const uintptr_t a = reinterpret_cast<uintptr_t>(static_cast<const char *>(base) + first * (2 * size_t(width)));
-    // (readfirstlane returns a signed int: widen through unsigned, not by sign extension)
-    const uintptr_t lo = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a))));
-    const uintptr_t hi = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a >> 32))));
     SlabRows s;
-    s.rsrc = __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(lo | (hi << 32)), 0,
-                                               int(unsigned(__builtin_amdgcn_readfirstlane(int(extent)))),
-                                               0x00020000);
+    s.rsrc = slab_resource(static_cast<const char *>(base) + first * (2 * size_t(width)), extent);
     s.pitch = pitch;
     s.pieces = unsigned(width) / 8u;
     return s;

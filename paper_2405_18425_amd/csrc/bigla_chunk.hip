@@ -84,12 +84,6 @@ namespace vig {
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-
 constexpr int kC = 64;          // chunk length (tokens)
 constexpr int kD = 64;          // dk = dv
 constexpr int kPitch = 72;      // LDS row pitch in bf16 elements (64 + 8: 16-byte aligned, bank-staggered)
@@ -100,31 +94,6 @@ constexpr float kGateFloorLog2 = -8.0f * kLog2e;  // per-step floor of the log-g
 constexpr float kFastRange = 60.0f;  // largest chunk log-decay (nats, any channel) the fast form accepts
 
 // ---- small device helpers ------------------------------------------------------------------
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_or_zero(float x)
-{
-    // lanes whose DPP source falls outside the 16-lane row receive 0
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
-}
-
-// Inclusive scan over the 16 lanes of a DPP row: prefix (DIR 0) or suffix (DIR 1).
-template <int DIR>
-__device__ __forceinline__ float row_scan(float x)
-{
-    if (DIR == 0) {
-        x += dpp_or_zero<0x111>(x);  // row_shr:1
-        x += dpp_or_zero<0x112>(x);
-        x += dpp_or_zero<0x114>(x);
-        x += dpp_or_zero<0x118>(x);
-    } else {
-        x += dpp_or_zero<0x101>(x);  // row_shl:1
-        x += dpp_or_zero<0x102>(x);
-        x += dpp_or_zero<0x104>(x);
-        x += dpp_or_zero<0x108>(x);
-    }
-    return x;
-}
 
 // Row-wide broadcasts (row_newbcast:n).  In scan order the far-edge lane holds the sub-block
 // total (lane 15 for the prefix scan, lane 0 for the suffix scan); the middle lane is the last
@@ -138,15 +107,6 @@ template <int DIR>
 __device__ __forceinline__ float bcast_mid(float x)
 {
     return DIR == 0 ? dpp_or_zero<0x157>(x) : dpp_or_zero<0x158>(x);
-}
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-__device__ __forceinline__ uint32_t pack2(float lo, float hi)
-{
-    f32x2 a = {lo, hi};
-    bf16x2 b = __builtin_convertvector(a, bf16x2);  // v_cvt_pk_bf16_f32, round to nearest even
-    return __builtin_bit_cast(uint32_t, b);
 }
 
 __device__ __forceinline__ bf16x8 pack8(const float *f)
@@ -167,26 +127,6 @@ __device__ __forceinline__ void unpack8(const uint4 &u, float *f)
     f[6] = bf16_lo_to_f32(u.w); f[7] = bf16_hi_to_f32(u.w);
 }
 
-__device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-}
-
-// Transposing LDS read: the 16 lanes of a row fetch a 4 (tokens) x 16 (columns) bf16 patch of a
-// row-major tile; lane n of the row receives the 4 tokens of column n.  Lane n supplies the
-// address of token n/4, columns 4*(n%4).. of the patch.
-__device__ __forceinline__ s16x4 lds_read_tr(const uint16_t *p)
-{
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
-}
-
-__device__ __forceinline__ bf16x8 join(s16x4 lo, s16x4 hi)
-{
-    typedef __attribute__((ext_vector_type(8))) short s16x8;
-    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, v);
-}
-
 // 16 bf16 values of one token held by a lane, packed two per dword
 struct Row16 {
     uint4 p[2];
@@ -197,25 +137,6 @@ struct Row16 {
 struct StagedRows {
     uint4 p[2];
 };
-
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-
-// One slab's rows of a tensor, reached through a buffer resource whose extent ends with the slab's
-// last token: the byte offset of a row is 32 bits wide, and a token past the sequence lies beyond
-// the extent, where the bounds check of the access returns zeros for a load (k = v = 0 and
-// log-gate 0 make such a token a no-op) and drops a store -- no clamp, no branch, no select.
-// The resource is the same in every lane; saying so keeps it in scalar registers.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const void *first_row, unsigned extent_bytes)
-{
-    const uintptr_t a = reinterpret_cast<uintptr_t>(first_row);
-    // (readfirstlane returns a signed int: widen through unsigned, not by sign extension)
-    const uintptr_t lo = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a))));
-    const uintptr_t hi = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a >> 32))));
-    const unsigned kRawDwords = 0x00020000u;  // untyped 32-bit data, bounds check on the byte offset
-    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(lo | (hi << 32)), 0,
-                                             int(unsigned(__builtin_amdgcn_readfirstlane(int(extent_bytes)))),
-                                             int(kRawDwords));
-}
 
 // Byte offsets of a lane's two pieces inside a chunk, for rows of kRow elements `pitch` bytes apart
 // (head-major [B, H, L, d]: pitch = 2 * kRow; token-major [B, L, H, d]: pitch = 2 * H * kRow).
@@ -482,8 +403,6 @@ __device__ __forceinline__ bf16x8 token_operand(const uint16_t (*tile)[kPitch], 
     const int tr_row = 4 * g + (r >> 2), tr_col = col0 + 4 * (r & 3);
     return join(lds_read_tr(&tile[16 * s0 + tr_row][tr_col]), lds_read_tr(&tile[16 * s1 + tr_row][tr_col]));
 }
-
-__device__ __forceinline__ uint2 pack4(const f32x4 &p) { return make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3])); }
 
 // The lane's column of the triangular 0/1 matrix of the gate scan, as the B operand of the two
 // K-steps over the chunk's tokens: slot s of step p is token i = 16*(2p + s/4) + 4g + s%4 and

@@ -34,11 +34,6 @@ constexpr int kThreads = 256;
 constexpr int kTokensPerWave = 16;
 constexpr int kPersistentBlocks = 768;  // three workgroups per CU walk the token tiles
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 // log(sigmoid(z)) = min(z, 0) - log(1 + exp(-|z|)), finite for every finite z.  The bare hardware
 // exp2 / log2 serve: the exponential's argument is <= 0 (an underflow to 0 is the right limit) and
@@ -49,13 +44,6 @@ __device__ __forceinline__ float log_sigmoid(float z)
     const float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
     const float e = __builtin_amdgcn_exp2f(-kLog2e * fabsf(z));
     return fmaf(-kLn2, __builtin_amdgcn_logf(1.f + e), fminf(z, 0.f));
-}
-
-__device__ __forceinline__ uint32_t pack2(float lo, float hi)
-{
-    f32x2 a = {lo, hi};
-    bf16x2 b = __builtin_convertvector(a, bf16x2);  // v_cvt_pk_bf16_f32, round to nearest even
-    return __builtin_bit_cast(uint32_t, b);
 }
 
 // Copy w2 ([width][16] bf16, 2 x 16 bytes per row) and the bias into LDS, eight loads in flight per
@@ -190,7 +178,6 @@ __global__ __launch_bounds__(kThreads) void gate_producer_bf16_kernel(
                 const size_t row = token_major ? (size_t(b_idx) * L + t_idx) * H + h : (size_t(b_idx) * H + h) * L + t_idx;
                 uint4 *dst = reinterpret_cast<uint4 *>((bwd ? g_bwd : g_fwd) + row * dk + j);
                 // streaming stores (nothing here reads the gates back): measured 2 us faster
-                typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
                 __builtin_nontemporal_store(u32x4{packed[0], packed[1], packed[2], packed[3]},
                                             reinterpret_cast<u32x4 *>(dst));
                 __builtin_nontemporal_store(u32x4{packed[4], packed[5], packed[6], packed[7]},

@@ -22,8 +22,6 @@ namespace {
 
 // A thread's slice of one pixel: 4 consecutive channels (8 bytes of bf16, 16 bytes of fp32),
 // widened to fp32 lanes.
-typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 template <typename T>
 struct vec4;
@@ -72,19 +70,6 @@ constexpr int kThreads = 256;
 // offset of a tap off the grid (or a row past it): beyond every resource's extent, so the load
 // returns zeros and the store is dropped
 constexpr unsigned kOffGrid = 0xfffffff0u;
-
-// Buffer resource over `bytes` bytes at p (the same in every lane: kept in scalar registers).
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const void *p, unsigned bytes)
-{
-    const uintptr_t a = reinterpret_cast<uintptr_t>(p);
-    // (readfirstlane returns a signed int: widen through unsigned, not by sign extension)
-    const uintptr_t lo = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a))));
-    const uintptr_t hi = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a >> 32))));
-    const unsigned kRawDwords = 0x00020000u;  // untyped 32-bit data, bounds check on the byte offset
-    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(lo | (hi << 32)), 0,
-                                             int(unsigned(__builtin_amdgcn_readfirstlane(int(bytes)))),
-                                             int(kRawDwords));
-}
 
 // One slab (batch element, head) per group of `blocks_per_slab` consecutive workgroups, so that
 // everything that depends on the slab is uniform over a workgroup.

@@ -39,6 +39,11 @@ int hip_status(hipError_t e)
     return VIG_ERR_HIP;
 }
 
+// The launch functions report hipGetLastError() after their launches.  That call returns the
+// thread's sticky error, which an unrelated earlier HIP call of the caller may have left behind:
+// it is cleared before anything is launched so that only this call's own error is reported.
+void clear_stale_hip_error() { (void)hipGetLastError(); }
+
 }  // namespace
 
 extern "C" {
@@ -89,6 +94,7 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
     // the chunkwise kernels address the rows of a slab (token-major: of a batch element) with 32-bit
     // byte offsets, up to one chunk past the sequence
     if (vig::bigla_chunk_supported(dk, dv, bf16) && !chunk_offsets_ok(L, H, layout)) return VIG_ERR_SHAPE;
+    clear_stale_hip_error();
     if (vig::bigla_chunk_supported(dk, dv, bf16))
         return hip_status(
             vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, heads_token_major, nullptr, workspace, s));
@@ -133,6 +139,7 @@ int bigla_bwd_plan(const void *q, const void *k, const void *v, const void *g_fw
         return VIG_ERR_ALIGN;
     const size_t need = bigla_bwd_workspace_bytes(B, H, L, dk_, dv_, dtype);
     if (!workspace || workspace_bytes < need) return VIG_ERR_WORKSPACE;
+    clear_stale_hip_error();
     return hip_status(vig::bigla_bwd_launch(q, k, v, g_fwd, g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, long(B) * H, L,
                                             dk_, dv_, dtype == VIG_BF16, layout == VIG_LAYOUT_BLHD ? H : 0,
                                             plan == VIG_BWD_RECURRENT, workspace, static_cast<hipStream_t>(stream)));
@@ -162,6 +169,7 @@ int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, con
     if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(gate_logits) || !aligned16(o_global) ||
         !aligned16(out))
         return VIG_ERR_ALIGN;
+    clear_stale_hip_error();
     return hip_status(vig::locality_gate_launch(x, w, bias, gate_logits, o_global, out, B, H, Hg, Wg, dv,
                                                 dtype == VIG_BF16, layout == VIG_LAYOUT_BLHD ? 1 : 0,
                                                 static_cast<hipStream_t>(stream)));
@@ -222,6 +230,7 @@ int bigla_locality_fwd(const void *q, const void *k, const void *v, const void *
     const size_t need = bigla_workspace_bytes(B, H, L, dk, dv, dtype);
     if (need > 0 && (!workspace || workspace_bytes < need)) return VIG_ERR_WORKSPACE;
     const vig::LocalityFusion fusion = {x, w, bias, gate_logits, H, Hg, Wg};
+    clear_stale_hip_error();
     return hip_status(vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, long(B) * H, L, dk,
                                               layout == VIG_LAYOUT_BLHD ? H : 0, &fusion, workspace,
                                               static_cast<hipStream_t>(stream)));
@@ -239,6 +248,7 @@ int gate_producer_fwd(const void *x, const void *w1, const void *w2, const void 
     if (!aligned16(x) || !aligned16(w1) || !aligned16(w2) || !aligned16(bias) || !aligned16(g_fwd) ||
         !aligned16(g_bwd))
         return VIG_ERR_ALIGN;
+    clear_stale_hip_error();
     return hip_status(vig::gate_producer_launch(x, w1, w2, bias, g_fwd, g_bwd, B, H, L, D, dk, tau,
                                                 dtype == VIG_BF16, layout == VIG_LAYOUT_BLHD ? 1 : 0,
                                                 static_cast<hipStream_t>(stream)));

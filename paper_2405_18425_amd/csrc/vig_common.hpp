@@ -32,6 +32,87 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2_t));
 }
 
+// ---- vector types, packing and matrix-core helpers shared by the MFMA kernels ---------------
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+// 2^x on the hardware's own instruction (v_exp_f32): no range handling, an underflow to 0 is the
+// right limit wherever it is used
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return pack_bf16x2(lo, hi); }
+__device__ __forceinline__ uint2 pack4(const f32x4 &p) { return make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3])); }
+__device__ __forceinline__ f32x4 unpack4(const uint2 &u)
+{
+    return f32x4{bf16_lo_to_f32(u.x), bf16_hi_to_f32(u.x), bf16_lo_to_f32(u.y), bf16_hi_to_f32(u.y)};
+}
+
+__device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// lanes whose DPP source falls outside the 16-lane row receive 0
+template <int CTRL>
+__device__ __forceinline__ float dpp_or_zero(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+
+// Inclusive scan over the 16 lanes of a DPP row: prefix sums (SUFFIX 0) or suffix sums (SUFFIX 1).
+template <int SUFFIX>
+__device__ __forceinline__ float row_scan(float x)
+{
+    if (SUFFIX == 0) {
+        x += dpp_or_zero<0x111>(x);  // row_shr:1
+        x += dpp_or_zero<0x112>(x);
+        x += dpp_or_zero<0x114>(x);
+        x += dpp_or_zero<0x118>(x);
+    } else {
+        x += dpp_or_zero<0x101>(x);  // row_shl:1
+        x += dpp_or_zero<0x102>(x);
+        x += dpp_or_zero<0x104>(x);
+        x += dpp_or_zero<0x108>(x);
+    }
+    return x;
+}
+
+// Transposing LDS read: the 16 lanes of a row fetch a 4 (rows) x 16 (columns) bf16 patch of a
+// row-major tile; lane n of the row receives the 4 rows of column n and supplies the address of
+// row n/4, columns 4*(n%4).. of the patch.
+__device__ __forceinline__ s16x4 lds_read_tr(const uint16_t *p)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(p));
+}
+
+__device__ __forceinline__ bf16x8 join(s16x4 lo, s16x4 hi)
+{
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// Buffer resource over `extent_bytes` bytes at p.  Offsets into it are 32 bits wide, and an access
+// beyond the extent returns zeros (load) or is dropped (store): the bounds check of the hardware
+// stands in for clamps, branches and selects on ragged ends.  The resource is the same in every
+// lane; saying so keeps it in scalar registers.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const void *p, unsigned extent_bytes)
+{
+    const uintptr_t a = reinterpret_cast<uintptr_t>(p);
+    // (readfirstlane returns a signed int: widen through unsigned, not by sign extension)
+    const uintptr_t lo = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a))));
+    const uintptr_t hi = unsigned(__builtin_amdgcn_readfirstlane(int(unsigned(a >> 32))));
+    const unsigned kRawDwords = 0x00020000u;  // untyped 32-bit data, bounds check on the byte offset
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(lo | (hi << 32)), 0,
+                                             int(unsigned(__builtin_amdgcn_readfirstlane(int(extent_bytes)))),
+                                             int(kRawDwords));
+}
+
 template <typename T>
 struct io;  // element load/store in fp32 terms
 

@@ -13,9 +13,13 @@ struct Record {
     hipEvent_t start, stop;
 };
 
+// Event pairs are created by vig_timing_enable(1), never inside a launch: once the pool is used
+// up, further launches go unrecorded.
+constexpr size_t kPoolRecords = 16384;
+
 struct TimingState {
     bool on = false;
-    std::vector<Record> pool;  // events are created once and reused
+    std::vector<Record> pool;
     size_t used = 0;
 };
 
@@ -26,17 +30,10 @@ thread_local TimingState g_timing;
 LaunchTimer::LaunchTimer(KernelId id, hipStream_t stream) : slot_(-1), stream_(stream)
 {
     TimingState &t = g_timing;
-    if (!t.on) return;
-    if (t.used == t.pool.size()) {
-        Record r;
-        r.id = id;
-        if (hipEventCreate(&r.start) != hipSuccess) return;
-        if (hipEventCreate(&r.stop) != hipSuccess) {
-            (void)hipEventDestroy(r.start);
-            return;
-        }
-        t.pool.push_back(r);
-    }
+    if (!t.on || t.used == t.pool.size()) return;
+    // a stream under graph capture is left alone: event records would become nodes of the graph
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capture) != hipSuccess || capture != hipStreamCaptureStatusNone) return;
     slot_ = int(t.used++);
     t.pool[slot_].id = id;
     (void)hipEventRecord(t.pool[slot_].start, stream_);
@@ -53,8 +50,22 @@ extern "C" {
 
 int vig_timing_enable(int on)
 {
-    vig::g_timing.on = on != 0;
-    vig::g_timing.used = 0;
+    vig::TimingState &t = vig::g_timing;
+    t.on = on != 0;
+    t.used = 0;
+    if (t.on && t.pool.size() < vig::kPoolRecords) {
+        t.pool.reserve(vig::kPoolRecords);
+        while (t.pool.size() < vig::kPoolRecords) {
+            vig::Record r;
+            r.id = -1;
+            if (hipEventCreate(&r.start) != hipSuccess) return VIG_ERR_HIP;
+            if (hipEventCreate(&r.stop) != hipSuccess) {
+                (void)hipEventDestroy(r.start);
+                return VIG_ERR_HIP;
+            }
+            t.pool.push_back(r);
+        }
+    }
     return VIG_OK;
 }
 

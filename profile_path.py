@@ -2,7 +2,7 @@
 workload, plus one plain device-to-device copy of known size that calibrates FETCH_SIZE /
 WRITE_SIZE (bytes = counter * factor, factor = known copy bytes / counter of the copy kernel).
 
-    rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir> -o p -- python3 -m paper_2405_18425_amd.profile_path 4 3
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir> -o p -- python3 <repo>/profile_path.py 4 3
 
 A third argument D > 0 adds the forget-gate producer in front of every pass (block input of width D
 for the same B, L, H, dk), feeding the gates it makes to bigla_fwd.  A fourth argument 1 or 2 runs
@@ -13,12 +13,15 @@ bigla_bwd_plan with the exact token-by-token kernels only.
 """
 from __future__ import annotations
 
-import sys
-
 import torch
 
-from . import binding as vb
-from . import workloads as wl
+import os
+import sys
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+
+from paper_2405_18425_amd import binding as vb  # noqa: E402
+from paper_2405_18425_amd import workloads as wl  # noqa: E402
 
 COPY_BYTES = 256 << 20  # calibration copy: reads 256 MiB, writes 256 MiB
 
