@@ -35,7 +35,9 @@ typedef enum {
     VIG_ERR_ALIGN = -5,       /* a pointer is not 16-byte aligned                        */
     VIG_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than bigla_workspace_bytes()  */
     VIG_ERR_HIP = -7,         /* a HIP call failed; see vig_last_hip_error()             */
-    VIG_ERR_LAYOUT = -8       /* layout is not a vig_layout                              */
+    VIG_ERR_LAYOUT = -8,      /* layout is not a vig_layout                              */
+    VIG_ERR_SCRATCH_LIMIT = -9 /* bigla_fwd_static_scratch: the problem needs more scratch
+                                 than VIG_STATIC_SCRATCH_BYTES                           */
 } vig_status;
 
 typedef enum { VIG_F32 = 0, VIG_BF16 = 1 } vig_dtype;
@@ -97,6 +99,28 @@ int bigla_fwd(const void *q, const void *k, const void *v, const void *g_fwd, co
 int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
                      void *out, int B, int H, int L, int dk, int dv, int dtype, int layout,
                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * bigla_fwd_layout for callers that cannot allocate device memory or pass a workspace: code that
+ * runs under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch
+ * that bigla_fwd_layout takes from the caller lives here in an array that is part of the library
+ * itself (VIG_STATIC_SCRATCH_BYTES bytes per GPU, held from the first call on that GPU until the
+ * process ends); inputs and the output are still the caller's.  The call allocates and frees
+ * nothing, neither directly nor through another library.  The first call on a GPU looks up the
+ * array's address on that GPU (make it outside a capture).
+ *   - Arguments, numerics, results and errors as for bigla_fwd_layout (bit-identical results).
+ *   - A problem for which bigla_workspace_bytes(...) exceeds VIG_STATIC_SCRATCH_BYTES is rejected
+ *     with VIG_ERR_SCRATCH_LIMIT before anything is launched.  The limit holds each of the five
+ *     benchmark configurations (the largest, B=8, H=6, L=4096, needs 42 MB).
+ *   - Every call on one GPU uses that GPU's one array, whose contents are unspecified between
+ *     calls (nothing in it has to start at zero: each call writes what it later reads).  Calls
+ *     that overlap in time on one GPU -- on different streams or from different threads -- race on
+ *     it; order them on one stream or with events.
+ */
+#define VIG_STATIC_SCRATCH_BYTES (48u << 20)
+int bigla_fwd_static_scratch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                             void *out, int B, int H, int L, int dk, int dv, int dtype, int layout,
+                             void *stream);
 
 /*
  * BiGLA backward -- the gradient of bigla_fwd (Section 4.2.1, Eq. (BiGLA); the paper trains

@@ -18,13 +18,15 @@ LIB_PATH = os.path.join(_HERE, "libvig_bigla.so")
 VIG_OK = 0
 VIG_ERR_NULL, VIG_ERR_SHAPE, VIG_ERR_DTYPE, VIG_ERR_UNSUPPORTED = -1, -2, -3, -4
 VIG_ERR_ALIGN, VIG_ERR_WORKSPACE, VIG_ERR_HIP, VIG_ERR_LAYOUT = -5, -6, -7, -8
+VIG_ERR_SCRATCH_LIMIT = -9
+VIG_STATIC_SCRATCH_BYTES = 48 << 20
 VIG_F32, VIG_BF16 = 0, 1
 VIG_LAYOUT_BHLD, VIG_LAYOUT_BLHD = 0, 1
 LAYOUTS = {"bhld": VIG_LAYOUT_BHLD, "blhd": VIG_LAYOUT_BLHD}
 PLANS = {"auto": 0, "two_launches": 1, "fused_epilogue": 2}
 
 # every symbol include/vig_bigla.h declares
-EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "locality_gate_fwd",
+EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "bigla_fwd_static_scratch", "locality_gate_fwd",
            "locality_gate_fwd_layout", "bigla_locality_workspace_bytes", "bigla_locality_fwd", "gate_producer_fwd",
            "bigla_bwd_workspace_bytes", "bigla_bwd", "bigla_bwd_plan",
            "vig_status_str", "vig_last_hip_error", "vig_timing_enable",
@@ -56,6 +58,8 @@ def lib() -> ctypes.CDLL:
         L.bigla_fwd.restype = ci
         L.bigla_fwd_layout.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
         L.bigla_fwd_layout.restype = ci
+        L.bigla_fwd_static_scratch.argtypes = [vp] * 6 + [ci] * 7 + [vp]
+        L.bigla_fwd_static_scratch.restype = ci
         L.locality_gate_fwd.argtypes = [vp] * 6 + [ci] * 6 + [vp]
         L.locality_gate_fwd.restype = ci
         L.locality_gate_fwd_layout.argtypes = [vp] * 6 + [ci] * 7 + [vp]
@@ -130,12 +134,14 @@ def _layout_code(layout) -> int:
     return LAYOUTS[layout]
 
 
-def bigla_fwd(q, k, v, g_fwd, g_bwd, out=None, workspace=None, layout="bhld"):
+def bigla_fwd(q, k, v, g_fwd, g_bwd, out=None, workspace=None, layout="bhld", static_scratch=False):
     """BiGLA forward (Section 4.2.1).  q,k,g_fwd,g_bwd: [B,H,L,dk]; v: [B,H,L,dv] -> out [B,H,L,dv]
     (layout "bhld"), or all of them token-major, [B,L,H,d] (layout "blhd").
 
     g_* are LOG forget gates (<= 0).  `workspace` is an optional uint8 GPU tensor of at least
     bigla_workspace_bytes(...) bytes; one is allocated with torch when absent.
+    static_scratch=True calls bigla_fwd_static_scratch instead: the library's own per-GPU scratch
+    array serves as workspace and, given `out`, nothing is allocated.
     """
     lay = _layout_code(layout)
     q = _dev(q, "q")
@@ -156,6 +162,13 @@ def bigla_fwd(q, k, v, g_fwd, g_bwd, out=None, workspace=None, layout="bhld"):
         out = torch.empty(tuple(v.shape), dtype=q.dtype, device=q.device)
     out = _dev(out, "out", tuple(v.shape), q)
     code = _dtype_code(q)
+    if static_scratch:
+        with torch.cuda.device(q.device):
+            st = lib().bigla_fwd_static_scratch(q.data_ptr(), k.data_ptr(), v.data_ptr(), g_fwd.data_ptr(),
+                                                g_bwd.data_ptr(), out.data_ptr(), B, H, L, dk, dv, code, lay,
+                                                _stream_ptr(q.device))
+        _check(st, "bigla_fwd_static_scratch")
+        return out
     need = bigla_workspace_bytes(B, H, L, dk, dv, code)
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)

@@ -2,6 +2,8 @@
 // Every step of the path runs in the kernels of the other translation units.
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/vig_bigla.h"
 #include "vig_kernels.hpp"
 
@@ -43,6 +45,38 @@ int hip_status(hipError_t e)
 // thread's sticky error, which an unrelated earlier HIP call of the caller may have left behind:
 // it is cleared before anything is launched so that only this call's own error is reported.
 void clear_stale_hip_error() { (void)hipGetLastError(); }
+
+// ---- scratch of the entry point that allocates nothing ----------------------------------------
+// The workspace of bigla_fwd_static_scratch: one array per GPU, part of the library's code object,
+// held from the first use on that GPU until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; the device address it yields (one per device) is what the
+// kernels receive, exactly as they receive the caller's workspace in bigla_fwd_layout.
+static __device__ __align__(256) unsigned char scratch[VIG_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// The device address of `scratch` on the current device (looked up once per device), or nullptr
+// with the HIP error recorded.
+void *static_scratch()
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+    if (e != hipSuccess) {
+        g_last_hip_error = int(e);
+        return nullptr;
+    }
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+        g_last_hip_error = int(e != hipSuccess ? e : hipErrorInvalidSymbol);
+        return nullptr;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);  // concurrent first calls store the same address
+    return p;
+}
 
 }  // namespace
 
@@ -100,6 +134,21 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
             vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, heads_token_major, nullptr, workspace, s));
     return hip_status(vig::bigla_recurrent_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, dv, bf16,
                                                   heads_token_major, workspace, s));
+}
+
+int bigla_fwd_static_scratch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                             void *out, int B, int H, int L, int dk, int dv, int dtype, int layout, void *stream)
+{
+    // sizes first: an invalid problem reports its own error, a valid one that is too large the limit
+    if (B <= 0 || H <= 0 || L <= 0 || dk <= 0 || dv <= 0) return VIG_ERR_SHAPE;
+    if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
+    if (!head_dim_ok(dk) || !head_dim_ok(dv)) return VIG_ERR_UNSUPPORTED;
+    if (!sizes_ok(B, H, L, dk > dv ? dk : dv)) return VIG_ERR_SHAPE;
+    if (bigla_workspace_bytes(B, H, L, dk, dv, dtype) > size_t(VIG_STATIC_SCRATCH_BYTES)) return VIG_ERR_SCRATCH_LIMIT;
+    void *ws = static_scratch();
+    if (!ws) return VIG_ERR_HIP;
+    return bigla_fwd_layout(q, k, v, g_fwd, g_bwd, out, B, H, L, dk, dv, dtype, layout, ws,
+                            size_t(VIG_STATIC_SCRATCH_BYTES), stream);
 }
 
 size_t bigla_bwd_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype)
@@ -268,6 +317,9 @@ const char *vig_status_str(int status)
         case VIG_ERR_WORKSPACE: return "VIG_ERR_WORKSPACE: workspace missing or too small";
         case VIG_ERR_HIP: return "VIG_ERR_HIP: a HIP call failed (see vig_last_hip_error)";
         case VIG_ERR_LAYOUT: return "VIG_ERR_LAYOUT: layout is not a vig_layout";
+        case VIG_ERR_SCRATCH_LIMIT:
+            return "VIG_ERR_SCRATCH_LIMIT: the problem needs more scratch than the library's static buffer "
+                   "(VIG_STATIC_SCRATCH_BYTES) holds";
     }
     return "unknown vig_status";
 }

@@ -29,7 +29,7 @@ def test_header_and_exports_agree():
 
 
 def test_status_strings():
-    for code in range(-8, 1):
+    for code in range(-9, 1):
         s = vb.status_str(code)
         assert s and "unknown" not in s
     assert "unknown" in vb.status_str(5)
@@ -39,6 +39,27 @@ def test_status_strings():
 def call_bigla(q=PTR, k=PTR, v=PTR, gf=PTR, gb=PTR, out=PTR, B=1, H=1, L=8, dk=16, dv=16, dtype=vb.VIG_F32,
                ws=None, ws_bytes=0):
     return vb.lib().bigla_fwd(q, k, v, gf, gb, out, B, H, L, dk, dv, dtype, ws, ws_bytes, None)
+
+
+def test_static_scratch_validation_codes():
+    """The entry point that allocates nothing validates on the host like bigla_fwd_layout, and refuses
+    what its static array cannot hold (no GPU is touched by any of these calls)."""
+    f = vb.lib().bigla_fwd_static_scratch
+
+    def call(q=PTR, out=PTR, B=1, H=1, L=8, dk=16, dv=16, dtype=vb.VIG_BF16, layout=vb.VIG_LAYOUT_BHLD):
+        return f(q, PTR, PTR, PTR, PTR, out, B, H, L, dk, dv, dtype, layout, None)
+
+    assert call(B=0) == vb.VIG_ERR_SHAPE
+    assert call(dtype=9) == vb.VIG_ERR_DTYPE
+    assert call(dk=48) == vb.VIG_ERR_UNSUPPORTED
+    assert call(B=1 << 20, H=1 << 20, L=1 << 20) == vb.VIG_ERR_SHAPE
+    # the five benchmark configurations fit, a much larger problem does not
+    for B, H, L in ((64, 3, 196), (64, 6, 196), (16, 12, 1024), (8, 6, 4096)):
+        assert 0 < vb.bigla_workspace_bytes(B, H, L, 64, 64, vb.VIG_BF16) <= vb.VIG_STATIC_SCRATCH_BYTES
+    assert vb.bigla_workspace_bytes(64, 16, 8192, 64, 64, vb.VIG_BF16) > vb.VIG_STATIC_SCRATCH_BYTES
+    assert call(B=64, H=16, L=8192, dk=64, dv=64) == vb.VIG_ERR_SCRATCH_LIMIT
+    header = open(HEADER).read()
+    assert f"#define VIG_STATIC_SCRATCH_BYTES ({vb.VIG_STATIC_SCRATCH_BYTES >> 20}u << 20)" in header
 
 
 def test_bigla_validation_codes():
