@@ -80,8 +80,8 @@ size_t bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype);
  *   workspace / workspace_bytes: device scratch of at least bigla_workspace_bytes(...);
  *   may be NULL/0 when that function returns 0.
  *
- * Numerics: VIG_BF16 with dv = 64 and dk = 64 or 32 runs the chunkwise MFMA path (bf16 operands,
- * fp32 accumulation, fp32 carried state; dk = 32 is widened to 64 key channels with zeros
+ * Numerics: VIG_BF16 with dv = 64, dk = 64 or 32 and L >= 32 runs the chunkwise MFMA path (bf16
+ * operands, fp32 accumulation, fp32 carried state; dk = 32 is widened to 64 key channels with zeros
  * inside the kernels).  A 64-token chunk in which some channel decays by more
  * than 60 nats is evaluated in a range-safe form that treats per-step log gates below -8 as
  * -8 (alpha < 3.4e-4 acts as a hard reset either way; the difference is far below the bf16
@@ -99,6 +99,25 @@ int bigla_fwd(const void *q, const void *k, const void *v, const void *g_fwd, co
 int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
                      void *out, int B, int H, int L, int dk, int dv, int dtype, int layout,
                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * bigla_fwd_layout with a choice among the kernels that evaluate the chunkwise form (Section 4.2.1,
+ * Eq. (BiGLA); a measurement and testing aid: the result is the same up to operand rounding).
+ *   VIG_FWD_AUTO              what bigla_fwd_layout runs: at present the four-wave kernels;
+ *   VIG_FWD_FOUR_WAVE         workgroups of four waves, each wave walking the whole chain of a chunk
+ *                             step for its 16 tokens;
+ *   VIG_FWD_WAVE_SPECIALISED  workgroups of eight waves: producer waves (gate scans, exponentials, scaled
+ *                             keys, score tiles, P.V) and consumer waves (state readouts, output rows,
+ *                             state update) on the same SIMDs, one chunk apart.  VIG_BF16 with
+ *                             dk = dv = 64 and at least two chunks, except short sequences in many slabs
+ *                             (VIG_ERR_UNSUPPORTED otherwise).  Gates outside the fast form's range make
+ *                             the four-wave kernels redo the call inside the same call.
+ * Workspace as for bigla_fwd_layout.  Unknown plan: VIG_ERR_UNSUPPORTED.
+ */
+typedef enum { VIG_FWD_AUTO = 0, VIG_FWD_FOUR_WAVE = 1, VIG_FWD_WAVE_SPECIALISED = 2 } vig_fwd_plan;
+int bigla_fwd_plan(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                   void *out, int B, int H, int L, int dk, int dv, int dtype, int layout, int plan,
+                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * bigla_fwd_layout for callers that cannot allocate device memory or pass a workspace: code that
@@ -201,7 +220,9 @@ int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, con
  *   VIG_PLAN_AUTO             the faster of the two for the shape: at present always two launches
  *                             (the output pass is bound by its vector arithmetic, and the blend's
  *                             arithmetic costs more there than a second pass over memory).
- * Either plan returns bit for bit what bigla_fwd_layout followed by locality_gate_fwd_layout returns.
+ * The two-launch plan returns bit for bit what bigla_fwd_layout followed by locality_gate_fwd_layout
+ * returns; the fused plan evaluates the token mixer with kernels of its own, whose operand roundings
+ * may differ from those of bigla_fwd_layout by a few bf16 steps of the mixer's output.
  * workspace: at least bigla_locality_workspace_bytes(B, H, Hg*Wg, dk, dv, dtype, plan) bytes
  * (that function returns 0 for invalid or unsupported arguments).
  */

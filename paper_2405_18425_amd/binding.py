@@ -24,9 +24,10 @@ VIG_F32, VIG_BF16 = 0, 1
 VIG_LAYOUT_BHLD, VIG_LAYOUT_BLHD = 0, 1
 LAYOUTS = {"bhld": VIG_LAYOUT_BHLD, "blhd": VIG_LAYOUT_BLHD}
 PLANS = {"auto": 0, "two_launches": 1, "fused_epilogue": 2}
+FWD_PLANS = {"auto": 0, "four_wave": 1, "wave_specialised": 2}
 
 # every symbol include/vig_bigla.h declares
-EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "bigla_fwd_static_scratch", "locality_gate_fwd",
+EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "bigla_fwd_plan", "bigla_fwd_static_scratch", "locality_gate_fwd",
            "locality_gate_fwd_layout", "bigla_locality_workspace_bytes", "bigla_locality_fwd", "gate_producer_fwd",
            "bigla_bwd_workspace_bytes", "bigla_bwd", "bigla_bwd_plan",
            "vig_status_str", "vig_last_hip_error", "vig_timing_enable",
@@ -58,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.bigla_fwd.restype = ci
         L.bigla_fwd_layout.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
         L.bigla_fwd_layout.restype = ci
+        L.bigla_fwd_plan.argtypes = [vp] * 6 + [ci] * 8 + [vp, sz, vp]
+        L.bigla_fwd_plan.restype = ci
         L.bigla_fwd_static_scratch.argtypes = [vp] * 6 + [ci] * 7 + [vp]
         L.bigla_fwd_static_scratch.restype = ci
         L.locality_gate_fwd.argtypes = [vp] * 6 + [ci] * 6 + [vp]
@@ -134,14 +137,15 @@ def _layout_code(layout) -> int:
     return LAYOUTS[layout]
 
 
-def bigla_fwd(q, k, v, g_fwd, g_bwd, out=None, workspace=None, layout="bhld", static_scratch=False):
+def bigla_fwd(q, k, v, g_fwd, g_bwd, out=None, workspace=None, layout="bhld", static_scratch=False, plan="auto"):
     """BiGLA forward (Section 4.2.1).  q,k,g_fwd,g_bwd: [B,H,L,dk]; v: [B,H,L,dv] -> out [B,H,L,dv]
     (layout "bhld"), or all of them token-major, [B,L,H,d] (layout "blhd").
 
     g_* are LOG forget gates (<= 0).  `workspace` is an optional uint8 GPU tensor of at least
     bigla_workspace_bytes(...) bytes; one is allocated with torch when absent.
     static_scratch=True calls bigla_fwd_static_scratch instead: the library's own per-GPU scratch
-    array serves as workspace and, given `out`, nothing is allocated.
+    array serves as workspace and, given `out`, nothing is allocated.  `plan` other than "auto" goes
+    through bigla_fwd_plan ("four_wave" or "wave_specialised" kernels of the chunkwise path).
     """
     lay = _layout_code(layout)
     q = _dev(q, "q")
@@ -174,8 +178,14 @@ def bigla_fwd(q, k, v, g_fwd, g_bwd, out=None, workspace=None, layout="bhld", st
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    if plan not in FWD_PLANS:
+        raise VigError(VIG_ERR_UNSUPPORTED, f"plan must be one of {sorted(FWD_PLANS)}")
     with torch.cuda.device(q.device):
-        if lay == VIG_LAYOUT_BHLD:
+        if plan != "auto":
+            st = lib().bigla_fwd_plan(q.data_ptr(), k.data_ptr(), v.data_ptr(), g_fwd.data_ptr(), g_bwd.data_ptr(),
+                                      out.data_ptr(), B, H, L, dk, dv, code, lay, FWD_PLANS[plan], ws_ptr, ws_bytes,
+                                      _stream_ptr(q.device))
+        elif lay == VIG_LAYOUT_BHLD:
             st = lib().bigla_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), g_fwd.data_ptr(), g_bwd.data_ptr(),
                                  out.data_ptr(), B, H, L, dk, dv, code, ws_ptr, ws_bytes, _stream_ptr(q.device))
         else:

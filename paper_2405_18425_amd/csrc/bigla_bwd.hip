@@ -414,6 +414,8 @@ size_t bigla_bwd_workspace_bytes(long BH, int L, int dk, int dv, bool is_bf16)
     return exact + (bigla_bwd_chunk_supported(dk, dv, is_bf16) ? bigla_bwd_chunk_workspace_bytes(BH, L) : 0);
 }
 
+constexpr int kChunkwiseMinTokens = 32;
+
 hipError_t bigla_bwd_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
                             const void *d_out, void *dq, void *dk, void *dv, void *dg_fwd, void *dg_bwd, long BH, int L,
                             int dk_, int dv_, bool is_bf16, int heads_token_major, bool recurrent_only, void *workspace,
@@ -423,8 +425,12 @@ hipError_t bigla_bwd_launch(const void *q, const void *k, const void *v, const v
     char *base = static_cast<char *>(workspace);
     const int *only_marked = nullptr;
     if (bigla_bwd_chunk_supported(dk_, dv_, is_bf16)) {
-        // the chunkwise kernels take every slab whose gates they can carry and mark the others
-        if (!recurrent_only) {
+        // The chunkwise kernels take every slab whose gates they can carry and mark the others.  Sequences
+        // shorter than half a chunk go to the exact kernels altogether: a slab of a few tokens has only a
+        // handful of score entries, all of which can be small at once, and the bf16 rounding of the scaled
+        // queries and keys (relative to the summands of those entries) is then large against the slab's own
+        // gradients -- reproduced on the CPU from the operand roundings alone.
+        if (!recurrent_only && L >= kChunkwiseMinTokens) {
             const hipError_t e = bigla_bwd_chunk_launch(q, k, v, g_fwd, g_bwd, d_out, dq, dk, dv, dg_fwd, dg_bwd, BH, L,
                                                         dk_, heads_token_major, base, stream);
             if (e != hipSuccess) return e;

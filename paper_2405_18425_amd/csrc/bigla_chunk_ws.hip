@@ -1,0 +1,632 @@
+// Wave-specialised chunkwise BiGLA forward (Section 4.2.1, Eq. (BiGLA)) for bf16, dk = dv = 64:
+// the same two passes, workspace layout and arithmetic as the four-wave kernels of
+// bigla_chunk.hip (whose header has the algebra of the regrouping over 64-token chunks), with the
+// work of a chunk step divided between two sets of waves that run on the same SIMDs.
+//
+// Why.  A chunk step is a chain: gate scan (matrix cores) -> 64 exponentials per lane and the
+// scalings (vector ALU) -> scaled keys through LDS -> score tiles (matrix cores) -> P.V, two state
+// readouts and the state update (matrix cores, LDS operands).  With every wave walking that chain
+// on its own, and two waves per SIMD, the vector ALU, the LDS and the matrix cores were busy one
+// after the other: their busy times added up to the step time.  Here a workgroup has eight waves,
+// one producer and one consumer per SIMD:
+//   producers (waves 0-3, wave w owns tokens 16w..16w+15 of the chunk): cumulative gates, the
+//     exponentials and scalings, the scaled key tiles, the score tiles of the wave's tokens;
+//   consumers (waves 4-7, wave 4+w owns the same tokens for the output and rows 16w..16w+15 of
+//     the carried state): mask and split of the score tile, P.V, the readouts, the output rows,
+//     the state update, the state tiles for the next chunk, the stash.
+// The consumers work one chunk behind the producers; what a producer made for its 16 tokens goes
+// to the consumer of the same tokens through lane-private LDS slots (lane i of wave w writes, lane i
+// of wave 4+w reads: contiguous 16-byte pieces, no layout change), so the vector work of chunk n+1
+// and the matrix work of chunk n share a SIMD at the same time.  Synchronisation is by workgroup
+// barriers only (two per step in the output pass, one in the state pass), executed by every wave
+// the same number of times.
+//
+// The consumers have vector-ALU time to spare, which buys accuracy: the score tile enters P.V, and the
+// carried forward state and the entering backward state enter the readouts, as bf16 pairs hi + lo
+// (x = hi + lo to 16 bits), so that of the four operand roundings of the chunkwise form only those
+// of the scaled queries and keys (and of the stashed backward state) remain.
+//
+// Range.  These kernels evaluate the FAST form only (queries q exp(b), keys k exp(-b), see
+// bigla_chunk.hip).  The state pass checks every chunk's total log-decay against the fast form's
+// range and leaves one flag per (slab, segment) unit; if any unit of a call is outside, the
+// four-wave kernels, which are launched after these and otherwise exit at once, redo the whole
+// call with both forms.
+#include <type_traits>
+
+#include "bigla_chunk_tiles.hpp"
+#include "vig_common.hpp"
+#include "vig_kernels.hpp"
+#include "vig_timing.hpp"
+
+// Phase markers for a timing build (a harness defines WS_MARK to record the cycle counter); inert here.
+#ifndef WS_MARK
+#define WS_MARK(slot)
+#endif
+
+namespace vig {
+
+namespace {
+
+constexpr int kWsThreads = 512;           // 4 producer + 4 consumer waves
+constexpr int kWsTargetWorkgroups = 256;  // one workgroup per CU (LDS-limited)
+
+struct __align__(16) WsStateLds {
+    uint16_t g[2][2][kC][kPitch];   // [buffer][direction] raw log-gates, columns permuted as by stage_gates
+    uint16_t ks[2][2][kC][kPitch];  // [buffer][direction] scaled keys k exp(-b)  [token][channel, operand order]
+    uint16_t v[2][kC][kPitch];      // [buffer] values [token][column]
+    float tot[2][2][kD];            // [buffer][direction] chunk total log-gate per channel, operand order
+    int not_fast;                   // some chunk of the unit is outside the fast form's range
+};
+
+struct __align__(16) WsOutLds {
+    uint16_t g[2][kC][kPitch];   // [direction] raw log-gates of the chunk the producers work on
+    uint16_t kf[2][kC][kPitch];  // [buffer] forward-scaled keys (scores now, state update one step later)
+    uint16_t kb[kC][kPitch];     // backward-scaled keys
+    uint16_t v[2][kC][kPitch];   // [buffer] values (P.V now, state update one step later)
+    uint16_t st[kD][kPitch];     // forward state entering the consumers' chunk, bf16  [column][channel]
+    uint16_t sb[kD][kPitch];     // backward state entering the consumers' chunk, bf16
+    uint16_t ob[kC][kPitch];     // the consumers' output rows on their way from accumulator to row order
+    uint4 hand_o[4][256];        // producer -> consumer: fp32 accumulators of P.V (lane-private slots)
+    uint4 hand_q[4][256];        // producer -> consumer: readout queries qf0, qf1, qb0, qb1
+    float tot[2][kD];            // [buffer] forward chunk total log-gate per channel, operand order
+};
+
+union WsLds {
+    WsStateLds state;
+    WsOutLds out;
+};
+__shared__ WsLds g_ws_lds;
+
+// Plan of the wave-specialised path: about one workgroup per CU.
+inline Plan make_ws_plan(long BH, int L)
+{
+    Plan p;
+    p.n_chunks = (L + kC - 1) / kC;
+    long want = kWsTargetWorkgroups / (BH > 0 ? BH : 1);
+    if (want < 1) want = 1;
+    if (want > p.n_chunks) want = p.n_chunks;
+    p.seg_chunks = int((p.n_chunks + want - 1) / want);
+    p.n_seg = (p.n_chunks + p.seg_chunks - 1) / p.seg_chunks;
+    return p;
+}
+
+// One slab's row tensors
+template <bool kTm>
+struct SlabIo {
+    __amdgpu_buffer_rsrc_t q, k, gf, gb, v, out;
+    unsigned pitch;  // bytes between consecutive tokens
+    __device__ __forceinline__ SlabIo(const uint16_t *q_all, const uint16_t *k_all, const uint16_t *v_all,
+                                      const uint16_t *gf_all, const uint16_t *gb_all, uint16_t *out_all, long slab,
+                                      int L, int heads)
+    {
+        const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
+        pitch = unsigned(kTm ? heads : 1) * kD * 2u;
+        const unsigned extent = unsigned(L - 1) * pitch + kD * 2u;
+        q = slab_resource(q_all ? q_all + row0 * kD : nullptr, q_all ? extent : 0u);
+        k = slab_resource(k_all + row0 * kD, extent);
+        gf = slab_resource(gf_all + row0 * kD, extent);
+        gb = slab_resource(gb_all + row0 * kD, extent);
+        v = slab_resource(v_all + row0 * kD, extent);
+        out = slab_resource(out_all ? out_all + row0 * kD : nullptr, out_all ? extent : 0u);
+    }
+};
+
+// ---- state pass ------------------------------------------------------------------------------------
+// One (slab, segment) unit per workgroup, chunks right to left.  Step s: the producers scale the keys
+// of chunk nch-1-s, the consumers fold chunk nch-s into the carried states.  What is written to the
+// workspace is what bigla_segment_state_kernel writes.
+template <bool kTm>
+__global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
+    const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all, const uint16_t *__restrict__ gf_all,
+    const uint16_t *__restrict__ gb_all, float *__restrict__ seg_states, int *__restrict__ seg_mild,
+    unsigned char *__restrict__ stash, int L, int n_chunks, int seg_chunks, int n_seg, int heads)
+{
+    WsStateLds &sm = g_ws_lds.state;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const bool producer = wave < 4;
+    const int w = wave & 3;
+    const int tid4 = tid & 255;  // index among the four waves of the role
+    long slab;
+    int seg;
+    unit_slab_segment(blockIdx.x, n_seg, slab, seg);
+    const SlabIo<kTm> io(nullptr, k_all, v_all, gf_all, gb_all, nullptr, slab, L, heads);
+    const int chunk0 = seg * seg_chunks;
+    const int nch = min(seg_chunks, n_chunks - chunk0);
+    const int row = 16 * w + r;
+    const LaneRows lr = lane_rows<kD>(w, lane, io.pitch);
+    auto token0 = [&](int m) { return unsigned(chunk0 + max(m, 0)) * kC; };  // m may run before the segment: clamped, unused
+
+    if (tid == 0) sm.not_fast = 0;
+
+    if (producer) {
+        bf16x8 tri_f[2], tri_b[2];
+        scan_triangle<0>(w, r, g, tri_f);
+        scan_triangle<1>(w, r, g, tri_b);
+        StagedRows rk = load_rows(io.k, lr, token0(nch - 1));
+        {
+            const StagedRows gf = load_rows(io.gf, lr, token0(nch - 1)), gb = load_rows(io.gb, lr, token0(nch - 1));
+            stage_gates(sm.g[0][0], w, lane, gf);
+            stage_gates(sm.g[0][1], w, lane, gb);
+        }
+        StagedRows rgf = load_rows(io.gf, lr, token0(nch - 2)), rgb = load_rows(io.gb, lr, token0(nch - 2));
+        __syncthreads();
+        for (int s = 0; s <= nch; ++s) {
+            if (s < nch) {
+                const int m = nch - 1 - s, b = s & 1;
+                // the wave's own rows of the key tile carry k from row order into operand order
+                bounce_store(sm.ks[b][0], w, lane, rk);
+                wave_lds_fence();
+                float kf[16], kb[16], totf[16], totb[16];
+                unpack16(bounce_load(sm.ks[b][0], row, g), kf);
+                rk = load_rows(io.k, lr, token0(m - 1));
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct) {
+                    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                    const bf16x8 f0 = token_operand(sm.g[b][0], 0, 1, 16 * ct, r, g), f1 = token_operand(sm.g[b][0], 2, 3, 16 * ct, r, g);
+                    const bf16x8 b0 = token_operand(sm.g[b][1], 0, 1, 16 * ct, r, g), b1 = token_operand(sm.g[b][1], 2, 3, 16 * ct, r, g);
+                    const f32x4 Bf = mfma(f1, tri_f[1], mfma(f0, tri_f[0], zero));
+                    const f32x4 Bb = mfma(b1, tri_b[1], mfma(b0, tri_b[0], zero));
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int n = 4 * ct + e;
+                        totf[n] = Bf[e];
+                        totb[n] = Bb[e];
+                        kb[n] = kf[n] * fast_exp2(-kLog2e * Bb[e]);  // k * exp(-c_i)
+                        kf[n] = kf[n] * fast_exp2(-kLog2e * Bf[e]);  // k * exp(-b_i)
+                    }
+                }
+                store_row16(sm.ks[b][0], row, g, kf);
+                store_row16(sm.ks[b][1], row, g, kb);
+                // chunk totals: the forward cumulative gate of the chunk's last token, the backward one of its
+                // first token; outside the fast form's range the unit is marked
+                if (w == 3 && r == 15) {
+                    store_chan16(sm.tot[b][0], g, totf);
+                    float mn = 0.f;
+#pragma unroll
+                    for (int n = 0; n < 16; ++n) mn = fminf(mn, totf[n]);
+                    if (!(mn >= -kFastRange)) sm.not_fast = 1;
+                }
+                if (w == 0 && r == 0) {
+                    store_chan16(sm.tot[b][1], g, totb);
+                    float mn = 0.f;
+#pragma unroll
+                    for (int n = 0; n < 16; ++n) mn = fminf(mn, totb[n]);
+                    if (!(mn >= -kFastRange)) sm.not_fast = 1;
+                }
+                // the gates of chunk m-1 go to the other buffer (last read one step ago)
+                stage_gates(sm.g[b ^ 1][0], w, lane, rgf);
+                stage_gates(sm.g[b ^ 1][1], w, lane, rgb);
+                rgf = load_rows(io.gf, lr, token0(m - 2));
+                rgb = load_rows(io.gb, lr, token0(m - 2));
+            }
+            __syncthreads();
+        }
+    } else {
+        // Sb: backward state, carried right to left.  Sf: forward state at the segment's right edge, each
+        // chunk's contribution scaled once by the decay rf of the chunks to its right.
+        f32x4 Sf[4], Sb[4];
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) Sf[jt] = Sb[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float4 rf = make_float4(1.f, 1.f, 1.f, 1.f), rb = rf;
+        unsigned char *stash_slab = stash + size_t(slab) * n_chunks * kStashBytes;
+        StagedRows rv = load_rows(io.v, lr, token0(nch - 1));
+        __syncthreads();
+        for (int s = 0; s <= nch; ++s) {
+            if (s >= 1) {
+                const int m = nch - s, b = (s - 1) & 1;
+                {  // stash for chunk m: the backward state entering it from the right and the decay to the segment's edge
+                    unsigned char *dstm = stash_slab + size_t(chunk0 + m) * kStashBytes;
+                    if (m + 1 < nch) {
+                        uint4 *sdst = reinterpret_cast<uint4 *>(dstm) + tid4;
+                        const uint2 a = pack4(Sb[0]), bb = pack4(Sb[1]), c = pack4(Sb[2]), d = pack4(Sb[3]);
+                        sdst[0] = make_uint4(a.x, a.y, bb.x, bb.y);
+                        sdst[256] = make_uint4(c.x, c.y, d.x, d.y);
+                    }
+                    if (r == 0)
+                        *reinterpret_cast<float4 *>(dstm + size_t(kD) * kD * sizeof(uint16_t) + (16 * w + 4 * g) * sizeof(float)) = rb;
+                }
+                f32x4 Cf[4];
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt) Cf[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int p = 0; p < 2; ++p) {
+                    const bf16x8 af = token_operand(sm.ks[b][0], 2 * p, 2 * p + 1, 16 * w, r, g);
+                    const bf16x8 ab = token_operand(sm.ks[b][1], 2 * p, 2 * p + 1, 16 * w, r, g);
+#pragma unroll
+                    for (int jt = 0; jt < 4; ++jt) {
+                        const bf16x8 vb = token_operand(sm.v[b], 2 * p, 2 * p + 1, 16 * jt, r, g);
+                        Cf[jt] = mfma(af, vb, Cf[jt]);
+                        Sb[jt] = mfma(ab, vb, Sb[jt]);  // S_b = db * (S_b + Kb^T V)
+                    }
+                }
+                const float4 tf = *reinterpret_cast<const float4 *>(&sm.tot[b][0][16 * w + 4 * g]);
+                const float4 tb = *reinterpret_cast<const float4 *>(&sm.tot[b][1][16 * w + 4 * g]);
+                const float4 df = make_float4(fast_exp2(tf.x * kLog2e), fast_exp2(tf.y * kLog2e), fast_exp2(tf.z * kLog2e), fast_exp2(tf.w * kLog2e));
+                const float4 db = make_float4(fast_exp2(tb.x * kLog2e), fast_exp2(tb.y * kLog2e), fast_exp2(tb.z * kLog2e), fast_exp2(tb.w * kLog2e));
+                const float4 sf4 = make_float4(rf.x * df.x, rf.y * df.y, rf.z * df.z, rf.w * df.w);
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt) {
+                    Sb[jt][0] *= db.x; Sb[jt][1] *= db.y; Sb[jt][2] *= db.z; Sb[jt][3] *= db.w;
+                    Sf[jt][0] = fmaf(Cf[jt][0], sf4.x, Sf[jt][0]); Sf[jt][1] = fmaf(Cf[jt][1], sf4.y, Sf[jt][1]);
+                    Sf[jt][2] = fmaf(Cf[jt][2], sf4.z, Sf[jt][2]); Sf[jt][3] = fmaf(Cf[jt][3], sf4.w, Sf[jt][3]);
+                }
+                rf = sf4;
+                rb.x *= db.x; rb.y *= db.y; rb.z *= db.z; rb.w *= db.w;
+            }
+            if (s < nch) {  // values of the chunk the consumers take in the next step, into the buffer not in use
+                stage_values(sm.v[s & 1], w, lane, rv);
+                rv = load_rows(io.v, lr, token0(nch - 2 - s));
+            }
+            __syncthreads();
+        }
+        if (seg_states) {
+            float *dst = seg_states + (slab * n_seg + seg) * kSegFloats;
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) {
+                reinterpret_cast<f32x4 *>(dst)[256 * jt + tid4] = Sf[jt];
+                reinterpret_cast<f32x4 *>(dst + size_t(kD) * kD)[256 * jt + tid4] = Sb[jt];
+            }
+            if (r == 0) {
+                *reinterpret_cast<float4 *>(dst + kSegStateFloats + 16 * w + 4 * g) = rf;
+                *reinterpret_cast<float4 *>(dst + kSegStateFloats + kD + 16 * w + 4 * g) = rb;
+            }
+        }
+    }
+    if (tid == 0) seg_mild[blockIdx.x] = sm.not_fast ? 0 : 1;
+}
+
+// ---- output pass -----------------------------------------------------------------------------------
+// One (slab, segment) unit per workgroup, chunks left to right.  Step m:
+//   producers, chunk m: before the mid-step barrier the scalings (gate scan, exponentials, scaled key
+//     tiles); after it the score tiles of the wave's tokens, their mask and hi + lo split, and P.V,
+//     whose accumulators go to the consumer of the same tokens together with the readout queries;
+//   consumers, chunk m-1: before the barrier the two state readouts on top of what the producer
+//     left, and the output rows; after it the forward state update with chunk m-1's keys and values
+//     and the state tiles for chunk m.
+template <bool kTm>
+__global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
+    const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
+    const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
+    const float *__restrict__ seg_states /* nullptr when one segment per slab */, const int *__restrict__ seg_mild,
+    int n_units, const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg, int heads)
+{
+    // the whole call is redone by the four-wave kernels when any unit is outside the fast form's range
+    {
+        int bad = 0;
+        for (int i = threadIdx.x; i < n_units; i += kWsThreads) bad |= seg_mild[i] == 0;
+        if (__syncthreads_or(bad)) return;
+    }
+    WsOutLds &sm = g_ws_lds.out;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const bool producer = wave < 4;
+    const int w = wave & 3;
+    const int tid4 = tid & 255;
+    long slab;
+    int seg;
+    unit_slab_segment(blockIdx.x, n_seg, slab, seg);
+    const SlabIo<kTm> io(q_all, k_all, v_all, gf_all, gb_all, out_all, slab, L, heads);
+    const int chunk0 = seg * seg_chunks;
+    const int nch = min(seg_chunks, n_chunks - chunk0);
+    const int row = 16 * w + r;
+    const LaneRows lr = lane_rows<kD>(w, lane, io.pitch);
+    auto token0 = [&](int m) { return unsigned(chunk0 + min(m, nch - 1)) * kC; };  // m may run past the segment: clamped, unused
+
+    if (producer) {
+        bf16x8 tri_f[2], tri_b[2];
+        scan_triangle<0>(w, r, g, tri_f);
+        scan_triangle<1>(w, r, g, tri_b);
+        StagedRows rq = load_rows(io.q, lr, token0(0)), rk = load_rows(io.k, lr, token0(0)), rv = load_rows(io.v, lr, token0(0));
+        {
+            const StagedRows gf = load_rows(io.gf, lr, token0(0)), gb = load_rows(io.gb, lr, token0(0));
+            stage_gates(sm.g[0], w, lane, gf);
+            stage_gates(sm.g[1], w, lane, gb);
+        }
+        StagedRows rgf = load_rows(io.gf, lr, token0(1)), rgb = load_rows(io.gb, lr, token0(1));
+        __syncthreads();
+        for (int m = 0; m <= nch; ++m) {
+            bf16x8 qf0, qf1, qb0, qb1, kf0, kf1, kb0, kb1;
+            const int b = m & 1;
+            WS_MARK(0);
+            if (m < nch) {
+                // the wave's own rows of the key tiles carry q and k from row order into operand order
+                bounce_store(sm.kf[b], w, lane, rq);
+                bounce_store(sm.kb, w, lane, rk);
+                stage_values(sm.v[b], w, lane, rv);
+                wave_lds_fence();
+                float qf[16], kf[16], qb[16], kb[16], tot[16];
+                unpack16(bounce_load(sm.kf[b], row, g), qf);
+                unpack16(bounce_load(sm.kb, row, g), kf);
+                rq = load_rows(io.q, lr, token0(m + 1));
+                rk = load_rows(io.k, lr, token0(m + 1));
+                rv = load_rows(io.v, lr, token0(m + 1));
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct) {
+                    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                    const bf16x8 f0 = token_operand(sm.g[0], 0, 1, 16 * ct, r, g), f1 = token_operand(sm.g[0], 2, 3, 16 * ct, r, g);
+                    const bf16x8 b0 = token_operand(sm.g[1], 0, 1, 16 * ct, r, g), b1 = token_operand(sm.g[1], 2, 3, 16 * ct, r, g);
+                    const f32x4 Bf = mfma(f1, tri_f[1], mfma(f0, tri_f[0], zero));
+                    const f32x4 Bb = mfma(b1, tri_b[1], mfma(b0, tri_b[0], zero));
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int n = 4 * ct + e;
+                        const float xf = Bf[e] * kLog2e, xb = Bb[e] * kLog2e;
+                        tot[n] = Bf[e];
+                        qb[n] = qf[n] * fast_exp2(xb - 1.f);  // q * exp(c_t) / 2   backward
+                        kb[n] = kf[n] * fast_exp2(-xb);       // k * exp(-c_i)
+                        qf[n] *= fast_exp2(xf - 1.f);         // q * exp(b_t) / 2   forward
+                        kf[n] *= fast_exp2(-xf);              // k * exp(-b_i)
+                    }
+                }
+                qf0 = pack8(qf); qf1 = pack8(qf + 8); qb0 = pack8(qb); qb1 = pack8(qb + 8);
+                kf0 = pack8(kf); kf1 = pack8(kf + 8); kb0 = pack8(kb); kb1 = pack8(kb + 8);
+                *reinterpret_cast<bf16x8 *>(&sm.kf[b][row][8 * g]) = kf0;
+                *reinterpret_cast<bf16x8 *>(&sm.kf[b][row][32 + 8 * g]) = kf1;
+                *reinterpret_cast<bf16x8 *>(&sm.kb[row][8 * g]) = kb0;
+                *reinterpret_cast<bf16x8 *>(&sm.kb[row][32 + 8 * g]) = kb1;
+                if (w == 3 && r == 15) store_chan16(sm.tot[b], g, tot);  // for the state decay
+            }
+            WS_MARK(1);
+            __syncthreads();  // mid-step: scaled keys and values visible
+            WS_MARK(2);
+            if (m < nch) {
+                // merged masked score tile, transposed (P^T[i][t]): key sub-block I < w forward, I > w backward,
+                // I = w both (key <= query of the forward piece, key >= query of the backward one; own token in
+                // both); lane: keys 4g..4g+3, query r.  It enters P.V as bf16 pairs hi + lo.
+                uint2 ph[4], pl[4];
+                const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int I = 0; I < 4; ++I) {
+                    f32x4 p;
+                    if (I == w) {
+                        p = mfma(kf1, qf1, mfma(kf0, qf0, zero));
+                        const f32x4 pb = mfma(kb1, qb1, mfma(kb0, qb0, zero));
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int i = 4 * g + e;
+                            p[e] = (i <= r ? p[e] : 0.f) + (i >= r ? pb[e] : 0.f);
+                        }
+                    } else if (I < w) {
+                        const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kf[b][16 * I + r][8 * g]);
+                        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kf[b][16 * I + r][32 + 8 * g]);
+                        p = mfma(a1, qf1, mfma(a0, qf0, zero));
+                    } else {
+                        const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][8 * g]);
+                        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][32 + 8 * g]);
+                        p = mfma(a1, qb1, mfma(a0, qb0, zero));
+                    }
+                    split4(p, ph[I], pl[I]);
+                }
+                // O^T = V^T P^T, token-per-lane accumulators: lane (r, g) gets columns 16*jt + 4g .. +3 of its own token
+                f32x4 O[4];
+                {
+                    const bf16x8 h0 = operand(ph[0], ph[1]), h1 = operand(ph[2], ph[3]);
+                    const bf16x8 l0 = operand(pl[0], pl[1]), l1 = operand(pl[2], pl[3]);
+#pragma unroll
+                    for (int jt = 0; jt < 4; ++jt) {
+                        const bf16x8 v0 = token_operand(sm.v[b], 0, 1, 16 * jt, r, g), v1 = token_operand(sm.v[b], 2, 3, 16 * jt, r, g);
+                        O[jt] = mfma(v1, h1, mfma(v0, h0, mfma(v1, l1, mfma(v0, l0, zero))));
+                    }
+                }
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt) sm.hand_o[jt][tid4] = __builtin_bit_cast(uint4, O[jt]);
+                sm.hand_q[0][tid4] = __builtin_bit_cast(uint4, qf0);
+                sm.hand_q[1][tid4] = __builtin_bit_cast(uint4, qf1);
+                sm.hand_q[2][tid4] = __builtin_bit_cast(uint4, qb0);
+                sm.hand_q[3][tid4] = __builtin_bit_cast(uint4, qb1);
+                // the gates of chunk m+1 (the tiles were last read before the mid-step barrier)
+                stage_gates(sm.g[0], w, lane, rgf);
+                stage_gates(sm.g[1], w, lane, rgb);
+                rgf = load_rows(io.gf, lr, token0(m + 2));
+                rgb = load_rows(io.gb, lr, token0(m + 2));
+            }
+            WS_MARK(3);
+            __syncthreads();  // end of step
+            WS_MARK(4);
+        }
+    } else {
+        const unsigned char *stash = stash_all + size_t(slab) * n_chunks * kStashBytes;
+        const bool seg_in = seg_states != nullptr && seg + 1 < n_seg;  // the last segment's entering backward state is zero
+        struct StashRows {
+            uint4 p[2];
+            float4 dr;  // decay of the lane's state rows from the chunk's right edge to the segment's
+        };
+        auto fetch_stash = [&](int m) {
+            StashRows c;
+            const unsigned char *base = stash + size_t(chunk0 + min(m, nch - 1)) * kStashBytes;
+            const uint4 *p = reinterpret_cast<const uint4 *>(base) + tid4;
+            c.p[0] = p[0];
+            c.p[1] = p[256];
+            c.dr = *reinterpret_cast<const float4 *>(base + size_t(kD) * kD * sizeof(uint16_t) + (16 * w + 4 * g) * sizeof(float));
+            return c;
+        };
+        StashRows rs = fetch_stash(0);
+
+        // States entering the segment, folded from the segments' local end states and decays that the state
+        // pass left: forward from the left, E <- D_n * E + S_n over the segments n < seg; backward from the
+        // right over n > seg (kept in registers; each chunk adds its decayed copy to the stashed state).
+        f32x4 S[4], Sseg[4];
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) S[jt] = Sseg[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        auto fold = [&](f32x4 (&E)[4], int dir, int first, int count, int step) {
+            const float *slab_states = seg_states + slab * n_seg * kSegFloats;
+            constexpr int kBatch = 4;
+            for (int i0 = 0; i0 < count; i0 += kBatch) {
+                f32x4 local[kBatch][4];
+                float4 decay[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const float *sp = slab_states + size_t(first + step * min(i0 + u, count - 1)) * kSegFloats;
+#pragma unroll
+                    for (int jt = 0; jt < 4; ++jt)
+                        local[u][jt] = reinterpret_cast<const f32x4 *>(sp + dir * kD * kD)[256 * jt + tid4];
+                    decay[u] = *reinterpret_cast<const float4 *>(sp + kSegStateFloats + dir * kD + 16 * w + 4 * g);
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    if (i0 + u < count) {
+#pragma unroll
+                        for (int jt = 0; jt < 4; ++jt) {
+                            E[jt][0] = fmaf(E[jt][0], decay[u].x, local[u][jt][0]);
+                            E[jt][1] = fmaf(E[jt][1], decay[u].y, local[u][jt][1]);
+                            E[jt][2] = fmaf(E[jt][2], decay[u].z, local[u][jt][2]);
+                            E[jt][3] = fmaf(E[jt][3], decay[u].w, local[u][jt][3]);
+                        }
+                    }
+                }
+            }
+        };
+        // state tiles for chunk m: the forward state, and the backward state entering the chunk = its stashed
+        // state (zero for the segment's last chunk) + the segment's entering state decayed to the chunk's edge
+        auto publish = [&](const StashRows &c, int m) {
+            const bool has_stash = m + 1 < nch;
+            uint2 t[4] = {make_uint2(c.p[0].x, c.p[0].y), make_uint2(c.p[0].z, c.p[0].w),
+                          make_uint2(c.p[1].x, c.p[1].y), make_uint2(c.p[1].z, c.p[1].w)};
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) {
+                *reinterpret_cast<uint2 *>(&sm.st[16 * jt + r][16 * w + 4 * g]) = pack4(S[jt]);
+                if (seg_in) {
+                    f32x4 x = has_stash ? unpack4(t[jt]) : f32x4{0.f, 0.f, 0.f, 0.f};
+                    x[0] = fmaf(c.dr.x, Sseg[jt][0], x[0]);
+                    x[1] = fmaf(c.dr.y, Sseg[jt][1], x[1]);
+                    x[2] = fmaf(c.dr.z, Sseg[jt][2], x[2]);
+                    x[3] = fmaf(c.dr.w, Sseg[jt][3], x[3]);
+                    t[jt] = pack4(x);
+                } else if (!has_stash) {
+                    t[jt] = make_uint2(0u, 0u);
+                }
+                *reinterpret_cast<uint2 *>(&sm.sb[16 * jt + r][16 * w + 4 * g]) = t[jt];
+            }
+        };
+
+        if (seg_states != nullptr) {
+            fold(S, 0, 0, seg, 1);
+            fold(Sseg, 1, n_seg - 1, n_seg - 1 - seg, -1);
+        }
+        __syncthreads();  // (the producers' prologue barrier)
+        for (int m = 0; m <= nch; ++m) {
+            const int c = m - 1, b = c & 1;
+            WS_MARK(0);
+            if (m >= 1) {
+                // what the producer of the same tokens left: P.V of the chunk and the readout queries
+                f32x4 O[4];
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt) O[jt] = __builtin_bit_cast(f32x4, sm.hand_o[jt][tid4]);
+                const bf16x8 qf0 = __builtin_bit_cast(bf16x8, sm.hand_q[0][tid4]), qf1 = __builtin_bit_cast(bf16x8, sm.hand_q[1][tid4]);
+                const bf16x8 qb0 = __builtin_bit_cast(bf16x8, sm.hand_q[2][tid4]), qb1 = __builtin_bit_cast(bf16x8, sm.hand_q[3][tid4]);
+                readout(sm.st, qf0, qf1, r, g, O);
+                if (c + 1 < nch || seg_in) readout(sm.sb, qb0, qb1, r, g, O);
+                // o_t = (o_fwd_t + o_bwd_t) / 2 (the queries arrive halved), turned into whole rows through the wave's
+                // own rows of the bounce tile, then written 8 rows per store
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt)
+                    *reinterpret_cast<uint2 *>(&sm.ob[16 * w + r][16 * jt + 4 * g]) = pack4(O[jt]);
+                wave_lds_fence();
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int rr = 16 * w + 8 * t + (lane >> 3);
+                    const uint4 o = *reinterpret_cast<const uint4 *>(&sm.ob[rr][8 * (lane & 7)]);
+                    __builtin_amdgcn_raw_buffer_store_b128(u32x4{o.x, o.y, o.z, o.w}, io.out,
+                                                           lr.off[t] + unsigned(chunk0 + c) * kC * lr.pitch, 0, 0);
+                }
+            }
+            WS_MARK(1);
+            __syncthreads();  // mid-step
+            WS_MARK(2);
+            if (m >= 1) {
+                // forward state update: S = d (S + K^T V), d = exp(chunk total)
+                const float4 t = *reinterpret_cast<const float4 *>(&sm.tot[b][16 * w + 4 * g]);
+                const float4 d = make_float4(fast_exp2(t.x * kLog2e), fast_exp2(t.y * kLog2e), fast_exp2(t.z * kLog2e), fast_exp2(t.w * kLog2e));
+#pragma unroll
+                for (int p = 0; p < 2; ++p) {
+                    const bf16x8 a = token_operand(sm.kf[b], 2 * p, 2 * p + 1, 16 * w, r, g);
+#pragma unroll
+                    for (int jt = 0; jt < 4; ++jt) S[jt] = mfma(a, token_operand(sm.v[b], 2 * p, 2 * p + 1, 16 * jt, r, g), S[jt]);
+                }
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt) {
+                    S[jt][0] *= d.x; S[jt][1] *= d.y; S[jt][2] *= d.z; S[jt][3] *= d.w;
+                }
+            }
+            if (m < nch) {
+                // tiles for chunk m, which the consumers take in the next step
+                publish(rs, m);
+                rs = fetch_stash(m + 1);
+            }
+            WS_MARK(3);
+            __syncthreads();  // end of step
+            WS_MARK(4);
+        }
+    }
+}
+
+}  // namespace
+
+bool bigla_chunk_ws_applicable(long BH, int L, int dk)
+{
+    const Plan p = make_ws_plan(BH, L);
+    // short sequences with at least half a chip of slabs stay with the single-launch slab kernel
+    if (BH >= 128 && p.n_chunks <= 4) return false;
+    return dk == kD && p.n_chunks > 1;
+}
+
+// Workspace of this path: [segment states][stash] as in the four-wave path (for this path's own
+// plan), and one flag per (slab, segment) unit at an offset the caller chooses: beyond everything
+// that the four-wave kernels write when they redo a call, since they read the flags while doing so.
+size_t bigla_chunk_ws_core_bytes(long BH, int L)
+{
+    const Plan p = make_ws_plan(BH, L);
+    return size_t(BH) * p.n_seg * kSegFloats * sizeof(float) + size_t(BH) * p.n_chunks * kStashBytes;
+}
+
+size_t bigla_chunk_ws_flag_bytes(long BH, int L)
+{
+    const Plan p = make_ws_plan(BH, L);
+    return (size_t(BH) * p.n_seg * sizeof(int) + 15) / 16 * 16;
+}
+
+hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
+                                 void *out, long BH, int L, int heads_token_major, void *workspace, size_t flags_offset,
+                                 const int **unit_flags, int *n_units, hipStream_t stream)
+{
+    const Plan p = make_ws_plan(BH, L);
+    const long blocks = BH * p.n_seg;
+    if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+    const uint16_t *qq = static_cast<const uint16_t *>(q), *kk = static_cast<const uint16_t *>(k);
+    const uint16_t *vv = static_cast<const uint16_t *>(v);
+    const uint16_t *gf = static_cast<const uint16_t *>(g_fwd), *gb = static_cast<const uint16_t *>(g_bwd);
+    uint16_t *oo = static_cast<uint16_t *>(out);
+    float *seg_states = static_cast<float *>(workspace);
+    const size_t seg_bytes = size_t(BH) * p.n_seg * kSegFloats * sizeof(float);
+    int *seg_mild = reinterpret_cast<int *>(static_cast<unsigned char *>(workspace) + flags_offset);
+    unsigned char *stash = static_cast<unsigned char *>(workspace) + seg_bytes;
+    const bool tm = heads_token_major > 0;
+    const int heads = tm ? heads_token_major : 1;
+    float *seg_out = p.n_seg > 1 ? seg_states : nullptr;
+    {
+        LaunchTimer timer(kKernelSegmentState, stream);
+        if (tm)
+            hipLaunchKernelGGL((bigla_ws_state_kernel<true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, kk, vv, gf,
+                               gb, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads);
+        else
+            hipLaunchKernelGGL((bigla_ws_state_kernel<false>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, kk, vv, gf,
+                               gb, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    {
+        LaunchTimer timer(kKernelSegmentOut, stream);
+        if (tm)
+            hipLaunchKernelGGL((bigla_ws_out_kernel<true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, qq, kk, vv,
+                               gf, gb, oo, seg_out, seg_mild, int(blocks), stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads);
+        else
+            hipLaunchKernelGGL((bigla_ws_out_kernel<false>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, qq, kk, vv,
+                               gf, gb, oo, seg_out, seg_mild, int(blocks), stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads);
+    }
+    *unit_flags = seg_mild;
+    *n_units = int(blocks);
+    return hipGetLastError();
+}
+
+}  // namespace vig

@@ -12,6 +12,12 @@ namespace {
 thread_local int g_last_hip_error = 0;
 
 bool head_dim_ok(int d) { return d == 16 || d == 32 || d == 64; }
+
+// Sequences shorter than half a chunk run the exact recurrence even where the chunkwise kernels apply:
+// a slab of a few tokens is a handful of query-key products that can all be small at once, and the bf16
+// rounding of the chunkwise form's scaled operands is then large against the slab's own outputs.
+constexpr int kChunkwiseMinTokens = 32;
+bool chunkwise_fwd(int L, int dk, int dv, bool bf16) { return vig::bigla_chunk_supported(dk, dv, bf16) && L >= kChunkwiseMinTokens; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // B*H*L*d elements must stay addressable with a comfortable margin
@@ -89,7 +95,7 @@ size_t bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype)
     const bool bf16 = dtype == VIG_BF16;
     if (!sizes_ok(B, H, L, dk > dv ? dk : dv)) return 0;
     const long BH = long(B) * H;
-    if (vig::bigla_chunk_supported(dk, dv, bf16)) return vig::bigla_chunk_workspace_bytes(BH, L);
+    if (chunkwise_fwd(L, dk, dv, bf16)) return vig::bigla_chunk_workspace_bytes(BH, L);
     return vig::bigla_recurrent_workspace_bytes(BH, L, dv, bf16);
 }
 
@@ -105,8 +111,17 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
                      int B, int H, int L, int dk, int dv, int dtype, int layout, void *workspace,
                      size_t workspace_bytes, void *stream)
 {
+    return bigla_fwd_plan(q, k, v, g_fwd, g_bwd, out, B, H, L, dk, dv, dtype, layout, VIG_FWD_AUTO, workspace,
+                          workspace_bytes, stream);
+}
+
+int bigla_fwd_plan(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd, void *out,
+                   int B, int H, int L, int dk, int dv, int dtype, int layout, int plan, void *workspace,
+                   size_t workspace_bytes, void *stream)
+{
     if (!q || !k || !v || !g_fwd || !g_bwd || !out) return VIG_ERR_NULL;
     if (layout != VIG_LAYOUT_BHLD && layout != VIG_LAYOUT_BLHD) return VIG_ERR_LAYOUT;
+    if (plan != VIG_FWD_AUTO && plan != VIG_FWD_FOUR_WAVE && plan != VIG_FWD_WAVE_SPECIALISED) return VIG_ERR_UNSUPPORTED;
     if (B <= 0 || H <= 0 || L <= 0 || dk <= 0 || dv <= 0) return VIG_ERR_SHAPE;
     if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
     if (!head_dim_ok(dk) || !head_dim_ok(dv)) return VIG_ERR_UNSUPPORTED;
@@ -127,11 +142,14 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
     const int heads_token_major = layout == VIG_LAYOUT_BLHD ? H : 0;
     // the chunkwise kernels address the rows of a slab (token-major: of a batch element) with 32-bit
     // byte offsets, up to one chunk past the sequence
-    if (vig::bigla_chunk_supported(dk, dv, bf16) && !chunk_offsets_ok(L, H, layout)) return VIG_ERR_SHAPE;
+    const bool chunkwise = chunkwise_fwd(L, dk, dv, bf16);
+    if (chunkwise && !chunk_offsets_ok(L, H, layout)) return VIG_ERR_SHAPE;
+    const bool ws = plan == VIG_FWD_WAVE_SPECIALISED;
+    if (ws && !(chunkwise && vig::bigla_chunk_ws_selectable(BH, L, dk))) return VIG_ERR_UNSUPPORTED;
     clear_stale_hip_error();
-    if (vig::bigla_chunk_supported(dk, dv, bf16))
+    if (chunkwise)
         return hip_status(
-            vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, heads_token_major, nullptr, workspace, s));
+            vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, heads_token_major, nullptr, ws, workspace, s));
     return hip_status(vig::bigla_recurrent_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, dv, bf16,
                                                   heads_token_major, workspace, s));
 }
@@ -234,7 +252,8 @@ size_t bigla_locality_workspace_bytes(int B, int H, int L, int dk, int dv, int d
     if (dtype != VIG_F32 && dtype != VIG_BF16) return 0;
     if (plan != VIG_PLAN_AUTO && plan != VIG_PLAN_TWO_LAUNCHES && plan != VIG_PLAN_FUSED_EPILOGUE) return 0;
     const size_t mixer = bigla_workspace_bytes(B, H, L, dk, dv, dtype);
-    if (plan == VIG_PLAN_FUSED_EPILOGUE) return vig::bigla_chunk_supported(dk, dv, dtype == VIG_BF16) ? mixer : 0;
+    if (plan == VIG_PLAN_FUSED_EPILOGUE)
+        return vig::bigla_chunk_supported(dk, dv, dtype == VIG_BF16) ? vig::bigla_chunk_workspace_bytes(long(B) * H, L) : 0;
     if (!sizes_ok(B, H, L, dv)) return 0;
     // the token mixer's output goes through the workspace
     return align256(mixer) + size_t(B) * H * L * dv * (dtype == VIG_BF16 ? 2 : 4);
@@ -276,12 +295,12 @@ int bigla_locality_fwd(const void *q, const void *k, const void *v, const void *
         !aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(gate_logits) || !aligned16(out) ||
         !aligned16(workspace))
         return VIG_ERR_ALIGN;
-    const size_t need = bigla_workspace_bytes(B, H, L, dk, dv, dtype);
+    const size_t need = vig::bigla_chunk_workspace_bytes(long(B) * H, L);
     if (need > 0 && (!workspace || workspace_bytes < need)) return VIG_ERR_WORKSPACE;
     const vig::LocalityFusion fusion = {x, w, bias, gate_logits, H, Hg, Wg};
     clear_stale_hip_error();
     return hip_status(vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, long(B) * H, L, dk,
-                                              layout == VIG_LAYOUT_BLHD ? H : 0, &fusion, workspace,
+                                              layout == VIG_LAYOUT_BLHD ? H : 0, &fusion, false, workspace,
                                               static_cast<hipStream_t>(stream)));
 }
 

@@ -142,8 +142,8 @@ def test_bigla_mixed_forms_in_one_call(B, H, L, dk):
 
 @pytest.mark.parametrize("layout", ("bhld", "blhd"))
 def test_bigla_many_short_slabs(layout):
-    """8192 slabs of twenty tokens: one-chunk sequences, a grid of thousands of workgroups (16 times
-    what the chip holds at once), forward and gradient."""
+    """8192 slabs of twenty tokens: a grid of thousands of workgroups (16 times what the chip holds at
+    once), forward and gradient, each slab held to the bound with its own rms."""
     import torch
     from paper_2405_18425_amd import binding as vb
 
@@ -157,12 +157,10 @@ def test_bigla_many_short_slabs(layout):
     torch.cuda.synchronize()
     if layout == "blhd":
         out = out.transpose(1, 2).contiguous()
-    # a slab of twenty tokens has little scale of its own (a few hundred cancelling dot products, and
-    # 8192 slabs to pick the unluckiest from): the floor of the bound is the rms over all slabs
-    flat = lambda a: a.reshape(1, 1, -1, a.shape[-1])
-    assert_close(flat(wl.widen(wl.from_torch(out, "bf16"), "bf16")), flat(run_bigla_oracle(s, "bf16")), TOL["bf16"],
-                 "many slabs")
-    worst = _check_bwd(s, "bf16", layout, "auto", what="many slabs", pool=True)
+    # sequences this short run the exact recurrences (forward and gradient): the bound is the one used
+    # everywhere, floored by each slab's own rms
+    assert_close(wl.widen(wl.from_torch(out, "bf16"), "bf16"), run_bigla_oracle(s, "bf16"), TOL["bf16"], "many slabs")
+    worst = _check_bwd(s, "bf16", layout, "auto", what="many slabs")
     _say(f"  gradient: worst error / bound = {worst:.3f}")
 
 
@@ -185,18 +183,107 @@ def test_bigla_very_long_sequence(layout):
         out = out.transpose(1, 2).contiguous()
     got = wl.widen(wl.from_torch(out, "bf16"), "bf16")
     ref = run_bigla_oracle(s, "bf16")
-    # Element by element on three windows (the head, the middle, the ragged tail), and in aggregate
-    # over everything.  Over all 8.4 M outputs the largest error sits at the element bound itself
-    # (one element 0.8 % over it in one layout): the bound is a multiple of the error's spread that
-    # a tensor of this size reaches, see the tolerance notes; the windows hold a million elements
-    # each, like the other full-size cases.
-    L = w.L
-    for lo, hi in ((0, 4096), (L // 2 - 2048, L // 2 + 2048), (L - 4101, L)):
-        assert_close(got[:, :, lo:hi], ref[:, :, lo:hi], TOL["bf16"], f"very long [{lo}:{hi})")
+    # every one of the 8.4 M outputs element by element, and the error in aggregate
+    rel = assert_close(got, ref, TOL["bf16"], "very long")
     rms = lambda a: np.sqrt(np.mean(a ** 2, axis=(2, 3)))
+    worst = float(np.max(np.abs(got - ref) / (TOL["bf16"] * (np.abs(ref) + rms(ref)[:, :, None, None]))))
+    _say(f"  max|err|/max|ref| = {rel:.3e}; worst error / element bound = {worst:.3f}")
     assert np.all(rms(got - ref) <= 5e-3 * rms(ref))
-    assert np.all(np.abs(got - ref) <= 1.5 * TOL["bf16"] * (np.abs(ref) + rms(ref)[:, :, None, None]))
     assert np.max(np.abs(got - ref)) <= TOL["bf16"] * np.max(np.abs(ref))     # max error relative to the largest output
+
+
+def _spiked_case_from_stream():
+    """The 95th case of a seeded stream of random shapes and gate regimes (generator seed 7): B=16,
+    H=12, L=128, 32-wide keys, token-major, gates of mean logit -1 with one step in a hundred set to
+    -25.  Its largest error once sat 17 % over the element bound; the stream is replayed so that the
+    case is exactly the same."""
+    rng = np.random.default_rng(7)
+    for case in range(95):
+        dk = (64, 32)[int(rng.integers(2))]
+        B = int(rng.choice([1, 2, 3, 4, 8, 16, 24, 40]))
+        H = int(rng.choice([1, 2, 3, 4, 6, 8, 12]))
+        L = int(rng.choice([5, 64, 65, 128, 130, 196, 300, 511, 512, 700, 1024, 1500, 2049]))
+        while B * H * L > 400_000:
+            B = max(1, B // 2)
+        layout = "blhd" if rng.random() < 0.4 else "bhld"
+        regime = ("mild", "mixed", "harsh")[int(rng.integers(3))]
+        mu = {"mild": 1.0, "mixed": -1.0, "harsh": -3.0}[regime]
+        if case < 94:
+            if regime != "mild":
+                for _ in range(2):  # the draws the earlier cases made for their two gate tensors
+                    rng.random((B, H, L, dk))
+                    rng.choice([2.0, 6.0, 25.0])
+            continue
+        w = wl.Workload(f"stream{case}", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=64, dtype="bf16", gate_mu=mu)
+        s = wl.generate(w, seed=5000 + case, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+        if regime != "mild":
+            for name in ("g_fwd", "g_bwd"):
+                g = wl.widen(s[name], "bf16")
+                spikes = rng.random(g.shape) < (0.01 if regime == "mixed" else 0.2)
+                g[spikes] = -float(rng.choice([2.0, 6.0, 25.0]))
+                s[name] = wl.store(g, "bf16")
+        return w, s, layout, regime
+
+
+def test_bigla_regression_spiked_gates():
+    """Seeded cases that once sat at or over the element bound (operand roundings of the chunkwise
+    form on heavy-tailed slabs): mild gates with isolated -25 spikes from a replayed random stream,
+    a second spiked case, and strongly decaying gates over 1280 tokens.  All are held to the one
+    bound used everywhere."""
+    import torch
+    from paper_2405_18425_amd import binding as vb
+
+    w, s, layout, regime = _spiked_case_from_stream()
+    _say(f"bigla regression {w} {layout} {regime}")
+    assert (w.B, w.H, w.L, w.dk, layout) == (16, 12, 128, 32, "blhd")
+    ref = run_bigla_oracle(s, "bf16")
+    for lay in ("blhd", "bhld"):
+        t = {n: wl.to_torch(a, "bf16", "cuda:0") for n, a in s.items()}
+        if lay == "blhd":
+            t = {n: a.transpose(1, 2).contiguous() for n, a in t.items()}
+        out = vb.bigla_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], layout=lay)
+        torch.cuda.synchronize()
+        if lay == "blhd":
+            out = out.transpose(1, 2).contiguous()
+        rel = assert_close(wl.widen(wl.from_torch(out, "bf16"), "bf16"), ref, TOL["bf16"], f"stream case, {lay}")
+        _say(f"  {lay}: max|err|/max|ref| = {rel:.3e}")
+    # mild gates, one step in a hundred a hard reset of -25
+    w2 = wl.Workload("spikes", B=2, H=6, Hg=1, Wg=700, dk=64, dv=64, dtype="bf16", gate_mu=1.0)
+    s2 = wl.generate(w2, seed=77, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+    r = np.random.default_rng(78)
+    for name in ("g_fwd", "g_bwd"):
+        g = wl.widen(s2[name], "bf16")
+        g[r.random(g.shape) < 0.01] = -25.0
+        s2[name] = wl.store(g, "bf16")
+    _say(f"bigla regression {w2}")
+    ref2 = run_bigla_oracle(s2, "bf16")
+    for plan in ("auto", "wave_specialised"):
+        assert_close(run_bigla_gpu(s2, "bf16", plan=plan), ref2, TOL["bf16"], f"spikes, {plan}")
+    # strong decay (the benchmark's gate statistics), 1280 tokens: one element was 1.7 % over the bound
+    w3 = wl.Workload("decay1280", B=2, H=6, Hg=32, Wg=40, dk=64, dv=64, dtype="bf16", gate_mu=-2.0)
+    s3 = wl.generate(w3, seed=21, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+    _say(f"bigla regression {w3}")
+    ref3 = run_bigla_oracle(s3, "bf16")
+    for plan in ("auto", "wave_specialised"):
+        rel = assert_close(run_bigla_gpu(s3, "bf16", plan=plan), ref3, TOL["bf16"], f"decay1280, {plan}")
+        _say(f"  {plan}: max|err|/max|ref| = {rel:.3e}")
+
+
+@pytest.mark.parametrize("L", (1, 2, 3, 5, 31))
+def test_bigla_bwd_regression_tiny_slabs(L):
+    """Slabs of a few tokens (inputs scaled by 1/4, gates near 1, both layouts): three-token slabs once
+    reached 1.13 times the bound for dv on the chunkwise kernels, which a CPU emulation of their operand
+    roundings reproduces; sequences this short now run the exact kernels.  Several seeds, among them
+    those on which the emulation exceeds the bound."""
+    for seed in (310, 276, 332, 185, 7):
+        w = wl.Workload(f"tiny{L}", B=2, H=3, Hg=1, Wg=L, dk=64, dv=64, dtype="bf16", gate_mu=2.54)
+        s = _bwd_inputs(w, seed=seed)
+        for n in ("q", "k", "v"):
+            s[n] = wl.store(wl.widen(s[n], "bf16") * 0.25, "bf16")
+        for layout in ("bhld", "blhd"):
+            worst = _check_bwd(s, "bf16", layout, "auto", what=f"tiny L={L} seed {seed} {layout}")
+        _say(f"tiny slabs L={L} seed {seed}: worst error / bound = {worst:.3f}")
+        assert_close(run_bigla_gpu(s, "bf16"), run_bigla_oracle(s, "bf16"), TOL["bf16"], f"tiny forward L={L}")
 
 
 @pytest.mark.parametrize("dtype", ("bf16", "f32"))
@@ -323,10 +410,12 @@ def test_path_end_to_end_hierarchical_stage_shapes(grid, H):
     (1, 1, 70, 1, 64, "bhld", 0.0, True),
 ])
 def test_bigla_locality_plans(B, H, Hg, Wg, dk, layout, mu, with_bias):
-    """Token mixer + locality blend as one call: the fused-epilogue plan (the blend inside the chunkwise
-    output pass) and the two-launch plan return the same bits as the two separate entry points, and
-    the result is the oracle's chain within the path's tolerance.  The conv input is a tensor of
-    its own (not the mixer's v)."""
+    """Token mixer + locality blend as one call: the two-launch plan returns the same bits as the two
+    separate entry points; the fused-epilogue plan (the blend inside the output pass of the four-wave
+    chunkwise kernels, whose operand roundings differ from those of the wave-specialised kernels that
+    bigla_fwd may run) agrees with them to a few bf16 steps of the mixer's output; both are the
+    oracle's chain within the path's tolerance.  The conv input is a tensor of its own (not the
+    mixer's v)."""
     import torch
     from paper_2405_18425_amd import binding as vb
     import oracle
@@ -350,10 +439,9 @@ def test_bigla_locality_plans(B, H, Hg, Wg, dk, layout, mu, with_bias):
         outs[plan] = vb.bigla_locality_fwd(t["q"], t["k"], t["v"], t["g_fwd"], t["g_bwd"], t["x"], t["conv_w"],
                                            t["gate_logits"], Hg, Wg, bias=tb, layout=layout, plan=plan)
     torch.cuda.synchronize()
-    for plan, o in outs.items():
+    for plan in ("two_launches", "auto"):
+        o = outs[plan]
         assert torch.equal(o, separate), f"{plan}: {(o != separate).sum().item()} elements differ from the separate calls"
-    got = outs["fused_epilogue"].transpose(1, 2) if layout == "blhd" else outs["fused_epilogue"]
-    got64 = wl.widen(wl.from_torch(got.contiguous(), w.dtype), w.dtype)
     ref_og = oracle.bigla(wd["q"], wd["k"], wd["v"], wd["g_fwd"], wd["g_bwd"])
     ref = oracle.locality_gate(wd["x"], wd["conv_w"], wd["gate_logits"], ref_og, Hg, Wg, bias64)
     assert np.array_equal(ref, oracle.bigla_locality(wd["q"], wd["k"], wd["v"], wd["g_fwd"], wd["g_bwd"], wd["x"],
@@ -362,7 +450,10 @@ def test_bigla_locality_plans(B, H, Hg, Wg, dk, layout, mu, with_bias):
     tol = TOL[w.dtype]
     rms = lambda a: np.sqrt(np.mean(a ** 2, axis=(2, 3), keepdims=True))
     bound = tol * (np.abs(ref) + rms(ref) + np.abs(ref_og) + rms(ref_og))
-    assert np.all(np.abs(got64 - ref) <= bound), float(np.max(np.abs(got64 - ref) - bound))
+    for plan in ("fused_epilogue", "two_launches"):
+        got = outs[plan].transpose(1, 2) if layout == "blhd" else outs[plan]
+        got64 = wl.widen(wl.from_torch(got.contiguous(), w.dtype), w.dtype)
+        assert np.all(np.abs(got64 - ref) <= bound), (plan, float(np.max(np.abs(got64 - ref) - bound)))
 
 
 def test_bigla_locality_other_shapes_take_two_launches():
@@ -592,11 +683,9 @@ def _bwd_inputs(w, seed):
     return s
 
 
-def _check_bwd(s, dtype, layout, plan, slabs=None, what="", pool=False):
+def _check_bwd(s, dtype, layout, plan, slabs=None, what=""):
     """bigla_bwd on the stored inputs s against the oracle's gradient (on all slabs, or on a
-    sample of (b, h) slabs: a slab's gradients depend on that slab only).  pool: the rms that
-    floors the bound is taken over all slabs together (slabs of a few tokens have no scale of
-    their own: a handful of cancelling dot products)."""
+    sample of (b, h) slabs: a slab's gradients depend on that slab only)."""
     import torch
     from paper_2405_18425_amd import binding as vb
     import oracle
@@ -613,10 +702,6 @@ def _check_bwd(s, dtype, layout, plan, slabs=None, what="", pool=False):
         wd = {n: np.stack([a[b, h] for (b, h) in slabs])[None] for n, a in wd.items()}
         got = [np.stack([a[b, h] for (b, h) in slabs])[None] for a in got]
     ref = oracle.bigla_bwd(*(wd[n] for n in BWD_NAMES))
-    if pool:
-        flat = lambda a: a.reshape(1, 1, -1, a.shape[-1])
-        wd = {n: flat(a) for n, a in wd.items()}
-        got, ref = [flat(a) for a in got], [flat(a) for a in ref]
     # The gate gradients are running sums of q * dq - k * dk (Section 4.2.1 differentiated): their
     # rounding error scales with those summands, not with the result, which is exactly zero where
     # a gate is inert (g_fwd of the first token, g_bwd of the last) and can be small elsewhere.
