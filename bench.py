@@ -10,10 +10,13 @@ Inputs are resident in HBM before the timed region.  The timed loop rotates thro
 independent buffer sets whose total size exceeds the 256 MB Infinity Cache, so that every step
 streams its operands from HBM rather than from a warm cache.
 
-Prints ONE JSON line (see the design doc for the fields).  `roofline` times the dominant kernel
-with HIP events recorded on its own stream inside the library (a second pass of the same K
-steps, so that event recording does not perturb `value`); `cpu_baseline` times the CPU oracle
-on the same workload on the host cores.
+Prints ONE JSON line.  `roofline` is that of the dominant entry
+point, bigla_fwd: its algorithmic bytes over the summed duration of ALL its launches, which are
+timed with HIP events recorded on their own stream inside the library (a second pass of the same
+K steps, so that event recording does not perturb `value`; the cost of an event pair itself is
+measured on an empty pair and taken off every duration).  `roofline.traffic` is read from the
+table in profiles/hbm_traffic.md that the rocprofv3 counter runs wrote.  `cpu_baseline` times the
+CPU oracle on the same workload on the host cores.
 """
 from __future__ import annotations
 
@@ -31,14 +34,23 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA peak
 CACHE_BYTES = 256 << 20        # Infinity Cache; buffer sets rotate over more than this
 
-# HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/bigla_path_vig_s_1024.md (read + written, calibrated with a plain copy), keyed by
-# (kernel, workload); None for pairs that were not profiled.
-MEASURED_TRAFFIC_BYTES = {
-    ("segment_out", "vig_s_1024"): 193.6e6,
-    ("segment_state", "vig_s_1024"): 138.8e6,
-    ("locality_gate", "vig_s_1024"): 109.2e6,
-}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+BIGLA_KERNELS = ("segment_state", "segment_out", "segment_out_general", "slab", "recurrent")
+
+
+def measured_traffic():
+    """HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: the rows
+    `| workload | kernel | read MB | written MB | bytes |` of profiles/hbm_traffic.md (written by
+    `profile_path.py traffic`), keyed by (workload, kernel).  Missing file or row: no figure."""
+    table = {}
+    try:
+        for line in open(TRAFFIC_TABLE):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) == 5 and cells[4].isdigit():
+                table[(cells[0], cells[1])] = int(cells[4])
+    except OSError:
+        pass
+    return table
 
 
 def parse_args():
@@ -57,6 +69,11 @@ def parse_args():
                          "measurement in detail.backward; not part of the step or of value)")
     ap.add_argument("--layout", choices=("bhld", "blhd"), default="bhld",
                     help="activation layout: head-major (default) or token-major [B,L,H,d] (side measurement)")
+    ap.add_argument("--fwd-plan", choices=("auto", "four_wave", "wave_specialised"), default="auto",
+                    help="kernels of the chunkwise forward (side measurement; auto is what bigla_fwd runs)")
+    ap.add_argument("--alias-slabs", action="store_true",
+                    help="side measurement of the contraction phase: every slab reads the first slab's q, k, v and "
+                         "gates (cache-resident inputs; outputs still written; one buffer set)")
     return ap.parse_args()
 
 
@@ -64,7 +81,7 @@ def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU; multi-GPU runs are not part of it "
-              "(the path shards over (batch, head) slabs with no exchange -- see DESIGN.md).", file=sys.stderr)
+              "(the path shards over (batch, head) slabs with no exchange).", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -87,7 +104,7 @@ def main():
     stored = wl.generate(w, seed=args.seed)
     base = {n: wl.to_torch(a, w.dtype, dev) for n, a in stored.items()}
     set_bytes = sum(t.numel() * t.element_size() for t in base.values()) + 2 * base["v"].numel() * esize
-    n_sets = 1 if args.single_set else max(2, -(-2 * CACHE_BYTES // set_bytes))
+    n_sets = 1 if (args.single_set or args.alias_slabs) else max(2, -(-2 * CACHE_BYTES // set_bytes))
     sets = []
     for i in range(n_sets):
         s = {n: (t if i == 0 or n == "conv_w" else torch.roll(t, shifts=i, dims=0).contiguous())
@@ -104,10 +121,12 @@ def main():
     def step(i):
         s = sets[i % n_sets]
         vb.bigla_fwd(s["q"], s["k"], s["v"], s["g_fwd"], s["g_bwd"], out=s["o_global"], workspace=workspace,
-                     layout=args.layout)
+                     layout=args.layout, plan=args.fwd_plan)
         vb.locality_gate_fwd(s["v"], s["conv_w"], s["gate_logits"], s["o_global"], w.Hg, w.Wg, out=s["out"],
                              layout=args.layout)
 
+    if args.alias_slabs:
+        vb.measure_alias_slabs(True)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -130,32 +149,41 @@ def main():
         if n:
             kern[name] = {"avg_us": ms * 1e3 / n, "launches_per_step": n / args.steps}
     vb.timing_enable(False)
+    if args.alias_slabs:
+        vb.measure_alias_slabs(False)
+    # what an event pair costs by itself: empty pairs on the same stream
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+    for a, b in pairs:
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    pair_us = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)[len(pairs) // 2]
+    for k in kern.values():
+        k["avg_us"] = max(k["avg_us"] - pair_us, 0.0)
 
-    # ---- roofline of the dominant kernel (algorithmic bytes / flops per head-token)
-    dominant = max(kern, key=lambda n: kern[n]["avg_us"] * kern[n]["launches_per_step"])
+    # ---- roofline of the dominant entry point (algorithmic bytes / flops per head-token)
     ht = w.head_tokens
     bigla_bytes = (4 * w.dk + 2 * w.dv) * esize * ht          # q,k,g_fwd,g_bwd,v read once, out written once
     bigla_flops = (8 * w.dk * w.dv + 2 * 64 * (w.dk + w.dv)) * ht  # chunkwise form at the nominal chunk of 64
     loc_bytes = 4 * esize * ht * w.dv                          # x, z, o_global read; out written
-    if dominant == "locality_gate":
-        alg_bytes = loc_bytes
-    else:
-        # the output kernel reads q, k, v and both gates once and writes out once: its launch carries
-        # the method's full algorithmic bytes; the whole-BiGLA fraction (all launches) is in `detail`
-        alg_bytes = bigla_bytes
-    dom_us = kern[dominant]["avg_us"]
-    achieved_gbs = alg_bytes / (dom_us * 1e-6) / 1e9
+    bigla_launches = [n for n in BIGLA_KERNELS if n in kern]
+    bigla_us = sum(kern[n]["avg_us"] * kern[n]["launches_per_step"] for n in bigla_launches)
+    traffic = measured_traffic()
+    per_launch = {n: traffic.get((w.name, n)) for n in bigla_launches}
+    # bigla_fwd is the dominant entry point: its algorithmic bytes (q, k, v, both gates read once, out written
+    # once) over the time of ALL its launches; the launches one by one are in `launches`
+    achieved_gbs = bigla_bytes / (bigla_us * 1e-6) / 1e9
     roofline = {
-        "kernel": dominant, "bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-        "traffic": MEASURED_TRAFFIC_BYTES.get((dominant, w.name)),
-        "avg_us": round(dom_us, 2), "algorithmic_bytes": alg_bytes,
+        "kernel": "bigla_fwd (" + " + ".join(bigla_launches) + ")", "bound": "hbm", "achieved": round(achieved_gbs, 1),
+        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
+        "traffic": (sum(per_launch.values()) if all(v is not None for v in per_launch.values()) and not args.alias_slabs
+                    and args.fwd_plan == "auto" and args.layout == "bhld" and not args.dk else None),
+        "avg_us": round(bigla_us, 2), "algorithmic_bytes": bigla_bytes,
+        "launches": {n: {"avg_us": round(kern[n]["avg_us"], 2), "traffic": per_launch[n]} for n in bigla_launches},
     }
-    bigla_us = sum(kern[n]["avg_us"] * kern[n]["launches_per_step"]
-                   for n in ("segment_state", "segment_out", "segment_out_general", "slab", "recurrent")
-                   if n in kern)
     extra = {
         "kernels_us": {n: round(k["avg_us"] * k["launches_per_step"], 2) for n, k in kern.items()},
+        "event_pair_us": round(pair_us, 2),
         "bigla_us": round(bigla_us, 2),
         "bigla_tokens_per_s": round(w.tokens / (bigla_us * 1e-6), 1),
         "bigla_tflops": round(bigla_flops / (bigla_us * 1e-6) / 1e12, 2),
@@ -167,6 +195,9 @@ def main():
         lus = kern["locality_gate"]["avg_us"]
         extra["locality_hbm_gbs"] = round(loc_bytes / (lus * 1e-6) / 1e9, 1)
         extra["locality_frac_hbm_peak"] = round(loc_bytes / (lus * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+        extra["locality_traffic"] = traffic.get((w.name, "locality_gate"))
+    if args.alias_slabs:
+        extra["alias_slabs"] = True
 
     # ---- side measurement: the gradient of the token mixer (d_out := the gate logits, any values do)
     if args.backward:
@@ -216,7 +247,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "L": w.L, "grid": [w.Hg, w.Wg], "dk": w.dk, "dv": w.dv,
-                   "gate_logit_mean": w.gate_mu, "layout": args.layout, "buffer_sets": n_sets, "set_bytes": set_bytes},
+                   "gate_logit_mean": w.gate_mu, "layout": args.layout, "buffer_sets": n_sets, "set_bytes": set_bytes,
+                   "fwd_plan": args.fwd_plan},
         "roofline": roofline, "cpu_baseline": cpu, "detail": extra,
     }
     print(json.dumps(line), flush=True)

@@ -103,15 +103,17 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
 /*
  * bigla_fwd_layout with a choice among the kernels that evaluate the chunkwise form (Section 4.2.1,
  * Eq. (BiGLA); a measurement and testing aid: the result is the same up to operand rounding).
- *   VIG_FWD_AUTO              what bigla_fwd_layout runs: at present the four-wave kernels;
+ *   VIG_FWD_AUTO              what bigla_fwd_layout runs: the eight-wave kernels where they apply,
+ *                             the four-wave kernels elsewhere;
  *   VIG_FWD_FOUR_WAVE         workgroups of four waves, each wave walking the whole chain of a chunk
  *                             step for its 16 tokens;
  *   VIG_FWD_WAVE_SPECIALISED  workgroups of eight waves: producer waves (gate scans, exponentials, scaled
  *                             keys, score tiles, P.V) and consumer waves (state readouts, output rows,
  *                             state update) on the same SIMDs, one chunk apart.  VIG_BF16 with
  *                             dk = dv = 64 and at least two chunks, except short sequences in many slabs
- *                             (VIG_ERR_UNSUPPORTED otherwise).  Gates outside the fast form's range make
- *                             the four-wave kernels redo the call inside the same call.
+ *                             (VIG_ERR_UNSUPPORTED otherwise).  A (slab, segment) unit whose gates are
+ *                             outside the fast form's range is evaluated by the general four-wave code
+ *                             inside the same launches.
  * Workspace as for bigla_fwd_layout.  Unknown plan: VIG_ERR_UNSUPPORTED.
  */
 typedef enum { VIG_FWD_AUTO = 0, VIG_FWD_FOUR_WAVE = 1, VIG_FWD_WAVE_SPECIALISED = 2 } vig_fwd_plan;
@@ -279,6 +281,16 @@ typedef enum {
 } vig_kernel;
 int vig_timing_enable(int on);
 int vig_timing_collect(int kernel, double *total_ms, long *launches);
+
+/*
+ * Measurement aid (no part of the method): vig_measure_alias_slabs(1) makes the chunkwise kernels of
+ * bigla_fwd read the q, k, v and gates of the first (batch, head) slab for every slab, so that those
+ * inputs stay cache-resident and the kernels' contractions can be timed without the stream from memory
+ * (outputs, and the workspace, are still written per slab; results are meaningless).  0 restores normal
+ * operation.  The call synchronises the device (it copies a flag into the kernels' constant state) and
+ * applies to every later call from any thread.
+ */
+int vig_measure_alias_slabs(int on);
 
 /* Human-readable name of a vig_status (static storage, never NULL). */
 const char *vig_status_str(int status);

@@ -31,7 +31,7 @@ EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "bigla_fwd_
            "locality_gate_fwd_layout", "bigla_locality_workspace_bytes", "bigla_locality_fwd", "gate_producer_fwd",
            "bigla_bwd_workspace_bytes", "bigla_bwd", "bigla_bwd_plan",
            "vig_status_str", "vig_last_hip_error", "vig_timing_enable",
-           "vig_timing_collect")
+           "vig_timing_collect", "vig_measure_alias_slabs")
 KERNELS = {"segment_state": 0, "segment_out": 2, "recurrent": 3, "locality_gate": 4,
            "segment_out_general": 5, "gate_producer": 6, "slab": 7, "backward": 8}
 
@@ -85,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.vig_last_hip_error.restype = ci
         L.vig_timing_enable.argtypes = [ci]
         L.vig_timing_enable.restype = ci
+        L.vig_measure_alias_slabs.argtypes = [ci]
+        L.vig_measure_alias_slabs.restype = ci
         L.vig_timing_collect.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_long)]
         L.vig_timing_collect.restype = ci
         _lib = L
@@ -370,3 +372,8 @@ def timing_collect(kernel: str):
     ms, n = ctypes.c_double(0.0), ctypes.c_long(0)
     _check(lib().vig_timing_collect(KERNELS[kernel], ctypes.byref(ms), ctypes.byref(n)), "vig_timing_collect")
     return ms.value, n.value
+
+
+def measure_alias_slabs(on: bool) -> None:
+    """Measurement aid: make every slab of the chunkwise forward kernels read slab 0's inputs."""
+    _check(lib().vig_measure_alias_slabs(1 if on else 0), "vig_measure_alias_slabs")

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvig_bigla.so")
-SOURCES = ("vig_api.hip", "vig_timing.hip", "bigla_recurrent.hip", "bigla_chunk.hip", "bigla_chunk_ws.hip", "locality_gate.hip",
+SOURCES = ("vig_api.hip", "vig_timing.hip", "bigla_recurrent.hip", "bigla_chunk.hip", "locality_gate.hip",
            "gate_producer.hip", "bigla_bwd.hip", "bigla_bwd_chunk.hip")
 # packed-fp32 VALU forms are kept off: plain float code must not be fused into v_pk_*_f32
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -521,17 +521,9 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
 // compiled general code address the same allocation as LDS (not through a generic reference).
 // The state pass and the output pass use it one after the other (the single-launch kernel for
 // one-segment plans runs both).
-// The wave-specialised kernels evaluate the fast form only and leave one flag per unit of THEIR plan
-// (0: some chunk is outside its range).  After them these kernels are launched with those flags and
-// redo the whole call if any is 0; otherwise every workgroup exits here.  redo_flags == nullptr:
-// a call of its own, always run.
-__device__ __forceinline__ bool redo_requested(const int *redo_flags, int n_redo)
-{
-    if (redo_flags == nullptr) return true;
-    int bad = 0;
-    for (int i = threadIdx.x; i < n_redo; i += kThreads) bad |= redo_flags[i] == 0;
-    return __syncthreads_or(bad) != 0;
-}
+// Measurement aid: when set (vig_measure_alias_slabs), every slab reads the inputs of slab 0, so that q, k,
+// v and the gates stay cache-resident while outputs and workspace are still written per slab.
+__device__ int g_alias_inputs = 0;
 
 union PathLds {
     OutLds out;
@@ -539,16 +531,26 @@ union PathLds {
 };
 __shared__ PathLds g_lds;
 
+// The LDS of a unit function: the four-wave kernels' own allocation, or, when the eight-wave kernels call
+// the general code for a unit outside the fast form's range (kInWs), the front of THEIR allocation.
+template <bool kInWs>
+__device__ __forceinline__ PathLds &path_lds();
+template <>
+__device__ __forceinline__ PathLds &path_lds<false>()
+{
+    return g_lds;
+}
+
 // kLoc: the 2D gating locality injection of `lf` is applied to every chunk's rows before they are
 // written, so that `out_all` receives the block output instead of the token mixer's.
-template <bool kFastOnly, int kDk, bool kTm, bool kLoc>
+template <bool kFastOnly, int kDk, bool kTm, bool kLoc, bool kInWs = false>
 __device__ __forceinline__ void out_unit(
     const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
     const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
     const float *__restrict__ seg_states, const unsigned char *__restrict__ stash_all, int L, int n_chunks,
     int seg_chunks, int n_seg, const long unit, int heads, const LocalityFusion &lf)
 {
-    OutLds &sm = g_lds.out;
+    OutLds &sm = path_lds<kInWs>().out;
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
     // The fast-form code of a 32-wide head skips the zero half of the key dimension: one K-step per
@@ -561,7 +563,8 @@ __device__ __forceinline__ void out_unit(
     unit_slab_segment(unit, n_seg, slab, seg);
     // first row of the slab and distance between its tokens, in rows of the tensor
     const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
-    const long base = row0 * kD, key_base = row0 * kDk;
+    const long row0_in = g_alias_inputs ? 0 : row0;
+    const long base = row0 * kD, in_base = row0_in * kD, key_base = row0_in * kDk;
     // bytes between consecutive tokens of the slab, and the slab's extent from its first row
     const unsigned key_pitch = unsigned(heads) * kDk * 2u, val_pitch = unsigned(heads) * kD * 2u;
     const unsigned key_extent = unsigned(L - 1) * key_pitch + kDk * 2u, val_extent = unsigned(L - 1) * val_pitch + kD * 2u;
@@ -569,7 +572,7 @@ __device__ __forceinline__ void out_unit(
     const __amdgpu_buffer_rsrc_t k = slab_resource(k_all + key_base, key_extent);
     const __amdgpu_buffer_rsrc_t g_fwd = slab_resource(gf_all + key_base, key_extent);
     const __amdgpu_buffer_rsrc_t g_bwd = slab_resource(gb_all + key_base, key_extent);
-    const __amdgpu_buffer_rsrc_t v = slab_resource(v_all + base, val_extent);
+    const __amdgpu_buffer_rsrc_t v = slab_resource(v_all + in_base, val_extent);
     const __amdgpu_buffer_rsrc_t out = slab_resource(out_all + base, val_extent);
     const unsigned char *stash = stash_all + size_t(slab) * n_chunks * kStashBytes;
 
@@ -764,14 +767,14 @@ __device__ __forceinline__ void out_unit(
     }
 }
 
-template <int kDk, bool kTm, bool kLoc>
+template <int kDk, bool kTm, bool kLoc, bool kInWs = false>
 __device__ __attribute__((noinline)) void out_unit_general(
     const uint16_t *q_all, const uint16_t *k_all, const uint16_t *v_all, const uint16_t *gf_all, const uint16_t *gb_all,
     uint16_t *out_all, const float *seg_states, const unsigned char *stash_all, int L, int n_chunks, int seg_chunks,
     int n_seg, const long unit, int heads, const LocalityFusion &lf)
 {
-    out_unit<false, kDk, kTm, kLoc>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L, n_chunks,
-                                    seg_chunks, n_seg, unit, heads, lf);
+    out_unit<false, kDk, kTm, kLoc, kInWs>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
+                                           n_chunks, seg_chunks, n_seg, unit, heads, lf);
 }
 
 // One workgroup per (slab, segment) unit.  kByFlag: units the state kernel flagged as mild run the
@@ -785,10 +788,8 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
     const float *__restrict__ seg_states /* states entering each segment, nullptr when one segment */,
     const int *__restrict__ seg_mild /* per unit: every chunk admits the fast form (kByFlag) */,
     const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg,
-    int heads /* used when kTm: activations are [B,L,H,d] */, const LocalityFusion lf /* used when kLoc */,
-    const int *__restrict__ redo_flags, int n_redo)
+    int heads /* used when kTm: activations are [B,L,H,d] */, const LocalityFusion lf /* used when kLoc */)
 {
-    if (!redo_requested(redo_flags, n_redo)) return;
     const long unit = blockIdx.x;
     if (kByFlag && seg_mild[unit] != 0)  // uniform over the workgroup
         out_unit<true, kDk, kTm, kLoc>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
@@ -805,19 +806,19 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_out_kernel(
 // kFwd = false (only with seg_states == nullptr): nothing reads the forward end state, so the fast
 // form skips the forward direction altogether (its cumulative gates, scaled keys and K^T V); the
 // forward chunk totals are still formed, for the choice of the form.
-template <int kDk, bool kTm, bool kFwd = true>
+template <int kDk, bool kTm, bool kFwd = true, bool kInWs = false>
 __device__ __forceinline__ bool state_unit(
     const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all, const uint16_t *__restrict__ gf_all,
     const uint16_t *__restrict__ gb_all, float *__restrict__ seg_states, unsigned char *__restrict__ stash, int L,
     int n_chunks, int seg_chunks, int n_seg, const long unit, int heads)
 {
-    StateLds &sm = g_lds.state;
+    StateLds &sm = path_lds<kInWs>().state;
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
     long slab;
     int seg;
     unit_slab_segment(unit, n_seg, slab, seg);
-    const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
+    const long row0 = g_alias_inputs ? 0 : (kTm ? (slab / heads) * L * heads + slab % heads : slab * L);
     // bytes between consecutive tokens of the slab, and the slab's extent from its first row
     const unsigned key_pitch = unsigned(heads) * kDk * 2u, val_pitch = unsigned(heads) * kD * 2u;
     const unsigned key_extent = unsigned(L - 1) * key_pitch + kDk * 2u, val_extent = unsigned(L - 1) * val_pitch + kD * 2u;
@@ -1063,9 +1064,8 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_segment_state_kernel(
     const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, const uint16_t *__restrict__ g_fwd,
     const uint16_t *__restrict__ g_bwd, float *__restrict__ seg_states, int *__restrict__ seg_mild,
     unsigned char *__restrict__ stash, int L, int n_chunks, int seg_chunks, int n_seg,
-    int heads /* used when kTm: activations are [B,L,H,d] */, const int *__restrict__ redo_flags, int n_redo)
+    int heads /* used when kTm: activations are [B,L,H,d] */)
 {
-    if (!redo_requested(redo_flags, n_redo)) return;
     const bool all_fast =
         state_unit<kDk, kTm>(k, v, g_fwd, g_bwd, seg_states, stash, L, n_chunks, seg_chunks, n_seg, blockIdx.x, heads);
     if (threadIdx.x == 0) seg_mild[blockIdx.x] = all_fast ? 1 : 0;
@@ -1079,10 +1079,8 @@ template <int kDk, bool kTm, bool kLoc>
 __global__ __launch_bounds__(kThreads, 2) void bigla_slab_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
     const uint16_t *__restrict__ g_fwd, const uint16_t *__restrict__ g_bwd, uint16_t *__restrict__ out,
-    unsigned char *__restrict__ stash, int L, int n_chunks, int heads, const LocalityFusion lf,
-    const int *__restrict__ redo_flags, int n_redo)
+    unsigned char *__restrict__ stash, int L, int n_chunks, int heads, const LocalityFusion lf)
 {
-    if (!redo_requested(redo_flags, n_redo)) return;
     const long unit = blockIdx.x;
     const bool all_fast =
         state_unit<kDk, kTm, false>(k, v, g_fwd, g_bwd, nullptr, stash, L, n_chunks, n_chunks, 1, unit, heads);
@@ -1097,6 +1095,12 @@ __global__ __launch_bounds__(kThreads, 2) void bigla_slab_kernel(
 
 }  // namespace
 
+}  // namespace vig
+
+#include "bigla_chunk_ws.hpp"
+
+namespace vig {
+
 bool bigla_chunk_supported(int dk, int dv, bool is_bf16) { return is_bf16 && dv == kD && (dk == kD || dk == kD / 2); }
 
 namespace {
@@ -1110,21 +1114,20 @@ size_t four_wave_bytes(long BH, int L)
     const Plan p = make_plan(BH, L);
     return seg_region_bytes(BH, p) + flag_region_bytes(BH, p) + size_t(BH) * p.n_chunks * kStashBytes;
 }
-// where the wave-specialised kernels leave their unit flags: beyond everything either path writes
-size_t ws_flags_offset(long BH, int L)
-{
-    const size_t a = four_wave_bytes(BH, L), b = bigla_chunk_ws_core_bytes(BH, L);
-    return ((a > b ? a : b) + 255) / 256 * 256;
-}
 }  // namespace
 
-size_t bigla_chunk_workspace_bytes(long BH, int L) { return ws_flags_offset(BH, L) + bigla_chunk_ws_flag_bytes(BH, L); }
+// either set of kernels may run a call: the workspace holds the larger of the two layouts
+size_t bigla_chunk_workspace_bytes(long BH, int L)
+{
+    const size_t a = four_wave_bytes(BH, L), b = bigla_chunk_ws_workspace_bytes(BH, L);
+    return a > b ? a : b;
+}
 
 namespace {
 template <int kDk, bool kTm, bool kLoc>
 hipError_t chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd, void *out,
                         long BH, int L, int heads_token_major, const LocalityFusion &lf, void *workspace,
-                        const int *redo_flags, int n_redo, hipStream_t stream)
+                        hipStream_t stream)
 {
     const Plan p = make_plan(BH, L);
     const long blocks = BH * p.n_seg;
@@ -1140,7 +1143,7 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
     if (p.n_seg == 1 && p.n_chunks > 1) {  // one workgroup per slab does both passes in one launch
         LaunchTimer timer(kKernelSlab, stream);
         hipLaunchKernelGGL((bigla_slab_kernel<kDk, kTm, kLoc>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, qq,
-                           kk, vv, gf, gb, oo, stash, L, p.n_chunks, heads_token_major, lf, redo_flags, n_redo);
+                           kk, vv, gf, gb, oo, stash, L, p.n_chunks, heads_token_major, lf);
         return hipGetLastError();
     }
     if (p.n_chunks > 1) {  // a single chunk has neither a stash nor entering states
@@ -1148,7 +1151,7 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
             LaunchTimer timer(kKernelSegmentState, stream);
             hipLaunchKernelGGL((bigla_segment_state_kernel<kDk, kTm>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, kk, vv,
                                gf, gb, seg_states, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg,
-                               heads_token_major, redo_flags, n_redo);
+                               heads_token_major);
         }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -1160,40 +1163,39 @@ hipError_t chunk_launch(const void *q, const void *k, const void *v, const void 
         if (flags)
             hipLaunchKernelGGL((bigla_segment_out_kernel<true, kDk, kTm, kLoc>), dim3((unsigned)blocks),
                                dim3(kThreads), 0, stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks,
-                               p.seg_chunks, p.n_seg, heads_token_major, lf, redo_flags, n_redo);
+                               p.seg_chunks, p.n_seg, heads_token_major, lf);
         else  // a single chunk per sequence: no state kernel has run, no flags exist
             hipLaunchKernelGGL((bigla_segment_out_kernel<false, kDk, kTm, kLoc>), dim3((unsigned)blocks),
                                dim3(kThreads), 0, stream, qq, kk, vv, gf, gb, oo, seg_in, flags, stash, L, p.n_chunks,
-                               p.seg_chunks, p.n_seg, heads_token_major, lf, redo_flags, n_redo);
+                               p.seg_chunks, p.n_seg, heads_token_major, lf);
     }
     return hipGetLastError();
 }
 }  // namespace
 
+hipError_t bigla_chunk_set_alias(int on) { return hipMemcpyToSymbol(HIP_SYMBOL(g_alias_inputs), &on, sizeof(int)); }
+
 bool bigla_chunk_ws_selectable(long BH, int L, int dk) { return bigla_chunk_ws_applicable(BH, L, dk); }
 
 hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
                               void *out, long BH, int L, int dk, int heads_token_major, const LocalityFusion *fusion,
-                              bool wave_specialised, void *workspace, hipStream_t stream)
+                              int kernels, void *workspace, hipStream_t stream)
 {
     const bool tm = heads_token_major > 0;
     const int heads = tm ? heads_token_major : 1;
     if (dk != kD && dk != kD / 2) return hipErrorInvalidValue;
     const LocalityFusion none = {};
     // (key width, layout, fused epilogue) pick the instantiation
-    // On request the wave-specialised kernels run first; the four-wave kernels launched after them exit
-    // at once unless a unit's gates were outside the fast form's range (they then redo the call).
-    const int *redo_flags = nullptr;
-    int n_redo = 0;
-    if (wave_specialised) {
-        if (fusion || !bigla_chunk_ws_applicable(BH, L, dk)) return hipErrorInvalidValue;
-        const hipError_t e = bigla_chunk_ws_launch(q, k, v, g_fwd, g_bwd, out, BH, L, heads_token_major, workspace,
-                                                   ws_flags_offset(BH, L), &redo_flags, &n_redo, stream);
-        if (e != hipSuccess) return e;
+    // kernels: 0 = the faster set for the shape (the eight-wave kernels where they apply), 1 = four-wave,
+    // 2 = eight-wave (an error where they do not apply)
+    const bool ws_ok = !fusion && bigla_chunk_ws_applicable(BH, L, dk);
+    if (kernels == 2 && !ws_ok) return hipErrorInvalidValue;
+    if (kernels == 2 || (kernels == 0 && ws_ok)) {
+        return bigla_chunk_ws_launch(q, k, v, g_fwd, g_bwd, out, BH, L, heads_token_major, workspace, stream);
     }
     auto go = [&](auto dk_c, auto tm_c, auto loc_c) {
         return chunk_launch<decltype(dk_c)::value, decltype(tm_c)::value, decltype(loc_c)::value>(
-            q, k, v, g_fwd, g_bwd, out, BH, L, heads, fusion ? *fusion : none, workspace, redo_flags, n_redo, stream);
+            q, k, v, g_fwd, g_bwd, out, BH, L, heads, fusion ? *fusion : none, workspace, stream);
     };
     using std::integral_constant;
     using std::true_type;

@@ -26,17 +26,17 @@
 // (x = hi + lo to 16 bits), so that of the four operand roundings of the chunkwise form only those
 // of the scaled queries and keys (and of the stashed backward state) remain.
 //
-// Range.  These kernels evaluate the FAST form only (queries q exp(b), keys k exp(-b), see
+// Range.  The eight-wave code evaluates the FAST form only (queries q exp(b), keys k exp(-b), see
 // bigla_chunk.hip).  The state pass checks every chunk's total log-decay against the fast form's
-// range and leaves one flag per (slab, segment) unit; if any unit of a call is outside, the
-// four-wave kernels, which are launched after these and otherwise exit at once, redo the whole
-// call with both forms.
-#include <type_traits>
-
-#include "bigla_chunk_tiles.hpp"
-#include "vig_common.hpp"
-#include "vig_kernels.hpp"
-#include "vig_timing.hpp"
+// range while it works; a (slab, segment) unit that turns out to be outside is redone on the spot,
+// by the general four-wave code of bigla_chunk.hip on four of the workgroup's eight waves (the other
+// four have left: a workgroup barrier waits for the surviving waves only), and flagged, and the
+// output pass runs the general code for the flagged units in the same way.  Nothing else changes:
+// both codes read and write the same workspace layout.
+//
+// This file is part of the translation unit of bigla_chunk.hip (included by it, after the four-wave
+// device code it calls).
+#pragma once
 
 // Phase markers for a timing build (a harness defines WS_MARK to record the cycle counter); inert here.
 #ifndef WS_MARK
@@ -74,8 +74,15 @@ struct __align__(16) WsOutLds {
 union WsLds {
     WsStateLds state;
     WsOutLds out;
+    PathLds general;  // the general four-wave code, for a unit outside the fast form's range
 };
 __shared__ WsLds g_ws_lds;
+
+template <>
+__device__ __forceinline__ PathLds &path_lds<true>()
+{
+    return g_ws_lds.general;
+}
 
 // Plan of the wave-specialised path: about one workgroup per CU.
 inline Plan make_ws_plan(long BH, int L)
@@ -100,13 +107,14 @@ struct SlabIo {
                                       int L, int heads)
     {
         const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
+        const long in0 = g_alias_inputs ? 0 : row0;
         pitch = unsigned(kTm ? heads : 1) * kD * 2u;
         const unsigned extent = unsigned(L - 1) * pitch + kD * 2u;
-        q = slab_resource(q_all ? q_all + row0 * kD : nullptr, q_all ? extent : 0u);
-        k = slab_resource(k_all + row0 * kD, extent);
-        gf = slab_resource(gf_all + row0 * kD, extent);
-        gb = slab_resource(gb_all + row0 * kD, extent);
-        v = slab_resource(v_all + row0 * kD, extent);
+        q = slab_resource(q_all ? q_all + in0 * kD : nullptr, q_all ? extent : 0u);
+        k = slab_resource(k_all + in0 * kD, extent);
+        gf = slab_resource(gf_all + in0 * kD, extent);
+        gb = slab_resource(gb_all + in0 * kD, extent);
+        v = slab_resource(v_all + in0 * kD, extent);
         out = slab_resource(out_all ? out_all + row0 * kD : nullptr, out_all ? extent : 0u);
     }
 };
@@ -260,7 +268,7 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
             }
             __syncthreads();
         }
-        if (seg_states) {
+        if (seg_states && sm.not_fast == 0) {  // (a unit outside the fast form's range is redone below)
             float *dst = seg_states + (slab * n_seg + seg) * kSegFloats;
 #pragma unroll
             for (int jt = 0; jt < 4; ++jt) {
@@ -273,7 +281,20 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
             }
         }
     }
-    if (tid == 0) seg_mild[blockIdx.x] = sm.not_fast ? 0 : 1;
+    // (every write of not_fast precedes the loops' last barrier)
+    const bool redo = sm.not_fast != 0;
+    if (tid == 0) seg_mild[blockIdx.x] = redo ? 0 : 1;
+    if (redo) {
+        // some chunk is outside the fast form's range: the general code redoes the unit on four waves
+        // (it overwrites everything the walk above has written for this unit)
+        if (wave >= 4) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // this wave's stash stores are out before it leaves
+            return;
+        }
+        __syncthreads();  // waits for the four waves that stay (and for the others to have left)
+        state_unit<kD, kTm, true, true>(k_all, v_all, gf_all, gb_all, seg_states, stash, L, n_chunks, seg_chunks, n_seg,
+                                        blockIdx.x, heads);
+    }
 }
 
 // ---- output pass -----------------------------------------------------------------------------------
@@ -289,13 +310,15 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
     const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
     const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
     const float *__restrict__ seg_states /* nullptr when one segment per slab */, const int *__restrict__ seg_mild,
-    int n_units, const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg, int heads)
+    const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg, int heads)
 {
-    // the whole call is redone by the four-wave kernels when any unit is outside the fast form's range
-    {
-        int bad = 0;
-        for (int i = threadIdx.x; i < n_units; i += kWsThreads) bad |= seg_mild[i] == 0;
-        if (__syncthreads_or(bad)) return;
+    if (seg_mild[blockIdx.x] == 0) {  // uniform over the workgroup
+        // a unit outside the fast form's range: the general four-wave code, on four waves
+        if (threadIdx.x >= 256) return;
+        const LocalityFusion none = {};
+        out_unit_general<kD, kTm, false, true>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
+                                               n_chunks, seg_chunks, n_seg, blockIdx.x, heads, none);
+        return;
     }
     WsOutLds &sm = g_ws_lds.out;
     const int tid = threadIdx.x;
@@ -561,7 +584,7 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
     }
 }
 
-}  // namespace
+// ---- host side ---------------------------------------------------------------------------------------
 
 bool bigla_chunk_ws_applicable(long BH, int L, int dk)
 {
@@ -571,24 +594,16 @@ bool bigla_chunk_ws_applicable(long BH, int L, int dk)
     return dk == kD && p.n_chunks > 1;
 }
 
-// Workspace of this path: [segment states][stash] as in the four-wave path (for this path's own
-// plan), and one flag per (slab, segment) unit at an offset the caller chooses: beyond everything
-// that the four-wave kernels write when they redo a call, since they read the flags while doing so.
-size_t bigla_chunk_ws_core_bytes(long BH, int L)
+// [segment states][unit flags][stash], as in the four-wave path, for this path's own plan
+size_t bigla_chunk_ws_workspace_bytes(long BH, int L)
 {
     const Plan p = make_ws_plan(BH, L);
-    return size_t(BH) * p.n_seg * kSegFloats * sizeof(float) + size_t(BH) * p.n_chunks * kStashBytes;
-}
-
-size_t bigla_chunk_ws_flag_bytes(long BH, int L)
-{
-    const Plan p = make_ws_plan(BH, L);
-    return (size_t(BH) * p.n_seg * sizeof(int) + 15) / 16 * 16;
+    return size_t(BH) * p.n_seg * kSegFloats * sizeof(float) + (size_t(BH) * p.n_seg * sizeof(int) + 15) / 16 * 16 +
+           size_t(BH) * p.n_chunks * kStashBytes;
 }
 
 hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
-                                 void *out, long BH, int L, int heads_token_major, void *workspace, size_t flags_offset,
-                                 const int **unit_flags, int *n_units, hipStream_t stream)
+                                 void *out, long BH, int L, int heads_token_major, void *workspace, hipStream_t stream)
 {
     const Plan p = make_ws_plan(BH, L);
     const long blocks = BH * p.n_seg;
@@ -599,8 +614,8 @@ hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, co
     uint16_t *oo = static_cast<uint16_t *>(out);
     float *seg_states = static_cast<float *>(workspace);
     const size_t seg_bytes = size_t(BH) * p.n_seg * kSegFloats * sizeof(float);
-    int *seg_mild = reinterpret_cast<int *>(static_cast<unsigned char *>(workspace) + flags_offset);
-    unsigned char *stash = static_cast<unsigned char *>(workspace) + seg_bytes;
+    int *seg_mild = reinterpret_cast<int *>(static_cast<unsigned char *>(workspace) + seg_bytes);
+    unsigned char *stash = reinterpret_cast<unsigned char *>(seg_mild) + (size_t(blocks) * sizeof(int) + 15) / 16 * 16;
     const bool tm = heads_token_major > 0;
     const int heads = tm ? heads_token_major : 1;
     float *seg_out = p.n_seg > 1 ? seg_states : nullptr;
@@ -619,14 +634,14 @@ hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, co
         LaunchTimer timer(kKernelSegmentOut, stream);
         if (tm)
             hipLaunchKernelGGL((bigla_ws_out_kernel<true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, qq, kk, vv,
-                               gf, gb, oo, seg_out, seg_mild, int(blocks), stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads);
+                               gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads);
         else
             hipLaunchKernelGGL((bigla_ws_out_kernel<false>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, qq, kk, vv,
-                               gf, gb, oo, seg_out, seg_mild, int(blocks), stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads);
+                               gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads);
     }
-    *unit_flags = seg_mild;
-    *n_units = int(blocks);
     return hipGetLastError();
 }
+
+}  // namespace
 
 }  // namespace vig

@@ -149,7 +149,7 @@ int bigla_fwd_plan(const void *q, const void *k, const void *v, const void *g_fw
     clear_stale_hip_error();
     if (chunkwise)
         return hip_status(
-            vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, heads_token_major, nullptr, ws, workspace, s));
+            vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, heads_token_major, nullptr, plan, workspace, s));
     return hip_status(vig::bigla_recurrent_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, dv, bf16,
                                                   heads_token_major, workspace, s));
 }
@@ -300,7 +300,7 @@ int bigla_locality_fwd(const void *q, const void *k, const void *v, const void *
     const vig::LocalityFusion fusion = {x, w, bias, gate_logits, H, Hg, Wg};
     clear_stale_hip_error();
     return hip_status(vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, long(B) * H, L, dk,
-                                              layout == VIG_LAYOUT_BLHD ? H : 0, &fusion, false, workspace,
+                                              layout == VIG_LAYOUT_BLHD ? H : 0, &fusion, VIG_FWD_FOUR_WAVE, workspace,
                                               static_cast<hipStream_t>(stream)));
 }
 

@@ -26,21 +26,14 @@ struct LocalityFusion {
     int H, Hg, Wg;
 };
 // fusion == nullptr: out receives the token mixer's output; otherwise the block output.
-// wave_specialised: run the eight-wave producer/consumer kernels (bigla_chunk_ws_selectable says where
-// they apply; not with a fusion) instead of the four-wave ones.
+// kernels: 0 = the faster set of kernels for the shape, 1 = the four-wave kernels, 2 = the eight-wave
+// producer/consumer kernels (bigla_chunk_ws_selectable says where they apply; never with a fusion).
 bool bigla_chunk_ws_selectable(long BH, int L, int dk);
+// measurement aid: every slab of the chunkwise forward kernels reads slab 0's q, k, v and gates (synchronous)
+hipError_t bigla_chunk_set_alias(int on);
 hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
                               void *out, long BH, int L, int dk, int heads_token_major, const LocalityFusion *fusion,
-                              bool wave_specialised, void *workspace, hipStream_t stream);
-
-// wave-specialised kernels of the chunkwise path (dk = dv = 64; fast form only: they leave one flag
-// per unit, 0 where the gates are outside its range, and the caller then redoes the call)
-bool bigla_chunk_ws_applicable(long BH, int L, int dk);
-size_t bigla_chunk_ws_core_bytes(long BH, int L);
-size_t bigla_chunk_ws_flag_bytes(long BH, int L);
-hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
-                                 void *out, long BH, int L, int heads_token_major, void *workspace, size_t flags_offset,
-                                 const int **unit_flags, int *n_units, hipStream_t stream);
+                              int kernels, void *workspace, hipStream_t stream);
 
 // ---- gradient of the token mixer -----------------------------------------------------------------
 // Exact fp32 recurrences for any supported head shape and both dtypes; for bf16 with dv = 64 and dk = 64 or 32 the

@@ -2,6 +2,7 @@
 #include <vector>
 
 #include "../../include/vig_bigla.h"
+#include "vig_kernels.hpp"
 #include "vig_timing.hpp"
 
 namespace vig {
@@ -67,6 +68,11 @@ int vig_timing_enable(int on)
         }
     }
     return VIG_OK;
+}
+
+int vig_measure_alias_slabs(int on)
+{
+    return vig::bigla_chunk_set_alias(on != 0 ? 1 : 0) == hipSuccess ? VIG_OK : VIG_ERR_HIP;
 }
 
 int vig_timing_collect(int kernel, double *total_ms, long *launches)
