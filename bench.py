@@ -14,7 +14,7 @@ Prints ONE JSON line.  `roofline` is that of the dominant entry
 point, bigla_fwd: its algorithmic bytes over the summed duration of ALL its launches, which are
 timed with HIP events recorded on their own stream inside the library (a second pass of the same
 K steps, so that event recording does not perturb `value`; the cost of an event pair itself is
-measured on an empty pair and taken off every duration).  `roofline.traffic` is read from the
+estimated from the excess of their sum over the step's wall time and taken off).  `roofline.traffic` is read from the
 table in profiles/hbm_traffic.md that the rocprofv3 counter runs wrote.  `cpu_baseline` times the
 CPU oracle on the same workload on the host cores.
 """
@@ -151,13 +151,12 @@ def main():
     vb.timing_enable(False)
     if args.alias_slabs:
         vb.measure_alias_slabs(False)
-    # what an event pair costs by itself: empty pairs on the same stream
-    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
-    for a, b in pairs:
-        a.record()
-        b.record()
-    torch.cuda.synchronize()
-    pair_us = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)[len(pairs) // 2]
+    # An event pair brackets its kernel plus the cost of the two records.  The launches of a step run back to
+    # back on one stream, so their true durations add up to the step's wall time at most: what the raw event
+    # times sum to beyond that is the records' cost, shared equally by the launches and taken off.
+    raw_sum = sum(k["avg_us"] * k["launches_per_step"] for k in kern.values())
+    n_launches = sum(k["launches_per_step"] for k in kern.values())
+    pair_us = max(raw_sum - ms_per_step * 1e3, 0.0) / n_launches
     for k in kern.values():
         k["avg_us"] = max(k["avg_us"] - pair_us, 0.0)
 

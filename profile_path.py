@@ -109,12 +109,17 @@ def summarize_kernels(directory: str) -> None:
               f"{float(r['MaxNs']) / 1e3:.2f} | {float(r['Percentage']):.1f} |")
 
 
-def _counter_means(directory: str):
-    """kernel -> counter -> mean over dispatches (each dispatch's value summed over its rows)"""
+def _counter_dispatches(directory: str):
+    """kernel -> counter -> dispatch -> value (summed over the dispatch's rows)"""
     per = collections.defaultdict(lambda: collections.defaultdict(lambda: collections.defaultdict(float)))
     for r in csv.DictReader(open(_find(directory, "counter_collection.csv"))):
         per[r["Kernel_Name"]][r["Counter_Name"]][r["Dispatch_Id"]] += float(r["Counter_Value"])
-    return {k: {c: sum(d.values()) / len(d) for c, d in cs.items()} for k, cs in per.items()}
+    return per
+
+
+def _counter_means(directory: str):
+    """kernel -> counter -> mean over dispatches"""
+    return {k: {c: sum(d.values()) / len(d) for c, d in cs.items()} for k, cs in _counter_dispatches(directory).items()}
 
 
 def summarize_counters(directory: str) -> None:
@@ -129,13 +134,15 @@ def summarize_counters(directory: str) -> None:
 def summarize_traffic(workload: str, fetch_dir: str, write_dir: str) -> None:
     fetch, write = _counter_means(fetch_dir), _counter_means(write_dir)
 
-    def calibration(means, counter):
-        for k, cs in means.items():
-            if "elementwise" in k and counter in cs and cs[counter] > 0:
-                return COPY_BYTES / cs[counter]
+    def calibration(directory, counter):
+        # the 256 MiB device-to-device copy is the runtime's copy kernel; its largest dispatch is the one meant
+        # (the host-to-device uploads of the inputs go through the same kernel with tiny counts)
+        for k, cs in _counter_dispatches(directory).items():
+            if "copyBuffer" in k and counter in cs and max(cs[counter].values()) > 1000:
+                return COPY_BYTES / max(cs[counter].values())
         raise SystemExit(f"no calibration copy with {counter}")
 
-    f_fac, w_fac = calibration(fetch, "FETCH_SIZE"), calibration(write, "WRITE_SIZE")
+    f_fac, w_fac = calibration(fetch_dir, "FETCH_SIZE"), calibration(write_dir, "WRITE_SIZE")
     print(f"<!-- calibration: FETCH_SIZE * {f_fac:.1f} bytes, WRITE_SIZE * {w_fac:.1f} bytes (a plain 256 MiB copy in the same runs) -->")
     print("| workload | kernel | read MB | written MB | bytes |")
     print("|---|---|---|---|---|")
