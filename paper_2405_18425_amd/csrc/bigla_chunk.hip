@@ -17,14 +17,17 @@
 //   update, S_out = diag(exp(b_end)) (S_in + sum_i (k_i exp(-b_i))^T v_i), and one query tile
 //   serves the scores AND the readout.  exp(-b_i) grows with the decay accumulated over the
 //   chunk, so this form is used only when the chunk's total log-decay provably stays within
-//   60 nats in every channel (the sum over its four 16-token sub-blocks of the largest
-//   per-channel sub-block total is checked).  Gates of the paper's form, sigmoid(z)^(1/16),
-//   stay far inside: 64 steps reach 60 nats only for z < -15 throughout.
+//   32 nats in every channel (the sum over its four 16-token sub-blocks of the largest
+//   per-channel sub-block total is checked): far inside fp32's range, and slow enough a decay
+//   that an output sums over enough tokens for the rounding of the scaled operands to stay
+//   within the stated tolerance.  Gates of the paper's form, sigmoid(z)^(1/16), stay inside:
+//   64 steps reach 32 nats only for z < -8 throughout.
 //   RANGE-SAFE.  Otherwise cumulative gates stay local to a sub-block: off-diagonal 16x16 tiles
 //   scale keys by the decay to the END of the key's own sub-block and queries by the decay from
 //   the START of the query's sub-block times the whole-sub-block factors in between, so every
 //   factor is <= 1 and underflow to 0 is the correct limit.  The diagonal tile refers both
-//   sides to the MIDDLE of the sub-block, so its factors span at most 8 steps in either sense;
+//   sides to the MIDDLE of the sub-block, so its factors span at most 8 steps in either sense
+//   (its operands are split into bf16 pairs hi + lo and multiplied as hi.hi + hi.lo + lo.hi);
 //   the per-step log-gate is floored at -8 there (alpha >= 3.4e-4; anything smaller is a hard
 //   reset whose leak is far below the bf16 tolerance), which keeps them within e^(+-64).
 // Masking is by select, never by multiplying with 0.
@@ -404,7 +407,9 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
 
     // per direction: diagonal-tile operands (referred to the middle of the sub-block), the keys
     // for off-diagonal tiles (decay to the far edge of their sub-block) and the running query
-    bf16x8 kd[2][2], qd[2][2];
+    // (each as hi + lo: a token's products with itself and its nearest neighbours carry the output where the
+    // decay is fast, which is where this form runs, so their operands keep 16 bits)
+    bf16x8 kd[2][2], qd[2][2], kdl[2][2], qdl[2][2];
     float cum[2][16], khat_f[16];
     {
         float X[16], Y[16], F[16], Emid[16], EB[16];
@@ -415,10 +420,12 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
         store_row16(sm.kf, row, g, khat_f);
 #pragma unroll
         for (int e = 0; e < 16; ++e) tmp[e] = kf[e] * Y[e];
-        kd[0][0] = pack8(tmp); kd[0][1] = pack8(tmp + 8);
+        pack8_split(tmp, kd[0][0], kdl[0][0]);
+        pack8_split(tmp + 8, kd[0][1], kdl[0][1]);
 #pragma unroll
         for (int e = 0; e < 16; ++e) tmp[e] = qf[e] * X[e];
-        qd[0][0] = pack8(tmp); qd[0][1] = pack8(tmp + 8);
+        pack8_split(tmp, qd[0][0], qdl[0][0]);
+        pack8_split(tmp + 8, qd[0][1], qdl[0][1]);
 #pragma unroll
         for (int e = 0; e < 16; ++e) cum[0][e] = tmp[e] * Emid[e];  // q * exp(decay since the sub-block's near edge)
     }
@@ -431,10 +438,12 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
         store_row16(sm.kb, row, g, tmp);
 #pragma unroll
         for (int e = 0; e < 16; ++e) tmp[e] = kf[e] * Y[e];
-        kd[1][0] = pack8(tmp); kd[1][1] = pack8(tmp + 8);
+        pack8_split(tmp, kd[1][0], kdl[1][0]);
+        pack8_split(tmp + 8, kd[1][1], kdl[1][1]);
 #pragma unroll
         for (int e = 0; e < 16; ++e) tmp[e] = qf[e] * X[e];
-        qd[1][0] = pack8(tmp); qd[1][1] = pack8(tmp + 8);
+        pack8_split(tmp, qd[1][0], qdl[1][0]);
+        pack8_split(tmp + 8, qd[1][1], qdl[1][1]);
 #pragma unroll
         for (int e = 0; e < 16; ++e) cum[1][e] = tmp[e] * Emid[e];
     }
@@ -482,8 +491,17 @@ __device__ __forceinline__ void out_chunk_safe(OutLds &sm, const int w, const in
     for (int I = 0; I < 4; ++I) {
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
         if (I == w) {
-            f32x4 pf = mfma(kd[0][1], qd[0][1], mfma(kd[0][0], qd[0][0], zero));
-            f32x4 pb = mfma(kd[1][1], qd[1][1], mfma(kd[1][0], qd[1][0], zero));
+            f32x4 pf = zero, pb = zero;
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {  // small terms first
+                pf = mfma(kdl[0][kk], qd[0][kk], mfma(kd[0][kk], qdl[0][kk], pf));
+                pb = mfma(kdl[1][kk], qd[1][kk], mfma(kd[1][kk], qdl[1][kk], pb));
+            }
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                pf = mfma(kd[0][kk], qd[0][kk], pf);
+                pb = mfma(kd[1][kk], qd[1][kk], pb);
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int i = 4 * g + e;

@@ -17,7 +17,11 @@ constexpr int kTargetWorkgroups = 512;  // segments are sized so that about this
 constexpr int kThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kGateFloorLog2 = -8.0f * kLog2e;  // per-step floor of the log-gate (range-safe form), log2 domain
-constexpr float kFastRange = 60.0f;  // largest chunk log-decay (nats, any channel) the fast form accepts
+// Largest chunk log-decay (nats, any channel) the fast form accepts.  exp(+-32) is far inside fp32; the limit is
+// set by accuracy, not range: the faster the decay, the fewer tokens an output sums over, and the rounding of the
+// exp-scaled operands of a token's nearest few products (which the range-safe form splits into two bf16 terms)
+// then stands against a smaller output.  Up to half a nat per step, elements stay within the stated bound.
+constexpr float kFastRange = 32.0f;
 
 // ---- small device helpers ------------------------------------------------------------------
 
@@ -43,6 +47,20 @@ __device__ __forceinline__ bf16x8 pack8(const float *f)
     u.z = pack2(f[4], f[5]);
     u.w = pack2(f[6], f[7]);
     return __builtin_bit_cast(bf16x8, u);
+}
+
+// f = hi + lo with both parts bf16: the pair carries 16 significant bits of every value
+__device__ __forceinline__ void pack8_split(const float *f, bf16x8 &hi, bf16x8 &lo)
+{
+    uint4 h, l;
+    uint32_t *hp = &h.x, *lp = &l.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        hp[i] = pack2(f[2 * i], f[2 * i + 1]);
+        lp[i] = pack2(f[2 * i] - bf16_lo_to_f32(hp[i]), f[2 * i + 1] - bf16_hi_to_f32(hp[i]));
+    }
+    hi = __builtin_bit_cast(bf16x8, h);
+    lo = __builtin_bit_cast(bf16x8, l);
 }
 
 __device__ __forceinline__ void unpack8(const uint4 &u, float *f)
