@@ -69,7 +69,7 @@ def parse_args():
                          "measurement in detail.backward; not part of the step or of value)")
     ap.add_argument("--layout", choices=("bhld", "blhd"), default="bhld",
                     help="activation layout: head-major (default) or token-major [B,L,H,d] (side measurement)")
-    ap.add_argument("--fwd-plan", choices=("auto", "four_wave", "wave_specialised"), default="auto",
+    ap.add_argument("--fwd-plan", choices=("auto", "four_wave", "wave_specialised", "slab_sweep"), default="auto",
                     help="kernels of the chunkwise forward (side measurement; auto is what bigla_fwd runs)")
     ap.add_argument("--alias-slabs", action="store_true",
                     help="side measurement of the contraction phase: every slab reads the first slab's q, k, v and "

@@ -115,9 +115,20 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
  *                             (VIG_ERR_UNSUPPORTED otherwise).  A (slab, segment) unit whose gates are
  *                             outside the fast form's range is evaluated by the general four-wave code
  *                             inside the same launches.
+ *   VIG_FWD_SLAB_SWEEP        the four-wave code with one workgroup per (batch, head) slab that sweeps the
+ *                             whole sequence twice in one launch (right to left for the backward states,
+ *                             left to right for the outputs): no segments, so k, v and the gates are read
+ *                             from memory once when the second sweep finds them in cache, at the price of
+ *                             B * H workgroups only.  What VIG_FWD_AUTO runs for short sequences in many
+ *                             slabs; selectable here for any shape of the chunkwise path.
  * Workspace as for bigla_fwd_layout.  Unknown plan: VIG_ERR_UNSUPPORTED.
  */
-typedef enum { VIG_FWD_AUTO = 0, VIG_FWD_FOUR_WAVE = 1, VIG_FWD_WAVE_SPECIALISED = 2 } vig_fwd_plan;
+typedef enum {
+    VIG_FWD_AUTO = 0,
+    VIG_FWD_FOUR_WAVE = 1,
+    VIG_FWD_WAVE_SPECIALISED = 2,
+    VIG_FWD_SLAB_SWEEP = 3
+} vig_fwd_plan;
 int bigla_fwd_plan(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
                    void *out, int B, int H, int L, int dk, int dv, int dtype, int layout, int plan,
                    void *workspace, size_t workspace_bytes, void *stream);

@@ -24,7 +24,7 @@ VIG_F32, VIG_BF16 = 0, 1
 VIG_LAYOUT_BHLD, VIG_LAYOUT_BLHD = 0, 1
 LAYOUTS = {"bhld": VIG_LAYOUT_BHLD, "blhd": VIG_LAYOUT_BLHD}
 PLANS = {"auto": 0, "two_launches": 1, "fused_epilogue": 2}
-FWD_PLANS = {"auto": 0, "four_wave": 1, "wave_specialised": 2}
+FWD_PLANS = {"auto": 0, "four_wave": 1, "wave_specialised": 2, "slab_sweep": 3}
 
 # every symbol include/vig_bigla.h declares
 EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "bigla_fwd_plan", "bigla_fwd_static_scratch", "locality_gate_fwd",
@@ -147,7 +147,7 @@ def bigla_fwd(q, k, v, g_fwd, g_bwd, out=None, workspace=None, layout="bhld", st
     bigla_workspace_bytes(...) bytes; one is allocated with torch when absent.
     static_scratch=True calls bigla_fwd_static_scratch instead: the library's own per-GPU scratch
     array serves as workspace and, given `out`, nothing is allocated.  `plan` other than "auto" goes
-    through bigla_fwd_plan ("four_wave" or "wave_specialised" kernels of the chunkwise path).
+    through bigla_fwd_plan ("four_wave", "wave_specialised" or "slab_sweep" kernels of the chunkwise path).
     """
     lay = _layout_code(layout)
     q = _dev(q, "q")

@@ -1144,10 +1144,14 @@ size_t bigla_chunk_workspace_bytes(long BH, int L)
 namespace {
 template <int kDk, bool kTm, bool kLoc>
 hipError_t chunk_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd, void *out,
-                        long BH, int L, int heads_token_major, const LocalityFusion &lf, void *workspace,
-                        hipStream_t stream)
+                        long BH, int L, int heads_token_major, const LocalityFusion &lf, bool slab_sweep,
+                        void *workspace, hipStream_t stream)
 {
-    const Plan p = make_plan(BH, L);
+    Plan p = make_plan(BH, L);
+    if (slab_sweep) {  // one segment per slab whatever the shape (needs no more workspace than the plan's own)
+        p.seg_chunks = p.n_chunks;
+        p.n_seg = 1;
+    }
     const long blocks = BH * p.n_seg;
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
     const uint16_t *qq = static_cast<const uint16_t *>(q), *kk = static_cast<const uint16_t *>(k);
@@ -1205,7 +1209,7 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
     const LocalityFusion none = {};
     // (key width, layout, fused epilogue) pick the instantiation
     // kernels: 0 = the faster set for the shape (the eight-wave kernels where they apply), 1 = four-wave,
-    // 2 = eight-wave (an error where they do not apply)
+    // 2 = eight-wave (an error where they do not apply), 3 = four-wave with one workgroup per slab
     const bool ws_ok = !fusion && bigla_chunk_ws_applicable(BH, L, dk);
     if (kernels == 2 && !ws_ok) return hipErrorInvalidValue;
     if (kernels == 2 || (kernels == 0 && ws_ok)) {
@@ -1213,7 +1217,7 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
     }
     auto go = [&](auto dk_c, auto tm_c, auto loc_c) {
         return chunk_launch<decltype(dk_c)::value, decltype(tm_c)::value, decltype(loc_c)::value>(
-            q, k, v, g_fwd, g_bwd, out, BH, L, heads, fusion ? *fusion : none, workspace, stream);
+            q, k, v, g_fwd, g_bwd, out, BH, L, heads, fusion ? *fusion : none, kernels == 3, workspace, stream);
     };
     using std::integral_constant;
     using std::true_type;

@@ -10,21 +10,22 @@
 // after the other: their busy times added up to the step time.  Here a workgroup has eight waves,
 // one producer and one consumer per SIMD:
 //   producers (waves 0-3, wave w owns tokens 16w..16w+15 of the chunk): cumulative gates, the
-//     exponentials and scalings, the scaled key tiles, the score tiles of the wave's tokens;
+//     exponentials and scalings, the scaled key tiles, the score tiles of the wave's tokens, their
+//     mask, and P.V (whose operands the producer holds in registers already);
 //   consumers (waves 4-7, wave 4+w owns the same tokens for the output and rows 16w..16w+15 of
-//     the carried state): mask and split of the score tile, P.V, the readouts, the output rows,
-//     the state update, the state tiles for the next chunk, the stash.
-// The consumers work one chunk behind the producers; what a producer made for its 16 tokens goes
-// to the consumer of the same tokens through lane-private LDS slots (lane i of wave w writes, lane i
-// of wave 4+w reads: contiguous 16-byte pieces, no layout change), so the vector work of chunk n+1
-// and the matrix work of chunk n share a SIMD at the same time.  Synchronisation is by workgroup
-// barriers only (two per step in the output pass, one in the state pass), executed by every wave
-// the same number of times.
+//     the carried state): the two state readouts, the output rows, the state update, the state
+//     tiles for the next chunk, the stash.
+// The consumers work one chunk behind the producers; what a producer made for its 16 tokens (the
+// fp32 accumulators of P.V and the scaled queries for the readouts) goes to the consumer of the
+// same tokens through lane-private LDS slots (lane i of wave w writes, lane i of wave 4+w reads:
+// contiguous 16-byte pieces, no layout change), so the vector work of chunk n+1 and the LDS-fed
+// matrix work of chunk n share a SIMD at the same time.  Synchronisation is by workgroup barriers
+// only (two per step in the output pass, one in the state pass), executed by every wave the same
+// number of times.
 //
-// The consumers have vector-ALU time to spare, which buys accuracy: the score tile enters P.V, and the
-// carried forward state and the entering backward state enter the readouts, as bf16 pairs hi + lo
-// (x = hi + lo to 16 bits), so that of the four operand roundings of the chunkwise form only those
-// of the scaled queries and keys (and of the stashed backward state) remain.
+// The score tile enters P.V as bf16 pairs hi + lo (x = hi + lo to 16 bits), so that of the operand
+// roundings of the chunkwise form only those of the scaled queries and keys and of the bf16 state
+// tiles remain.
 //
 // Range.  The eight-wave code evaluates the FAST form only (queries q exp(b), keys k exp(-b), see
 // bigla_chunk.hip).  The state pass checks every chunk's total log-decay against the fast form's

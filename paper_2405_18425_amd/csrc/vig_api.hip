@@ -121,7 +121,9 @@ int bigla_fwd_plan(const void *q, const void *k, const void *v, const void *g_fw
 {
     if (!q || !k || !v || !g_fwd || !g_bwd || !out) return VIG_ERR_NULL;
     if (layout != VIG_LAYOUT_BHLD && layout != VIG_LAYOUT_BLHD) return VIG_ERR_LAYOUT;
-    if (plan != VIG_FWD_AUTO && plan != VIG_FWD_FOUR_WAVE && plan != VIG_FWD_WAVE_SPECIALISED) return VIG_ERR_UNSUPPORTED;
+    if (plan != VIG_FWD_AUTO && plan != VIG_FWD_FOUR_WAVE && plan != VIG_FWD_WAVE_SPECIALISED &&
+        plan != VIG_FWD_SLAB_SWEEP)
+        return VIG_ERR_UNSUPPORTED;
     if (B <= 0 || H <= 0 || L <= 0 || dk <= 0 || dv <= 0) return VIG_ERR_SHAPE;
     if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
     if (!head_dim_ok(dk) || !head_dim_ok(dv)) return VIG_ERR_UNSUPPORTED;

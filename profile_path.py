@@ -12,7 +12,7 @@ bigla_fwd.  mode 1 or 2 runs each pass through bigla_locality_fwd with the two-l
 fused-epilogue plan (2) instead of the two separate entry points; 3 runs bigla_bwd (the gradient of
 the token mixer, with the locality step's input as output gradient) after each forward pass, 4 the
 same through bigla_bwd_plan with the exact token-by-token kernels only.
-Options: --fwd-plan auto|four_wave|wave_specialised (kernels of the chunkwise forward);
+Options: --fwd-plan auto|four_wave|wave_specialised|slab_sweep (kernels of the chunkwise forward);
 --alias-slabs (every slab reads the first slab's inputs: cache-resident contraction phase).
 
 Summary modes (no GPU): they read the CSV files rocprofv3 wrote and print markdown.

@@ -165,6 +165,21 @@ def test_gate_producer_validation_codes():
     assert call(x=PTR + 8) == vb.VIG_ERR_ALIGN
 
 
+def test_bigla_fwd_plan_validation_codes():
+    L = vb.lib()
+
+    def call(plan, dk=64, dtype=vb.VIG_BF16, layout=vb.VIG_LAYOUT_BHLD, q=PTR):
+        return L.bigla_fwd_plan(q, PTR, PTR, PTR, PTR, PTR, 1, 1, 128, dk, 64, dtype, layout, plan, None, 0, None)
+
+    assert call(4) == vb.VIG_ERR_UNSUPPORTED
+    assert call(-1) == vb.VIG_ERR_UNSUPPORTED
+    for plan in vb.FWD_PLANS.values():
+        assert call(plan, q=None) == vb.VIG_ERR_NULL
+        assert call(plan, layout=7) == vb.VIG_ERR_LAYOUT
+        assert call(plan, dtype=5) == vb.VIG_ERR_DTYPE
+        assert call(plan) == vb.VIG_ERR_WORKSPACE  # a valid chunkwise problem without its workspace
+
+
 def test_bigla_locality_validation_codes():
     L = vb.lib()
 

@@ -291,6 +291,27 @@ def test_bigla_regression_spiked_gates():
         _say(f"  {plan}: max|err|/max|ref| = {rel:.3e}")
 
 
+@pytest.mark.parametrize("plan", ("four_wave", "wave_specialised", "slab_sweep"))
+@pytest.mark.parametrize("B,H,L,dk,mu", [(2, 6, 1024, 64, -2.0), (3, 2, 4096, 64, 0.0), (5, 3, 700, 64, 1.0),
+                                         (4, 2, 1500, 32, -1.0)])
+def test_bigla_fwd_plans(plan, B, H, L, dk, mu):
+    """Every selectable set of kernels of the chunkwise forward against the oracle, with a stretch of fast
+    decay in one slab (that unit leaves the fast form; the others stay in it)."""
+    from paper_2405_18425_amd import binding as vb
+    w = wl.Workload("plans", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=64, dtype="bf16", gate_mu=mu)
+    _say(f"bigla_fwd_plan {plan} {w}")
+    s = wl.generate(w, seed=61, tensors=("q", "k", "v", "g_fwd", "g_bwd"))
+    g = wl.widen(s["g_fwd"], "bf16")
+    g[-1, -1, L // 3:L // 3 + 50, ::2] = -2.0
+    s["g_fwd"] = wl.store(g, "bf16")
+    if plan == "wave_specialised" and dk != 64:
+        with pytest.raises(vb.VigError):
+            run_bigla_gpu(s, "bf16", plan=plan)
+        return
+    rel = assert_close(run_bigla_gpu(s, "bf16", plan=plan), run_bigla_oracle(s, "bf16"), TOL["bf16"], plan)
+    _say(f"  max|err|/max|ref| = {rel:.3e}")
+
+
 @pytest.mark.parametrize("L", (1, 2, 3, 5, 31))
 def test_bigla_bwd_regression_tiny_slabs(L):
     """Slabs of a few tokens (inputs scaled by 1/4, gates near 1, both layouts): three-token slabs once
