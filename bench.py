@@ -67,6 +67,9 @@ def parse_args():
     ap.add_argument("--backward", action="store_true",
                     help="also time bigla_bwd, the gradient of the token mixer, on the same buffers (side "
                          "measurement in detail.backward; not part of the step or of value)")
+    ap.add_argument("--gate-width", type=int, default=0,
+                    help="also time the step with the forget-gate producer in front (block input of this width), as "
+                         "two launches and with the state pass making the gates (side measurement in detail.gated)")
     ap.add_argument("--layout", choices=("bhld", "blhd"), default="bhld",
                     help="activation layout: head-major (default) or token-major [B,L,H,d] (side measurement)")
     ap.add_argument("--fwd-plan", choices=("auto", "four_wave", "wave_specialised", "slab_sweep"), default="auto",
@@ -219,6 +222,36 @@ def main():
         bwd_us = (time.perf_counter() - b0) * 1e6 / n_bwd
         extra["backward"] = {"us": round(bwd_us, 2), "tokens_per_s": round(w.tokens / (bwd_us * 1e-6), 1),
                              "calls": n_bwd, "vs_forward_mixer": round(bwd_us / bigla_us, 2)}
+
+    # ---- side measurement: the step with the gate producer in front of it (Section 3 gate), both plans
+    if args.gate_width:
+        gi = wl.generate_gate_inputs(w.B, w.L, args.gate_width, w.H, w.dk, w.dtype, seed=args.seed, bias_mu=w.gate_mu)
+        gt = {n: wl.to_torch(a, w.dtype, dev) for n, a in gi.items()}
+        gw1, gw2 = gt["w1"].t().contiguous(), gt["w2"].t().contiguous()
+        xs = [torch.roll(gt["x"], shifts=i, dims=0).contiguous() for i in range(n_sets)]
+        gws = torch.empty(int(vb.lib().gated_bigla_workspace_bytes(w.B, w.H, w.L, w.dk, w.dv, code)), dtype=torch.uint8,
+                          device=dev)
+        gated = {"D": args.gate_width}
+        for plan in ("separate", "in_state_pass"):
+            def gstep(i):
+                s = sets[i % n_sets]
+                vb.gated_bigla_fwd(xs[i % n_sets], gw1, gw2, s["q"], s["k"], s["v"], bias=gt["bias"], layout=args.layout,
+                                   plan=plan, out=s["o_global"], g_fwd=s["g_fwd"], g_bwd=s["g_bwd"], workspace=gws)
+                vb.locality_gate_fwd(s["v"], s["conv_w"], s["gate_logits"], s["o_global"], w.Hg, w.Wg, out=s["out"],
+                                     layout=args.layout)
+            try:
+                for i in range(args.warmup):
+                    gstep(i)
+            except vb.VigError:
+                gated[plan + "_us"] = None
+                continue
+            torch.cuda.synchronize()
+            g0 = time.perf_counter()
+            for i in range(args.steps):
+                gstep(i)
+            torch.cuda.synchronize()
+            gated[plan + "_us"] = round((time.perf_counter() - g0) * 1e6 / args.steps, 2)
+        extra["gated"] = gated
 
     # ---- CPU oracle on the host cores (reported baseline, not the target)
     cpu = None

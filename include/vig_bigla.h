@@ -273,6 +273,31 @@ int gate_producer_fwd(const void *x, const void *w1, const void *w2, const void 
                       void *stream);
 
 /*
+ * The gate producer and the token mixer as one call -- Section 3 (gate) and all of Eq. (BiGLA),
+ * Section 4.2.1: gate_producer_fwd(x, w1, w2, bias -> g_fwd, g_bwd) followed by
+ * bigla_fwd_layout(q, k, v, g_fwd, g_bwd -> out).  g_fwd and g_bwd are OUTPUTS here as well: the log gates
+ * are returned (the mixer's gradient needs them), in `layout` like q, k, v and out.  Arguments as for those
+ * two functions.
+ *   VIG_GATES_SEPARATE       the two launches one after the other (every shape and dtype they support);
+ *   VIG_GATES_IN_STATE_PASS  x W1 alone in a small launch (32 bytes per token, in the workspace); the state
+ *                            pass of the chunkwise mixer then makes each chunk's gates itself from it, writes
+ *                            them to g_fwd / g_bwd for the output pass and never reads them back: the gates
+ *                            cross memory twice (written, read by the output pass) instead of three times.
+ *                            Same arithmetic as gate_producer_fwd, bit for bit.  VIG_BF16, dk = dv = 64,
+ *                            where bigla_fwd_plan admits VIG_FWD_WAVE_SPECIALISED (VIG_ERR_UNSUPPORTED
+ *                            otherwise, and while vig_measure_alias_slabs is on);
+ *   VIG_GATES_AUTO           VIG_GATES_IN_STATE_PASS where it applies, else VIG_GATES_SEPARATE.
+ * workspace: at least gated_bigla_workspace_bytes(B, H, L, dk, dv, dtype) bytes (0 for invalid or unsupported
+ * arguments; it covers every plan).
+ */
+typedef enum { VIG_GATES_AUTO = 0, VIG_GATES_SEPARATE = 1, VIG_GATES_IN_STATE_PASS = 2 } vig_gates_plan;
+size_t gated_bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype);
+int gated_bigla_fwd(const void *x, const void *w1, const void *w2, const void *bias, const void *q, const void *k,
+                    const void *v, void *g_fwd, void *g_bwd, void *out, int B, int H, int L, int D, int dk, int dv,
+                    float tau, int dtype, int layout, int plan, void *workspace, size_t workspace_bytes,
+                    void *stream);
+
+/*
  * Measurement aid (no part of the method): per-kernel timing with HIP events recorded on the
  * stream each kernel is launched on.  vig_timing_enable(1) clears the records and makes every
  * later launch of this library from the calling thread record a start/stop event pair;
@@ -282,7 +307,7 @@ int gate_producer_fwd(const void *x, const void *w1, const void *w2, const void 
  */
 typedef enum {
     VIG_KERNEL_SEGMENT_STATE = 0, /* chunkwise path, launch 1: segment end states + stash     */
-    /* 1 is not in use */
+    VIG_KERNEL_GATE_LOWRANK = 1,  /* x W1 alone, for the gate producer inside the state pass   */
     VIG_KERNEL_SEGMENT_OUT = 2,   /* chunkwise path, launch 2: output pass                    */
     VIG_KERNEL_RECURRENT = 3,     /* exact fp32 recurrence                                    */
     VIG_KERNEL_LOCALITY_GATE = 4, /* depthwise conv + gate                                    */

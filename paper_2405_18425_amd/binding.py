@@ -25,14 +25,16 @@ VIG_LAYOUT_BHLD, VIG_LAYOUT_BLHD = 0, 1
 LAYOUTS = {"bhld": VIG_LAYOUT_BHLD, "blhd": VIG_LAYOUT_BLHD}
 PLANS = {"auto": 0, "two_launches": 1, "fused_epilogue": 2}
 FWD_PLANS = {"auto": 0, "four_wave": 1, "wave_specialised": 2, "slab_sweep": 3}
+GATES_PLANS = {"auto": 0, "separate": 1, "in_state_pass": 2}
 
 # every symbol include/vig_bigla.h declares
 EXPORTS = ("bigla_workspace_bytes", "bigla_fwd", "bigla_fwd_layout", "bigla_fwd_plan", "bigla_fwd_static_scratch", "locality_gate_fwd",
            "locality_gate_fwd_layout", "bigla_locality_workspace_bytes", "bigla_locality_fwd", "gate_producer_fwd",
+           "gated_bigla_workspace_bytes", "gated_bigla_fwd",
            "bigla_bwd_workspace_bytes", "bigla_bwd", "bigla_bwd_plan",
            "vig_status_str", "vig_last_hip_error", "vig_timing_enable",
            "vig_timing_collect", "vig_measure_alias_slabs")
-KERNELS = {"segment_state": 0, "segment_out": 2, "recurrent": 3, "locality_gate": 4,
+KERNELS = {"segment_state": 0, "gate_lowrank": 1, "segment_out": 2, "recurrent": 3, "locality_gate": 4,
            "segment_out_general": 5, "gate_producer": 6, "slab": 7, "backward": 8}
 
 _lib = None
@@ -79,6 +81,10 @@ def lib() -> ctypes.CDLL:
         L.bigla_bwd_plan.restype = ci
         L.gate_producer_fwd.argtypes = [vp] * 6 + [ci] * 5 + [ctypes.c_float, ci, ci, vp]
         L.gate_producer_fwd.restype = ci
+        L.gated_bigla_workspace_bytes.argtypes = [ci] * 6
+        L.gated_bigla_workspace_bytes.restype = sz
+        L.gated_bigla_fwd.argtypes = [vp] * 10 + [ci] * 6 + [ctypes.c_float, ci, ci, ci, vp, sz, vp]
+        L.gated_bigla_fwd.restype = ci
         L.vig_status_str.argtypes = [ci]
         L.vig_status_str.restype = ctypes.c_char_p
         L.vig_last_hip_error.argtypes = []
@@ -360,6 +366,52 @@ def gate_producer_fwd(x, w1, w2, H: int, dk: int, bias=None, tau: float = 16.0, 
                                      _stream_ptr(x.device))
     _check(st, "gate_producer_fwd")
     return g_fwd, g_bwd
+
+
+def gated_bigla_fwd(x, w1, w2, q, k, v, bias=None, tau: float = 16.0, layout="bhld", plan="auto", out=None,
+                    g_fwd=None, g_bwd=None, workspace=None):
+    """gate_producer_fwd then bigla_fwd as one call (Section 3 gate; Eq. (BiGLA)): returns (out, g_fwd, g_bwd).
+
+    plan "in_state_pass": the chunkwise state pass makes the gates itself from x W1; "separate": two launches.
+    """
+    lay = _layout_code(layout)
+    if plan not in GATES_PLANS:
+        raise VigError(VIG_ERR_UNSUPPORTED, f"plan must be one of {sorted(GATES_PLANS)}")
+    q = _dev(q, "q")
+    if q.dim() != 4:
+        raise VigError(VIG_ERR_SHAPE, "q must be 4-dimensional")
+    if lay == VIG_LAYOUT_BHLD:
+        B, H, L, dk = q.shape
+    else:
+        B, L, H, dk = q.shape
+    dv = v.shape[-1]
+    x = _dev(x, "x", None, q)
+    if x.dim() != 3 or x.shape[0] != B or x.shape[1] != L:
+        raise VigError(VIG_ERR_SHAPE, "x must be [B,L,D]")
+    D = x.shape[2]
+    w1 = _dev(w1, "w1", (16, D), q)
+    w2 = _dev(w2, "w2", (2 * H * dk, 16), q)
+    if bias is not None:
+        bias = _dev(bias, "bias", (2 * H * dk,), q)
+    kshape = tuple(q.shape)
+    vshape = kshape[:-1] + (dv,)
+    k = _dev(k, "k", kshape, q)
+    v = _dev(v, "v", vshape, q)
+    g_fwd = torch.empty(kshape, dtype=q.dtype, device=q.device) if g_fwd is None else _dev(g_fwd, "g_fwd", kshape, q)
+    g_bwd = torch.empty(kshape, dtype=q.dtype, device=q.device) if g_bwd is None else _dev(g_bwd, "g_bwd", kshape, q)
+    out = torch.empty(vshape, dtype=q.dtype, device=q.device) if out is None else _dev(out, "out", vshape, q)
+    code = _dtype_code(q)
+    need = lib().gated_bigla_workspace_bytes(B, H, L, dk, dv, code)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    with torch.cuda.device(q.device):
+        st = lib().gated_bigla_fwd(x.data_ptr(), w1.data_ptr(), w2.data_ptr(),
+                                   bias.data_ptr() if bias is not None else None, q.data_ptr(), k.data_ptr(),
+                                   v.data_ptr(), g_fwd.data_ptr(), g_bwd.data_ptr(), out.data_ptr(), B, H, L, D, dk,
+                                   dv, float(tau), code, lay, GATES_PLANS[plan], workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), _stream_ptr(q.device))
+    _check(st, "gated_bigla_fwd")
+    return out, g_fwd, g_bwd
 
 
 def timing_enable(on: bool) -> None:

@@ -120,15 +120,30 @@ struct SlabIo {
     }
 };
 
+// Where the log forget gates come from when the state pass makes them itself (kGates): the low-rank half
+// x W1 of the gate producer (Section 3; Eq. (BiGLA), lines 1-2), bf16 [B][L][16], and the producer's second
+// weight matrix w2 [2*H*dk][16] and bias [2*H*dk] (may be null).
+struct GateSource {
+    const uint16_t *lowrank, *w2, *bias;
+    float inv_tau;
+    int n_heads;
+};
+
 // ---- state pass ------------------------------------------------------------------------------------
 // One (slab, segment) unit per workgroup, chunks right to left.  Step s: the producers scale the keys
 // of chunk nch-1-s, the consumers fold chunk nch-s into the carried states.  What is written to the
 // workspace is what bigla_segment_state_kernel writes.
-template <bool kTm>
+//
+// kGates: g_fwd and g_bwd are OUTPUTS.  One step ahead of the scans that read them, the waves make the gates
+// of a chunk, log sigmoid((x W1) w2^T + b) / tau with the arithmetic of gate_producer_bf16_kernel bit for bit
+// (the wave of tokens 16w..16w+15 does what that kernel's wave does for 16 tokens, for the 64 channels of its
+// head in one direction), put them into the gate tiles in LDS, and write them to memory for the output pass;
+// no gates are loaded.
+template <bool kTm, bool kGates = false>
 __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
-    const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all, const uint16_t *__restrict__ gf_all,
-    const uint16_t *__restrict__ gb_all, float *__restrict__ seg_states, int *__restrict__ seg_mild,
-    unsigned char *__restrict__ stash, int L, int n_chunks, int seg_chunks, int n_seg, int heads)
+    const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all, const uint16_t *gf_all,
+    const uint16_t *gb_all, float *__restrict__ seg_states, int *__restrict__ seg_mild,
+    unsigned char *__restrict__ stash, int L, int n_chunks, int seg_chunks, int n_seg, int heads, GateSource gs)
 {
     WsStateLds &sm = g_ws_lds.state;
     const int tid = threadIdx.x;
@@ -148,17 +163,86 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
 
     if (tid == 0) sm.not_fast = 0;
 
+    // kGates: lane (r, g) of wave w makes the gates of channels 16g..16g+15 of token 16w + r of a chunk, the
+    // consumer waves those of the forward direction, the producer waves those of the backward direction (the
+    // two roles share a SIMD's vector ALU; split like this neither role's step grows by the whole job).  A
+    // operands (w2 rows of the head, arranged as in gate_producer_bf16_kernel so that the four tiles leave the
+    // lane 16 consecutive channels) and the bias stay in registers.
+    const int gdir = producer ? 1 : 0;
+    s16x4 gate_a[4];
+    f32x4 gate_bias[4];  // element e of tile i: channel 16g + 4i + e (the accumulators' initial value)
+    const uint16_t *lowrank_rows = nullptr;
+    if (kGates) {
+        const int head = int(slab % gs.n_heads);
+        lowrank_rows = gs.lowrank + size_t(slab / gs.n_heads) * L * 16;
+        const int arow = 16 * (r >> 2) + (r & 3);
+        const int base = (gdir * gs.n_heads + head) * kD;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            gate_a[i] = __builtin_bit_cast(s16x4, *reinterpret_cast<const uint2 *>(gs.w2 + size_t(base + arow + 4 * i) * 16 + 4 * g));
+        uint4 braw[2];
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+            braw[hh] = gs.bias ? *reinterpret_cast<const uint4 *>(gs.bias + base + 16 * g + 8 * hh) : make_uint4(0u, 0u, 0u, 0u);
+        const uint32_t b[8] = {braw[0].x, braw[0].y, braw[0].z, braw[0].w, braw[1].x, braw[1].y, braw[1].z, braw[1].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            gate_bias[i] = f32x4{bf16_lo_to_f32(b[2 * i]), bf16_hi_to_f32(b[2 * i]), bf16_lo_to_f32(b[2 * i + 1]),
+                                 bf16_hi_to_f32(b[2 * i + 1])};
+    }
+    // the low-rank row of the lane's token in chunk m of the segment (zeros past the sequence or the segment)
+    auto fetch_lowrank = [&](int m) {
+        const long t = long(chunk0 + m) * kC + row;
+        uint2 h = make_uint2(0u, 0u);
+        if (kGates && m >= 0 && t < L) h = *reinterpret_cast<const uint2 *>(lowrank_rows + t * 16 + 4 * g);
+        return h;
+    };
+    // this role's gates of chunk m from its low-rank rows: into gate tile buffer `buf` and out to memory.  Rows
+    // past the sequence get log-gate 0 in LDS (they must not decay anything) and their stores are dropped by the
+    // bounds check of the slab's buffer resource.
+    auto make_gates = [&](const uint2 lowrank_row, int m, int buf) {
+        const s16x4 hop = __builtin_bit_cast(s16x4, lowrank_row);
+        const bool live = long(chunk0 + m) * kC + row < L;
+        const unsigned off = (unsigned(chunk0 + m) * kC + unsigned(row)) * io.pitch + 32u * unsigned(g);
+        uint32_t packed[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {  // channels 16g + 4i .. + 3
+            const f32x4 z = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(gate_a[i], hop, gate_bias[i], 0, 0, 0);
+            const float o0 = log_sigmoid(z[0]) * gs.inv_tau, o1 = log_sigmoid(z[1]) * gs.inv_tau;
+            const float o2 = log_sigmoid(z[2]) * gs.inv_tau, o3 = log_sigmoid(z[3]) * gs.inv_tau;
+            packed[2 * i] = live ? pack2(o0, o1) : 0u;
+            packed[2 * i + 1] = live ? pack2(o2, o3) : 0u;
+        }
+        // column order of stage_gates: channels 16g + 8p + 4h + e at column 32 (g / 2) + 16 h + 4 (2 (g % 2) + p) + e
+        uint16_t(*tile)[kPitch] = sm.g[buf][gdir];
+        const int c0 = 32 * (g >> 1) + 8 * (g & 1);
+        *reinterpret_cast<uint2 *>(&tile[row][c0]) = make_uint2(packed[0], packed[1]);
+        *reinterpret_cast<uint2 *>(&tile[row][c0 + 16]) = make_uint2(packed[2], packed[3]);
+        *reinterpret_cast<uint2 *>(&tile[row][c0 + 4]) = make_uint2(packed[4], packed[5]);
+        *reinterpret_cast<uint2 *>(&tile[row][c0 + 20]) = make_uint2(packed[6], packed[7]);
+        const __amdgpu_buffer_rsrc_t dst = gdir == 0 ? io.gf : io.gb;
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{packed[0], packed[1], packed[2], packed[3]}, dst, off, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{packed[4], packed[5], packed[6], packed[7]}, dst, off + 16u, 0, 0);
+    };
+    uint2 rlow = make_uint2(0u, 0u);
+    if (kGates) {
+        make_gates(fetch_lowrank(nch - 1), nch - 1, 0);
+        rlow = fetch_lowrank(nch - 2);
+    }
+
     if (producer) {
         bf16x8 tri_f[2], tri_b[2];
         scan_triangle<0>(w, r, g, tri_f);
         scan_triangle<1>(w, r, g, tri_b);
         StagedRows rk = load_rows(io.k, lr, token0(nch - 1));
-        {
+        StagedRows rgf, rgb;
+        if (!kGates) {
             const StagedRows gf = load_rows(io.gf, lr, token0(nch - 1)), gb = load_rows(io.gb, lr, token0(nch - 1));
             stage_gates(sm.g[0][0], w, lane, gf);
             stage_gates(sm.g[0][1], w, lane, gb);
+            rgf = load_rows(io.gf, lr, token0(nch - 2));
+            rgb = load_rows(io.gb, lr, token0(nch - 2));
         }
-        StagedRows rgf = load_rows(io.gf, lr, token0(nch - 2)), rgb = load_rows(io.gb, lr, token0(nch - 2));
         __syncthreads();
         for (int s = 0; s <= nch; ++s) {
             if (s < nch) {
@@ -203,11 +287,15 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
                     for (int n = 0; n < 16; ++n) mn = fminf(mn, totb[n]);
                     if (!(mn >= -kFastRange)) sm.not_fast = 1;
                 }
-                // the gates of chunk m-1 go to the other buffer (last read one step ago)
-                stage_gates(sm.g[b ^ 1][0], w, lane, rgf);
-                stage_gates(sm.g[b ^ 1][1], w, lane, rgb);
-                rgf = load_rows(io.gf, lr, token0(m - 2));
-                rgb = load_rows(io.gb, lr, token0(m - 2));
+                if (!kGates) {  // the gates of chunk m-1 go to the other buffer (last read one step ago)
+                    stage_gates(sm.g[b ^ 1][0], w, lane, rgf);
+                    stage_gates(sm.g[b ^ 1][1], w, lane, rgb);
+                    rgf = load_rows(io.gf, lr, token0(m - 2));
+                    rgb = load_rows(io.gb, lr, token0(m - 2));
+                } else if (m >= 1) {  // the backward gates of chunk m-1
+                    make_gates(rlow, m - 1, b ^ 1);
+                    rlow = fetch_lowrank(m - 2);
+                }
             }
             __syncthreads();
         }
@@ -220,8 +308,13 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
         float4 rf = make_float4(1.f, 1.f, 1.f, 1.f), rb = rf;
         unsigned char *stash_slab = stash + size_t(slab) * n_chunks * kStashBytes;
         StagedRows rv = load_rows(io.v, lr, token0(nch - 1));
+
         __syncthreads();
         for (int s = 0; s <= nch; ++s) {
+            if (kGates && s + 1 < nch) {  // the forward gates of the chunk the producers take in the next step
+                make_gates(rlow, nch - 2 - s, (s + 1) & 1);
+                rlow = fetch_lowrank(nch - 3 - s);
+            }
             if (s >= 1) {
                 const int m = nch - s, b = (s - 1) & 1;
                 {  // stash for chunk m: the backward state entering it from the right and the decay to the segment's edge
@@ -293,6 +386,7 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
             return;
         }
         __syncthreads();  // waits for the four waves that stay (and for the others to have left)
+        if (kGates) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // the gates the other waves wrote are read below
         state_unit<kD, kTm, true, true>(k_all, v_all, gf_all, gb_all, seg_states, stash, L, n_chunks, seg_chunks, n_seg,
                                         blockIdx.x, heads);
     }
@@ -603,8 +697,10 @@ size_t bigla_chunk_ws_workspace_bytes(long BH, int L)
            size_t(BH) * p.n_chunks * kStashBytes;
 }
 
+// gates: null when g_fwd and g_bwd are inputs; otherwise the state pass makes them (and writes them there)
 hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
-                                 void *out, long BH, int L, int heads_token_major, void *workspace, hipStream_t stream)
+                                 void *out, long BH, int L, int heads_token_major, void *workspace, hipStream_t stream,
+                                 const GateSource *gates = nullptr)
 {
     const Plan p = make_ws_plan(BH, L);
     const long blocks = BH * p.n_seg;
@@ -622,12 +718,19 @@ hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, co
     float *seg_out = p.n_seg > 1 ? seg_states : nullptr;
     {
         LaunchTimer timer(kKernelSegmentState, stream);
-        if (tm)
+        const GateSource none = {};
+        if (gates && tm)
+            hipLaunchKernelGGL((bigla_ws_state_kernel<true, true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, kk,
+                               vv, gf, gb, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, *gates);
+        else if (gates)
+            hipLaunchKernelGGL((bigla_ws_state_kernel<false, true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, kk,
+                               vv, gf, gb, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, *gates);
+        else if (tm)
             hipLaunchKernelGGL((bigla_ws_state_kernel<true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, kk, vv, gf,
-                               gb, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads);
+                               gb, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, none);
         else
             hipLaunchKernelGGL((bigla_ws_state_kernel<false>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, kk, vv, gf,
-                               gb, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads);
+                               gb, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, none);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -35,17 +35,6 @@ constexpr int kTokensPerWave = 16;
 constexpr int kPersistentBlocks = 768;  // three workgroups per CU walk the token tiles
 
 
-// log(sigmoid(z)) = min(z, 0) - log(1 + exp(-|z|)), finite for every finite z.  The bare hardware
-// exp2 / log2 serve: the exponential's argument is <= 0 (an underflow to 0 is the right limit) and
-// the logarithm's lies in [1, 2], so neither needs the range handling of the library functions,
-// which costs more vector instructions than the two transcendentals themselves.
-__device__ __forceinline__ float log_sigmoid(float z)
-{
-    const float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
-    const float e = __builtin_amdgcn_exp2f(-kLog2e * fabsf(z));
-    return fmaf(-kLn2, __builtin_amdgcn_logf(1.f + e), fminf(z, 0.f));
-}
-
 // Copy w2 ([width][16] bf16, 2 x 16 bytes per row) and the bias into LDS, eight loads in flight per
 // thread and batch (a load-store-load-store loop would pay one memory round trip per 16 bytes).
 __device__ __forceinline__ void stage_weights(const uint16_t *w2, const uint16_t *bias, uint16_t *s_w2,
@@ -140,34 +129,32 @@ __global__ __launch_bounds__(kThreads) void gate_producer_bf16_kernel(
         const long b_idx = tok_c / L;
         const int t_idx = int(tok_c % L);
         for (int cb = 0; cb < width; cb += 64) {
+            const int c = min(cb + 16 * g, width - 16);  // first of this lane's 16 channels (a ragged last group: unused)
+            // the bias enters as the accumulator's initial value: element e of tile i is channel c + 4i + e
             f32x4 z[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int ch = min(cb + arow + 4 * i, width - 1);  // a ragged last group repeats a row, unused
-                const uint2 a2 = *reinterpret_cast<const uint2 *>(w2src + size_t(ch) * kRank + 4 * g);
-                const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-                z[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a2), hop, zero, 0, 0, 0);
-            }
-            const int c = cb + 16 * g;  // first of this lane's 16 channels
-            if (c >= width) continue;
-            float bv[16];
             if (bsrc) {
                 const uint4 b0 = *reinterpret_cast<const uint4 *>(bsrc + c), b1 = *reinterpret_cast<const uint4 *>(bsrc + c + 8);
                 const uint32_t raw[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
 #pragma unroll
-                for (int n = 0; n < 8; ++n) {
-                    bv[2 * n] = bf16_lo_to_f32(raw[n]);
-                    bv[2 * n + 1] = bf16_hi_to_f32(raw[n]);
-                }
+                for (int i = 0; i < 4; ++i)
+                    z[i] = f32x4{bf16_lo_to_f32(raw[2 * i]), bf16_hi_to_f32(raw[2 * i]), bf16_lo_to_f32(raw[2 * i + 1]),
+                                 bf16_hi_to_f32(raw[2 * i + 1])};
             } else {
 #pragma unroll
-                for (int n = 0; n < 16; ++n) bv[n] = 0.f;
+                for (int i = 0; i < 4; ++i) z[i] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int ch = min(cb + arow + 4 * i, width - 1);  // a ragged last group repeats a row, unused
+                const uint2 a2 = *reinterpret_cast<const uint2 *>(w2src + size_t(ch) * kRank + 4 * g);
+                z[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a2), hop, z[i], 0, 0, 0);
+            }
+            if (cb + 16 * g >= width) continue;
             uint32_t packed[8];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {  // channel c + 4i + e
-                const float o0 = log_sigmoid(z[i][0] + bv[4 * i + 0]) * inv_tau, o1 = log_sigmoid(z[i][1] + bv[4 * i + 1]) * inv_tau;
-                const float o2 = log_sigmoid(z[i][2] + bv[4 * i + 2]) * inv_tau, o3 = log_sigmoid(z[i][3] + bv[4 * i + 3]) * inv_tau;
+                const float o0 = log_sigmoid(z[i][0]) * inv_tau, o1 = log_sigmoid(z[i][1]) * inv_tau;
+                const float o2 = log_sigmoid(z[i][2]) * inv_tau, o3 = log_sigmoid(z[i][3]) * inv_tau;
                 packed[2 * i] = pack2(o0, o1);
                 packed[2 * i + 1] = pack2(o2, o3);
             }
@@ -185,6 +172,36 @@ __global__ __launch_bounds__(kThreads) void gate_producer_bf16_kernel(
             }
         }
     }
+}
+
+// The low-rank half alone, for the token mixer's state pass when it makes the gates itself: GEMM 1 exactly as
+// above (same operands, same order of accumulation), the bf16 B operand of GEMM 2 written out instead of used:
+// lowrank[token][16], 32 bytes per token.  One wave per 16 tokens.
+template <int kSteps>
+__global__ __launch_bounds__(kThreads) void gate_lowrank_bf16_kernel(const uint16_t *__restrict__ x,
+                                                                     const uint16_t *__restrict__ w1,
+                                                                     uint16_t *__restrict__ lowrank, long tokens, int D)
+{
+    const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    const long tile = long(blockIdx.x) * (kThreads / 64) + (threadIdx.x >> 6);
+    const long tok = tile * kTokensPerWave + r;
+    if (tile * kTokensPerWave >= tokens) return;
+    const uint4 *wrow = reinterpret_cast<const uint4 *>(w1 + size_t(r) * D) + g;
+    const uint4 *xrow = reinterpret_cast<const uint4 *>(x + size_t(tok < tokens ? tok : tokens - 1) * D) + g;
+    uint4 wa[kSteps], xa[kSteps];
+#pragma unroll
+    for (int kk = 0; kk < kSteps; ++kk) {
+        xa[kk] = xrow[4 * kk];
+        wa[kk] = wrow[4 * kk];
+    }
+    f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int kk = 0; kk < kSteps; ++kk)
+        acc[kk & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wa[kk]),
+                                                              __builtin_bit_cast(bf16x8, xa[kk]), acc[kk & 1], 0, 0, 0);
+    const uint2 hb = make_uint2(pack2(acc[0][0] + acc[1][0], acc[0][1] + acc[1][1]),
+                                pack2(acc[0][2] + acc[1][2], acc[0][3] + acc[1][3]));
+    if (tok < tokens) *reinterpret_cast<uint2 *>(lowrank + size_t(tok) * kRank + 4 * g) = hb;
 }
 
 // fp32: one workgroup per 16 tokens; thread (t, rank) forms the low-rank product, then the threads
@@ -287,6 +304,29 @@ hipError_t gate_producer_launch(const void *x, const void *w1, const void *w2, c
                            static_cast<float *>(g_fwd), static_cast<float *>(g_bwd), tokens, H, L, D, dk, inv_tau,
                            token_major);
     }
+    return hipGetLastError();
+}
+
+hipError_t gate_lowrank_launch(const void *x, const void *w1, void *lowrank, int B, int L, int D, hipStream_t stream)
+{
+    const long tokens = long(B) * L;
+    const long tiles = (tokens + kTokensPerWave - 1) / kTokensPerWave;
+    const long blocks = (tiles + kThreads / 64 - 1) / (kThreads / 64);
+    if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+    LaunchTimer timer(kKernelGateLowrank, stream);
+#define VIG_LR_CASE(KS)                                                                                            \
+    case KS:                                                                                                       \
+        hipLaunchKernelGGL((gate_lowrank_bf16_kernel<KS>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,      \
+                           static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w1),                    \
+                           static_cast<uint16_t *>(lowrank), tokens, D);                                           \
+        break
+    switch (D / 32) {
+        VIG_LR_CASE(1); VIG_LR_CASE(2); VIG_LR_CASE(3); VIG_LR_CASE(4); VIG_LR_CASE(5); VIG_LR_CASE(6);
+        VIG_LR_CASE(7); VIG_LR_CASE(8); VIG_LR_CASE(10); VIG_LR_CASE(12); VIG_LR_CASE(16); VIG_LR_CASE(18);
+        VIG_LR_CASE(20); VIG_LR_CASE(24); VIG_LR_CASE(32);
+        default: return hipErrorInvalidValue;
+    }
+#undef VIG_LR_CASE
     return hipGetLastError();
 }
 

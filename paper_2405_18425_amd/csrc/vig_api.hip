@@ -324,6 +324,61 @@ int gate_producer_fwd(const void *x, const void *w1, const void *w2, const void 
                                                 static_cast<hipStream_t>(stream)));
 }
 
+namespace {
+size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+}  // namespace
+
+size_t gated_bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype)
+{
+    if (B <= 0 || H <= 0 || L <= 0 || !head_dim_ok(dk) || !head_dim_ok(dv)) return 0;
+    if (dtype != VIG_F32 && dtype != VIG_BF16) return 0;
+    // the mixer's workspace, then the low-rank product (bf16 [B][L][16])
+    return round256(bigla_workspace_bytes(B, H, L, dk, dv, dtype)) + round256(size_t(B) * L * 16 * 2);
+}
+
+int gated_bigla_fwd(const void *x, const void *w1, const void *w2, const void *bias, const void *q, const void *k,
+                    const void *v, void *g_fwd, void *g_bwd, void *out, int B, int H, int L, int D, int dk, int dv,
+                    float tau, int dtype, int layout, int plan, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x || !w1 || !w2 || !q || !k || !v || !g_fwd || !g_bwd || !out) return VIG_ERR_NULL;
+    if (layout != VIG_LAYOUT_BHLD && layout != VIG_LAYOUT_BLHD) return VIG_ERR_LAYOUT;
+    if (plan != VIG_GATES_AUTO && plan != VIG_GATES_SEPARATE && plan != VIG_GATES_IN_STATE_PASS) return VIG_ERR_UNSUPPORTED;
+    if (B <= 0 || H <= 0 || L <= 0 || D <= 0 || dk <= 0 || dv <= 0 || !(tau > 0.f)) return VIG_ERR_SHAPE;
+    if (dtype != VIG_F32 && dtype != VIG_BF16) return VIG_ERR_DTYPE;
+    if (!head_dim_ok(dk) || !head_dim_ok(dv) || !vig::gate_producer_width_ok(D, dtype == VIG_BF16)) return VIG_ERR_UNSUPPORTED;
+    if (!sizes_ok(B, L, D, 1) || !sizes_ok(B, L, H, 2 * dk) || !sizes_ok(B, H, L, dk > dv ? dk : dv) ||
+        long(H) * dk > (1 << 20))
+        return VIG_ERR_SHAPE;
+    const size_t need = gated_bigla_workspace_bytes(B, H, L, dk, dv, dtype);
+    if (!workspace || workspace_bytes < need) return VIG_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return VIG_ERR_ALIGN;
+    const bool bf16 = dtype == VIG_BF16;
+    const long BH = long(B) * H;
+    const bool fusable = chunkwise_fwd(L, dk, dv, bf16) && dk == 64 && vig::bigla_chunk_gated_selectable(BH, L, dk) &&
+                         chunk_offsets_ok(L, H, layout);
+    if (plan == VIG_GATES_IN_STATE_PASS && !fusable) return VIG_ERR_UNSUPPORTED;
+    const size_t mixer_bytes = round256(bigla_workspace_bytes(B, H, L, dk, dv, dtype));
+    if (plan == VIG_GATES_SEPARATE || !fusable) {
+        const int st = gate_producer_fwd(x, w1, w2, bias, g_fwd, g_bwd, B, H, L, D, dk, tau, dtype, layout, stream);
+        if (st != VIG_OK) return st;
+        return bigla_fwd_layout(q, k, v, g_fwd, g_bwd, out, B, H, L, dk, dv, dtype, layout, workspace, mixer_bytes, stream);
+    }
+    // the checks the two separate entry points make
+    if (layout == VIG_LAYOUT_BLHD &&
+        (L >= (1 << 24) || long(H) * 64 >= (1 << 24) || long(L) * H * (dk > dv ? dk : dv) >= (1L << 31)))
+        return VIG_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(w1) || !aligned16(w2) || !aligned16(bias) || !aligned16(q) || !aligned16(k) ||
+        !aligned16(v) || !aligned16(g_fwd) || !aligned16(g_bwd) || !aligned16(out))
+        return VIG_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    void *lowrank = static_cast<unsigned char *>(workspace) + mixer_bytes;
+    clear_stale_hip_error();
+    const hipError_t e = vig::gate_lowrank_launch(x, w1, lowrank, B, L, D, s);
+    if (e != hipSuccess) return hip_status(e);
+    return hip_status(vig::bigla_chunk_gated_launch(q, k, v, g_fwd, g_bwd, out, BH, L, H,
+                                                    layout == VIG_LAYOUT_BLHD ? H : 0, lowrank, w2, bias, tau, workspace, s));
+}
+
 const char *vig_status_str(int status)
 {
     switch (status) {

@@ -113,6 +113,17 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const void *p, u
                                              int(kRawDwords));
 }
 
+// log(sigmoid(z)) = min(z, 0) - log(1 + exp(-|z|)), finite for every finite z.  The bare hardware
+// exp2 / log2 serve: the exponential's argument is <= 0 (an underflow to 0 is the right limit) and
+// the logarithm's lies in [1, 2], so neither needs the range handling of the library functions,
+// which costs more vector instructions than the two transcendentals themselves.
+__device__ __forceinline__ float log_sigmoid(float z)
+{
+    const float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+    const float e = __builtin_amdgcn_exp2f(-kLog2e * fabsf(z));
+    return fmaf(-kLn2, __builtin_amdgcn_logf(1.f + e), fminf(z, 0.f));
+}
+
 template <typename T>
 struct io;  // element load/store in fp32 terms
 

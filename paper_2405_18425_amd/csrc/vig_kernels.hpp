@@ -35,6 +35,13 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
                               void *out, long BH, int L, int dk, int heads_token_major, const LocalityFusion *fusion,
                               int kernels, void *workspace, hipStream_t stream);
 
+// The eight-wave kernels with the state pass making the gates from the gate producer's low-rank half
+// (lowrank [B][L][16] bf16); g_fwd, g_bwd are written.  dk = dv = 64, bf16.
+bool bigla_chunk_gated_selectable(long BH, int L, int dk);
+hipError_t bigla_chunk_gated_launch(const void *q, const void *k, const void *v, void *g_fwd, void *g_bwd, void *out,
+                                    long BH, int L, int n_heads, int heads_token_major, const void *lowrank,
+                                    const void *w2, const void *bias, float tau, void *workspace, hipStream_t stream);
+
 // ---- gradient of the token mixer -----------------------------------------------------------------
 // Exact fp32 recurrences for any supported head shape and both dtypes; for bf16 with dv = 64 and dk = 64 or 32 the
 // chunkwise matrix-core kernels run first and leave to the exact ones only the slabs they mark
@@ -62,5 +69,7 @@ bool gate_producer_width_ok(int D, bool is_bf16);
 hipError_t gate_producer_launch(const void *x, const void *w1, const void *w2, const void *bias, void *g_fwd,
                                 void *g_bwd, int B, int H, int L, int D, int dk, float tau, bool is_bf16,
                                 int token_major, hipStream_t stream);
+// x W1 alone, bf16: lowrank [B][L][16]
+hipError_t gate_lowrank_launch(const void *x, const void *w1, void *lowrank, int B, int L, int D, hipStream_t stream);
 
 }  // namespace vig

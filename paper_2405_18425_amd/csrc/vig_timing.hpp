@@ -8,7 +8,7 @@ namespace vig {
 
 enum KernelId {
     kKernelSegmentState = 0,
-    // 1: retired (a scan over segment states that the output pass now does itself)
+    kKernelGateLowrank = 1,
     kKernelSegmentOut = 2,
     kKernelRecurrent = 3,
     kKernelLocalityGate = 4,

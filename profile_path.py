@@ -11,7 +11,8 @@ of every pass (block input of width D for the same B, L, H, dk), feeding the gat
 bigla_fwd.  mode 1 or 2 runs each pass through bigla_locality_fwd with the two-launch plan (1) or the
 fused-epilogue plan (2) instead of the two separate entry points; 3 runs bigla_bwd (the gradient of
 the token mixer, with the locality step's input as output gradient) after each forward pass, 4 the
-same through bigla_bwd_plan with the exact token-by-token kernels only.
+same through bigla_bwd_plan with the exact token-by-token kernels only; 5 and 6 (with D > 0) run the gate producer
+and the token mixer through gated_bigla_fwd, the state pass making the gates itself (5) or as two launches (6).
 Options: --fwd-plan auto|four_wave|wave_specialised|slab_sweep (kernels of the chunkwise forward);
 --alias-slabs (every slab reads the first slab's inputs: cache-resident contraction phase).
 
@@ -41,7 +42,7 @@ COPY_BYTES = 256 << 20  # calibration copy: reads 256 MiB, writes 256 MiB
 KERNEL_KEYS = (("bigla_segment_state_kernel", "segment_state"), ("bigla_ws_state_kernel", "segment_state"),
                ("bigla_segment_out_kernel", "segment_out"), ("bigla_ws_out_kernel", "segment_out"),
                ("bigla_slab_kernel", "slab"), ("locality_gate_kernel", "locality_gate"),
-               ("gate_producer", "gate_producer"))
+               ("gate_producer", "gate_producer"), ("gate_lowrank", "gate_lowrank"))
 
 
 def run(cfg: int, passes: int, gate_width: int, mode: int, fwd_plan: str, alias: bool) -> None:
@@ -66,6 +67,12 @@ def run(cfg: int, passes: int, gate_width: int, mode: int, fwd_plan: str, alias:
         vb.measure_alias_slabs(True)
     og = out = None
     for _ in range(passes):
+        if gp is not None and mode in (5, 6):
+            og, _, _ = vb.gated_bigla_fwd(gp["x"], gp["w1"], gp["w2"], t["q"], t["k"], t["v"], bias=gp["bias"],
+                                          plan={5: "in_state_pass", 6: "separate"}[mode], g_fwd=t["g_fwd"],
+                                          g_bwd=t["g_bwd"])
+            out = vb.locality_gate_fwd(t["v"], t["conv_w"], t["gate_logits"], og, w.Hg, w.Wg)
+            continue
         if gp is not None:
             vb.gate_producer_fwd(gp["x"], gp["w1"], gp["w2"], w.H, w.dk, bias=gp["bias"], g_fwd=t["g_fwd"],
                                  g_bwd=t["g_bwd"])

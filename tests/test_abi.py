@@ -180,6 +180,38 @@ def test_bigla_fwd_plan_validation_codes():
         assert call(plan) == vb.VIG_ERR_WORKSPACE  # a valid chunkwise problem without its workspace
 
 
+def test_gated_bigla_validation_codes():
+    L = vb.lib()
+
+    def call(x=PTR, w1=PTR, w2=PTR, bias=None, q=PTR, k=PTR, v=PTR, gf=PTR, gb=PTR, out=PTR, B=1, H=1, Lq=128, D=64,
+             dk=64, dv=64, tau=16.0, dtype=vb.VIG_BF16, layout=vb.VIG_LAYOUT_BHLD, plan=0, ws=PTR, ws_bytes=1 << 30):
+        return L.gated_bigla_fwd(x, w1, w2, bias, q, k, v, gf, gb, out, B, H, Lq, D, dk, dv, tau, dtype, layout, plan,
+                                 ws, ws_bytes, None)
+
+    for name in ("x", "w1", "w2", "q", "k", "v", "gf", "gb", "out"):
+        assert call(**{name: None}) == vb.VIG_ERR_NULL
+    for name in ("B", "H", "Lq", "D", "dk", "dv"):
+        assert call(**{name: 0}) == vb.VIG_ERR_SHAPE
+    assert call(tau=0.0) == vb.VIG_ERR_SHAPE
+    assert call(dtype=3) == vb.VIG_ERR_DTYPE
+    assert call(layout=2) == vb.VIG_ERR_LAYOUT
+    assert call(plan=3) == vb.VIG_ERR_UNSUPPORTED
+    assert call(D=48) == vb.VIG_ERR_UNSUPPORTED
+    assert call(dk=48) == vb.VIG_ERR_UNSUPPORTED
+    assert call(ws=None, ws_bytes=0) == vb.VIG_ERR_WORKSPACE
+    assert call(ws_bytes=64) == vb.VIG_ERR_WORKSPACE
+    assert call(ws=PTR + 8) == vb.VIG_ERR_ALIGN
+    # the plan whose state pass makes the gates: bf16, dk = dv = 64, at least two chunks
+    fused = vb.GATES_PLANS["in_state_pass"]
+    assert call(plan=fused, dtype=vb.VIG_F32) == vb.VIG_ERR_UNSUPPORTED
+    assert call(plan=fused, dk=32) == vb.VIG_ERR_UNSUPPORTED
+    assert call(plan=fused, Lq=40) == vb.VIG_ERR_UNSUPPORTED
+    assert call(plan=fused, q=PTR + 8) == vb.VIG_ERR_ALIGN
+    assert L.gated_bigla_workspace_bytes(8, 6, 4096, 64, 64, vb.VIG_BF16) >= \
+        L.bigla_workspace_bytes(8, 6, 4096, 64, 64, vb.VIG_BF16) + 8 * 4096 * 32
+    assert L.gated_bigla_workspace_bytes(8, 6, 4096, 48, 64, vb.VIG_BF16) == 0
+
+
 def test_bigla_locality_validation_codes():
     L = vb.lib()
 

@@ -676,6 +676,52 @@ def test_gate_producer_into_bigla_chain():
     assert_close(wl.widen(wl.from_torch(out, "bf16"), "bf16"), ref, TOL["bf16"], "bigla on produced gates")
 
 
+@pytest.mark.parametrize("B,L,D,H,layout,bias_mu,with_bias", [
+    (2, 1024, 384, 6, "bhld", -2.0, True),     # several segments per slab
+    (3, 300, 192, 3, "blhd", 0.0, True),       # ragged last chunk, token-major
+    (2, 130, 64, 2, "bhld", 1.0, False),       # three chunks, no bias
+    (1, 4096, 384, 2, "bhld", -1.0, True),     # two slabs cut into many segments
+    (2, 700, 128, 4, "blhd", -12.0, True),     # gates of -0.75 per step: every unit leaves the fast form
+    (2, 640, 128, 3, "bhld", -7.0, True),      # around the fast form's limit: some units inside, some outside
+])
+def test_gated_bigla_plans(B, L, D, H, layout, bias_mu, with_bias):
+    """Gate producer + token mixer as one call (Section 3 gate into Eq. (BiGLA)): the plan whose state pass makes
+    the gates itself against the oracle's chain, and bit for bit against the two separate launches."""
+    import torch
+    import oracle
+    from paper_2405_18425_amd import binding as vb
+
+    dk = dv = 64
+    _say(f"gated_bigla B{B} L{L} D{D} H{H} {layout} bias_mu {bias_mu}")
+    st = wl.generate_gate_inputs(B, L, D, H, dk, "bf16", seed=L + H, bias_mu=bias_mu)
+    w = wl.Workload("gated", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=dv, dtype="bf16", gate_mu=0.0)
+    s = wl.generate(w, seed=L + H + 1, tensors=("q", "k", "v"))
+    t = {n: wl.to_torch(a, "bf16", "cuda:0") for n, a in {**st, **s}.items()}
+    if layout == "blhd":
+        for n in ("q", "k", "v"):
+            t[n] = t[n].transpose(1, 2).contiguous()
+    w1, w2 = t["w1"].t().contiguous(), t["w2"].t().contiguous()
+    bias = t["bias"] if with_bias else None
+    res = {}
+    for plan in ("in_state_pass", "separate", "auto"):
+        out, gf, gb = vb.gated_bigla_fwd(t["x"], w1, w2, t["q"], t["k"], t["v"], bias=bias, layout=layout, plan=plan)
+        torch.cuda.synchronize()
+        res[plan] = (out, gf, gb)
+    for i, name in enumerate(("out", "g_fwd", "g_bwd")):
+        assert torch.equal(res["in_state_pass"][i], res["separate"][i]), f"{name}: fused != separate"
+        assert torch.equal(res["auto"][i], res["separate"][i]), f"{name}: auto != separate"
+    back = (lambda a: a.transpose(1, 2).contiguous()) if layout == "blhd" else (lambda a: a)
+    out, gf, gb = (wl.widen(wl.from_torch(back(a), "bf16"), "bf16") for a in res["in_state_pass"])
+    wd = {n: wl.widen(a, "bf16") for n, a in {**st, **s}.items()}
+    rf, rb = oracle.gate_producer(wd["x"], wd["w1"], wd["w2"], H, dk, wd["bias"] if with_bias else None, 16.0)
+    assert_close(gf, rf, TOL["bf16"], "g_fwd")
+    assert_close(gb, rb, TOL["bf16"], "g_bwd")
+    # the mixer on the gates as stored (bf16), and the whole chain in fp64 with unrounded gates
+    assert_close(out, oracle.bigla(wd["q"], wd["k"], wd["v"], gf, gb), TOL["bf16"], "mixer on the stored gates")
+    rel = assert_close(out, oracle.bigla(wd["q"], wd["k"], wd["v"], rf, rb), TOL["bf16"], "chain")
+    _say(f"  chain: max|err|/max|ref| = {rel:.3e}")
+
+
 def test_path_captured_in_a_hip_graph():
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
     synchronisation), so a step can be captured in a HIP graph.  Every replay -- with eager work
