@@ -1205,7 +1205,7 @@ hipError_t bigla_chunk_set_alias(int on)
     return hipMemcpyToSymbol(HIP_SYMBOL(g_alias_inputs), &on, sizeof(int));
 }
 
-bool bigla_chunk_gated_selectable(long BH, int L, int dk) { return bigla_chunk_ws_applicable(BH, L, dk); }
+bool bigla_chunk_gated_selectable(long BH, int L, int dk) { return !g_alias_on && bigla_chunk_ws_applicable(BH, L, dk); }
 
 // bigla_chunk_launch with the eight-wave kernels, the state pass making the gates from the gate producer's
 // low-rank half (and writing them to g_fwd, g_bwd, which the output pass then reads).
