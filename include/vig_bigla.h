@@ -229,14 +229,19 @@ int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, con
  *                             kernel reads it back (any supported shape and dtype);
  *   VIG_PLAN_FUSED_EPILOGUE   the output pass of the chunkwise path applies the blend to each chunk's
  *                             rows before writing them, so the token mixer's output (rounded to bf16
- *                             as bigla_fwd would store it) never goes through memory.  VIG_BF16 with
- *                             dv = 64 and dk = 64 or 32 only (VIG_ERR_UNSUPPORTED otherwise);
- *   VIG_PLAN_AUTO             the faster of the two for the shape: at present always two launches
- *                             (the output pass is bound by its vector arithmetic, and the blend's
- *                             arithmetic costs more there than a second pass over memory).
+ *                             as bigla_fwd would store it) never goes through memory: a sixth fewer
+ *                             bytes per step and no intermediate tensor, at about the speed of two
+ *                             launches where the eight-wave kernels carry it (dk = 64, grids under 65
+ *                             columns, the shapes of VIG_FWD_WAVE_SPECIALISED) and slower elsewhere.
+ *                             VIG_BF16 with dv = 64 and dk = 64 or 32 only (VIG_ERR_UNSUPPORTED
+ *                             otherwise);
+ *   VIG_PLAN_AUTO             two launches (the output pass is bound by its vector arithmetic, and
+ *                             the blend's arithmetic costs there what the second pass over memory
+ *                             costs): the fused plan is for callers who cannot afford the
+ *                             intermediate tensor.
  * The two-launch plan returns bit for bit what bigla_fwd_layout followed by locality_gate_fwd_layout
- * returns; the fused plan evaluates the token mixer with kernels of its own, whose operand roundings
- * may differ from those of bigla_fwd_layout by a few bf16 steps of the mixer's output.
+ * returns; the fused plan may differ from it by a bf16 step of an output here and there (it sums the
+ * conv's taps in pairs, and for some shapes evaluates the token mixer with another set of kernels).
  * workspace: at least bigla_locality_workspace_bytes(B, H, Hg*Wg, dk, dv, dtype, plan) bytes
  * (that function returns 0 for invalid or unsupported arguments).
  */

@@ -1237,10 +1237,12 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
     // (key width, layout, fused epilogue) pick the instantiation
     // kernels: 0 = the faster set for the shape (the eight-wave kernels where they apply), 1 = four-wave,
     // 2 = eight-wave (an error where they do not apply), 3 = four-wave with one workgroup per slab
-    const bool ws_ok = !fusion && bigla_chunk_ws_applicable(BH, L, dk);
+    // (with a fusion: grids narrow enough for the eight-wave epilogue's ring of conv-input rows)
+    const bool ws_ok = bigla_chunk_ws_applicable(BH, L, dk) && (!fusion || (fusion->Wg < kXHalo && L < (1 << 22)));
     if (kernels == 2 && !ws_ok) return hipErrorInvalidValue;
     if (kernels == 2 || (kernels == 0 && ws_ok)) {
-        return bigla_chunk_ws_launch(q, k, v, g_fwd, g_bwd, out, BH, L, heads_token_major, workspace, stream);
+        return bigla_chunk_ws_launch(q, k, v, g_fwd, g_bwd, out, BH, L, heads_token_major, workspace, stream, nullptr,
+                                     fusion);
     }
     auto go = [&](auto dk_c, auto tm_c, auto loc_c) {
         return chunk_launch<decltype(dk_c)::value, decltype(tm_c)::value, decltype(loc_c)::value>(

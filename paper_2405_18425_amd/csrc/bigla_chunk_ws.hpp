@@ -49,6 +49,18 @@ namespace vig {
 namespace {
 
 constexpr int kWsThreads = 512;           // 4 producer + 4 consumer waves
+// Rows of the conv input that the locality epilogue keeps in LDS: the 3x3 neighbourhoods of a chunk's 64 tokens
+// span the chunk and kXHalo tokens on either side (a grid row and one token: grids up to kXHalo - 1 columns
+// wide); the 64 rows that the next chunk adds are staged once every wave is through with the current chunk's.
+constexpr int kXHalo = 65;
+constexpr int kXRing = 256;  // >= 64 + 2 * kXHalo, and a power of two: row of token t is t mod kXRing
+
+// c + a.lo * b.lo + a.hi * b.hi on bf16 pairs, fp32 result
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
+{
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
+}
 constexpr int kWsTargetWorkgroups = 256;  // one workgroup per CU (LDS-limited)
 
 struct __align__(16) WsStateLds {
@@ -78,6 +90,9 @@ union WsLds {
     PathLds general;  // the general four-wave code, for a unit outside the fast form's range
 };
 __shared__ WsLds g_ws_lds;
+// locality epilogue: the rows of the conv input around the consumers' chunk, a ring indexed by token, and one row
+// of zeros (taps beside the grid).  An object of its own: only the kernels with the epilogue allocate it.
+__shared__ __align__(16) uint16_t g_ws_xr[kXRing + 1][kD];
 
 template <>
 __device__ __forceinline__ PathLds &path_lds<true>()
@@ -245,6 +260,7 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
         }
         __syncthreads();
         for (int s = 0; s <= nch; ++s) {
+            WS_MARK(0);
             if (s < nch) {
                 const int m = nch - 1 - s, b = s & 1;
                 // the wave's own rows of the key tile carry k from row order into operand order
@@ -297,7 +313,9 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
                     rlow = fetch_lowrank(m - 2);
                 }
             }
+            WS_MARK(5);
             __syncthreads();
+            WS_MARK(6);
         }
     } else {
         // Sb: backward state, carried right to left.  Sf: forward state at the segment's right edge, each
@@ -311,6 +329,7 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
 
         __syncthreads();
         for (int s = 0; s <= nch; ++s) {
+            WS_MARK(0);
             if (kGates && s + 1 < nch) {  // the forward gates of the chunk the producers take in the next step
                 make_gates(rlow, nch - 2 - s, (s + 1) & 1);
                 rlow = fetch_lowrank(nch - 3 - s);
@@ -360,7 +379,9 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
                 stage_values(sm.v[s & 1], w, lane, rv);
                 rv = load_rows(io.v, lr, token0(nch - 2 - s));
             }
+            WS_MARK(5);
             __syncthreads();
+            WS_MARK(6);
         }
         if (seg_states && sm.not_fast == 0) {  // (a unit outside the fast form's range is redone below)
             float *dst = seg_states + (slab * n_seg + seg) * kSegFloats;
@@ -392,6 +413,11 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
     }
 }
 
+// kernel argument of the output pass without the locality epilogue: converts to an all-zero LocalityFusion
+struct NoFusion {
+    __host__ __device__ operator LocalityFusion() const { return LocalityFusion{nullptr, nullptr, nullptr, nullptr, 0, 0, 0}; }
+};
+
 // ---- output pass -----------------------------------------------------------------------------------
 // One (slab, segment) unit per workgroup, chunks left to right.  Step m:
 //   producers, chunk m: before the mid-step barrier the scalings (gate scan, exponentials, scaled key
@@ -400,19 +426,27 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
 //   consumers, chunk m-1: before the barrier the two state readouts on top of what the producer
 //     left, and the output rows; after it the forward state update with chunk m-1's keys and values
 //     and the state tiles for chunk m.
-template <bool kTm>
+//
+// kLoc: the 2D gating locality injection of `lf` (Section 4.2.2) is applied to the output rows before they are
+// written: out = G * (bias + sum_taps w * x) + (1 - G) * o as in the stand-alone kernel (fp32, o rounded to
+// bf16 first), the taps summed two at a time by v_dot2c_f32_bf16.  The conv input's rows around the chunk sit in an
+// LDS ring that the consumers fill one chunk ahead (every row of x is read from memory once per segment, plus
+// the halo at the segment's ends); rows outside the sequence read as zeros through the buffer bounds check,
+// taps beside the grid are pointed at a row of zeros.  Needs Wg < kXHalo.
+template <bool kTm, bool kLoc = false>
 __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
     const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
     const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
     const float *__restrict__ seg_states /* nullptr when one segment per slab */, const int *__restrict__ seg_mild,
-    const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg, int heads)
+    const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg, int heads,
+    const typename std::conditional<kLoc, LocalityFusion, NoFusion>::type lf_arg)
 {
+    const LocalityFusion lf = lf_arg;
     if (seg_mild[blockIdx.x] == 0) {  // uniform over the workgroup
         // a unit outside the fast form's range: the general four-wave code, on four waves
         if (threadIdx.x >= 256) return;
-        const LocalityFusion none = {};
-        out_unit_general<kD, kTm, false, true>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
-                                               n_chunks, seg_chunks, n_seg, blockIdx.x, heads, none);
+        out_unit_general<kD, kTm, kLoc, true>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
+                                              n_chunks, seg_chunks, n_seg, blockIdx.x, heads, lf);
         return;
     }
     WsOutLds &sm = g_ws_lds.out;
@@ -431,6 +465,97 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
     const LaneRows lr = lane_rows<kD>(w, lane, io.pitch);
     auto token0 = [&](int m) { return unsigned(chunk0 + min(m, nch - 1)) * kC; };  // m may run past the segment: clamped, unused
 
+    // ---- locality epilogue (kLoc): what both roles need.  A lane writes 8 channels of two of its wave's 16 output
+    // rows; the consumer waves blend the first of the two in their first half-step, the producer waves the second
+    // in their second half-step (after the mid-step barrier the rounded rows are in the bounce tile), so that
+    // neither role's half grows by the whole job.
+    const int c0 = 8 * (lane & 7);  // the lane's channels of the rows it writes
+    uint32_t wp[8][5];
+    float cbias[8];
+    __amdgpu_buffer_rsrc_t rz = io.v;
+    const float inv_wg = 1.f / float(lf.Wg > 0 ? lf.Wg : 1);
+    auto ring_slot = [&](int tok) { return tok & (kXRing - 1); };
+    if (kLoc) {
+        const int head = int(slab % lf.H);
+        // taps [channel][9] bf16: the lane's 8 channels are 72 consecutive values.  Kept as bf16 pairs of
+        // taps (0,1) (2,3) (4,5) (6,7) (8,-): a pair meets the same two taps of the input in one
+        // v_dot2c_f32_bf16 (exact products, fp32 sum).
+        const uint16_t *tp = static_cast<const uint16_t *>(lf.w) + size_t(head * kD + c0) * 9;
+        uint4 raw[9];
+#pragma unroll
+        for (int i = 0; i < 9; ++i) raw[i] = reinterpret_cast<const uint4 *>(tp)[i];
+        const uint32_t *rw = reinterpret_cast<const uint32_t *>(raw);
+        auto tap = [&](int e, int k) { const int i = 9 * e + k; return (rw[i >> 1] >> (16 * (i & 1))) & 0xffffu; };
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) wp[e][pr] = tap(e, 2 * pr) | (tap(e, 2 * pr + 1) << 16);
+            wp[e][4] = tap(e, 8);
+        }
+        if (lf.bias) {
+            unpack8(*reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(lf.bias) + head * kD + c0), cbias);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) cbias[e] = 0.f;
+        }
+        const long row0 = kTm ? (slab / heads) * long(L) * heads + slab % heads : slab * long(L);
+        rz = slab_resource(static_cast<const uint16_t *>(lf.gate_logits) + row0 * kD, unsigned(L - 1) * io.pitch + kD * 2u);
+    }
+    // the lane's gate logits of row t (of its two) of chunk c of the segment
+    auto load_z = [&](int c, int t) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rz, lr.off[t] + unsigned(chunk0 + min(c, nch - 1)) * kC * lr.pitch, 0, 0);
+        return make_uint4(v.x, v.y, v.z, v.w);
+    };
+    // out = G * (bias + conv) + (1 - G) * o for row t of chunk c, from the rounded row in the bounce tile; stored
+    auto blend_row = [&](int c, int t, const uint4 zrow) {
+        const int rr = 16 * w + 8 * t + (lane >> 3);
+        uint4 o = *reinterpret_cast<const uint4 *>(&sm.ob[rr][c0]);
+        if (kLoc) {
+            const int tok = (chunk0 + c) * kC + rr;
+            // grid column of the token (tok < 2^22, checked at launch: the float quotient is off by one at most)
+            int xp = tok - int(float(tok) * inv_wg) * lf.Wg;
+            xp += xp < 0 ? lf.Wg : 0;
+            xp -= xp >= lf.Wg ? lf.Wg : 0;
+            const bool left = xp > 0, right = xp + 1 < lf.Wg;
+            float acc[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = cbias[e];
+            // the nine neighbours' rows (8 channels each); rows above and below the grid are rows outside
+            // the sequence: zeros in the ring
+            uint4 xn[9];
+#pragma unroll
+            for (int ky = -1; ky <= 1; ++ky)
+#pragma unroll
+                for (int kx = -1; kx <= 1; ++kx) {
+                    const bool in = kx < 0 ? left : (kx > 0 ? right : true);
+                    const int slot = in ? ring_slot(tok + ky * lf.Wg + kx) : kXRing;
+                    xn[3 * (ky + 1) + kx + 1] = *reinterpret_cast<const uint4 *>(&g_ws_xr[slot][c0]);
+                }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {  // channels 2j, 2j+1 of the lane's eight
+                auto dword = [&](int k) { const uint4 &v = xn[k]; return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w)); };
+#pragma unroll
+                for (int pr = 0; pr < 4; ++pr) {
+                    const uint32_t a = dword(2 * pr), b2 = dword(2 * pr + 1);
+                    acc[2 * j] = dot2(__builtin_amdgcn_perm(b2, a, 0x05040100u), wp[2 * j][pr], acc[2 * j]);
+                    acc[2 * j + 1] = dot2(__builtin_amdgcn_perm(b2, a, 0x07060302u), wp[2 * j + 1][pr], acc[2 * j + 1]);
+                }
+                acc[2 * j] = dot2(dword(8) & 0xffffu, wp[2 * j][4], acc[2 * j]);
+                acc[2 * j + 1] = dot2(dword(8) >> 16, wp[2 * j + 1][4], acc[2 * j + 1]);
+            }
+            float zf[8], of[8];
+            unpack8(zrow, zf);
+            unpack8(o, of);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float gate = __builtin_amdgcn_rcpf(1.f + __expf(-zf[e]));
+                acc[e] = fmaf(gate, acc[e] - of[e], of[e]);
+            }
+            o = make_uint4(pack2(acc[0], acc[1]), pack2(acc[2], acc[3]), pack2(acc[4], acc[5]), pack2(acc[6], acc[7]));
+        }
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{o.x, o.y, o.z, o.w}, io.out, lr.off[t] + unsigned(chunk0 + c) * kC * lr.pitch, 0, 0);
+    };
+
     if (producer) {
         bf16x8 tri_f[2], tri_b[2];
         scan_triangle<0>(w, r, g, tri_f);
@@ -442,6 +567,7 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
             stage_gates(sm.g[1], w, lane, gb);
         }
         StagedRows rgf = load_rows(io.gf, lr, token0(1)), rgb = load_rows(io.gb, lr, token0(1));
+        uint4 rz1 = make_uint4(0u, 0u, 0u, 0u);
         __syncthreads();
         for (int m = 0; m <= nch; ++m) {
             bf16x8 qf0, qf1, qb0, qb1, kf0, kf1, kb0, kb1;
@@ -488,6 +614,12 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
             WS_MARK(1);
             __syncthreads();  // mid-step: scaled keys and values visible
             WS_MARK(2);
+            // locality epilogue: the second row of the lane's two of chunk m-1, which the consumers have left rounded
+            // in the bounce tile before the barrier (they overwrite it after the end-of-step barrier)
+            if (kLoc) {
+                if (m >= 1) blend_row(m - 1, 1, rz1);
+                rz1 = load_z(m, 1);  // gate logits of the row blended a step from now
+            }
             if (m < nch) {
                 // merged masked score tile, transposed (P^T[i][t]): key sub-block I < w forward, I > w backward,
                 // I = w both (key <= query of the forward piece, key >= query of the backward one; own token in
@@ -618,6 +750,34 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
             }
         };
 
+        // ---- locality epilogue, consumer side: the ring of conv-input rows and prefetch registers
+        auto group_token0 = [&](int j) { return (chunk0 + j - 1) * kC + kXHalo; };
+        // group j: the 64 tokens that become needed with chunk j of the segment (their first: kXHalo past its start)
+        auto stage_group = [&](const StagedRows &s, int j) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int slot = ring_slot(group_token0(j) + 16 * w + 8 * t + (lane >> 3));
+                *reinterpret_cast<uint4 *>(&g_ws_xr[slot][c0]) = s.p[t];
+            }
+        };
+        __amdgpu_buffer_rsrc_t rx = io.v;
+        StagedRows rxg;
+        uint4 rz0 = make_uint4(0u, 0u, 0u, 0u);
+        if (kLoc) {
+            const long row0 = kTm ? (slab / heads) * long(L) * heads + slab % heads : slab * long(L);
+            const unsigned extent = unsigned(L - 1) * io.pitch + kD * 2u;
+            rx = slab_resource(static_cast<const uint16_t *>(lf.x) + row0 * kD, extent);
+            if (tid4 < 8) *reinterpret_cast<uint4 *>(&g_ws_xr[kXRing][8 * tid4]) = make_uint4(0u, 0u, 0u, 0u);
+            // what the first chunk needs: groups -2 .. 1 (tokens -127 .. 128 around the segment's start)
+            StagedRows first[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) first[j] = load_rows(rx, lr, unsigned(group_token0(j - 2)));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) stage_group(first[j], j - 2);
+            rxg = load_rows(rx, lr, unsigned(group_token0(2)));
+            rz0 = load_z(0, 0);
+        }
+
         if (seg_states != nullptr) {
             fold(S, 0, 0, seg, 1);
             fold(Sseg, 1, n_seg - 1, n_seg - 1 - seg, -1);
@@ -641,18 +801,30 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
                 for (int jt = 0; jt < 4; ++jt)
                     *reinterpret_cast<uint2 *>(&sm.ob[16 * w + r][16 * jt + 4 * g]) = pack4(O[jt]);
                 wave_lds_fence();
+                if (kLoc) {
+                    // (the producer of the same tokens writes the second of the lane's two rows)
+                    blend_row(c, 0, rz0);
+                    rz0 = load_z(m, 0);  // the next chunk's gate logits
+                } else {
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int rr = 16 * w + 8 * t + (lane >> 3);
-                    const uint4 o = *reinterpret_cast<const uint4 *>(&sm.ob[rr][8 * (lane & 7)]);
-                    __builtin_amdgcn_raw_buffer_store_b128(u32x4{o.x, o.y, o.z, o.w}, io.out,
-                                                           lr.off[t] + unsigned(chunk0 + c) * kC * lr.pitch, 0, 0);
+                    for (int t = 0; t < 2; ++t) {
+                        const int rr = 16 * w + 8 * t + (lane >> 3);
+                        const uint4 o = *reinterpret_cast<const uint4 *>(&sm.ob[rr][8 * (lane & 7)]);
+                        __builtin_amdgcn_raw_buffer_store_b128(u32x4{o.x, o.y, o.z, o.w}, io.out,
+                                                               lr.off[t] + unsigned(chunk0 + c) * kC * lr.pitch, 0, 0);
+                    }
                 }
             }
             WS_MARK(1);
             __syncthreads();  // mid-step
             WS_MARK(2);
             if (m >= 1) {
+                if (kLoc) {
+                    // the rows that the next chunk's neighbourhoods add: every wave is through with this chunk's, and
+                    // the ring slots they take hold rows that no later chunk needs
+                    stage_group(rxg, m + 1);
+                    rxg = load_rows(rx, lr, unsigned(group_token0(m + 2)));
+                }
                 // forward state update: S = d (S + K^T V), d = exp(chunk total)
                 const float4 t = *reinterpret_cast<const float4 *>(&sm.tot[b][16 * w + 4 * g]);
                 const float4 d = make_float4(fast_exp2(t.x * kLog2e), fast_exp2(t.y * kLog2e), fast_exp2(t.z * kLog2e), fast_exp2(t.w * kLog2e));
@@ -700,7 +872,7 @@ size_t bigla_chunk_ws_workspace_bytes(long BH, int L)
 // gates: null when g_fwd and g_bwd are inputs; otherwise the state pass makes them (and writes them there)
 hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
                                  void *out, long BH, int L, int heads_token_major, void *workspace, hipStream_t stream,
-                                 const GateSource *gates = nullptr)
+                                 const GateSource *gates = nullptr, const LocalityFusion *fusion = nullptr)
 {
     const Plan p = make_ws_plan(BH, L);
     const long blocks = BH * p.n_seg;
@@ -736,12 +908,19 @@ hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, co
     if (e != hipSuccess) return e;
     {
         LaunchTimer timer(kKernelSegmentOut, stream);
-        if (tm)
+        const NoFusion none = {};
+        if (fusion && tm)
+            hipLaunchKernelGGL((bigla_ws_out_kernel<true, true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, qq, kk,
+                               vv, gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, *fusion);
+        else if (fusion)
+            hipLaunchKernelGGL((bigla_ws_out_kernel<false, true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, qq, kk,
+                               vv, gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, *fusion);
+        else if (tm)
             hipLaunchKernelGGL((bigla_ws_out_kernel<true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, qq, kk, vv,
-                               gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads);
+                               gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, none);
         else
             hipLaunchKernelGGL((bigla_ws_out_kernel<false>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, qq, kk, vv,
-                               gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads);
+                               gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, none);
     }
     return hipGetLastError();
 }

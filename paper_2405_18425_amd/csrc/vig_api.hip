@@ -302,7 +302,7 @@ int bigla_locality_fwd(const void *q, const void *k, const void *v, const void *
     const vig::LocalityFusion fusion = {x, w, bias, gate_logits, H, Hg, Wg};
     clear_stale_hip_error();
     return hip_status(vig::bigla_chunk_launch(q, k, v, g_fwd, g_bwd, out, long(B) * H, L, dk,
-                                              layout == VIG_LAYOUT_BLHD ? H : 0, &fusion, VIG_FWD_FOUR_WAVE, workspace,
+                                              layout == VIG_LAYOUT_BLHD ? H : 0, &fusion, VIG_FWD_AUTO, workspace,
                                               static_cast<hipStream_t>(stream)));
 }
 

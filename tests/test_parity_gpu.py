@@ -451,14 +451,19 @@ def test_path_end_to_end_hierarchical_stage_shapes(grid, H):
     (1, 2, 100, 3, 64, "bhld", 0.0, True),      # many grid rows per chunk
     (1, 1, 1, 70, 64, "bhld", 0.0, True),       # degenerate grids: a single row, a single column
     (1, 1, 70, 1, 64, "bhld", 0.0, True),
+    (2, 6, 64, 64, 64, "bhld", -2.0, True),     # the benchmark grid: the widest the eight-wave epilogue takes
+    (3, 2, 64, 64, 64, "blhd", 0.0, False),
+    (2, 2, 30, 47, 64, "bhld", 1.0, True),      # grid rows that straddle chunks, ragged final chunk
+    (1, 2, 128, 33, 64, "blhd", -1.0, True),    # 66 chunks in 33-token rows, many segments
+    (2, 3, 40, 40, 64, "bhld", -12.0, True),    # every unit outside the fast form: general code inside the launches
+    (1, 3, 33, 65, 64, "bhld", 0.0, True),      # one column too wide for it: the four-wave epilogue
 ])
 def test_bigla_locality_plans(B, H, Hg, Wg, dk, layout, mu, with_bias):
     """Token mixer + locality blend as one call: the two-launch plan returns the same bits as the two
-    separate entry points; the fused-epilogue plan (the blend inside the output pass of the four-wave
-    chunkwise kernels, whose operand roundings differ from those of the wave-specialised kernels that
-    bigla_fwd may run) agrees with them to a few bf16 steps of the mixer's output; both are the
-    oracle's chain within the path's tolerance.  The conv input is a tensor of its own (not the
-    mixer's v)."""
+    separate entry points; the fused-epilogue plan (the blend inside the output pass) does too wherever it
+    runs the kernel set that bigla_fwd runs, and elsewhere agrees to a few bf16 steps of the mixer's output
+    (the two sets round their operands differently); both are the oracle's chain within the path's
+    tolerance.  The conv input is a tensor of its own (not the mixer's v)."""
     import torch
     from paper_2405_18425_amd import binding as vb
     import oracle
@@ -485,6 +490,18 @@ def test_bigla_locality_plans(B, H, Hg, Wg, dk, layout, mu, with_bias):
     for plan in ("two_launches", "auto"):
         o = outs[plan]
         assert torch.equal(o, separate), f"{plan}: {(o != separate).sum().item()} elements differ from the separate calls"
+    # bigla_fwd runs the eight-wave kernels for 64-wide keys and at least two chunks unless the sequences are short
+    # and many; elsewhere both calls run the four-wave kernels, whose epilogue repeats the locality kernel's
+    # arithmetic (the eight-wave epilogue sums the taps in pairs)
+    n_chunks = (Hg * Wg + 63) // 64
+    eight_wave = dk == 64 and n_chunks > 1 and not (B * H >= 128 and n_chunks <= 4)
+    o = outs["fused_epilogue"]
+    if not eight_wave:
+        assert torch.equal(o, separate), f"fused: {(o != separate).sum().item()} elements differ from the separate calls"
+    else:  # a bf16 step of an output here and there
+        d = (o.float() - separate.float()).abs()
+        assert float(d.max()) <= 2.0 ** -6 * float(separate.float().abs().max()), float(d.max())
+        assert float((d > 0).float().mean()) < 0.05 or Wg >= 65, float((d > 0).float().mean())
     ref_og = oracle.bigla(wd["q"], wd["k"], wd["v"], wd["g_fwd"], wd["g_bwd"])
     ref = oracle.locality_gate(wd["x"], wd["conv_w"], wd["gate_logits"], ref_og, Hg, Wg, bias64)
     assert np.array_equal(ref, oracle.bigla_locality(wd["q"], wd["k"], wd["v"], wd["g_fwd"], wd["g_bwd"], wd["x"],
