@@ -82,11 +82,12 @@ size_t bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype);
  *
  * Numerics: VIG_BF16 with dv = 64, dk = 64 or 32 and L >= 32 runs the chunkwise MFMA path (bf16
  * operands, fp32 accumulation, fp32 carried state; dk = 32 is widened to 64 key channels with zeros
- * inside the kernels).  A 64-token chunk in which some channel decays by more
- * than 32 nats (half a nat per step) is evaluated in a range-safe form, slower and with the
- * operands of every token's nearest products kept to 16 bits, that treats per-step log gates
- * below -8 as -8 (alpha < 3.4e-4 acts as a hard reset either way; the difference is far below
- * the bf16 tolerance).  Every other case runs the exact recurrence in fp32 arithmetic.
+ * inside the kernels).  Where some channel of a 64-token chunk decays by more than 32 nats (half
+ * a nat per step), the operands of every token's nearest products are kept to 16 bits: at full
+ * speed up to 60 nats per chunk where the eight-wave kernels run (dk = 64, see bigla_fwd_plan),
+ * otherwise in a range-safe form, several times slower, that treats per-step log gates below -8
+ * as -8 (alpha < 3.4e-4 acts as a hard reset either way; the difference is far below the bf16
+ * tolerance).  Every other case runs the exact recurrence in fp32 arithmetic.
  */
 int bigla_fwd(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
               void *out, int B, int H, int L, int dk, int dv, int dtype, void *workspace,

@@ -21,7 +21,9 @@
 //   per-channel sub-block total is checked): far inside fp32's range, and slow enough a decay
 //   that an output sums over enough tokens for the rounding of the scaled operands to stay
 //   within the stated tolerance.  Gates of the paper's form, sigmoid(z)^(1/16), stay inside:
-//   64 steps reach 32 nats only for z < -8 throughout.
+//   64 steps reach 32 nats only for z < -8 throughout.  (The eight-wave kernels of
+//   bigla_chunk_ws.hpp keep the fast form up to 60 nats, with split operands for the diagonal
+//   score tiles beyond 32.)
 //   RANGE-SAFE.  Otherwise cumulative gates stay local to a sub-block: off-diagonal 16x16 tiles
 //   scale keys by the decay to the END of the key's own sub-block and queries by the decay from
 //   the START of the query's sub-block times the whole-sub-block factors in between, so every
@@ -770,7 +772,7 @@ __device__ __forceinline__ void out_unit(
             chunk_gate_scan(sm.gf, tri_f, r, g, Bf, Tf);
             chunk_gate_scan(sm.gb, tri_b, r, g, Bb, Tb);
             // same totals in every wave: the choice is uniform over the workgroup
-            fast = fmaxf(chunk_decay_max(Tf), chunk_decay_max(Tb)) <= kFastRange;
+            fast = fmaxf(chunk_decay_max(Tf), chunk_decay_max(Tb)) <= kMildRange;
             if (fast)
                 out_chunk_fast(sm, w, r, g, Bf, Bb, Tf, q_row, k_row, fl, op, prefetch_first);
             else
@@ -945,7 +947,7 @@ __device__ __forceinline__ bool state_unit(
             for (int n = 0; n < 16; ++n) t[n] = T[n >> 2][n & 3];
             if (r == 0) store_chan16(sm.tot[1], g, t);
         }
-        const bool fast = fmaxf(max_f, max_b) <= kFastRange;  // uniform over the workgroup
+        const bool fast = fmaxf(max_f, max_b) <= kMildRange;  // uniform over the workgroup
         all_fast = all_fast && fast;
         next.gf = load_rows(g_fwd, kr, far_token0);
         float4 df, db;  // this chunk's decay, rows at LDS positions 16w + 4g + e

@@ -17,11 +17,16 @@ constexpr int kTargetWorkgroups = 512;  // segments are sized so that about this
 constexpr int kThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kGateFloorLog2 = -8.0f * kLog2e;  // per-step floor of the log-gate (range-safe form), log2 domain
-// Largest chunk log-decay (nats, any channel) the fast form accepts.  exp(+-32) is far inside fp32; the limit is
-// set by accuracy, not range: the faster the decay, the fewer tokens an output sums over, and the rounding of the
-// exp-scaled operands of a token's nearest few products (which the range-safe form splits into two bf16 terms)
-// then stands against a smaller output.  Up to half a nat per step, elements stay within the stated bound.
-constexpr float kFastRange = 32.0f;
+// Chunk log-decays (nats, largest over the channels) that bound the forms of a chunk's evaluation.
+//   kFastRange: beyond it the factors exp(-b) of the fast form leave the range in which fp32 products of
+//     them are safe; such chunks take the range-safe form.
+//   kMildRange: the faster the decay, the fewer tokens an output sums over, and the rounding of the exp-scaled
+//     operands of a token's nearest few products then stands against a smaller output.  Up to half a nat per step
+//     elements stay within the stated bound with bf16 operands; beyond it the operands of the diagonal score
+//     tile are split into two bf16 terms: the eight-wave kernels do that inside the fast form, the four-wave
+//     kernels take the range-safe form (which splits them always).
+constexpr float kFastRange = 60.0f;
+constexpr float kMildRange = 32.0f;
 
 // ---- small device helpers ------------------------------------------------------------------
 

@@ -28,12 +28,16 @@
 // tiles remain.
 //
 // Range.  The eight-wave code evaluates the FAST form only (queries q exp(b), keys k exp(-b), see
-// bigla_chunk.hip).  The state pass checks every chunk's total log-decay against the fast form's
-// range while it works; a (slab, segment) unit that turns out to be outside is redone on the spot,
-// by the general four-wave code of bigla_chunk.hip on four of the workgroup's eight waves (the other
-// four have left: a workgroup barrier waits for the surviving waves only), and flagged, and the
-// output pass runs the general code for the flagged units in the same way.  Nothing else changes:
-// both codes read and write the same workspace layout.
+// bigla_chunk.hip).  The state pass checks every chunk's total log-decay while it works and leaves
+// a flag per (slab, segment) unit.  A unit in which some chunk decays by more than kMildRange is
+// evaluated with the operands of the diagonal score tiles split into bf16 pairs hi + lo (three
+// products instead of one for those tiles: with fast decay an output is little more than its
+// token's nearest products, and their operands then need the bits).  A unit in which some chunk
+// is outside the fast form's range altogether (kFastRange) is redone on the spot by the general
+// four-wave code of bigla_chunk.hip on four of the workgroup's eight waves (the other four have
+// left: a workgroup barrier waits for the surviving waves only), and the output pass runs the
+// general code for it in the same way.  Nothing else changes: both codes read and write the same
+// workspace layout.
 //
 // This file is part of the translation unit of bigla_chunk.hip (included by it, after the four-wave
 // device code it calls).
@@ -69,6 +73,7 @@ struct __align__(16) WsStateLds {
     uint16_t v[2][kC][kPitch];      // [buffer] values [token][column]
     float tot[2][2][kD];            // [buffer][direction] chunk total log-gate per channel, operand order
     int not_fast;                   // some chunk of the unit is outside the fast form's range
+    int strong;                     // some chunk of the unit decays by more than kMildRange
 };
 
 struct __align__(16) WsOutLds {
@@ -176,7 +181,7 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
     const LaneRows lr = lane_rows<kD>(w, lane, io.pitch);
     auto token0 = [&](int m) { return unsigned(chunk0 + max(m, 0)) * kC; };  // m may run before the segment: clamped, unused
 
-    if (tid == 0) sm.not_fast = 0;
+    if (tid == 0) sm.not_fast = sm.strong = 0;
 
     // kGates: lane (r, g) of wave w makes the gates of channels 16g..16g+15 of token 16w + r of a chunk, the
     // consumer waves those of the forward direction, the producer waves those of the backward direction (the
@@ -295,6 +300,7 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
 #pragma unroll
                     for (int n = 0; n < 16; ++n) mn = fminf(mn, totf[n]);
                     if (!(mn >= -kFastRange)) sm.not_fast = 1;
+                    if (!(mn >= -kMildRange)) sm.strong = 1;
                 }
                 if (w == 0 && r == 0) {
                     store_chan16(sm.tot[b][1], g, totb);
@@ -302,6 +308,7 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
 #pragma unroll
                     for (int n = 0; n < 16; ++n) mn = fminf(mn, totb[n]);
                     if (!(mn >= -kFastRange)) sm.not_fast = 1;
+                    if (!(mn >= -kMildRange)) sm.strong = 1;
                 }
                 if (!kGates) {  // the gates of chunk m-1 go to the other buffer (last read one step ago)
                     stage_gates(sm.g[b ^ 1][0], w, lane, rgf);
@@ -397,8 +404,9 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
         }
     }
     // (every write of not_fast precedes the loops' last barrier)
+    // the unit's flag for the output pass: 0 general code, 1 fast form, 2 fast form with split diagonal operands
     const bool redo = sm.not_fast != 0;
-    if (tid == 0) seg_mild[blockIdx.x] = redo ? 0 : 1;
+    if (tid == 0) seg_mild[blockIdx.x] = redo ? 0 : (sm.strong != 0 ? 2 : 1);
     if (redo) {
         // some chunk is outside the fast form's range: the general code redoes the unit on four waves
         // (it overwrites everything the walk above has written for this unit)
@@ -433,22 +441,16 @@ struct NoFusion {
 // LDS ring that the consumers fill one chunk ahead (every row of x is read from memory once per segment, plus
 // the halo at the segment's ends); rows outside the sequence read as zeros through the buffer bounds check,
 // taps beside the grid are pointed at a row of zeros.  Needs Wg < kXHalo.
-template <bool kTm, bool kLoc = false>
-__global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
+//
+// split_diag (a compile-time copy of the walk for either value, so that the common one carries nothing of the
+// other): fast decay somewhere in the unit, the operands of the diagonal score tiles keep 16 bits (hi + lo).
+template <bool kTm, bool kLoc, bool split_diag>
+__device__ __forceinline__ void ws_out_unit(
     const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
     const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
-    const float *__restrict__ seg_states /* nullptr when one segment per slab */, const int *__restrict__ seg_mild,
-    const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg, int heads,
-    const typename std::conditional<kLoc, LocalityFusion, NoFusion>::type lf_arg)
+    const float *__restrict__ seg_states, const unsigned char *__restrict__ stash_all, int L, int n_chunks,
+    int seg_chunks, int n_seg, int heads, const LocalityFusion &lf)
 {
-    const LocalityFusion lf = lf_arg;
-    if (seg_mild[blockIdx.x] == 0) {  // uniform over the workgroup
-        // a unit outside the fast form's range: the general four-wave code, on four waves
-        if (threadIdx.x >= 256) return;
-        out_unit_general<kD, kTm, kLoc, true>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
-                                              n_chunks, seg_chunks, n_seg, blockIdx.x, heads, lf);
-        return;
-    }
     WsOutLds &sm = g_ws_lds.out;
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
@@ -571,6 +573,7 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
         __syncthreads();
         for (int m = 0; m <= nch; ++m) {
             bf16x8 qf0, qf1, qb0, qb1, kf0, kf1, kb0, kb1;
+            bf16x8 lo[8];  // split_diag: the low halves of the eight operands above, in that order
             const int b = m & 1;
             WS_MARK(0);
             if (m < nch) {
@@ -603,8 +606,15 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
                         kf[n] *= fast_exp2(-xf);              // k * exp(-b_i)
                     }
                 }
-                qf0 = pack8(qf); qf1 = pack8(qf + 8); qb0 = pack8(qb); qb1 = pack8(qb + 8);
-                kf0 = pack8(kf); kf1 = pack8(kf + 8); kb0 = pack8(kb); kb1 = pack8(kb + 8);
+                if (split_diag) {
+                    pack8_split(qf, qf0, lo[0]); pack8_split(qf + 8, qf1, lo[1]);
+                    pack8_split(qb, qb0, lo[2]); pack8_split(qb + 8, qb1, lo[3]);
+                    pack8_split(kf, kf0, lo[4]); pack8_split(kf + 8, kf1, lo[5]);
+                    pack8_split(kb, kb0, lo[6]); pack8_split(kb + 8, kb1, lo[7]);
+                } else {
+                    qf0 = pack8(qf); qf1 = pack8(qf + 8); qb0 = pack8(qb); qb1 = pack8(qb + 8);
+                    kf0 = pack8(kf); kf1 = pack8(kf + 8); kb0 = pack8(kb); kb1 = pack8(kb + 8);
+                }
                 *reinterpret_cast<bf16x8 *>(&sm.kf[b][row][8 * g]) = kf0;
                 *reinterpret_cast<bf16x8 *>(&sm.kf[b][row][32 + 8 * g]) = kf1;
                 *reinterpret_cast<bf16x8 *>(&sm.kb[row][8 * g]) = kb0;
@@ -630,8 +640,14 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
                 for (int I = 0; I < 4; ++I) {
                     f32x4 p;
                     if (I == w) {
-                        p = mfma(kf1, qf1, mfma(kf0, qf0, zero));
-                        const f32x4 pb = mfma(kb1, qb1, mfma(kb0, qb0, zero));
+                        f32x4 pb = zero;
+                        p = zero;
+                        if (split_diag) {  // hi.lo + lo.hi first (the small terms), then hi.hi
+                            p = mfma(lo[5], qf1, mfma(lo[4], qf0, mfma(kf1, lo[1], mfma(kf0, lo[0], p))));
+                            pb = mfma(lo[7], qb1, mfma(lo[6], qb0, mfma(kb1, lo[3], mfma(kb0, lo[2], pb))));
+                        }
+                        p = mfma(kf1, qf1, mfma(kf0, qf0, p));
+                        pb = mfma(kb1, qb1, mfma(kb0, qb0, pb));
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const int i = 4 * g + e;
@@ -848,6 +864,30 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
             __syncthreads();  // end of step
             WS_MARK(4);
         }
+    }
+}
+
+template <bool kTm, bool kLoc = false>
+__global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
+    const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
+    const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
+    const float *__restrict__ seg_states /* nullptr when one segment per slab */, const int *__restrict__ seg_mild,
+    const unsigned char *__restrict__ stash_all, int L, int n_chunks, int seg_chunks, int n_seg, int heads,
+    const typename std::conditional<kLoc, LocalityFusion, NoFusion>::type lf_arg)
+{
+    const LocalityFusion lf = lf_arg;
+    const int unit_flag = seg_mild[blockIdx.x];  // what the state pass found: uniform over the workgroup
+    if (unit_flag == 0) {
+        // a unit outside the fast form's range: the general four-wave code, on four waves
+        if (threadIdx.x >= 256) return;
+        out_unit_general<kD, kTm, kLoc, true>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
+                                              n_chunks, seg_chunks, n_seg, blockIdx.x, heads, lf);
+    } else if (unit_flag == 2) {
+        ws_out_unit<kTm, kLoc, true>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L, n_chunks,
+                                     seg_chunks, n_seg, heads, lf);
+    } else {
+        ws_out_unit<kTm, kLoc, false>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L, n_chunks,
+                                      seg_chunks, n_seg, heads, lf);
     }
 }
 

@@ -54,14 +54,16 @@ def _range_edge_inputs(w, per_step, seed):
     return s
 
 
-# bf16 stores -0.4805, -0.5, -0.5195: chunk totals of 30.75 and 32 nats (inside the fast form's 32) and 33.25;
-# -0.9492 and -2 are decays under which an output is little more than the token's own q.k v
-@pytest.mark.parametrize("per_step", (0.48, 0.5, 0.52, 0.95, 2.0))
+# bf16 stores -0.4805, -0.5, -0.5195: chunk totals of 30.75 and 32 nats (bf16 operands throughout) and 33.25 (from
+# here on the diagonal score tiles have split operands: inside the fast form in the eight-wave kernels, in the
+# range-safe form elsewhere); -0.6992 and -0.8984 (44.75 and 57.5 nats) stay inside the fast form's range of 60,
+# -0.9492 (60.75) leaves it; at -2 an output is little more than the token's own q.k v
+@pytest.mark.parametrize("per_step", (0.48, 0.5, 0.52, 0.7, 0.9, 0.95, 2.0))
 @pytest.mark.parametrize("L,dk,seed", ((1024, 64, 41), (333, 64, 41), (1024, 32, 41), (1024, 32, 44), (1024, 32, 42)))
 def test_bigla_fast_form_range_edge(per_step, L, dk, seed):
     """Uniform decay that puts every chunk total just inside, and just beyond, the range in which the
     chunkwise kernels may use the factored form q exp(b) . k exp(-b) (Section 4.4's chunk form has no such
-    limit on paper; the kernels keep it to decays under which the rounded operands stay within tolerance)."""
+    limit on paper; the kernels keep its bf16 operands to decays under which they stay within tolerance)."""
     w = wl.Workload("edge", B=3, H=4, Hg=1, Wg=L, dk=dk, dv=64, dtype="bf16", gate_mu=1.0)
     _say(f"bigla range edge {per_step} L{L} dk{dk}")
     s = _range_edge_inputs(w, per_step, seed=seed)
