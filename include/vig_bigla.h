@@ -84,7 +84,7 @@ size_t bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype);
  * operands, fp32 accumulation, fp32 carried state; dk = 32 is widened to 64 key channels with zeros
  * inside the kernels).  Where some channel of a 64-token chunk decays by more than 32 nats (half
  * a nat per step), the operands of every token's nearest products are kept to 16 bits: at full
- * speed up to 60 nats per chunk where the eight-wave kernels run (dk = 64, see bigla_fwd_plan),
+ * speed up to 60 nats per chunk where the eight-wave kernels run (see bigla_fwd_plan),
  * otherwise in a range-safe form, several times slower, that treats per-step log gates below -8
  * as -8 (alpha < 3.4e-4 acts as a hard reset either way; the difference is far below the bf16
  * tolerance).  Every other case runs the exact recurrence in fp32 arithmetic.
@@ -111,8 +111,8 @@ int bigla_fwd_layout(const void *q, const void *k, const void *v, const void *g_
  *                             step for its 16 tokens;
  *   VIG_FWD_WAVE_SPECIALISED  workgroups of eight waves: producer waves (gate scans, exponentials, scaled
  *                             keys, score tiles, P.V) and consumer waves (state readouts, output rows,
- *                             state update) on the same SIMDs, one chunk apart.  VIG_BF16 with
- *                             dk = dv = 64 and at least two chunks, except short sequences in many slabs
+ *                             state update) on the same SIMDs, one chunk apart.  VIG_BF16 with dv = 64,
+ *                             dk = 64 or 32 and at least two chunks, except short sequences in many slabs
  *                             (VIG_ERR_UNSUPPORTED otherwise).  A (slab, segment) unit whose gates are
  *                             outside the fast form's range is evaluated by the general four-wave code
  *                             inside the same launches.
@@ -232,8 +232,8 @@ int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, con
  *                             rows before writing them, so the token mixer's output (rounded to bf16
  *                             as bigla_fwd would store it) never goes through memory: a sixth fewer
  *                             bytes per step and no intermediate tensor, at about the speed of two
- *                             launches where the eight-wave kernels carry it (dk = 64, grids under 65
- *                             columns, the shapes of VIG_FWD_WAVE_SPECIALISED) and slower elsewhere.
+ *                             launches where the eight-wave kernels carry it (grids under 65 columns,
+ *                             the shapes of VIG_FWD_WAVE_SPECIALISED) and slower elsewhere.
  *                             VIG_BF16 with dv = 64 and dk = 64 or 32 only (VIG_ERR_UNSUPPORTED
  *                             otherwise);
  *   VIG_PLAN_AUTO             two launches (the output pass is bound by its vector arithmetic, and

@@ -1207,7 +1207,7 @@ hipError_t bigla_chunk_set_alias(int on)
     return hipMemcpyToSymbol(HIP_SYMBOL(g_alias_inputs), &on, sizeof(int));
 }
 
-bool bigla_chunk_gated_selectable(long BH, int L, int dk) { return !g_alias_on && bigla_chunk_ws_applicable(BH, L, dk); }
+bool bigla_chunk_gated_selectable(long BH, int L, int dk) { return !g_alias_on && dk == kD && bigla_chunk_ws_applicable(BH, L, dk); }
 
 // bigla_chunk_launch with the eight-wave kernels, the state pass making the gates from the gate producer's
 // low-rank half (and writing them to g_fwd, g_bwd, which the output pass then reads).
@@ -1223,7 +1223,7 @@ hipError_t bigla_chunk_gated_launch(const void *q, const void *k, const void *v,
     gs.bias = static_cast<const uint16_t *>(bias);
     gs.inv_tau = 1.f / tau;
     gs.n_heads = n_heads;
-    return bigla_chunk_ws_launch(q, k, v, g_fwd, g_bwd, out, BH, L, heads_token_major, workspace, stream, &gs);
+    return bigla_chunk_ws_launch(q, k, v, g_fwd, g_bwd, out, BH, L, kD, heads_token_major, workspace, stream, &gs);
 }
 
 bool bigla_chunk_ws_selectable(long BH, int L, int dk) { return bigla_chunk_ws_applicable(BH, L, dk); }
@@ -1243,8 +1243,8 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
     const bool ws_ok = bigla_chunk_ws_applicable(BH, L, dk) && (!fusion || (fusion->Wg < kXHalo && L < (1 << 22)));
     if (kernels == 2 && !ws_ok) return hipErrorInvalidValue;
     if (kernels == 2 || (kernels == 0 && ws_ok)) {
-        return bigla_chunk_ws_launch(q, k, v, g_fwd, g_bwd, out, BH, L, heads_token_major, workspace, stream, nullptr,
-                                     fusion);
+        return bigla_chunk_ws_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, heads_token_major, workspace, stream,
+                                     nullptr, fusion);
     }
     auto go = [&](auto dk_c, auto tm_c, auto loc_c) {
         return chunk_launch<decltype(dk_c)::value, decltype(tm_c)::value, decltype(loc_c)::value>(

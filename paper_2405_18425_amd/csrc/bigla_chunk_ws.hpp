@@ -1,4 +1,4 @@
-// Wave-specialised chunkwise BiGLA forward (Section 4.2.1, Eq. (BiGLA)) for bf16, dk = dv = 64:
+// Wave-specialised chunkwise BiGLA forward (Section 4.2.1, Eq. (BiGLA)) for bf16, dv = 64, dk = 64 or 32:
 // the same two passes, workspace layout and arithmetic as the four-wave kernels of
 // bigla_chunk.hip (whose header has the algebra of the regrouping over 64-token chunks), with the
 // work of a chunk step divided between two sets of waves that run on the same SIMDs.
@@ -118,11 +118,15 @@ inline Plan make_ws_plan(long BH, int L)
     return p;
 }
 
-// One slab's row tensors
-template <bool kTm>
+// One slab's row tensors.  kDk: width of the q, k and gate rows (64, or 32: the rows are then widened to the
+// kernels' 64 channels with zeros as they are taken out of the registers they were loaded into, and the code
+// skips the zero half: two of the four 16-channel tiles, one of the two K-steps of every contraction over
+// channels, state rows 32..63).
+template <bool kTm, int kDk = kD>
 struct SlabIo {
     __amdgpu_buffer_rsrc_t q, k, gf, gb, v, out;
-    unsigned pitch;  // bytes between consecutive tokens
+    unsigned pitch;      // bytes between consecutive tokens of v and out
+    unsigned key_pitch;  // of q, k and the gates
     __device__ __forceinline__ SlabIo(const uint16_t *q_all, const uint16_t *k_all, const uint16_t *v_all,
                                       const uint16_t *gf_all, const uint16_t *gb_all, uint16_t *out_all, long slab,
                                       int L, int heads)
@@ -130,11 +134,13 @@ struct SlabIo {
         const long row0 = kTm ? (slab / heads) * L * heads + slab % heads : slab * L;
         const long in0 = g_alias_inputs ? 0 : row0;
         pitch = unsigned(kTm ? heads : 1) * kD * 2u;
+        key_pitch = unsigned(kTm ? heads : 1) * kDk * 2u;
         const unsigned extent = unsigned(L - 1) * pitch + kD * 2u;
-        q = slab_resource(q_all ? q_all + in0 * kD : nullptr, q_all ? extent : 0u);
-        k = slab_resource(k_all + in0 * kD, extent);
-        gf = slab_resource(gf_all + in0 * kD, extent);
-        gb = slab_resource(gb_all + in0 * kD, extent);
+        const unsigned key_extent = unsigned(L - 1) * key_pitch + kDk * 2u;
+        q = slab_resource(q_all ? q_all + in0 * kDk : nullptr, q_all ? key_extent : 0u);
+        k = slab_resource(k_all + in0 * kDk, key_extent);
+        gf = slab_resource(gf_all + in0 * kDk, key_extent);
+        gb = slab_resource(gb_all + in0 * kDk, key_extent);
         v = slab_resource(v_all + in0 * kD, extent);
         out = slab_resource(out_all ? out_all + row0 * kD : nullptr, out_all ? extent : 0u);
     }
@@ -159,7 +165,7 @@ struct GateSource {
 // (the wave of tokens 16w..16w+15 does what that kernel's wave does for 16 tokens, for the 64 channels of its
 // head in one direction), put them into the gate tiles in LDS, and write them to memory for the output pass;
 // no gates are loaded.
-template <bool kTm, bool kGates = false>
+template <bool kTm, bool kGates = false, int kDk = kD>
 __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
     const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all, const uint16_t *gf_all,
     const uint16_t *gb_all, float *__restrict__ seg_states, int *__restrict__ seg_mild,
@@ -174,12 +180,19 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
     long slab;
     int seg;
     unit_slab_segment(blockIdx.x, n_seg, slab, seg);
-    const SlabIo<kTm> io(nullptr, k_all, v_all, gf_all, gb_all, nullptr, slab, L, heads);
+    static_assert(!kGates || kDk == kD, "the gates are made for 64-wide heads");
+    constexpr int kCt = kDk / 16;       // 16-channel tiles that carry data
+    const bool owns_rows = 16 * w < kDk;  // consumer wave w carries state rows 16w .. 16w+15
+    const SlabIo<kTm, kDk> io(nullptr, k_all, v_all, gf_all, gb_all, nullptr, slab, L, heads);
     const int chunk0 = seg * seg_chunks;
     const int nch = min(seg_chunks, n_chunks - chunk0);
     const int row = 16 * w + r;
-    const LaneRows lr = lane_rows<kD>(w, lane, io.pitch);
+    const LaneRows lr = lane_rows<kD>(w, lane, io.pitch), lrk = lane_rows<kDk>(w, lane, io.key_pitch);
     auto token0 = [&](int m) { return unsigned(chunk0 + max(m, 0)) * kC; };  // m may run before the segment: clamped, unused
+    auto load_keys = [&](__amdgpu_buffer_rsrc_t rows, int m) {
+        StagedRows s = load_rows(rows, lrk, token0(m));
+        return s;
+    };
 
     if (tid == 0) sm.not_fast = sm.strong = 0;
 
@@ -254,14 +267,16 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
         bf16x8 tri_f[2], tri_b[2];
         scan_triangle<0>(w, r, g, tri_f);
         scan_triangle<1>(w, r, g, tri_b);
-        StagedRows rk = load_rows(io.k, lr, token0(nch - 1));
+        StagedRows rk = load_keys(io.k, nch - 1);
         StagedRows rgf, rgb;
         if (!kGates) {
-            const StagedRows gf = load_rows(io.gf, lr, token0(nch - 1)), gb = load_rows(io.gb, lr, token0(nch - 1));
+            StagedRows gf = load_keys(io.gf, nch - 1), gb = load_keys(io.gb, nch - 1);
+            zero_widened_half<kDk>(gf, lane);
+            zero_widened_half<kDk>(gb, lane);
             stage_gates(sm.g[0][0], w, lane, gf);
             stage_gates(sm.g[0][1], w, lane, gb);
-            rgf = load_rows(io.gf, lr, token0(nch - 2));
-            rgb = load_rows(io.gb, lr, token0(nch - 2));
+            rgf = load_keys(io.gf, nch - 2);
+            rgb = load_keys(io.gb, nch - 2);
         }
         __syncthreads();
         for (int s = 0; s <= nch; ++s) {
@@ -269,13 +284,16 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
             if (s < nch) {
                 const int m = nch - 1 - s, b = s & 1;
                 // the wave's own rows of the key tile carry k from row order into operand order
+                zero_widened_half<kDk>(rk, lane);
                 bounce_store(sm.ks[b][0], w, lane, rk);
                 wave_lds_fence();
                 float kf[16], kb[16], totf[16], totb[16];
                 unpack16(bounce_load(sm.ks[b][0], row, g), kf);
-                rk = load_rows(io.k, lr, token0(m - 1));
+                rk = load_keys(io.k, m - 1);
 #pragma unroll
-                for (int ct = 0; ct < 4; ++ct) {
+                for (int n = 4 * kCt; n < 16; ++n) kb[n] = totf[n] = totb[n] = 0.f;  // (kf is zero there already)
+#pragma unroll
+                for (int ct = 0; ct < kCt; ++ct) {
                     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
                     const bf16x8 f0 = token_operand(sm.g[b][0], 0, 1, 16 * ct, r, g), f1 = token_operand(sm.g[b][0], 2, 3, 16 * ct, r, g);
                     const bf16x8 b0 = token_operand(sm.g[b][1], 0, 1, 16 * ct, r, g), b1 = token_operand(sm.g[b][1], 2, 3, 16 * ct, r, g);
@@ -311,10 +329,12 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
                     if (!(mn >= -kMildRange)) sm.strong = 1;
                 }
                 if (!kGates) {  // the gates of chunk m-1 go to the other buffer (last read one step ago)
+                    zero_widened_half<kDk>(rgf, lane);
+                    zero_widened_half<kDk>(rgb, lane);
                     stage_gates(sm.g[b ^ 1][0], w, lane, rgf);
                     stage_gates(sm.g[b ^ 1][1], w, lane, rgb);
-                    rgf = load_rows(io.gf, lr, token0(m - 2));
-                    rgb = load_rows(io.gb, lr, token0(m - 2));
+                    rgf = load_keys(io.gf, m - 2);
+                    rgb = load_keys(io.gb, m - 2);
                 } else if (m >= 1) {  // the backward gates of chunk m-1
                     make_gates(rlow, m - 1, b ^ 1);
                     rlow = fetch_lowrank(m - 2);
@@ -345,15 +365,18 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
                 const int m = nch - s, b = (s - 1) & 1;
                 {  // stash for chunk m: the backward state entering it from the right and the decay to the segment's edge
                     unsigned char *dstm = stash_slab + size_t(chunk0 + m) * kStashBytes;
-                    if (m + 1 < nch) {
+                    // (a 32-wide head: the state rows 32..63 are zero, and neither stored here nor fetched by the
+                    // output pass; a unit redone by the general code gets its whole stash from that code)
+                    if (m + 1 < nch && owns_rows) {
                         uint4 *sdst = reinterpret_cast<uint4 *>(dstm) + tid4;
                         const uint2 a = pack4(Sb[0]), bb = pack4(Sb[1]), c = pack4(Sb[2]), d = pack4(Sb[3]);
                         sdst[0] = make_uint4(a.x, a.y, bb.x, bb.y);
                         sdst[256] = make_uint4(c.x, c.y, d.x, d.y);
                     }
-                    if (r == 0)
+                    if (r == 0 && owns_rows)
                         *reinterpret_cast<float4 *>(dstm + size_t(kD) * kD * sizeof(uint16_t) + (16 * w + 4 * g) * sizeof(float)) = rb;
                 }
+              if (owns_rows) {
                 f32x4 Cf[4];
 #pragma unroll
                 for (int jt = 0; jt < 4; ++jt) Cf[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -381,6 +404,7 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
                 }
                 rf = sf4;
                 rb.x *= db.x; rb.y *= db.y; rb.z *= db.z; rb.w *= db.w;
+              }
             }
             if (s < nch) {  // values of the chunk the consumers take in the next step, into the buffer not in use
                 stage_values(sm.v[s & 1], w, lane, rv);
@@ -416,8 +440,8 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
         }
         __syncthreads();  // waits for the four waves that stay (and for the others to have left)
         if (kGates) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // the gates the other waves wrote are read below
-        state_unit<kD, kTm, true, true>(k_all, v_all, gf_all, gb_all, seg_states, stash, L, n_chunks, seg_chunks, n_seg,
-                                        blockIdx.x, heads);
+        state_unit<kDk, kTm, true, true>(k_all, v_all, gf_all, gb_all, seg_states, stash, L, n_chunks, seg_chunks, n_seg,
+                                         blockIdx.x, heads);
     }
 }
 
@@ -444,7 +468,7 @@ struct NoFusion {
 //
 // split_diag (a compile-time copy of the walk for either value, so that the common one carries nothing of the
 // other): fast decay somewhere in the unit, the operands of the diagonal score tiles keep 16 bits (hi + lo).
-template <bool kTm, bool kLoc, bool split_diag>
+template <bool kTm, bool kLoc, bool split_diag, int kDk>
 __device__ __forceinline__ void ws_out_unit(
     const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
     const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
@@ -460,11 +484,14 @@ __device__ __forceinline__ void ws_out_unit(
     long slab;
     int seg;
     unit_slab_segment(blockIdx.x, n_seg, slab, seg);
-    const SlabIo<kTm> io(q_all, k_all, v_all, gf_all, gb_all, out_all, slab, L, heads);
+    constexpr int kCt = kDk / 16;   // 16-channel tiles that carry data
+    constexpr int kKs = kDk / 32;   // K-steps of a contraction over channels
+    const bool owns_rows = 16 * w < kDk;  // consumer wave w carries state rows 16w .. 16w+15
+    const SlabIo<kTm, kDk> io(q_all, k_all, v_all, gf_all, gb_all, out_all, slab, L, heads);
     const int chunk0 = seg * seg_chunks;
     const int nch = min(seg_chunks, n_chunks - chunk0);
     const int row = 16 * w + r;
-    const LaneRows lr = lane_rows<kD>(w, lane, io.pitch);
+    const LaneRows lr = lane_rows<kD>(w, lane, io.pitch), lrk = lane_rows<kDk>(w, lane, io.key_pitch);
     auto token0 = [&](int m) { return unsigned(chunk0 + min(m, nch - 1)) * kC; };  // m may run past the segment: clamped, unused
 
     // ---- locality epilogue (kLoc): what both roles need.  A lane writes 8 channels of two of its wave's 16 output
@@ -558,26 +585,37 @@ __device__ __forceinline__ void ws_out_unit(
         __builtin_amdgcn_raw_buffer_store_b128(u32x4{o.x, o.y, o.z, o.w}, io.out, lr.off[t] + unsigned(chunk0 + c) * kC * lr.pitch, 0, 0);
     };
 
+    // a contraction over the channels that carry data: one K-step for a 32-wide head, two otherwise
+    auto dotk = [](bf16x8 a0, bf16x8 a1, bf16x8 b0, bf16x8 b1, f32x4 acc) {
+        acc = mfma(a0, b0, acc);
+        if (kKs > 1) acc = mfma(a1, b1, acc);
+        return acc;
+    };
+
     if (producer) {
         bf16x8 tri_f[2], tri_b[2];
         scan_triangle<0>(w, r, g, tri_f);
         scan_triangle<1>(w, r, g, tri_b);
-        StagedRows rq = load_rows(io.q, lr, token0(0)), rk = load_rows(io.k, lr, token0(0)), rv = load_rows(io.v, lr, token0(0));
+        StagedRows rq = load_rows(io.q, lrk, token0(0)), rk = load_rows(io.k, lrk, token0(0)), rv = load_rows(io.v, lr, token0(0));
         {
-            const StagedRows gf = load_rows(io.gf, lr, token0(0)), gb = load_rows(io.gb, lr, token0(0));
+            StagedRows gf = load_rows(io.gf, lrk, token0(0)), gb = load_rows(io.gb, lrk, token0(0));
+            zero_widened_half<kDk>(gf, lane);
+            zero_widened_half<kDk>(gb, lane);
             stage_gates(sm.g[0], w, lane, gf);
             stage_gates(sm.g[1], w, lane, gb);
         }
-        StagedRows rgf = load_rows(io.gf, lr, token0(1)), rgb = load_rows(io.gb, lr, token0(1));
+        StagedRows rgf = load_rows(io.gf, lrk, token0(1)), rgb = load_rows(io.gb, lrk, token0(1));
         uint4 rz1 = make_uint4(0u, 0u, 0u, 0u);
         __syncthreads();
         for (int m = 0; m <= nch; ++m) {
-            bf16x8 qf0, qf1, qb0, qb1, kf0, kf1, kb0, kb1;
-            bf16x8 lo[8];  // split_diag: the low halves of the eight operands above, in that order
+            bf16x8 qf0 = {}, qf1 = {}, qb0 = {}, qb1 = {}, kf0 = {}, kf1 = {}, kb0 = {}, kb1 = {};
+            bf16x8 lo[8] = {};  // split_diag: the low halves of the eight operands above, in that order
             const int b = m & 1;
             WS_MARK(0);
             if (m < nch) {
                 // the wave's own rows of the key tiles carry q and k from row order into operand order
+                zero_widened_half<kDk>(rq, lane);
+                zero_widened_half<kDk>(rk, lane);
                 bounce_store(sm.kf[b], w, lane, rq);
                 bounce_store(sm.kb, w, lane, rk);
                 stage_values(sm.v[b], w, lane, rv);
@@ -585,11 +623,13 @@ __device__ __forceinline__ void ws_out_unit(
                 float qf[16], kf[16], qb[16], kb[16], tot[16];
                 unpack16(bounce_load(sm.kf[b], row, g), qf);
                 unpack16(bounce_load(sm.kb, row, g), kf);
-                rq = load_rows(io.q, lr, token0(m + 1));
-                rk = load_rows(io.k, lr, token0(m + 1));
+                rq = load_rows(io.q, lrk, token0(m + 1));
+                rk = load_rows(io.k, lrk, token0(m + 1));
                 rv = load_rows(io.v, lr, token0(m + 1));
 #pragma unroll
-                for (int ct = 0; ct < 4; ++ct) {
+                for (int n = 4 * kCt; n < 16; ++n) qb[n] = kb[n] = tot[n] = 0.f;  // (qf and kf are zero there already)
+#pragma unroll
+                for (int ct = 0; ct < kCt; ++ct) {
                     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
                     const bf16x8 f0 = token_operand(sm.g[0], 0, 1, 16 * ct, r, g), f1 = token_operand(sm.g[0], 2, 3, 16 * ct, r, g);
                     const bf16x8 b0 = token_operand(sm.g[1], 0, 1, 16 * ct, r, g), b1 = token_operand(sm.g[1], 2, 3, 16 * ct, r, g);
@@ -607,18 +647,24 @@ __device__ __forceinline__ void ws_out_unit(
                     }
                 }
                 if (split_diag) {
-                    pack8_split(qf, qf0, lo[0]); pack8_split(qf + 8, qf1, lo[1]);
-                    pack8_split(qb, qb0, lo[2]); pack8_split(qb + 8, qb1, lo[3]);
-                    pack8_split(kf, kf0, lo[4]); pack8_split(kf + 8, kf1, lo[5]);
-                    pack8_split(kb, kb0, lo[6]); pack8_split(kb + 8, kb1, lo[7]);
+                    pack8_split(qf, qf0, lo[0]); pack8_split(qb, qb0, lo[2]);
+                    pack8_split(kf, kf0, lo[4]); pack8_split(kb, kb0, lo[6]);
+                    if (kKs > 1) {
+                        pack8_split(qf + 8, qf1, lo[1]); pack8_split(qb + 8, qb1, lo[3]);
+                        pack8_split(kf + 8, kf1, lo[5]); pack8_split(kb + 8, kb1, lo[7]);
+                    }
                 } else {
-                    qf0 = pack8(qf); qf1 = pack8(qf + 8); qb0 = pack8(qb); qb1 = pack8(qb + 8);
-                    kf0 = pack8(kf); kf1 = pack8(kf + 8); kb0 = pack8(kb); kb1 = pack8(kb + 8);
+                    qf0 = pack8(qf); qb0 = pack8(qb); kf0 = pack8(kf); kb0 = pack8(kb);
+                    if (kKs > 1) {
+                        qf1 = pack8(qf + 8); qb1 = pack8(qb + 8); kf1 = pack8(kf + 8); kb1 = pack8(kb + 8);
+                    }
                 }
                 *reinterpret_cast<bf16x8 *>(&sm.kf[b][row][8 * g]) = kf0;
-                *reinterpret_cast<bf16x8 *>(&sm.kf[b][row][32 + 8 * g]) = kf1;
                 *reinterpret_cast<bf16x8 *>(&sm.kb[row][8 * g]) = kb0;
-                *reinterpret_cast<bf16x8 *>(&sm.kb[row][32 + 8 * g]) = kb1;
+                if (kKs > 1) {  // (the upper K-step of the key tiles is never read otherwise)
+                    *reinterpret_cast<bf16x8 *>(&sm.kf[b][row][32 + 8 * g]) = kf1;
+                    *reinterpret_cast<bf16x8 *>(&sm.kb[row][32 + 8 * g]) = kb1;
+                }
                 if (w == 3 && r == 15) store_chan16(sm.tot[b], g, tot);  // for the state decay
             }
             WS_MARK(1);
@@ -643,24 +689,22 @@ __device__ __forceinline__ void ws_out_unit(
                         f32x4 pb = zero;
                         p = zero;
                         if (split_diag) {  // hi.lo + lo.hi first (the small terms), then hi.hi
-                            p = mfma(lo[5], qf1, mfma(lo[4], qf0, mfma(kf1, lo[1], mfma(kf0, lo[0], p))));
-                            pb = mfma(lo[7], qb1, mfma(lo[6], qb0, mfma(kb1, lo[3], mfma(kb0, lo[2], pb))));
+                            p = dotk(lo[4], lo[5], qf0, qf1, dotk(kf0, kf1, lo[0], lo[1], p));
+                            pb = dotk(lo[6], lo[7], qb0, qb1, dotk(kb0, kb1, lo[2], lo[3], pb));
                         }
-                        p = mfma(kf1, qf1, mfma(kf0, qf0, p));
-                        pb = mfma(kb1, qb1, mfma(kb0, qb0, pb));
+                        p = dotk(kf0, kf1, qf0, qf1, p);
+                        pb = dotk(kb0, kb1, qb0, qb1, pb);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const int i = 4 * g + e;
                             p[e] = (i <= r ? p[e] : 0.f) + (i >= r ? pb[e] : 0.f);
                         }
                     } else if (I < w) {
-                        const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kf[b][16 * I + r][8 * g]);
-                        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kf[b][16 * I + r][32 + 8 * g]);
-                        p = mfma(a1, qf1, mfma(a0, qf0, zero));
+                        p = mfma(*reinterpret_cast<const bf16x8 *>(&sm.kf[b][16 * I + r][8 * g]), qf0, zero);
+                        if (kKs > 1) p = mfma(*reinterpret_cast<const bf16x8 *>(&sm.kf[b][16 * I + r][32 + 8 * g]), qf1, p);
                     } else {
-                        const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][8 * g]);
-                        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][32 + 8 * g]);
-                        p = mfma(a1, qb1, mfma(a0, qb0, zero));
+                        p = mfma(*reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][8 * g]), qb0, zero);
+                        if (kKs > 1) p = mfma(*reinterpret_cast<const bf16x8 *>(&sm.kb[16 * I + r][32 + 8 * g]), qb1, p);
                     }
                     split4(p, ph[I], pl[I]);
                 }
@@ -678,14 +722,18 @@ __device__ __forceinline__ void ws_out_unit(
 #pragma unroll
                 for (int jt = 0; jt < 4; ++jt) sm.hand_o[jt][tid4] = __builtin_bit_cast(uint4, O[jt]);
                 sm.hand_q[0][tid4] = __builtin_bit_cast(uint4, qf0);
-                sm.hand_q[1][tid4] = __builtin_bit_cast(uint4, qf1);
                 sm.hand_q[2][tid4] = __builtin_bit_cast(uint4, qb0);
-                sm.hand_q[3][tid4] = __builtin_bit_cast(uint4, qb1);
+                if (kKs > 1) {
+                    sm.hand_q[1][tid4] = __builtin_bit_cast(uint4, qf1);
+                    sm.hand_q[3][tid4] = __builtin_bit_cast(uint4, qb1);
+                }
                 // the gates of chunk m+1 (the tiles were last read before the mid-step barrier)
+                zero_widened_half<kDk>(rgf, lane);
+                zero_widened_half<kDk>(rgb, lane);
                 stage_gates(sm.g[0], w, lane, rgf);
                 stage_gates(sm.g[1], w, lane, rgb);
-                rgf = load_rows(io.gf, lr, token0(m + 2));
-                rgb = load_rows(io.gb, lr, token0(m + 2));
+                rgf = load_rows(io.gf, lrk, token0(m + 2));
+                rgb = load_rows(io.gb, lrk, token0(m + 2));
             }
             WS_MARK(3);
             __syncthreads();  // end of step
@@ -699,7 +747,8 @@ __device__ __forceinline__ void ws_out_unit(
             float4 dr;  // decay of the lane's state rows from the chunk's right edge to the segment's
         };
         auto fetch_stash = [&](int m) {
-            StashRows c;
+            StashRows c = {};
+            if (!owns_rows) return c;  // (a 32-wide head: state rows 32..63 are zero and not stored)
             const unsigned char *base = stash + size_t(chunk0 + min(m, nch - 1)) * kStashBytes;
             const uint4 *p = reinterpret_cast<const uint4 *>(base) + tid4;
             c.p[0] = p[0];
@@ -794,7 +843,7 @@ __device__ __forceinline__ void ws_out_unit(
             rz0 = load_z(0, 0);
         }
 
-        if (seg_states != nullptr) {
+        if (seg_states != nullptr && owns_rows) {
             fold(S, 0, 0, seg, 1);
             fold(Sseg, 1, n_seg - 1, n_seg - 1 - seg, -1);
         }
@@ -807,10 +856,14 @@ __device__ __forceinline__ void ws_out_unit(
                 f32x4 O[4];
 #pragma unroll
                 for (int jt = 0; jt < 4; ++jt) O[jt] = __builtin_bit_cast(f32x4, sm.hand_o[jt][tid4]);
-                const bf16x8 qf0 = __builtin_bit_cast(bf16x8, sm.hand_q[0][tid4]), qf1 = __builtin_bit_cast(bf16x8, sm.hand_q[1][tid4]);
-                const bf16x8 qb0 = __builtin_bit_cast(bf16x8, sm.hand_q[2][tid4]), qb1 = __builtin_bit_cast(bf16x8, sm.hand_q[3][tid4]);
-                readout(sm.st, qf0, qf1, r, g, O);
-                if (c + 1 < nch || seg_in) readout(sm.sb, qb0, qb1, r, g, O);
+                const bf16x8 qf0 = __builtin_bit_cast(bf16x8, sm.hand_q[0][tid4]), qb0 = __builtin_bit_cast(bf16x8, sm.hand_q[2][tid4]);
+                bf16x8 qf1 = {}, qb1 = {};
+                if (kKs > 1) {
+                    qf1 = __builtin_bit_cast(bf16x8, sm.hand_q[1][tid4]);
+                    qb1 = __builtin_bit_cast(bf16x8, sm.hand_q[3][tid4]);
+                }
+                readout<kKs>(sm.st, qf0, qf1, r, g, O);
+                if (c + 1 < nch || seg_in) readout<kKs>(sm.sb, qb0, qb1, r, g, O);
                 // o_t = (o_fwd_t + o_bwd_t) / 2 (the queries arrive halved), turned into whole rows through the wave's
                 // own rows of the bounce tile, then written 8 rows per store
 #pragma unroll
@@ -841,6 +894,7 @@ __device__ __forceinline__ void ws_out_unit(
                     stage_group(rxg, m + 1);
                     rxg = load_rows(rx, lr, unsigned(group_token0(m + 2)));
                 }
+              if (owns_rows) {
                 // forward state update: S = d (S + K^T V), d = exp(chunk total)
                 const float4 t = *reinterpret_cast<const float4 *>(&sm.tot[b][16 * w + 4 * g]);
                 const float4 d = make_float4(fast_exp2(t.x * kLog2e), fast_exp2(t.y * kLog2e), fast_exp2(t.z * kLog2e), fast_exp2(t.w * kLog2e));
@@ -854,8 +908,9 @@ __device__ __forceinline__ void ws_out_unit(
                 for (int jt = 0; jt < 4; ++jt) {
                     S[jt][0] *= d.x; S[jt][1] *= d.y; S[jt][2] *= d.z; S[jt][3] *= d.w;
                 }
+              }
             }
-            if (m < nch) {
+            if (m < nch && owns_rows) {
                 // tiles for chunk m, which the consumers take in the next step
                 publish(rs, m);
                 rs = fetch_stash(m + 1);
@@ -867,7 +922,7 @@ __device__ __forceinline__ void ws_out_unit(
     }
 }
 
-template <bool kTm, bool kLoc = false>
+template <bool kTm, bool kLoc = false, int kDk = kD>
 __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
     const uint16_t *__restrict__ q_all, const uint16_t *__restrict__ k_all, const uint16_t *__restrict__ v_all,
     const uint16_t *__restrict__ gf_all, const uint16_t *__restrict__ gb_all, uint16_t *__restrict__ out_all,
@@ -880,14 +935,14 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_out_kernel(
     if (unit_flag == 0) {
         // a unit outside the fast form's range: the general four-wave code, on four waves
         if (threadIdx.x >= 256) return;
-        out_unit_general<kD, kTm, kLoc, true>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
-                                              n_chunks, seg_chunks, n_seg, blockIdx.x, heads, lf);
+        out_unit_general<kDk, kTm, kLoc, true>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
+                                               n_chunks, seg_chunks, n_seg, blockIdx.x, heads, lf);
     } else if (unit_flag == 2) {
-        ws_out_unit<kTm, kLoc, true>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L, n_chunks,
-                                     seg_chunks, n_seg, heads, lf);
+        ws_out_unit<kTm, kLoc, true, kDk>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
+                                          n_chunks, seg_chunks, n_seg, heads, lf);
     } else {
-        ws_out_unit<kTm, kLoc, false>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L, n_chunks,
-                                      seg_chunks, n_seg, heads, lf);
+        ws_out_unit<kTm, kLoc, false, kDk>(q_all, k_all, v_all, gf_all, gb_all, out_all, seg_states, stash_all, L,
+                                           n_chunks, seg_chunks, n_seg, heads, lf);
     }
 }
 
@@ -898,7 +953,7 @@ bool bigla_chunk_ws_applicable(long BH, int L, int dk)
     const Plan p = make_ws_plan(BH, L);
     // short sequences with at least half a chip of slabs stay with the single-launch slab kernel
     if (BH >= 128 && p.n_chunks <= 4) return false;
-    return dk == kD && p.n_chunks > 1;
+    return (dk == kD || dk == kD / 2) && p.n_chunks > 1;
 }
 
 // [segment states][unit flags][stash], as in the four-wave path, for this path's own plan
@@ -909,14 +964,15 @@ size_t bigla_chunk_ws_workspace_bytes(long BH, int L)
            size_t(BH) * p.n_chunks * kStashBytes;
 }
 
-// gates: null when g_fwd and g_bwd are inputs; otherwise the state pass makes them (and writes them there)
+// gates: null when g_fwd and g_bwd are inputs; otherwise the state pass makes them (and writes them there; dk = 64)
 hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
-                                 void *out, long BH, int L, int heads_token_major, void *workspace, hipStream_t stream,
-                                 const GateSource *gates = nullptr, const LocalityFusion *fusion = nullptr)
+                                 void *out, long BH, int L, int dk, int heads_token_major, void *workspace,
+                                 hipStream_t stream, const GateSource *gates = nullptr,
+                                 const LocalityFusion *fusion = nullptr)
 {
     const Plan p = make_ws_plan(BH, L);
     const long blocks = BH * p.n_seg;
-    if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+    if (blocks > 0x7fffffffL || (gates && dk != kD)) return hipErrorInvalidValue;
     const uint16_t *qq = static_cast<const uint16_t *>(q), *kk = static_cast<const uint16_t *>(k);
     const uint16_t *vv = static_cast<const uint16_t *>(v);
     const uint16_t *gf = static_cast<const uint16_t *>(g_fwd), *gb = static_cast<const uint16_t *>(g_bwd);
@@ -928,39 +984,46 @@ hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, co
     const bool tm = heads_token_major > 0;
     const int heads = tm ? heads_token_major : 1;
     float *seg_out = p.n_seg > 1 ? seg_states : nullptr;
+    const dim3 grid((unsigned)blocks), block(kWsThreads);
+    using std::integral_constant;
+    typedef integral_constant<bool, true> yes;
+    typedef integral_constant<bool, false> no;
+    typedef integral_constant<int, kD> wide;
+    typedef integral_constant<int, kD / 2> half;
     {
         LaunchTimer timer(kKernelSegmentState, stream);
         const GateSource none = {};
-        if (gates && tm)
-            hipLaunchKernelGGL((bigla_ws_state_kernel<true, true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, kk,
-                               vv, gf, gb, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, *gates);
-        else if (gates)
-            hipLaunchKernelGGL((bigla_ws_state_kernel<false, true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, kk,
-                               vv, gf, gb, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, *gates);
-        else if (tm)
-            hipLaunchKernelGGL((bigla_ws_state_kernel<true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, kk, vv, gf,
-                               gb, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, none);
-        else
-            hipLaunchKernelGGL((bigla_ws_state_kernel<false>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, kk, vv, gf,
-                               gb, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, none);
+        auto go = [&](auto tm_c, auto gates_c, auto dk_c) {
+            hipLaunchKernelGGL((bigla_ws_state_kernel<decltype(tm_c)::value, decltype(gates_c)::value, decltype(dk_c)::value>),
+                               grid, block, 0, stream, kk, vv, gf, gb, seg_out, seg_mild, stash, L, p.n_chunks,
+                               p.seg_chunks, p.n_seg, heads, gates ? *gates : none);
+        };
+        if (gates) {
+            if (tm) go(yes{}, yes{}, wide{}); else go(no{}, yes{}, wide{});
+        } else if (dk == kD) {
+            if (tm) go(yes{}, no{}, wide{}); else go(no{}, no{}, wide{});
+        } else {
+            if (tm) go(yes{}, no{}, half{}); else go(no{}, no{}, half{});
+        }
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     {
         LaunchTimer timer(kKernelSegmentOut, stream);
-        const NoFusion none = {};
-        if (fusion && tm)
-            hipLaunchKernelGGL((bigla_ws_out_kernel<true, true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, qq, kk,
-                               vv, gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, *fusion);
-        else if (fusion)
-            hipLaunchKernelGGL((bigla_ws_out_kernel<false, true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, qq, kk,
-                               vv, gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, *fusion);
-        else if (tm)
-            hipLaunchKernelGGL((bigla_ws_out_kernel<true>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, qq, kk, vv,
-                               gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, none);
-        else
-            hipLaunchKernelGGL((bigla_ws_out_kernel<false>), dim3((unsigned)blocks), dim3(kWsThreads), 0, stream, qq, kk, vv,
-                               gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks, p.seg_chunks, p.n_seg, heads, none);
+        auto go = [&](auto tm_c, auto loc_c, auto dk_c) {
+            typename std::conditional<decltype(loc_c)::value, LocalityFusion, NoFusion>::type arg = {};
+            if constexpr (decltype(loc_c)::value) arg = *fusion;
+            hipLaunchKernelGGL((bigla_ws_out_kernel<decltype(tm_c)::value, decltype(loc_c)::value, decltype(dk_c)::value>),
+                               grid, block, 0, stream, qq, kk, vv, gf, gb, oo, seg_out, seg_mild, stash, L, p.n_chunks,
+                               p.seg_chunks, p.n_seg, heads, arg);
+        };
+        if (dk == kD) {
+            if (fusion) { if (tm) go(yes{}, yes{}, wide{}); else go(no{}, yes{}, wide{}); }
+            else { if (tm) go(yes{}, no{}, wide{}); else go(no{}, no{}, wide{}); }
+        } else {
+            if (fusion) { if (tm) go(yes{}, yes{}, half{}); else go(no{}, yes{}, half{}); }
+            else { if (tm) go(yes{}, no{}, half{}); else go(no{}, no{}, half{}); }
+        }
     }
     return hipGetLastError();
 }
