@@ -289,7 +289,7 @@ int gate_producer_fwd(const void *x, const void *w1, const void *w2, const void 
  *                            pass of the chunkwise mixer then makes each chunk's gates itself from it, writes
  *                            them to g_fwd / g_bwd for the output pass and never reads them back: the gates
  *                            cross memory twice (written, read by the output pass) instead of three times.
- *                            Same arithmetic as gate_producer_fwd, bit for bit.  VIG_BF16, dk = dv = 64,
+ *                            Same arithmetic as gate_producer_fwd, bit for bit.  VIG_BF16, dv = 64,
  *                            where bigla_fwd_plan admits VIG_FWD_WAVE_SPECIALISED (VIG_ERR_UNSUPPORTED
  *                            otherwise, and while vig_measure_alias_slabs is on);
  *   VIG_GATES_AUTO           VIG_GATES_IN_STATE_PASS where it applies, else VIG_GATES_SEPARATE.

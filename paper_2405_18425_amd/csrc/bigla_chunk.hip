@@ -1207,15 +1207,15 @@ hipError_t bigla_chunk_set_alias(int on)
     return hipMemcpyToSymbol(HIP_SYMBOL(g_alias_inputs), &on, sizeof(int));
 }
 
-bool bigla_chunk_gated_selectable(long BH, int L, int dk) { return !g_alias_on && dk == kD && bigla_chunk_ws_applicable(BH, L, dk); }
+bool bigla_chunk_gated_selectable(long BH, int L, int dk) { return !g_alias_on && bigla_chunk_ws_applicable(BH, L, dk); }
 
 // bigla_chunk_launch with the eight-wave kernels, the state pass making the gates from the gate producer's
 // low-rank half (and writing them to g_fwd, g_bwd, which the output pass then reads).
 hipError_t bigla_chunk_gated_launch(const void *q, const void *k, const void *v, void *g_fwd, void *g_bwd, void *out,
-                                    long BH, int L, int n_heads, int heads_token_major, const void *lowrank,
+                                    long BH, int L, int dk, int n_heads, int heads_token_major, const void *lowrank,
                                     const void *w2, const void *bias, float tau, void *workspace, hipStream_t stream)
 {
-    if (!bigla_chunk_ws_applicable(BH, L, kD) || n_heads <= 0 || BH % n_heads != 0) return hipErrorInvalidValue;
+    if (!bigla_chunk_ws_applicable(BH, L, dk) || n_heads <= 0 || BH % n_heads != 0) return hipErrorInvalidValue;
     if (g_alias_on) return hipErrorInvalidValue;  // aliased slabs would all write the first slab's gates
     GateSource gs;
     gs.lowrank = static_cast<const uint16_t *>(lowrank);
@@ -1223,7 +1223,7 @@ hipError_t bigla_chunk_gated_launch(const void *q, const void *k, const void *v,
     gs.bias = static_cast<const uint16_t *>(bias);
     gs.inv_tau = 1.f / tau;
     gs.n_heads = n_heads;
-    return bigla_chunk_ws_launch(q, k, v, g_fwd, g_bwd, out, BH, L, kD, heads_token_major, workspace, stream, &gs);
+    return bigla_chunk_ws_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, heads_token_major, workspace, stream, &gs);
 }
 
 bool bigla_chunk_ws_selectable(long BH, int L, int dk) { return bigla_chunk_ws_applicable(BH, L, dk); }

@@ -180,7 +180,6 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
     long slab;
     int seg;
     unit_slab_segment(blockIdx.x, n_seg, slab, seg);
-    static_assert(!kGates || kDk == kD, "the gates are made for 64-wide heads");
     constexpr int kCt = kDk / 16;       // 16-channel tiles that carry data
     const bool owns_rows = 16 * w < kDk;  // consumer wave w carries state rows 16w .. 16w+15
     const SlabIo<kTm, kDk> io(nullptr, k_all, v_all, gf_all, gb_all, nullptr, slab, L, heads);
@@ -208,15 +207,16 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
     if (kGates) {
         const int head = int(slab % gs.n_heads);
         lowrank_rows = gs.lowrank + size_t(slab / gs.n_heads) * L * 16;
-        const int arow = 16 * (r >> 2) + (r & 3);
-        const int base = (gdir * gs.n_heads + head) * kD;
+        // (a 32-wide head has channels for the lanes g = 0, 1 only; the others repeat those rows and make zeros)
+        const int arow = (16 * (r >> 2)) % kDk + (r & 3);
+        const int base = (gdir * gs.n_heads + head) * kDk;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             gate_a[i] = __builtin_bit_cast(s16x4, *reinterpret_cast<const uint2 *>(gs.w2 + size_t(base + arow + 4 * i) * 16 + 4 * g));
         uint4 braw[2];
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh)
-            braw[hh] = gs.bias ? *reinterpret_cast<const uint4 *>(gs.bias + base + 16 * g + 8 * hh) : make_uint4(0u, 0u, 0u, 0u);
+            braw[hh] = gs.bias ? *reinterpret_cast<const uint4 *>(gs.bias + base + (16 * g) % kDk + 8 * hh) : make_uint4(0u, 0u, 0u, 0u);
         const uint32_t b[8] = {braw[0].x, braw[0].y, braw[0].z, braw[0].w, braw[1].x, braw[1].y, braw[1].z, braw[1].w};
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -235,8 +235,9 @@ __global__ __launch_bounds__(kWsThreads) void bigla_ws_state_kernel(
     // bounds check of the slab's buffer resource.
     auto make_gates = [&](const uint2 lowrank_row, int m, int buf) {
         const s16x4 hop = __builtin_bit_cast(s16x4, lowrank_row);
-        const bool live = long(chunk0 + m) * kC + row < L;
-        const unsigned off = (unsigned(chunk0 + m) * kC + unsigned(row)) * io.pitch + 32u * unsigned(g);
+        const bool live = long(chunk0 + m) * kC + row < L && 16 * g < kDk;
+        // (lanes without channels of their own store nowhere: an offset beyond the slab's extent, also 16 bytes on)
+        const unsigned off = 16 * g < kDk ? (unsigned(chunk0 + m) * kC + unsigned(row)) * io.key_pitch + 32u * unsigned(g) : 0xf0000000u;
         uint32_t packed[8];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {  // channels 16g + 4i .. + 3
@@ -964,7 +965,7 @@ size_t bigla_chunk_ws_workspace_bytes(long BH, int L)
            size_t(BH) * p.n_chunks * kStashBytes;
 }
 
-// gates: null when g_fwd and g_bwd are inputs; otherwise the state pass makes them (and writes them there; dk = 64)
+// gates: null when g_fwd and g_bwd are inputs; otherwise the state pass makes them (and writes them there)
 hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, const void *g_fwd, const void *g_bwd,
                                  void *out, long BH, int L, int dk, int heads_token_major, void *workspace,
                                  hipStream_t stream, const GateSource *gates = nullptr,
@@ -972,7 +973,7 @@ hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, co
 {
     const Plan p = make_ws_plan(BH, L);
     const long blocks = BH * p.n_seg;
-    if (blocks > 0x7fffffffL || (gates && dk != kD)) return hipErrorInvalidValue;
+    if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
     const uint16_t *qq = static_cast<const uint16_t *>(q), *kk = static_cast<const uint16_t *>(k);
     const uint16_t *vv = static_cast<const uint16_t *>(v);
     const uint16_t *gf = static_cast<const uint16_t *>(g_fwd), *gb = static_cast<const uint16_t *>(g_bwd);
@@ -998,8 +999,10 @@ hipError_t bigla_chunk_ws_launch(const void *q, const void *k, const void *v, co
                                grid, block, 0, stream, kk, vv, gf, gb, seg_out, seg_mild, stash, L, p.n_chunks,
                                p.seg_chunks, p.n_seg, heads, gates ? *gates : none);
         };
-        if (gates) {
+        if (gates && dk == kD) {
             if (tm) go(yes{}, yes{}, wide{}); else go(no{}, yes{}, wide{});
+        } else if (gates) {
+            if (tm) go(yes{}, yes{}, half{}); else go(no{}, yes{}, half{});
         } else if (dk == kD) {
             if (tm) go(yes{}, no{}, wide{}); else go(no{}, no{}, wide{});
         } else {

@@ -354,7 +354,7 @@ int gated_bigla_fwd(const void *x, const void *w1, const void *w2, const void *b
     if (!aligned16(workspace)) return VIG_ERR_ALIGN;
     const bool bf16 = dtype == VIG_BF16;
     const long BH = long(B) * H;
-    const bool fusable = chunkwise_fwd(L, dk, dv, bf16) && dk == 64 && vig::bigla_chunk_gated_selectable(BH, L, dk) &&
+    const bool fusable = chunkwise_fwd(L, dk, dv, bf16) && vig::bigla_chunk_gated_selectable(BH, L, dk) &&
                          chunk_offsets_ok(L, H, layout);
     if (plan == VIG_GATES_IN_STATE_PASS && !fusable) return VIG_ERR_UNSUPPORTED;
     const size_t mixer_bytes = round256(bigla_workspace_bytes(B, H, L, dk, dv, dtype));
@@ -375,7 +375,7 @@ int gated_bigla_fwd(const void *x, const void *w1, const void *w2, const void *b
     clear_stale_hip_error();
     const hipError_t e = vig::gate_lowrank_launch(x, w1, lowrank, B, L, D, s);
     if (e != hipSuccess) return hip_status(e);
-    return hip_status(vig::bigla_chunk_gated_launch(q, k, v, g_fwd, g_bwd, out, BH, L, H,
+    return hip_status(vig::bigla_chunk_gated_launch(q, k, v, g_fwd, g_bwd, out, BH, L, dk, H,
                                                     layout == VIG_LAYOUT_BLHD ? H : 0, lowrank, w2, bias, tau, workspace, s));
 }
 

@@ -36,10 +36,10 @@ hipError_t bigla_chunk_launch(const void *q, const void *k, const void *v, const
                               int kernels, void *workspace, hipStream_t stream);
 
 // The eight-wave kernels with the state pass making the gates from the gate producer's low-rank half
-// (lowrank [B][L][16] bf16); g_fwd, g_bwd are written.  dk = dv = 64, bf16; not while slabs are aliased.
+// (lowrank [B][L][16] bf16); g_fwd, g_bwd are written.  bf16, dv = 64, dk = 64 or 32; not while slabs are aliased.
 bool bigla_chunk_gated_selectable(long BH, int L, int dk);
 hipError_t bigla_chunk_gated_launch(const void *q, const void *k, const void *v, void *g_fwd, void *g_bwd, void *out,
-                                    long BH, int L, int n_heads, int heads_token_major, const void *lowrank,
+                                    long BH, int L, int dk, int n_heads, int heads_token_major, const void *lowrank,
                                     const void *w2, const void *bias, float tau, void *workspace, hipStream_t stream);
 
 // ---- gradient of the token mixer -----------------------------------------------------------------

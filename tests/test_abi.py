@@ -204,7 +204,7 @@ def test_gated_bigla_validation_codes():
     # the plan whose state pass makes the gates: bf16, dk = dv = 64, at least two chunks
     fused = vb.GATES_PLANS["in_state_pass"]
     assert call(plan=fused, dtype=vb.VIG_F32) == vb.VIG_ERR_UNSUPPORTED
-    assert call(plan=fused, dk=32) == vb.VIG_ERR_UNSUPPORTED
+    assert call(plan=fused, dk=16, dv=16) == vb.VIG_ERR_UNSUPPORTED
     assert call(plan=fused, Lq=40) == vb.VIG_ERR_UNSUPPORTED
     assert call(plan=fused, q=PTR + 8) == vb.VIG_ERR_ALIGN
     assert L.gated_bigla_workspace_bytes(8, 6, 4096, 64, 64, vb.VIG_BF16) >= \

@@ -690,23 +690,26 @@ def test_gate_producer_into_bigla_chain():
     assert_close(wl.widen(wl.from_torch(out, "bf16"), "bf16"), ref, TOL["bf16"], "bigla on produced gates")
 
 
-@pytest.mark.parametrize("B,L,D,H,layout,bias_mu,with_bias", [
-    (2, 1024, 384, 6, "bhld", -2.0, True),     # several segments per slab
-    (3, 300, 192, 3, "blhd", 0.0, True),       # ragged last chunk, token-major
-    (2, 130, 64, 2, "bhld", 1.0, False),       # three chunks, no bias
-    (1, 4096, 384, 2, "bhld", -1.0, True),     # two slabs cut into many segments
-    (2, 700, 128, 4, "blhd", -12.0, True),     # gates of -0.75 per step: every unit leaves the fast form
-    (2, 640, 128, 3, "bhld", -7.0, True),      # around the fast form's limit: some units inside, some outside
+@pytest.mark.parametrize("B,L,D,H,layout,bias_mu,with_bias,dk", [
+    (2, 1024, 384, 6, "bhld", -2.0, True, 64),     # several segments per slab
+    (3, 300, 192, 3, "blhd", 0.0, True, 64),       # ragged last chunk, token-major
+    (2, 130, 64, 2, "bhld", 1.0, False, 64),       # three chunks, no bias
+    (1, 4096, 384, 2, "bhld", -1.0, True, 64),     # two slabs cut into many segments
+    (2, 700, 128, 4, "blhd", -16.0, True, 64),     # gates of -1 per step: every unit leaves the fast form
+    (2, 640, 128, 3, "bhld", -12.0, True, 64),     # around the fast form's limit: some units inside, some outside
+    (2, 640, 128, 3, "bhld", -7.0, True, 64),      # chunks beyond 32 nats: split diagonal operands
+    (2, 1024, 384, 6, "bhld", -2.0, True, 32),     # the paper's head shape: 32-wide keys and gates
+    (3, 300, 192, 3, "blhd", -13.0, False, 32),    # token-major, ragged, units inside and outside the fast form
 ])
-def test_gated_bigla_plans(B, L, D, H, layout, bias_mu, with_bias):
+def test_gated_bigla_plans(B, L, D, H, layout, bias_mu, with_bias, dk):
     """Gate producer + token mixer as one call (Section 3 gate into Eq. (BiGLA)): the plan whose state pass makes
     the gates itself against the oracle's chain, and bit for bit against the two separate launches."""
     import torch
     import oracle
     from paper_2405_18425_amd import binding as vb
 
-    dk = dv = 64
-    _say(f"gated_bigla B{B} L{L} D{D} H{H} {layout} bias_mu {bias_mu}")
+    dv = 64
+    _say(f"gated_bigla B{B} L{L} D{D} H{H} dk{dk} {layout} bias_mu {bias_mu}")
     st = wl.generate_gate_inputs(B, L, D, H, dk, "bf16", seed=L + H, bias_mu=bias_mu)
     w = wl.Workload("gated", B=B, H=H, Hg=1, Wg=L, dk=dk, dv=dv, dtype="bf16", gate_mu=0.0)
     s = wl.generate(w, seed=L + H + 1, tensors=("q", "k", "v"))
