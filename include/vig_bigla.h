@@ -82,8 +82,8 @@ size_t bigla_workspace_bytes(int B, int H, int L, int dk, int dv, int dtype);
  *
  * Numerics: VIG_BF16 with dv = 64, dk = 64 or 32 and L >= 32 runs the chunkwise MFMA path (bf16
  * operands, fp32 accumulation, fp32 carried state; dk = 32 is widened to 64 key channels with zeros
- * inside the kernels).  Where some channel of a 64-token chunk decays by more than 32 nats (half
- * a nat per step), the operands of every token's nearest products are kept to 16 bits: at full
+ * inside the kernels).  Where some channel of a 64-token chunk decays by more than 16 nats (a quarter
+ * of a nat per step), the operands of every token's nearest products are kept to 16 bits: at full
  * speed up to 60 nats per chunk where the eight-wave kernels run (see bigla_fwd_plan),
  * otherwise in a range-safe form, several times slower, that treats per-step log gates below -8
  * as -8 (alpha < 3.4e-4 acts as a hard reset either way; the difference is far below the bf16
@@ -234,8 +234,9 @@ int locality_gate_fwd_layout(const void *x, const void *w, const void *bias, con
  *                             bytes per step and no intermediate tensor, at about the speed of two
  *                             launches where the eight-wave kernels carry it (grids under 65 columns,
  *                             the shapes of VIG_FWD_WAVE_SPECIALISED) and slower elsewhere.
- *                             VIG_BF16 with dv = 64 and dk = 64 or 32 only (VIG_ERR_UNSUPPORTED
- *                             otherwise);
+ *                             VIG_BF16 with dv = 64, dk = 64 or 32 and at least 32 tokens only,
+ *                             the cases in which bigla_fwd runs the chunkwise path
+ *                             (VIG_ERR_UNSUPPORTED otherwise);
  *   VIG_PLAN_AUTO             two launches (the output pass is bound by its vector arithmetic, and
  *                             the blend's arithmetic costs there what the second pass over memory
  *                             costs): the fused plan is for callers who cannot afford the

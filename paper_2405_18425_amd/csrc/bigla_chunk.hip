@@ -17,13 +17,13 @@
 //   update, S_out = diag(exp(b_end)) (S_in + sum_i (k_i exp(-b_i))^T v_i), and one query tile
 //   serves the scores AND the readout.  exp(-b_i) grows with the decay accumulated over the
 //   chunk, so this form is used only when the chunk's total log-decay provably stays within
-//   32 nats in every channel (the sum over its four 16-token sub-blocks of the largest
+//   16 nats in every channel (the sum over its four 16-token sub-blocks of the largest
 //   per-channel sub-block total is checked): far inside fp32's range, and slow enough a decay
 //   that an output sums over enough tokens for the rounding of the scaled operands to stay
 //   within the stated tolerance.  Gates of the paper's form, sigmoid(z)^(1/16), stay inside:
-//   64 steps reach 32 nats only for z < -8 throughout.  (The eight-wave kernels of
+//   64 steps reach 16 nats only for z < -4 throughout.  (The eight-wave kernels of
 //   bigla_chunk_ws.hpp keep the fast form up to 60 nats, with split operands for the diagonal
-//   score tiles beyond 32.)
+//   score tiles beyond 16.)
 //   RANGE-SAFE.  Otherwise cumulative gates stay local to a sub-block: off-diagonal 16x16 tiles
 //   scale keys by the decay to the END of the key's own sub-block and queries by the decay from
 //   the START of the query's sub-block times the whole-sub-block factors in between, so every

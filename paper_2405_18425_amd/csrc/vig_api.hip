@@ -255,7 +255,7 @@ size_t bigla_locality_workspace_bytes(int B, int H, int L, int dk, int dv, int d
     if (plan != VIG_PLAN_AUTO && plan != VIG_PLAN_TWO_LAUNCHES && plan != VIG_PLAN_FUSED_EPILOGUE) return 0;
     const size_t mixer = bigla_workspace_bytes(B, H, L, dk, dv, dtype);
     if (plan == VIG_PLAN_FUSED_EPILOGUE)
-        return vig::bigla_chunk_supported(dk, dv, dtype == VIG_BF16) ? vig::bigla_chunk_workspace_bytes(long(B) * H, L) : 0;
+        return chunkwise_fwd(L, dk, dv, dtype == VIG_BF16) ? vig::bigla_chunk_workspace_bytes(long(B) * H, L) : 0;
     if (!sizes_ok(B, H, L, dv)) return 0;
     // the token mixer's output goes through the workspace
     return align256(mixer) + size_t(B) * H * L * dv * (dtype == VIG_BF16 ? 2 : 4);
@@ -290,7 +290,8 @@ int bigla_locality_fwd(const void *q, const void *k, const void *v, const void *
         return locality_gate_fwd_layout(x, w, bias, gate_logits, o_global, out, B, H, Hg, Wg, dv, dtype, layout,
                                         stream);
     }
-    if (!vig::bigla_chunk_supported(dk, dv, bf16)) return VIG_ERR_UNSUPPORTED;
+    // the epilogue lives in the chunkwise kernels; shorter sequences are left to the exact recurrence
+    if (!chunkwise_fwd(L, dk, dv, bf16)) return VIG_ERR_UNSUPPORTED;
     if (!sizes_ok(B, H, L, dk > dv ? dk : dv) || long(B) * H > 0x7fffffffL) return VIG_ERR_SHAPE;
     if (!chunk_offsets_ok(L, H, layout)) return VIG_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g_fwd) || !aligned16(g_bwd) ||

@@ -248,7 +248,11 @@ def test_bigla_locality_validation_codes():
     assert a == vb.bigla_workspace_bytes(8, 6, 4096, 64, 64, vb.VIG_BF16)
     assert b >= a + 8 * 6 * 4096 * 64 * 2
     assert L.bigla_locality_workspace_bytes(8, 6, 4096, 64, 64, vb.VIG_BF16, 0) in (a, b)
-    assert call(x=PTR + 8, plan=fused, ws=PTR, ws_bytes=1 << 30) == vb.VIG_ERR_ALIGN
+    assert call(x=PTR + 8, Hg=8, Wg=8, plan=fused, ws=PTR, ws_bytes=1 << 30) == vb.VIG_ERR_ALIGN
+    # sequences under 32 tokens are the exact recurrence's (no chunkwise launch to carry the epilogue)
+    assert call(Hg=4, Wg=4, plan=fused, ws=PTR, ws_bytes=1 << 30) == vb.VIG_ERR_UNSUPPORTED
+    assert L.bigla_locality_workspace_bytes(1, 1, 16, 64, 64, vb.VIG_BF16, fused) == 0
+    assert call(Hg=4, Wg=8, plan=fused, ws=PTR + 4, ws_bytes=1 << 30) == vb.VIG_ERR_ALIGN
     # token-major rows of one batch element are addressed with 32-bit byte offsets
     assert call(B=1, H=64, Hg=1 << 10, Wg=1 << 10, layout=vb.VIG_LAYOUT_BLHD, plan=fused, ws=PTR,
                 ws_bytes=1 << 40) == vb.VIG_ERR_SHAPE
